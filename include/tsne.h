@@ -1,0 +1,161 @@
+/*
+ * tsne.h -- C ABI of the MI355X (gfx950) Barnes-Hut t-SNE library.
+ *
+ * The library implements the per-iteration gradient step of Barnes-Hut t-SNE as
+ * laid out in Algorithm 1 of "t-SNE-CUDA" (arXiv 1807.11824): tree build,
+ * repulsive forces with the Z estimate, attractive forces over the sparse P,
+ * and the update of the embedding -- plus the one-off construction of P.
+ *
+ * Conventions
+ *  - Every pointer named d_* is a DEVICE pointer into memory the caller owns
+ *    (e.g. a torch tensor's data_ptr()); every other pointer is a HOST pointer.
+ *  - The library allocates no device memory: the caller passes one workspace of
+ *    at least tsne_workspace_bytes() / tsne_build_P_workspace_bytes() bytes,
+ *    256-byte aligned, which must stay alive while the context is in use.
+ *  - All work is enqueued on the caller's HIP stream (`stream` is a hipStream_t
+ *    passed as void*; NULL = the default stream).  tsne_step() and
+ *    tsne_gradient() never synchronise the host; tsne_run(), tsne_status(),
+ *    tsne_kl() and tsne_build_P() do.
+ *  - Arguments are validated on the host before anything is enqueued.  Every
+ *    function returns TSNE_OK (0) or a negative tsne_error; nothing aborts.
+ *  - One context must not be used from two threads at once.
+ */
+#ifndef TSNE_H
+#define TSNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TSNE_OK = 0,
+    TSNE_EINVAL = -1,  /* bad argument (null pointer, size or parameter out of range) */
+    TSNE_ENOSPC = -2,  /* workspace or output capacity too small */
+    TSNE_EHIP = -3,    /* a HIP call failed; see tsne_last_error() */
+    TSNE_ESTATE = -4,  /* call out of order (e.g. tsne_step before tsne_set_P) */
+    TSNE_ENUM = -5     /* numerical trouble reported by the device; see tsne_status() */
+} tsne_error;
+
+/* Bits of the device status word returned by tsne_status(). */
+#define TSNE_STATUS_NONFINITE 1u     /* a coordinate of Y was NaN or infinite */
+#define TSNE_STATUS_CELL_OVERFLOW 2u /* the quad tree needed more cells than the workspace holds */
+#define TSNE_STATUS_WALK_OVERFLOW 4u /* internal stack / list bound hit during the tree walk */
+
+/* The wavefront width: points are walked through the tree in groups of this
+ * many consecutive positions of the spatial order, all taking the same
+ * accept / open decisions (Sec. III-C, last paragraph: divergence-free walk). */
+#define TSNE_GROUP 64
+
+typedef struct {
+    int32_t n;                    /* number of points, >= 1 */
+    float theta;                  /* Eq. (14) threshold; 0 <= theta <= 0.7; 0 = all pairs */
+    float lr;                     /* learning rate (200) */
+    float exaggeration;           /* factor on the attractive term early on (12) */
+    int32_t exaggeration_iters;   /* iterations [0, this) are exaggerated (250) */
+    float momentum_early;         /* 0.5 */
+    float momentum_late;          /* 0.8 */
+    int32_t momentum_switch_iter; /* 250 */
+    float gain_inc;               /* 0.2 */
+    float gain_dec;               /* 0.8 */
+    float gain_min;               /* 0.01 */
+    int32_t morton_bits;          /* grid bits per axis = maximum tree depth, 1..16 (16) */
+    int32_t leaf_cap;             /* a cell with at most this many points is a leaf, >= 1 (8) */
+    int32_t overlap;              /* 1: attractive forces run on a second stream beside the tree work */
+} tsne_params;
+
+typedef struct tsne_ctx tsne_ctx; /* opaque, host side, owned by the library */
+
+/* Fills *p with the defaults quoted above for n points. */
+int tsne_default_params(tsne_params *p, int32_t n);
+
+/* Bytes of device workspace a context with these parameters needs (upper bound). */
+int tsne_workspace_bytes(const tsne_params *p, size_t *bytes);
+
+/* Creates a context.  d_workspace: device memory, >= tsne_workspace_bytes(), 256-byte aligned;
+ * the optimiser state (velocity, gains) lives inside it.  The context starts with velocity 0,
+ * gains 1 and no P. */
+int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_workspace, size_t workspace_bytes);
+void tsne_destroy(tsne_ctx *ctx);
+
+/*
+ * Alg. 1 lines 1-2: affinities.  For every row of X (n x d, row-major float, device) the exact k
+ * nearest neighbours under squared Euclidean distance (Sec. III-B; self excluded, ordered by
+ * (distance, index)), then Eq. (1) restricted to those neighbours with sigma_i set so that the
+ * row's entropy is ln(perplexity), then p_ij = (p_j|i + p_i|j) / 2N stored as CSR with ascending
+ * columns (at most 2 n k entries).
+ * Outputs (device, caller-owned): d_row_ptr[n+1], d_col[cap_nnz], d_val[cap_nnz];
+ * cap_nnz >= 2*n*k always suffices.  *nnz (host) receives the entry count.
+ * Optional outputs (may be NULL): d_knn_idx[n*k] neighbour indices, d_knn_d2[n*k] squared distances.
+ * *n_unconverged (host, may be NULL) receives the number of rows whose entropy could not be
+ * brought within 1e-5 of the target (e.g. all neighbours equidistant).
+ * Synchronises the stream before returning.
+ */
+int tsne_build_P_workspace_bytes(int32_t n, int32_t d, int32_t k, size_t *bytes);
+int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k,
+                 int32_t *d_row_ptr, int32_t *d_col, float *d_val, int64_t cap_nnz, int64_t *nnz,
+                 int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged,
+                 void *d_workspace, size_t workspace_bytes, void *stream);
+
+/* Hands a CSR matrix P (n rows, int32 indices, float values, all on the device) to the context.
+ * Borrowed, not copied: it must outlive every later call on the context. */
+int tsne_set_P(tsne_ctx *ctx, const int32_t *d_row_ptr, const int32_t *d_col, const float *d_val, int64_t nnz);
+
+/* Resets the optimiser state: velocity = 0, gains = 1 (enqueued). */
+int tsne_init_state(tsne_ctx *ctx);
+
+/* Copies the optimiser state out of / into the context (device arrays of n x 2 floats);
+ * with Y and the iteration index this is everything needed to stop and resume. */
+int tsne_get_state(tsne_ctx *ctx, float *d_velocity, float *d_gains);
+int tsne_set_state(tsne_ctx *ctx, const float *d_velocity, const float *d_gains);
+
+/*
+ * Alg. 1 lines 4-8, once: tree build over d_Y (Sec. III-C steps 1-4), repulsive forces and Z
+ * (step 5, Eq. (14)-(15)), attractive forces (Eq. (5)), update with gains and momentum.
+ * d_Y: n x 2 floats, interleaved, updated in place.  iter: 0-based iteration index; it selects
+ * exaggeration and momentum.  Enqueues only.
+ */
+int tsne_step(tsne_ctx *ctx, float *d_Y, int32_t iter);
+
+/* Alg. 1 lines 3-9: n_iter steps starting at iteration iter0; then synchronises and returns
+ * TSNE_ENUM if the device reported trouble. */
+int tsne_run(tsne_ctx *ctx, float *d_Y, int32_t iter0, int32_t n_iter);
+
+/*
+ * The forces at a fixed Y without the update (what the tests compare with the CPU oracle).
+ * d_attr:  n x 2, A_i = sum_j p_ij w_ij (y_i - y_j), w = 1/(1+|y_i-y_j|^2)      (Eq. (5) times Z)
+ * d_rep:   n x 2, R_i = sum over accepted cells n_c w^2 (y_i - y_c) + opened leaves (Eq. (15))
+ * d_Z:     one double, the Barnes-Hut estimate of Eq. (4)
+ * The gradient of Eq. (7) is 4 (alpha A - R / Z).  Any output may be NULL.  Enqueues only.
+ */
+int tsne_gradient(tsne_ctx *ctx, const float *d_Y, float *d_attr, float *d_rep, double *d_Z);
+
+/*
+ * Copies out the tree of the last tsne_step / tsne_gradient (device arrays, any may be NULL):
+ * d_keys[n]   interleaved grid key of every point (x in even bits), original order
+ * d_perm[n]   spatial order: position p holds original index d_perm[p]
+ * cells in depth-first pre-order, children in quadrant order, cap_cells entries each:
+ * d_depth, d_lo, d_hi (member positions [lo,hi)), d_leaf (0/1), d_com (2 floats per cell)
+ * d_root[3]   lower corner x, y and side of the root square
+ * *n_cells (host) receives the cell count.  Synchronises.
+ */
+int tsne_export_tree(tsne_ctx *ctx, uint32_t *d_keys, int32_t *d_perm, int32_t cap_cells,
+                     int32_t *d_depth, int32_t *d_lo, int32_t *d_hi, int32_t *d_leaf, float *d_com,
+                     float *d_root, int32_t *n_cells);
+
+/* KL(P||Q) of Sec. III-A for the embedding d_Y with the exact Z of Eq. (4) (all pairs, O(n^2)).
+ * A harness utility, not part of the step.  Synchronises. */
+int tsne_kl(tsne_ctx *ctx, const float *d_Y, double *kl);
+
+/* Synchronises the stream and returns the device status bits (0 = fine) in *status. */
+int tsne_status(tsne_ctx *ctx, uint32_t *status);
+
+const char *tsne_strerror(int code);
+const char *tsne_last_error(const tsne_ctx *ctx); /* detail of the last failure on this context */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSNE_H */

@@ -1,0 +1,3 @@
+"""Barnes-Hut t-SNE gradient step for MI355X (gfx950): thin binding over libtsne_hip.so."""
+from .binding import (TsneParams, Tsne, build_P, build_P_workspace_bytes, lib, TsneError,  # noqa: F401
+                      STATUS_NONFINITE, STATUS_CELL_OVERFLOW, STATUS_WALK_OVERFLOW)

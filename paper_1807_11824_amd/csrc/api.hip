@@ -1,0 +1,332 @@
+// C ABI of the library (include/tsne.h): argument checks, workspace carve-up and the
+// order in which the kernels of one iteration are enqueued (Alg. 1 lines 3-9).
+#include "tsne_internal.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+constexpr int KL_PART_DOUBLES = 3 * 1024;
+
+size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+int32_t cell_capacity(int32_t n, int32_t bits)
+{
+    // Every cell but the root has a parent with more than leaf_cap >= 1 points, and each level
+    // holds at most n cells, so n (bits + 1) + 1 always suffices; ordinary embeddings need well
+    // under n cells, and 4n + 4096 covers chains of one-child cells over clumps of duplicates.
+    int64_t worst = (int64_t)n * (bits + 1) + 1;
+    int64_t want = (int64_t)4 * n + 4096;
+    return (int32_t)(worst < want ? worst : want);
+}
+
+// Walks the workspace layout; with base == nullptr it only measures.
+size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
+{
+    const size_t n = (size_t)p->n;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *ptr = base ? base + off : nullptr;
+        off += up(bytes);
+        return (void *)ptr;
+    };
+    const int32_t cap = cell_capacity(p->n, p->morton_bits);
+    const size_t nblk_sort = (n + SORT_TILE - 1) / SORT_TILE;
+    const size_t nblk_lev = (n + LEVEL_TILE - 1) / LEVEL_TILE;
+    const size_t ngroups = (n + WAVE - 1) / WAVE;
+    void *q;
+    q = take(sizeof(float4) * 2 * BBOX_MAX_BLOCKS); if (c) c->bbox_part = (float4 *)q;
+    q = take(sizeof(float4));                        if (c) c->root = (float4 *)q;
+    q = take(sizeof(uint32_t));                      if (c) c->status = (uint32_t *)q;
+    q = take(sizeof(uint32_t));                      if (c) c->ncells = (uint32_t *)q;
+    for (int k = 0; k < 2; ++k) {
+        q = take(4 * n); if (c) c->keys[k] = (uint32_t *)q;
+        q = take(4 * n); if (c) c->idx[k] = (uint32_t *)q;
+    }
+    q = take(4 * n);                                 if (c) c->keys_orig = (uint32_t *)q;
+    q = take(4 * 256 * nblk_sort);                   if (c) c->hist = (uint32_t *)q;
+    q = take(4 * 256);                               if (c) c->dtot = (uint32_t *)q;
+    q = take(8 * n);                                 if (c) c->Ys = (float2 *)q;
+    q = take(2 * n);                                 if (c) c->lev = (uint16_t *)q;
+    q = take(sizeof(ScanPart) * nblk_lev);           if (c) c->part = (ScanPart *)q;
+    q = take(4 * (n + 1));                           if (c) c->cellseq = (uint32_t *)q;
+    q = take(16 * (n + 1));                          if (c) c->ps = (double2 *)q;
+    q = take(sizeof(Cell) * (size_t)cap);            if (c) { c->cells = (Cell *)q; c->cap_cells = cap; }
+    q = take(8 * n);                                 if (c) c->R = (float2 *)q;
+    q = take(8 * n);                                 if (c) c->A = (float2 *)q;
+    q = take(8 * n);                                 if (c) c->uY = (float2 *)q;
+    q = take(8 * n);                                 if (c) c->gains = (float2 *)q;
+    q = take(8 * ngroups);                           if (c) c->zpart = (double *)q;
+    q = take(8);                                     if (c) c->Z = (double *)q;
+    q = take(8 * KL_PART_DOUBLES);                   if (c) c->kl_part = (double *)q;
+    return off;
+}
+
+int check_params(const tsne_params *p)
+{
+    if (!p) return TSNE_EINVAL;
+    if (p->n < 1 || p->n > (1 << 30)) return TSNE_EINVAL;
+    if (!(p->theta >= 0.0f) || p->theta > 0.7f) return TSNE_EINVAL;
+    if (p->morton_bits < 1 || p->morton_bits > 16) return TSNE_EINVAL;
+    if (p->leaf_cap < 1) return TSNE_EINVAL;
+    if (!isfinite(p->lr) || !isfinite(p->exaggeration) || !isfinite(p->momentum_early) ||
+        !isfinite(p->momentum_late) || !isfinite(p->gain_inc) || !isfinite(p->gain_dec) || !isfinite(p->gain_min))
+        return TSNE_EINVAL;
+    return TSNE_OK;
+}
+
+int fail_hip(tsne_ctx *c, hipError_t e, const char *where)
+{
+    if (c) snprintf(c->err, sizeof(c->err), "%s: %s", where, hipGetErrorString(e));
+    return TSNE_EHIP;
+}
+
+int fail(tsne_ctx *c, int code, const char *msg)
+{
+    if (c) snprintf(c->err, sizeof(c->err), "%s", msg);
+    return code;
+}
+
+// Forces at d_Y into c->A, c->R, c->Z.  The attractive kernel only needs Y and P, so with
+// overlap it runs on the second stream while the tree is built and walked on the first.
+int enqueue_forces(tsne_ctx *c, const float *d_Y)
+{
+    hipError_t e;
+    const bool two = c->p.overlap && c->stream2;
+    if (two) {
+        if ((e = hipEventRecord(c->ev_fork, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
+        if ((e = hipStreamWaitEvent(c->stream2, c->ev_fork, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
+        if ((e = launch_attract(c, d_Y, c->stream2)) != hipSuccess) return fail_hip(c, e, "attract");
+        if ((e = hipEventRecord(c->ev_join, c->stream2)) != hipSuccess) return fail_hip(c, e, "event record");
+    }
+    if ((e = launch_tree_build(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "tree build");
+    if ((e = launch_walk(c, c->stream)) != hipSuccess) return fail_hip(c, e, "walk");
+    if (two) {
+        if ((e = hipStreamWaitEvent(c->stream, c->ev_join, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
+    } else {
+        if ((e = launch_attract(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "attract");
+    }
+    c->tree_valid = 1;
+    return TSNE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tsne_default_params(tsne_params *p, int32_t n)
+{
+    if (!p) return TSNE_EINVAL;
+    memset(p, 0, sizeof(*p));
+    p->n = n;
+    p->theta = 0.5f;
+    p->lr = 200.0f;
+    p->exaggeration = 12.0f;
+    p->exaggeration_iters = 250;
+    p->momentum_early = 0.5f;
+    p->momentum_late = 0.8f;
+    p->momentum_switch_iter = 250;
+    p->gain_inc = 0.2f;
+    p->gain_dec = 0.8f;
+    p->gain_min = 0.01f;
+    p->morton_bits = 16;
+    p->leaf_cap = 8;
+    p->overlap = 1;
+    return TSNE_OK;
+}
+
+int tsne_workspace_bytes(const tsne_params *p, size_t *bytes)
+{
+    int rc = check_params(p);
+    if (rc != TSNE_OK || !bytes) return TSNE_EINVAL;
+    *bytes = carve(nullptr, p, nullptr);
+    return TSNE_OK;
+}
+
+int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_workspace, size_t workspace_bytes)
+{
+    if (!out) return TSNE_EINVAL;
+    *out = nullptr;
+    int rc = check_params(p);
+    if (rc != TSNE_OK) return rc;
+    if (!d_workspace || ((uintptr_t)d_workspace % ALIGN) != 0) return TSNE_EINVAL;
+    if (workspace_bytes < carve(nullptr, p, nullptr)) return TSNE_ENOSPC;
+    tsne_ctx *c = new (std::nothrow) tsne_ctx();
+    if (!c) return TSNE_ENOSPC;
+    memset(c, 0, sizeof(*c));
+    c->p = *p;
+    c->stream = (hipStream_t)stream;
+    carve(c, p, (char *)d_workspace);
+    hipError_t e;
+    if (p->overlap) {
+        // default priority on purpose; non-blocking so that it does not serialise with stream 0
+        if ((e = hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming)) != hipSuccess) {
+            tsne_destroy(c);
+            return TSNE_EHIP;
+        }
+    }
+    if ((e = hipMemsetAsync(c->status, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
+        (e = hipMemsetAsync(c->ncells, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
+        (e = launch_fill_state(c, c->stream)) != hipSuccess) {
+        tsne_destroy(c);
+        return TSNE_EHIP;
+    }
+    *out = c;
+    return TSNE_OK;
+}
+
+void tsne_destroy(tsne_ctx *c)
+{
+    if (!c) return;
+    if (c->stream2) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    delete c;
+}
+
+int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, const float *d_val, int64_t nnz)
+{
+    if (!c) return TSNE_EINVAL;
+    if (!d_row_ptr || nnz < 0 || nnz > 0x7FFFFFFFll || (nnz > 0 && (!d_col || !d_val)))
+        return fail(c, TSNE_EINVAL, "tsne_set_P: null array or nnz out of range");
+    c->row_ptr = d_row_ptr; c->col = d_col; c->val = d_val; c->nnz = nnz;
+    c->have_P = 1;
+    return TSNE_OK;
+}
+
+int tsne_init_state(tsne_ctx *c)
+{
+    if (!c) return TSNE_EINVAL;
+    hipError_t e = launch_fill_state(c, c->stream);
+    return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "fill state");
+}
+
+int tsne_get_state(tsne_ctx *c, float *d_velocity, float *d_gains)
+{
+    if (!c || !d_velocity || !d_gains) return TSNE_EINVAL;
+    const size_t b = 8 * (size_t)c->p.n;
+    hipError_t e;
+    if ((e = hipMemcpyAsync(d_velocity, c->uY, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess ||
+        (e = hipMemcpyAsync(d_gains, c->gains, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess)
+        return fail_hip(c, e, "copy state");
+    return TSNE_OK;
+}
+
+int tsne_set_state(tsne_ctx *c, const float *d_velocity, const float *d_gains)
+{
+    if (!c || !d_velocity || !d_gains) return TSNE_EINVAL;
+    const size_t b = 8 * (size_t)c->p.n;
+    hipError_t e;
+    if ((e = hipMemcpyAsync(c->uY, d_velocity, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess ||
+        (e = hipMemcpyAsync(c->gains, d_gains, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess)
+        return fail_hip(c, e, "copy state");
+    return TSNE_OK;
+}
+
+int tsne_step(tsne_ctx *c, float *d_Y, int32_t iter)
+{
+    if (!c || !d_Y || iter < 0) return TSNE_EINVAL;
+    if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_step: no P (call tsne_set_P first)");
+    int rc = enqueue_forces(c, d_Y);
+    if (rc != TSNE_OK) return rc;
+    const float alpha = iter < c->p.exaggeration_iters ? c->p.exaggeration : 1.0f;
+    const float mom = iter < c->p.momentum_switch_iter ? c->p.momentum_early : c->p.momentum_late;
+    hipError_t e = launch_update(c, d_Y, alpha, mom, c->stream);
+    return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "update");
+}
+
+int tsne_status(tsne_ctx *c, uint32_t *status)
+{
+    if (!c || !status) return TSNE_EINVAL;
+    hipError_t e = hipMemcpyAsync(status, c->status, sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "status");
+}
+
+int tsne_run(tsne_ctx *c, float *d_Y, int32_t iter0, int32_t n_iter)
+{
+    if (!c || !d_Y || iter0 < 0 || n_iter < 0) return TSNE_EINVAL;
+    for (int32_t it = iter0; it < iter0 + n_iter; ++it) {
+        int rc = tsne_step(c, d_Y, it);
+        if (rc != TSNE_OK) return rc;
+    }
+    uint32_t st = 0;
+    int rc = tsne_status(c, &st);
+    if (rc != TSNE_OK) return rc;
+    if (st) {
+        snprintf(c->err, sizeof(c->err), "device status 0x%x", st);
+        return TSNE_ENUM;
+    }
+    return TSNE_OK;
+}
+
+int tsne_gradient(tsne_ctx *c, const float *d_Y, float *d_attr, float *d_rep, double *d_Z)
+{
+    if (!c || !d_Y) return TSNE_EINVAL;
+    if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_gradient: no P (call tsne_set_P first)");
+    int rc = enqueue_forces(c, d_Y);
+    if (rc != TSNE_OK) return rc;
+    const size_t b = 8 * (size_t)c->p.n;
+    hipError_t e = hipSuccess;
+    if (d_attr) e = hipMemcpyAsync(d_attr, c->A, b, hipMemcpyDeviceToDevice, c->stream);
+    if (e == hipSuccess && d_rep) e = hipMemcpyAsync(d_rep, c->R, b, hipMemcpyDeviceToDevice, c->stream);
+    if (e == hipSuccess && d_Z) e = hipMemcpyAsync(d_Z, c->Z, 8, hipMemcpyDeviceToDevice, c->stream);
+    return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "copy forces");
+}
+
+int tsne_export_tree(tsne_ctx *c, uint32_t *d_keys, int32_t *d_perm, int32_t cap_cells, int32_t *d_depth,
+                     int32_t *d_lo, int32_t *d_hi, int32_t *d_leaf, float *d_com, float *d_root, int32_t *n_cells)
+{
+    if (!c || cap_cells < 0) return TSNE_EINVAL;
+    if (!c->tree_valid) return fail(c, TSNE_ESTATE, "tsne_export_tree: no tree built yet");
+    const size_t n = (size_t)c->p.n;
+    hipError_t e = hipSuccess;
+    if (d_keys) e = hipMemcpyAsync(d_keys, c->keys_orig, 4 * n, hipMemcpyDeviceToDevice, c->stream);
+    if (e == hipSuccess && d_perm)
+        e = hipMemcpyAsync(d_perm, c->idx[c->sorted_buf], 4 * n, hipMemcpyDeviceToDevice, c->stream);
+    if (e == hipSuccess && d_root) e = hipMemcpyAsync(d_root, c->root, 12, hipMemcpyDeviceToDevice, c->stream);
+    if (e == hipSuccess) e = launch_export_cells(c, cap_cells, d_depth, d_lo, d_hi, d_leaf, d_com, c->stream);
+    uint32_t m = 0;
+    if (e == hipSuccess) e = hipMemcpyAsync(&m, c->ncells, 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "export tree");
+    if (n_cells) *n_cells = (int32_t)m;
+    if ((int64_t)m > (int64_t)c->cap_cells) return fail(c, TSNE_ENUM, "tree needed more cells than the workspace holds");
+    if ((int64_t)m > (int64_t)cap_cells && (d_depth || d_lo || d_hi || d_leaf || d_com))
+        return fail(c, TSNE_ENOSPC, "tsne_export_tree: cap_cells too small");
+    return TSNE_OK;
+}
+
+int tsne_kl(tsne_ctx *c, const float *d_Y, double *kl)
+{
+    if (!c || !d_Y || !kl) return TSNE_EINVAL;
+    if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_kl: no P");
+    hipError_t e = launch_kl(c, d_Y, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(kl, c->kl_part, 8, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "kl");
+}
+
+const char *tsne_strerror(int code)
+{
+    switch (code) {
+    case TSNE_OK: return "ok";
+    case TSNE_EINVAL: return "invalid argument";
+    case TSNE_ENOSPC: return "workspace or output capacity too small";
+    case TSNE_EHIP: return "HIP runtime error";
+    case TSNE_ESTATE: return "call out of order";
+    case TSNE_ENUM: return "numerical trouble reported by the device";
+    default: return "unknown error";
+    }
+}
+
+const char *tsne_last_error(const tsne_ctx *c) { return c ? c->err : ""; }
+
+}  // extern "C"

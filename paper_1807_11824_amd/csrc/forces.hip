@@ -1,0 +1,177 @@
+// Attractive forces over the sparse P (Eq. (5), Alg. 1 lines 6-7 fused: P.Q is never stored),
+// the update of the embedding (Alg. 1 line 8) and the exact-Z KL utility.
+#include "tsne_internal.h"
+
+#include <math.h>
+
+// A_i = sum_j p_ij w_ij (y_i - y_j), w_ij = 1/(1+|y_i-y_j|^2).  LPR lanes share one CSR row:
+// col/val are read as contiguous segments, y_j is an 8-byte gather, and the two partial sums
+// are combined with xor-shuffles inside the LPR-lane group.  No atomics: the result is
+// deterministic.
+template <int LPR>
+__global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col,
+                                                   const float *__restrict__ val, const float2 *__restrict__ Y, int n,
+                                                   float2 *__restrict__ A)
+{
+    const int row = (int)((blockIdx.x * 256u + threadIdx.x) / LPR);
+    const int sub = (int)(threadIdx.x % LPR);
+    float ax = 0.f, ay = 0.f;
+    if (row < n) {
+        const int s = row_ptr[row], e = row_ptr[row + 1];
+        const float2 yi = Y[row];
+        for (int j = s + sub; j < e; j += LPR) {
+            const int c = col[j];
+            const float v = val[j];
+            const float2 yj = Y[c];
+            const float dx = yi.x - yj.x, dy = yi.y - yj.y;
+            const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+            const float pw = v * w;
+            ax = fmaf(pw, dx, ax);
+            ay = fmaf(pw, dy, ay);
+        }
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) {
+        ax += __shfl_xor(ax, o, WAVE);
+        ay += __shfl_xor(ay, o, WAVE);
+    }
+    if (row < n && sub == 0) A[row] = make_float2(ax, ay);
+}
+
+hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s)
+{
+    constexpr int LPR = 16;
+    const int n = c->p.n;
+    const unsigned blocks = (unsigned)(((int64_t)n * LPR + 255) / 256);
+    hipLaunchKernelGGL(attract_csr<LPR>, dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val,
+                       (const float2 *)d_Y, n, c->A);
+    return hipGetLastError();
+}
+
+// Alg. 1 line 8.  grad = 4 (alpha A - R / Z) (Eq. (7)); per coordinate the gain grows by
+// gain_inc when gradient and velocity differ in sign (sign in {-1,0,+1}) and is multiplied by
+// gain_dec otherwise, floored at gain_min; velocity = momentum velocity - lr gain grad;
+// y += velocity.
+__device__ __forceinline__ int sign3(float v) { return v > 0.f ? 1 : (v < 0.f ? -1 : 0); }
+
+__global__ __launch_bounds__(256) void update_k(float *__restrict__ Y, float *__restrict__ uY, float *__restrict__ gains,
+                                                const float *__restrict__ A, const float *__restrict__ R,
+                                                const double *__restrict__ Z, int n2, float alpha, float momentum,
+                                                float lr, float gain_inc, float gain_dec, float gain_min)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= n2) return;
+    const float invZ = (float)(1.0 / *Z);
+    const float grad = 4.0f * (alpha * A[c] - R[c] * invZ);
+    float g = gains[c], u = uY[c];
+    g = (sign3(grad) != sign3(u)) ? g + gain_inc : g * gain_dec;
+    g = fmaxf(g, gain_min);
+    u = momentum * u - lr * g * grad;
+    gains[c] = g;
+    uY[c] = u;
+    Y[c] += u;
+}
+
+hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s)
+{
+    const int n2 = 2 * c->p.n;
+    hipLaunchKernelGGL(update_k, dim3((n2 + 255) / 256), dim3(256), 0, s, d_Y, (float *)c->uY, (float *)c->gains,
+                       (const float *)c->A, (const float *)c->R, c->Z, n2, alpha, momentum, c->p.lr, c->p.gain_inc,
+                       c->p.gain_dec, c->p.gain_min);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_state_k(float *__restrict__ uY, float *__restrict__ gains, int n2)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < n2) { uY[c] = 0.f; gains[c] = 1.f; }
+}
+
+hipError_t launch_fill_state(tsne_ctx *c, hipStream_t s)
+{
+    const int n2 = 2 * c->p.n;
+    hipLaunchKernelGGL(fill_state_k, dim3((n2 + 255) / 256), dim3(256), 0, s, (float *)c->uY, (float *)c->gains, n2);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ KL with exact Z (harness utility)
+// Z of Eq. (4) over all ordered pairs: tile j through LDS, accumulate in double per block.
+constexpr int KL_BLOCKS = 1024;
+
+__global__ __launch_bounds__(256) void exact_z_k(const float2 *__restrict__ Y, int n, double *__restrict__ part)
+{
+    __shared__ float2 tile[256];
+    __shared__ double ws[4];
+    double acc = 0.0;
+    for (int i0 = blockIdx.x * 256; i0 < n; i0 += gridDim.x * 256) {
+        const int i = i0 + threadIdx.x;
+        const float2 yi = Y[i < n ? i : 0];
+        float z = 0.f;
+        for (int j0 = 0; j0 < n; j0 += 256) {
+            __syncthreads();
+            const int j = j0 + threadIdx.x;
+            tile[threadIdx.x] = j < n ? Y[j] : make_float2(INFINITY, INFINITY);   // w = 0
+            __syncthreads();
+            float zt = 0.f;
+#pragma unroll 8
+            for (int t = 0; t < 256; ++t) {
+                const float dx = yi.x - tile[t].x, dy = yi.y - tile[t].y;
+                zt += 1.0f / (fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+            }
+            z += zt;
+        }
+        if (i < n) acc += (double)z - 1.0;   // the j = i term contributed exactly 1
+    }
+    acc = wave_sum(acc);
+    if (lane_id() == 0) ws[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = ws[0] + ws[1] + ws[2] + ws[3];
+}
+
+// sum over stored entries of p ln(p (1+d^2)); rows over a grid-stride loop
+__global__ __launch_bounds__(256) void kl_terms_k(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col,
+                                                  const float *__restrict__ val, const float2 *__restrict__ Y, int n,
+                                                  double *__restrict__ part_t, double *__restrict__ part_p)
+{
+    __shared__ double ws[4], wp[4];
+    double t = 0.0, ps = 0.0;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
+        const float2 yi = Y[i];
+        for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            const double pv = (double)val[e];
+            if (!(pv > 0.0)) continue;
+            const float2 yj = Y[col[e]];
+            const double dx = (double)yi.x - (double)yj.x, dy = (double)yi.y - (double)yj.y;
+            t += pv * log(pv * (1.0 + dx * dx + dy * dy));
+            ps += pv;
+        }
+    }
+    t = wave_sum(t); ps = wave_sum(ps);
+    if (lane_id() == 0) { ws[threadIdx.x >> 6] = t; wp[threadIdx.x >> 6] = ps; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        part_t[blockIdx.x] = ws[0] + ws[1] + ws[2] + ws[3];
+        part_p[blockIdx.x] = wp[0] + wp[1] + wp[2] + wp[3];
+    }
+}
+
+// KL = sum p ln(p/q) = sum p ln(p (1+d^2)) + ln Z sum p
+__global__ void kl_final_k(double *__restrict__ part, int nb)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double Z = 0.0, t = 0.0, ps = 0.0;
+    for (int i = 0; i < nb; ++i) { Z += part[i]; t += part[nb + i]; ps += part[2 * nb + i]; }
+    part[0] = t + log(Z) * ps;
+    part[1] = Z;
+}
+
+hipError_t launch_kl(tsne_ctx *c, const float *d_Y, hipStream_t s)
+{
+    const int n = c->p.n;
+    const float2 *Y = (const float2 *)d_Y;
+    hipLaunchKernelGGL(exact_z_k, dim3(KL_BLOCKS), dim3(256), 0, s, Y, n, c->kl_part);
+    hipLaunchKernelGGL(kl_terms_k, dim3(KL_BLOCKS), dim3(256), 0, s, c->row_ptr, c->col, c->val, Y, n,
+                       c->kl_part + KL_BLOCKS, c->kl_part + 2 * KL_BLOCKS);
+    hipLaunchKernelGGL(kl_final_k, dim3(1), dim3(64), 0, s, c->kl_part, KL_BLOCKS);
+    return hipGetLastError();
+}

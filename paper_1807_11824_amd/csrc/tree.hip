@@ -1,0 +1,551 @@
+// Sec. III-C steps 1-4 of the paper on gfx950: bounding box, grid keys, spatial sort,
+// quad tree and cell summaries.  Nothing here walks pointers or inserts points one by one:
+// the tree is read off the sorted keys.
+//
+//   bbox_partial / bbox_final   step 1   min/max reduction -> root square (power-of-two side)
+//   morton_encode               step 2a  16-bit grid coordinates, bit-interleaved key
+//   radix_hist / _scan / _scatter  step 4  stable LSD radix sort of (key, index), 8 bits a pass
+//   gather_levels               step 2b  which cells start at each sorted position
+//   scan_partials / downsweep   step 3   prefix sums: cell numbering and running coordinate sums
+//   write_cells                 steps 2c+3  cell records: members, count, centre of mass, children
+//
+// A cell at depth t is the run of sorted positions sharing the top 2t key bits.  A position p
+// opens cells at depths tmin(p).. where tmin is fixed by the first digit in which key[p] differs
+// from key[p-1]; the chain stops at the first depth whose parent holds <= leaf_cap points.
+// Numbering cells by (position, depth) is exactly depth-first pre-order, so one scalar prefix
+// sum over "cells opened at p" numbers the whole tree, and the centre of mass of any cell is a
+// difference of two entries of the double-precision running sum of the sorted coordinates.
+#include "tsne_internal.h"
+
+#include <math.h>
+
+// ------------------------------------------------------------------ bounding box
+__global__ __launch_bounds__(256) void bbox_partial(const float2 *__restrict__ Y, int n,
+                                                    float4 *__restrict__ part, uint32_t *status)
+{
+    float mnx = INFINITY, mny = INFINITY, mxx = -INFINITY, mxy = -INFINITY;
+    bool bad = false;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        float2 y = Y[i];
+        bad |= !(isfinite(y.x) && isfinite(y.y));
+        mnx = fminf(mnx, y.x); mxx = fmaxf(mxx, y.x);
+        mny = fminf(mny, y.y); mxy = fmaxf(mxy, y.y);
+    }
+    mnx = wave_min(mnx); mny = wave_min(mny); mxx = wave_max(mxx); mxy = wave_max(mxy);
+    __shared__ float4 smn[4], smx[4];
+    int w = threadIdx.x >> 6;
+    if (lane_id() == 0) { smn[w] = make_float4(mnx, mny, 0, 0); smx[w] = make_float4(mxx, mxy, 0, 0); }
+    if (__any(bad) && lane_id() == 0) atomicOr(status, TSNE_STATUS_NONFINITE);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k) {
+            mnx = fminf(mnx, smn[k].x); mny = fminf(mny, smn[k].y);
+            mxx = fmaxf(mxx, smx[k].x); mxy = fmaxf(mxy, smx[k].y);
+        }
+        part[2 * blockIdx.x] = make_float4(mnx, mny, 0, 0);
+        part[2 * blockIdx.x + 1] = make_float4(mxx, mxy, 0, 0);
+    }
+}
+
+// Root square: lower corner (min x, min y); side = smallest power of two >= the larger extent,
+// at least 2^-40; scale S = 2^bits / side (an exact power of two).
+__global__ __launch_bounds__(256) void bbox_final(const float4 *__restrict__ part, int nparts, int bits,
+                                                  float4 *__restrict__ root, uint32_t *status)
+{
+    float mnx = INFINITY, mny = INFINITY, mxx = -INFINITY, mxy = -INFINITY;
+    for (int i = threadIdx.x; i < nparts; i += blockDim.x) {
+        float4 a = part[2 * i], b = part[2 * i + 1];
+        mnx = fminf(mnx, a.x); mny = fminf(mny, a.y);
+        mxx = fmaxf(mxx, b.x); mxy = fmaxf(mxy, b.y);
+    }
+    mnx = wave_min(mnx); mny = wave_min(mny); mxx = wave_max(mxx); mxy = wave_max(mxy);
+    __shared__ float4 smn[4], smx[4];
+    int w = threadIdx.x >> 6;
+    if (lane_id() == 0) { smn[w] = make_float4(mnx, mny, 0, 0); smx[w] = make_float4(mxx, mxy, 0, 0); }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k) {
+            mnx = fminf(mnx, smn[k].x); mny = fminf(mny, smn[k].y);
+            mxx = fmaxf(mxx, smx[k].x); mxy = fmaxf(mxy, smx[k].y);
+        }
+        float ex = mxx - mnx, ey = mxy - mny;
+        float e = fmaxf(ex, ey);
+        float W = ldexpf(1.0f, -40);
+        if (!isfinite(e) || !isfinite(mnx) || !isfinite(mny)) {
+            atomicOr(status, TSNE_STATUS_NONFINITE);
+            mnx = 0.0f; mny = 0.0f; W = 1.0f;
+        } else if (e > W) {
+            int ex2;
+            float m = frexpf(e, &ex2);          // e = m 2^ex2, m in [0.5, 1)
+            W = (m == 0.5f) ? e : ldexpf(1.0f, ex2);
+        }
+        float S = ldexpf(1.0f, bits) / W;
+        *root = make_float4(mnx, mny, W, S);
+    }
+}
+
+// ------------------------------------------------------------------ grid keys
+__device__ __forceinline__ uint32_t spread16(uint32_t v)
+{
+    v &= 0xFFFFu;
+    v = (v | (v << 8)) & 0x00FF00FFu;
+    v = (v | (v << 4)) & 0x0F0F0F0Fu;
+    v = (v | (v << 2)) & 0x33333333u;
+    v = (v | (v << 1)) & 0x55555555u;
+    return v;
+}
+
+// One rounding per operation: the subtraction rounds, the product with a power of two is exact.
+__device__ __forceinline__ uint32_t grid_coord(float v, float origin, float S, uint32_t qmax)
+{
+#pragma clang fp contract(off)
+    float r = v - origin;
+    float s = r * S;
+    float f = floorf(s);
+    return f >= (float)qmax ? qmax : (f > 0.0f ? (uint32_t)f : 0u);
+}
+
+__global__ __launch_bounds__(256) void morton_encode(const float2 *__restrict__ Y, int n,
+                                                     const float4 *__restrict__ root, int bits,
+                                                     uint32_t *__restrict__ keys_orig,
+                                                     uint32_t *__restrict__ keys, uint32_t *__restrict__ idx)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float4 r = *root;
+    float2 y = Y[i];
+    uint32_t qmax = (1u << bits) - 1u;
+    uint32_t qx = grid_coord(y.x, r.x, r.w, qmax);
+    uint32_t qy = grid_coord(y.y, r.y, r.w, qmax);
+    uint32_t key = spread16(qx) | (spread16(qy) << 1);
+    keys_orig[i] = key;
+    keys[i] = key;
+    idx[i] = (uint32_t)i;
+}
+
+// ------------------------------------------------------------------ radix sort (stable, LSD, 8 bits)
+// hist layout: hist[digit * nblk + block].
+__global__ __launch_bounds__(SORT_THREADS) void radix_hist(const uint32_t *__restrict__ keys, int n, int shift,
+                                                           uint32_t *__restrict__ hist, int nblk)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    int base = blockIdx.x * SORT_TILE;
+#pragma unroll
+    for (int r = 0; r < SORT_ITEMS; ++r) {
+        int e = base + r * SORT_THREADS + threadIdx.x;
+        if (e < n) atomicAdd(&h[(keys[e] >> shift) & 0xFFu], 1u);
+    }
+    __syncthreads();
+    hist[threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+// Block d turns hist[d][0..nblk) into its exclusive prefix and stores the digit total.
+__global__ __launch_bounds__(256) void radix_scan(uint32_t *__restrict__ hist, int nblk, uint32_t *__restrict__ dtot)
+{
+    __shared__ uint32_t wsum[4];
+    uint32_t *row = hist + (size_t)blockIdx.x * nblk;
+    uint32_t carry = 0;
+    int w = threadIdx.x >> 6;
+    for (int b0 = 0; b0 < nblk; b0 += 256) {
+        int b = b0 + threadIdx.x;
+        int v = b < nblk ? (int)row[b] : 0;
+        int tot;
+        int ex = wave_excl_scan(v, &tot);
+        if (lane_id() == 0) wsum[w] = (uint32_t)tot;
+        __syncthreads();
+        uint32_t wbase = 0, all = 0;
+        for (int k = 0; k < 4; ++k) { if (k < w) wbase += wsum[k]; all += wsum[k]; }
+        if (b < nblk) row[b] = carry + wbase + (uint32_t)ex;
+        carry += all;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) dtot[blockIdx.x] = carry;
+}
+
+__global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint32_t *__restrict__ keys_in,
+                                                              const uint32_t *__restrict__ idx_in,
+                                                              uint32_t *__restrict__ keys_out,
+                                                              uint32_t *__restrict__ idx_out, int n, int shift,
+                                                              const uint32_t *__restrict__ hist,
+                                                              const uint32_t *__restrict__ dtot, int nblk)
+{
+    __shared__ uint32_t whist[4][256];   // per-wave running digit counts
+    __shared__ uint32_t gbase[256];      // global start of (digit, this block)
+    __shared__ uint32_t dscan[256];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    for (int k = 0; k < 4; ++k) whist[k][tid] = 0;
+    // exclusive scan of the 256 digit totals
+    {
+        int v = (int)dtot[tid], tot;
+        int ex = wave_excl_scan(v, &tot);
+        if (lane == 0) dscan[w] = (uint32_t)tot;
+        __syncthreads();
+        uint32_t wb = 0;
+        for (int k = 0; k < w; ++k) wb += dscan[k];
+        __syncthreads();
+        gbase[tid] = wb + (uint32_t)ex + hist[tid * nblk + blockIdx.x];
+    }
+    __syncthreads();
+    const int base = blockIdx.x * SORT_TILE + w * (WAVE * SORT_ITEMS);
+    uint32_t key[SORT_ITEMS], rank[SORT_ITEMS];
+#pragma unroll
+    for (int r = 0; r < SORT_ITEMS; ++r) {
+        int e = base + r * WAVE + lane;
+        bool valid = e < n;
+        key[r] = valid ? keys_in[e] : 0u;
+        uint32_t d = (key[r] >> shift) & 0xFFu;
+        // lanes of this round holding the same digit
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            uint64_t bal = __ballot((d >> b) & 1u);
+            peers &= ((d >> b) & 1u) ? bal : ~bal;
+        }
+        uint32_t before = (uint32_t)__popcll(peers & lanemask_lt());
+        uint32_t pre = whist[w][d];
+        rank[r] = pre + before;
+        __syncthreads();
+        if (valid && before == 0) whist[w][d] = pre + (uint32_t)__popcll(peers);
+        __syncthreads();
+    }
+    // start of each wave's share inside the block's run of a digit
+    {
+        uint32_t c0 = whist[0][tid], c1 = whist[1][tid], c2 = whist[2][tid];
+        __syncthreads();
+        whist[0][tid] = 0; whist[1][tid] = c0; whist[2][tid] = c0 + c1; whist[3][tid] = c0 + c1 + c2;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < SORT_ITEMS; ++r) {
+        int e = base + r * WAVE + lane;
+        if (e < n) {
+            uint32_t d = (key[r] >> shift) & 0xFFu;
+            uint32_t pos = gbase[d] + whist[w][d] + rank[r];
+            keys_out[pos] = key[r];
+            idx_out[pos] = idx_in[e];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ cells opened at each position
+// Sorted keys: the positions whose key shifted right by sh equals pre form one contiguous run.
+__device__ __forceinline__ uint32_t run_end(const uint32_t *__restrict__ keys, uint32_t n, uint32_t p, int sh,
+                                            uint32_t pre)
+{
+    uint32_t lo = p, hi, step = 1;
+    for (;;) {
+        uint64_t cand = (uint64_t)p + step;
+        if (cand >= n) { hi = n; break; }
+        if ((keys[cand] >> sh) != pre) { hi = (uint32_t)cand; break; }
+        lo = (uint32_t)cand;
+        step <<= 1;
+    }
+    while (hi - lo > 1) {
+        uint32_t mid = lo + ((hi - lo) >> 1);
+        if ((keys[mid] >> sh) != pre) hi = mid; else lo = mid;
+    }
+    return hi;
+}
+
+__device__ __forceinline__ uint32_t run_begin(const uint32_t *__restrict__ keys, uint32_t p, int sh, uint32_t pre)
+{
+    int64_t lo, hi = p, step = 1;
+    for (;;) {
+        int64_t cand = (int64_t)p - step;
+        if (cand < 0) { lo = -1; break; }
+        if ((keys[cand] >> sh) != pre) { lo = cand; break; }
+        hi = cand;
+        step <<= 1;
+    }
+    while (hi - lo > 1) {
+        int64_t mid = lo + ((hi - lo) >> 1);
+        if ((keys[mid] >> sh) != pre) lo = mid; else hi = mid;
+    }
+    return (uint32_t)hi;
+}
+
+// Depths [tmin, tend) of the cells that start at sorted position p.
+__device__ __forceinline__ void levels_at(const uint32_t *__restrict__ keys, uint32_t n, uint32_t p, int B,
+                                          uint32_t C, int *tmin_out, int *tend_out)
+{
+    uint32_t key = keys[p];
+    int tmin;
+    if (p == 0) tmin = 0;
+    else {
+        uint32_t x = key ^ keys[p - 1];
+        tmin = x ? B - ((31 - __clz((int)x)) >> 1) : B + 1;
+    }
+    int tend = tmin;
+    if (tmin <= B) {
+        uint32_t pc;   // number of points in the parent of the candidate cell
+        if (tmin == 0) pc = 0xFFFFFFFFu;
+        else if (tmin == 1) pc = n;
+        else {
+            int sh = 2 * (B - (tmin - 1));
+            uint32_t pre = key >> sh;
+            pc = run_end(keys, n, p, sh, pre) - run_begin(keys, p, sh, pre);
+        }
+        int t = tmin;
+        while (t <= B && pc > C) {
+            tend = t + 1;
+            if (t == 0) pc = n;
+            else {
+                int sh = 2 * (B - t);
+                pc = run_end(keys, n, p, sh, key >> sh) - p;
+            }
+            ++t;
+        }
+    }
+    *tmin_out = tmin;
+    *tend_out = tend;
+}
+
+// Also moves the points into spatial order (step 4) and reduces each tile's (cells, sum x, sum y).
+__global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__restrict__ Y,
+                                                               const uint32_t *__restrict__ keys,
+                                                               const uint32_t *__restrict__ perm, int n, int B, int C,
+                                                               float2 *__restrict__ Ys, uint16_t *__restrict__ lev,
+                                                               ScanPart *__restrict__ part)
+{
+    __shared__ double sx[4], sy[4];
+    __shared__ uint32_t sc[4];
+    int p0 = blockIdx.x * LEVEL_TILE + threadIdx.x * LEVEL_ITEMS;
+    double ax = 0.0, ay = 0.0;
+    uint32_t ac = 0;
+#pragma unroll
+    for (int k = 0; k < LEVEL_ITEMS; ++k) {
+        int p = p0 + k;
+        if (p < n) {
+            float2 y = Y[min(perm[p], (uint32_t)n - 1u)];
+            Ys[p] = y;
+            ax += (double)y.x; ay += (double)y.y;
+            int tmin, tend;
+            levels_at(keys, (uint32_t)n, (uint32_t)p, B, (uint32_t)C, &tmin, &tend);
+            lev[p] = (uint16_t)(tmin | (tend << 8));
+            ac += (uint32_t)(tend - tmin);
+        }
+    }
+    ax = wave_sum(ax); ay = wave_sum(ay); ac = wave_sum(ac);
+    int w = threadIdx.x >> 6;
+    if (lane_id() == 0) { sx[w] = ax; sy[w] = ay; sc[w] = ac; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        ScanPart q;
+        q.sx = ((sx[0] + sx[1]) + sx[2]) + sx[3];
+        q.sy = ((sy[0] + sy[1]) + sy[2]) + sy[3];
+        q.cnt = sc[0] + sc[1] + sc[2] + sc[3];
+        q.pad = 0;
+        part[blockIdx.x] = q;
+    }
+}
+
+// One block: exclusive prefix over the tile partials; total cell count to *ncells.
+__global__ __launch_bounds__(1024) void scan_partials(ScanPart *__restrict__ part, int nparts,
+                                                      uint32_t *__restrict__ ncells, uint32_t cap_cells,
+                                                      uint32_t *status)
+{
+    __shared__ double wx[16], wy[16];
+    __shared__ uint32_t wc[16];
+    const int tid = threadIdx.x, w = tid >> 6;
+    const int per = (nparts + 1023) / 1024;
+    const int s = tid * per, e = min(nparts, s + per);
+    double ax = 0.0, ay = 0.0;
+    uint32_t ac = 0;
+    for (int i = s; i < e; ++i) { ax += part[i].sx; ay += part[i].sy; ac += part[i].cnt; }
+    // inclusive scan across the wave, then across the 16 waves
+    double ix = ax, iy = ay;
+    uint32_t icn = ac;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        double tx = __shfl_up(ix, o, WAVE), ty = __shfl_up(iy, o, WAVE);
+        uint32_t tc = __shfl_up(icn, o, WAVE);
+        if (lane_id() >= o) { ix += tx; iy += ty; icn += tc; }
+    }
+    if (lane_id() == WAVE - 1) { wx[w] = ix; wy[w] = iy; wc[w] = icn; }
+    __syncthreads();
+    double bx = 0.0, by = 0.0;
+    uint32_t bc = 0;
+    for (int k = 0; k < w; ++k) { bx += wx[k]; by += wy[k]; bc += wc[k]; }
+    double px = bx + (ix - ax), py = by + (iy - ay);   // exclusive prefix of this thread's first item
+    uint32_t pc = bc + (icn - ac);
+    for (int i = s; i < e; ++i) {
+        ScanPart q = part[i];
+        ScanPart o;
+        o.sx = px; o.sy = py; o.cnt = pc; o.pad = 0;
+        part[i] = o;
+        px += q.sx; py += q.sy; pc += q.cnt;
+    }
+    if (tid == 1023) {
+        // thread 1023 holds the grand total whether or not it owned items
+        *ncells = pc;
+        if (pc > cap_cells) atomicOr(status, TSNE_STATUS_CELL_OVERFLOW);
+    }
+}
+
+// Per position: index of the first cell opened there, and the running sums of the sorted
+// coordinates (ps[p] = sum of Ys[0..p), ps[n] = total).
+__global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restrict__ Ys,
+                                                           const uint16_t *__restrict__ lev, int n,
+                                                           const ScanPart *__restrict__ part,
+                                                           uint32_t *__restrict__ cellseq, double2 *__restrict__ ps)
+{
+    __shared__ double wx[4], wy[4];
+    __shared__ uint32_t wc[4];
+    const int tid = threadIdx.x, w = tid >> 6;
+    int p0 = blockIdx.x * LEVEL_TILE + tid * LEVEL_ITEMS;
+    float2 y[LEVEL_ITEMS];
+    uint32_t c[LEVEL_ITEMS];
+    double ax = 0.0, ay = 0.0;
+    uint32_t ac = 0;
+#pragma unroll
+    for (int k = 0; k < LEVEL_ITEMS; ++k) {
+        int p = p0 + k;
+        if (p < n) {
+            y[k] = Ys[p];
+            uint32_t l = lev[p];
+            c[k] = (l >> 8) - (l & 0xFFu);
+        } else { y[k] = make_float2(0.f, 0.f); c[k] = 0; }
+        ax += (double)y[k].x; ay += (double)y[k].y; ac += c[k];
+    }
+    double ix = ax, iy = ay;
+    uint32_t icn = ac;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        double tx = __shfl_up(ix, o, WAVE), ty = __shfl_up(iy, o, WAVE);
+        uint32_t tc = __shfl_up(icn, o, WAVE);
+        if (lane_id() >= o) { ix += tx; iy += ty; icn += tc; }
+    }
+    if (lane_id() == WAVE - 1) { wx[w] = ix; wy[w] = iy; wc[w] = icn; }
+    __syncthreads();
+    ScanPart b = part[blockIdx.x];
+    double px = b.sx, py = b.sy;
+    uint32_t pc = b.cnt;
+    for (int k = 0; k < w; ++k) { px += wx[k]; py += wy[k]; pc += wc[k]; }
+    px += ix - ax; py += iy - ay; pc += icn - ac;
+#pragma unroll
+    for (int k = 0; k < LEVEL_ITEMS; ++k) {
+        int p = p0 + k;
+        if (p < n) {
+            cellseq[p] = pc;
+            ps[p] = make_double2(px, py);
+            px += (double)y[k].x; py += (double)y[k].y; pc += c[k];
+            if (p == n - 1) { cellseq[n] = pc; ps[n] = make_double2(px, py); }
+        }
+    }
+}
+
+// First position in [s, e) whose digit (2 bits at sh) is >= q; e if none.
+__device__ __forceinline__ uint32_t digit_lower_bound(const uint32_t *__restrict__ keys, uint32_t s, uint32_t e,
+                                                      int sh, uint32_t q)
+{
+    while (s < e) {
+        uint32_t mid = s + ((e - s) >> 1);
+        if (((keys[mid] >> sh) & 3u) < q) s = mid + 1; else e = mid;
+    }
+    return s;
+}
+
+__global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ keys, const uint16_t *__restrict__ lev,
+                                                   const uint32_t *__restrict__ cellseq,
+                                                   const double2 *__restrict__ ps, int n, int B, int C,
+                                                   Cell *__restrict__ cells, uint32_t cap_cells)
+{
+    uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= (uint32_t)n) return;
+    uint32_t l = lev[p];
+    int tmin = (int)(l & 0xFFu), tend = (int)(l >> 8);
+    if (tend <= tmin) return;
+    uint32_t key = keys[p];
+    uint32_t id0 = cellseq[p];
+    double2 s0 = ps[p];
+    for (int t = tmin; t < tend; ++t) {
+        uint32_t id = id0 + (uint32_t)(t - tmin);
+        if (id >= cap_cells) return;
+        uint32_t e = (t == 0) ? (uint32_t)n : run_end(keys, (uint32_t)n, p, 2 * (B - t), key >> (2 * (B - t)));
+        uint32_t cnt = e - p;
+        double2 s1 = ps[e];
+        Cell c;
+        c.cx = (float)((s1.x - s0.x) / (double)cnt);
+        c.cy = (float)((s1.y - s0.y) / (double)cnt);
+        c.cnt = cnt;
+        bool leaf = cnt <= (uint32_t)C || t == B;
+        c.meta = (uint32_t)t | (leaf ? 0x100u : 0u);
+        c.lo = p;
+        c.c1 = c.c2 = c.c3 = TSNE_NONE;
+        if (!leaf) {
+            int sh = 2 * (B - t - 1);
+            uint32_t kids[3];
+            int nk = 0;
+            uint32_t s = p;
+            uint32_t qfirst = (keys[p] >> sh) & 3u;
+            for (uint32_t q = qfirst + 1; q < 4; ++q) {
+                uint32_t b = digit_lower_bound(keys, s, e, sh, q);
+                if (b < e && ((keys[b] >> sh) & 3u) == q) kids[nk++] = cellseq[b];
+                s = b;
+            }
+            if (nk > 0) c.c1 = kids[0];
+            if (nk > 1) c.c2 = kids[1];
+            if (nk > 2) c.c3 = kids[2];
+        }
+        cells[id] = c;
+    }
+}
+
+// ------------------------------------------------------------------ export (tests only)
+__global__ void export_cells_k(const Cell *__restrict__ cells, const uint32_t *__restrict__ ncells, int cap,
+                               int32_t *depth, int32_t *lo, int32_t *hi, int32_t *leaf, float *com)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    int m = (int)min(*ncells, (uint32_t)cap);
+    if (i >= m) return;
+    Cell c = cells[i];
+    if (depth) depth[i] = (int32_t)(c.meta & 0xFFu);
+    if (lo) lo[i] = (int32_t)c.lo;
+    if (hi) hi[i] = (int32_t)(c.lo + c.cnt);
+    if (leaf) leaf[i] = (int32_t)((c.meta >> 8) & 1u);
+    if (com) { com[2 * i] = c.cx; com[2 * i + 1] = c.cy; }
+}
+
+hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t *lo, int32_t *hi, int32_t *leaf,
+                               float *com, hipStream_t s)
+{
+    if (cap <= 0) return hipSuccess;
+    int m = cap < c->cap_cells ? cap : c->cap_cells;
+    hipLaunchKernelGGL(export_cells_k, dim3((m + 255) / 256), dim3(256), 0, s, c->cells, c->ncells, m, depth, lo, hi,
+                       leaf, com);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ host: enqueue the whole build
+hipError_t launch_tree_build(tsne_ctx *c, const float *d_Y, hipStream_t s)
+{
+    const int n = c->p.n, B = c->p.morton_bits, C = c->p.leaf_cap;
+    const float2 *Y = (const float2 *)d_Y;
+    int nb = (n + 255) / 256;
+    int bb = nb < BBOX_MAX_BLOCKS ? nb : BBOX_MAX_BLOCKS;
+    hipLaunchKernelGGL(bbox_partial, dim3(bb), dim3(256), 0, s, Y, n, c->bbox_part, c->status);
+    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(256), 0, s, c->bbox_part, bb, B, c->root, c->status);
+    hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],
+                       c->idx[0]);
+    int nblk = (n + SORT_TILE - 1) / SORT_TILE;
+    int cur = 0;
+    for (int shift = 0; shift < 2 * B; shift += 8) {
+        hipLaunchKernelGGL(radix_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, c->keys[cur], n, shift, c->hist, nblk);
+        hipLaunchKernelGGL(radix_scan, dim3(256), dim3(256), 0, s, c->hist, nblk, c->dtot);
+        hipLaunchKernelGGL(radix_scatter, dim3(nblk), dim3(SORT_THREADS), 0, s, c->keys[cur], c->idx[cur],
+                           c->keys[cur ^ 1], c->idx[cur ^ 1], n, shift, c->hist, c->dtot, nblk);
+        cur ^= 1;
+    }
+    c->sorted_buf = cur;
+    int nl = (n + LEVEL_TILE - 1) / LEVEL_TILE;
+    hipLaunchKernelGGL(gather_levels, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B, C,
+                       c->Ys, c->lev, c->part);
+    hipLaunchKernelGGL(scan_partials, dim3(1), dim3(1024), 0, s, c->part, nl, c->ncells, (uint32_t)c->cap_cells,
+                       c->status);
+    hipLaunchKernelGGL(downsweep, dim3(nl), dim3(LEVEL_THREADS), 0, s, c->Ys, c->lev, n, c->part, c->cellseq, c->ps);
+    hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, c->keys[cur], c->lev, c->cellseq, c->ps, n, B, C,
+                       c->cells, (uint32_t)c->cap_cells);
+    return hipGetLastError();
+}

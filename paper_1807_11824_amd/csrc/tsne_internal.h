@@ -1,0 +1,121 @@
+// Internal declarations shared by the HIP translation units of the library.
+// gfx950 only: wavefronts are 64 lanes wide and the code relies on it.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tsne.h"
+
+#define TSNE_NONE 0xFFFFFFFFu
+#define WAVE 64
+
+// One quad-tree cell, 32 bytes so that a lane fetches it with two 16-byte loads.
+// Cells are stored in depth-first pre-order; the first child of cell c is c + 1.
+struct __align__(32) Cell {
+    float cx, cy;      // centre of mass (Eq. (15): y_cell)
+    uint32_t cnt;      // N_cell
+    uint32_t meta;     // depth | (leaf << 8)
+    uint32_t lo;       // first member position in the spatial order
+    uint32_t c1, c2, c3;  // 2nd..4th existing child, TSNE_NONE if absent
+};
+
+struct ScanPart {
+    double sx, sy;
+    uint32_t cnt;
+    uint32_t pad;
+};
+
+// Tiling constants that host and device must agree on.
+constexpr int SORT_THREADS = 256;
+constexpr int SORT_ITEMS = 8;
+constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
+constexpr int LEVEL_THREADS = 256;
+constexpr int LEVEL_ITEMS = 4;
+constexpr int LEVEL_TILE = LEVEL_THREADS * LEVEL_ITEMS;
+constexpr int BBOX_MAX_BLOCKS = 1024;
+
+struct tsne_ctx {
+    tsne_params p;
+    hipStream_t stream;
+    hipStream_t stream2;
+    hipEvent_t ev_fork, ev_join;
+    int have_P, tree_valid;
+    // borrowed P
+    const int32_t *row_ptr, *col;
+    const float *val;
+    int64_t nnz;
+    // workspace carve-up
+    float4 *bbox_part;   // [BBOX_MAX_BLOCKS*2]  (min, max) pairs
+    float4 *root;        // x0, y0, W, S
+    uint32_t *status;    // device status word
+    uint32_t *ncells;    // device cell count
+    uint32_t *keys[2], *idx[2];
+    uint32_t *keys_orig; // keys in original order (kept for export)
+    uint32_t *hist, *dtot;
+    float2 *Ys;
+    uint16_t *lev;
+    ScanPart *part;
+    uint32_t *cellseq;
+    double2 *ps;
+    Cell *cells;
+    int32_t cap_cells;
+    float2 *R, *A, *uY, *gains;
+    double *zpart, *Z;
+    double *kl_part;
+    int sorted_buf;      // which of keys[]/idx[] holds the sorted result
+    char err[256];
+};
+
+// ---- launchers (each enqueues on the given stream and returns the launch error) ----
+hipError_t launch_tree_build(tsne_ctx *c, const float *d_Y, hipStream_t s);
+hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
+hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s);
+hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s);
+hipError_t launch_fill_state(tsne_ctx *c, hipStream_t s);
+hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t *lo, int32_t *hi,
+                               int32_t *leaf, float *com, hipStream_t s);
+hipError_t launch_kl(tsne_ctx *c, const float *d_Y, hipStream_t s);  // result in c->kl_part[0]
+
+// ---- wave helpers ----
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
+
+__device__ __forceinline__ uint64_t lanemask_lt()
+{
+    return (1ull << lane_id()) - 1ull;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+__device__ __forceinline__ float wave_min(float v)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+
+// Exclusive prefix sum over the 64 lanes; *total receives the wave sum.
+__device__ __forceinline__ int wave_excl_scan(int v, int *total)
+{
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        int t = __shfl_up(inc, o, WAVE);
+        if (lane_id() >= o) inc += t;
+    }
+    *total = __shfl(inc, WAVE - 1, WAVE);
+    return inc - v;
+}

@@ -1,0 +1,209 @@
+// Sec. III-C step 5 of the paper on gfx950: repulsive forces and the Z estimate by a
+// Barnes-Hut walk, one wavefront per group of 64 consecutive points of the spatial order.
+//
+// The walk is split into two roles so that no lane ever waits on a pointer chase:
+//   lanes = cells    up to 64 cells are popped from the wave's stack and tested at once against
+//                    the group's bounding box with Eq. (14) (side^2 < theta^2 dist^2, the
+//                    distance taken from the cell's centre of mass to the nearest point of the
+//                    box, so the test holds for every point of the group);
+//                    accepted cells go to an interaction list in LDS as (y_cell, N_cell),
+//                    rejected inner cells push their children, rejected leaves put their
+//                    points on the same list with N = 1;
+//   lanes = points   the list is drained: every lane adds N w^2 (y_i - y_cell) and N w,
+//                    w = 1/(1+|y_i - y_cell|^2), for its own point (Eq. (15) and the Z note
+//                    that follows it); list entries are LDS broadcasts.
+// A point meets itself exactly once (its own leaf is always opened when theta^2 < 1/2) with
+// w = 1 and zero force; the Z accumulator therefore starts at -1.
+#include "tsne_internal.h"
+
+#include <math.h>
+
+constexpr int WALK_STACK = 1024;     // entries; see the bound argued at the pop
+constexpr int WALK_LIST = 768;       // interaction list entries (16 B each)
+constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied lane-parallel
+
+__device__ __forceinline__ bool accept_cell(float side2, float theta2, float cx, float cy, float bx0, float bx1,
+                                            float by0, float by1)
+{
+#pragma clang fp contract(off)
+    float ax = bx0 - cx, bx = cx - bx1;
+    float ay = by0 - cy, by = cy - by1;
+    float dx = fmaxf(fmaxf(ax, bx), 0.0f);
+    float dy = fmaxf(fmaxf(ay, by), 0.0f);
+    float dx2 = dx * dx, dy2 = dy * dy;
+    float d2 = dx2 + dy2;
+    float rhs = theta2 * d2;
+    return side2 < rhs;
+}
+
+__device__ __forceinline__ void drain(const float4 *__restrict__ ilist, int cnt, float x, float y, float &fx,
+                                      float &fy, float &z)
+{
+    __syncthreads();
+    int e = 0;
+    for (; e + 4 <= cnt; e += 4) {
+        float4 c0 = ilist[e], c1 = ilist[e + 1], c2 = ilist[e + 2], c3 = ilist[e + 3];
+        float dx0 = x - c0.x, dy0 = y - c0.y, dx1 = x - c1.x, dy1 = y - c1.y;
+        float dx2 = x - c2.x, dy2 = y - c2.y, dx3 = x - c3.x, dy3 = y - c3.y;
+        float q0 = __builtin_amdgcn_rcpf(fmaf(dy0, dy0, fmaf(dx0, dx0, 1.0f)));
+        float q1 = __builtin_amdgcn_rcpf(fmaf(dy1, dy1, fmaf(dx1, dx1, 1.0f)));
+        float q2 = __builtin_amdgcn_rcpf(fmaf(dy2, dy2, fmaf(dx2, dx2, 1.0f)));
+        float q3 = __builtin_amdgcn_rcpf(fmaf(dy3, dy3, fmaf(dx3, dx3, 1.0f)));
+        float n0 = c0.z * q0, n1 = c1.z * q1, n2 = c2.z * q2, n3 = c3.z * q3;
+        z += n0; z += n1; z += n2; z += n3;
+        n0 *= q0; n1 *= q1; n2 *= q2; n3 *= q3;
+        fx = fmaf(n0, dx0, fx); fy = fmaf(n0, dy0, fy);
+        fx = fmaf(n1, dx1, fx); fy = fmaf(n1, dy1, fy);
+        fx = fmaf(n2, dx2, fx); fy = fmaf(n2, dy2, fy);
+        fx = fmaf(n3, dx3, fx); fy = fmaf(n3, dy3, fy);
+    }
+    for (; e < cnt; ++e) {
+        float4 c = ilist[e];
+        float dx = x - c.x, dy = y - c.y;
+        float q = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+        float nq = c.z * q;
+        z += nq;
+        nq *= q;
+        fx = fmaf(nq, dx, fx); fy = fmaf(nq, dy, fy);
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, const float2 *__restrict__ Ys,
+                                                const uint32_t *__restrict__ perm, int n,
+                                                const float4 *__restrict__ root, float theta2,
+                                                const uint32_t *__restrict__ ncells, uint32_t cap_cells,
+                                                float2 *__restrict__ R, double *__restrict__ zpart,
+                                                uint32_t *status)
+{
+    __shared__ uint32_t stack[WALK_STACK];
+    __shared__ float4 ilist[WALK_LIST];
+    const int lane = (int)threadIdx.x;
+    const int g = (int)blockIdx.x;
+    const int p = g * WAVE + lane;
+    const bool valid = p < n;
+    const uint32_t m_cells = *ncells;
+    if (m_cells > cap_cells) {        // tree did not fit: flagged by the build, produce zeros
+        if (valid) R[min(perm[p], (uint32_t)n - 1u)] = make_float2(0.f, 0.f);
+        if (lane == 0) zpart[g] = 0.0;
+        return;
+    }
+    // own point; idle lanes of the last group shadow its first point and are never written out
+    float2 me = Ys[valid ? p : g * WAVE];
+    const float x = me.x, y = me.y;
+    const float bx0 = wave_min(x), bx1 = wave_max(x), by0 = wave_min(y), by1 = wave_max(y);
+    const float W = root->z;
+    float fx = 0.f, fy = 0.f, z = -1.0f;
+    int sp = 1, ic = 0;
+    bool overflow = false;
+    uint32_t rounds = 0;
+    if (lane == 0) stack[0] = 0u;
+    __syncthreads();
+    while (sp > 0) {
+        // Pop.  64 cells at once push at most 256 children (net +192); when that could pass
+        // the end of the stack the wave falls back to one cell per round, i.e. plain
+        // depth-first search, which adds at most 3 entries per level below the popped cell
+        // (<= 45 with 16 levels).  Either way sp stays <= WALK_STACK - 3.
+        const int take = (sp <= WALK_STACK - 240) ? (sp < WAVE ? sp : WAVE) : 1;
+        const bool act = lane < take;
+        // every cell is popped at most once, so more rounds than cells means a malformed tree;
+        // ids and member positions are clamped so that even then no access leaves the arrays
+        if (++rounds > m_cells) { overflow = true; break; }
+        const uint32_t id = act ? min(stack[sp - take + lane], m_cells - 1u) : 0u;
+        sp -= take;
+        const uint4 *cp = reinterpret_cast<const uint4 *>(cells + id);
+        const uint4 ca = cp[0], cb = cp[1];
+        const float cx = __uint_as_float(ca.x), cy = __uint_as_float(ca.y);
+        const uint32_t cnt = ca.z, depth = ca.w & 0xFFu;
+        const bool leaf = (ca.w >> 8) & 1u;
+        const float side = ldexpf(W, -(int)depth);   // exact: W is a power of two
+        const float side2 = side * side;
+        const bool pass = accept_cell(side2, theta2, cx, cy, bx0, bx1, by0, by1);
+        const bool acc = act && pass;
+        const bool open = act && !pass && leaf;
+        const bool desc = act && !pass && !leaf;
+        const bool ofast = open && cnt <= (uint32_t)WALK_FAST_LEAF;
+        // room on the list for this round's accepted cells and small leaves
+        const uint64_t macc = __ballot(acc);
+        int mtot;
+        const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
+        const int nacc = __popcll(macc);
+        if (ic + nacc + mtot > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
+        if (acc) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
+        ic += nacc;
+        if (ofast) {
+            for (uint32_t j = 0; j < cnt; ++j) {
+                float2 q = Ys[min(cb.x + j, (uint32_t)n - 1u)];
+                ilist[ic + moff + (int)j] = make_float4(q.x, q.y, 1.0f, 0.f);
+            }
+        }
+        ic += mtot;
+        // large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF): one at a time
+        uint64_t mbig = __ballot(open && !ofast);
+        while (mbig) {
+            const int b = __ffsll((long long)mbig) - 1;
+            mbig &= mbig - 1;
+            const uint32_t lo_b = __shfl(cb.x, b, WAVE), cnt_b = __shfl(cnt, b, WAVE);
+            for (uint32_t j0 = 0; j0 < cnt_b; j0 += WAVE) {
+                const int m = (int)min((uint32_t)WAVE, cnt_b - j0);
+                if (ic + m > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
+                if (lane < m) {
+                    float2 q = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
+                    ilist[ic + lane] = make_float4(q.x, q.y, 1.0f, 0.f);
+                }
+                ic += m;
+            }
+        }
+        // children of rejected inner cells, pushed in lane order (deeper cells end on top)
+        const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
+        int ctot;
+        const int coff = wave_excl_scan(nch, &ctot);
+        if (sp + ctot > WALK_STACK) { overflow = true; break; }   // unreachable for a well-formed tree
+        if (desc) {
+            int o = sp + coff;
+            stack[o++] = id + 1u;
+            if (cb.y != TSNE_NONE) stack[o++] = cb.y;
+            if (cb.z != TSNE_NONE) stack[o++] = cb.z;
+            if (cb.w != TSNE_NONE) stack[o++] = cb.w;
+        }
+        sp += ctot;
+        __syncthreads();
+    }
+    if (overflow) {
+        if (lane == 0) atomicOr(status, TSNE_STATUS_WALK_OVERFLOW);
+        fx = fy = 0.f; z = 0.f; ic = 0;
+    }
+    drain(ilist, ic, x, y, fx, fy, z);
+    if (valid) R[min(perm[p], (uint32_t)n - 1u)] = make_float2(fx, fy);
+    double zd = wave_sum(valid ? (double)z : 0.0);
+    if (lane == 0) zpart[g] = zd;
+}
+
+// Z = sum of the per-group partial sums, in a fixed order.
+__global__ __launch_bounds__(1024) void z_final(const double *__restrict__ zpart, int ngroups, double *__restrict__ Z)
+{
+    __shared__ double ws[16];
+    double a = 0.0;
+    const int per = (ngroups + 1023) / 1024;
+    const int s = threadIdx.x * per, e = min(ngroups, s + per);
+    for (int i = s; i < e; ++i) a += zpart[i];
+    a = wave_sum(a);
+    if (lane_id() == 0) ws[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int k = 0; k < 16; ++k) t += ws[k];
+        *Z = t;
+    }
+}
+
+hipError_t launch_walk(tsne_ctx *c, hipStream_t s)
+{
+    const int n = c->p.n;
+    const int ngroups = (n + WAVE - 1) / WAVE;
+    const float theta2 = c->p.theta * c->p.theta;
+    hipLaunchKernelGGL(bh_walk, dim3(ngroups), dim3(WAVE), 0, s, c->cells, c->Ys, c->idx[c->sorted_buf], n, c->root,
+                       theta2, c->ncells, (uint32_t)c->cap_cells, c->R, c->zpart, c->status);
+    hipLaunchKernelGGL(z_final, dim3(1), dim3(1024), 0, s, c->zpart, ngroups, c->Z);
+    return hipGetLastError();
+}
