@@ -414,11 +414,11 @@ int32_t oracle_tree(const uint32_t *sorted_keys, const float *Ys, int32_t n, int
 /* sorted order (group = 1 is the per-point search of the text; a larger    */
 /* group makes all its points take the same decisions, which is how a tree  */
 /* code keeps the lanes of one wavefront together).  A cell is accepted for */
-/* a group when Eq. (14) holds with r_cell = side of the cell, y_cell = its */
-/* centre of mass, and the distance taken from y_cell to the NEAREST point  */
-/* of the group's bounding box -- so Eq. (14) then holds for every point of */
-/* the group.  The test is evaluated in single precision, squared:          */
-/*      side^2 < theta^2 * dist^2.                                          */
+/* a group when Eq. (14) holds for EVERY point of the group, with r_cell =  */
+/* side of the cell and y_cell = its centre of mass.  The test is evaluated */
+/* in single precision, squared, one rounding per operation (the sum of the */
+/* two squares is one fused multiply-add):                                  */
+/*      side^2 < theta^2 * ((y_i - y_cell).y^2 + (y_i - y_cell).x^2).       */
 /* Accepted cell: every point of the group gets n w^2 (y_i - y_cell) and    */
 /* n w, w = 1/(1+|y_i - y_cell|^2).  Rejected inner cell: descend into its  */
 /* children.  Rejected leaf: its points are taken one by one, j = i skipped */
@@ -432,7 +432,6 @@ typedef struct {
     const float *Ys;
     float W, theta2;
     int32_t g0, g1;          /* positions of the group */
-    float bx0, bx1, by0, by1;
     double *rx, *ry, *z;     /* per member of the group */
     int64_t st[3];
 } walk_t;
@@ -443,14 +442,15 @@ static void walk_rec(walk_t *K, int32_t id)
     volatile float side = ldexpf(K->W, -T->depth[id]);
     volatile float side2 = side * side;
     float cx = T->com[2 * id], cy = T->com[2 * id + 1];
-    volatile float ax = K->bx0 - cx, bx = cx - K->bx1;
-    volatile float ay = K->by0 - cy, by = cy - K->by1;
-    float dx = ax > bx ? ax : bx; if (dx < 0.0f) dx = 0.0f;
-    float dy = ay > by ? ay : by; if (dy < 0.0f) dy = 0.0f;
-    volatile float dx2 = dx * dx, dy2 = dy * dy;
-    volatile float dist2 = dx2 + dy2;
-    volatile float rhs = K->theta2 * dist2;
-    if (side2 < rhs) {
+    int all_pass = 1;
+    for (int32_t p = K->g0; p < K->g1 && all_pass; ++p) {
+        volatile float dx = K->Ys[2 * p] - cx, dy = K->Ys[2 * p + 1] - cy;
+        volatile float dx2 = dx * dx;
+        volatile float dist2 = fmaf(dy, dy, dx2);
+        volatile float rhs = K->theta2 * dist2;
+        if (!(side2 < rhs)) all_pass = 0;
+    }
+    if (all_pass) {
         double n = (double)(T->hi[id] - T->lo[id]);
         for (int32_t p = K->g0; p < K->g1; ++p) {
             double ddx = (double)K->Ys[2 * p] - (double)cx, ddy = (double)K->Ys[2 * p + 1] - (double)cy;
@@ -517,13 +517,6 @@ int32_t oracle_repulse_bh(const float *Y, int32_t n, float theta, int32_t leaf_c
             walk_t K;
             K.T = &T; K.Ys = Ys; K.W = root[2]; K.theta2 = th2;
             K.g0 = g * group; K.g1 = K.g0 + group < n ? K.g0 + group : n;
-            K.bx0 = K.bx1 = Ys[2 * K.g0]; K.by0 = K.by1 = Ys[2 * K.g0 + 1];
-            for (int32_t p = K.g0; p < K.g1; ++p) {
-                if (Ys[2 * p] < K.bx0) K.bx0 = Ys[2 * p];
-                if (Ys[2 * p] > K.bx1) K.bx1 = Ys[2 * p];
-                if (Ys[2 * p + 1] < K.by0) K.by0 = Ys[2 * p + 1];
-                if (Ys[2 * p + 1] > K.by1) K.by1 = Ys[2 * p + 1];
-            }
             int32_t gs = K.g1 - K.g0;
             K.rx = calloc((size_t)gs, 8); K.ry = calloc((size_t)gs, 8); K.z = calloc((size_t)gs, 8);
             K.st[0] = K.st[1] = K.st[2] = 0;

@@ -1,37 +1,46 @@
 // Sec. III-C step 5 of the paper on gfx950: repulsive forces and the Z estimate by a
 // Barnes-Hut walk, one wavefront per group of 64 consecutive points of the spatial order.
 //
-// The walk is split into two roles so that no lane ever waits on a pointer chase:
-//   lanes = cells    up to 64 cells are popped from the wave's stack and tested at once against
-//                    the group's bounding box with Eq. (14) (side^2 < theta^2 dist^2, the
-//                    distance taken from the cell's centre of mass to the nearest point of the
-//                    box, so the test holds for every point of the group);
-//                    accepted cells go to an interaction list in LDS as (y_cell, N_cell),
-//                    rejected inner cells push their children, rejected leaves put their
-//                    points on the same list with N = 1;
+// A cell is accepted for a group when Eq. (14) (side^2 < theta^2 |y_i - y_cell|^2, y_cell the
+// centre of mass) holds for every point of the group, so all 64 lanes always take the same
+// path.  The walk alternates between two roles so that no lane ever waits on a pointer chase:
+//
+//   lanes = cells    up to 64 cells are popped from the wave's stack and tested at once.
+//        sift        cheap test against the group's bounding box: the distance from y_cell to
+//                    the box is a lower bound of the distance to every point, and every step of
+//                    the single-precision test is monotone, so passing here implies passing for
+//                    each point, bit for bit.  Cells that fail wait on a short pending list.
+//        settle      64 pending cells at a time: minimum of |y_i - y_cell|^2 over the group's
+//                    points (LDS broadcasts), then the exact test.  Accepted cells go to an
+//                    interaction list in LDS as (y_cell, N_cell); rejected inner cells push
+//                    their children; rejected leaves put their points on the list with N = 1.
 //   lanes = points   the list is drained: every lane adds N w^2 (y_i - y_cell) and N w,
 //                    w = 1/(1+|y_i - y_cell|^2), for its own point (Eq. (15) and the Z note
 //                    that follows it); list entries are LDS broadcasts.
-// A point meets itself exactly once (its own leaf is always opened when theta^2 < 1/2) with
-// w = 1 and zero force; the Z accumulator therefore starts at -1.
+//
+// A point meets itself exactly once (the leaf that holds it can never pass its own test when
+// theta^2 < 1/2) with w = 1 and zero force; the Z accumulator therefore starts at -1.
 #include "tsne_internal.h"
 
 #include <math.h>
 
-constexpr int WALK_STACK = 1024;     // entries; see the bound argued at the pop
+constexpr int WALK_STACK = 1024;     // stack entries
+constexpr int WALK_ROOM = 304;       // settle needs room for 256 children + 48 (depth-first slack)
+constexpr int WALK_PEND = 128;       // pending list entries
 constexpr int WALK_LIST = 768;       // interaction list entries (16 B each)
-constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied lane-parallel
+constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied by their own lane
 
-__device__ __forceinline__ bool accept_cell(float side2, float theta2, float cx, float cy, float bx0, float bx1,
-                                            float by0, float by1)
+// side^2 < theta^2 * d2, with d2 = fma(dy, dy, dx*dx): one rounding per operation.
+__device__ __forceinline__ float dist2_rounded(float dx, float dy)
 {
 #pragma clang fp contract(off)
-    float ax = bx0 - cx, bx = cx - bx1;
-    float ay = by0 - cy, by = cy - by1;
-    float dx = fmaxf(fmaxf(ax, bx), 0.0f);
-    float dy = fmaxf(fmaxf(ay, by), 0.0f);
-    float dx2 = dx * dx, dy2 = dy * dy;
-    float d2 = dx2 + dy2;
+    float dx2 = dx * dx;
+    return fmaf(dy, dy, dx2);
+}
+
+__device__ __forceinline__ bool passes(float side2, float theta2, float d2)
+{
+#pragma clang fp contract(off)
     float rhs = theta2 * d2;
     return side2 < rhs;
 }
@@ -77,97 +86,142 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
                                                 uint32_t *status)
 {
     __shared__ uint32_t stack[WALK_STACK];
+    __shared__ uint32_t pend[WALK_PEND];
+    __shared__ float2 pts[WAVE];
     __shared__ float4 ilist[WALK_LIST];
     const int lane = (int)threadIdx.x;
     const int g = (int)blockIdx.x;
     const int p = g * WAVE + lane;
     const bool valid = p < n;
     const uint32_t m_cells = *ncells;
-    if (m_cells > cap_cells) {        // tree did not fit: flagged by the build, produce zeros
+    if (m_cells > cap_cells || m_cells == 0u) {   // tree did not fit: flagged by the build, produce zeros
         if (valid) R[min(perm[p], (uint32_t)n - 1u)] = make_float2(0.f, 0.f);
         if (lane == 0) zpart[g] = 0.0;
         return;
     }
     // own point; idle lanes of the last group shadow its first point and are never written out
-    float2 me = Ys[valid ? p : g * WAVE];
+    const float2 me = Ys[valid ? p : g * WAVE];
     const float x = me.x, y = me.y;
+    pts[lane] = me;
     const float bx0 = wave_min(x), bx1 = wave_max(x), by0 = wave_min(y), by1 = wave_max(y);
     const float W = root->z;
     float fx = 0.f, fy = 0.f, z = -1.0f;
-    int sp = 1, ic = 0;
+    int sp = 1, np = 0, ic = 0;
     bool overflow = false;
     uint32_t rounds = 0;
     if (lane == 0) stack[0] = 0u;
     __syncthreads();
-    while (sp > 0) {
-        // Pop.  64 cells at once push at most 256 children (net +192); when that could pass
-        // the end of the stack the wave falls back to one cell per round, i.e. plain
-        // depth-first search, which adds at most 3 entries per level below the popped cell
-        // (<= 45 with 16 levels).  Either way sp stays <= WALK_STACK - 3.
-        const int take = (sp <= WALK_STACK - 240) ? (sp < WAVE ? sp : WAVE) : 1;
-        const bool act = lane < take;
-        // every cell is popped at most once, so more rounds than cells means a malformed tree;
-        // ids and member positions are clamped so that even then no access leaves the arrays
-        if (++rounds > m_cells) { overflow = true; break; }
-        const uint32_t id = act ? min(stack[sp - take + lane], m_cells - 1u) : 0u;
-        sp -= take;
-        const uint4 *cp = reinterpret_cast<const uint4 *>(cells + id);
-        const uint4 ca = cp[0], cb = cp[1];
-        const float cx = __uint_as_float(ca.x), cy = __uint_as_float(ca.y);
-        const uint32_t cnt = ca.z, depth = ca.w & 0xFFu;
-        const bool leaf = (ca.w >> 8) & 1u;
-        const float side = ldexpf(W, -(int)depth);   // exact: W is a power of two
-        const float side2 = side * side;
-        const bool pass = accept_cell(side2, theta2, cx, cy, bx0, bx1, by0, by1);
-        const bool acc = act && pass;
-        const bool open = act && !pass && leaf;
-        const bool desc = act && !pass && !leaf;
-        const bool ofast = open && cnt <= (uint32_t)WALK_FAST_LEAF;
-        // room on the list for this round's accepted cells and small leaves
-        const uint64_t macc = __ballot(acc);
-        int mtot;
-        const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
-        const int nacc = __popcll(macc);
-        if (ic + nacc + mtot > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
-        if (acc) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
-        ic += nacc;
-        if (ofast) {
-            for (uint32_t j = 0; j < cnt; ++j) {
-                float2 q = Ys[min(cb.x + j, (uint32_t)n - 1u)];
-                ilist[ic + moff + (int)j] = make_float4(q.x, q.y, 1.0f, 0.f);
-            }
+    while (sp > 0 || np > 0) {
+        // every cell is sifted at most once and settled at most once, so more rounds than
+        // 2 * cells means a malformed tree; ids and member positions are clamped so that even
+        // then no access leaves the arrays
+        if (++rounds > 2u * m_cells + 2u) { overflow = true; break; }
+        // Stack bound: settling 64 cells pushes at most 256 children, so it only runs with
+        // WALK_ROOM entries free; above that mark the wave settles the single top cell per
+        // round instead -- plain depth-first search, which adds at most 3 entries per level
+        // below the popped cell (<= 45 for 16 levels) before it shrinks again.
+        const bool pressure = sp > WALK_STACK - WALK_ROOM;
+        if (!pressure && sp > 0 && np < WAVE) {
+            // ---- sift: bounding-box test of up to 64 stacked cells
+            const int take = sp < WAVE ? sp : WAVE;
+            const bool act = lane < take;
+            const uint32_t id = act ? min(stack[sp - take + lane], m_cells - 1u) : 0u;
+            sp -= take;
+            const uint4 ca = *reinterpret_cast<const uint4 *>(cells + id);
+            const float cx = __uint_as_float(ca.x), cy = __uint_as_float(ca.y);
+            const float side = ldexpf(W, -(int)(ca.w & 0xFFu));   // exact: W is a power of two
+            const float dx = fmaxf(fmaxf(bx0 - cx, cx - bx1), 0.0f);
+            const float dy = fmaxf(fmaxf(by0 - cy, cy - by1), 0.0f);
+            const bool pass = passes(side * side, theta2, dist2_rounded(dx, dy));
+            const uint64_t macc = __ballot(act && pass), mrej = __ballot(act && !pass);
+            const int nacc = __popcll(macc);
+            if (ic + nacc > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
+            if (act && pass) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)ca.z, 0.f);
+            ic += nacc;
+            if (act && !pass) pend[np + __popcll(mrej & lanemask_lt())] = id;
+            np += __popcll(mrej);
+            __syncthreads();
         }
-        ic += mtot;
-        // large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF): one at a time
-        uint64_t mbig = __ballot(open && !ofast);
-        while (mbig) {
-            const int b = __ffsll((long long)mbig) - 1;
-            mbig &= mbig - 1;
-            const uint32_t lo_b = __shfl(cb.x, b, WAVE), cnt_b = __shfl(cnt, b, WAVE);
-            for (uint32_t j0 = 0; j0 < cnt_b; j0 += WAVE) {
-                const int m = (int)min((uint32_t)WAVE, cnt_b - j0);
-                if (ic + m > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
-                if (lane < m) {
-                    float2 q = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
-                    ilist[ic + lane] = make_float4(q.x, q.y, 1.0f, 0.f);
+        if (pressure || np >= WAVE || (sp == 0 && np > 0)) {
+            // ---- settle: exact test of up to 64 cells (or of the top of the stack under pressure)
+            int take;
+            uint32_t id;
+            if (pressure) {
+                take = 1;
+                id = lane == 0 ? stack[sp - 1] : 0u;
+                sp -= 1;
+            } else {
+                take = np < WAVE ? np : WAVE;
+                id = lane < take ? pend[np - take + lane] : 0u;
+                np -= take;
+            }
+            const bool act = lane < take;
+            id = min(id, m_cells - 1u);
+            const uint4 *cp = reinterpret_cast<const uint4 *>(cells + id);
+            const uint4 ca = cp[0], cb = cp[1];
+            const float cx = __uint_as_float(ca.x), cy = __uint_as_float(ca.y);
+            const uint32_t cnt = ca.z;
+            const bool leaf = (ca.w >> 8) & 1u;
+            const float side = ldexpf(W, -(int)(ca.w & 0xFFu));
+            float dmin = INFINITY;
+#pragma unroll 8
+            for (int i = 0; i < WAVE; ++i) {
+                const float2 q = pts[i];
+                dmin = fminf(dmin, dist2_rounded(q.x - cx, q.y - cy));
+            }
+            const bool pass = passes(side * side, theta2, dmin);
+            const bool acc = act && pass;
+            const bool open = act && !pass && leaf;
+            const bool desc = act && !pass && !leaf;
+            const bool ofast = open && cnt <= (uint32_t)WALK_FAST_LEAF;
+            const uint64_t macc = __ballot(acc);
+            int mtot;
+            const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
+            const int nacc = __popcll(macc);
+            if (ic + nacc + mtot > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
+            if (acc) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
+            ic += nacc;
+            if (ofast) {
+                float2 q[WALK_FAST_LEAF];
+#pragma unroll
+                for (int j = 0; j < WALK_FAST_LEAF; ++j)
+                    q[j] = Ys[min(cb.x + (uint32_t)j, (uint32_t)n - 1u)];
+#pragma unroll
+                for (int j = 0; j < WALK_FAST_LEAF; ++j)
+                    if ((uint32_t)j < cnt) ilist[ic + moff + j] = make_float4(q[j].x, q[j].y, 1.0f, 0.f);
+            }
+            ic += mtot;
+            // large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF): one at a time
+            uint64_t mbig = __ballot(open && !ofast);
+            while (mbig) {
+                const int b = __ffsll((long long)mbig) - 1;
+                mbig &= mbig - 1;
+                const uint32_t lo_b = __shfl(cb.x, b, WAVE), cnt_b = __shfl(cnt, b, WAVE);
+                for (uint32_t j0 = 0; j0 < cnt_b; j0 += WAVE) {
+                    const int m = (int)min((uint32_t)WAVE, cnt_b - j0);
+                    if (ic + m > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
+                    if (lane < m) {
+                        const float2 q = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
+                        ilist[ic + lane] = make_float4(q.x, q.y, 1.0f, 0.f);
+                    }
+                    ic += m;
                 }
-                ic += m;
             }
+            // children of rejected inner cells
+            const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
+            int ctot;
+            const int coff = wave_excl_scan(nch, &ctot);
+            if (sp + ctot > WALK_STACK) { overflow = true; break; }   // unreachable for a well-formed tree
+            if (desc) {
+                int o = sp + coff;
+                stack[o++] = id + 1u;
+                if (cb.y != TSNE_NONE) stack[o++] = cb.y;
+                if (cb.z != TSNE_NONE) stack[o++] = cb.z;
+                if (cb.w != TSNE_NONE) stack[o++] = cb.w;
+            }
+            sp += ctot;
+            __syncthreads();
         }
-        // children of rejected inner cells, pushed in lane order (deeper cells end on top)
-        const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
-        int ctot;
-        const int coff = wave_excl_scan(nch, &ctot);
-        if (sp + ctot > WALK_STACK) { overflow = true; break; }   // unreachable for a well-formed tree
-        if (desc) {
-            int o = sp + coff;
-            stack[o++] = id + 1u;
-            if (cb.y != TSNE_NONE) stack[o++] = cb.y;
-            if (cb.z != TSNE_NONE) stack[o++] = cb.z;
-            if (cb.w != TSNE_NONE) stack[o++] = cb.w;
-        }
-        sp += ctot;
-        __syncthreads();
     }
     if (overflow) {
         if (lane == 0) atomicOr(status, TSNE_STATUS_WALK_OVERFLOW);

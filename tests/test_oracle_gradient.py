@@ -207,13 +207,15 @@ def test_run_resume_is_bitwise(small_problem):
 
 
 def test_run_lowers_kl(small_problem):
+    """A converged Barnes-Hut run ends at the KL of a converged exact run (trajectories are
+    chaotic, so only the end value is compared, and only after enough iterations)."""
     P, Y0 = small_problem["P"], small_problem["Y"] * 1e-3
-    pr = oracle.RunParams.default(exaggeration_iters=50, momentum_switch_iter=50)
+    pr = oracle.RunParams.default(exaggeration_iters=100, momentum_switch_iter=100)
     kl0 = oracle.kl(Y0, P["row_ptr"], P["col"], P["val"])
-    Y, _, _ = oracle.run(Y0, P["row_ptr"], P["col"], P["val"], pr, 200)
+    Y, _, _ = oracle.run(Y0, P["row_ptr"], P["col"], P["val"], pr, 800)
     kl1 = oracle.kl(Y, P["row_ptr"], P["col"], P["val"])
-    pr0 = oracle.RunParams.default(exaggeration_iters=50, momentum_switch_iter=50, theta=0.0)
-    Ye, _, _ = oracle.run(Y0, P["row_ptr"], P["col"], P["val"], pr0, 200)
+    pr0 = oracle.RunParams.default(exaggeration_iters=100, momentum_switch_iter=100, theta=0.0)
+    Ye, _, _ = oracle.run(Y0, P["row_ptr"], P["col"], P["val"], pr0, 800)
     kle = oracle.kl(Ye, P["row_ptr"], P["col"], P["val"])
     assert kl1 < 0.5 * kl0
-    assert abs(kl1 - kle) <= 0.15 * kle     # BH run lands near where the exact run lands (N is tiny)
+    assert abs(kl1 - kle) <= 0.08 * kle
