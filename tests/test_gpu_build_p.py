@@ -1,0 +1,96 @@
+"""GPU vs oracle: kNN indices bit-exact, calibrated and symmetrised P within float rounding."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1807_11824_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_P(X, perplexity, k):
+    import torch
+    from paper_1807_11824_amd import build_P
+    Xd = torch.from_numpy(np.ascontiguousarray(X)).to("cuda:0")
+    r = build_P(Xd, perplexity, k, want_knn=True)
+    out = {}
+    for key, v in r.items():
+        out[key] = v.cpu().numpy() if hasattr(v, "cpu") else v
+    return out
+
+
+def _check_against_oracle(X, perplexity, k, rows=None):
+    perplexity = float(np.float32(perplexity))     # the C ABI takes the perplexity as a float
+    g = _gpu_P(X, perplexity, k)
+    n = X.shape[0]
+    if rows is None:
+        o = oracle.build_P(X, perplexity, k)
+        assert np.array_equal(g["knn_idx"], o["idx"])
+        assert np.allclose(g["knn_d2"], o["d2"], rtol=1e-6, atol=0)
+        assert g["unconverged"] == o["unconverged"]
+        assert np.array_equal(g["row_ptr"], o["row_ptr"])
+        assert np.array_equal(g["col"], o["col"])
+        # float storage of a double-precision value: half an ulp, plus the bisection's 1e-10 stop
+        rel = np.abs(g["val"].astype(np.float64) - o["val"]) / np.maximum(o["val"], 1e-300)
+        print("max rel err of val", rel.max(), "at", int(rel.argmax()), "oracle val", o["val"][rel.argmax()], flush=True)
+        assert np.allclose(g["val"], o["val"], rtol=2e-7, atol=1e-30)
+    else:
+        idx, d2 = oracle.knn(X, k, rows=rows)
+        assert np.array_equal(g["knn_idx"][rows], idx)
+        assert np.allclose(g["knn_d2"][rows], d2, rtol=1e-6, atol=0)
+        cond, _, _ = oracle.cond_p(d2, perplexity)
+    # invariants that hold at any size (Sec. III-A/B)
+    import scipy.sparse as sp
+    M = sp.csr_matrix((g["val"], g["col"], g["row_ptr"]), shape=(n, n))
+    assert (M != M.T).nnz == 0
+    assert abs(g["val"].astype(np.float64).sum() - 1.0) < 1e-5
+    assert n * k <= g["nnz"] <= 2 * n * k
+    assert np.all(np.diff(g["row_ptr"]) >= k)
+    return g
+
+
+def test_config1_full():
+    X, _ = synth.config1()
+    g = _check_against_oracle(X, 30.0, 90)
+    assert g["unconverged"] == 0
+
+
+def test_lattice_ties():
+    """Exact integer distances with many ties: order by (distance, index), fall-back selection path."""
+    X = synth.lattice(700, 6, span=3, seed=1)
+    _check_against_oracle(X, 5.0, 17)
+
+
+@pytest.mark.parametrize("n,d,k", [(300, 51, 20), (1000, 7, 40), (129, 33, 128), (2500, 130, 90)])
+def test_ragged_shapes(n, d, k):
+    rng = np.random.default_rng(d)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    _check_against_oracle(X, min(30.0, k / 3.0), k)
+
+
+def test_duplicates():
+    rng = np.random.default_rng(0)
+    X = np.repeat(rng.standard_normal((200, 16)).astype(np.float32), 3, axis=0)
+    _check_against_oracle(X, 5.0, 15)
+
+
+def test_config2_shape_sampled_rows():
+    X, _ = synth.config2(n=20000)
+    rows = np.random.default_rng(1).choice(20000, 256, replace=False).astype(np.int32)
+    _check_against_oracle(X, 30.0, 90, rows=np.sort(rows))
+
+
+def test_config3_shape_sampled_rows():
+    X, _ = synth.config3(n=6000)
+    rows = np.random.default_rng(2).choice(6000, 128, replace=False).astype(np.int32)
+    _check_against_oracle(X, 50.0, 150, rows=np.sort(rows))
+
+
+def test_bad_arguments():
+    import torch
+    from paper_1807_11824_amd import build_P, TsneError
+    X = torch.zeros((10, 4), device="cuda:0")
+    with pytest.raises(TsneError):
+        build_P(X, 3.0, 10)        # k must be < n
+    with pytest.raises(TsneError):
+        build_P(X, 9.0, 5)         # perplexity must be <= k
