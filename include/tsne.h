@@ -149,6 +149,19 @@ int tsne_export_tree(tsne_ctx *ctx, uint32_t *d_keys, int32_t *d_perm, int32_t c
  * A harness utility, not part of the step.  Synchronises. */
 int tsne_kl(tsne_ctx *ctx, const float *d_Y, double *kl);
 
+/*
+ * Per-phase GPU time of tsne_step, measured with HIP events recorded on the streams the kernels
+ * run on.  tsne_timing_begin() arms the next max_steps calls of tsne_step (6 events per step);
+ * tsne_timing_end() synchronises, and returns the number of steps timed plus the mean milliseconds
+ * per step of the four phases (any pointer may be NULL):
+ *   ms[0] tree build (Sec. III-C steps 1-4)   ms[1] walk + Z (step 5)
+ *   ms[2] attractive forces (Eq. (5))         ms[3] update (Alg. 1 line 8)
+ * With overlap = 1 the attractive kernel runs beside the tree phases, so the four do not add up
+ * to the step time.
+ */
+int tsne_timing_begin(tsne_ctx *ctx, int32_t max_steps);
+int tsne_timing_end(tsne_ctx *ctx, int32_t *steps, float ms[4]);
+
 /* Synchronises the stream and returns the device status bits (0 = fine) in *status. */
 int tsne_status(tsne_ctx *ctx, uint32_t *status);
 

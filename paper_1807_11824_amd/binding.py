@@ -62,6 +62,8 @@ def lib():
         "tsne_export_tree": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, C.POINTER(i32)]),
         "tsne_kl": (C.c_int, [vp, vp, C.POINTER(C.c_double)]),
         "tsne_status": (C.c_int, [vp, C.POINTER(C.c_uint32)]),
+        "tsne_timing_begin": (C.c_int, [vp, i32]),
+        "tsne_timing_end": (C.c_int, [vp, C.POINTER(i32), C.POINTER(C.c_float)]),
         "tsne_strerror": (C.c_char_p, [C.c_int]),
         "tsne_last_error": (C.c_char_p, [vp]),
     }
@@ -230,6 +232,15 @@ class Tsne:
         v = C.c_double(0)
         self._check(self.L.tsne_kl(self._ctx, _ptr(Y), C.byref(v)), "tsne_kl")
         return v.value
+
+    def timing_begin(self, max_steps):
+        self._check(self.L.tsne_timing_begin(self._ctx, max_steps), "tsne_timing_begin")
+
+    def timing_end(self):
+        steps = C.c_int32(0)
+        ms = (C.c_float * 4)()
+        self._check(self.L.tsne_timing_end(self._ctx, C.byref(steps), ms), "tsne_timing_end")
+        return dict(steps=steps.value, tree_ms=ms[0], walk_ms=ms[1], attract_ms=ms[2], update_ms=ms[3])
 
     def status(self):
         s = C.c_uint32(0)

@@ -4,6 +4,7 @@
 
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -49,6 +50,7 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
         q = take(4 * n); if (c) c->idx[k] = (uint32_t *)q;
     }
     q = take(4 * n);                                 if (c) c->keys_orig = (uint32_t *)q;
+    q = take(4 * n);                                 if (c) c->row_order = (uint32_t *)q;
     q = take(4 * 256 * nblk_sort);                   if (c) c->hist = (uint32_t *)q;
     q = take(4 * 256);                               if (c) c->dtot = (uint32_t *)q;
     q = take(8 * n);                                 if (c) c->Ys = (float2 *)q;
@@ -94,25 +96,47 @@ int fail(tsne_ctx *c, int code, const char *msg)
 
 // Forces at d_Y into c->A, c->R, c->Z.  The attractive kernel only needs Y and P, so with
 // overlap it runs on the second stream while the tree is built and walked on the first.
-int enqueue_forces(tsne_ctx *c, const float *d_Y)
+int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
 {
     hipError_t e;
     const bool two = c->p.overlap && c->stream2;
+    hipStream_t sa = two ? c->stream2 : c->stream;   // where the attractive kernel runs
     if (two) {
         if ((e = hipEventRecord(c->ev_fork, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
         if ((e = hipStreamWaitEvent(c->stream2, c->ev_fork, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
-        if ((e = launch_attract(c, d_Y, c->stream2)) != hipSuccess) return fail_hip(c, e, "attract");
+        if (ev) (void)hipEventRecord(ev[3], sa);
+        if ((e = launch_attract(c, d_Y, sa)) != hipSuccess) return fail_hip(c, e, "attract");
+        if (ev) (void)hipEventRecord(ev[4], sa);
         if ((e = hipEventRecord(c->ev_join, c->stream2)) != hipSuccess) return fail_hip(c, e, "event record");
     }
+    if (ev) (void)hipEventRecord(ev[0], c->stream);
     if ((e = launch_tree_build(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "tree build");
+    if (ev) (void)hipEventRecord(ev[1], c->stream);
     if ((e = launch_walk(c, c->stream)) != hipSuccess) return fail_hip(c, e, "walk");
+    if (ev) (void)hipEventRecord(ev[2], c->stream);
     if (two) {
         if ((e = hipStreamWaitEvent(c->stream, c->ev_join, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
     } else {
+        if (ev) (void)hipEventRecord(ev[3], sa);
         if ((e = launch_attract(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "attract");
+        if (ev) (void)hipEventRecord(ev[4], sa);
     }
+    // the attractive kernel of the NEXT call visits rows in this call's spatial order (it has
+    // finished by now on either stream, so the array is free to overwrite)
+    if ((e = hipMemcpyAsync(c->row_order, c->idx[c->sorted_buf], 4 * (size_t)c->p.n, hipMemcpyDeviceToDevice,
+                            c->stream)) != hipSuccess)
+        return fail_hip(c, e, "copy row order");
     c->tree_valid = 1;
     return TSNE_OK;
+}
+
+void free_timing(tsne_ctx *c)
+{
+    if (!c->tev) return;
+    for (int i = 0; i < 6 * c->t_cap; ++i) if (c->tev[i]) (void)hipEventDestroy(c->tev[i]);
+    free(c->tev);
+    c->tev = nullptr;
+    c->t_cap = c->t_used = 0;
 }
 
 }  // namespace
@@ -174,7 +198,8 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
     }
     if ((e = hipMemsetAsync(c->status, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
         (e = hipMemsetAsync(c->ncells, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
-        (e = launch_fill_state(c, c->stream)) != hipSuccess) {
+        (e = launch_fill_state(c, c->stream)) != hipSuccess ||
+        (e = launch_iota(c->row_order, p->n, c->stream)) != hipSuccess) {
         tsne_destroy(c);
         return TSNE_EHIP;
     }
@@ -188,6 +213,7 @@ void tsne_destroy(tsne_ctx *c)
     if (c->stream2) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    free_timing(c);
     delete c;
 }
 
@@ -234,12 +260,50 @@ int tsne_step(tsne_ctx *c, float *d_Y, int32_t iter)
 {
     if (!c || !d_Y || iter < 0) return TSNE_EINVAL;
     if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_step: no P (call tsne_set_P first)");
-    int rc = enqueue_forces(c, d_Y);
+    hipEvent_t *ev = (c->tev && c->t_used < c->t_cap) ? c->tev + 6 * c->t_used : nullptr;
+    int rc = enqueue_forces(c, d_Y, ev);
     if (rc != TSNE_OK) return rc;
     const float alpha = iter < c->p.exaggeration_iters ? c->p.exaggeration : 1.0f;
     const float mom = iter < c->p.momentum_switch_iter ? c->p.momentum_early : c->p.momentum_late;
     hipError_t e = launch_update(c, d_Y, alpha, mom, c->stream);
+    if (ev) { (void)hipEventRecord(ev[5], c->stream); c->t_used += 1; }
     return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "update");
+}
+
+int tsne_timing_begin(tsne_ctx *c, int32_t max_steps)
+{
+    if (!c || max_steps < 1 || max_steps > (1 << 20)) return TSNE_EINVAL;
+    free_timing(c);
+    c->tev = (hipEvent_t *)calloc((size_t)6 * max_steps, sizeof(hipEvent_t));
+    if (!c->tev) return TSNE_ENOSPC;
+    c->t_cap = max_steps;
+    for (int i = 0; i < 6 * max_steps; ++i) {
+        hipError_t e = hipEventCreate(&c->tev[i]);
+        if (e != hipSuccess) { free_timing(c); return fail_hip(c, e, "event create"); }
+    }
+    return TSNE_OK;
+}
+
+int tsne_timing_end(tsne_ctx *c, int32_t *steps, float ms[4])
+{
+    if (!c) return TSNE_EINVAL;
+    if (!c->tev) return fail(c, TSNE_ESTATE, "tsne_timing_end: timing was not begun");
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e == hipSuccess && c->stream2) e = hipStreamSynchronize(c->stream2);
+    if (e != hipSuccess) return fail_hip(c, e, "sync");
+    double acc[4] = {0, 0, 0, 0};
+    static const int from[4] = {0, 1, 3, 2}, to[4] = {1, 2, 4, 5};
+    for (int s = 0; s < c->t_used; ++s)
+        for (int q = 0; q < 4; ++q) {
+            float t = 0.f;
+            e = hipEventElapsedTime(&t, c->tev[6 * s + from[q]], c->tev[6 * s + to[q]]);
+            if (e != hipSuccess) { free_timing(c); return fail_hip(c, e, "event elapsed"); }
+            acc[q] += t;
+        }
+    if (steps) *steps = c->t_used;
+    if (ms) for (int q = 0; q < 4; ++q) ms[q] = c->t_used ? (float)(acc[q] / c->t_used) : 0.f;
+    free_timing(c);
+    return TSNE_OK;
 }
 
 int tsne_status(tsne_ctx *c, uint32_t *status)
@@ -271,7 +335,7 @@ int tsne_gradient(tsne_ctx *c, const float *d_Y, float *d_attr, float *d_rep, do
 {
     if (!c || !d_Y) return TSNE_EINVAL;
     if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_gradient: no P (call tsne_set_P first)");
-    int rc = enqueue_forces(c, d_Y);
+    int rc = enqueue_forces(c, d_Y, nullptr);
     if (rc != TSNE_OK) return rc;
     const size_t b = 8 * (size_t)c->p.n;
     hipError_t e = hipSuccess;

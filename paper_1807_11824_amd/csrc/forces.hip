@@ -8,14 +8,20 @@
 // col/val are read as contiguous segments, y_j is an 8-byte gather, and the two partial sums
 // are combined with xor-shuffles inside the LPR-lane group.  No atomics: the result is
 // deterministic.
+//
+// Rows are visited in the order given by `order` (the spatial order of an earlier tree build):
+// rows that are close in the embedding share most of their neighbours, so the y_j gathers of
+// one workgroup and its neighbours on the chip keep hitting the same cache lines.  The result
+// of a row does not depend on when it is computed.
 template <int LPR>
 __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col,
                                                    const float *__restrict__ val, const float2 *__restrict__ Y, int n,
-                                                   float2 *__restrict__ A)
+                                                   const uint32_t *__restrict__ order, float2 *__restrict__ A)
 {
-    const int row = (int)((blockIdx.x * 256u + threadIdx.x) / LPR);
+    const int slot = (int)((blockIdx.x * 256u + threadIdx.x) / LPR);
     const int sub = (int)(threadIdx.x % LPR);
     float ax = 0.f, ay = 0.f;
+    const int row = slot < n ? (int)min(order[slot], (uint32_t)n - 1u) : n;
     if (row < n) {
         const int s = row_ptr[row], e = row_ptr[row + 1];
         const float2 yi = Y[row];
@@ -44,7 +50,7 @@ hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s)
     const int n = c->p.n;
     const unsigned blocks = (unsigned)(((int64_t)n * LPR + 255) / 256);
     hipLaunchKernelGGL(attract_csr<LPR>, dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val,
-                       (const float2 *)d_Y, n, c->A);
+                       (const float2 *)d_Y, n, c->row_order, c->A);
     return hipGetLastError();
 }
 
@@ -85,6 +91,18 @@ __global__ __launch_bounds__(256) void fill_state_k(float *__restrict__ uY, floa
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c < n2) { uY[c] = 0.f; gains[c] = 1.f; }
+}
+
+__global__ __launch_bounds__(256) void iota_k(uint32_t *__restrict__ a, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) a[i] = (uint32_t)i;
+}
+
+hipError_t launch_iota(uint32_t *a, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(iota_k, dim3((n + 255) / 256), dim3(256), 0, s, a, n);
+    return hipGetLastError();
 }
 
 hipError_t launch_fill_state(tsne_ctx *c, hipStream_t s)

@@ -52,6 +52,7 @@ struct tsne_ctx {
     uint32_t *ncells;    // device cell count
     uint32_t *keys[2], *idx[2];
     uint32_t *keys_orig; // keys in original order (kept for export)
+    uint32_t *row_order; // order in which the attractive kernel visits the rows (an earlier spatial order)
     uint32_t *hist, *dtot;
     float2 *Ys;
     uint16_t *lev;
@@ -64,6 +65,9 @@ struct tsne_ctx {
     double *zpart, *Z;
     double *kl_part;
     int sorted_buf;      // which of keys[]/idx[] holds the sorted result
+    // optional per-phase timing: 6 events per armed step
+    hipEvent_t *tev;
+    int t_cap, t_used;
     char err[256];
 };
 
@@ -73,6 +77,7 @@ hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s);
 hipError_t launch_fill_state(tsne_ctx *c, hipStream_t s);
+hipError_t launch_iota(uint32_t *a, int n, hipStream_t s);
 hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t *lo, int32_t *hi,
                                int32_t *leaf, float *com, hipStream_t s);
 hipError_t launch_kl(tsne_ctx *c, const float *d_Y, hipStream_t s);  // result in c->kl_part[0]
