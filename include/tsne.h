@@ -64,11 +64,25 @@ typedef struct {
     int32_t morton_bits;          /* grid bits per axis = maximum tree depth, 1..16 (16) */
     int32_t leaf_cap;             /* a cell with at most this many points is a leaf, >= 1 (8) */
     int32_t overlap;              /* 1: attractive forces run on a second stream beside the tree work */
+    int32_t graph_order_iters;    /* > 0 (and max_nnz > 0): at tsne_set_P the library renumbers its private
+                                     copy of the points and of P so that points that are neighbours in P get
+                                     nearby numbers: a seeded pseudo-random value per point is averaged over
+                                     the P-neighbourhood this many times and the points are sorted by it.
+                                     The sparsity pattern becomes banded, so the y_j gathers of Eq. (5) stay
+                                     cache-resident.  Nothing the method computes changes except float
+                                     rounding and the order of points with equal grid keys.  (8) */
+    int32_t reorder_every;        /* > 0 (and max_nnz > 0): additionally renumber along the current spatial
+                                     order of the embedding every this many steps; pays off once neighbours
+                                     in P are neighbours in the plane.  (0 = never) */
+    int64_t max_nnz;              /* capacity for the private copy of P that renumbering needs: the workspace
+                                     grows by 16 bytes per entry.  0 disables renumbering; P is then only
+                                     borrowed and a stop/resume is bitwise reproducible. */
 } tsne_params;
 
 typedef struct tsne_ctx tsne_ctx; /* opaque, host side, owned by the library */
 
-/* Fills *p with the defaults quoted above for n points. */
+/* Fills *p with the defaults quoted above for n points (max_nnz = 0: set it to the entry count of P,
+ * at most 2 n k, to enable renumbering). */
 int tsne_default_params(tsne_params *p, int32_t n);
 
 /* Bytes of device workspace a context with these parameters needs (upper bound). */
@@ -100,7 +114,9 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                  void *d_workspace, size_t workspace_bytes, void *stream);
 
 /* Hands a CSR matrix P (n rows, int32 indices, float values, all on the device) to the context.
- * Borrowed, not copied: it must outlive every later call on the context. */
+ * Borrowed: it must outlive every later call on the context (with renumbering on, the library works
+ * from a relabelled private copy but still reads the original for tsne_kl).  With renumbering on,
+ * nnz must not exceed max_nnz.  Column indices must lie in [0, n). */
 int tsne_set_P(tsne_ctx *ctx, const int32_t *d_row_ptr, const int32_t *d_col, const float *d_val, int64_t nnz);
 
 /* Resets the optimiser state: velocity = 0, gains = 1 (enqueued). */

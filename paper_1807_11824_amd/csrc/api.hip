@@ -61,8 +61,23 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     q = take(sizeof(Cell) * (size_t)cap);            if (c) { c->cells = (Cell *)q; c->cap_cells = cap; }
     q = take(8 * n);                                 if (c) c->R = (float2 *)q;
     q = take(8 * n);                                 if (c) c->A = (float2 *)q;
-    q = take(8 * n);                                 if (c) c->uY = (float2 *)q;
-    q = take(8 * n);                                 if (c) c->gains = (float2 *)q;
+    q = take(8 * n);                                 if (c) c->Yi = (float2 *)q;
+    const bool reorder = (p->reorder_every > 0 || p->graph_order_iters > 0) && p->max_nnz > 0;
+    for (int k = 0; k < (reorder ? 2 : 1); ++k) {
+        q = take(8 * n); if (c) c->uYb[k] = (float2 *)q;
+        q = take(8 * n); if (c) c->gainsb[k] = (float2 *)q;
+        q = take(4 * n); if (c) c->orig[k] = (uint32_t *)q;
+    }
+    if (reorder) {
+        const size_t m = (size_t)p->max_nnz;
+        q = take(4 * n); if (c) c->inv = (uint32_t *)q;
+        q = take(4 * n); if (c) c->lenbuf = (int32_t *)q;
+        for (int k = 0; k < 2; ++k) {
+            q = take(4 * (n + 1)); if (c) c->rp_i[k] = (int32_t *)q;
+            q = take(4 * m);       if (c) c->col_i[k] = (int32_t *)q;
+            q = take(4 * m);       if (c) c->val_i[k] = (float *)q;
+        }
+    }
     q = take(8 * ngroups);                           if (c) c->zpart = (double *)q;
     q = take(8);                                     if (c) c->Z = (double *)q;
     q = take(8 * KL_PART_DOUBLES);                   if (c) c->kl_part = (double *)q;
@@ -76,6 +91,8 @@ int check_params(const tsne_params *p)
     if (!(p->theta >= 0.0f) || p->theta > 0.7f) return TSNE_EINVAL;
     if (p->morton_bits < 1 || p->morton_bits > 16) return TSNE_EINVAL;
     if (p->leaf_cap < 1) return TSNE_EINVAL;
+    if (p->reorder_every < 0 || p->graph_order_iters < 0 || p->graph_order_iters > 1000) return TSNE_EINVAL;
+    if (p->max_nnz < 0 || p->max_nnz > 0x7FFFFFFFll) return TSNE_EINVAL;
     if (!isfinite(p->lr) || !isfinite(p->exaggeration) || !isfinite(p->momentum_early) ||
         !isfinite(p->momentum_late) || !isfinite(p->gain_inc) || !isfinite(p->gain_dec) || !isfinite(p->gain_min))
         return TSNE_EINVAL;
@@ -101,6 +118,8 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
     hipError_t e;
     const bool two = c->p.overlap && c->stream2;
     hipStream_t sa = two ? c->stream2 : c->stream;   // where the attractive kernel runs
+    if (ev) (void)hipEventRecord(ev[0], c->stream);
+    if ((e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
     if (two) {
         if ((e = hipEventRecord(c->ev_fork, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
         if ((e = hipStreamWaitEvent(c->stream2, c->ev_fork, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
@@ -109,8 +128,7 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
         if (ev) (void)hipEventRecord(ev[4], sa);
         if ((e = hipEventRecord(c->ev_join, c->stream2)) != hipSuccess) return fail_hip(c, e, "event record");
     }
-    if (ev) (void)hipEventRecord(ev[0], c->stream);
-    if ((e = launch_tree_build(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "tree build");
+    if ((e = launch_tree_build(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree build");
     if (ev) (void)hipEventRecord(ev[1], c->stream);
     if ((e = launch_walk(c, c->stream)) != hipSuccess) return fail_hip(c, e, "walk");
     if (ev) (void)hipEventRecord(ev[2], c->stream);
@@ -121,12 +139,32 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
         if ((e = launch_attract(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "attract");
         if (ev) (void)hipEventRecord(ev[4], sa);
     }
-    // the attractive kernel of the NEXT call visits rows in this call's spatial order (it has
-    // finished by now on either stream, so the array is free to overwrite)
-    if ((e = hipMemcpyAsync(c->row_order, c->idx[c->sorted_buf], 4 * (size_t)c->p.n, hipMemcpyDeviceToDevice,
+    // Without renumbering, the attractive kernel of the NEXT call visits rows in this call's
+    // spatial order (the kernel has finished by now on either stream, so the array is free to
+    // overwrite).  With renumbering the slots themselves are ordered and rows go in slot order.
+    if (!c->reorder_on &&
+        (e = hipMemcpyAsync(c->row_order, c->idx[c->sorted_buf], 4 * (size_t)c->p.n, hipMemcpyDeviceToDevice,
                             c->stream)) != hipSuccess)
         return fail_hip(c, e, "copy row order");
     c->tree_valid = 1;
+    return TSNE_OK;
+}
+
+// Back to the caller's numbering (slot s = point s): needed before a new P is taken over.
+int reset_slot_order(tsne_ctx *c)
+{
+    if (c->identity) return TSNE_OK;
+    const int a = c->cur_state, b = a ^ 1, n = c->p.n;
+    hipError_t e;
+    if ((e = launch_scatter2(c->uYb[a], c->orig[a], c->uYb[b], n, c->stream)) != hipSuccess ||
+        (e = launch_scatter2(c->gainsb[a], c->orig[a], c->gainsb[b], n, c->stream)) != hipSuccess ||
+        (e = launch_iota(c->orig[b], n, c->stream)) != hipSuccess ||
+        (e = launch_iota(c->row_order, n, c->stream)) != hipSuccess)
+        return fail_hip(c, e, "reset slot order");
+    c->cur_state = b;
+    c->identity = 1;
+    c->steps_since_reorder = 0;
+    c->row_ptr = c->user_row_ptr; c->col = c->user_col; c->val = c->user_val;
     return TSNE_OK;
 }
 
@@ -161,6 +199,9 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->morton_bits = 16;
     p->leaf_cap = 8;
     p->overlap = 1;
+    p->graph_order_iters = 8;
+    p->reorder_every = 0;
+    p->max_nnz = 0;
     return TSNE_OK;
 }
 
@@ -186,6 +227,9 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
     c->p = *p;
     c->stream = (hipStream_t)stream;
     carve(c, p, (char *)d_workspace);
+    c->reorder_on = (p->reorder_every > 0 || p->graph_order_iters > 0) && p->max_nnz > 0;
+    c->identity = 1;
+    c->cur_P = 1;
     hipError_t e;
     if (p->overlap) {
         // default priority on purpose; non-blocking so that it does not serialise with stream 0
@@ -199,7 +243,8 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
     if ((e = hipMemsetAsync(c->status, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
         (e = hipMemsetAsync(c->ncells, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
         (e = launch_fill_state(c, c->stream)) != hipSuccess ||
-        (e = launch_iota(c->row_order, p->n, c->stream)) != hipSuccess) {
+        (e = launch_iota(c->row_order, p->n, c->stream)) != hipSuccess ||
+        (e = launch_iota(c->orig[0], p->n, c->stream)) != hipSuccess) {
         tsne_destroy(c);
         return TSNE_EHIP;
     }
@@ -222,8 +267,17 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     if (!c) return TSNE_EINVAL;
     if (!d_row_ptr || nnz < 0 || nnz > 0x7FFFFFFFll || (nnz > 0 && (!d_col || !d_val)))
         return fail(c, TSNE_EINVAL, "tsne_set_P: null array or nnz out of range");
+    if (c->reorder_on && nnz > c->p.max_nnz) return fail(c, TSNE_ENOSPC, "tsne_set_P: nnz exceeds max_nnz");
+    int rc = reset_slot_order(c);
+    if (rc != TSNE_OK) return rc;
+    c->user_row_ptr = d_row_ptr; c->user_col = d_col; c->user_val = d_val;
     c->row_ptr = d_row_ptr; c->col = d_col; c->val = d_val; c->nnz = nnz;
     c->have_P = 1;
+    if (c->reorder_on && c->p.graph_order_iters > 0 && nnz > 0) {
+        hipError_t e;
+        if ((e = launch_graph_order(c, c->stream)) != hipSuccess || (e = launch_reorder(c, c->stream)) != hipSuccess)
+            return fail_hip(c, e, "graph order");
+    }
     return TSNE_OK;
 }
 
@@ -237,10 +291,10 @@ int tsne_init_state(tsne_ctx *c)
 int tsne_get_state(tsne_ctx *c, float *d_velocity, float *d_gains)
 {
     if (!c || !d_velocity || !d_gains) return TSNE_EINVAL;
-    const size_t b = 8 * (size_t)c->p.n;
+    const int a = c->cur_state;
     hipError_t e;
-    if ((e = hipMemcpyAsync(d_velocity, c->uY, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess ||
-        (e = hipMemcpyAsync(d_gains, c->gains, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess)
+    if ((e = launch_scatter2(c->uYb[a], c->orig[a], (float2 *)d_velocity, c->p.n, c->stream)) != hipSuccess ||
+        (e = launch_scatter2(c->gainsb[a], c->orig[a], (float2 *)d_gains, c->p.n, c->stream)) != hipSuccess)
         return fail_hip(c, e, "copy state");
     return TSNE_OK;
 }
@@ -248,10 +302,10 @@ int tsne_get_state(tsne_ctx *c, float *d_velocity, float *d_gains)
 int tsne_set_state(tsne_ctx *c, const float *d_velocity, const float *d_gains)
 {
     if (!c || !d_velocity || !d_gains) return TSNE_EINVAL;
-    const size_t b = 8 * (size_t)c->p.n;
+    const int a = c->cur_state;
     hipError_t e;
-    if ((e = hipMemcpyAsync(c->uY, d_velocity, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess ||
-        (e = hipMemcpyAsync(c->gains, d_gains, b, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess)
+    if ((e = launch_gather2((const float2 *)d_velocity, c->orig[a], c->uYb[a], c->p.n, c->stream)) != hipSuccess ||
+        (e = launch_gather2((const float2 *)d_gains, c->orig[a], c->gainsb[a], c->p.n, c->stream)) != hipSuccess)
         return fail_hip(c, e, "copy state");
     return TSNE_OK;
 }
@@ -267,7 +321,12 @@ int tsne_step(tsne_ctx *c, float *d_Y, int32_t iter)
     const float mom = iter < c->p.momentum_switch_iter ? c->p.momentum_early : c->p.momentum_late;
     hipError_t e = launch_update(c, d_Y, alpha, mom, c->stream);
     if (ev) { (void)hipEventRecord(ev[5], c->stream); c->t_used += 1; }
-    return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "update");
+    if (e != hipSuccess) return fail_hip(c, e, "update");
+    if (c->reorder_on && c->p.reorder_every > 0 && ++c->steps_since_reorder >= c->p.reorder_every) {
+        c->steps_since_reorder = 0;
+        if ((e = launch_reorder(c, c->stream)) != hipSuccess) return fail_hip(c, e, "reorder");
+    }
+    return TSNE_OK;
 }
 
 int tsne_timing_begin(tsne_ctx *c, int32_t max_steps)
@@ -337,10 +396,10 @@ int tsne_gradient(tsne_ctx *c, const float *d_Y, float *d_attr, float *d_rep, do
     if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_gradient: no P (call tsne_set_P first)");
     int rc = enqueue_forces(c, d_Y, nullptr);
     if (rc != TSNE_OK) return rc;
-    const size_t b = 8 * (size_t)c->p.n;
+    const uint32_t *orig = c->orig[c->cur_state];
     hipError_t e = hipSuccess;
-    if (d_attr) e = hipMemcpyAsync(d_attr, c->A, b, hipMemcpyDeviceToDevice, c->stream);
-    if (e == hipSuccess && d_rep) e = hipMemcpyAsync(d_rep, c->R, b, hipMemcpyDeviceToDevice, c->stream);
+    if (d_attr) e = launch_scatter2(c->A, orig, (float2 *)d_attr, c->p.n, c->stream);
+    if (e == hipSuccess && d_rep) e = launch_scatter2(c->R, orig, (float2 *)d_rep, c->p.n, c->stream);
     if (e == hipSuccess && d_Z) e = hipMemcpyAsync(d_Z, c->Z, 8, hipMemcpyDeviceToDevice, c->stream);
     return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "copy forces");
 }
@@ -350,11 +409,8 @@ int tsne_export_tree(tsne_ctx *c, uint32_t *d_keys, int32_t *d_perm, int32_t cap
 {
     if (!c || cap_cells < 0) return TSNE_EINVAL;
     if (!c->tree_valid) return fail(c, TSNE_ESTATE, "tsne_export_tree: no tree built yet");
-    const size_t n = (size_t)c->p.n;
     hipError_t e = hipSuccess;
-    if (d_keys) e = hipMemcpyAsync(d_keys, c->keys_orig, 4 * n, hipMemcpyDeviceToDevice, c->stream);
-    if (e == hipSuccess && d_perm)
-        e = hipMemcpyAsync(d_perm, c->idx[c->sorted_buf], 4 * n, hipMemcpyDeviceToDevice, c->stream);
+    if (d_keys || d_perm) e = launch_export_order(c, d_keys, d_perm, c->stream);
     if (e == hipSuccess && d_root) e = hipMemcpyAsync(d_root, c->root, 12, hipMemcpyDeviceToDevice, c->stream);
     if (e == hipSuccess) e = launch_export_cells(c, cap_cells, d_depth, d_lo, d_hi, d_leaf, d_com, c->stream);
     uint32_t m = 0;

@@ -13,7 +13,17 @@
 // rows that are close in the embedding share most of their neighbours, so the y_j gathers of
 // one workgroup and its neighbours on the chip keep hitting the same cache lines.  The result
 // of a row does not depend on when it is computed.
-template <int LPR>
+#ifndef ATTRACT_LPR
+#define ATTRACT_LPR 16
+#endif
+#ifndef ATTRACT_VEC
+#define ATTRACT_VEC 4
+#endif
+
+// The kernel is bound by memory latency unless every lane keeps several independent loads in
+// flight: each pass of a lane covers VEC consecutive entries (one 16-byte load of columns, one
+// of values when VEC = 4), then issues the VEC gathers of y_j together, then does the arithmetic.
+template <int LPR, int VEC>
 __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col,
                                                    const float *__restrict__ val, const float2 *__restrict__ Y, int n,
                                                    const uint32_t *__restrict__ order, float2 *__restrict__ A)
@@ -25,15 +35,31 @@ __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ r
     if (row < n) {
         const int s = row_ptr[row], e = row_ptr[row + 1];
         const float2 yi = Y[row];
-        for (int j = s + sub; j < e; j += LPR) {
-            const int c = col[j];
-            const float v = val[j];
-            const float2 yj = Y[c];
-            const float dx = yi.x - yj.x, dy = yi.y - yj.y;
-            const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
-            const float pw = v * w;
-            ax = fmaf(pw, dx, ax);
-            ay = fmaf(pw, dy, ay);
+        for (int j0 = s + sub * VEC; j0 < e; j0 += LPR * VEC) {
+            int c[VEC];
+            float v[VEC];
+            float2 yj[VEC];
+            if (j0 + VEC <= e) {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) { c[q] = col[j0 + q]; v[q] = val[j0 + q]; }
+            } else {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) {
+                    const bool in = j0 + q < e;
+                    c[q] = in ? col[j0 + q] : row;     // padding: own point, weight 0
+                    v[q] = in ? val[j0 + q] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) yj[q] = Y[c[q]];
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) {
+                const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
+                const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+                const float pw = v[q] * w;
+                ax = fmaf(pw, dx, ax);
+                ay = fmaf(pw, dy, ay);
+            }
         }
     }
 #pragma unroll
@@ -46,11 +72,12 @@ __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ r
 
 hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s)
 {
-    constexpr int LPR = 16;
+    constexpr int LPR = ATTRACT_LPR;
     const int n = c->p.n;
     const unsigned blocks = (unsigned)(((int64_t)n * LPR + 255) / 256);
-    hipLaunchKernelGGL(attract_csr<LPR>, dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val,
-                       (const float2 *)d_Y, n, c->row_order, c->A);
+    (void)d_Y;
+    hipLaunchKernelGGL((attract_csr<LPR, ATTRACT_VEC>), dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val,
+                       c->Yi, n, c->row_order, c->A);
     return hipGetLastError();
 }
 
@@ -60,30 +87,36 @@ hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s)
 // y += velocity.
 __device__ __forceinline__ int sign3(float v) { return v > 0.f ? 1 : (v < 0.f ? -1 : 0); }
 
-__global__ __launch_bounds__(256) void update_k(float *__restrict__ Y, float *__restrict__ uY, float *__restrict__ gains,
-                                                const float *__restrict__ A, const float *__restrict__ R,
-                                                const double *__restrict__ Z, int n2, float alpha, float momentum,
-                                                float lr, float gain_inc, float gain_dec, float gain_min)
+__global__ __launch_bounds__(256) void update_k(float2 *__restrict__ Y, const uint32_t *__restrict__ orig,
+                                                const float2 *__restrict__ Yi, float2 *__restrict__ uY,
+                                                float2 *__restrict__ gains, const float2 *__restrict__ A,
+                                                const float2 *__restrict__ R, const double *__restrict__ Z, int n,
+                                                float alpha, float momentum, float lr, float gain_inc, float gain_dec,
+                                                float gain_min)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= n2) return;
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n) return;
     const float invZ = (float)(1.0 / *Z);
-    const float grad = 4.0f * (alpha * A[c] - R[c] * invZ);
-    float g = gains[c], u = uY[c];
-    g = (sign3(grad) != sign3(u)) ? g + gain_inc : g * gain_dec;
-    g = fmaxf(g, gain_min);
-    u = momentum * u - lr * g * grad;
-    gains[c] = g;
-    uY[c] = u;
-    Y[c] += u;
+    const float2 a = A[s], r = R[s];
+    float2 g = gains[s], u = uY[s], y = Yi[s];
+    const float gx = 4.0f * (alpha * a.x - r.x * invZ), gy = 4.0f * (alpha * a.y - r.y * invZ);
+    g.x = (sign3(gx) != sign3(u.x)) ? g.x + gain_inc : g.x * gain_dec;
+    g.y = (sign3(gy) != sign3(u.y)) ? g.y + gain_inc : g.y * gain_dec;
+    g.x = fmaxf(g.x, gain_min); g.y = fmaxf(g.y, gain_min);
+    u.x = momentum * u.x - lr * g.x * gx;
+    u.y = momentum * u.y - lr * g.y * gy;
+    gains[s] = g;
+    uY[s] = u;
+    y.x += u.x; y.y += u.y;
+    Y[min(orig[s], (uint32_t)n - 1u)] = y;
 }
 
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s)
 {
-    const int n2 = 2 * c->p.n;
-    hipLaunchKernelGGL(update_k, dim3((n2 + 255) / 256), dim3(256), 0, s, d_Y, (float *)c->uY, (float *)c->gains,
-                       (const float *)c->A, (const float *)c->R, c->Z, n2, alpha, momentum, c->p.lr, c->p.gain_inc,
-                       c->p.gain_dec, c->p.gain_min);
+    const int n = c->p.n;
+    hipLaunchKernelGGL(update_k, dim3((n + 255) / 256), dim3(256), 0, s, (float2 *)d_Y, c->orig[c->cur_state], c->Yi,
+                       c->uYb[c->cur_state], c->gainsb[c->cur_state], c->A, c->R, c->Z, n, alpha, momentum, c->p.lr,
+                       c->p.gain_inc, c->p.gain_dec, c->p.gain_min);
     return hipGetLastError();
 }
 
@@ -108,7 +141,8 @@ hipError_t launch_iota(uint32_t *a, int n, hipStream_t s)
 hipError_t launch_fill_state(tsne_ctx *c, hipStream_t s)
 {
     const int n2 = 2 * c->p.n;
-    hipLaunchKernelGGL(fill_state_k, dim3((n2 + 255) / 256), dim3(256), 0, s, (float *)c->uY, (float *)c->gains, n2);
+    hipLaunchKernelGGL(fill_state_k, dim3((n2 + 255) / 256), dim3(256), 0, s, (float *)c->uYb[c->cur_state],
+                       (float *)c->gainsb[c->cur_state], n2);
     return hipGetLastError();
 }
 
@@ -188,7 +222,7 @@ hipError_t launch_kl(tsne_ctx *c, const float *d_Y, hipStream_t s)
     const int n = c->p.n;
     const float2 *Y = (const float2 *)d_Y;
     hipLaunchKernelGGL(exact_z_k, dim3(KL_BLOCKS), dim3(256), 0, s, Y, n, c->kl_part);
-    hipLaunchKernelGGL(kl_terms_k, dim3(KL_BLOCKS), dim3(256), 0, s, c->row_ptr, c->col, c->val, Y, n,
+    hipLaunchKernelGGL(kl_terms_k, dim3(KL_BLOCKS), dim3(256), 0, s, c->user_row_ptr, c->user_col, c->user_val, Y, n,
                        c->kl_part + KL_BLOCKS, c->kl_part + 2 * KL_BLOCKS);
     hipLaunchKernelGGL(kl_final_k, dim3(1), dim3(64), 0, s, c->kl_part, KL_BLOCKS);
     return hipGetLastError();

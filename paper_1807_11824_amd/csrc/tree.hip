@@ -20,13 +20,17 @@
 #include <math.h>
 
 // ------------------------------------------------------------------ bounding box
-__global__ __launch_bounds__(256) void bbox_partial(const float2 *__restrict__ Y, int n,
-                                                    float4 *__restrict__ part, uint32_t *status)
+// Also brings the caller's Y (original point order) into the library's slot order:
+// Yi[s] = Y[orig[s]].
+__global__ __launch_bounds__(256) void bbox_partial(const float2 *__restrict__ Y, const uint32_t *__restrict__ orig,
+                                                    float2 *__restrict__ Yi, int n, float4 *__restrict__ part,
+                                                    uint32_t *status)
 {
     float mnx = INFINITY, mny = INFINITY, mxx = -INFINITY, mxy = -INFINITY;
     bool bad = false;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-        float2 y = Y[i];
+        float2 y = Y[min(orig[i], (uint32_t)n - 1u)];
+        Yi[i] = y;
         bad |= !(isfinite(y.x) && isfinite(y.y));
         mnx = fminf(mnx, y.x); mxx = fmaxf(mxx, y.x);
         mny = fminf(mny, y.y); mxy = fmaxf(mxy, y.y);
@@ -519,19 +523,19 @@ hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t
 }
 
 // ------------------------------------------------------------------ host: enqueue the whole build
-hipError_t launch_tree_build(tsne_ctx *c, const float *d_Y, hipStream_t s)
+static int bbox_blocks(int n)
 {
-    const int n = c->p.n, B = c->p.morton_bits, C = c->p.leaf_cap;
-    const float2 *Y = (const float2 *)d_Y;
     int nb = (n + 255) / 256;
-    int bb = nb < BBOX_MAX_BLOCKS ? nb : BBOX_MAX_BLOCKS;
-    hipLaunchKernelGGL(bbox_partial, dim3(bb), dim3(256), 0, s, Y, n, c->bbox_part, c->status);
-    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(256), 0, s, c->bbox_part, bb, B, c->root, c->status);
-    hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],
-                       c->idx[0]);
-    int nblk = (n + SORT_TILE - 1) / SORT_TILE;
+    return nb < BBOX_MAX_BLOCKS ? nb : BBOX_MAX_BLOCKS;
+}
+
+// Stable LSD radix sort of (keys[0], idx[0]) on the low nbits bits, 8 bits a pass.
+hipError_t launch_sort(tsne_ctx *c, int nbits, hipStream_t s)
+{
+    const int n = c->p.n;
+    const int nblk = (n + SORT_TILE - 1) / SORT_TILE;
     int cur = 0;
-    for (int shift = 0; shift < 2 * B; shift += 8) {
+    for (int shift = 0; shift < nbits; shift += 8) {
         hipLaunchKernelGGL(radix_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, c->keys[cur], n, shift, c->hist, nblk);
         hipLaunchKernelGGL(radix_scan, dim3(256), dim3(256), 0, s, c->hist, nblk, c->dtot);
         hipLaunchKernelGGL(radix_scatter, dim3(nblk), dim3(SORT_THREADS), 0, s, c->keys[cur], c->idx[cur],
@@ -539,6 +543,28 @@ hipError_t launch_tree_build(tsne_ctx *c, const float *d_Y, hipStream_t s)
         cur ^= 1;
     }
     c->sorted_buf = cur;
+    return hipGetLastError();
+}
+
+// Step 1, first half: the caller's Y into slot order plus per-block bounding boxes.
+hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s)
+{
+    const int n = c->p.n;
+    hipLaunchKernelGGL(bbox_partial, dim3(bbox_blocks(n)), dim3(256), 0, s, (const float2 *)d_Y,
+                       c->orig[c->cur_state], c->Yi, n, c->bbox_part, c->status);
+    return hipGetLastError();
+}
+
+hipError_t launch_tree_build(tsne_ctx *c, hipStream_t s)
+{
+    const int n = c->p.n, B = c->p.morton_bits, C = c->p.leaf_cap;
+    const float2 *Y = c->Yi;
+    const int nb = (n + 255) / 256, bb = bbox_blocks(n);
+    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(256), 0, s, c->bbox_part, bb, B, c->root, c->status);
+    hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],
+                       c->idx[0]);
+    (void)launch_sort(c, 2 * B, s);
+    const int cur = c->sorted_buf;
     int nl = (n + LEVEL_TILE - 1) / LEVEL_TILE;
     hipLaunchKernelGGL(gather_levels, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B, C,
                        c->Ys, c->lev, c->part);

@@ -41,10 +41,18 @@ struct tsne_ctx {
     hipStream_t stream2;
     hipEvent_t ev_fork, ev_join;
     int have_P, tree_valid;
-    // borrowed P
+    // P in the caller's numbering (borrowed) and in the library's current slot numbering
+    const int32_t *user_row_ptr, *user_col;
+    const float *user_val;
     const int32_t *row_ptr, *col;
     const float *val;
     int64_t nnz;
+    // slot order: slot s holds original point orig[cur_state][s]; velocity and gains live in slot order
+    int reorder_on, cur_state, cur_P, steps_since_reorder, identity;
+    uint32_t *orig[2], *inv;
+    int32_t *rp_i[2], *col_i[2], *lenbuf;
+    float *val_i[2];
+    float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
     float4 *bbox_part;   // [BBOX_MAX_BLOCKS*2]  (min, max) pairs
     float4 *root;        // x0, y0, W, S
@@ -61,7 +69,7 @@ struct tsne_ctx {
     double2 *ps;
     Cell *cells;
     int32_t cap_cells;
-    float2 *R, *A, *uY, *gains;
+    float2 *R, *A;
     double *zpart, *Z;
     double *kl_part;
     int sorted_buf;      // which of keys[]/idx[] holds the sorted result
@@ -72,10 +80,17 @@ struct tsne_ctx {
 };
 
 // ---- launchers (each enqueues on the given stream and returns the launch error) ----
-hipError_t launch_tree_build(tsne_ctx *c, const float *d_Y, hipStream_t s);
+hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
+hipError_t launch_tree_build(tsne_ctx *c, hipStream_t s);
 hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s);
+hipError_t launch_reorder(tsne_ctx *c, hipStream_t s);
+hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in idx[sorted_buf]
+hipError_t launch_sort(tsne_ctx *c, int nbits, hipStream_t s);  // sorts keys[0]/idx[0]; result in [sorted_buf]
+hipError_t launch_scatter2(const float2 *in, const uint32_t *orig, float2 *out, int n, hipStream_t s);
+hipError_t launch_gather2(const float2 *in, const uint32_t *orig, float2 *out, int n, hipStream_t s);
+hipError_t launch_export_order(tsne_ctx *c, uint32_t *d_keys, int32_t *d_perm, hipStream_t s);
 hipError_t launch_fill_state(tsne_ctx *c, hipStream_t s);
 hipError_t launch_iota(uint32_t *a, int n, hipStream_t s);
 hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t *lo, int32_t *hi,

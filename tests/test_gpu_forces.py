@@ -107,3 +107,37 @@ def test_deterministic():
     a = _gpu_forces(Y, rp, col, val)
     b = _gpu_forces(Y, rp, col, val)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and a[2] == b[2]
+
+
+def test_renumbering_changes_nothing_but_the_layout():
+    """With periodic renumbering on, forces at a given Y equal those of a fresh context without it,
+    and the optimiser state maps back to the caller's point order."""
+    import torch
+    from paper_1807_11824_amd import Tsne
+    dev = torch.device("cuda:0")
+    n = 20_011
+    rp, col, val = random_symmetric_csr(n, 30, seed=3)
+    P = [torch.from_numpy(a).to(dev) for a in (rp, col, val)]
+    Y = torch.from_numpy(synth.y0(n, seed=2)).to(dev)
+    a = Tsne(n, reorder_every=7, max_nnz=len(col), exaggeration=4.0)
+    a.set_P(*P)
+    a.run(Y, 40)                     # renumbers five times
+    assert a.status() == 0
+    b = Tsne(n, reorder_every=0, exaggeration=4.0)
+    b.set_P(*P)
+    Aa, Ra, Za = a.gradient(Y)
+    Ab, Rb, Zb = b.gradient(Y)
+    assert torch.equal(Aa, Ab)       # same entries in the same order within every row
+    assert rel_l2(Ra.cpu().numpy(), Rb.cpu().numpy()) <= 1e-5
+    assert abs(float(Za[0]) - float(Zb[0])) <= 1e-6 * float(Zb[0])
+    ta, tb = a.export_tree(), b.export_tree()
+    assert torch.equal(ta["keys"], tb["keys"]) and ta["m"] == tb["m"]
+    assert torch.equal(ta["depth"], tb["depth"]) and torch.equal(ta["lo"], tb["lo"]) and torch.equal(ta["hi"], tb["hi"])
+    # one more step from the same state on both: the state of `a` is handed to `b` in the caller's order
+    u, g = a.get_state()
+    b.set_state(u, g)
+    Ya, Yb = Y.clone(), Y.clone()
+    a.step(Ya, 40)
+    b.step(Yb, 40)
+    assert rel_l2(Ya.cpu().numpy(), Yb.cpu().numpy()) <= 1e-5
+    a.close(); b.close()
