@@ -70,7 +70,7 @@ typedef struct {
                                      the P-neighbourhood this many times and the points are sorted by it.
                                      The sparsity pattern becomes banded, so the y_j gathers of Eq. (5) stay
                                      cache-resident.  Nothing the method computes changes except float
-                                     rounding and the order of points with equal grid keys.  (8) */
+                                     rounding and the order of points with equal grid keys.  (64) */
     int32_t reorder_every;        /* > 0 (and max_nnz > 0): additionally renumber along the current spatial
                                      order of the embedding every this many steps; pays off once neighbours
                                      in P are neighbours in the plane.  (0 = never) */

@@ -199,7 +199,7 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->morton_bits = 16;
     p->leaf_cap = 8;
     p->overlap = 1;
-    p->graph_order_iters = 8;
+    p->graph_order_iters = 64;
     p->reorder_every = 0;
     p->max_nnz = 0;
     return TSNE_OK;

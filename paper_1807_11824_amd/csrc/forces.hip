@@ -13,17 +13,10 @@
 // rows that are close in the embedding share most of their neighbours, so the y_j gathers of
 // one workgroup and its neighbours on the chip keep hitting the same cache lines.  The result
 // of a row does not depend on when it is computed.
-#ifndef ATTRACT_LPR
-#define ATTRACT_LPR 16
-#endif
-#ifndef ATTRACT_VEC
-#define ATTRACT_VEC 4
-#endif
-
 // The kernel is bound by memory latency unless every lane keeps several independent loads in
-// flight: each pass of a lane covers VEC consecutive entries (one 16-byte load of columns, one
-// of values when VEC = 4), then issues the VEC gathers of y_j together, then does the arithmetic.
-template <int LPR, int VEC>
+// flight: each pass of a lane covers U entries (stride LPR), issues their y_j gathers together,
+// then does the arithmetic.
+template <int LPR, int U>
 __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col,
                                                    const float *__restrict__ val, const float2 *__restrict__ Y, int n,
                                                    const uint32_t *__restrict__ order, float2 *__restrict__ A)
@@ -35,25 +28,21 @@ __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ r
     if (row < n) {
         const int s = row_ptr[row], e = row_ptr[row + 1];
         const float2 yi = Y[row];
-        for (int j0 = s + sub * VEC; j0 < e; j0 += LPR * VEC) {
-            int c[VEC];
-            float v[VEC];
-            float2 yj[VEC];
-            if (j0 + VEC <= e) {
+        for (int j0 = s + sub; j0 < e; j0 += LPR * U) {
+            int c[U];
+            float v[U];
+            float2 yj[U];
 #pragma unroll
-                for (int q = 0; q < VEC; ++q) { c[q] = col[j0 + q]; v[q] = val[j0 + q]; }
-            } else {
-#pragma unroll
-                for (int q = 0; q < VEC; ++q) {
-                    const bool in = j0 + q < e;
-                    c[q] = in ? col[j0 + q] : row;     // padding: own point, weight 0
-                    v[q] = in ? val[j0 + q] : 0.f;
-                }
+            for (int q = 0; q < U; ++q) {
+                const int j = j0 + q * LPR;
+                const bool in = j < e;
+                c[q] = in ? col[j] : row;     // padding: own point, weight 0
+                v[q] = in ? val[j] : 0.f;
             }
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) yj[q] = Y[c[q]];
+            for (int q = 0; q < U; ++q) yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) {
+            for (int q = 0; q < U; ++q) {
                 const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
                 const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
                 const float pw = v[q] * w;
@@ -70,14 +59,78 @@ __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ r
     if (row < n && sub == 0) A[row] = make_float2(ax, ay);
 }
 
+// Variant for renumbered points (slot order follows the structure of P, so row i's columns lie
+// mostly within a band around i): a workgroup owns ROWS consecutive rows and first stages
+// Y[r0 - HALO, r0 + ROWS + HALO) in LDS; gathers that fall inside the window are LDS reads, the
+// rest go to memory as before.  Entries of a row are taken in the same lane order as in the
+// kernel above, so both produce the same sums.
+constexpr int AW_ROWS = 256, AW_HALO = 2048, AW_LPR = 16, AW_U = 4;
+
+__global__ __launch_bounds__(256) void attract_csr_window(const int32_t *__restrict__ row_ptr,
+                                                          const int32_t *__restrict__ col, const float *__restrict__ val,
+                                                          const float2 *__restrict__ Y, int n, float2 *__restrict__ A)
+{
+    constexpr int WIN = AW_ROWS + 2 * AW_HALO;
+    __shared__ float2 win[WIN];
+    const int r0 = (int)blockIdx.x * AW_ROWS;
+    const int wlo = max(0, r0 - AW_HALO), whi = min(n, r0 + AW_ROWS + AW_HALO);
+    for (int t = threadIdx.x; t < whi - wlo; t += 256) win[t] = Y[wlo + t];
+    __syncthreads();
+    const int sub = (int)(threadIdx.x % AW_LPR);
+    for (int rr = (int)threadIdx.x / AW_LPR; rr < AW_ROWS; rr += 256 / AW_LPR) {
+        const int row = r0 + rr;
+        float ax = 0.f, ay = 0.f;
+        if (row < n) {
+            const int s = row_ptr[row], e = row_ptr[row + 1];
+            const float2 yi = win[row - wlo];
+            for (int j0 = s + sub; j0 < e; j0 += AW_LPR * AW_U) {
+                int c[AW_U];
+                float v[AW_U];
+                float2 yj[AW_U];
+#pragma unroll
+                for (int q = 0; q < AW_U; ++q) {
+                    const int j = j0 + q * AW_LPR;
+                    const bool in = j < e;
+                    c[q] = in ? col[j] : row;     // padding: own point, weight 0
+                    v[q] = in ? val[j] : 0.f;
+                }
+#pragma unroll
+                for (int q = 0; q < AW_U; ++q) {
+                    const unsigned off = (unsigned)(c[q] - wlo);
+                    if (off < (unsigned)(whi - wlo)) yj[q] = win[off];
+                    else yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
+                }
+#pragma unroll
+                for (int q = 0; q < AW_U; ++q) {
+                    const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
+                    const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+                    const float pw = v[q] * w;
+                    ax = fmaf(pw, dx, ax);
+                    ay = fmaf(pw, dy, ay);
+                }
+            }
+        }
+#pragma unroll
+        for (int o = AW_LPR / 2; o > 0; o >>= 1) {
+            ax += __shfl_xor(ax, o, WAVE);
+            ay += __shfl_xor(ay, o, WAVE);
+        }
+        if (row < n && sub == 0) A[row] = make_float2(ax, ay);
+    }
+}
+
 hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s)
 {
-    constexpr int LPR = ATTRACT_LPR;
     const int n = c->p.n;
-    const unsigned blocks = (unsigned)(((int64_t)n * LPR + 255) / 256);
     (void)d_Y;
-    hipLaunchKernelGGL((attract_csr<LPR, ATTRACT_VEC>), dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val,
-                       c->Yi, n, c->row_order, c->A);
+    if (c->reorder_on && !c->identity) {
+        hipLaunchKernelGGL(attract_csr_window, dim3((n + AW_ROWS - 1) / AW_ROWS), dim3(256), 0, s, c->row_ptr, c->col,
+                           c->val, c->Yi, n, c->A);
+    } else {
+        const unsigned blocks = (unsigned)(((int64_t)n * AW_LPR + 255) / 256);
+        hipLaunchKernelGGL((attract_csr<AW_LPR, AW_U>), dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val,
+                           c->Yi, n, c->row_order, c->A);
+    }
     return hipGetLastError();
 }
 

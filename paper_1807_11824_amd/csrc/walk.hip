@@ -27,7 +27,10 @@
 constexpr int WALK_STACK = 1024;     // stack entries
 constexpr int WALK_ROOM = 304;       // settle needs room for 256 children + 48 (depth-first slack)
 constexpr int WALK_PEND = 128;       // pending list entries
-constexpr int WALK_LIST = 768;       // interaction list entries (16 B each)
+#ifndef WALK_LIST_N
+#define WALK_LIST_N 576
+#endif
+constexpr int WALK_LIST = WALK_LIST_N;       // interaction list entries (16 B each), >= 64 + 64 * WALK_FAST_LEAF
 constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied by their own lane
 
 // side^2 < theta^2 * d2, with d2 = fma(dy, dy, dx*dx): one rounding per operation.
@@ -45,35 +48,36 @@ __device__ __forceinline__ bool passes(float side2, float theta2, float d2)
     return side2 < rhs;
 }
 
+// One interaction: y_cell (c.x, c.y) with weight c.z = N_cell.
+#define TSNE_INTERACT(c)                                                      \
+    {                                                                         \
+        const float dx_ = x - (c).x, dy_ = y - (c).y;                         \
+        const float q_ = __builtin_amdgcn_rcpf(fmaf(dy_, dy_, fmaf(dx_, dx_, 1.0f))); \
+        z = fmaf((c).z, q_, z);                                               \
+        const float f_ = (c).z * q_ * q_;                                     \
+        fx = fmaf(f_, dx_, fx);                                               \
+        fy = fmaf(f_, dy_, fy);                                               \
+    }
+
 __device__ __forceinline__ void drain(const float4 *__restrict__ ilist, int cnt, float x, float y, float &fx,
                                       float &fy, float &z)
 {
     __syncthreads();
     int e = 0;
-    for (; e + 4 <= cnt; e += 4) {
-        float4 c0 = ilist[e], c1 = ilist[e + 1], c2 = ilist[e + 2], c3 = ilist[e + 3];
-        float dx0 = x - c0.x, dy0 = y - c0.y, dx1 = x - c1.x, dy1 = y - c1.y;
-        float dx2 = x - c2.x, dy2 = y - c2.y, dx3 = x - c3.x, dy3 = y - c3.y;
-        float q0 = __builtin_amdgcn_rcpf(fmaf(dy0, dy0, fmaf(dx0, dx0, 1.0f)));
-        float q1 = __builtin_amdgcn_rcpf(fmaf(dy1, dy1, fmaf(dx1, dx1, 1.0f)));
-        float q2 = __builtin_amdgcn_rcpf(fmaf(dy2, dy2, fmaf(dx2, dx2, 1.0f)));
-        float q3 = __builtin_amdgcn_rcpf(fmaf(dy3, dy3, fmaf(dx3, dx3, 1.0f)));
-        float n0 = c0.z * q0, n1 = c1.z * q1, n2 = c2.z * q2, n3 = c3.z * q3;
-        z += n0; z += n1; z += n2; z += n3;
-        n0 *= q0; n1 *= q1; n2 *= q2; n3 *= q3;
-        fx = fmaf(n0, dx0, fx); fy = fmaf(n0, dy0, fy);
-        fx = fmaf(n1, dx1, fx); fy = fmaf(n1, dy1, fy);
-        fx = fmaf(n2, dx2, fx); fy = fmaf(n2, dy2, fy);
-        fx = fmaf(n3, dx3, fx); fy = fmaf(n3, dy3, fy);
+    if (cnt >= 8) {
+        // two register sets take turns: one is filled from LDS while the other is used
+        float4 a0 = ilist[0], a1 = ilist[1], a2 = ilist[2], a3 = ilist[3];
+        for (e = 4; e + 8 <= cnt; e += 8) {
+            const float4 b0 = ilist[e], b1 = ilist[e + 1], b2 = ilist[e + 2], b3 = ilist[e + 3];
+            TSNE_INTERACT(a0) TSNE_INTERACT(a1) TSNE_INTERACT(a2) TSNE_INTERACT(a3)
+            a0 = ilist[e + 4]; a1 = ilist[e + 5]; a2 = ilist[e + 6]; a3 = ilist[e + 7];
+            TSNE_INTERACT(b0) TSNE_INTERACT(b1) TSNE_INTERACT(b2) TSNE_INTERACT(b3)
+        }
+        TSNE_INTERACT(a0) TSNE_INTERACT(a1) TSNE_INTERACT(a2) TSNE_INTERACT(a3)
     }
     for (; e < cnt; ++e) {
-        float4 c = ilist[e];
-        float dx = x - c.x, dy = y - c.y;
-        float q = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
-        float nq = c.z * q;
-        z += nq;
-        nq *= q;
-        fx = fmaf(nq, dx, fx); fy = fmaf(nq, dy, fy);
+        const float4 c = ilist[e];
+        TSNE_INTERACT(c)
     }
     __syncthreads();
 }
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
     const float bx0 = wave_min(x), bx1 = wave_max(x), by0 = wave_min(y), by1 = wave_max(y);
     const float W = root->z;
     float fx = 0.f, fy = 0.f, z = -1.0f;
-    int sp = 1, np = 0, ic = 0;
+    int sp = 1, np = 0, ic = 0;   // wave-uniform; kept in scalar registers via readfirstlane
     bool overflow = false;
     uint32_t rounds = 0;
     if (lane == 0) stack[0] = 0u;
@@ -137,9 +141,9 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
             const int nacc = __popcll(macc);
             if (ic + nacc > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
             if (act && pass) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)ca.z, 0.f);
-            ic += nacc;
+            ic = __builtin_amdgcn_readfirstlane(ic + nacc);
             if (act && !pass) pend[np + __popcll(mrej & lanemask_lt())] = id;
-            np += __popcll(mrej);
+            np = __builtin_amdgcn_readfirstlane(np + __popcll(mrej));
             __syncthreads();
         }
         if (pressure || np >= WAVE || (sp == 0 && np > 0)) {
@@ -177,10 +181,11 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
             const uint64_t macc = __ballot(acc);
             int mtot;
             const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
+            mtot = __builtin_amdgcn_readfirstlane(mtot);
             const int nacc = __popcll(macc);
             if (ic + nacc + mtot > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
             if (acc) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
-            ic += nacc;
+            ic = __builtin_amdgcn_readfirstlane(ic + nacc);
             if (ofast) {
                 float2 q[WALK_FAST_LEAF];
 #pragma unroll
@@ -190,7 +195,7 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
                 for (int j = 0; j < WALK_FAST_LEAF; ++j)
                     if ((uint32_t)j < cnt) ilist[ic + moff + j] = make_float4(q[j].x, q[j].y, 1.0f, 0.f);
             }
-            ic += mtot;
+            ic = __builtin_amdgcn_readfirstlane(ic + mtot);
             // large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF): one at a time
             uint64_t mbig = __ballot(open && !ofast);
             while (mbig) {
@@ -211,6 +216,7 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
             const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
             int ctot;
             const int coff = wave_excl_scan(nch, &ctot);
+            ctot = __builtin_amdgcn_readfirstlane(ctot);
             if (sp + ctot > WALK_STACK) { overflow = true; break; }   // unreachable for a well-formed tree
             if (desc) {
                 int o = sp + coff;
@@ -219,7 +225,7 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
                 if (cb.z != TSNE_NONE) stack[o++] = cb.z;
                 if (cb.w != TSNE_NONE) stack[o++] = cb.w;
             }
-            sp += ctot;
+            sp = __builtin_amdgcn_readfirstlane(sp + ctot);
             __syncthreads();
         }
     }
