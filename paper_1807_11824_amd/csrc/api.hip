@@ -59,6 +59,9 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     q = take(4 * (n + 1));                           if (c) c->cellseq = (uint32_t *)q;
     q = take(16 * (n + 1));                          if (c) c->ps = (double2 *)q;
     q = take(sizeof(Cell) * (size_t)cap);            if (c) { c->cells = (Cell *)q; c->cap_cells = cap; }
+    const int32_t big_cap = (int32_t)(n / 8 + 1024);
+    q = take(sizeof(uint32_t));                      if (c) c->big_count = (uint32_t *)q;
+    q = take(sizeof(uint2) * (size_t)big_cap);       if (c) { c->big_list = (uint2 *)q; c->big_cap = big_cap; }
     q = take(8 * n);                                 if (c) c->R = (float2 *)q;
     q = take(8 * n);                                 if (c) c->A = (float2 *)q;
     q = take(8 * n);                                 if (c) c->Yi = (float2 *)q;
@@ -117,19 +120,24 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
 {
     hipError_t e;
     const bool two = c->p.overlap && c->stream2;
+    const bool late = c->p.overlap == 2;             // attraction beside the walk instead of beside the tree build
     hipStream_t sa = two ? c->stream2 : c->stream;   // where the attractive kernel runs
-    if (ev) (void)hipEventRecord(ev[0], c->stream);
-    if ((e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
-    if (two) {
+    auto fork_attract = [&]() -> int {
         if ((e = hipEventRecord(c->ev_fork, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
         if ((e = hipStreamWaitEvent(c->stream2, c->ev_fork, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
         if (ev) (void)hipEventRecord(ev[3], sa);
         if ((e = launch_attract(c, d_Y, sa)) != hipSuccess) return fail_hip(c, e, "attract");
         if (ev) (void)hipEventRecord(ev[4], sa);
         if ((e = hipEventRecord(c->ev_join, c->stream2)) != hipSuccess) return fail_hip(c, e, "event record");
-    }
+        return TSNE_OK;
+    };
+    int rc;
+    if (ev) (void)hipEventRecord(ev[0], c->stream);
+    if ((e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
+    if (two && !late && (rc = fork_attract()) != TSNE_OK) return rc;
     if ((e = launch_tree_build(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree build");
     if (ev) (void)hipEventRecord(ev[1], c->stream);
+    if (two && late && (rc = fork_attract()) != TSNE_OK) return rc;
     if ((e = launch_walk(c, c->stream)) != hipSuccess) return fail_hip(c, e, "walk");
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     if (two) {

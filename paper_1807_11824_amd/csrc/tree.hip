@@ -175,9 +175,11 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint32_t *__
                                                               const uint32_t *__restrict__ hist,
                                                               const uint32_t *__restrict__ dtot, int nblk)
 {
-    __shared__ uint32_t whist[4][256];   // per-wave running digit counts
+    __shared__ uint32_t whist[4][256];   // per-wave running digit counts, later per-wave starts
     __shared__ uint32_t gbase[256];      // global start of (digit, this block)
-    __shared__ uint32_t dscan[256];
+    __shared__ uint32_t lstart[256];     // start of the digit inside the locally sorted tile
+    __shared__ uint32_t dscan[4];
+    __shared__ uint32_t skey[SORT_TILE], sidx[SORT_TILE];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     for (int k = 0; k < 4; ++k) whist[k][tid] = 0;
     // exclusive scan of the 256 digit totals
@@ -188,17 +190,18 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint32_t *__
         __syncthreads();
         uint32_t wb = 0;
         for (int k = 0; k < w; ++k) wb += dscan[k];
-        __syncthreads();
         gbase[tid] = wb + (uint32_t)ex + hist[tid * nblk + blockIdx.x];
     }
     __syncthreads();
-    const int base = blockIdx.x * SORT_TILE + w * (WAVE * SORT_ITEMS);
-    uint32_t key[SORT_ITEMS], rank[SORT_ITEMS];
+    const int tile0 = blockIdx.x * SORT_TILE;
+    const int base = tile0 + w * (WAVE * SORT_ITEMS);
+    uint32_t key[SORT_ITEMS], val[SORT_ITEMS], rank[SORT_ITEMS];
 #pragma unroll
     for (int r = 0; r < SORT_ITEMS; ++r) {
         int e = base + r * WAVE + lane;
         bool valid = e < n;
         key[r] = valid ? keys_in[e] : 0u;
+        val[r] = valid ? idx_in[e] : 0u;
         uint32_t d = (key[r] >> shift) & 0xFFu;
         // lanes of this round holding the same digit
         uint64_t peers = __ballot(valid);
@@ -214,29 +217,77 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint32_t *__
         if (valid && before == 0) whist[w][d] = pre + (uint32_t)__popcll(peers);
         __syncthreads();
     }
-    // start of each wave's share inside the block's run of a digit
+    // per digit: where each wave's share starts inside the block's run, and where the run starts
+    // inside the locally sorted tile
     {
-        uint32_t c0 = whist[0][tid], c1 = whist[1][tid], c2 = whist[2][tid];
+        const uint32_t c0 = whist[0][tid], c1 = whist[1][tid], c2 = whist[2][tid], c3 = whist[3][tid];
+        int tot;
+        const int ex = wave_excl_scan((int)(c0 + c1 + c2 + c3), &tot);
         __syncthreads();
+        if (lane == 0) dscan[w] = (uint32_t)tot;
         whist[0][tid] = 0; whist[1][tid] = c0; whist[2][tid] = c0 + c1; whist[3][tid] = c0 + c1 + c2;
+        __syncthreads();
+        uint32_t wb = 0;
+        for (int k = 0; k < w; ++k) wb += dscan[k];
+        lstart[tid] = wb + (uint32_t)ex;
     }
     __syncthreads();
+    // stable local sort through LDS ...
 #pragma unroll
     for (int r = 0; r < SORT_ITEMS; ++r) {
         int e = base + r * WAVE + lane;
         if (e < n) {
             uint32_t d = (key[r] >> shift) & 0xFFu;
-            uint32_t pos = gbase[d] + whist[w][d] + rank[r];
-            keys_out[pos] = key[r];
-            idx_out[pos] = idx_in[e];
+            uint32_t lp = lstart[d] + whist[w][d] + rank[r];
+            skey[lp] = key[r];
+            sidx[lp] = val[r];
         }
+    }
+    __syncthreads();
+    // ... so that consecutive threads write consecutive addresses within each digit's run
+    const int cnt = min(SORT_TILE, n - tile0);
+    for (int j = tid; j < cnt; j += SORT_THREADS) {
+        const uint32_t k = skey[j];
+        const uint32_t d = (k >> shift) & 0xFFu;
+        const uint32_t pos = gbase[d] + ((uint32_t)j - lstart[d]);
+        keys_out[pos] = k;
+        idx_out[pos] = sidx[j];
     }
 }
 
 // ------------------------------------------------------------------ cells opened at each position
+// The searches below are chains of dependent reads of the sorted keys, almost always within a
+// few dozen positions of where they start.  Each workgroup therefore keeps the keys of its own
+// positions plus a halo on both sides in LDS; reads outside that window go to memory.
+constexpr int KEY_HALO = 256;
+
+struct KeyWindow {
+    const uint32_t *__restrict__ keys;   // sorted keys in memory
+    const uint32_t *lds;                 // keys[lo, lo + len)
+    uint32_t lo, len;
+    __device__ __forceinline__ uint32_t operator[](uint32_t q) const
+    {
+        const uint32_t off = q - lo;
+        return off < len ? lds[off] : keys[q];
+    }
+};
+
+// Cooperative fill; the caller synchronises the workgroup afterwards.
+__device__ __forceinline__ KeyWindow key_window_fill(const uint32_t *__restrict__ keys, uint32_t n, uint32_t first,
+                                                     uint32_t count, uint32_t *lds)
+{
+    KeyWindow w;
+    w.keys = keys;
+    w.lds = lds;
+    w.lo = first > (uint32_t)KEY_HALO ? first - KEY_HALO : 0u;
+    const uint32_t hi = min(n, first + count + KEY_HALO);
+    w.len = hi > w.lo ? hi - w.lo : 0u;
+    for (uint32_t t = threadIdx.x; t < w.len; t += blockDim.x) lds[t] = keys[w.lo + t];
+    return w;
+}
+
 // Sorted keys: the positions whose key shifted right by sh equals pre form one contiguous run.
-__device__ __forceinline__ uint32_t run_end(const uint32_t *__restrict__ keys, uint32_t n, uint32_t p, int sh,
-                                            uint32_t pre)
+__device__ __forceinline__ uint32_t run_end(const KeyWindow &keys, uint32_t n, uint32_t p, int sh, uint32_t pre)
 {
     uint32_t lo = p, hi, step = 1;
     for (;;) {
@@ -253,7 +304,7 @@ __device__ __forceinline__ uint32_t run_end(const uint32_t *__restrict__ keys, u
     return hi;
 }
 
-__device__ __forceinline__ uint32_t run_begin(const uint32_t *__restrict__ keys, uint32_t p, int sh, uint32_t pre)
+__device__ __forceinline__ uint32_t run_begin(const KeyWindow &keys, uint32_t p, int sh, uint32_t pre)
 {
     int64_t lo, hi = p, step = 1;
     for (;;) {
@@ -271,7 +322,7 @@ __device__ __forceinline__ uint32_t run_begin(const uint32_t *__restrict__ keys,
 }
 
 // Depths [tmin, tend) of the cells that start at sorted position p.
-__device__ __forceinline__ void levels_at(const uint32_t *__restrict__ keys, uint32_t n, uint32_t p, int B,
+__device__ __forceinline__ void levels_at(const KeyWindow &keys, uint32_t n, uint32_t p, int B,
                                           uint32_t C, int *tmin_out, int *tend_out)
 {
     uint32_t key = keys[p];
@@ -306,6 +357,46 @@ __device__ __forceinline__ void levels_at(const uint32_t *__restrict__ keys, uin
     *tend_out = tend;
 }
 
+// The same answer without any search when leaf_cap is small: the cell of depth s around p holds
+// more than C points iff at least C of the 2C nearest positions (C on either side) share p's
+// top s digits (L[j], R[j]: number of leading digits p shares with positions p-j, p+j).
+constexpr int LEVELS_WINDOW_MAXC = 16;
+
+__device__ __forceinline__ int common_digits(uint32_t a, uint32_t b, int B)
+{
+    const uint32_t x = a ^ b;
+    return x ? B - 1 - ((31 - __clz((int)x)) >> 1) : B;
+}
+
+__device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n, uint32_t p, int B, int C,
+                                              int *tmin_out, int *tend_out)
+{
+    const uint32_t key = keys[p];
+    const int tmin = p == 0 ? 0 : (key == keys[p - 1] ? B + 1 : common_digits(key, keys[p - 1], B) + 1);
+    int L[LEVELS_WINDOW_MAXC], R[LEVELS_WINDOW_MAXC];
+#pragma unroll
+    for (int j = 1; j <= LEVELS_WINDOW_MAXC; ++j) {
+        L[j - 1] = (j <= C && p >= (uint32_t)j) ? common_digits(key, keys[p - j], B) : -1;
+        R[j - 1] = (j <= C && p + j < n) ? common_digits(key, keys[p + j], B) : -1;
+    }
+    // deepest s in [0, B] with at least C of the 2C neighbours sharing s digits (-1 if none):
+    // the count is non-increasing in s, so bisect
+    int lo = -1, hi = B + 1;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < LEVELS_WINDOW_MAXC; ++j) cnt += (L[j] >= mid) + (R[j] >= mid);
+        if (cnt >= C) lo = mid; else hi = mid;
+    }
+    const int smax = lo;
+    // cell (t, p) exists iff t == 0 or the depth t-1 cell around p holds more than C points
+    int tend = min(B, smax + 1) + 1;
+    if (tend < tmin) tend = tmin;
+    *tmin_out = tmin;
+    *tend_out = tend;
+}
+
 // Also moves the points into spatial order (step 4) and reduces each tile's (cells, sum x, sum y).
 __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__restrict__ Y,
                                                                const uint32_t *__restrict__ keys,
@@ -315,18 +406,26 @@ __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__r
 {
     __shared__ double sx[4], sy[4];
     __shared__ uint32_t sc[4];
-    int p0 = blockIdx.x * LEVEL_TILE + threadIdx.x * LEVEL_ITEMS;
+    __shared__ uint32_t kwin[LEVEL_TILE + 2 * KEY_HALO];
+    const KeyWindow kw = key_window_fill(keys, (uint32_t)n, blockIdx.x * LEVEL_TILE, LEVEL_TILE, kwin);
+    __syncthreads();
     double ax = 0.0, ay = 0.0;
     uint32_t ac = 0;
+    float2 y[LEVEL_ITEMS];
 #pragma unroll
     for (int k = 0; k < LEVEL_ITEMS; ++k) {
-        int p = p0 + k;
+        const int p = blockIdx.x * LEVEL_TILE + k * LEVEL_THREADS + threadIdx.x;
+        y[k] = p < n ? Y[min(perm[p], (uint32_t)n - 1u)] : make_float2(0.f, 0.f);
+    }
+#pragma unroll
+    for (int k = 0; k < LEVEL_ITEMS; ++k) {
+        const int p = blockIdx.x * LEVEL_TILE + k * LEVEL_THREADS + threadIdx.x;
         if (p < n) {
-            float2 y = Y[min(perm[p], (uint32_t)n - 1u)];
-            Ys[p] = y;
-            ax += (double)y.x; ay += (double)y.y;
+            Ys[p] = y[k];
+            ax += (double)y[k].x; ay += (double)y[k].y;
             int tmin, tend;
-            levels_at(keys, (uint32_t)n, (uint32_t)p, B, (uint32_t)C, &tmin, &tend);
+            if (C <= LEVELS_WINDOW_MAXC) levels_window(kw, (uint32_t)n, (uint32_t)p, B, C, &tmin, &tend);
+            else levels_at(kw, (uint32_t)n, (uint32_t)p, B, (uint32_t)C, &tmin, &tend);
             lev[p] = (uint16_t)(tmin | (tend << 8));
             ac += (uint32_t)(tend - tmin);
         }
@@ -348,8 +447,9 @@ __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__r
 // One block: exclusive prefix over the tile partials; total cell count to *ncells.
 __global__ __launch_bounds__(1024) void scan_partials(ScanPart *__restrict__ part, int nparts,
                                                       uint32_t *__restrict__ ncells, uint32_t cap_cells,
-                                                      uint32_t *status)
+                                                      uint32_t *status, uint32_t *__restrict__ big_count)
 {
+    if (threadIdx.x == 0) *big_count = 0u;    // list of large cells filled by write_cells
     __shared__ double wx[16], wy[16];
     __shared__ uint32_t wc[16];
     const int tid = threadIdx.x, w = tid >> 6;
@@ -441,7 +541,7 @@ __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restr
 }
 
 // First position in [s, e) whose digit (2 bits at sh) is >= q; e if none.
-__device__ __forceinline__ uint32_t digit_lower_bound(const uint32_t *__restrict__ keys, uint32_t s, uint32_t e,
+__device__ __forceinline__ uint32_t digit_lower_bound(const KeyWindow &keys, uint32_t s, uint32_t e,
                                                       int sh, uint32_t q)
 {
     while (s < e) {
@@ -451,23 +551,41 @@ __device__ __forceinline__ uint32_t digit_lower_bound(const uint32_t *__restrict
     return s;
 }
 
+// A cell whose run of positions ends inside the workgroup's key window is finished on the spot
+// (all its searches stay in LDS).  The few large cells near the top of the tree would each be a
+// chain of dozens of dependent memory reads in a single lane; they are put on a list instead
+// and finished by write_big_cells, four lanes per cell.
 __global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ keys, const uint16_t *__restrict__ lev,
                                                    const uint32_t *__restrict__ cellseq,
                                                    const double2 *__restrict__ ps, int n, int B, int C,
-                                                   Cell *__restrict__ cells, uint32_t cap_cells)
+                                                   Cell *__restrict__ cells, uint32_t cap_cells,
+                                                   uint32_t *__restrict__ big_count, uint2 *__restrict__ big_list,
+                                                   uint32_t big_cap)
 {
+    __shared__ uint32_t kwin[256 + 2 * KEY_HALO];
+    const KeyWindow kw = key_window_fill(keys, (uint32_t)n, blockIdx.x * 256u, 256u, kwin);
+    __syncthreads();
     uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= (uint32_t)n) return;
     uint32_t l = lev[p];
     int tmin = (int)(l & 0xFFu), tend = (int)(l >> 8);
     if (tend <= tmin) return;
-    uint32_t key = keys[p];
+    uint32_t key = kw[p];
     uint32_t id0 = cellseq[p];
     double2 s0 = ps[p];
+    const uint32_t wend = kw.lo + kw.len;                  // one past the last position in the window
+    const uint32_t wlast_key = kw.lds[kw.len - 1];
     for (int t = tmin; t < tend; ++t) {
         uint32_t id = id0 + (uint32_t)(t - tmin);
         if (id >= cap_cells) return;
-        uint32_t e = (t == 0) ? (uint32_t)n : run_end(keys, (uint32_t)n, p, 2 * (B - t), key >> (2 * (B - t)));
+        // does the cell end inside the window?
+        const bool inside = wend >= (uint32_t)n || (t > 0 && (wlast_key >> (2 * (B - t))) != (key >> (2 * (B - t))));
+        if (!inside) {
+            const uint32_t slot = atomicAdd(big_count, 1u);
+            if (slot < big_cap) { big_list[slot] = make_uint2(p, (uint32_t)t); continue; }
+            // list full (cannot happen for capacity n/8 + 1024 unless most cells are huge): finish it here
+        }
+        uint32_t e = (t == 0) ? (uint32_t)n : run_end(kw, (uint32_t)n, p, 2 * (B - t), key >> (2 * (B - t)));
         uint32_t cnt = e - p;
         double2 s1 = ps[e];
         Cell c;
@@ -483,10 +601,10 @@ __global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ 
             uint32_t kids[3];
             int nk = 0;
             uint32_t s = p;
-            uint32_t qfirst = (keys[p] >> sh) & 3u;
+            uint32_t qfirst = (key >> sh) & 3u;
             for (uint32_t q = qfirst + 1; q < 4; ++q) {
-                uint32_t b = digit_lower_bound(keys, s, e, sh, q);
-                if (b < e && ((keys[b] >> sh) & 3u) == q) kids[nk++] = cellseq[b];
+                uint32_t b = digit_lower_bound(kw, s, e, sh, q);
+                if (b < e && ((kw[b] >> sh) & 3u) == q) kids[nk++] = cellseq[b];
                 s = b;
             }
             if (nk > 0) c.c1 = kids[0];
@@ -495,6 +613,82 @@ __global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ 
         }
         cells[id] = c;
     }
+}
+
+// First position x in [lo, n) with (keys[x] >> sh) >= target, n if none (keys sorted).
+__device__ __forceinline__ uint32_t shifted_lower_bound(const uint32_t *__restrict__ keys, uint32_t lo, uint32_t n,
+                                                        int sh, uint64_t target)
+{
+    uint32_t hi = n;
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if ((uint64_t)(keys[mid] >> sh) < target) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// Four lanes per listed cell: lane 0 finds the end of the cell, lanes 1-3 the first position of
+// quadrants 1-3 among its points (all four are lower bounds in the globally sorted keys).
+__global__ __launch_bounds__(256) void write_big_cells(const uint32_t *__restrict__ keys, const uint16_t *__restrict__ lev,
+                                                       const uint32_t *__restrict__ cellseq,
+                                                       const double2 *__restrict__ ps, int n, int B, int C,
+                                                       Cell *__restrict__ cells, uint32_t cap_cells,
+                                                       const uint32_t *__restrict__ big_count,
+                                                       const uint2 *__restrict__ big_list, uint32_t big_cap)
+{
+    const uint32_t item = (blockIdx.x * 256u + threadIdx.x) >> 2;
+    const int role = (int)(threadIdx.x & 3u);
+    const uint32_t m = min(*big_count, big_cap);
+    const bool live = item < m;
+    uint32_t p = 0;
+    int t = 0;
+    if (live) { const uint2 it = big_list[item]; p = it.x; t = (int)it.y; }
+    const uint32_t key = live ? keys[p] : 0u;
+    uint32_t found = (uint32_t)n;
+    if (live) {
+        if (role == 0) {
+            if (t > 0) {
+                const int sh = 2 * (B - t);
+                found = shifted_lower_bound(keys, p, (uint32_t)n, sh, (uint64_t)(key >> sh) + 1ull);
+            }
+        } else if (t < B) {
+            const int sh = 2 * (B - t - 1);
+            const uint64_t parent = t > 0 ? (uint64_t)(key >> (2 * (B - t))) : 0ull;
+            found = shifted_lower_bound(keys, p, (uint32_t)n, sh, (parent << 2) + (uint64_t)role);
+        }
+    }
+    const int base = (int)(threadIdx.x & 63u) & ~3;
+    const uint32_t e = __shfl(found, base, WAVE);
+    const uint32_t b1 = min(__shfl(found, base + 1, WAVE), e);
+    const uint32_t b2 = min(__shfl(found, base + 2, WAVE), e);
+    const uint32_t b3 = min(__shfl(found, base + 3, WAVE), e);
+    if (!live || role != 0) return;
+    const uint32_t l = lev[p];
+    const uint32_t id = cellseq[p] + (uint32_t)(t - (int)(l & 0xFFu));
+    if (id >= cap_cells) return;
+    const uint32_t cnt = e - p;
+    const double2 s0 = ps[p], s1 = ps[e];
+    Cell c;
+    c.cx = (float)((s1.x - s0.x) / (double)cnt);
+    c.cy = (float)((s1.y - s0.y) / (double)cnt);
+    c.cnt = cnt;
+    const bool leaf = cnt <= (uint32_t)C || t == B;
+    c.meta = (uint32_t)t | (leaf ? 0x100u : 0u);
+    c.lo = p;
+    c.c1 = c.c2 = c.c3 = TSNE_NONE;
+    if (!leaf) {
+        // quadrant q > first quadrant exists iff its first position precedes the next boundary
+        const uint32_t qfirst = (key >> (2 * (B - t - 1))) & 3u;
+        const uint32_t bnd[5] = {p, b1, b2, b3, e};
+        uint32_t kids[3];
+        int nk = 0;
+        for (uint32_t q = qfirst + 1; q < 4; ++q)
+            if (bnd[q] < bnd[q + 1]) kids[nk++] = cellseq[bnd[q]];
+        if (nk > 0) c.c1 = kids[0];
+        if (nk > 1) c.c2 = kids[1];
+        if (nk > 2) c.c3 = kids[2];
+    }
+    cells[id] = c;
 }
 
 // ------------------------------------------------------------------ export (tests only)
@@ -569,9 +763,12 @@ hipError_t launch_tree_build(tsne_ctx *c, hipStream_t s)
     hipLaunchKernelGGL(gather_levels, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B, C,
                        c->Ys, c->lev, c->part);
     hipLaunchKernelGGL(scan_partials, dim3(1), dim3(1024), 0, s, c->part, nl, c->ncells, (uint32_t)c->cap_cells,
-                       c->status);
+                       c->status, c->big_count);
     hipLaunchKernelGGL(downsweep, dim3(nl), dim3(LEVEL_THREADS), 0, s, c->Ys, c->lev, n, c->part, c->cellseq, c->ps);
     hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, c->keys[cur], c->lev, c->cellseq, c->ps, n, B, C,
-                       c->cells, (uint32_t)c->cap_cells);
+                       c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list, (uint32_t)c->big_cap);
+    hipLaunchKernelGGL(write_big_cells, dim3((c->big_cap * 4 + 255) / 256), dim3(256), 0, s, c->keys[cur], c->lev,
+                       c->cellseq, c->ps, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
+                       (uint32_t)c->big_cap);
     return hipGetLastError();
 }
