@@ -6,14 +6,17 @@
 // path.  The walk alternates between two roles so that no lane ever waits on a pointer chase:
 //
 //   lanes = cells    up to 64 cells are popped from the wave's stack and tested at once.
-//        sift        cheap test against the group's bounding box: the distance from y_cell to
-//                    the box is a lower bound of the distance to every point, and every step of
-//                    the single-precision test is monotone, so passing here implies passing for
-//                    each point, bit for bit.  Cells that fail wait on a short pending list.
+//        sift        two cheap tests.  Against the group's bounding box: the distance from y_cell
+//                    to the box is a lower bound of the distance to every point, and every step
+//                    of the single-precision test is monotone, so passing here implies passing
+//                    for each point, bit for bit.  Against four witness points of the group: if
+//                    one of them fails Eq. (14) the cell is rejected.  The few cells neither
+//                    test decides wait on a short pending list.
 //        settle      64 pending cells at a time: minimum of |y_i - y_cell|^2 over the group's
-//                    points (LDS broadcasts), then the exact test.  Accepted cells go to an
-//                    interaction list in LDS as (y_cell, N_cell); rejected inner cells push
-//                    their children; rejected leaves put their points on the list with N = 1.
+//                    points (LDS broadcasts), then the exact test.
+//                    Either way accepted cells go to an interaction list in LDS as
+//                    (y_cell, N_cell); rejected inner cells push their children; rejected leaves
+//                    put their points on the list with N = 1.
 //   lanes = points   the list is drained: every lane adds N w^2 (y_i - y_cell) and N w,
 //                    w = 1/(1+|y_i - y_cell|^2), for its own point (Eq. (15) and the Z note
 //                    that follows it); list entries are LDS broadcasts.
@@ -24,14 +27,31 @@
 
 #include <math.h>
 
-constexpr int WALK_STACK = 1024;     // stack entries
-constexpr int WALK_ROOM = 304;       // settle needs room for 256 children + 48 (depth-first slack)
+#ifndef WALK_STACK_N
+#define WALK_STACK_N 512
+#endif
+constexpr int WALK_STACK = WALK_STACK_N;   // stack entries
+constexpr int WALK_SLACK = 48;       // head room for a depth-first descent (3 entries per level, 16 levels)
 constexpr int WALK_PEND = 128;       // pending list entries
 #ifndef WALK_LIST_N
 #define WALK_LIST_N 576
 #endif
 constexpr int WALK_LIST = WALK_LIST_N;       // interaction list entries (16 B each), >= 64 + 64 * WALK_FAST_LEAF
 constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied by their own lane
+
+#ifdef WALK_STATS
+// instrumentation for tuning builds only: sums and maxima over all waves of one launch
+__device__ unsigned long long g_walk_stats[16];
+extern "C" int tsne_debug_walk_stats(unsigned long long *out, int reset)
+{
+    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_walk_stats), sizeof(g_walk_stats)) != hipSuccess) return -1;
+    if (reset) { unsigned long long z[16] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(g_walk_stats), z, sizeof(z)); }
+    return 0;
+}
+#define WSTAT(stmt) stmt
+#else
+#define WSTAT(stmt)
+#endif
 
 // side^2 < theta^2 * d2, with d2 = fma(dy, dy, dx*dx): one rounding per operation.
 __device__ __forceinline__ float dist2_rounded(float dx, float dy)
@@ -113,127 +133,141 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
     int sp = 1, np = 0, ic = 0;   // wave-uniform; kept in scalar registers via readfirstlane
     bool overflow = false;
     uint32_t rounds = 0;
+    WSTAT(unsigned st_sift = 0; unsigned st_settle = 0; unsigned st_press = 0; unsigned st_maxsp = 0; unsigned st_inter = 0;
+          unsigned st_sifted = 0; unsigned st_settled = 0;)
     if (lane == 0) stack[0] = 0u;
     __syncthreads();
+    // four members of the group used as quick witnesses: if Eq. (14) fails for one of them the
+    // cell is rejected for the group without looking at the other 60
+    const float2 w0 = pts[0], w1 = pts[21], w2 = pts[42], w3 = pts[63];
     while (sp > 0 || np > 0) {
-        // every cell is sifted at most once and settled at most once, so more rounds than
-        // 2 * cells means a malformed tree; ids and member positions are clamped so that even
-        // then no access leaves the arrays
+        // every cell is popped from the stack at most once and from the pending list at most
+        // once, so more rounds than 2 * cells means a malformed tree; ids and member positions
+        // are clamped so that even then no access leaves the arrays
         if (++rounds > 2u * m_cells + 2u) { overflow = true; break; }
-        // Stack bound: settling 64 cells pushes at most 256 children, so it only runs with
-        // WALK_ROOM entries free; above that mark the wave settles the single top cell per
-        // round instead -- plain depth-first search, which adds at most 3 entries per level
-        // below the popped cell (<= 45 for 16 levels) before it shrinks again.
-        const bool pressure = sp > WALK_STACK - WALK_ROOM;
-        if (!pressure && sp > 0 && np < WAVE) {
-            // ---- sift: bounding-box test of up to 64 stacked cells
-            const int take = sp < WAVE ? sp : WAVE;
-            const bool act = lane < take;
-            const uint32_t id = act ? min(stack[sp - take + lane], m_cells - 1u) : 0u;
+        // Stack bound: every popped cell pushes at most 4 children.  A round takes as many
+        // cells as still leave WALK_SLACK entries free afterwards whatever they push; when not
+        // even one cell fits that rule the wave takes the single top cell per round -- plain
+        // depth-first search, which adds at most 3 entries per level below the popped cell
+        // (<= 45 for 16 levels) before it shrinks again.  So sp never passes WALK_STACK - 3.
+        const int room = WALK_STACK - WALK_SLACK - sp;
+        const bool pressure = room < 3;
+        const bool from_pending = room >= 4 && (np >= WAVE || sp == 0);
+        // (np >= 64 in a stack round only happens when the stack is nearly full: settle at once,
+        //  so that the pending list cannot outgrow its 128 entries)
+        const bool exact = from_pending || pressure || np >= WAVE;
+        int take;
+        uint32_t id;
+        if (from_pending) {
+            take = min(min(np, WAVE), room >> 2);            // pending cells free no stack entry
+            id = lane < take ? pend[np - take + lane] : 0u;
+            np -= take;
+            WSTAT(st_settle++; st_settled += take;)
+        } else {
+            take = pressure ? 1 : min(min(sp, WAVE), room / 3);   // a popped cell nets at most +3
+            id = lane < take ? stack[sp - take + lane] : 0u;
+            WSTAT(st_sift++; st_sifted += take; if ((unsigned)sp > st_maxsp) st_maxsp = sp; if (pressure) st_press++;)
             sp -= take;
-            const uint4 ca = *reinterpret_cast<const uint4 *>(cells + id);
-            const float cx = __uint_as_float(ca.x), cy = __uint_as_float(ca.y);
-            const float side = ldexpf(W, -(int)(ca.w & 0xFFu));   // exact: W is a power of two
-            const float dx = fmaxf(fmaxf(bx0 - cx, cx - bx1), 0.0f);
-            const float dy = fmaxf(fmaxf(by0 - cy, cy - by1), 0.0f);
-            const bool pass = passes(side * side, theta2, dist2_rounded(dx, dy));
-            const uint64_t macc = __ballot(act && pass), mrej = __ballot(act && !pass);
-            const int nacc = __popcll(macc);
-            if (ic + nacc > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
-            if (act && pass) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)ca.z, 0.f);
-            ic = __builtin_amdgcn_readfirstlane(ic + nacc);
-            if (act && !pass) pend[np + __popcll(mrej & lanemask_lt())] = id;
-            np = __builtin_amdgcn_readfirstlane(np + __popcll(mrej));
-            __syncthreads();
         }
-        if (pressure || np >= WAVE || (sp == 0 && np > 0)) {
-            // ---- settle: exact test of up to 64 cells (or of the top of the stack under pressure)
-            int take;
-            uint32_t id;
-            if (pressure) {
-                take = 1;
-                id = lane == 0 ? stack[sp - 1] : 0u;
-                sp -= 1;
-            } else {
-                take = np < WAVE ? np : WAVE;
-                id = lane < take ? pend[np - take + lane] : 0u;
-                np -= take;
-            }
-            const bool act = lane < take;
-            id = min(id, m_cells - 1u);
-            const uint4 *cp = reinterpret_cast<const uint4 *>(cells + id);
-            const uint4 ca = cp[0], cb = cp[1];
-            const float cx = __uint_as_float(ca.x), cy = __uint_as_float(ca.y);
-            const uint32_t cnt = ca.z;
-            const bool leaf = (ca.w >> 8) & 1u;
-            const float side = ldexpf(W, -(int)(ca.w & 0xFFu));
+        const bool act = lane < take;
+        id = min(id, m_cells - 1u);
+        const uint4 *cp = reinterpret_cast<const uint4 *>(cells + id);
+        const uint4 ca = cp[0], cb = cp[1];
+        const float cx = __uint_as_float(ca.x), cy = __uint_as_float(ca.y);
+        const uint32_t cnt = ca.z;
+        const bool leaf = (ca.w >> 8) & 1u;
+        const float side = ldexpf(W, -(int)(ca.w & 0xFFu));   // exact: W is a power of two
+        const float side2 = side * side;
+        bool pass, decided;
+        if (exact) {
+            // settle: minimum squared distance from y_cell to the 64 points of the group
             float dmin = INFINITY;
 #pragma unroll 8
             for (int i = 0; i < WAVE; ++i) {
                 const float2 q = pts[i];
                 dmin = fminf(dmin, dist2_rounded(q.x - cx, q.y - cy));
             }
-            const bool pass = passes(side * side, theta2, dmin);
-            const bool acc = act && pass;
-            const bool open = act && !pass && leaf;
-            const bool desc = act && !pass && !leaf;
-            const bool ofast = open && cnt <= (uint32_t)WALK_FAST_LEAF;
-            const uint64_t macc = __ballot(acc);
-            int mtot;
-            const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
-            mtot = __builtin_amdgcn_readfirstlane(mtot);
-            const int nacc = __popcll(macc);
-            if (ic + nacc + mtot > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
-            if (acc) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
-            ic = __builtin_amdgcn_readfirstlane(ic + nacc);
-            if (ofast) {
-                float2 q[WALK_FAST_LEAF];
-#pragma unroll
-                for (int j = 0; j < WALK_FAST_LEAF; ++j)
-                    q[j] = Ys[min(cb.x + (uint32_t)j, (uint32_t)n - 1u)];
-#pragma unroll
-                for (int j = 0; j < WALK_FAST_LEAF; ++j)
-                    if ((uint32_t)j < cnt) ilist[ic + moff + j] = make_float4(q[j].x, q[j].y, 1.0f, 0.f);
-            }
-            ic = __builtin_amdgcn_readfirstlane(ic + mtot);
-            // large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF): one at a time
-            uint64_t mbig = __ballot(open && !ofast);
-            while (mbig) {
-                const int b = __ffsll((long long)mbig) - 1;
-                mbig &= mbig - 1;
-                const uint32_t lo_b = __shfl(cb.x, b, WAVE), cnt_b = __shfl(cnt, b, WAVE);
-                for (uint32_t j0 = 0; j0 < cnt_b; j0 += WAVE) {
-                    const int m = (int)min((uint32_t)WAVE, cnt_b - j0);
-                    if (ic + m > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
-                    if (lane < m) {
-                        const float2 q = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
-                        ilist[ic + lane] = make_float4(q.x, q.y, 1.0f, 0.f);
-                    }
-                    ic += m;
-                }
-            }
-            // children of rejected inner cells
-            const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
-            int ctot;
-            const int coff = wave_excl_scan(nch, &ctot);
-            ctot = __builtin_amdgcn_readfirstlane(ctot);
-            if (sp + ctot > WALK_STACK) { overflow = true; break; }   // unreachable for a well-formed tree
-            if (desc) {
-                int o = sp + coff;
-                stack[o++] = id + 1u;
-                if (cb.y != TSNE_NONE) stack[o++] = cb.y;
-                if (cb.z != TSNE_NONE) stack[o++] = cb.z;
-                if (cb.w != TSNE_NONE) stack[o++] = cb.w;
-            }
-            sp = __builtin_amdgcn_readfirstlane(sp + ctot);
-            __syncthreads();
+            pass = passes(side2, theta2, dmin);
+            decided = true;
+        } else {
+            // sift: the bounding box settles most acceptances, the witnesses most rejections
+            const float dx = fmaxf(fmaxf(bx0 - cx, cx - bx1), 0.0f);
+            const float dy = fmaxf(fmaxf(by0 - cy, cy - by1), 0.0f);
+            pass = passes(side2, theta2, dist2_rounded(dx, dy));
+            const float dw = fminf(fminf(dist2_rounded(w0.x - cx, w0.y - cy), dist2_rounded(w1.x - cx, w1.y - cy)),
+                                   fminf(dist2_rounded(w2.x - cx, w2.y - cy), dist2_rounded(w3.x - cx, w3.y - cy)));
+            decided = pass || !passes(side2, theta2, dw);
         }
+        const bool acc = act && pass;
+        const bool und = act && !decided;
+        const bool open = act && decided && !pass && leaf;
+        const bool desc = act && decided && !pass && !leaf;
+        const bool ofast = open && cnt <= (uint32_t)WALK_FAST_LEAF;
+        const uint64_t macc = __ballot(acc);
+        int mtot;
+        const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
+        mtot = __builtin_amdgcn_readfirstlane(mtot);
+        const int nacc = __popcll(macc);
+        if (ic + nacc + mtot > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
+        if (acc) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
+        ic = __builtin_amdgcn_readfirstlane(ic + nacc);
+        if (ofast) {
+            float2 q[WALK_FAST_LEAF];
+#pragma unroll
+            for (int j = 0; j < WALK_FAST_LEAF; ++j)
+                q[j] = Ys[min(cb.x + (uint32_t)j, (uint32_t)n - 1u)];
+#pragma unroll
+            for (int j = 0; j < WALK_FAST_LEAF; ++j)
+                if ((uint32_t)j < cnt) ilist[ic + moff + j] = make_float4(q[j].x, q[j].y, 1.0f, 0.f);
+        }
+        ic = __builtin_amdgcn_readfirstlane(ic + mtot);
+        // undecided cells wait for a full batch (only met in sift rounds, where np < 64)
+        const uint64_t mund = __ballot(und);
+        if (und) pend[np + __popcll(mund & lanemask_lt())] = id;
+        np = __builtin_amdgcn_readfirstlane(np + __popcll(mund));
+        // large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF): one at a time
+        uint64_t mbig = __ballot(open && !ofast);
+        while (mbig) {
+            const int b = __ffsll((long long)mbig) - 1;
+            mbig &= mbig - 1;
+            const uint32_t lo_b = __shfl(cb.x, b, WAVE), cnt_b = __shfl(cnt, b, WAVE);
+            for (uint32_t j0 = 0; j0 < cnt_b; j0 += WAVE) {
+                const int m = (int)min((uint32_t)WAVE, cnt_b - j0);
+                if (ic + m > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
+                if (lane < m) {
+                    const float2 q = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
+                    ilist[ic + lane] = make_float4(q.x, q.y, 1.0f, 0.f);
+                }
+                ic += m;
+            }
+        }
+        // children of rejected inner cells
+        const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
+        int ctot;
+        const int coff = wave_excl_scan(nch, &ctot);
+        ctot = __builtin_amdgcn_readfirstlane(ctot);
+        if (sp + ctot > WALK_STACK) { overflow = true; break; }   // unreachable for a well-formed tree
+        if (desc) {
+            int o = sp + coff;
+            stack[o++] = id + 1u;
+            if (cb.y != TSNE_NONE) stack[o++] = cb.y;
+            if (cb.z != TSNE_NONE) stack[o++] = cb.z;
+            if (cb.w != TSNE_NONE) stack[o++] = cb.w;
+        }
+        sp = __builtin_amdgcn_readfirstlane(sp + ctot);
+        __syncthreads();
     }
     if (overflow) {
         if (lane == 0) atomicOr(status, TSNE_STATUS_WALK_OVERFLOW);
         fx = fy = 0.f; z = 0.f; ic = 0;
     }
     drain(ilist, ic, x, y, fx, fy, z);
+    WSTAT(if (lane == 0) {
+        atomicAdd(&g_walk_stats[0], 1ull); atomicAdd(&g_walk_stats[1], (unsigned long long)st_sift);
+        atomicAdd(&g_walk_stats[2], (unsigned long long)st_settle); atomicAdd(&g_walk_stats[3], (unsigned long long)st_press);
+        atomicAdd(&g_walk_stats[4], (unsigned long long)st_sifted); atomicAdd(&g_walk_stats[5], (unsigned long long)st_settled);
+        atomicMax(&g_walk_stats[6], (unsigned long long)st_maxsp); atomicAdd(&g_walk_stats[7], (unsigned long long)st_maxsp);
+    })
     if (valid) R[min(perm[p], (uint32_t)n - 1u)] = make_float2(fx, fy);
     double zd = wave_sum(valid ? (double)z : 0.0);
     if (lane == 0) zpart[g] = zd;
