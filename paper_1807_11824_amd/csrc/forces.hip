@@ -64,7 +64,13 @@ __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ r
 // Y[r0 - HALO, r0 + ROWS + HALO) in LDS; gathers that fall inside the window are LDS reads, the
 // rest go to memory as before.  Entries of a row are taken in the same lane order as in the
 // kernel above, so both produce the same sums.
-constexpr int AW_ROWS = 256, AW_HALO = 2048, AW_LPR = 16, AW_U = 4;
+#ifndef AW_HALO_N
+#define AW_HALO_N 1280
+#endif
+#ifndef AW_ROWS_N
+#define AW_ROWS_N 128
+#endif
+constexpr int AW_ROWS = AW_ROWS_N, AW_HALO = AW_HALO_N, AW_LPR = 16, AW_U = 4;
 
 __global__ __launch_bounds__(256) void attract_csr_window(const int32_t *__restrict__ row_ptr,
                                                           const int32_t *__restrict__ col, const float *__restrict__ val,

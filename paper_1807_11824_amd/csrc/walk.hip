@@ -113,6 +113,10 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
     __shared__ uint32_t pend[WALK_PEND];
     __shared__ float2 pts[WAVE];
     __shared__ float4 ilist[WALK_LIST];
+#ifdef WALK_LDS_PAD
+    __shared__ uint32_t lds_pad[WALK_LDS_PAD / 4];   // tuning builds: lowers the number of resident groups per CU
+    if (threadIdx.x == 0 && n < 0) lds_pad[0] = 1;
+#endif
     const int lane = (int)threadIdx.x;
     const int g = (int)blockIdx.x;
     const int p = g * WAVE + lane;
