@@ -1,0 +1,135 @@
+"""Full runs through tsne_run / tsne_step: final KL against the oracle's, stop/resume, error paths."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1807_11824_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _golden():
+    with open(os.path.join(HERE, "golden", "oracle_run_kl.json")) as f:
+        return json.load(f)
+
+
+def _gpu_full_run(name, **params):
+    import torch
+    from paper_1807_11824_amd import Tsne, build_P
+    cfg = synth.CONFIGS[name]
+    X, _ = {"cfg1": synth.config1, "cfg2": synth.config2}[name]()
+    dev = torch.device("cuda:0")
+    P = build_P(torch.from_numpy(X).to(dev), cfg["perplexity"], cfg["k"])
+    t = Tsne(cfg["n"], max_nnz=P["nnz"], **params)
+    t.set_P(P["row_ptr"], P["col"], P["val"])
+    Y = torch.from_numpy(synth.y0(cfg["n"])).to(dev)
+    kl0 = t.kl(Y)
+    t.run(Y, 1000)
+    kl1 = t.kl(Y)
+    st = t.status()
+    t.close()
+    return kl0, kl1, st, P["nnz"]
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_final_kl_matches_oracle_run(name):
+    """Same P, same Y0, same parameters: the embeddings differ point by point (the dynamics are
+    chaotic) but the objective they reach must agree within 1 %."""
+    gold = _golden()
+    if name not in gold:
+        pytest.skip(f"no stored oracle run for {name}")
+    kl0, kl1, st, nnz = _gpu_full_run(name)
+    g = gold[name]
+    print(f"{name}: KL start gpu {kl0:.6f} oracle {g['kl_start']:.6f}; final gpu {kl1:.6f} oracle {g['kl_final']:.6f}",
+          flush=True)
+    assert st == 0 and nnz == g["nnz"]
+    assert abs(kl0 - g["kl_start"]) <= 1e-4 * g["kl_start"]      # same P, same Y0, exact Z on both sides
+    assert abs(kl1 - g["kl_final"]) <= 0.01 * g["kl_final"]
+
+
+def test_kl_utility_matches_oracle():
+    import torch
+    from paper_1807_11824_amd import Tsne
+    X, _ = synth.config1(n=1500)
+    P = oracle.build_P(X, 20.0, 60)
+    dev = torch.device("cuda:0")
+    t = Tsne(1500)
+    t.set_P(torch.from_numpy(P["row_ptr"]).to(dev), torch.from_numpy(P["col"]).to(dev),
+            torch.from_numpy(P["val"].astype(np.float32)).to(dev))
+    Y = synth.clustered_embedding(1500, n_clusters=10, spread=10.0, sigma=1.0, seed=3)
+    got = t.kl(torch.from_numpy(Y).to(dev))
+    want = oracle.kl(Y.astype(np.float64), P["row_ptr"], P["col"], P["val"].astype(np.float32).astype(np.float64))
+    assert abs(got - want) <= 1e-5 * abs(want)
+    t.close()
+
+
+def test_stop_and_resume_is_bitwise_without_renumbering():
+    import torch
+    from paper_1807_11824_amd import Tsne
+    from helpers import random_symmetric_csr
+    dev = torch.device("cuda:0")
+    n = 10_007
+    rp, col, val = random_symmetric_csr(n, 20, seed=4)
+    P = [torch.from_numpy(a).to(dev) for a in (rp, col, val)]
+    Y0 = torch.from_numpy(synth.y0(n, seed=3)).to(dev)
+    kw = dict(exaggeration_iters=30, momentum_switch_iter=30)
+    a = Tsne(n, **kw); a.set_P(*P)
+    Ya = Y0.clone(); a.run(Ya, 100)
+    b = Tsne(n, **kw); b.set_P(*P)
+    Yb = Y0.clone(); b.run(Yb, 40)
+    u, g = b.get_state()
+    c = Tsne(n, **kw); c.set_P(*P); c.set_state(u, g)
+    c.run(Yb, 60, iter0=40)
+    assert torch.equal(Ya, Yb)
+    for t in (a, b, c):
+        assert t.status() == 0
+        t.close()
+
+
+def test_step_equals_oracle_update():
+    """One tsne_step from a known state against the oracle's gradient + update in double."""
+    import torch
+    from paper_1807_11824_amd import Tsne
+    from helpers import random_symmetric_csr, rel_l2
+    dev = torch.device("cuda:0")
+    n = 3000
+    rp, col, val = random_symmetric_csr(n, 15, seed=5)
+    Y = synth.clustered_embedding(n, n_clusters=12, spread=8.0, sigma=0.7, seed=7)
+    rng = np.random.default_rng(0)
+    u0 = (rng.standard_normal((n, 2)) * 0.05).astype(np.float32)
+    g0 = (0.5 + rng.random((n, 2))).astype(np.float32)
+    t = Tsne(n)
+    t.set_P(*[torch.from_numpy(a).to(dev) for a in (rp, col, val)])
+    t.set_state(torch.from_numpy(u0).to(dev), torch.from_numpy(g0).to(dev))
+    Yd = torch.from_numpy(Y).to(dev)
+    t.step(Yd, 300)                                   # past exaggeration: alpha = 1, momentum 0.8
+    u1, g1 = t.get_state()
+    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=0.5, leaf_cap=8, group=64, alpha=1.0)
+    Yo, uo, go = Y.astype(np.float64), u0.astype(np.float64), g0.astype(np.float64)
+    oracle.update(Yo, uo, go, o["grad"], momentum=0.8, lr=200.0)
+    # gains switch on the sign of the gradient: compare where the gradient is not within rounding of 0
+    safe = np.abs(o["grad"]) > 1e-6 * np.abs(o["grad"]).max()
+    assert np.allclose(g1.cpu().numpy()[safe], go[safe], rtol=1e-6)
+    assert rel_l2(u1.cpu().numpy()[safe], uo[safe]) <= 1e-4
+    assert rel_l2(Yd.cpu().numpy(), Yo) <= 1e-5
+    t.close()
+
+
+def test_call_order_errors():
+    import torch
+    from paper_1807_11824_amd import Tsne, TsneError
+    t = Tsne(100)
+    Y = torch.zeros((100, 2), device="cuda:0")
+    with pytest.raises(TsneError) as e:
+        t.step(Y, 0)
+    assert e.value.code == -4
+    with pytest.raises(TsneError):
+        t.export_tree()
+    with pytest.raises(TsneError):
+        t.timing_end()
+    t.close()
