@@ -20,6 +20,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 STANDIN_D = 64                 # see workload_inputs()
 STANDIN_MEAN_SCALE = 2.0
+# HBM bytes per launch of the attraction kernel from the committed counter runs, keyed by (workload, nnz)
+MEASURED_TRAFFIC = {("cfg5", 176122426): 1.566e9}
 
 
 def workload_inputs(name):
@@ -71,6 +73,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap", type=int, default=1)
     ap.add_argument("--leaf-cap", type=int, default=8)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for the profiler's byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported", file=sys.stderr)
@@ -90,6 +94,14 @@ def main():
     t_build = time.time() - t0
     del Xd
     nnz = P["nnz"]
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     Y0 = synth.y0(n)
     Yd = torch.from_numpy(Y0).to(dev)
@@ -135,8 +147,11 @@ def main():
         "end_to_end_s_1000_iters": t_build + ms_step,
         "step_algorithmic_GB": step_bytes / 1e9,
         "step_hbm_frac": step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"kernel": "attract_csr", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+        "roofline": {"kernel": "attract_csr_window", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     # measured with rocprofv3 FETCH_SIZE / WRITE_SIZE on this workload, scaled by a 1 GiB copy
+                     # (profiles/attract_csr_window_cfg5_hbm_traffic.md); bytes per launch
+                     "traffic": MEASURED_TRAFFIC.get((args.workload, nnz))},
     }
     out["end_to_end_s_1000_iters"] = t_build + ms_step  # ms/step * 1000 steps / 1000 ms
     if not args.no_cpu_baseline:

@@ -26,7 +26,7 @@ namespace {
 constexpr size_t ALIGN = 256;
 __host__ __device__ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
-constexpr int QB = 8192;        // query rows per pass
+constexpr int QB = 65536;       // query rows per pass
 constexpr int DBC = 2048;       // database rows per launch (bounds what one launch can append per row)
 constexpr int MAX_KP = 2048;    // k' limit
 constexpr int SORT_CAP = 4096;  // candidate buffer entries per row = LDS sort size
