@@ -120,7 +120,9 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
 {
     hipError_t e;
     const bool two = c->p.overlap && c->stream2;
-    const bool late = c->p.overlap == 2;             // attraction beside the walk instead of beside the tree build
+    // where the attractive kernel is forked off: 1 = right after the gather (beside the whole tree
+    // build), 3 = after the sort (beside cell construction and walk), 2 = after the tree (beside the walk)
+    const int fork_at = c->p.overlap;
     hipStream_t sa = two ? c->stream2 : c->stream;   // where the attractive kernel runs
     auto fork_attract = [&]() -> int {
         if ((e = hipEventRecord(c->ev_fork, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
@@ -134,10 +136,12 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
     int rc;
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     if ((e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
-    if (two && !late && (rc = fork_attract()) != TSNE_OK) return rc;
-    if ((e = launch_tree_build(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree build");
+    if (two && fork_at == 1 && (rc = fork_attract()) != TSNE_OK) return rc;
+    if ((e = launch_tree_sort(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree sort");
+    if (two && fork_at == 3 && (rc = fork_attract()) != TSNE_OK) return rc;
+    if ((e = launch_tree_cells(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree cells");
     if (ev) (void)hipEventRecord(ev[1], c->stream);
-    if (two && late && (rc = fork_attract()) != TSNE_OK) return rc;
+    if (two && fork_at != 1 && fork_at != 3 && (rc = fork_attract()) != TSNE_OK) return rc;
     if ((e = launch_walk(c, c->stream)) != hipSuccess) return fail_hip(c, e, "walk");
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     if (two) {

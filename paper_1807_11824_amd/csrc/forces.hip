@@ -70,7 +70,10 @@ __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ r
 #ifndef AW_ROWS_N
 #define AW_ROWS_N 128
 #endif
-constexpr int AW_ROWS = AW_ROWS_N, AW_HALO = AW_HALO_N, AW_LPR = 16, AW_U = 4;
+#ifndef AW_DUAL_N
+#define AW_DUAL_N 2
+#endif
+constexpr int AW_ROWS = AW_ROWS_N, AW_HALO = AW_HALO_N, AW_LPR = 16, AW_U = 4, AW_DUAL = AW_DUAL_N;
 
 __global__ __launch_bounds__(256) void attract_csr_window(const int32_t *__restrict__ row_ptr,
                                                           const int32_t *__restrict__ col, const float *__restrict__ val,
@@ -83,45 +86,69 @@ __global__ __launch_bounds__(256) void attract_csr_window(const int32_t *__restr
     for (int t = threadIdx.x; t < whi - wlo; t += 256) win[t] = Y[wlo + t];
     __syncthreads();
     const int sub = (int)(threadIdx.x % AW_LPR);
-    for (int rr = (int)threadIdx.x / AW_LPR; rr < AW_ROWS; rr += 256 / AW_LPR) {
-        const int row = r0 + rr;
-        float ax = 0.f, ay = 0.f;
-        if (row < n) {
-            const int s = row_ptr[row], e = row_ptr[row + 1];
-            const float2 yi = win[row - wlo];
-            for (int j0 = s + sub; j0 < e; j0 += AW_LPR * AW_U) {
-                int c[AW_U];
-                float v[AW_U];
-                float2 yj[AW_U];
+    constexpr int GROUPS = 256 / AW_LPR;
+    // every 16-lane group works on AW_DUAL rows at a time so that twice as many loads are in flight
+    for (int rr = (int)threadIdx.x / AW_LPR; rr < AW_ROWS; rr += GROUPS * AW_DUAL) {
+        int row[AW_DUAL], j0[AW_DUAL], e[AW_DUAL];
+        float2 yi[AW_DUAL];
+        float ax[AW_DUAL], ay[AW_DUAL];
+        bool more = false;
+#pragma unroll
+        for (int d = 0; d < AW_DUAL; ++d) {
+            row[d] = r0 + rr + d * GROUPS;
+            const bool live = rr + d * GROUPS < AW_ROWS && row[d] < n;
+            if (!live) row[d] = -1;
+            j0[d] = live ? row_ptr[row[d]] + sub : 0;
+            e[d] = live ? row_ptr[row[d] + 1] : 0;
+            yi[d] = live ? win[row[d] - wlo] : make_float2(0.f, 0.f);
+            ax[d] = ay[d] = 0.f;
+            more |= j0[d] < e[d];
+        }
+        while (__any(more)) {
+            int c[AW_DUAL][AW_U];
+            float v[AW_DUAL][AW_U];
+            float2 yj[AW_DUAL][AW_U];
+#pragma unroll
+            for (int d = 0; d < AW_DUAL; ++d)
 #pragma unroll
                 for (int q = 0; q < AW_U; ++q) {
-                    const int j = j0 + q * AW_LPR;
-                    const bool in = j < e;
-                    c[q] = in ? col[j] : row;     // padding: own point, weight 0
-                    v[q] = in ? val[j] : 0.f;
+                    const int j = j0[d] + q * AW_LPR;
+                    const bool in = j < e[d];
+                    c[d][q] = in ? col[j] : wlo;      // padding: any in-window point, weight 0
+                    v[d][q] = in ? val[j] : 0.f;
                 }
 #pragma unroll
-                for (int q = 0; q < AW_U; ++q) {
-                    const unsigned off = (unsigned)(c[q] - wlo);
-                    if (off < (unsigned)(whi - wlo)) yj[q] = win[off];
-                    else yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
-                }
+            for (int d = 0; d < AW_DUAL; ++d)
 #pragma unroll
                 for (int q = 0; q < AW_U; ++q) {
-                    const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
+                    const unsigned off = (unsigned)(c[d][q] - wlo);
+                    if (off < (unsigned)(whi - wlo)) yj[d][q] = win[off];
+                    else yj[d][q] = Y[min((uint32_t)c[d][q], (uint32_t)n - 1u)];
+                }
+            more = false;
+#pragma unroll
+            for (int d = 0; d < AW_DUAL; ++d) {
+#pragma unroll
+                for (int q = 0; q < AW_U; ++q) {
+                    const float dx = yi[d].x - yj[d][q].x, dy = yi[d].y - yj[d][q].y;
                     const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
-                    const float pw = v[q] * w;
-                    ax = fmaf(pw, dx, ax);
-                    ay = fmaf(pw, dy, ay);
+                    const float pw = v[d][q] * w;
+                    ax[d] = fmaf(pw, dx, ax[d]);
+                    ay[d] = fmaf(pw, dy, ay[d]);
                 }
+                j0[d] += AW_LPR * AW_U;
+                more |= j0[d] < e[d];
             }
         }
 #pragma unroll
-        for (int o = AW_LPR / 2; o > 0; o >>= 1) {
-            ax += __shfl_xor(ax, o, WAVE);
-            ay += __shfl_xor(ay, o, WAVE);
+        for (int d = 0; d < AW_DUAL; ++d) {
+#pragma unroll
+            for (int o = AW_LPR / 2; o > 0; o >>= 1) {
+                ax[d] += __shfl_xor(ax[d], o, WAVE);
+                ay[d] += __shfl_xor(ay[d], o, WAVE);
+            }
+            if (row[d] >= 0 && sub == 0) A[row[d]] = make_float2(ax[d], ay[d]);
         }
-        if (row < n && sub == 0) A[row] = make_float2(ax, ay);
     }
 }
 

@@ -749,15 +749,24 @@ hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_tree_build(tsne_ctx *c, hipStream_t s)
+// Step 1 second half, step 2a and step 4: root square, keys, spatial sort.
+hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
 {
-    const int n = c->p.n, B = c->p.morton_bits, C = c->p.leaf_cap;
+    const int n = c->p.n, B = c->p.morton_bits;
     const float2 *Y = c->Yi;
     const int nb = (n + 255) / 256, bb = bbox_blocks(n);
     hipLaunchKernelGGL(bbox_final, dim3(1), dim3(256), 0, s, c->bbox_part, bb, B, c->root, c->status);
     hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],
                        c->idx[0]);
-    (void)launch_sort(c, 2 * B, s);
+    return launch_sort(c, 2 * B, s);
+}
+
+// Steps 2b, 2c and 3: cells, counts, centres of mass from the sorted keys.
+hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s)
+{
+    const int n = c->p.n, B = c->p.morton_bits, C = c->p.leaf_cap;
+    const float2 *Y = c->Yi;
+    const int nb = (n + 255) / 256;
     const int cur = c->sorted_buf;
     int nl = (n + LEVEL_TILE - 1) / LEVEL_TILE;
     hipLaunchKernelGGL(gather_levels, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B, C,

@@ -84,7 +84,8 @@ struct tsne_ctx {
 
 // ---- launchers (each enqueues on the given stream and returns the launch error) ----
 hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
-hipError_t launch_tree_build(tsne_ctx *c, hipStream_t s);
+hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s);
+hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);
 hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s);
