@@ -28,9 +28,11 @@ __host__ __device__ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN 
 
 constexpr int QB = 65536;       // query rows per pass
 constexpr int DBC = 2048;       // database rows per launch (bounds what one launch can append per row)
-constexpr int MAX_KP = 2048;    // k' limit
+constexpr int MAX_KP = 1920;    // k' limit: k' + COMPACT_SLACK + DBC must fit the LDS sort
 constexpr int SORT_CAP = 4096;  // candidate buffer entries per row = LDS sort size
 constexpr int TM = 128, TN = 128, BK = 32, LDS_STRIDE = BK + 4;
+constexpr int COMPACT_SLACK = 128; // new candidates per row that trigger a re-sort of its buffer
+constexpr int KFLUSH = 64;      // columns summed on the matrix cores before a flush into the running sum
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -102,7 +104,7 @@ __device__ __forceinline__ void store_slab(float *__restrict__ S, const float4 v
 }
 
 // One 128 x 128 tile of query rows [q0 + 128 bx, ..) against database rows [j0 + 128 by, ..).
-__global__ __launch_bounds__(256) void knn_tile_mfma(const float *__restrict__ X, int n, int d, int q0, int qend,
+__global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict__ X, int n, int d, int q0, int qend,
                                                      int j0, int jend, const float *__restrict__ norms,
                                                      const float *__restrict__ tau, int *__restrict__ cnt,
                                                      uint64_t *__restrict__ cand, int cap)
@@ -113,13 +115,17 @@ __global__ __launch_bounds__(256) void knn_tile_mfma(const float *__restrict__ X
     const int wm = w >> 1, wn = w & 1;
     const int qa = q0 + blockIdx.x * TM, ja = j0 + blockIdx.y * TN;
     const bool vec = (d & 3) == 0;
-    floatx16 acc[2][2];
+    // Two-level accumulation: the matrix cores sum KFLUSH columns into `part`, which is then added
+    // to `acc` and cleared.  The rounding error of a dot product of length d drops from order d to
+    // order KFLUSH + d / KFLUSH units in the last place, which is what lets a small candidate
+    // margin certify rows at D in the thousands.
+    floatx16 acc[2][2], part[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+            for (int i = 0; i < 16; ++i) { acc[a][b][i] = 0.f; part[a][b][i] = 0.f; }
     float4 ra[4], rb[4];
     load_slab(X, d, qa, qend, 0, vec, ra);
     load_slab(X, d, ja, jend, 0, vec, rb);
@@ -134,27 +140,39 @@ __global__ __launch_bounds__(256) void knn_tile_mfma(const float *__restrict__ X
             load_slab(X, d, ja, jend, k0 + BK, vec, rb);
         }
         // each lane owns 16 of the slab's 32 columns (h selects the half); the same column
-        // assignment is used for both operands, so the products pair up correctly
-        float fa[2][16], fb[2][16];
+        // assignment is used for both operands, so the products pair up correctly.  The 16
+        // columns are taken in two rounds of 8 to keep the fragment registers at 32.
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const float *pa = As + (wm * 64 + m * 32 + r32) * LDS_STRIDE + h * 16;
-            const float *pb = Bs + (wn * 64 + m * 32 + r32) * LDS_STRIDE + h * 16;
+        for (int half = 0; half < 2; ++half) {
+            float fa[2][8], fb[2][8];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 va = *reinterpret_cast<const float4 *>(pa + 4 * q);
-                float4 vb = *reinterpret_cast<const float4 *>(pb + 4 * q);
-                fa[m][4 * q] = va.x; fa[m][4 * q + 1] = va.y; fa[m][4 * q + 2] = va.z; fa[m][4 * q + 3] = va.w;
-                fb[m][4 * q] = vb.x; fb[m][4 * q + 1] = vb.y; fb[m][4 * q + 2] = vb.z; fb[m][4 * q + 3] = vb.w;
+            for (int m = 0; m < 2; ++m) {
+                const float *pa = As + (wm * 64 + m * 32 + r32) * LDS_STRIDE + h * 16 + half * 8;
+                const float *pb = Bs + (wn * 64 + m * 32 + r32) * LDS_STRIDE + h * 16 + half * 8;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    float4 va = *reinterpret_cast<const float4 *>(pa + 4 * q);
+                    float4 vb = *reinterpret_cast<const float4 *>(pb + 4 * q);
+                    fa[m][4 * q] = va.x; fa[m][4 * q + 1] = va.y; fa[m][4 * q + 2] = va.z; fa[m][4 * q + 3] = va.w;
+                    fb[m][4 * q] = vb.x; fb[m][4 * q + 1] = vb.y; fb[m][4 * q + 2] = vb.z; fb[m][4 * q + 3] = vb.w;
+                }
             }
-        }
 #pragma unroll
-        for (int s = 0; s < 16; ++s)
+            for (int s = 0; s < 8; ++s)
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        part[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a][s], fb[b][s], part[a][b], 0, 0, 0);
+        }
+        if (((k0 / BK) % (KFLUSH / BK)) == (KFLUSH / BK) - 1 || k0 + BK >= d) {
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a][s], fb[b][s], acc[a][b], 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) { acc[a][b][i] += part[a][b][i]; part[a][b][i] = 0.f; }
+        }
     }
     // epilogue: lane holds column (lane % 32) and rows 8 (i / 4) + 4 (lane / 32) + i % 4 of each block
 #pragma unroll
@@ -198,7 +216,7 @@ __device__ __forceinline__ void bitonic_sort(uint64_t *s, int size)
 }
 
 __global__ __launch_bounds__(256) void knn_compact(float *__restrict__ tau, int *__restrict__ cnt,
-                                                   uint64_t *__restrict__ cand, int cap, int kp, int rows)
+                                                   uint64_t *__restrict__ cand, int cap, int kp, int rows, int force)
 {
     __shared__ uint64_t s[SORT_CAP];
     const int row = blockIdx.x;
@@ -206,6 +224,9 @@ __global__ __launch_bounds__(256) void knn_compact(float *__restrict__ tau, int 
     int c = cnt[row];
     if (c > cap) c = cap;
     if (c < kp) return;                 // not yet k' candidates: the cut-off stays +inf
+    // sort only when enough new candidates have piled up to matter, when the next slab could
+    // overflow the buffer, or at the end (force); in between the cut-off is merely a bit stale
+    if (!force && tau[row] < INFINITY && c < kp + COMPACT_SLACK && c + DBC <= cap) return;
     int size = 1;
     while (size < c) size <<= 1;
     uint64_t *buf = cand + (size_t)row * cap;
@@ -275,7 +296,11 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
         // at most E, so they are farther than the exact k-th candidate if tau - E > D_k
         bool ok = c >= k;
         if (ok && c < n - 1) {
-            const double E = (double)(d + 16) * 5.9604644775390625e-08 * ((double)norms[i] + (double)norm_max) * 2.0;
+            // error of the float distance: each product and each addition rounds once (2 KFLUSH per
+            // partial sum), d / KFLUSH additions of partial sums, a few for norms and the final
+            // combination; terms are bounded by (|q|^2 + |x|^2) / 2 in sum; the whole doubled for safety
+            const double roundings = 2.0 * KFLUSH + (double)((d + KFLUSH - 1) / KFLUSH) + 16.0;
+            const double E = roundings * 5.9604644775390625e-08 * ((double)norms[i] + (double)norm_max) * 2.0;
             const double Dk = dd[order[k - 1]];
             ok = (double)tau[row] - E > Dk;
         }
@@ -563,7 +588,7 @@ struct Layout {
 
 int margin_kp(int n, int k)
 {
-    int kp = k + 32;
+    int kp = k + (k / 2 > 32 ? k / 2 : 32);
     if (kp > n - 1) kp = n - 1;
     return kp;
 }
@@ -574,7 +599,7 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
     size_t off = 0;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up(bytes); return (void *)p; };
     const int kp = margin_kp(n, k);
-    const int cap = kp + DBC;
+    const int cap = kp + COMPACT_SLACK + DBC;   // <= SORT_CAP because kp <= MAX_KP
     const size_t qb = (size_t)(n < QB ? n : QB);
     void *q;
     q = take(4 * (size_t)n); if (L) L->norms = (float *)q;
@@ -599,7 +624,7 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
 int check_args(int32_t n, int32_t d, int32_t k)
 {
     if (n < 2 || d < 1 || k < 1 || k >= n) return TSNE_EINVAL;
-    if (k + 32 > MAX_KP || d > 4096) return TSNE_EINVAL;
+    if (k + (k / 2 > 32 ? k / 2 : 32) > MAX_KP || d > 4096) return TSNE_EINVAL;
     if ((int64_t)2 * n * k > 0x7FFFFFFFll) return TSNE_EINVAL;
     return TSNE_OK;
 }
@@ -656,7 +681,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
             dim3 grid((rows + TM - 1) / TM, (jend - j0 + TN - 1) / TN);
             hipLaunchKernelGGL(knn_tile_mfma, grid, dim3(256), 0, s, d_X, n, d, q0, qend, j0, jend, L.norms, L.tau,
                                L.cnt, L.cand, cap);
-            hipLaunchKernelGGL(knn_compact, dim3(rows), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows);
+            hipLaunchKernelGGL(knn_compact, dim3(rows), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows,
+                               jend >= n ? 1 : 0);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, q0, rows, k, kp, L.norms,
                            norm_max, L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
