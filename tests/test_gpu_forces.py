@@ -141,3 +141,55 @@ def test_renumbering_changes_nothing_but_the_layout():
     b.step(Yb, 40)
     assert rel_l2(Ya.cpu().numpy(), Yb.cpu().numpy()) <= 1e-5
     a.close(); b.close()
+
+
+@pytest.mark.parametrize("leaf_cap,bits,theta", [(40, 16, 0.5), (3, 6, 0.5), (8, 16, 0.7), (16, 16, 0.3), (200, 16, 0.5)])
+def test_other_tree_parameters(leaf_cap, bits, theta):
+    """Large leaves (lane-serial leaf path), a coarse grid with crowded deepest cells, the largest theta."""
+    import torch
+    from paper_1807_11824_amd import Tsne
+    n = 6001
+    Y = synth.clustered_embedding(n, n_clusters=15, spread=6.0, sigma=0.4, seed=9)
+    rp, col, val = random_symmetric_csr(n, 12, seed=6)
+    dev = torch.device("cuda:0")
+    t = Tsne(n, theta=theta, leaf_cap=leaf_cap, morton_bits=bits)
+    t.set_P(*[torch.from_numpy(a).to(dev) for a in (rp, col, val)])
+    A, R, Z = t.gradient(torch.from_numpy(Y).to(dev))
+    assert t.status() == 0
+    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=theta, leaf_cap=leaf_cap, group=64, bits=bits)
+    assert rel_l2(R.cpu().numpy(), o["R"]) <= TOL
+    assert abs(float(Z[0]) - o["Z"]) <= 1e-5 * o["Z"]
+    t.close()
+
+
+def test_renumbered_context_small_and_empty_rows():
+    """Renumbering with rows of P that are empty, n below one window, and a second tsne_set_P."""
+    import torch
+    from paper_1807_11824_amd import Tsne
+    dev = torch.device("cuda:0")
+    n = 777
+    rp, col, val = random_symmetric_csr(n, 6, seed=8)
+    # empty a few rows (and the matching columns) to keep the pattern symmetric
+    import scipy.sparse as sp
+    M = sp.csr_matrix((val, col, rp), shape=(n, n)).tolil()
+    for i in (0, 5, 300, n - 1):
+        M[i, :] = 0
+        M[:, i] = 0
+    M = M.tocsr(); M.eliminate_zeros(); M.sort_indices()
+    rp2, col2, val2 = M.indptr.astype(np.int32), M.indices.astype(np.int32), M.data.astype(np.float32)
+    Y = synth.y0(n, seed=5) * 100
+    t = Tsne(n, max_nnz=len(col) + 10, graph_order_iters=5, reorder_every=3)
+    ref = Tsne(n)
+    for (a, b, c) in ((rp2, col2, val2), (rp, col, val)):
+        P = [torch.from_numpy(x).to(dev) for x in (a, b, c)]
+        t.set_P(*P)
+        ref.set_P(*P)
+        Yd = torch.from_numpy(Y).to(dev)
+        Aa, Ra, Za = t.gradient(Yd)
+        Ab, Rb, Zb = ref.gradient(Yd)
+        assert torch.equal(Aa, Ab)
+        assert rel_l2(Ra.cpu().numpy(), Rb.cpu().numpy()) <= 1e-5
+        Y1 = Yd.clone()
+        t.run(Y1, 7)
+        assert t.status() == 0 and torch.isfinite(Y1).all()
+    t.close(); ref.close()
