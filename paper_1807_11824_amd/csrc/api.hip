@@ -59,6 +59,8 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     q = take(4 * (n + 1));                           if (c) c->cellseq = (uint32_t *)q;
     q = take(16 * (n + 1));                          if (c) c->ps = (double2 *)q;
     q = take(sizeof(Cell) * (size_t)cap);            if (c) { c->cells = (Cell *)q; c->cap_cells = cap; }
+    q = take(4 * (size_t)cap);                       if (c) c->cell_p = (uint32_t *)q;
+    q = take((size_t)cap);                           if (c) c->cell_t = (uint8_t *)q;
     const int32_t big_cap = (int32_t)(n / 8 + 1024);
     q = take(sizeof(uint32_t));                      if (c) c->big_count = (uint32_t *)q;
     q = take(sizeof(uint2) * (size_t)big_cap);       if (c) { c->big_list = (uint2 *)q; c->big_cap = big_cap; }

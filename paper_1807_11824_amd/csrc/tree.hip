@@ -368,28 +368,47 @@ __device__ __forceinline__ int common_digits(uint32_t a, uint32_t b, int B)
     return x ? B - 1 - ((31 - __clz((int)x)) >> 1) : B;
 }
 
+// CT > 0: leaf_cap known at compile time (all indices static, no bisection); CT = 0: any
+// leaf_cap <= LEVELS_WINDOW_MAXC at run time.
+template <int CT>
 __device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n, uint32_t p, int B, int C,
                                               int *tmin_out, int *tend_out)
 {
     const uint32_t key = keys[p];
     const int tmin = p == 0 ? 0 : (key == keys[p - 1] ? B + 1 : common_digits(key, keys[p - 1], B) + 1);
-    int L[LEVELS_WINDOW_MAXC], R[LEVELS_WINDOW_MAXC];
+    int smax;
+    if (CT > 0) {
+        // C-th largest of the two non-increasing lists: max over k of min(L[k], R[CT - k]), with
+        // L[0] = R[0] = B standing for "no neighbour needed on that side"
+        int L[CT + 1], R[CT + 1];
+        L[0] = R[0] = B;
 #pragma unroll
-    for (int j = 1; j <= LEVELS_WINDOW_MAXC; ++j) {
-        L[j - 1] = (j <= C && p >= (uint32_t)j) ? common_digits(key, keys[p - j], B) : -1;
-        R[j - 1] = (j <= C && p + j < n) ? common_digits(key, keys[p + j], B) : -1;
-    }
-    // deepest s in [0, B] with at least C of the 2C neighbours sharing s digits (-1 if none):
-    // the count is non-increasing in s, so bisect
-    int lo = -1, hi = B + 1;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        int cnt = 0;
+        for (int j = 1; j <= CT; ++j) {
+            L[j] = p >= (uint32_t)j ? common_digits(key, keys[p - j], B) : -1;
+            R[j] = p + j < n ? common_digits(key, keys[p + j], B) : -1;
+        }
+        smax = -1;
 #pragma unroll
-        for (int j = 0; j < LEVELS_WINDOW_MAXC; ++j) cnt += (L[j] >= mid) + (R[j] >= mid);
-        if (cnt >= C) lo = mid; else hi = mid;
+        for (int k = 0; k <= CT; ++k) smax = max(smax, min(L[k], R[CT - k]));
+    } else {
+        int L[LEVELS_WINDOW_MAXC], R[LEVELS_WINDOW_MAXC];
+#pragma unroll
+        for (int j = 1; j <= LEVELS_WINDOW_MAXC; ++j) {
+            L[j - 1] = (j <= C && p >= (uint32_t)j) ? common_digits(key, keys[p - j], B) : -1;
+            R[j - 1] = (j <= C && p + j < n) ? common_digits(key, keys[p + j], B) : -1;
+        }
+        // deepest s in [0, B] with at least C of the 2C neighbours sharing s digits (-1 if none):
+        // the count is non-increasing in s, so bisect
+        int lo = -1, hi = B + 1;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            int cnt = 0;
+#pragma unroll
+            for (int j = 0; j < LEVELS_WINDOW_MAXC; ++j) cnt += (L[j] >= mid) + (R[j] >= mid);
+            if (cnt >= C) lo = mid; else hi = mid;
+        }
+        smax = lo;
     }
-    const int smax = lo;
     // cell (t, p) exists iff t == 0 or the depth t-1 cell around p holds more than C points
     int tend = min(B, smax + 1) + 1;
     if (tend < tmin) tend = tmin;
@@ -398,6 +417,7 @@ __device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n,
 }
 
 // Also moves the points into spatial order (step 4) and reduces each tile's (cells, sum x, sum y).
+template <int CT>
 __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__restrict__ Y,
                                                                const uint32_t *__restrict__ keys,
                                                                const uint32_t *__restrict__ perm, int n, int B, int C,
@@ -424,7 +444,7 @@ __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__r
             Ys[p] = y[k];
             ax += (double)y[k].x; ay += (double)y[k].y;
             int tmin, tend;
-            if (C <= LEVELS_WINDOW_MAXC) levels_window(kw, (uint32_t)n, (uint32_t)p, B, C, &tmin, &tend);
+            if (CT > 0 || C <= LEVELS_WINDOW_MAXC) levels_window<CT>(kw, (uint32_t)n, (uint32_t)p, B, C, &tmin, &tend);
             else levels_at(kw, (uint32_t)n, (uint32_t)p, B, (uint32_t)C, &tmin, &tend);
             lev[p] = (uint16_t)(tmin | (tend << 8));
             ac += (uint32_t)(tend - tmin);
@@ -493,14 +513,16 @@ __global__ __launch_bounds__(1024) void scan_partials(ScanPart *__restrict__ par
 __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restrict__ Ys,
                                                            const uint16_t *__restrict__ lev, int n,
                                                            const ScanPart *__restrict__ part,
-                                                           uint32_t *__restrict__ cellseq, double2 *__restrict__ ps)
+                                                           uint32_t *__restrict__ cellseq, double2 *__restrict__ ps,
+                                                           uint32_t *__restrict__ cell_p, uint8_t *__restrict__ cell_t,
+                                                           uint32_t cap_cells)
 {
     __shared__ double wx[4], wy[4];
     __shared__ uint32_t wc[4];
     const int tid = threadIdx.x, w = tid >> 6;
     int p0 = blockIdx.x * LEVEL_TILE + tid * LEVEL_ITEMS;
     float2 y[LEVEL_ITEMS];
-    uint32_t c[LEVEL_ITEMS];
+    uint32_t c[LEVEL_ITEMS], t0[LEVEL_ITEMS];
     double ax = 0.0, ay = 0.0;
     uint32_t ac = 0;
 #pragma unroll
@@ -510,7 +532,8 @@ __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restr
             y[k] = Ys[p];
             uint32_t l = lev[p];
             c[k] = (l >> 8) - (l & 0xFFu);
-        } else { y[k] = make_float2(0.f, 0.f); c[k] = 0; }
+            t0[k] = l & 0xFFu;
+        } else { y[k] = make_float2(0.f, 0.f); c[k] = 0; t0[k] = 0; }
         ax += (double)y[k].x; ay += (double)y[k].y; ac += c[k];
     }
     double ix = ax, iy = ay;
@@ -534,6 +557,8 @@ __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restr
         if (p < n) {
             cellseq[p] = pc;
             ps[p] = make_double2(px, py);
+            for (uint32_t q = 0; q < c[k]; ++q)
+                if (pc + q < cap_cells) { cell_p[pc + q] = (uint32_t)p; cell_t[pc + q] = (uint8_t)(t0[k] + q); }
             px += (double)y[k].x; py += (double)y[k].y; pc += c[k];
             if (p == n - 1) { cellseq[n] = pc; ps[n] = make_double2(px, py); }
         }
@@ -551,59 +576,67 @@ __device__ __forceinline__ uint32_t digit_lower_bound(const KeyWindow &keys, uin
     return s;
 }
 
-// A cell whose run of positions ends inside the workgroup's key window is finished on the spot
-// (all its searches stay in LDS).  The few large cells near the top of the tree would each be a
-// chain of dozens of dependent memory reads in a single lane; they are put on a list instead
-// and finished by write_big_cells, four lanes per cell.
-__global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ keys, const uint16_t *__restrict__ lev,
+// One lane per cell (cells are numbered in pre-order, so the cells of a workgroup start at
+// non-decreasing positions and the keys they search sit in one short stretch, staged in LDS).
+// A cell whose run of positions ends inside that stretch is finished on the spot.  The few large
+// cells near the top of the tree would each be a chain of dozens of dependent memory reads in a
+// single lane; they are put on a list instead and finished by write_big_cells, four lanes per cell.
+constexpr int CELL_WINDOW = 4096;
+
+__global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ keys,
                                                    const uint32_t *__restrict__ cellseq,
-                                                   const double2 *__restrict__ ps, int n, int B, int C,
+                                                   const double2 *__restrict__ ps,
+                                                   const uint32_t *__restrict__ cell_p, const uint8_t *__restrict__ cell_t,
+                                                   const uint32_t *__restrict__ ncells, int n, int B, int C,
                                                    Cell *__restrict__ cells, uint32_t cap_cells,
                                                    uint32_t *__restrict__ big_count, uint2 *__restrict__ big_list,
                                                    uint32_t big_cap)
 {
-    __shared__ uint32_t kwin[256 + 2 * KEY_HALO];
-    const KeyWindow kw = key_window_fill(keys, (uint32_t)n, blockIdx.x * 256u, 256u, kwin);
-    __syncthreads();
-    uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= (uint32_t)n) return;
-    uint32_t l = lev[p];
-    int tmin = (int)(l & 0xFFu), tend = (int)(l >> 8);
-    if (tend <= tmin) return;
-    uint32_t key = kw[p];
-    uint32_t id0 = cellseq[p];
-    double2 s0 = ps[p];
-    const uint32_t wend = kw.lo + kw.len;                  // one past the last position in the window
-    const uint32_t wlast_key = kw.lds[kw.len - 1];
-    for (int t = tmin; t < tend; ++t) {
-        uint32_t id = id0 + (uint32_t)(t - tmin);
-        if (id >= cap_cells) return;
-        // does the cell end inside the window?
-        const bool inside = wend >= (uint32_t)n || (t > 0 && (wlast_key >> (2 * (B - t))) != (key >> (2 * (B - t))));
-        if (!inside) {
+    __shared__ uint32_t kwin[CELL_WINDOW];
+    const uint32_t m = min(*ncells, cap_cells);
+    for (uint32_t base = blockIdx.x * 256u; base < m; base += gridDim.x * 256u) {
+        const uint32_t id = base + threadIdx.x;
+        const bool live = id < m;
+        const uint32_t p_first = cell_p[base], p_last = cell_p[min(base + 255u, m - 1u)];
+        KeyWindow kw;
+        kw.keys = keys;
+        kw.lds = kwin;
+        kw.lo = p_first;
+        kw.len = min(min((uint32_t)n, p_last + 1u + (uint32_t)KEY_HALO) - p_first, (uint32_t)CELL_WINDOW);
+        __syncthreads();                    // previous round's readers are done with the window
+        for (uint32_t q = threadIdx.x; q < kw.len; q += 256u) kwin[q] = keys[p_first + q];
+        __syncthreads();
+        if (!live) continue;
+        const uint32_t p = cell_p[id];
+        const int t = (int)cell_t[id];
+        const uint32_t key = kw[p];
+        const uint32_t wend = kw.lo + kw.len;                  // one past the last position in the window
+        if (p < wend && wend < (uint32_t)n &&
+            (t == 0 || (kwin[kw.len - 1] >> (2 * (B - t))) == (key >> (2 * (B - t))))) {
+            // the cell runs past the window: a large cell
             const uint32_t slot = atomicAdd(big_count, 1u);
             if (slot < big_cap) { big_list[slot] = make_uint2(p, (uint32_t)t); continue; }
             // list full (cannot happen for capacity n/8 + 1024 unless most cells are huge): finish it here
         }
-        uint32_t e = (t == 0) ? (uint32_t)n : run_end(kw, (uint32_t)n, p, 2 * (B - t), key >> (2 * (B - t)));
-        uint32_t cnt = e - p;
-        double2 s1 = ps[e];
+        const uint32_t e = (t == 0) ? (uint32_t)n : run_end(kw, (uint32_t)n, p, 2 * (B - t), key >> (2 * (B - t)));
+        const uint32_t cnt = e - p;
+        const double2 s0 = ps[p], s1 = ps[e];
         Cell c;
         c.cx = (float)((s1.x - s0.x) / (double)cnt);
         c.cy = (float)((s1.y - s0.y) / (double)cnt);
         c.cnt = cnt;
-        bool leaf = cnt <= (uint32_t)C || t == B;
+        const bool leaf = cnt <= (uint32_t)C || t == B;
         c.meta = (uint32_t)t | (leaf ? 0x100u : 0u);
         c.lo = p;
         c.c1 = c.c2 = c.c3 = TSNE_NONE;
         if (!leaf) {
-            int sh = 2 * (B - t - 1);
+            const int sh = 2 * (B - t - 1);
             uint32_t kids[3];
             int nk = 0;
             uint32_t s = p;
-            uint32_t qfirst = (key >> sh) & 3u;
+            const uint32_t qfirst = (key >> sh) & 3u;
             for (uint32_t q = qfirst + 1; q < 4; ++q) {
-                uint32_t b = digit_lower_bound(kw, s, e, sh, q);
+                const uint32_t b = digit_lower_bound(kw, s, e, sh, q);
                 if (b < e && ((kw[b] >> sh) & 3u) == q) kids[nk++] = cellseq[b];
                 s = b;
             }
@@ -769,13 +802,20 @@ hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s)
     const int nb = (n + 255) / 256;
     const int cur = c->sorted_buf;
     int nl = (n + LEVEL_TILE - 1) / LEVEL_TILE;
-    hipLaunchKernelGGL(gather_levels, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B, C,
-                       c->Ys, c->lev, c->part);
+    if (C == 8)
+        hipLaunchKernelGGL(gather_levels<8>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B,
+                           C, c->Ys, c->lev, c->part);
+    else
+        hipLaunchKernelGGL(gather_levels<0>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B,
+                           C, c->Ys, c->lev, c->part);
     hipLaunchKernelGGL(scan_partials, dim3(1), dim3(1024), 0, s, c->part, nl, c->ncells, (uint32_t)c->cap_cells,
                        c->status, c->big_count);
-    hipLaunchKernelGGL(downsweep, dim3(nl), dim3(LEVEL_THREADS), 0, s, c->Ys, c->lev, n, c->part, c->cellseq, c->ps);
-    hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, c->keys[cur], c->lev, c->cellseq, c->ps, n, B, C,
-                       c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list, (uint32_t)c->big_cap);
+    hipLaunchKernelGGL(downsweep, dim3(nl), dim3(LEVEL_THREADS), 0, s, c->Ys, c->lev, n, c->part, c->cellseq, c->ps,
+                       c->cell_p, c->cell_t, (uint32_t)c->cap_cells);
+    // grid sized for n cells (a typical tree has about n / 3); the kernel strides if there are more
+    hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, c->keys[cur], c->cellseq, c->ps, c->cell_p, c->cell_t,
+                       c->ncells, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
+                       (uint32_t)c->big_cap);
     hipLaunchKernelGGL(write_big_cells, dim3((c->big_cap * 4 + 255) / 256), dim3(256), 0, s, c->keys[cur], c->lev,
                        c->cellseq, c->ps, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
                        (uint32_t)c->big_cap);

@@ -69,6 +69,8 @@ struct tsne_ctx {
     double2 *ps;
     Cell *cells;
     int32_t cap_cells;
+    uint32_t *cell_p;      // position and depth of every cell, by cell number
+    uint8_t *cell_t;
     uint32_t *big_count;   // cells too large for the in-LDS searches, finished by a second kernel
     uint2 *big_list;
     int32_t big_cap;
