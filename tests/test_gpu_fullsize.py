@@ -1,0 +1,81 @@
+"""The benchmark's own configuration at full size (N = 1,281,167): sampled kNN rows, invariants of P,
+and the forces of the context bench.py times, against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def full():
+    import torch
+    import bench
+    from paper_1807_11824_amd import build_P
+    X, cfg = bench.workload_inputs("cfg5")
+    dev = torch.device("cuda:0")
+    P = build_P(torch.from_numpy(X).to(dev), cfg["perplexity"], cfg["k"], want_knn=True)
+    return dict(X=X, cfg=cfg, P=P)
+
+
+def test_knn_rows_and_P_invariants(full):
+    X, cfg, P = full["X"], full["cfg"], full["P"]
+    n, k = cfg["n"], cfg["k"]
+    print(f"n={n} nnz={P['nnz']} unconverged={P['unconverged']}", flush=True)
+    rows = np.sort(np.random.default_rng(0).choice(n, 48, replace=False).astype(np.int32))
+    idx, d2 = oracle.knn(X, k, rows=rows)
+    assert np.array_equal(P["knn_idx"][rows.tolist()].cpu().numpy(), idx)
+    assert np.allclose(P["knn_d2"][rows.tolist()].cpu().numpy(), d2, rtol=1e-6)
+    cond, _, bad = oracle.cond_p(d2, cfg["perplexity"])
+    assert bad == 0 and P["unconverged"] == 0
+    rp = P["row_ptr"].cpu().numpy(); col = P["col"].cpu().numpy(); val = P["val"].cpu().numpy()
+    assert n * k <= P["nnz"] <= 2 * n * k and rp[-1] == P["nnz"]
+    assert abs(val.astype(np.float64).sum() - 1.0) < 1e-4
+    assert np.all(np.diff(rp) >= k)
+    # sampled rows: columns ascending, value = (p_j|i + p_i|j) / 2N for the oracle's conditionals, symmetric partner
+    for r, i in enumerate(rows):
+        c = col[rp[i]:rp[i + 1]]; v = val[rp[i]:rp[i + 1]]
+        assert np.all(np.diff(c) > 0)
+        for a, j in enumerate(idx[r][:10]):
+            pos = np.searchsorted(c, j)
+            assert c[pos] == j
+            cj = col[rp[j]:rp[j + 1]]
+            back = np.searchsorted(cj, i)
+            assert cj[back] == i and val[rp[j] + back] == v[pos]        # bitwise symmetric
+            assert v[pos] >= cond[r, a] / (2.0 * n) * (1 - 1e-6)          # at least this row's share
+
+
+def test_forces_in_bench_configuration(full):
+    """Same context parameters as bench.py (renumbering on, second stream), a few steps in, all N points."""
+    import torch
+    from paper_1807_11824_amd import Tsne, synth
+    cfg, P = full["cfg"], full["P"]
+    n = cfg["n"]
+    dev = torch.device("cuda:0")
+    ts = Tsne(n, overlap=1, leaf_cap=8, max_nnz=P["nnz"])
+    ts.set_P(P["row_ptr"], P["col"], P["val"])
+    Y = torch.from_numpy(synth.y0(n)).to(dev)
+    ts.run(Y, 30)
+    A, R, Z = ts.gradient(Y)
+    assert ts.status() == 0
+    Yh = Y.cpu().numpy()
+    o = oracle.grad_bh(Yh, P["row_ptr"].cpu().numpy(), P["col"].cpu().numpy(),
+                       P["val"].cpu().numpy().astype(np.float64), theta=0.5, leaf_cap=8, group=64, alpha=12.0)
+    g = 4.0 * (12.0 * A.cpu().numpy().astype(np.float64) - R.cpu().numpy().astype(np.float64) / float(Z[0]))
+    errs = dict(A=rel_l2(A.cpu().numpy(), o["A"]), R=rel_l2(R.cpu().numpy(), o["R"]),
+                Z=abs(float(Z[0]) - o["Z"]) / o["Z"], grad=rel_l2(g, o["grad"]))
+    print("full-size parity", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert errs["grad"] <= 1e-4 and errs["A"] <= 1e-4 and errs["R"] <= 1e-4 and errs["Z"] <= 1e-5
+    t = ts.export_tree()
+    want = oracle.tree(Yh, bits=16, leaf_cap=8)
+    assert t["m"] == want["m"]
+    assert np.array_equal(t["keys"].cpu().numpy().view(np.uint32), want["keys"])
+    assert np.array_equal(t["depth"].cpu().numpy(), want["depth"])
+    assert np.array_equal(t["lo"].cpu().numpy(), want["lo"]) and np.array_equal(t["hi"].cpu().numpy(), want["hi"])
+    # order of equal keys is the one thing renumbering may change: compare the key sequence, check a permutation
+    perm = t["perm"].cpu().numpy()
+    assert np.array_equal(want["keys"][perm], want["sorted_keys"])
+    assert np.array_equal(np.sort(perm), np.arange(n))
+    ts.close()
