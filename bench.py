@@ -21,7 +21,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 STANDIN_D = 64                 # see workload_inputs()
 STANDIN_MEAN_SCALE = 2.0
 # HBM bytes per launch of the attraction kernel from the committed counter runs, keyed by (workload, nnz)
-MEASURED_TRAFFIC = {("cfg5", 176122426): 1.566e9}
+MEASURED_TRAFFIC = {}
 
 
 def workload_inputs(name):
@@ -71,7 +71,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--overlap", type=int, default=1)
+    ap.add_argument("--overlap", type=int, default=2)
     ap.add_argument("--leaf-cap", type=int, default=8)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for the profiler's byte counters)")
@@ -147,7 +147,7 @@ def main():
         "end_to_end_s_1000_iters": t_build + ms_step,
         "step_algorithmic_GB": step_bytes / 1e9,
         "step_hbm_frac": step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"kernel": "attract_csr_window", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"kernel": "attract_near (+ attract_far)", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      # measured with rocprofv3 FETCH_SIZE / WRITE_SIZE on this workload, scaled by a 1 GiB copy
                      # (profiles/attract_csr_window_cfg5_hbm_traffic.md); bytes per launch

@@ -63,7 +63,10 @@ typedef struct {
     float gain_min;               /* 0.01 */
     int32_t morton_bits;          /* grid bits per axis = maximum tree depth, 1..16 (16) */
     int32_t leaf_cap;             /* a cell with at most this many points is a leaf, >= 1 (8) */
-    int32_t overlap;              /* 1: attractive forces run on a second stream beside the tree work */
+    int32_t overlap;              /* the attractive forces run on a second stream: 2 = beside the tree walk
+                                     (arithmetic-bound walk and memory-bound attraction share the compute
+                                     units), 1 = from the start of the tree build, 3 = from the end of the sort;
+                                     0 = everything on one stream.  (2) */
     int32_t graph_order_iters;    /* > 0 (and max_nnz > 0): at tsne_set_P the library renumbers its private
                                      copy of the points and of P so that points that are neighbours in P get
                                      nearby numbers: a seeded pseudo-random value per point is averaged over
@@ -74,6 +77,15 @@ typedef struct {
     int32_t reorder_every;        /* > 0 (and max_nnz > 0): additionally renumber along the current spatial
                                      order of the embedding every this many steps; pays off once neighbours
                                      in P are neighbours in the plane.  (0 = never) */
+    int32_t attract_resident;     /* resident workgroups (512 lanes) of the attraction kernel per compute unit
+                                     when the points are renumbered; each works through a contiguous share of
+                                     the rows.  A small number keeps HBM busy and leaves the rest of every
+                                     compute unit to the tree walk.  0 = library's choice.  (1) */
+    int32_t walk_resident;        /* > 0: the tree walk runs as this many resident waves per compute unit that
+                                     take groups of points from a counter, instead of one wave per group, so
+                                     that walk and attraction hold fixed shares of every compute unit; used
+                                     when there are more groups than resident waves.  0 = one wave per group.
+                                     (14) */
     int64_t max_nnz;              /* capacity for the private copy of P that renumbering needs: the workspace
                                      grows by 16 bytes per entry.  0 disables renumbering; P is then only
                                      borrowed and a stop/resume is bitwise reproducible. */
@@ -172,7 +184,7 @@ int tsne_kl(tsne_ctx *ctx, const float *d_Y, double *kl);
  * per step of the four phases (any pointer may be NULL):
  *   ms[0] tree build (Sec. III-C steps 1-4)   ms[1] walk + Z (step 5)
  *   ms[2] attractive forces (Eq. (5))         ms[3] update (Alg. 1 line 8)
- * With overlap = 1 the attractive kernel runs beside the tree phases, so the four do not add up
+ * With overlap on the attractive kernel runs beside other phases, so the four do not add up
  * to the step time.
  */
 int tsne_timing_begin(tsne_ctx *ctx, int32_t max_steps);

@@ -62,7 +62,7 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     q = take(4 * (size_t)cap);                       if (c) c->cell_p = (uint32_t *)q;
     q = take((size_t)cap);                           if (c) c->cell_t = (uint8_t *)q;
     const int32_t big_cap = (int32_t)(n / 8 + 1024);
-    q = take(sizeof(uint32_t));                      if (c) c->big_count = (uint32_t *)q;
+    q = take(2 * sizeof(uint32_t));                  if (c) { c->big_count = (uint32_t *)q; c->walk_counter = c->big_count + 1; }
     q = take(sizeof(uint2) * (size_t)big_cap);       if (c) { c->big_list = (uint2 *)q; c->big_cap = big_cap; }
     q = take(8 * n);                                 if (c) c->R = (float2 *)q;
     q = take(8 * n);                                 if (c) c->A = (float2 *)q;
@@ -75,14 +75,17 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     }
     if (reorder) {
         const size_t m = (size_t)p->max_nnz;
+        const size_t ms = m + (ATTRACT_CHUNK - 1) * n + ATTRACT_SLACK;   // near rows are padded to whole chunks
         q = take(4 * n); if (c) c->inv = (uint32_t *)q;
-        q = take(4 * n); if (c) c->lenbuf = (int32_t *)q;
-        for (int k = 0; k < 2; ++k) {
-            q = take(4 * (n + 1)); if (c) c->rp_i[k] = (int32_t *)q;
-            q = take(4 * m);       if (c) c->col_i[k] = (int32_t *)q;
-            q = take(4 * m);       if (c) c->val_i[k] = (float *)q;
-        }
+        q = take(4 * n); if (c) c->len_near = (int32_t *)q;
+        q = take(4 * n); if (c) c->len_far = (int32_t *)q;
+        q = take(4 * (n + 1)); if (c) c->rp_near = (int32_t *)q;
+        q = take(4 * (n + 1)); if (c) c->rp_far = (int32_t *)q;
+        q = take(2 * ms);      if (c) c->col_near = (uint16_t *)q;
+        q = take(4 * (m + ATTRACT_SLACK)); if (c) c->col_far = (int32_t *)q;
+        q = take(4 * ms);      if (c) c->val_s = (float *)q;
     }
+    q = take(4 * (ATTRACT_MAX_PARTS + 1));           if (c) c->arow = (int32_t *)q;
     q = take(8 * ngroups);                           if (c) c->zpart = (double *)q;
     q = take(8);                                     if (c) c->Z = (double *)q;
     q = take(8 * KL_PART_DOUBLES);                   if (c) c->kl_part = (double *)q;
@@ -97,7 +100,11 @@ int check_params(const tsne_params *p)
     if (p->morton_bits < 1 || p->morton_bits > 16) return TSNE_EINVAL;
     if (p->leaf_cap < 1) return TSNE_EINVAL;
     if (p->reorder_every < 0 || p->graph_order_iters < 0 || p->graph_order_iters > 1000) return TSNE_EINVAL;
+    if (p->attract_resident < 0 || p->attract_resident > 64) return TSNE_EINVAL;
+    if (p->walk_resident < 0 || p->walk_resident > 32) return TSNE_EINVAL;
     if (p->max_nnz < 0 || p->max_nnz > 0x7FFFFFFFll) return TSNE_EINVAL;
+    // the renumbered copy pads every row to whole chunks and is indexed with int32
+    if (p->max_nnz > 0 && p->max_nnz + (ATTRACT_CHUNK - 1ll) * p->n + ATTRACT_SLACK > 0x7FFFFFFFll) return TSNE_EINVAL;
     if (!isfinite(p->lr) || !isfinite(p->exaggeration) || !isfinite(p->momentum_early) ||
         !isfinite(p->momentum_late) || !isfinite(p->gain_inc) || !isfinite(p->gain_dec) || !isfinite(p->gain_min))
         return TSNE_EINVAL;
@@ -178,7 +185,7 @@ int reset_slot_order(tsne_ctx *c)
     c->cur_state = b;
     c->identity = 1;
     c->steps_since_reorder = 0;
-    c->row_ptr = c->user_row_ptr; c->col = c->user_col; c->val = c->user_val;
+    c->arow_valid = 0;
     return TSNE_OK;
 }
 
@@ -212,9 +219,11 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->gain_min = 0.01f;
     p->morton_bits = 16;
     p->leaf_cap = 8;
-    p->overlap = 1;
+    p->overlap = 2;
     p->graph_order_iters = 64;
     p->reorder_every = 0;
+    p->attract_resident = 1;
+    p->walk_resident = 14;
     p->max_nnz = 0;
     return TSNE_OK;
 }
@@ -243,8 +252,16 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
     carve(c, p, (char *)d_workspace);
     c->reorder_on = (p->reorder_every > 0 || p->graph_order_iters > 0) && p->max_nnz > 0;
     c->identity = 1;
-    c->cur_P = 1;
     hipError_t e;
+    {
+        int dev = 0;
+        if ((e = hipGetDevice(&dev)) != hipSuccess ||
+            (e = hipDeviceGetAttribute(&c->num_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess ||
+            c->num_cu <= 0) {
+            tsne_destroy(c);
+            return TSNE_EHIP;
+        }
+    }
     if (p->overlap) {
         // default priority on purpose; non-blocking so that it does not serialise with stream 0
         if ((e = hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking)) != hipSuccess ||
@@ -285,7 +302,8 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     int rc = reset_slot_order(c);
     if (rc != TSNE_OK) return rc;
     c->user_row_ptr = d_row_ptr; c->user_col = d_col; c->user_val = d_val;
-    c->row_ptr = d_row_ptr; c->col = d_col; c->val = d_val; c->nnz = nnz;
+    c->nnz = nnz;
+    c->arow_valid = 0;
     c->have_P = 1;
     if (c->reorder_on && c->p.graph_order_iters > 0 && nnz > 0) {
         hipError_t e;

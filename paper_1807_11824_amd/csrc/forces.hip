@@ -59,96 +59,240 @@ __global__ __launch_bounds__(256) void attract_csr(const int32_t *__restrict__ r
     if (row < n && sub == 0) A[row] = make_float2(ax, ay);
 }
 
-// Variant for renumbered points (slot order follows the structure of P, so row i's columns lie
-// mostly within a band around i): a workgroup owns ROWS consecutive rows and first stages
-// Y[r0 - HALO, r0 + ROWS + HALO) in LDS; gathers that fall inside the window are LDS reads, the
-// rest go to memory as before.  Entries of a row are taken in the same lane order as in the
-// kernel above, so both produce the same sums.
-#ifndef AW_HALO_N
-#define AW_HALO_N 1280
-#endif
-#ifndef AW_ROWS_N
-#define AW_ROWS_N 128
-#endif
-#ifndef AW_DUAL_N
-#define AW_DUAL_N 2
-#endif
-constexpr int AW_ROWS = AW_ROWS_N, AW_HALO = AW_HALO_N, AW_LPR = 16, AW_U = 4, AW_DUAL = AW_DUAL_N;
+constexpr int AW_LPR = 16, AW_U = 4;
 
-__global__ __launch_bounds__(256) void attract_csr_window(const int32_t *__restrict__ row_ptr,
-                                                          const int32_t *__restrict__ col, const float *__restrict__ val,
-                                                          const float2 *__restrict__ Y, int n, float2 *__restrict__ A)
+// ---- renumbered points: P is stored as a near part (a band around the diagonal) and a far part.
+//
+// attract_near streams the near part.  The grid is a fixed number of resident workgroups;
+// workgroup b owns the contiguous rows [arow[b], arow[b + 1]) (equal shares of the entries) and
+// moves through them ATTRACT_ROWS at a time.  Y of the band around the current rows lives in a
+// ring in LDS that slides with the rows (only the points that enter are loaded), so every y_j
+// gather is an LDS read -- the stored 16-bit column IS the byte offset into the ring -- and
+// the only global loads of the inner loop are 16-byte pieces of the column and value streams
+// (6 bytes per entry).  Four lanes share a row; a lane takes eight consecutive entries of each
+// 32-entry chunk, and rows are stored padded to whole chunks so that no load needs a guard.
+// Every group keeps AN_PD chunks in flight, requested unconditionally right after the stage's
+// registers were used, so loads are issued long before they are needed and eight waves per
+// compute unit keep HBM busy -- which leaves most of every compute unit to the tree walk that
+// runs beside it (the kernel is held to 64 registers for the same reason).  Within one window
+// step the rows are handed to the groups longest first through a counter in LDS, one row
+// ahead; a row's sum does not depend on which group takes it or when.
+#ifndef AN_PD_N
+#define AN_PD_N 2
+#endif
+constexpr int AN_THREADS = 512, AN_ROWS = ATTRACT_ROWS, AN_S = ATTRACT_RING, AN_LPR = 4, AN_CH = ATTRACT_CHUNK;
+static_assert(AN_CH == 8 * AN_LPR, "a lane takes two quads of a chunk");
+constexpr int AN_PD = AN_PD_N, AN_GROUPS = AN_THREADS / AN_LPR;
+
+__global__ void attract_partition(const int32_t *__restrict__ rp_near, int n, int parts, int32_t *__restrict__ arow)
 {
-    constexpr int WIN = AW_ROWS + 2 * AW_HALO;
-    __shared__ float2 win[WIN];
-    const int r0 = (int)blockIdx.x * AW_ROWS;
-    const int wlo = max(0, r0 - AW_HALO), whi = min(n, r0 + AW_ROWS + AW_HALO);
-    for (int t = threadIdx.x; t < whi - wlo; t += 256) win[t] = Y[wlo + t];
+    const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (b > parts) return;
+    // weight of rows [0, r): their entries plus a fixed cost per row
+    const int64_t total = (int64_t)rp_near[n] + 16ll * n;
+    const int64_t target = total * b / parts;
+    int lo = 0, hi = n;   // smallest r with weight(r) >= target
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)rp_near[mid] + 16ll * mid >= target) hi = mid; else lo = mid + 1;
+    }
+    arow[b] = b == parts ? n : lo;
+}
+
+__global__ __attribute__((amdgpu_waves_per_eu(8))) __launch_bounds__(AN_THREADS) void
+attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, const float4 *__restrict__ val4,
+             const float2 *__restrict__ Y, int n, const int32_t *__restrict__ arow, float2 *__restrict__ A)
+{
+    __shared__ float2 ring[AN_S];
+    __shared__ float2 aout[AN_ROWS];
+    __shared__ int rps[AN_ROWS + 1];
+    __shared__ int next_row;
+    __shared__ int bucket[64];
+    __shared__ uint16_t order[AN_ROWS];
+    static_assert(AN_ROWS <= 65536, "rows per step");
+    constexpr int KPT = (AN_ROWS + AN_THREADS - 1) / AN_THREADS;
+    const int rb = min(max(arow[blockIdx.x], 0), n), re = min(max(arow[blockIdx.x + 1], rb), n);
+    if (rb >= re) return;
+    const int tid = (int)threadIdx.x, sub = tid % AN_LPR, grp = tid / AN_LPR;
+    const char *ringb = reinterpret_cast<const char *>(ring);
+    for (int t = tid; t < 2 * ATTRACT_BAND; t += AN_THREADS) {
+        const int i = rb - ATTRACT_BAND + t;
+        if (i >= 0 && i < n) ring[(unsigned)i % AN_S] = Y[i];
+    }
+    int prev_r0 = 0, prev_rows = 0;
+    for (int r0 = rb; r0 < re; r0 += AN_ROWS) {
+        __syncthreads();   // the previous rows are finished: aout is complete, ring slots may be reused
+        for (int t = tid; t < prev_rows; t += AN_THREADS) A[prev_r0 + t] = aout[t];
+        for (int t = tid; t < AN_ROWS; t += AN_THREADS) {
+            const int i = r0 + ATTRACT_BAND + t;
+            if (i < n) ring[(unsigned)i % AN_S] = Y[i];
+        }
+        const int rows = min(AN_ROWS, re - r0);
+        for (int t = tid; t <= rows; t += AN_THREADS) rps[t] = rp[r0 + t];
+        if (tid < 64) bucket[tid] = 0;
+        if (tid == 0) next_row = 2 * AN_GROUPS;
+        __syncthreads();
+        // the rows are handed out longest first (counting sort by chunk count, 64 classes), so
+        // that no group is left with a long row when the others have run out of work
+        {
+            int key[KPT], pos[KPT];
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                const int t = tid + k * AN_THREADS;
+                key[k] = 0; pos[k] = 0;
+                if (t < rows) {
+                    key[k] = 63 - min((rps[t + 1] - rps[t]) >> 5, 63);
+                    pos[k] = atomicAdd(&bucket[key[k]], 1);
+                }
+            }
+            __syncthreads();
+            if (tid < 64) {
+                int tot;
+                const int ex = wave_excl_scan(bucket[tid], &tot);
+                bucket[tid] = ex;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                const int t = tid + k * AN_THREADS;
+                if (t < rows) order[bucket[key[k]] + pos[k]] = (uint16_t)t;
+            }
+            __syncthreads();
+        }
+        const int slot0 = r0 % AN_S;     // ring slot of local row 0
+        // cursor of this group: current row (local, -1 when there is none), next chunk, row end;
+        // the row after it is fetched one row ahead so that the counter's latency stays hidden
+        int crow = grp < rows ? (int)order[grp] : -1;
+        int jb = crow >= 0 ? rps[crow] : 0, je = crow >= 0 ? rps[crow + 1] : 0;
+        int nrow = grp + AN_GROUPS < rows ? (int)order[grp + AN_GROUPS] : -1;
+        int njb = nrow >= 0 ? rps[nrow] : 0, nje = nrow >= 0 ? rps[nrow + 1] : 0;
+        uint4 C[AN_PD];          // eight 16-bit ring offsets
+        float4 V[AN_PD][2];
+        int R[AN_PD];
+        bool OK[AN_PD], FIN[AN_PD];
+        float ax = 0.f, ay = 0.f;
+        // request the cursor's next chunk into stage s and move the cursor (rows are whole
+        // chunks; a lane takes entries 8 sub .. 8 sub + 7 of the chunk)
+#define AN_ISSUE(s)                                                                      \
+        {                                                                                \
+            const int off_ = (jb >> 3) + sub;                                            \
+            R[s] = crow;                                                                 \
+            OK[s] = crow >= 0 && jb < je;                                                \
+            FIN[s] = crow >= 0 && jb + AN_CH >= je;                                      \
+            C[s] = col8[off_];                                                           \
+            V[s][0] = val4[2 * off_];                                                    \
+            V[s][1] = val4[2 * off_ + 1];                                                \
+            if (__any(FIN[s])) {                                                         \
+                int t_ = 0;                                                              \
+                if (FIN[s] && sub == 0) t_ = atomicAdd(&next_row, 1);                    \
+                t_ = first4(t_);                                                         \
+                if (FIN[s]) {                                                            \
+                    crow = nrow; jb = njb; je = nje;                                     \
+                    nrow = t_ < rows ? (int)order[t_] : -1;                              \
+                    njb = nrow >= 0 ? rps[nrow] : 0;                                     \
+                    nje = nrow >= 0 ? rps[nrow + 1] : 0;                                 \
+                } else if (crow >= 0) {                                                  \
+                    jb += AN_CH;                                                         \
+                }                                                                        \
+            } else if (crow >= 0) {                                                      \
+                jb += AN_CH;                                                             \
+            }                                                                            \
+        }
+        // one interaction; o = byte offset of y_j in the ring
+#define AN_ONE(o, p)                                                                     \
+        {                                                                                \
+            const float2 yj_ = *reinterpret_cast<const float2 *>(ringb + min((o), (unsigned)(AN_S - 1) * 8u)); \
+            const float dx = yi.x - yj_.x, dy = yi.y - yj_.y;                            \
+            const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));     \
+            const float pw = (p) * w;                                                    \
+            ax = fmaf(pw, dx, ax);                                                       \
+            ay = fmaf(pw, dy, ay);                                                       \
+        }
+#pragma unroll
+        for (int s = 0; s < AN_PD; ++s) AN_ISSUE(s)
+        for (;;) {
+            bool live = false;
+#pragma unroll
+            for (int s = 0; s < AN_PD; ++s) {
+                const uint4 c = C[s];
+                const float4 v0 = V[s][0], v1 = V[s][1];
+                const int r = R[s];
+                const bool ok = OK[s], fin = FIN[s];
+                live |= r >= 0;
+                if (ok) {
+                    int sl = slot0 + r;
+                    sl = sl >= AN_S ? sl - AN_S : sl;
+                    const float2 yi = ring[sl];
+                    AN_ONE(c.x & 0xFFFFu, v0.x) AN_ONE(c.x >> 16, v0.y) AN_ONE(c.y & 0xFFFFu, v0.z) AN_ONE(c.y >> 16, v0.w)
+                    AN_ONE(c.z & 0xFFFFu, v1.x) AN_ONE(c.z >> 16, v1.y) AN_ONE(c.w & 0xFFFFu, v1.z) AN_ONE(c.w >> 16, v1.w)
+                }
+                if (__any(fin)) {
+                    const float sx = sum4(ax), sy = sum4(ay);
+                    if (fin) {
+                        if (sub == 0) aout[r] = make_float2(sx, sy);
+                        ax = ay = 0.f;
+                    }
+                }
+                // refill the stage only now that its registers are free: requesting earlier
+                // makes the compiler copy the arriving data at the loop end, which waits for it
+                AN_ISSUE(s)
+            }
+            if (!__any(live)) break;
+        }
+#undef AN_ISSUE
+#undef AN_ONE
+        prev_r0 = r0;
+        prev_rows = rows;
+    }
     __syncthreads();
-    const int sub = (int)(threadIdx.x % AW_LPR);
-    constexpr int GROUPS = 256 / AW_LPR;
-    // every 16-lane group works on AW_DUAL rows at a time so that twice as many loads are in flight
-    for (int rr = (int)threadIdx.x / AW_LPR; rr < AW_ROWS; rr += GROUPS * AW_DUAL) {
-        int row[AW_DUAL], j0[AW_DUAL], e[AW_DUAL];
-        float2 yi[AW_DUAL];
-        float ax[AW_DUAL], ay[AW_DUAL];
-        bool more = false;
+    for (int t = tid; t < prev_rows; t += AN_THREADS) A[prev_r0 + t] = aout[t];
+}
+
+// The far part: eight lanes per row, y_j gathered from memory; adds to what attract_near left.
+__global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
+                                                   const float *__restrict__ val, const float2 *__restrict__ Y, int n,
+                                                   float2 *__restrict__ A)
+{
+    const int row = (int)((blockIdx.x * 256u + threadIdx.x) / 8);
+    const int sub = (int)(threadIdx.x % 8);
+    int s = 0, e = 0;
+    if (row < n) { s = rp[row]; e = rp[row + 1]; }
+    if (!__any(s < e)) return;
+    const int far0 = rp[0];      // values sit behind the near part, columns start at 0
+    float ax = 0.f, ay = 0.f;
+    if (s < e) {
+        const float2 yi = Y[row];
+        for (int j0 = s + sub; j0 < e; j0 += 8 * 4) {
+            int c[4];
+            float v[4];
+            float2 yj[4];
 #pragma unroll
-        for (int d = 0; d < AW_DUAL; ++d) {
-            row[d] = r0 + rr + d * GROUPS;
-            const bool live = rr + d * GROUPS < AW_ROWS && row[d] < n;
-            if (!live) row[d] = -1;
-            j0[d] = live ? row_ptr[row[d]] + sub : 0;
-            e[d] = live ? row_ptr[row[d] + 1] : 0;
-            yi[d] = live ? win[row[d] - wlo] : make_float2(0.f, 0.f);
-            ax[d] = ay[d] = 0.f;
-            more |= j0[d] < e[d];
-        }
-        while (__any(more)) {
-            int c[AW_DUAL][AW_U];
-            float v[AW_DUAL][AW_U];
-            float2 yj[AW_DUAL][AW_U];
+            for (int q = 0; q < 4; ++q) {
+                const int j = j0 + 8 * q;
+                const bool in = j < e;
+                c[q] = in ? col[j - far0] : row;
+                v[q] = in ? val[j] : 0.f;
+            }
 #pragma unroll
-            for (int d = 0; d < AW_DUAL; ++d)
+            for (int q = 0; q < 4; ++q) yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
 #pragma unroll
-                for (int q = 0; q < AW_U; ++q) {
-                    const int j = j0[d] + q * AW_LPR;
-                    const bool in = j < e[d];
-                    c[d][q] = in ? col[j] : wlo;      // padding: any in-window point, weight 0
-                    v[d][q] = in ? val[j] : 0.f;
-                }
-#pragma unroll
-            for (int d = 0; d < AW_DUAL; ++d)
-#pragma unroll
-                for (int q = 0; q < AW_U; ++q) {
-                    const unsigned off = (unsigned)(c[d][q] - wlo);
-                    if (off < (unsigned)(whi - wlo)) yj[d][q] = win[off];
-                    else yj[d][q] = Y[min((uint32_t)c[d][q], (uint32_t)n - 1u)];
-                }
-            more = false;
-#pragma unroll
-            for (int d = 0; d < AW_DUAL; ++d) {
-#pragma unroll
-                for (int q = 0; q < AW_U; ++q) {
-                    const float dx = yi[d].x - yj[d][q].x, dy = yi[d].y - yj[d][q].y;
-                    const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
-                    const float pw = v[d][q] * w;
-                    ax[d] = fmaf(pw, dx, ax[d]);
-                    ay[d] = fmaf(pw, dy, ay[d]);
-                }
-                j0[d] += AW_LPR * AW_U;
-                more |= j0[d] < e[d];
+            for (int q = 0; q < 4; ++q) {
+                const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
+                const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+                const float pw = v[q] * w;
+                ax = fmaf(pw, dx, ax);
+                ay = fmaf(pw, dy, ay);
             }
         }
+    }
 #pragma unroll
-        for (int d = 0; d < AW_DUAL; ++d) {
-#pragma unroll
-            for (int o = AW_LPR / 2; o > 0; o >>= 1) {
-                ax[d] += __shfl_xor(ax[d], o, WAVE);
-                ay[d] += __shfl_xor(ay[d], o, WAVE);
-            }
-            if (row[d] >= 0 && sub == 0) A[row[d]] = make_float2(ax[d], ay[d]);
-        }
+    for (int o = 4; o > 0; o >>= 1) {
+        ax += __shfl_xor(ax, o, WAVE);
+        ay += __shfl_xor(ay, o, WAVE);
+    }
+    if (s < e && sub == 0) {
+        const float2 a = A[row];
+        A[row] = make_float2(a.x + ax, a.y + ay);
     }
 }
 
@@ -157,12 +301,21 @@ hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s)
     const int n = c->p.n;
     (void)d_Y;
     if (c->reorder_on && !c->identity) {
-        hipLaunchKernelGGL(attract_csr_window, dim3((n + AW_ROWS - 1) / AW_ROWS), dim3(256), 0, s, c->row_ptr, c->col,
-                           c->val, c->Yi, n, c->A);
+        const int per_cu = c->p.attract_resident > 0 ? c->p.attract_resident : 2;
+        const int parts = max(1, min(min(per_cu * c->num_cu, ATTRACT_MAX_PARTS), (n + AN_ROWS - 1) / AN_ROWS));
+        if (!c->arow_valid) {   // P changed since the rows were shared out
+            hipLaunchKernelGGL(attract_partition, dim3((parts + 256) / 256), dim3(256), 0, s, c->rp_near, n, parts,
+                               c->arow);
+            c->arow_valid = 1;
+        }
+        hipLaunchKernelGGL(attract_near, dim3(parts), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
+                           (const float4 *)c->val_s, c->Yi, n, c->arow, c->A);
+        hipLaunchKernelGGL(attract_far, dim3((unsigned)(((int64_t)n * 8 + 255) / 256)), dim3(256), 0, s, c->rp_far,
+                           c->col_far, c->val_s, c->Yi, n, c->A);
     } else {
         const unsigned blocks = (unsigned)(((int64_t)n * AW_LPR + 255) / 256);
-        hipLaunchKernelGGL((attract_csr<AW_LPR, AW_U>), dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val,
-                           c->Yi, n, c->row_order, c->A);
+        hipLaunchKernelGGL((attract_csr<AW_LPR, AW_U>), dim3(blocks), dim3(256), 0, s, c->user_row_ptr, c->user_col,
+                           c->user_val, c->Yi, n, c->row_order, c->A);
     }
     return hipGetLastError();
 }

@@ -1,12 +1,14 @@
-// Renumbering of the points along the current spatial order.
+// Renumbering of the points.
 //
 // The paper names the attractive forces as the bottleneck because the sparsity pattern of P is
-// disorganised (Sec. IV-D): row i gathers y_j from all over memory.  Once the embedding has
-// formed, neighbours in P are neighbours in the plane, so storing the points in the order of
-// the space-filling curve (which the tree build computes anyway, Sec. III-C step 4) turns those
-// gathers into accesses to a small, cache-resident window.  Nothing the method computes
-// changes: P keeps its values and the order of the entries inside every row, only row and
-// column numbers are relabelled; `orig` maps the library's slots back to the caller's indices.
+// disorganised (Sec. IV-D): row i gathers y_j from all over memory.  The library therefore keeps
+// its own numbering of the points ("slots", `orig` maps them back to the caller's indices) in
+// which neighbours in P get nearby numbers -- from the structure of P (below) or from the
+// spatial order of the embedding, which the tree build computes anyway (Sec. III-C step 4).
+// In that numbering almost all of P lies in a band around the diagonal.  The private copy of
+// P is stored split: the near part (|column - row| <= ATTRACT_BAND), which the attraction
+// kernel serves from a sliding window of Y in LDS, and the far remainder.  Values and the
+// order of the entries inside each part of a row are those of the caller's P.
 #include "tsne_internal.h"
 
 // position p of the new order takes over old slot s = perm[p]
@@ -14,21 +16,51 @@ __global__ __launch_bounds__(256) void reorder_state_k(const uint32_t *__restric
                                                        const uint32_t *__restrict__ orig_in, uint32_t *__restrict__ orig_out,
                                                        const float2 *__restrict__ u_in, float2 *__restrict__ u_out,
                                                        const float2 *__restrict__ g_in, float2 *__restrict__ g_out,
-                                                       const int32_t *__restrict__ rp_in, uint32_t *__restrict__ inv,
-                                                       int32_t *__restrict__ len)
+                                                       uint32_t *__restrict__ inv)
 {
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= n) return;
     const uint32_t s = min(perm[p], (uint32_t)n - 1u);
-    orig_out[p] = orig_in[s];
+    const uint32_t o = min(orig_in[s], (uint32_t)n - 1u);
+    orig_out[p] = o;
     u_out[p] = u_in[s];
     g_out[p] = g_in[s];
-    inv[s] = (uint32_t)p;
-    len[p] = rp_in[s + 1] - rp_in[s];
+    inv[o] = (uint32_t)p;
 }
 
-// rp_out = exclusive prefix sum of len (single block; runs once per renumbering)
-__global__ __launch_bounds__(1024) void scan_len_k(const int32_t *__restrict__ len, int n, int32_t *__restrict__ rp_out)
+__device__ __forceinline__ bool in_band(uint32_t col_slot, int row_slot)
+{
+    const int d = (int)col_slot - row_slot;
+    return d <= ATTRACT_BAND && d >= -ATTRACT_BAND;
+}
+
+// 16 lanes per slot p: how many entries of the caller's row orig[p] fall in the band
+__global__ __launch_bounds__(256) void split_count_k(const uint32_t *__restrict__ orig, const uint32_t *__restrict__ inv,
+                                                     int n, const int32_t *__restrict__ urp,
+                                                     const int32_t *__restrict__ ucol, int32_t *__restrict__ len_near,
+                                                     int32_t *__restrict__ len_far)
+{
+    const int p = (int)((blockIdx.x * 256u + threadIdx.x) / 16);
+    const int sub = (int)(threadIdx.x % 16);
+    int near = 0, len = 0;
+    if (p < n) {
+        const uint32_t u = min(orig[p], (uint32_t)n - 1u);
+        const int src = urp[u];
+        len = urp[u + 1] - src;
+        for (int e = sub; e < len; e += 16)
+            near += in_band(inv[min((uint32_t)ucol[src + e], (uint32_t)n - 1u)], p) ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) near += __shfl_xor(near, o, WAVE);
+    if (p < n && sub == 0) {
+        len_near[p] = (near + ATTRACT_CHUNK - 1) / ATTRACT_CHUNK * ATTRACT_CHUNK;     // padded to whole chunks
+        len_far[p] = len - near;
+    }
+}
+
+// rp_out = base + exclusive prefix sum of len (single block; runs once per renumbering)
+__global__ __launch_bounds__(1024) void scan_len_k(const int32_t *__restrict__ len, int n, const int32_t *__restrict__ base,
+                                                   int32_t *__restrict__ rp_out)
 {
     __shared__ long long ws[16];
     const int per = (n + 1023) / 1024;
@@ -43,27 +75,58 @@ __global__ __launch_bounds__(1024) void scan_len_k(const int32_t *__restrict__ l
     }
     if (lane_id() == WAVE - 1) ws[threadIdx.x >> 6] = inc;
     __syncthreads();
-    long long pre = inc - a;
+    long long pre = inc - a + (base ? (long long)*base : 0ll);
     for (int q = 0; q < (int)(threadIdx.x >> 6); ++q) pre += ws[q];
     for (int i = s; i < e; ++i) { rp_out[i] = (int32_t)pre; pre += len[i]; }
     if (threadIdx.x == 1023) rp_out[n] = (int32_t)pre;
 }
 
-// 16 lanes copy one row: entries keep their order, columns are relabelled
-__global__ __launch_bounds__(256) void reorder_rows_k(const uint32_t *__restrict__ perm, const uint32_t *__restrict__ inv,
-                                                      int n, const int32_t *__restrict__ rp_in,
-                                                      const int32_t *__restrict__ col_in, const float *__restrict__ val_in,
-                                                      const int32_t *__restrict__ rp_out, int32_t *__restrict__ col_out,
-                                                      float *__restrict__ val_out)
+// 16 lanes copy one row: columns are relabelled, the entries go to the near or the far part in
+// their original order, and the near part is filled up to whole chunks with (own slot, 0)
+__global__ __launch_bounds__(256) void split_fill_k(const uint32_t *__restrict__ orig, const uint32_t *__restrict__ inv,
+                                                    int n, const int32_t *__restrict__ urp,
+                                                    const int32_t *__restrict__ ucol, const float *__restrict__ uval,
+                                                    const int32_t *__restrict__ rp_near, const int32_t *__restrict__ rp_far,
+                                                    uint16_t *__restrict__ col_near, int32_t *__restrict__ col_far,
+                                                    float *__restrict__ val_s)
 {
     const int p = (int)((blockIdx.x * 256u + threadIdx.x) / 16);
     const int sub = (int)(threadIdx.x % 16);
     if (p >= n) return;
-    const uint32_t s = min(perm[p], (uint32_t)n - 1u);
-    const int src = rp_in[s], len = rp_in[s + 1] - src, dst = rp_out[p];
-    for (int e = sub; e < len; e += 16) {
-        col_out[dst + e] = (int32_t)inv[min((uint32_t)col_in[src + e], (uint32_t)n - 1u)];
-        val_out[dst + e] = val_in[src + e];
+    const int shift = (int)(lane_id() & 48);          // first lane of this 16-lane group
+    const uint32_t below = (1u << sub) - 1u;
+    const uint32_t u = min(orig[p], (uint32_t)n - 1u);
+    const int src = urp[u], len = urp[u + 1] - src;
+    int dn = rp_near[p], df = rp_far[p];
+    const int far0 = rp_far[0];
+    const int end_near = rp_near[p + 1];
+    for (int e0 = 0; e0 < len; e0 += 16) {
+        const int e = e0 + sub;
+        const bool in = e < len;
+        uint32_t cs = 0u;
+        float v = 0.f;
+        if (in) {
+            cs = inv[min((uint32_t)ucol[src + e], (uint32_t)n - 1u)];
+            v = uval[src + e];
+        }
+        const bool near = in && in_band(cs, p);
+        const uint32_t mn = (uint32_t)(__ballot(near) >> shift) & 0xFFFFu;
+        const uint32_t mf = (uint32_t)(__ballot(in && !near) >> shift) & 0xFFFFu;
+        if (near) {   // near columns are stored as the byte offset of the point in the ring of Y
+            const int d = dn + __popc(mn & below);
+            col_near[d] = (uint16_t)((cs % (uint32_t)ATTRACT_RING) * 8u);
+            val_s[d] = v;
+        } else if (in) {
+            const int d = df + __popc(mf & below);
+            col_far[d - far0] = (int32_t)cs;
+            val_s[d] = v;
+        }
+        dn += __popc(mn);
+        df += __popc(mf);
+    }
+    for (int d = dn + sub; d < end_near; d += 16) {       // padding: own point, weight 0
+        col_near[d] = (uint16_t)((p % ATTRACT_RING) * 8);
+        val_s[d] = 0.f;
     }
 }
 
@@ -72,18 +135,19 @@ hipError_t launch_reorder(tsne_ctx *c, hipStream_t s)
     const int n = c->p.n;
     const uint32_t *perm = c->idx[c->sorted_buf];
     const int a = c->cur_state, b = a ^ 1;
-    const int pb = c->cur_P ^ 1;        // internal CSR buffer to fill
     hipLaunchKernelGGL(reorder_state_k, dim3((n + 255) / 256), dim3(256), 0, s, perm, n, c->orig[a], c->orig[b],
-                       c->uYb[a], c->uYb[b], c->gainsb[a], c->gainsb[b], c->row_ptr, c->inv, c->lenbuf);
-    hipLaunchKernelGGL(scan_len_k, dim3(1), dim3(1024), 0, s, c->lenbuf, n, c->rp_i[pb]);
+                       c->uYb[a], c->uYb[b], c->gainsb[a], c->gainsb[b], c->inv);
     const unsigned blocks = (unsigned)(((int64_t)n * 16 + 255) / 256);
-    hipLaunchKernelGGL(reorder_rows_k, dim3(blocks), dim3(256), 0, s, perm, c->inv, n, c->row_ptr, c->col, c->val,
-                       c->rp_i[pb], c->col_i[pb], c->val_i[pb]);
+    hipLaunchKernelGGL(split_count_k, dim3(blocks), dim3(256), 0, s, c->orig[b], c->inv, n, c->user_row_ptr, c->user_col,
+                       c->len_near, c->len_far);
+    hipLaunchKernelGGL(scan_len_k, dim3(1), dim3(1024), 0, s, c->len_near, n, (const int32_t *)nullptr, c->rp_near);
+    hipLaunchKernelGGL(scan_len_k, dim3(1), dim3(1024), 0, s, c->len_far, n, (const int32_t *)(c->rp_near + n), c->rp_far);
+    hipLaunchKernelGGL(split_fill_k, dim3(blocks), dim3(256), 0, s, c->orig[b], c->inv, n, c->user_row_ptr, c->user_col,
+                       c->user_val, c->rp_near, c->rp_far, c->col_near, c->col_far, c->val_s);
     hipError_t e = launch_iota(c->row_order, n, s);
     if (e != hipSuccess) return e;
     c->cur_state = b;
-    c->cur_P = pb;
-    c->row_ptr = c->rp_i[pb]; c->col = c->col_i[pb]; c->val = c->val_i[pb];
+    c->arow_valid = 0;
     c->identity = 0;
     return hipGetLastError();
 }
@@ -141,7 +205,7 @@ hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s)
     hipLaunchKernelGGL(graph_seed_k, dim3((n + 255) / 256), dim3(256), 0, s, xa, n);
     const unsigned blocks = (unsigned)(((int64_t)n * 16 + 255) / 256);
     for (int t = 0; t < c->p.graph_order_iters; ++t) {
-        hipLaunchKernelGGL(graph_smooth_k, dim3(blocks), dim3(256), 0, s, c->row_ptr, c->col, c->val, xa, n, xb);
+        hipLaunchKernelGGL(graph_smooth_k, dim3(blocks), dim3(256), 0, s, c->user_row_ptr, c->user_col, c->user_val, xa, n, xb);
         float *tmp = xa; xa = xb; xb = tmp;
     }
     hipLaunchKernelGGL(graph_keys_k, dim3((n + 255) / 256), dim3(256), 0, s, xa, n, c->keys[0], c->idx[0]);

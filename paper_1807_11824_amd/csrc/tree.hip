@@ -469,7 +469,10 @@ __global__ __launch_bounds__(1024) void scan_partials(ScanPart *__restrict__ par
                                                       uint32_t *__restrict__ ncells, uint32_t cap_cells,
                                                       uint32_t *status, uint32_t *__restrict__ big_count)
 {
-    if (threadIdx.x == 0) *big_count = 0u;    // list of large cells filled by write_cells
+    if (threadIdx.x == 0) {
+        big_count[0] = 0u;    // list of large cells filled by write_cells
+        big_count[1] = 0u;    // work counter of the walk
+    }
     __shared__ double wx[16], wy[16];
     __shared__ uint32_t wc[16];
     const int tid = threadIdx.x, w = tid >> 6;

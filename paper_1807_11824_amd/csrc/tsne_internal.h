@@ -34,24 +34,41 @@ constexpr int LEVEL_THREADS = 256;
 constexpr int LEVEL_ITEMS = 4;
 constexpr int LEVEL_TILE = LEVEL_THREADS * LEVEL_ITEMS;
 constexpr int BBOX_MAX_BLOCKS = 1024;
+constexpr int ATTRACT_BAND = 1280;       // half width of the near part of the renumbered P
+#ifndef ATTRACT_ROWS_N
+#define ATTRACT_ROWS_N 512
+#endif
+constexpr int ATTRACT_ROWS = ATTRACT_ROWS_N;        // rows the attraction kernel's window of Y advances by
+constexpr int ATTRACT_RING = ATTRACT_ROWS + 2 * ATTRACT_BAND;   // points in that window (a ring in LDS)
+static_assert(ATTRACT_RING * 8 <= 65536, "ring offsets are stored in 16 bits");
+constexpr int ATTRACT_CHUNK = 32;        // near rows are padded to a multiple of this many entries
+constexpr int ATTRACT_SLACK = 64;        // entries readable past the end of col_s / val_s
+constexpr int ATTRACT_MAX_PARTS = 16384; // most resident workgroups of the attraction kernel
 
 struct tsne_ctx {
     tsne_params p;
     hipStream_t stream;
     hipStream_t stream2;
+    int num_cu;                    // compute units of the current device
     hipEvent_t ev_fork, ev_join;
     int have_P, tree_valid;
-    // P in the caller's numbering (borrowed) and in the library's current slot numbering
+    // P in the caller's numbering (borrowed)
     const int32_t *user_row_ptr, *user_col;
     const float *user_val;
-    const int32_t *row_ptr, *col;
-    const float *val;
     int64_t nnz;
     // slot order: slot s holds original point orig[cur_state][s]; velocity and gains live in slot order
-    int reorder_on, cur_state, cur_P, steps_since_reorder, identity;
-    uint32_t *orig[2], *inv;
-    int32_t *rp_i[2], *col_i[2], *lenbuf;
-    float *val_i[2];
+    int reorder_on, cur_state, steps_since_reorder, identity;
+    uint32_t *orig[2], *inv;     // inv: caller's index -> slot
+    // P in slot numbering, split by distance from the diagonal (valid while !identity): entries
+    // with |column - row| <= ATTRACT_BAND form the near part (rows padded with zero weights to a
+    // multiple of ATTRACT_CHUNK entries, so every row starts on a 128-byte line and no line is
+    // shared between rows), the others the far part.  Values of both live in val_s, the far part
+    // after the near part (rp_far holds positions in val_s).  A near column is stored as the
+    // 16-bit byte offset of its point in the LDS ring of Y that the attraction kernel keeps
+    // (8 (column mod ATTRACT_RING)); far columns are slot numbers, col_far[j - rp_far[0]].
+    int32_t *rp_near, *rp_far, *col_far, *len_near, *len_far;
+    uint16_t *col_near;
+    float *val_s;
     float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
     float4 *bbox_part;   // [BBOX_MAX_BLOCKS*2]  (min, max) pairs
@@ -60,6 +77,8 @@ struct tsne_ctx {
     uint32_t *ncells;    // device cell count
     uint32_t *keys[2], *idx[2];
     uint32_t *keys_orig; // keys in original order (kept for export)
+    int32_t *arow;              // first row of each resident workgroup of the attraction kernel (+ end)
+    int arow_valid;             // arow matches the current near part
     uint32_t *row_order; // order in which the attractive kernel visits the rows (an earlier spatial order)
     uint32_t *hist, *dtot;
     float2 *Ys;
@@ -71,6 +90,7 @@ struct tsne_ctx {
     int32_t cap_cells;
     uint32_t *cell_p;      // position and depth of every cell, by cell number
     uint8_t *cell_t;
+    uint32_t *walk_counter; // work counter of the resident walk (zeroed by the tree build)
     uint32_t *big_count;   // cells too large for the in-LDS searches, finished by a second kernel
     uint2 *big_list;
     int32_t big_cap;
@@ -132,6 +152,31 @@ __device__ __forceinline__ float wave_max(float v)
     for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
     return v;
 }
+
+// Data-parallel primitive moves between lanes (no LDS traffic).  CTRL: 0xB1 swaps neighbours,
+// 0x4E swaps pairs inside every four lanes, 0x141 mirrors every eight lanes, 0x00 copies the
+// first lane of every four, 0x114 shifts by four lanes inside every sixteen.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true); }
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
+// sum over every aligned group of eight lanes, delivered to all eight; all lanes must be active
+__device__ __forceinline__ float sum8(float v)
+{
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    v += dpp_f<0x141>(v);
+    return v;
+}
+// the same for groups of four lanes
+__device__ __forceinline__ float sum4(float v)
+{
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    return v;
+}
+// value of the first lane of every aligned group of four lanes
+__device__ __forceinline__ int first4(int v) { return dpp_i<0x00>(v); }
 
 // Exclusive prefix sum over the 64 lanes; *total receives the wave sum.
 __device__ __forceinline__ int wave_excl_scan(int v, int *total)

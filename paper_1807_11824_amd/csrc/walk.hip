@@ -14,12 +14,16 @@
 //                    test decides wait on a short pending list.
 //        settle      64 pending cells at a time: minimum of |y_i - y_cell|^2 over the group's
 //                    points (LDS broadcasts), then the exact test.
-//                    Either way accepted cells go to an interaction list in LDS as
-//                    (y_cell, N_cell); rejected inner cells push their children; rejected leaves
-//                    put their points on the list with N = 1.
-//   lanes = points   the list is drained: every lane adds N w^2 (y_i - y_cell) and N w,
+//                    Either way accepted cells go to a list in LDS as (y_cell, N_cell);
+//                    rejected inner cells push their children; rejected leaves put their
+//                    points on a second list.
+//   lanes = points   the lists are drained: every lane adds N w^2 (y_i - y_cell) and N w,
 //                    w = 1/(1+|y_i - y_cell|^2), for its own point (Eq. (15) and the Z note
 //                    that follows it); list entries are LDS broadcasts.
+//
+// The LDS arrays of a wave are sized to seven allocation granules (1280 bytes each) and the
+// kernel is held to 96 registers: with those numbers 14 walking waves fit on a compute unit
+// beside one workgroup of the attraction kernel, and 18 alone.
 //
 // A point meets itself exactly once (the leaf that holds it can never pass its own test when
 // theta^2 < 1/2) with w = 1 and zero force; the Z accumulator therefore starts at -1.
@@ -33,11 +37,16 @@
 constexpr int WALK_STACK = WALK_STACK_N;   // stack entries
 constexpr int WALK_SLACK = 48;       // head room for a depth-first descent (3 entries per level, 16 levels)
 constexpr int WALK_PEND = 128;       // pending list entries
-#ifndef WALK_LIST_N
-#define WALK_LIST_N 576
-#endif
-constexpr int WALK_LIST = WALK_LIST_N;       // interaction list entries (16 B each), >= 64 + 64 * WALK_FAST_LEAF
 constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied by their own lane
+#ifndef WALK_CLIST_N
+#define WALK_CLIST_N 96
+#endif
+#ifndef WALK_PLIST_N
+#define WALK_PLIST_N 512
+#endif
+constexpr int WALK_CLIST = WALK_CLIST_N;     // accepted cells waiting for the drain (16 B each), >= 64
+constexpr int WALK_PLIST = WALK_PLIST_N;     // points of opened leaves waiting (8 B each), >= 64 * WALK_FAST_LEAF
+static_assert(WALK_CLIST >= WAVE && WALK_PLIST >= WAVE * WALK_FAST_LEAF, "one round must fit");
 
 #ifdef WALK_STATS
 // instrumentation for tuning builds only: sums and maxima over all waves of one launch
@@ -79,46 +88,72 @@ __device__ __forceinline__ bool passes(float side2, float theta2, float d2)
         fy = fmaf(f_, dy_, fy);                                               \
     }
 
-__device__ __forceinline__ void drain(const float4 *__restrict__ ilist, int cnt, float x, float y, float &fx,
-                                      float &fy, float &z)
+// The same for a single point (weight 1).
+#define TSNE_INTERACT1(c)                                                     \
+    {                                                                         \
+        const float dx_ = x - (c).x, dy_ = y - (c).y;                         \
+        const float q_ = __builtin_amdgcn_rcpf(fmaf(dy_, dy_, fmaf(dx_, dx_, 1.0f))); \
+        z += q_;                                                              \
+        const float f_ = q_ * q_;                                             \
+        fx = fmaf(f_, dx_, fx);                                               \
+        fy = fmaf(f_, dy_, fy);                                               \
+    }
+
+// lanes = points: every lane adds the listed cells' (points') contributions for its own point.
+// Two register sets take turns: one is filled from LDS while the other is used.
+__device__ __forceinline__ void drain_cells(const float4 *__restrict__ list, int cnt, float x, float y, float &fx,
+                                            float &fy, float &z)
 {
     __syncthreads();
     int e = 0;
     if (cnt >= 8) {
-        // two register sets take turns: one is filled from LDS while the other is used
-        float4 a0 = ilist[0], a1 = ilist[1], a2 = ilist[2], a3 = ilist[3];
+        float4 a0 = list[0], a1 = list[1], a2 = list[2], a3 = list[3];
         for (e = 4; e + 8 <= cnt; e += 8) {
-            const float4 b0 = ilist[e], b1 = ilist[e + 1], b2 = ilist[e + 2], b3 = ilist[e + 3];
+            const float4 b0 = list[e], b1 = list[e + 1], b2 = list[e + 2], b3 = list[e + 3];
             TSNE_INTERACT(a0) TSNE_INTERACT(a1) TSNE_INTERACT(a2) TSNE_INTERACT(a3)
-            a0 = ilist[e + 4]; a1 = ilist[e + 5]; a2 = ilist[e + 6]; a3 = ilist[e + 7];
+            a0 = list[e + 4]; a1 = list[e + 5]; a2 = list[e + 6]; a3 = list[e + 7];
             TSNE_INTERACT(b0) TSNE_INTERACT(b1) TSNE_INTERACT(b2) TSNE_INTERACT(b3)
         }
         TSNE_INTERACT(a0) TSNE_INTERACT(a1) TSNE_INTERACT(a2) TSNE_INTERACT(a3)
     }
     for (; e < cnt; ++e) {
-        const float4 c = ilist[e];
+        const float4 c = list[e];
         TSNE_INTERACT(c)
     }
     __syncthreads();
 }
 
-__global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, const float2 *__restrict__ Ys,
-                                                const uint32_t *__restrict__ perm, int n,
-                                                const float4 *__restrict__ root, float theta2,
-                                                const uint32_t *__restrict__ ncells, uint32_t cap_cells,
-                                                float2 *__restrict__ R, double *__restrict__ zpart,
-                                                uint32_t *status)
+__device__ __forceinline__ void drain_points(const float2 *__restrict__ list, int cnt, float x, float y, float &fx,
+                                             float &fy, float &z)
 {
-    __shared__ uint32_t stack[WALK_STACK];
-    __shared__ uint32_t pend[WALK_PEND];
-    __shared__ float2 pts[WAVE];
-    __shared__ float4 ilist[WALK_LIST];
-#ifdef WALK_LDS_PAD
-    __shared__ uint32_t lds_pad[WALK_LDS_PAD / 4];   // tuning builds: lowers the number of resident groups per CU
-    if (threadIdx.x == 0 && n < 0) lds_pad[0] = 1;
-#endif
+    __syncthreads();
+    int e = 0;
+    if (cnt >= 8) {
+        float2 a0 = list[0], a1 = list[1], a2 = list[2], a3 = list[3];
+        for (e = 4; e + 8 <= cnt; e += 8) {
+            const float2 b0 = list[e], b1 = list[e + 1], b2 = list[e + 2], b3 = list[e + 3];
+            TSNE_INTERACT1(a0) TSNE_INTERACT1(a1) TSNE_INTERACT1(a2) TSNE_INTERACT1(a3)
+            a0 = list[e + 4]; a1 = list[e + 5]; a2 = list[e + 6]; a3 = list[e + 7];
+            TSNE_INTERACT1(b0) TSNE_INTERACT1(b1) TSNE_INTERACT1(b2) TSNE_INTERACT1(b3)
+        }
+        TSNE_INTERACT1(a0) TSNE_INTERACT1(a1) TSNE_INTERACT1(a2) TSNE_INTERACT1(a3)
+    }
+    for (; e < cnt; ++e) {
+        const float2 c = list[e];
+        TSNE_INTERACT1(c)
+    }
+    __syncthreads();
+}
+
+// The walk of one group g.  stack / pend / pts / clist / plist are the wave's LDS arrays.
+__device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_t *pend, float2 *pts, float4 *clist,
+                                           float2 *plist,
+                                           const Cell *__restrict__ cells, const float2 *__restrict__ Ys,
+                                           const uint32_t *__restrict__ perm, int n, const float4 *__restrict__ root,
+                                           float theta2, const uint32_t *__restrict__ ncells, uint32_t cap_cells,
+                                           float2 *__restrict__ R, double *__restrict__ zpart, uint32_t *status)
+{
     const int lane = (int)threadIdx.x;
-    const int g = (int)blockIdx.x;
     const int p = g * WAVE + lane;
     const bool valid = p < n;
     const uint32_t m_cells = *ncells;
@@ -127,6 +162,7 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
         if (lane == 0) zpart[g] = 0.0;
         return;
     }
+    __syncthreads();   // the previous group of this wave is done with the LDS arrays
     // own point; idle lanes of the last group shadow its first point and are never written out
     const float2 me = Ys[valid ? p : g * WAVE];
     const float x = me.x, y = me.y;
@@ -134,7 +170,7 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
     const float bx0 = wave_min(x), bx1 = wave_max(x), by0 = wave_min(y), by1 = wave_max(y);
     const float W = root->z;
     float fx = 0.f, fy = 0.f, z = -1.0f;
-    int sp = 1, np = 0, ic = 0;   // wave-uniform; kept in scalar registers via readfirstlane
+    int sp = 1, np = 0, icc = 0, icp = 0;   // wave-uniform; kept in scalar registers via readfirstlane
     bool overflow = false;
     uint32_t rounds = 0;
     WSTAT(unsigned st_sift = 0; unsigned st_settle = 0; unsigned st_press = 0; unsigned st_maxsp = 0; unsigned st_inter = 0;
@@ -212,9 +248,10 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
         const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
         mtot = __builtin_amdgcn_readfirstlane(mtot);
         const int nacc = __popcll(macc);
-        if (ic + nacc + mtot > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
-        if (acc) ilist[ic + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
-        ic = __builtin_amdgcn_readfirstlane(ic + nacc);
+        if (icc + nacc > WALK_CLIST) { drain_cells(clist, icc, x, y, fx, fy, z); icc = 0; }
+        if (acc) clist[icc + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
+        icc = __builtin_amdgcn_readfirstlane(icc + nacc);
+        if (icp + mtot > WALK_PLIST) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; }
         if (ofast) {
             float2 q[WALK_FAST_LEAF];
 #pragma unroll
@@ -222,9 +259,9 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
                 q[j] = Ys[min(cb.x + (uint32_t)j, (uint32_t)n - 1u)];
 #pragma unroll
             for (int j = 0; j < WALK_FAST_LEAF; ++j)
-                if ((uint32_t)j < cnt) ilist[ic + moff + j] = make_float4(q[j].x, q[j].y, 1.0f, 0.f);
+                if ((uint32_t)j < cnt) plist[icp + moff + j] = q[j];
         }
-        ic = __builtin_amdgcn_readfirstlane(ic + mtot);
+        icp = __builtin_amdgcn_readfirstlane(icp + mtot);
         // undecided cells wait for a full batch (only met in sift rounds, where np < 64)
         const uint64_t mund = __ballot(und);
         if (und) pend[np + __popcll(mund & lanemask_lt())] = id;
@@ -237,12 +274,9 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
             const uint32_t lo_b = __shfl(cb.x, b, WAVE), cnt_b = __shfl(cnt, b, WAVE);
             for (uint32_t j0 = 0; j0 < cnt_b; j0 += WAVE) {
                 const int m = (int)min((uint32_t)WAVE, cnt_b - j0);
-                if (ic + m > WALK_LIST) { drain(ilist, ic, x, y, fx, fy, z); ic = 0; }
-                if (lane < m) {
-                    const float2 q = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
-                    ilist[ic + lane] = make_float4(q.x, q.y, 1.0f, 0.f);
-                }
-                ic += m;
+                if (icp + m > WALK_PLIST) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; }
+                if (lane < m) plist[icp + lane] = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
+                icp += m;
             }
         }
         // children of rejected inner cells
@@ -263,9 +297,10 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
     }
     if (overflow) {
         if (lane == 0) atomicOr(status, TSNE_STATUS_WALK_OVERFLOW);
-        fx = fy = 0.f; z = 0.f; ic = 0;
+        fx = fy = 0.f; z = 0.f; icc = icp = 0;
     }
-    drain(ilist, ic, x, y, fx, fy, z);
+    drain_cells(clist, icc, x, y, fx, fy, z);
+    drain_points(plist, icp, x, y, fx, fy, z);
     WSTAT(if (lane == 0) {
         atomicAdd(&g_walk_stats[0], 1ull); atomicAdd(&g_walk_stats[1], (unsigned long long)st_sift);
         atomicAdd(&g_walk_stats[2], (unsigned long long)st_settle); atomicAdd(&g_walk_stats[3], (unsigned long long)st_press);
@@ -275,6 +310,40 @@ __global__ __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, 
     if (valid) R[min(perm[p], (uint32_t)n - 1u)] = make_float2(fx, fy);
     double zd = wave_sum(valid ? (double)z : 0.0);
     if (lane == 0) zpart[g] = zd;
+}
+
+// One wave per workgroup.  With a work counter the grid is a fixed number of resident waves that
+// take groups from the counter until none is left (every wave ends when the counter has passed
+// the number of groups); without one, workgroup g walks group g.
+__global__ __attribute__((amdgpu_waves_per_eu(5))) __launch_bounds__(WAVE) void bh_walk(const Cell *__restrict__ cells, const float2 *__restrict__ Ys,
+                                                const uint32_t *__restrict__ perm, int n,
+                                                const float4 *__restrict__ root, float theta2,
+                                                const uint32_t *__restrict__ ncells, uint32_t cap_cells,
+                                                float2 *__restrict__ R, double *__restrict__ zpart,
+                                                uint32_t *status, uint32_t *counter)
+{
+    __shared__ uint32_t stack[WALK_STACK];
+    __shared__ uint32_t pend[WALK_PEND];
+    __shared__ float2 pts[WAVE];
+    __shared__ float4 clist[WALK_CLIST];
+    __shared__ float2 plist[WALK_PLIST];
+    const int ngroups = (n + WAVE - 1) / WAVE;
+    if (!counter) {
+        walk_group((int)blockIdx.x, stack, pend, pts, clist, plist, cells, Ys, perm, n, root, theta2, ncells, cap_cells, R,
+                   zpart, status);
+        return;
+    }
+    __shared__ uint32_t next_group;
+    for (;;) {
+        // lane 0 draws the next group; every lane reads the same number back from LDS
+        __syncthreads();
+        if (threadIdx.x == 0) next_group = atomicAdd(counter, 1u);
+        __syncthreads();
+        const uint32_t g = (uint32_t)__builtin_amdgcn_readfirstlane((int)next_group);
+        if (g >= (uint32_t)ngroups) break;
+        walk_group((int)g, stack, pend, pts, clist, plist, cells, Ys, perm, n, root, theta2, ncells, cap_cells, R, zpart,
+                   status);
+    }
 }
 
 // Z = sum of the per-group partial sums, in a fixed order.
@@ -300,8 +369,13 @@ hipError_t launch_walk(tsne_ctx *c, hipStream_t s)
     const int n = c->p.n;
     const int ngroups = (n + WAVE - 1) / WAVE;
     const float theta2 = c->p.theta * c->p.theta;
-    hipLaunchKernelGGL(bh_walk, dim3(ngroups), dim3(WAVE), 0, s, c->cells, c->Ys, c->idx[c->sorted_buf], n, c->root,
-                       theta2, c->ncells, (uint32_t)c->cap_cells, c->R, c->zpart, c->status);
+    // walk_resident > 0: that many resident waves per compute unit share the groups through a
+    // counter (zeroed by the tree build), which leaves a known part of every unit to the attraction
+    const bool resident = c->p.walk_resident > 0 && ngroups > c->p.walk_resident * c->num_cu;
+    const int grid = resident ? c->p.walk_resident * c->num_cu : ngroups;
+    hipLaunchKernelGGL(bh_walk, dim3(grid), dim3(WAVE), 0, s, c->cells, c->Ys, c->idx[c->sorted_buf], n, c->root,
+                       theta2, c->ncells, (uint32_t)c->cap_cells, c->R, c->zpart, c->status,
+                       resident ? c->walk_counter : (uint32_t *)nullptr);
     hipLaunchKernelGGL(z_final, dim3(1), dim3(1024), 0, s, c->zpart, ngroups, c->Z);
     return hipGetLastError();
 }

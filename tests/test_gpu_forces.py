@@ -127,7 +127,8 @@ def test_renumbering_changes_nothing_but_the_layout():
     b.set_P(*P)
     Aa, Ra, Za = a.gradient(Y)
     Ab, Rb, Zb = b.gradient(Y)
-    assert torch.equal(Aa, Ab)       # same entries in the same order within every row
+    # same entries; a row is summed as (near part) + (far part) in the renumbered copy
+    assert rel_l2(Aa.cpu().numpy(), Ab.cpu().numpy()) <= 1e-6
     assert rel_l2(Ra.cpu().numpy(), Rb.cpu().numpy()) <= 1e-5
     assert abs(float(Za[0]) - float(Zb[0])) <= 1e-6 * float(Zb[0])
     ta, tb = a.export_tree(), b.export_tree()
@@ -187,7 +188,7 @@ def test_renumbered_context_small_and_empty_rows():
         Yd = torch.from_numpy(Y).to(dev)
         Aa, Ra, Za = t.gradient(Yd)
         Ab, Rb, Zb = ref.gradient(Yd)
-        assert torch.equal(Aa, Ab)
+        assert rel_l2(Aa.cpu().numpy(), Ab.cpu().numpy()) <= 1e-6
         assert rel_l2(Ra.cpu().numpy(), Rb.cpu().numpy()) <= 1e-5
         Y1 = Yd.clone()
         t.run(Y1, 7)
