@@ -86,6 +86,12 @@ typedef struct {
                                      that walk and attraction hold fixed shares of every compute unit; used
                                      when there are more groups than resident waves.  0 = one wave per group.
                                      (14) */
+    int32_t attract_early;        /* percent (0..90) of the attraction's streaming work that is started beside
+                                     the tree build by a quarter as many workgroups as there are compute
+                                     units; the rest runs beside the walk.  Only with overlap = 2.  The tree
+                                     kernels are latency-bound and slow down under any extra memory traffic
+                                     (measured: 0.24 -> 0.33 ms at 20 percent), so only the small far part
+                                     runs there by default.  (0) */
     int64_t max_nnz;              /* capacity for the private copy of P that renumbering needs: the workspace
                                      grows by 16 bytes per entry.  0 disables renumbering; P is then only
                                      borrowed and a stop/resume is bitwise reproducible. */
@@ -179,7 +185,7 @@ int tsne_kl(tsne_ctx *ctx, const float *d_Y, double *kl);
 
 /*
  * Per-phase GPU time of tsne_step, measured with HIP events recorded on the streams the kernels
- * run on.  tsne_timing_begin() arms the next max_steps calls of tsne_step (6 events per step);
+ * run on.  tsne_timing_begin() arms the next max_steps calls of tsne_step (9 events per step);
  * tsne_timing_end() synchronises, and returns the number of steps timed plus the mean milliseconds
  * per step of the four phases (any pointer may be NULL):
  *   ms[0] tree build (Sec. III-C steps 1-4)   ms[1] walk + Z (step 5)

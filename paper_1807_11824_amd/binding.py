@@ -28,7 +28,7 @@ class TsneParams(C.Structure):
                 ("momentum_switch_iter", C.c_int32), ("gain_inc", C.c_float), ("gain_dec", C.c_float),
                 ("gain_min", C.c_float), ("morton_bits", C.c_int32), ("leaf_cap", C.c_int32),
                 ("overlap", C.c_int32), ("graph_order_iters", C.c_int32), ("reorder_every", C.c_int32),
-                ("attract_resident", C.c_int32), ("walk_resident", C.c_int32),
+                ("attract_resident", C.c_int32), ("walk_resident", C.c_int32), ("attract_early", C.c_int32),
                 ("max_nnz", C.c_int64)]
 
 

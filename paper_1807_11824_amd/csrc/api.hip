@@ -102,6 +102,7 @@ int check_params(const tsne_params *p)
     if (p->reorder_every < 0 || p->graph_order_iters < 0 || p->graph_order_iters > 1000) return TSNE_EINVAL;
     if (p->attract_resident < 0 || p->attract_resident > 64) return TSNE_EINVAL;
     if (p->walk_resident < 0 || p->walk_resident > 32) return TSNE_EINVAL;
+    if (p->attract_early < 0 || p->attract_early > 90) return TSNE_EINVAL;
     if (p->max_nnz < 0 || p->max_nnz > 0x7FFFFFFFll) return TSNE_EINVAL;
     // the renumbered copy pads every row to whole chunks and is indexed with int32
     if (p->max_nnz > 0 && p->max_nnz + (ATTRACT_CHUNK - 1ll) * p->n + ATTRACT_SLACK > 0x7FFFFFFFll) return TSNE_EINVAL;
@@ -123,42 +124,63 @@ int fail(tsne_ctx *c, int code, const char *msg)
     return code;
 }
 
-// Forces at d_Y into c->A, c->R, c->Z.  The attractive kernel only needs Y and P, so with
-// overlap it runs on the second stream while the tree is built and walked on the first.
+// Events of one timed step: 0 start, 1 tree built, 2 walk done, 3 / 4 main part of the attraction,
+// 5 update done, 6 / 7 early part of the attraction, 8 update started.
+constexpr int NEV = 9;
+
+// Forces at d_Y into c->A, c->R, c->Z.  The attraction only needs Y and P, so with overlap it runs
+// on the second stream: overlap 1 from the gather on, 3 from the end of the sort, 2 (default) in
+// two pieces -- a small early piece beside the tree build (the tree kernels are short and
+// latency-bound, a few streaming workgroups do not slow them much) and the main piece beside the
+// walk, whose arithmetic and the attraction's memory traffic use different parts of the chip.
 int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
 {
     hipError_t e;
+    (void)d_Y;
     const bool two = c->p.overlap && c->stream2;
-    // where the attractive kernel is forked off: 1 = right after the gather (beside the whole tree
-    // build), 3 = after the sort (beside cell construction and walk), 2 = after the tree (beside the walk)
-    const int fork_at = c->p.overlap;
-    hipStream_t sa = two ? c->stream2 : c->stream;   // where the attractive kernel runs
-    auto fork_attract = [&]() -> int {
-        if ((e = hipEventRecord(c->ev_fork, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
-        if ((e = hipStreamWaitEvent(c->stream2, c->ev_fork, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
+    const int mode = c->p.overlap;
+    hipStream_t sa = two ? c->stream2 : c->stream;   // where the attraction runs
+    auto fork = [&](hipEvent_t evt) -> int {
+        if ((e = hipEventRecord(evt, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
+        if ((e = hipStreamWaitEvent(c->stream2, evt, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
+        return TSNE_OK;
+    };
+    auto early = [&]() -> int {
+        if (ev) (void)hipEventRecord(ev[6], sa);
+        if ((e = launch_attract_early(c, sa)) != hipSuccess) return fail_hip(c, e, "attract (early part)");
+        if (ev) (void)hipEventRecord(ev[7], sa);
+        return TSNE_OK;
+    };
+    auto mainpart = [&]() -> int {
         if (ev) (void)hipEventRecord(ev[3], sa);
-        if ((e = launch_attract(c, d_Y, sa)) != hipSuccess) return fail_hip(c, e, "attract");
+        if ((e = launch_attract_main(c, sa)) != hipSuccess) return fail_hip(c, e, "attract");
         if (ev) (void)hipEventRecord(ev[4], sa);
-        if ((e = hipEventRecord(c->ev_join, c->stream2)) != hipSuccess) return fail_hip(c, e, "event record");
+        if (two && (e = hipEventRecord(c->ev_join, c->stream2)) != hipSuccess) return fail_hip(c, e, "event record");
         return TSNE_OK;
     };
     int rc;
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     if ((e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
-    if (two && fork_at == 1 && (rc = fork_attract()) != TSNE_OK) return rc;
+    if (two && (mode == 1 || mode == 2)) {
+        if ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = early()) != TSNE_OK) return rc;
+        if (mode == 1 && (rc = mainpart()) != TSNE_OK) return rc;
+    }
     if ((e = launch_tree_sort(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree sort");
-    if (two && fork_at == 3 && (rc = fork_attract()) != TSNE_OK) return rc;
+    if (two && mode == 3 && ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = early()) != TSNE_OK || (rc = mainpart()) != TSNE_OK))
+        return rc;
     if ((e = launch_tree_cells(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree cells");
     if (ev) (void)hipEventRecord(ev[1], c->stream);
-    if (two && fork_at != 1 && fork_at != 3 && (rc = fork_attract()) != TSNE_OK) return rc;
+    if (two && mode != 1 && mode != 3) {
+        if (mode != 2 && ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = early()) != TSNE_OK)) return rc;
+        if (mode == 2 && (rc = fork(c->ev_fork2)) != TSNE_OK) return rc;
+        if ((rc = mainpart()) != TSNE_OK) return rc;
+    }
     if ((e = launch_walk(c, c->stream)) != hipSuccess) return fail_hip(c, e, "walk");
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     if (two) {
         if ((e = hipStreamWaitEvent(c->stream, c->ev_join, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
     } else {
-        if (ev) (void)hipEventRecord(ev[3], sa);
-        if ((e = launch_attract(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "attract");
-        if (ev) (void)hipEventRecord(ev[4], sa);
+        if ((rc = early()) != TSNE_OK || (rc = mainpart()) != TSNE_OK) return rc;
     }
     // Without renumbering, the attractive kernel of the NEXT call visits rows in this call's
     // spatial order (the kernel has finished by now on either stream, so the array is free to
@@ -192,7 +214,7 @@ int reset_slot_order(tsne_ctx *c)
 void free_timing(tsne_ctx *c)
 {
     if (!c->tev) return;
-    for (int i = 0; i < 6 * c->t_cap; ++i) if (c->tev[i]) (void)hipEventDestroy(c->tev[i]);
+    for (int i = 0; i < NEV * c->t_cap; ++i) if (c->tev[i]) (void)hipEventDestroy(c->tev[i]);
     free(c->tev);
     c->tev = nullptr;
     c->t_cap = c->t_used = 0;
@@ -224,6 +246,7 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->reorder_every = 0;
     p->attract_resident = 1;
     p->walk_resident = 14;
+    p->attract_early = 0;
     p->max_nnz = 0;
     return TSNE_OK;
 }
@@ -266,6 +289,7 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
         // default priority on purpose; non-blocking so that it does not serialise with stream 0
         if ((e = hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking)) != hipSuccess ||
             (e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&c->ev_fork2, hipEventDisableTiming)) != hipSuccess ||
             (e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming)) != hipSuccess) {
             tsne_destroy(c);
             return TSNE_EHIP;
@@ -288,6 +312,7 @@ void tsne_destroy(tsne_ctx *c)
     if (!c) return;
     if (c->stream2) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_fork2) (void)hipEventDestroy(c->ev_fork2);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     free_timing(c);
     delete c;
@@ -346,11 +371,12 @@ int tsne_step(tsne_ctx *c, float *d_Y, int32_t iter)
 {
     if (!c || !d_Y || iter < 0) return TSNE_EINVAL;
     if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_step: no P (call tsne_set_P first)");
-    hipEvent_t *ev = (c->tev && c->t_used < c->t_cap) ? c->tev + 6 * c->t_used : nullptr;
+    hipEvent_t *ev = (c->tev && c->t_used < c->t_cap) ? c->tev + NEV * c->t_used : nullptr;
     int rc = enqueue_forces(c, d_Y, ev);
     if (rc != TSNE_OK) return rc;
     const float alpha = iter < c->p.exaggeration_iters ? c->p.exaggeration : 1.0f;
     const float mom = iter < c->p.momentum_switch_iter ? c->p.momentum_early : c->p.momentum_late;
+    if (ev) (void)hipEventRecord(ev[8], c->stream);
     hipError_t e = launch_update(c, d_Y, alpha, mom, c->stream);
     if (ev) { (void)hipEventRecord(ev[5], c->stream); c->t_used += 1; }
     if (e != hipSuccess) return fail_hip(c, e, "update");
@@ -365,10 +391,10 @@ int tsne_timing_begin(tsne_ctx *c, int32_t max_steps)
 {
     if (!c || max_steps < 1 || max_steps > (1 << 20)) return TSNE_EINVAL;
     free_timing(c);
-    c->tev = (hipEvent_t *)calloc((size_t)6 * max_steps, sizeof(hipEvent_t));
+    c->tev = (hipEvent_t *)calloc((size_t)NEV * max_steps, sizeof(hipEvent_t));
     if (!c->tev) return TSNE_ENOSPC;
     c->t_cap = max_steps;
-    for (int i = 0; i < 6 * max_steps; ++i) {
+    for (int i = 0; i < NEV * max_steps; ++i) {
         hipError_t e = hipEventCreate(&c->tev[i]);
         if (e != hipSuccess) { free_timing(c); return fail_hip(c, e, "event create"); }
     }
@@ -383,13 +409,14 @@ int tsne_timing_end(tsne_ctx *c, int32_t *steps, float ms[4])
     if (e == hipSuccess && c->stream2) e = hipStreamSynchronize(c->stream2);
     if (e != hipSuccess) return fail_hip(c, e, "sync");
     double acc[4] = {0, 0, 0, 0};
-    static const int from[4] = {0, 1, 3, 2}, to[4] = {1, 2, 4, 5};
+    // tree, walk, attraction (main piece + early piece), update
+    static const int from[5] = {0, 1, 3, 8, 6}, to[5] = {1, 2, 4, 5, 7}, into[5] = {0, 1, 2, 3, 2};
     for (int s = 0; s < c->t_used; ++s)
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 5; ++q) {
             float t = 0.f;
-            e = hipEventElapsedTime(&t, c->tev[6 * s + from[q]], c->tev[6 * s + to[q]]);
+            e = hipEventElapsedTime(&t, c->tev[NEV * s + from[q]], c->tev[NEV * s + to[q]]);
             if (e != hipSuccess) { free_timing(c); return fail_hip(c, e, "event elapsed"); }
-            acc[q] += t;
+            acc[into[q]] += t;
         }
     if (steps) *steps = c->t_used;
     if (ms) for (int q = 0; q < 4; ++q) ms[q] = c->t_used ? (float)(acc[q] / c->t_used) : 0.f;

@@ -84,24 +84,29 @@ constexpr int AN_THREADS = 512, AN_ROWS = ATTRACT_ROWS, AN_S = ATTRACT_RING, AN_
 static_assert(AN_CH == 8 * AN_LPR, "a lane takes two quads of a chunk");
 constexpr int AN_PD = AN_PD_N, AN_GROUPS = AN_THREADS / AN_LPR;
 
-__global__ void attract_partition(const int32_t *__restrict__ rp_near, int n, int parts, int32_t *__restrict__ arow)
+// Shares of the rows for the resident workgroups: the first k1 workgroups (the part that runs
+// beside the tree build) split the first `early` percent of the work evenly, the other k2 split
+// the rest.  Work of rows [0, r) = their entries plus a fixed cost per row.
+__global__ void attract_partition(const int32_t *__restrict__ rp_near, int n, int k1, int k2, int early,
+                                  int32_t *__restrict__ arow)
 {
     const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (b > parts) return;
-    // weight of rows [0, r): their entries plus a fixed cost per row
+    if (b > k1 + k2) return;
     const int64_t total = (int64_t)rp_near[n] + 16ll * n;
-    const int64_t target = total * b / parts;
-    int lo = 0, hi = n;   // smallest r with weight(r) >= target
+    const int64_t cut = k1 > 0 ? total * early / 100 : 0;
+    const int64_t target = b < k1 ? cut * b / k1 : cut + (total - cut) * (b - k1) / k2;
+    int lo = 0, hi = n;   // smallest r with work(r) >= target
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
         if ((int64_t)rp_near[mid] + 16ll * mid >= target) hi = mid; else lo = mid + 1;
     }
-    arow[b] = b == parts ? n : lo;
+    arow[b] = b == k1 + k2 ? n : lo;
 }
 
 __global__ __attribute__((amdgpu_waves_per_eu(8))) __launch_bounds__(AN_THREADS) void
 attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, const float4 *__restrict__ val4,
-             const float2 *__restrict__ Y, int n, const int32_t *__restrict__ arow, float2 *__restrict__ A)
+             const float2 *__restrict__ Y, int n, const int32_t *__restrict__ arow, int share0,
+             float2 *__restrict__ A)
 {
     __shared__ float2 ring[AN_S];
     __shared__ float2 aout[AN_ROWS];
@@ -111,7 +116,8 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
     __shared__ uint16_t order[AN_ROWS];
     static_assert(AN_ROWS <= 65536, "rows per step");
     constexpr int KPT = (AN_ROWS + AN_THREADS - 1) / AN_THREADS;
-    const int rb = min(max(arow[blockIdx.x], 0), n), re = min(max(arow[blockIdx.x + 1], rb), n);
+    const int share = share0 + (int)blockIdx.x;
+    const int rb = min(max(arow[share], 0), n), re = min(max(arow[share + 1], rb), n);
     if (rb >= re) return;
     const int tid = (int)threadIdx.x, sub = tid % AN_LPR, grp = tid / AN_LPR;
     const char *ringb = reinterpret_cast<const char *>(ring);
@@ -122,7 +128,10 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
     int prev_r0 = 0, prev_rows = 0;
     for (int r0 = rb; r0 < re; r0 += AN_ROWS) {
         __syncthreads();   // the previous rows are finished: aout is complete, ring slots may be reused
-        for (int t = tid; t < prev_rows; t += AN_THREADS) A[prev_r0 + t] = aout[t];
+        for (int t = tid; t < prev_rows; t += AN_THREADS) {   // the far part is already there
+            const float2 a = A[prev_r0 + t], b = aout[t];
+            A[prev_r0 + t] = make_float2(a.x + b.x, a.y + b.y);
+        }
         for (int t = tid; t < AN_ROWS; t += AN_THREADS) {
             const int i = r0 + ATTRACT_BAND + t;
             if (i < n) ring[(unsigned)i % AN_S] = Y[i];
@@ -245,10 +254,14 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
         prev_rows = rows;
     }
     __syncthreads();
-    for (int t = tid; t < prev_rows; t += AN_THREADS) A[prev_r0 + t] = aout[t];
+    for (int t = tid; t < prev_rows; t += AN_THREADS) {
+        const float2 a = A[prev_r0 + t], b = aout[t];
+        A[prev_r0 + t] = make_float2(a.x + b.x, a.y + b.y);
+    }
 }
 
-// The far part: eight lanes per row, y_j gathered from memory; adds to what attract_near left.
+// The far part: eight lanes per row, y_j gathered from memory.  Runs first and writes every row
+// (zero where a row has no far entries); attract_near adds its sums afterwards.
 __global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
                                                    const float *__restrict__ val, const float2 *__restrict__ Y, int n,
                                                    float2 *__restrict__ A)
@@ -257,61 +270,77 @@ __global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ r
     const int sub = (int)(threadIdx.x % 8);
     int s = 0, e = 0;
     if (row < n) { s = rp[row]; e = rp[row + 1]; }
-    if (!__any(s < e)) return;
-    const int far0 = rp[0];      // values sit behind the near part, columns start at 0
     float ax = 0.f, ay = 0.f;
-    if (s < e) {
-        const float2 yi = Y[row];
-        for (int j0 = s + sub; j0 < e; j0 += 8 * 4) {
-            int c[4];
-            float v[4];
-            float2 yj[4];
+    if (__any(s < e)) {
+        const int far0 = rp[0];      // values sit behind the near part, columns start at 0
+        if (s < e) {
+            const float2 yi = Y[row];
+            for (int j0 = s + sub; j0 < e; j0 += 8 * 4) {
+                int c[4];
+                float v[4];
+                float2 yj[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int j = j0 + 8 * q;
-                const bool in = j < e;
-                c[q] = in ? col[j - far0] : row;
-                v[q] = in ? val[j] : 0.f;
-            }
+                for (int q = 0; q < 4; ++q) {
+                    const int j = j0 + 8 * q;
+                    const bool in = j < e;
+                    c[q] = in ? col[j - far0] : row;
+                    v[q] = in ? val[j] : 0.f;
+                }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
+                for (int q = 0; q < 4; ++q) yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
-                const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
-                const float pw = v[q] * w;
-                ax = fmaf(pw, dx, ax);
-                ay = fmaf(pw, dy, ay);
+                for (int q = 0; q < 4; ++q) {
+                    const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
+                    const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+                    const float pw = v[q] * w;
+                    ax = fmaf(pw, dx, ax);
+                    ay = fmaf(pw, dy, ay);
+                }
             }
         }
+        ax = sum8(ax);
+        ay = sum8(ay);
     }
-#pragma unroll
-    for (int o = 4; o > 0; o >>= 1) {
-        ax += __shfl_xor(ax, o, WAVE);
-        ay += __shfl_xor(ay, o, WAVE);
-    }
-    if (s < e && sub == 0) {
-        const float2 a = A[row];
-        A[row] = make_float2(a.x + ax, a.y + ay);
-    }
+    if (row < n && sub == 0) A[row] = make_float2(ax, ay);
 }
 
-hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s)
+// share-out of the rows (once per P), then the part of the attraction that may run early
+static void attract_shares(const tsne_ctx *c, int *k1, int *k2)
 {
     const int n = c->p.n;
-    (void)d_Y;
+    const int per_cu = c->p.attract_resident > 0 ? c->p.attract_resident : 1;
+    const int tiles = (n + AN_ROWS - 1) / AN_ROWS;
+    *k2 = max(1, min(min(per_cu * c->num_cu, ATTRACT_MAX_PARTS / 2), tiles));
+    *k1 = c->p.attract_early > 0 ? max(1, min(c->num_cu / 4, tiles)) : 0;
+}
+
+hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s)
+{
+    const int n = c->p.n;
+    if (!(c->reorder_on && !c->identity)) return hipSuccess;
+    int k1, k2;
+    attract_shares(c, &k1, &k2);
+    if (!c->arow_valid) {   // P changed since the rows were shared out
+        hipLaunchKernelGGL(attract_partition, dim3((k1 + k2 + 256) / 256), dim3(256), 0, s, c->rp_near, n, k1, k2,
+                           c->p.attract_early, c->arow);
+        c->arow_valid = 1;
+    }
+    hipLaunchKernelGGL(attract_far, dim3((unsigned)(((int64_t)n * 8 + 255) / 256)), dim3(256), 0, s, c->rp_far,
+                       c->col_far, c->val_s, c->Yi, n, c->A);
+    if (k1 > 0)
+        hipLaunchKernelGGL(attract_near, dim3(k1), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
+                           (const float4 *)c->val_s, c->Yi, n, c->arow, 0, c->A);
+    return hipGetLastError();
+}
+
+hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s)
+{
+    const int n = c->p.n;
     if (c->reorder_on && !c->identity) {
-        const int per_cu = c->p.attract_resident > 0 ? c->p.attract_resident : 2;
-        const int parts = max(1, min(min(per_cu * c->num_cu, ATTRACT_MAX_PARTS), (n + AN_ROWS - 1) / AN_ROWS));
-        if (!c->arow_valid) {   // P changed since the rows were shared out
-            hipLaunchKernelGGL(attract_partition, dim3((parts + 256) / 256), dim3(256), 0, s, c->rp_near, n, parts,
-                               c->arow);
-            c->arow_valid = 1;
-        }
-        hipLaunchKernelGGL(attract_near, dim3(parts), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
-                           (const float4 *)c->val_s, c->Yi, n, c->arow, c->A);
-        hipLaunchKernelGGL(attract_far, dim3((unsigned)(((int64_t)n * 8 + 255) / 256)), dim3(256), 0, s, c->rp_far,
-                           c->col_far, c->val_s, c->Yi, n, c->A);
+        int k1, k2;
+        attract_shares(c, &k1, &k2);
+        hipLaunchKernelGGL(attract_near, dim3(k2), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
+                           (const float4 *)c->val_s, c->Yi, n, c->arow, k1, c->A);
     } else {
         const unsigned blocks = (unsigned)(((int64_t)n * AW_LPR + 255) / 256);
         hipLaunchKernelGGL((attract_csr<AW_LPR, AW_U>), dim3(blocks), dim3(256), 0, s, c->user_row_ptr, c->user_col,

@@ -652,19 +652,31 @@ __global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ 
 }
 
 // First position x in [lo, n) with (keys[x] >> sh) >= target, n if none (keys sorted).
-__device__ __forceinline__ uint32_t shifted_lower_bound(const uint32_t *__restrict__ keys, uint32_t lo, uint32_t n,
-                                                        int sh, uint64_t target)
+// First position i in [lo, n) with (keys[i] >> sh) >= target (n if there is none), found by the
+// whole wave: every round the 64 lanes probe 64 evenly spaced positions of the remaining range,
+// which shrinks 64-fold, so four rounds cover any n.  All lanes must call with the same
+// arguments; every probed index lies inside [lo, n) whatever the keys hold.
+__device__ __forceinline__ uint32_t wave_shifted_lower_bound(const uint32_t *__restrict__ keys, uint32_t lo, uint32_t n,
+                                                             int sh, uint64_t target)
 {
     uint32_t hi = n;
+    const uint32_t lane = (uint32_t)lane_id();
     while (lo < hi) {
-        const uint32_t mid = lo + ((hi - lo) >> 1);
-        if ((uint64_t)(keys[mid] >> sh) < target) lo = mid + 1; else hi = mid;
+        const uint32_t step = (hi - lo + 63u) >> 6;
+        const uint64_t probe = (uint64_t)lo + (uint64_t)(lane + 1u) * step - 1ull;
+        bool below = false;
+        if (probe < (uint64_t)hi) below = (uint64_t)(keys[probe] >> sh) < target;
+        const uint32_t c = (uint32_t)__popcll(__ballot(below));   // the keys are sorted: lanes 0..c-1
+        const uint64_t top = (uint64_t)lo + (uint64_t)(c + 1u) * step - 1ull;
+        lo += c * step;
+        hi = top < (uint64_t)hi ? (uint32_t)top : hi;
     }
     return lo;
 }
 
-// Four lanes per listed cell: lane 0 finds the end of the cell, lanes 1-3 the first position of
-// quadrants 1-3 among its points (all four are lower bounds in the globally sorted keys).
+// One workgroup per listed cell, one wave per search: wave 0 finds the end of the cell, waves
+// 1-3 the first position of quadrants 1-3 among its points (all four are lower bounds in the
+// globally sorted keys).
 __global__ __launch_bounds__(256) void write_big_cells(const uint32_t *__restrict__ keys, const uint16_t *__restrict__ lev,
                                                        const uint32_t *__restrict__ cellseq,
                                                        const double2 *__restrict__ ps, int n, int B, int C,
@@ -672,59 +684,60 @@ __global__ __launch_bounds__(256) void write_big_cells(const uint32_t *__restric
                                                        const uint32_t *__restrict__ big_count,
                                                        const uint2 *__restrict__ big_list, uint32_t big_cap)
 {
-    const uint32_t item = (blockIdx.x * 256u + threadIdx.x) >> 2;
-    const int role = (int)(threadIdx.x & 3u);
+    __shared__ uint32_t found_s[4];
+    const int role = (int)(threadIdx.x >> 6);
     const uint32_t m = min(*big_count, big_cap);
-    const bool live = item < m;
-    uint32_t p = 0;
-    int t = 0;
-    if (live) { const uint2 it = big_list[item]; p = it.x; t = (int)it.y; }
-    const uint32_t key = live ? keys[p] : 0u;
-    uint32_t found = (uint32_t)n;
-    if (live) {
+    for (uint32_t item = blockIdx.x; item < m; item += gridDim.x) {
+        const uint2 it = big_list[item];
+        const uint32_t p = min(it.x, (uint32_t)n - 1u);
+        const int t = min((int)it.y, B);
+        const uint32_t key = keys[p];
+        uint32_t found = (uint32_t)n;
         if (role == 0) {
             if (t > 0) {
                 const int sh = 2 * (B - t);
-                found = shifted_lower_bound(keys, p, (uint32_t)n, sh, (uint64_t)(key >> sh) + 1ull);
+                found = wave_shifted_lower_bound(keys, p, (uint32_t)n, sh, (uint64_t)(key >> sh) + 1ull);
             }
         } else if (t < B) {
             const int sh = 2 * (B - t - 1);
             const uint64_t parent = t > 0 ? (uint64_t)(key >> (2 * (B - t))) : 0ull;
-            found = shifted_lower_bound(keys, p, (uint32_t)n, sh, (parent << 2) + (uint64_t)role);
+            found = wave_shifted_lower_bound(keys, p, (uint32_t)n, sh, (parent << 2) + (uint64_t)role);
         }
+        if (lane_id() == 0) found_s[role] = found;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t e = found_s[0];
+            const uint32_t b1 = min(found_s[1], e), b2 = min(found_s[2], e), b3 = min(found_s[3], e);
+            const uint32_t l = lev[p];
+            const uint32_t id = cellseq[p] + (uint32_t)(t - (int)(l & 0xFFu));
+            if (id < cap_cells) {
+                const uint32_t cnt = e - p;
+                const double2 s0 = ps[p], s1 = ps[e];
+                Cell c;
+                c.cx = (float)((s1.x - s0.x) / (double)cnt);
+                c.cy = (float)((s1.y - s0.y) / (double)cnt);
+                c.cnt = cnt;
+                const bool leaf = cnt <= (uint32_t)C || t == B;
+                c.meta = (uint32_t)t | (leaf ? 0x100u : 0u);
+                c.lo = p;
+                c.c1 = c.c2 = c.c3 = TSNE_NONE;
+                if (!leaf) {
+                    // quadrant q > first quadrant exists iff its first position precedes the next boundary
+                    const uint32_t qfirst = (key >> (2 * (B - t - 1))) & 3u;
+                    const uint32_t bnd[5] = {p, b1, b2, b3, e};
+                    uint32_t kids[3];
+                    int nk = 0;
+                    for (uint32_t q = qfirst + 1; q < 4; ++q)
+                        if (bnd[q] < bnd[q + 1]) kids[nk++] = cellseq[bnd[q]];
+                    if (nk > 0) c.c1 = kids[0];
+                    if (nk > 1) c.c2 = kids[1];
+                    if (nk > 2) c.c3 = kids[2];
+                }
+                cells[id] = c;
+            }
+        }
+        __syncthreads();
     }
-    const int base = (int)(threadIdx.x & 63u) & ~3;
-    const uint32_t e = __shfl(found, base, WAVE);
-    const uint32_t b1 = min(__shfl(found, base + 1, WAVE), e);
-    const uint32_t b2 = min(__shfl(found, base + 2, WAVE), e);
-    const uint32_t b3 = min(__shfl(found, base + 3, WAVE), e);
-    if (!live || role != 0) return;
-    const uint32_t l = lev[p];
-    const uint32_t id = cellseq[p] + (uint32_t)(t - (int)(l & 0xFFu));
-    if (id >= cap_cells) return;
-    const uint32_t cnt = e - p;
-    const double2 s0 = ps[p], s1 = ps[e];
-    Cell c;
-    c.cx = (float)((s1.x - s0.x) / (double)cnt);
-    c.cy = (float)((s1.y - s0.y) / (double)cnt);
-    c.cnt = cnt;
-    const bool leaf = cnt <= (uint32_t)C || t == B;
-    c.meta = (uint32_t)t | (leaf ? 0x100u : 0u);
-    c.lo = p;
-    c.c1 = c.c2 = c.c3 = TSNE_NONE;
-    if (!leaf) {
-        // quadrant q > first quadrant exists iff its first position precedes the next boundary
-        const uint32_t qfirst = (key >> (2 * (B - t - 1))) & 3u;
-        const uint32_t bnd[5] = {p, b1, b2, b3, e};
-        uint32_t kids[3];
-        int nk = 0;
-        for (uint32_t q = qfirst + 1; q < 4; ++q)
-            if (bnd[q] < bnd[q + 1]) kids[nk++] = cellseq[bnd[q]];
-        if (nk > 0) c.c1 = kids[0];
-        if (nk > 1) c.c2 = kids[1];
-        if (nk > 2) c.c3 = kids[2];
-    }
-    cells[id] = c;
 }
 
 // ------------------------------------------------------------------ export (tests only)
@@ -819,7 +832,7 @@ hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s)
     hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, c->keys[cur], c->cellseq, c->ps, c->cell_p, c->cell_t,
                        c->ncells, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
                        (uint32_t)c->big_cap);
-    hipLaunchKernelGGL(write_big_cells, dim3((c->big_cap * 4 + 255) / 256), dim3(256), 0, s, c->keys[cur], c->lev,
+    hipLaunchKernelGGL(write_big_cells, dim3(4096), dim3(256), 0, s, c->keys[cur], c->lev,
                        c->cellseq, c->ps, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
                        (uint32_t)c->big_cap);
     return hipGetLastError();

@@ -50,7 +50,7 @@ struct tsne_ctx {
     hipStream_t stream;
     hipStream_t stream2;
     int num_cu;                    // compute units of the current device
-    hipEvent_t ev_fork, ev_join;
+    hipEvent_t ev_fork, ev_fork2, ev_join;
     int have_P, tree_valid;
     // P in the caller's numbering (borrowed)
     const int32_t *user_row_ptr, *user_col;
@@ -109,7 +109,8 @@ hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s);
 hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);
 hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
-hipError_t launch_attract(tsne_ctx *c, const float *d_Y, hipStream_t s);
+hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s);
+hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s);
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s);
 hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in idx[sorted_buf]
@@ -178,15 +179,19 @@ __device__ __forceinline__ float sum4(float v)
 // value of the first lane of every aligned group of four lanes
 __device__ __forceinline__ int first4(int v) { return dpp_i<0x00>(v); }
 
-// Exclusive prefix sum over the 64 lanes; *total receives the wave sum.
+// Exclusive prefix sum over the 64 lanes; *total receives the wave sum.  All lanes must be
+// active.  Log-step shifts inside every row of 16 lanes (0x111, 0x112, 0x114, 0x118: shift right
+// by 1, 2, 4, 8 with zero fill), then the last lane of a row is added to the next row (0x142,
+// rows 1 and 3) and lane 31 to the upper half (0x143, rows 2 and 3).
 __device__ __forceinline__ int wave_excl_scan(int v, int *total)
 {
     int inc = v;
-#pragma unroll
-    for (int o = 1; o < WAVE; o <<= 1) {
-        int t = __shfl_up(inc, o, WAVE);
-        if (lane_id() >= o) inc += t;
-    }
-    *total = __shfl(inc, WAVE - 1, WAVE);
+    inc += __builtin_amdgcn_update_dpp(0, inc, 0x111, 0xF, 0xF, true);
+    inc += __builtin_amdgcn_update_dpp(0, inc, 0x112, 0xF, 0xF, true);
+    inc += __builtin_amdgcn_update_dpp(0, inc, 0x114, 0xF, 0xF, true);
+    inc += __builtin_amdgcn_update_dpp(0, inc, 0x118, 0xF, 0xF, true);
+    inc += __builtin_amdgcn_update_dpp(0, inc, 0x142, 0xA, 0xF, false);
+    inc += __builtin_amdgcn_update_dpp(0, inc, 0x143, 0xC, 0xF, false);
+    *total = __builtin_amdgcn_readlane(inc, WAVE - 1);
     return inc - v;
 }

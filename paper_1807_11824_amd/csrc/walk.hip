@@ -346,14 +346,12 @@ __global__ __attribute__((amdgpu_waves_per_eu(5))) __launch_bounds__(WAVE) void 
     }
 }
 
-// Z = sum of the per-group partial sums, in a fixed order.
+// Z = sum of the per-group partial sums, in a fixed order (thread t takes groups t, t + 1024, ...).
 __global__ __launch_bounds__(1024) void z_final(const double *__restrict__ zpart, int ngroups, double *__restrict__ Z)
 {
     __shared__ double ws[16];
     double a = 0.0;
-    const int per = (ngroups + 1023) / 1024;
-    const int s = threadIdx.x * per, e = min(ngroups, s + per);
-    for (int i = s; i < e; ++i) a += zpart[i];
+    for (int i = (int)threadIdx.x; i < ngroups; i += 1024) a += zpart[i];
     a = wave_sum(a);
     if (lane_id() == 0) ws[threadIdx.x >> 6] = a;
     __syncthreads();
