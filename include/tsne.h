@@ -92,9 +92,12 @@ typedef struct {
                                      kernels are latency-bound and slow down under any extra memory traffic
                                      (measured: 0.24 -> 0.33 ms at 20 percent), so only the small far part
                                      runs there by default.  (0) */
-    int64_t max_nnz;              /* capacity for the private copy of P that renumbering needs: the workspace
-                                     grows by 16 bytes per entry.  0 disables renumbering; P is then only
-                                     borrowed and a stop/resume is bitwise reproducible. */
+    int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
+                                     10 bytes per entry plus 186 bytes per point (rows are padded).  0 disables
+                                     renumbering; P is then only borrowed and a stop/resume is bitwise
+                                     reproducible.  With renumbering a row of the attractive sum is added up
+                                     as (entries near the diagonal) + (the others): deterministic, equal to
+                                     the plain order up to rounding. */
 } tsne_params;
 
 typedef struct tsne_ctx tsne_ctx; /* opaque, host side, owned by the library */

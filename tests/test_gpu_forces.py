@@ -194,3 +194,66 @@ def test_renumbered_context_small_and_empty_rows():
         t.run(Y1, 7)
         assert t.status() == 0 and torch.isfinite(Y1).all()
     t.close(); ref.close()
+
+
+def _banded_csr(n, k, band, far_every, seed):
+    """Symmetric CSR whose entries lie within `band` of the diagonal, plus a long-range pair for every
+    `far_every`-th row: the structure a renumbered kNN matrix has (near part + sparse far remainder)."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(seed)
+    rows = np.repeat(np.arange(n), k)
+    cols = rows + rng.integers(-band, band + 1, size=n * k)
+    keep = (cols >= 0) & (cols < n) & (cols != rows)
+    rows, cols = rows[keep], cols[keep]
+    fr = np.arange(0, n, far_every)
+    fc = rng.integers(0, n, size=fr.size)
+    ok = fr != fc
+    rows = np.concatenate([rows, fr[ok]]); cols = np.concatenate([cols, fc[ok]])
+    w = rng.random(rows.size) + 0.1
+    M = sp.coo_matrix((w, (rows, cols)), shape=(n, n)).tocsr()
+    M = M + M.T
+    M.sum_duplicates(); M.sort_indices()
+    M = M / M.sum()
+    return M.indptr.astype(np.int32), M.indices.astype(np.int32), M.data.astype(np.float32)
+
+
+def test_near_and_far_parts_against_the_oracle():
+    """Renumbered copy of a banded P: the streaming kernel over the near part (several window steps, several
+    workgroups, rows of very different lengths incl. empty ones) and the far remainder, against the oracle."""
+    n = 70_001
+    rp, col, val = _banded_csr(n, 24, 900, 7, seed=11)
+    # a few hub rows (long) and empty rows
+    import scipy.sparse as sp
+    M = sp.csr_matrix((val, col, rp), shape=(n, n)).tolil()
+    for i in (3, 4000, 65_000):
+        M[i, :] = 0
+        M[:, i] = 0
+    M = M.tocsr(); M.eliminate_zeros(); M.sort_indices()
+    rp, col, val = M.indptr.astype(np.int32), M.indices.astype(np.int32), M.data.astype(np.float32)
+    Y = synth.clustered_embedding(n, n_clusters=80, seed=12)
+    A, R, Z, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4)
+    assert st == 0
+    Ao = oracle.attract(Y, rp, col, val.astype(np.float64))
+    assert rel_l2(A, Ao) <= 1e-6
+    # the same through the plain kernel (no renumbering): equal up to the order of the additions
+    A2, R2, Z2, st2 = _gpu_forces(Y, rp, col, val)
+    assert st2 == 0 and rel_l2(A, A2) <= 1e-6
+    assert np.array_equal(R, R2) or rel_l2(R, R2) <= 1e-6
+
+
+def test_launch_shapes_change_nothing():
+    """Stream layout (overlap 0-3), resident or one-wave-per-group walk, share of the attraction started early:
+    every output of tsne_gradient is bitwise the same."""
+    import torch
+    n = 300_007            # more groups than 14 resident waves on each of 256 compute units
+    rp, col, val = _banded_csr(n, 12, 700, 11, seed=21)
+    Y = synth.clustered_embedding(n, n_clusters=300, seed=22)
+    ref = None
+    for params in (dict(overlap=0, walk_resident=0), dict(overlap=2), dict(overlap=1, walk_resident=0),
+                   dict(overlap=3, walk_resident=6), dict(overlap=2, attract_early=35, attract_resident=2)):
+        A, R, Z, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, **params)
+        assert st == 0
+        if ref is None:
+            ref = (A, R, Z)
+        else:
+            assert np.array_equal(A, ref[0]) and np.array_equal(R, ref[1]) and Z == ref[2], params
