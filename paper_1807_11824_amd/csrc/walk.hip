@@ -266,17 +266,35 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
         const uint64_t mund = __ballot(und);
         if (und) pend[np + __popcll(mund & lanemask_lt())] = id;
         np = __builtin_amdgcn_readfirstlane(np + __popcll(mund));
-        // large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF): one at a time
-        uint64_t mbig = __ballot(open && !ofast);
-        while (mbig) {
-            const int b = __ffsll((long long)mbig) - 1;
-            mbig &= mbig - 1;
-            const uint32_t lo_b = __shfl(cb.x, b, WAVE), cnt_b = __shfl(cnt, b, WAVE);
-            for (uint32_t j0 = 0; j0 < cnt_b; j0 += WAVE) {
-                const int m = (int)min((uint32_t)WAVE, cnt_b - j0);
-                if (icp + m > WALK_PLIST) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; }
-                if (lane < m) plist[icp + lane] = Ys[min(lo_b + j0 + lane, (uint32_t)n - 1u)];
-                icp += m;
+        // Large leaves (only at the maximum depth, or when leaf_cap > WALK_FAST_LEAF).  Their members
+        // are consecutive positions; the lanes copy the concatenation of all of them, 64 points a
+        // step: a prefix sum gives every leaf its offset, and lane t finds its leaf as the last
+        // lane whose offset is <= t (other lanes have empty segments, which the search skips).
+        const bool big = open && !ofast;
+        if (__any(big)) {
+            int tbig;
+            // (leaves of one round are different cells, so their sizes add up to at most n)
+            const int boff = wave_excl_scan(big ? (int)cnt : 0, &tbig);
+            tbig = __builtin_amdgcn_readfirstlane(tbig);
+            for (int base = 0; base < tbig;) {
+                if (WALK_PLIST - icp < WAVE) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; }
+                const int take = min(tbig - base, WALK_PLIST - icp);
+                for (int k = 0; k < take; k += WAVE) {
+                    const int t = base + k + lane;
+                    const int tt = min(t, tbig - 1);
+                    int owner = 0;
+#pragma unroll
+                    for (int s = WAVE / 2; s > 0; s >>= 1) {
+                        const int c = owner + s;            // < 64: owner + s never passes 63
+                        if (__shfl(boff, c, WAVE) <= tt) owner = c;
+                    }
+                    const uint32_t first = __shfl(cb.x, owner, WAVE);
+                    const int ooff = __shfl(boff, owner, WAVE);
+                    if (t < base + take)
+                        plist[icp + k + lane] = Ys[min(first + (uint32_t)(tt - ooff), (uint32_t)n - 1u)];
+                }
+                icp = __builtin_amdgcn_readfirstlane(icp + take);
+                base += take;
             }
         }
         // children of rejected inner cells
