@@ -62,7 +62,7 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     q = take(4 * (size_t)cap);                       if (c) c->cell_p = (uint32_t *)q;
     q = take((size_t)cap);                           if (c) c->cell_t = (uint8_t *)q;
     const int32_t big_cap = (int32_t)(n / 8 + 1024);
-    q = take(2 * sizeof(uint32_t));                  if (c) { c->big_count = (uint32_t *)q; c->walk_counter = c->big_count + 1; }
+    q = take((1 + WALK_COUNTERS) * sizeof(uint32_t));                  if (c) { c->big_count = (uint32_t *)q; c->walk_counter = c->big_count + 1; }
     q = take(sizeof(uint2) * (size_t)big_cap);       if (c) { c->big_list = (uint2 *)q; c->big_cap = big_cap; }
     q = take(8 * n);                                 if (c) c->R = (float2 *)q;
     q = take(8 * n);                                 if (c) c->A = (float2 *)q;

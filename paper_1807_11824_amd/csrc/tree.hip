@@ -471,8 +471,8 @@ __global__ __launch_bounds__(1024) void scan_partials(ScanPart *__restrict__ par
 {
     if (threadIdx.x == 0) {
         big_count[0] = 0u;    // list of large cells filled by write_cells
-        big_count[1] = 0u;    // work counter of the walk
     }
+    if (threadIdx.x < WALK_COUNTERS) big_count[1 + threadIdx.x] = 0u;    // work counters of the walk
     __shared__ double wx[16], wy[16];
     __shared__ uint32_t wc[16];
     const int tid = threadIdx.x, w = tid >> 6;

@@ -34,6 +34,7 @@ constexpr int LEVEL_THREADS = 256;
 constexpr int LEVEL_ITEMS = 4;
 constexpr int LEVEL_TILE = LEVEL_THREADS * LEVEL_ITEMS;
 constexpr int BBOX_MAX_BLOCKS = 1024;
+constexpr int WALK_COUNTERS = 16;        // work counters of the resident walk (a power of two)
 constexpr int ATTRACT_BAND = 1280;       // half width of the near part of the renumbered P
 #ifndef ATTRACT_ROWS_N
 #define ATTRACT_ROWS_N 512

@@ -351,16 +351,24 @@ __global__ __attribute__((amdgpu_waves_per_eu(5))) __launch_bounds__(WAVE) void 
                    zpart, status);
         return;
     }
+    // The first group of a wave is its workgroup number; further groups come from counters.
+    // (All waves start together: if each began with a draw, thousands of atomics on one address
+    // would queue up and the last wave would start tens of microseconds late.)  Same-address
+    // atomics are served one after the other, about one every 20 ns, which 20 000 draws in a
+    // third of a millisecond would saturate: the groups are dealt into WALK_COUNTERS classes
+    // (group mod WALK_COUNTERS), each with its own counter and its own share of the waves.
+    // The grid is a multiple of WALK_COUNTERS, so every class has grid / WALK_COUNTERS waves.
     __shared__ uint32_t next_group;
-    for (;;) {
-        // lane 0 draws the next group; every lane reads the same number back from LDS
-        __syncthreads();
-        if (threadIdx.x == 0) next_group = atomicAdd(counter, 1u);
-        __syncthreads();
-        const uint32_t g = (uint32_t)__builtin_amdgcn_readfirstlane((int)next_group);
-        if (g >= (uint32_t)ngroups) break;
+    const uint32_t cls = blockIdx.x % WALK_COUNTERS, dealt = gridDim.x / WALK_COUNTERS;
+    uint32_t g = blockIdx.x;
+    while (g < (uint32_t)ngroups) {
         walk_group((int)g, stack, pend, pts, clist, plist, cells, Ys, perm, n, root, theta2, ncells, cap_cells, R, zpart,
                    status);
+        // lane 0 draws the next group of the class; every lane reads the number back from LDS
+        __syncthreads();
+        if (threadIdx.x == 0) next_group = cls + WALK_COUNTERS * (dealt + atomicAdd(counter + cls, 1u));
+        __syncthreads();
+        g = (uint32_t)__builtin_amdgcn_readfirstlane((int)next_group);
     }
 }
 
@@ -387,8 +395,9 @@ hipError_t launch_walk(tsne_ctx *c, hipStream_t s)
     const float theta2 = c->p.theta * c->p.theta;
     // walk_resident > 0: that many resident waves per compute unit share the groups through a
     // counter (zeroed by the tree build), which leaves a known part of every unit to the attraction
-    const bool resident = c->p.walk_resident > 0 && ngroups > c->p.walk_resident * c->num_cu;
-    const int grid = resident ? c->p.walk_resident * c->num_cu : ngroups;
+    const bool resident = c->p.walk_resident > 0 && ngroups > c->p.walk_resident * c->num_cu &&
+                          c->p.walk_resident * c->num_cu >= WALK_COUNTERS;
+    const int grid = resident ? c->p.walk_resident * c->num_cu / WALK_COUNTERS * WALK_COUNTERS : ngroups;
     hipLaunchKernelGGL(bh_walk, dim3(grid), dim3(WAVE), 0, s, c->cells, c->Ys, c->idx[c->sorted_buf], n, c->root,
                        theta2, c->ncells, (uint32_t)c->cap_cells, c->R, c->zpart, c->status,
                        resident ? c->walk_counter : (uint32_t *)nullptr);
