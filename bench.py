@@ -107,16 +107,17 @@ def main():
     Yd = torch.from_numpy(Y0).to(dev)
     ts = Tsne(n, overlap=args.overlap, leaf_cap=args.leaf_cap, max_nnz=nnz)
     ts.set_P(P["row_ptr"], P["col"], P["val"])
+    # one tsne_run call per region: inside a run the library keeps the embedding in its own order
+    # from one iteration to the next (the caller's Y is still written every iteration)
     it = 0
-    for _ in range(args.warmup):
-        ts.step(Yd, it)
-        it += 1
+    if args.warmup:
+        ts.run(Yd, args.warmup, iter0=it)
+        it += args.warmup
     torch.cuda.synchronize()
     ts.timing_begin(args.steps)
     t0 = time.time()
-    for _ in range(args.steps):
-        ts.step(Yd, it)
-        it += 1
+    ts.run(Yd, args.steps, iter0=it)
+    it += args.steps
     torch.cuda.synchronize()
     dt = time.time() - t0
     tm = ts.timing_end()

@@ -2,6 +2,8 @@
 // order in which the kernels of one iteration are enqueued (Alg. 1 lines 3-9).
 #include "tsne_internal.h"
 
+#include <algorithm>
+
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -41,7 +43,8 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     const size_t nblk_lev = (n + LEVEL_TILE - 1) / LEVEL_TILE;
     const size_t ngroups = (n + WAVE - 1) / WAVE;
     void *q;
-    q = take(sizeof(float4) * 2 * BBOX_MAX_BLOCKS); if (c) c->bbox_part = (float4 *)q;
+    const size_t nbox = std::max<size_t>(BBOX_MAX_BLOCKS, (n + 255) / 256);
+    q = take(sizeof(float4) * 2 * nbox);             if (c) c->bbox_part = (float4 *)q;
     q = take(sizeof(float4));                        if (c) c->root = (float4 *)q;
     q = take(sizeof(uint32_t));                      if (c) c->status = (uint32_t *)q;
     q = take(sizeof(uint32_t));                      if (c) c->ncells = (uint32_t *)q;
@@ -133,10 +136,9 @@ constexpr int NEV = 9;
 // two pieces -- a small early piece beside the tree build (the tree kernels are short and
 // latency-bound, a few streaming workgroups do not slow them much) and the main piece beside the
 // walk, whose arithmetic and the attraction's memory traffic use different parts of the chip.
-int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
+int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev, bool cached = false)
 {
     hipError_t e;
-    (void)d_Y;
     const bool two = c->p.overlap && c->stream2;
     const int mode = c->p.overlap;
     hipStream_t sa = two ? c->stream2 : c->stream;   // where the attraction runs
@@ -160,7 +162,8 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev)
     };
     int rc;
     if (ev) (void)hipEventRecord(ev[0], c->stream);
-    if ((e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
+    // (inside tsne_run the previous update has already left Y in slot order and its bounding box)
+    if (!cached && (e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
     if (two && (mode == 1 || mode == 2)) {
         if ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = early()) != TSNE_OK) return rc;
         if (mode == 1 && (rc = mainpart()) != TSNE_OK) return rc;
@@ -367,24 +370,37 @@ int tsne_set_state(tsne_ctx *c, const float *d_velocity, const float *d_gains)
     return TSNE_OK;
 }
 
-int tsne_step(tsne_ctx *c, float *d_Y, int32_t iter)
+namespace {
+// One iteration.  cached: Yi / the bounding box were left by the previous call's update (same Y,
+// untouched since); keep: leave them for the next call.
+int step_impl(tsne_ctx *c, float *d_Y, int32_t iter, bool cached, bool keep)
 {
-    if (!c || !d_Y || iter < 0) return TSNE_EINVAL;
-    if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_step: no P (call tsne_set_P first)");
     hipEvent_t *ev = (c->tev && c->t_used < c->t_cap) ? c->tev + NEV * c->t_used : nullptr;
-    int rc = enqueue_forces(c, d_Y, ev);
+    const bool use = cached && c->yi_fresh;
+    c->yi_fresh = 0;
+    int rc = enqueue_forces(c, d_Y, ev, use);
     if (rc != TSNE_OK) return rc;
     const float alpha = iter < c->p.exaggeration_iters ? c->p.exaggeration : 1.0f;
     const float mom = iter < c->p.momentum_switch_iter ? c->p.momentum_early : c->p.momentum_late;
     if (ev) (void)hipEventRecord(ev[8], c->stream);
-    hipError_t e = launch_update(c, d_Y, alpha, mom, c->stream);
+    hipError_t e = launch_update(c, d_Y, alpha, mom, keep ? 1 : 0, c->stream);
     if (ev) { (void)hipEventRecord(ev[5], c->stream); c->t_used += 1; }
     if (e != hipSuccess) return fail_hip(c, e, "update");
+    c->yi_fresh = keep ? 1 : 0;
     if (c->reorder_on && c->p.reorder_every > 0 && ++c->steps_since_reorder >= c->p.reorder_every) {
         c->steps_since_reorder = 0;
+        c->yi_fresh = 0;      // the slots are renumbered: Yi is stale
         if ((e = launch_reorder(c, c->stream)) != hipSuccess) return fail_hip(c, e, "reorder");
     }
     return TSNE_OK;
+}
+}  // namespace
+
+int tsne_step(tsne_ctx *c, float *d_Y, int32_t iter)
+{
+    if (!c || !d_Y || iter < 0) return TSNE_EINVAL;
+    if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_step: no P (call tsne_set_P first)");
+    return step_impl(c, d_Y, iter, false, false);
 }
 
 int tsne_timing_begin(tsne_ctx *c, int32_t max_steps)
@@ -435,10 +451,14 @@ int tsne_status(tsne_ctx *c, uint32_t *status)
 int tsne_run(tsne_ctx *c, float *d_Y, int32_t iter0, int32_t n_iter)
 {
     if (!c || !d_Y || iter0 < 0 || n_iter < 0) return TSNE_EINVAL;
+    if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_run: no P (call tsne_set_P first)");
+    // Between the iterations of one call nobody else touches Y, so every update hands the next
+    // iteration the embedding in slot order and its bounding box.
     for (int32_t it = iter0; it < iter0 + n_iter; ++it) {
-        int rc = tsne_step(c, d_Y, it);
-        if (rc != TSNE_OK) return rc;
+        int rc = step_impl(c, d_Y, it, it > iter0, it + 1 < iter0 + n_iter);
+        if (rc != TSNE_OK) { c->yi_fresh = 0; return rc; }
     }
+    c->yi_fresh = 0;
     uint32_t st = 0;
     int rc = tsne_status(c, &st);
     if (rc != TSNE_OK) return rc;

@@ -355,36 +355,62 @@ hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s)
 // y += velocity.
 __device__ __forceinline__ int sign3(float v) { return v > 0.f ? 1 : (v < 0.f ? -1 : 0); }
 
-__global__ __launch_bounds__(256) void update_k(float2 *__restrict__ Y, const uint32_t *__restrict__ orig,
-                                                const float2 *__restrict__ Yi, float2 *__restrict__ uY,
-                                                float2 *__restrict__ gains, const float2 *__restrict__ A,
-                                                const float2 *__restrict__ R, const double *__restrict__ Z, int n,
-                                                float alpha, float momentum, float lr, float gain_inc, float gain_dec,
-                                                float gain_min)
+// With `part` set the kernel also leaves what the next iteration starts from: the new point in
+// slot order (Yi) and the workgroup's bounding box, so that a run of several iterations neither
+// gathers Y again nor makes a separate pass for the box (Sec. III-C step 1).
+__global__ __launch_bounds__(256) void update_k(float2 *__restrict__ Y, const uint32_t *__restrict__ orig, float2 *Yi,
+                                                float2 *__restrict__ uY, float2 *__restrict__ gains,
+                                                const float2 *__restrict__ A, const float2 *__restrict__ R,
+                                                const double *__restrict__ Z, int n, float alpha, float momentum,
+                                                float lr, float gain_inc, float gain_dec, float gain_min,
+                                                float4 *__restrict__ part, uint32_t *status)
 {
     const int s = blockIdx.x * blockDim.x + threadIdx.x;
-    if (s >= n) return;
-    const float invZ = (float)(1.0 / *Z);
-    const float2 a = A[s], r = R[s];
-    float2 g = gains[s], u = uY[s], y = Yi[s];
-    const float gx = 4.0f * (alpha * a.x - r.x * invZ), gy = 4.0f * (alpha * a.y - r.y * invZ);
-    g.x = (sign3(gx) != sign3(u.x)) ? g.x + gain_inc : g.x * gain_dec;
-    g.y = (sign3(gy) != sign3(u.y)) ? g.y + gain_inc : g.y * gain_dec;
-    g.x = fmaxf(g.x, gain_min); g.y = fmaxf(g.y, gain_min);
-    u.x = momentum * u.x - lr * g.x * gx;
-    u.y = momentum * u.y - lr * g.y * gy;
-    gains[s] = g;
-    uY[s] = u;
-    y.x += u.x; y.y += u.y;
-    Y[min(orig[s], (uint32_t)n - 1u)] = y;
+    const bool live = s < n;
+    float2 y = make_float2(0.f, 0.f);
+    if (live) {
+        const float invZ = (float)(1.0 / *Z);
+        const float2 a = A[s], r = R[s];
+        float2 g = gains[s], u = uY[s];
+        y = Yi[s];
+        const float gx = 4.0f * (alpha * a.x - r.x * invZ), gy = 4.0f * (alpha * a.y - r.y * invZ);
+        g.x = (sign3(gx) != sign3(u.x)) ? g.x + gain_inc : g.x * gain_dec;
+        g.y = (sign3(gy) != sign3(u.y)) ? g.y + gain_inc : g.y * gain_dec;
+        g.x = fmaxf(g.x, gain_min); g.y = fmaxf(g.y, gain_min);
+        u.x = momentum * u.x - lr * g.x * gx;
+        u.y = momentum * u.y - lr * g.y * gy;
+        gains[s] = g;
+        uY[s] = u;
+        y.x += u.x; y.y += u.y;
+        Y[min(orig[s], (uint32_t)n - 1u)] = y;
+    }
+    if (!part) return;
+    if (live) Yi[s] = y;
+    const bool bad = live && !(isfinite(y.x) && isfinite(y.y));
+    float mnx = wave_min(live ? y.x : INFINITY), mny = wave_min(live ? y.y : INFINITY);
+    float mxx = wave_max(live ? y.x : -INFINITY), mxy = wave_max(live ? y.y : -INFINITY);
+    __shared__ float4 smn[4], smx[4];
+    const int w = threadIdx.x >> 6;
+    if (lane_id() == 0) { smn[w] = make_float4(mnx, mny, 0, 0); smx[w] = make_float4(mxx, mxy, 0, 0); }
+    if (__any(bad) && lane_id() == 0) atomicOr(status, TSNE_STATUS_NONFINITE);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k) {
+            mnx = fminf(mnx, smn[k].x); mny = fminf(mny, smn[k].y);
+            mxx = fmaxf(mxx, smx[k].x); mxy = fmaxf(mxy, smx[k].y);
+        }
+        part[2 * blockIdx.x] = make_float4(mnx, mny, 0, 0);
+        part[2 * blockIdx.x + 1] = make_float4(mxx, mxy, 0, 0);
+    }
 }
 
-hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s)
+hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, hipStream_t s)
 {
-    const int n = c->p.n;
-    hipLaunchKernelGGL(update_k, dim3((n + 255) / 256), dim3(256), 0, s, (float2 *)d_Y, c->orig[c->cur_state], c->Yi,
+    const int n = c->p.n, nb = (n + 255) / 256;
+    hipLaunchKernelGGL(update_k, dim3(nb), dim3(256), 0, s, (float2 *)d_Y, c->orig[c->cur_state], c->Yi,
                        c->uYb[c->cur_state], c->gainsb[c->cur_state], c->A, c->R, c->Z, n, alpha, momentum, c->p.lr,
-                       c->p.gain_inc, c->p.gain_dec, c->p.gain_min);
+                       c->p.gain_inc, c->p.gain_dec, c->p.gain_min, keep ? c->bbox_part : (float4 *)nullptr, c->status);
+    if (keep) c->bbox_nparts = nb;
     return hipGetLastError();
 }
 

@@ -795,6 +795,7 @@ hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s)
     const int n = c->p.n;
     hipLaunchKernelGGL(bbox_partial, dim3(bbox_blocks(n)), dim3(256), 0, s, (const float2 *)d_Y,
                        c->orig[c->cur_state], c->Yi, n, c->bbox_part, c->status);
+    c->bbox_nparts = bbox_blocks(n);
     return hipGetLastError();
 }
 
@@ -803,8 +804,8 @@ hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
 {
     const int n = c->p.n, B = c->p.morton_bits;
     const float2 *Y = c->Yi;
-    const int nb = (n + 255) / 256, bb = bbox_blocks(n);
-    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(256), 0, s, c->bbox_part, bb, B, c->root, c->status);
+    const int nb = (n + 255) / 256;
+    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(256), 0, s, c->bbox_part, c->bbox_nparts, B, c->root, c->status);
     hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],
                        c->idx[0]);
     return launch_sort(c, 2 * B, s);

@@ -72,7 +72,9 @@ struct tsne_ctx {
     float *val_s;
     float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
-    float4 *bbox_part;   // [BBOX_MAX_BLOCKS*2]  (min, max) pairs
+    float4 *bbox_part;   // (min, max) pairs of the bounding box, one per workgroup of the kernel that made them
+    int bbox_nparts;     // how many pairs are valid
+    int yi_fresh;        // Yi and bbox_part already hold the embedding of the next step (left by update_k)
     float4 *root;        // x0, y0, W, S
     uint32_t *status;    // device status word
     uint32_t *ncells;    // device cell count
@@ -112,7 +114,7 @@ hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);
 hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s);
-hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, hipStream_t s);
+hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, hipStream_t s);
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s);
 hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in idx[sorted_buf]
 hipError_t launch_sort(tsne_ctx *c, int nbits, hipStream_t s);  // sorts keys[0]/idx[0]; result in [sorted_buf]

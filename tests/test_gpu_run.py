@@ -133,3 +133,32 @@ def test_call_order_errors():
     with pytest.raises(TsneError):
         t.timing_end()
     t.close()
+
+
+def test_run_equals_repeated_steps_bitwise():
+    """tsne_run keeps the embedding in slot order between its iterations (the update writes it together with
+    the bounding box); the trajectory must be the one repeated tsne_step calls give, bit for bit."""
+    import torch
+    from paper_1807_11824_amd import Tsne, build_P
+    dev = torch.device("cuda:0")
+    X, _ = synth.gaussian_mixture(6000, 16, 12, 6.0, 1.0, seed=3)
+    P = build_P(torch.from_numpy(X).to(dev), 20.0, 60)
+    for kw in (dict(), dict(max_nnz=P["nnz"]), dict(max_nnz=P["nnz"], reorder_every=4)):
+        a = Tsne(6000, **kw); b = Tsne(6000, **kw)
+        for t in (a, b):
+            t.set_P(P["row_ptr"], P["col"], P["val"])
+        Ya = torch.from_numpy(synth.y0(6000, seed=9)).to(dev); Yb = Ya.clone()
+        a.run(Ya, 13)
+        for it in range(13):
+            b.step(Yb, it)
+        assert torch.equal(Ya, Yb), kw
+        ua, ga = a.get_state(); ub, gb = b.get_state()
+        assert torch.equal(ua, ub) and torch.equal(ga, gb), kw
+        # a second run continues from the caller's Y (which the caller may have changed in between)
+        Ya += 0.5; Yb += 0.5
+        a.run(Ya, 5, iter0=13)
+        for it in range(13, 18):
+            b.step(Yb, it)
+        assert torch.equal(Ya, Yb), kw
+        assert a.status() == 0 and b.status() == 0
+        a.close(); b.close()
