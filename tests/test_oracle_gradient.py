@@ -71,7 +71,10 @@ def test_force_decomposition_matches_eq3(small_problem):
     assert np.linalg.norm(r["grad"] - want) <= 1e-12 * np.linalg.norm(want)
     # exaggeration multiplies the attractive term only
     r12 = oracle.grad_exact(Y, P["row_ptr"], P["col"], P["val"], alpha=12.0)
-    assert np.allclose(r12["grad"], 4.0 * (12.0 * r["A"] - r["R"] / Z), rtol=1e-13, atol=0)
+    # (compared in the norm: single components of 12 A - R / Z cancel almost completely, and the oracle's
+    #  Z is a parallel sum whose last bits depend on the thread schedule)
+    want12 = 4.0 * (12.0 * r["A"] - r["R"] / Z)
+    assert np.linalg.norm(r12["grad"] - want12) <= 1e-12 * np.linalg.norm(want12)
 
 
 def test_net_force_is_zero(small_problem):
