@@ -65,6 +65,7 @@ def lib():
         "tsne_kl": (C.c_int, [vp, vp, C.POINTER(C.c_double)]),
         "tsne_status": (C.c_int, [vp, C.POINTER(C.c_uint32)]),
         "tsne_timing_begin": (C.c_int, [vp, i32]),
+        "tsne_timing_begin_every": (C.c_int, [vp, i32, i32]),
         "tsne_timing_end": (C.c_int, [vp, C.POINTER(i32), C.POINTER(C.c_float)]),
         "tsne_strerror": (C.c_char_p, [C.c_int]),
         "tsne_last_error": (C.c_char_p, [vp]),
@@ -235,8 +236,8 @@ class Tsne:
         self._check(self.L.tsne_kl(self._ctx, _ptr(Y), C.byref(v)), "tsne_kl")
         return v.value
 
-    def timing_begin(self, max_steps):
-        self._check(self.L.tsne_timing_begin(self._ctx, max_steps), "tsne_timing_begin")
+    def timing_begin(self, max_steps, every=1):
+        self._check(self.L.tsne_timing_begin_every(self._ctx, max_steps, every), "tsne_timing_begin_every")
 
     def timing_end(self):
         steps = C.c_int32(0)

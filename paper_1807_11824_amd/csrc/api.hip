@@ -84,6 +84,9 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
         q = take(4 * n); if (c) c->len_far = (int32_t *)q;
         q = take(4 * (n + 1)); if (c) c->rp_near = (int32_t *)q;
         q = take(4 * (n + 1)); if (c) c->rp_far = (int32_t *)q;
+        q = take(4 * n);       if (c) c->far_rows = (uint32_t *)q;
+        q = take(4);           if (c) c->far_count = (uint32_t *)q;
+        q = take(8 * n);       if (c) c->Afar = (float2 *)q;
         q = take(2 * ms);      if (c) c->col_near = (uint16_t *)q;
         q = take(4 * (m + ATTRACT_SLACK)); if (c) c->col_far = (int32_t *)q;
         q = take(4 * ms);      if (c) c->val_s = (float *)q;
@@ -375,7 +378,8 @@ namespace {
 // untouched since); keep: leave them for the next call.
 int step_impl(tsne_ctx *c, float *d_Y, int32_t iter, bool cached, bool keep)
 {
-    hipEvent_t *ev = (c->tev && c->t_used < c->t_cap) ? c->tev + NEV * c->t_used : nullptr;
+    hipEvent_t *ev = nullptr;      // timed steps: every t_every-th one while slots are left
+    if (c->tev && c->t_used < c->t_cap && (c->t_seen++ % c->t_every) == 0) ev = c->tev + NEV * c->t_used;
     const bool use = cached && c->yi_fresh;
     c->yi_fresh = 0;
     int rc = enqueue_forces(c, d_Y, ev, use);
@@ -403,10 +407,14 @@ int tsne_step(tsne_ctx *c, float *d_Y, int32_t iter)
     return step_impl(c, d_Y, iter, false, false);
 }
 
-int tsne_timing_begin(tsne_ctx *c, int32_t max_steps)
+int tsne_timing_begin(tsne_ctx *c, int32_t max_steps) { return tsne_timing_begin_every(c, max_steps, 1); }
+
+int tsne_timing_begin_every(tsne_ctx *c, int32_t max_steps, int32_t every)
 {
-    if (!c || max_steps < 1 || max_steps > (1 << 20)) return TSNE_EINVAL;
+    if (!c || max_steps < 1 || max_steps > (1 << 20) || every < 1) return TSNE_EINVAL;
     free_timing(c);
+    c->t_every = every;
+    c->t_seen = 0;
     c->tev = (hipEvent_t *)calloc((size_t)NEV * max_steps, sizeof(hipEvent_t));
     if (!c->tev) return TSNE_ENOSPC;
     c->t_cap = max_steps;

@@ -106,7 +106,7 @@ __global__ void attract_partition(const int32_t *__restrict__ rp_near, int n, in
 __global__ __attribute__((amdgpu_waves_per_eu(8))) __launch_bounds__(AN_THREADS) void
 attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, const float4 *__restrict__ val4,
              const float2 *__restrict__ Y, int n, const int32_t *__restrict__ arow, int share0,
-             float2 *__restrict__ A)
+             const int32_t *__restrict__ rp_far, const float2 *__restrict__ Afar, float2 *__restrict__ A)
 {
     __shared__ float2 ring[AN_S];
     __shared__ float2 aout[AN_ROWS];
@@ -128,9 +128,11 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
     int prev_r0 = 0, prev_rows = 0;
     for (int r0 = rb; r0 < re; r0 += AN_ROWS) {
         __syncthreads();   // the previous rows are finished: aout is complete, ring slots may be reused
-        for (int t = tid; t < prev_rows; t += AN_THREADS) {   // the far part is already there
-            const float2 a = A[prev_r0 + t], b = aout[t];
-            A[prev_r0 + t] = make_float2(a.x + b.x, a.y + b.y);
+        for (int t = tid; t < prev_rows; t += AN_THREADS) {   // near sum + far sum (where the row has a far part)
+            const int r = prev_r0 + t;
+            float2 a = aout[t];
+            if (rp_far[r + 1] > rp_far[r]) { const float2 b = Afar[r]; a.x += b.x; a.y += b.y; }
+            A[r] = a;
         }
         for (int t = tid; t < AN_ROWS; t += AN_THREADS) {
             const int i = r0 + ATTRACT_BAND + t;
@@ -255,55 +257,63 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
     }
     __syncthreads();
     for (int t = tid; t < prev_rows; t += AN_THREADS) {
-        const float2 a = A[prev_r0 + t], b = aout[t];
-        A[prev_r0 + t] = make_float2(a.x + b.x, a.y + b.y);
+        const int r = prev_r0 + t;
+        float2 a = aout[t];
+        if (rp_far[r + 1] > rp_far[r]) { const float2 b = Afar[r]; a.x += b.x; a.y += b.y; }
+        A[r] = a;
     }
 }
 
-// The far part: eight lanes per row, y_j gathered from memory.  Runs first and writes every row
-// (zero where a row has no far entries); attract_near adds its sums afterwards.
+// The far part: sixteen lanes per listed row (the rows that have far entries, about one in seven
+// on the benchmark workload), y_j gathered from memory.  Runs first, beside the tree build;
+// attract_near adds the sums to its own.
 __global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
                                                    const float *__restrict__ val, const float2 *__restrict__ Y, int n,
-                                                   float2 *__restrict__ A)
+                                                   const uint32_t *__restrict__ far_rows,
+                                                   const uint32_t *__restrict__ far_count, float2 *__restrict__ Afar)
 {
-    const int row = (int)((blockIdx.x * 256u + threadIdx.x) / 8);
-    const int sub = (int)(threadIdx.x % 8);
-    int s = 0, e = 0;
-    if (row < n) { s = rp[row]; e = rp[row + 1]; }
-    float ax = 0.f, ay = 0.f;
-    if (__any(s < e)) {
-        const int far0 = rp[0];      // values sit behind the near part, columns start at 0
-        if (s < e) {
-            const float2 yi = Y[row];
-            for (int j0 = s + sub; j0 < e; j0 += 8 * 4) {
-                int c[4];
-                float v[4];
-                float2 yj[4];
+    const int sub = (int)(threadIdx.x % 16);
+    const uint32_t m = min(*far_count, (uint32_t)n);
+    const int far0 = rp[0];      // values sit behind the near part, columns start at 0
+    for (uint32_t i = (blockIdx.x * 256u + threadIdx.x) / 16; i < m; i += gridDim.x * 16u) {
+        const int row = (int)min(far_rows[i], (uint32_t)n - 1u);
+        const int s = rp[row], e = rp[row + 1];
+        const float2 yi = Y[row];
+        float ax = 0.f, ay = 0.f;
+        for (int j0 = s + sub; j0 < e; j0 += 16 * 4) {
+            int c[4];
+            float v[4];
+            float2 yj[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int j = j0 + 8 * q;
-                    const bool in = j < e;
-                    c[q] = in ? col[j - far0] : row;
-                    v[q] = in ? val[j] : 0.f;
-                }
+            for (int q = 0; q < 4; ++q) {
+                const int j = j0 + 16 * q;
+                const bool in = j < e;
+                c[q] = in ? col[j - far0] : row;
+                v[q] = in ? val[j] : 0.f;
+            }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
+            for (int q = 0; q < 4; ++q) yj[q] = Y[min((uint32_t)c[q], (uint32_t)n - 1u)];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
-                    const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
-                    const float pw = v[q] * w;
-                    ax = fmaf(pw, dx, ax);
-                    ay = fmaf(pw, dy, ay);
-                }
+            for (int q = 0; q < 4; ++q) {
+                const float dx = yi.x - yj[q].x, dy = yi.y - yj[q].y;
+                const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+                const float pw = v[q] * w;
+                ax = fmaf(pw, dx, ax);
+                ay = fmaf(pw, dy, ay);
             }
         }
-        ax = sum8(ax);
-        ay = sum8(ay);
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {
+            ax += __shfl_xor(ax, o, WAVE);
+            ay += __shfl_xor(ay, o, WAVE);
+        }
+        if (sub == 0) Afar[row] = make_float2(ax, ay);
     }
-    if (row < n && sub == 0) A[row] = make_float2(ax, ay);
 }
 
+#ifndef FAR_BLOCKS
+#define FAR_BLOCKS 1024
+#endif
 // share-out of the rows (once per P), then the part of the attraction that may run early
 static void attract_shares(const tsne_ctx *c, int *k1, int *k2)
 {
@@ -325,11 +335,11 @@ hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s)
                            c->p.attract_early, c->arow);
         c->arow_valid = 1;
     }
-    hipLaunchKernelGGL(attract_far, dim3((unsigned)(((int64_t)n * 8 + 255) / 256)), dim3(256), 0, s, c->rp_far,
-                       c->col_far, c->val_s, c->Yi, n, c->A);
+    hipLaunchKernelGGL(attract_far, dim3((unsigned)min((n + 15) / 16, FAR_BLOCKS)), dim3(256), 0, s, c->rp_far, c->col_far,
+                       c->val_s, c->Yi, n, c->far_rows, c->far_count, c->Afar);
     if (k1 > 0)
         hipLaunchKernelGGL(attract_near, dim3(k1), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
-                           (const float4 *)c->val_s, c->Yi, n, c->arow, 0, c->A);
+                           (const float4 *)c->val_s, c->Yi, n, c->arow, 0, c->rp_far, c->Afar, c->A);
     return hipGetLastError();
 }
 
@@ -340,7 +350,7 @@ hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s)
         int k1, k2;
         attract_shares(c, &k1, &k2);
         hipLaunchKernelGGL(attract_near, dim3(k2), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
-                           (const float4 *)c->val_s, c->Yi, n, c->arow, k1, c->A);
+                           (const float4 *)c->val_s, c->Yi, n, c->arow, k1, c->rp_far, c->Afar, c->A);
     } else {
         const unsigned blocks = (unsigned)(((int64_t)n * AW_LPR + 255) / 256);
         hipLaunchKernelGGL((attract_csr<AW_LPR, AW_U>), dim3(blocks), dim3(256), 0, s, c->user_row_ptr, c->user_col,

@@ -28,6 +28,8 @@ __global__ __launch_bounds__(256) void reorder_state_k(const uint32_t *__restric
     inv[o] = (uint32_t)p;
 }
 
+__global__ void zero_word_k(uint32_t *w) { *w = 0u; }
+
 __device__ __forceinline__ bool in_band(uint32_t col_slot, int row_slot)
 {
     const int d = (int)col_slot - row_slot;
@@ -38,7 +40,8 @@ __device__ __forceinline__ bool in_band(uint32_t col_slot, int row_slot)
 __global__ __launch_bounds__(256) void split_count_k(const uint32_t *__restrict__ orig, const uint32_t *__restrict__ inv,
                                                      int n, const int32_t *__restrict__ urp,
                                                      const int32_t *__restrict__ ucol, int32_t *__restrict__ len_near,
-                                                     int32_t *__restrict__ len_far)
+                                                     int32_t *__restrict__ len_far, uint32_t *__restrict__ far_rows,
+                                                     uint32_t *__restrict__ far_count)
 {
     const int p = (int)((blockIdx.x * 256u + threadIdx.x) / 16);
     const int sub = (int)(threadIdx.x % 16);
@@ -55,6 +58,7 @@ __global__ __launch_bounds__(256) void split_count_k(const uint32_t *__restrict_
     if (p < n && sub == 0) {
         len_near[p] = (near + ATTRACT_CHUNK - 1) / ATTRACT_CHUNK * ATTRACT_CHUNK;     // padded to whole chunks
         len_far[p] = len - near;
+        if (len > near) far_rows[atomicAdd(far_count, 1u)] = (uint32_t)p;   // any order will do
     }
 }
 
@@ -138,8 +142,9 @@ hipError_t launch_reorder(tsne_ctx *c, hipStream_t s)
     hipLaunchKernelGGL(reorder_state_k, dim3((n + 255) / 256), dim3(256), 0, s, perm, n, c->orig[a], c->orig[b],
                        c->uYb[a], c->uYb[b], c->gainsb[a], c->gainsb[b], c->inv);
     const unsigned blocks = (unsigned)(((int64_t)n * 16 + 255) / 256);
+    hipLaunchKernelGGL(zero_word_k, dim3(1), dim3(1), 0, s, c->far_count);
     hipLaunchKernelGGL(split_count_k, dim3(blocks), dim3(256), 0, s, c->orig[b], c->inv, n, c->user_row_ptr, c->user_col,
-                       c->len_near, c->len_far);
+                       c->len_near, c->len_far, c->far_rows, c->far_count);
     hipLaunchKernelGGL(scan_len_k, dim3(1), dim3(1024), 0, s, c->len_near, n, (const int32_t *)nullptr, c->rp_near);
     hipLaunchKernelGGL(scan_len_k, dim3(1), dim3(1024), 0, s, c->len_far, n, (const int32_t *)(c->rp_near + n), c->rp_far);
     hipLaunchKernelGGL(split_fill_k, dim3(blocks), dim3(256), 0, s, c->orig[b], c->inv, n, c->user_row_ptr, c->user_col,

@@ -53,8 +53,8 @@ __global__ __launch_bounds__(256) void bbox_partial(const float2 *__restrict__ Y
 
 // Root square: lower corner (min x, min y); side = smallest power of two >= the larger extent,
 // at least 2^-40; scale S = 2^bits / side (an exact power of two).
-__global__ __launch_bounds__(256) void bbox_final(const float4 *__restrict__ part, int nparts, int bits,
-                                                  float4 *__restrict__ root, uint32_t *status)
+__global__ __launch_bounds__(1024) void bbox_final(const float4 *__restrict__ part, int nparts, int bits,
+                                                   float4 *__restrict__ root, uint32_t *status)
 {
     float mnx = INFINITY, mny = INFINITY, mxx = -INFINITY, mxy = -INFINITY;
     for (int i = threadIdx.x; i < nparts; i += blockDim.x) {
@@ -63,12 +63,12 @@ __global__ __launch_bounds__(256) void bbox_final(const float4 *__restrict__ par
         mxx = fmaxf(mxx, b.x); mxy = fmaxf(mxy, b.y);
     }
     mnx = wave_min(mnx); mny = wave_min(mny); mxx = wave_max(mxx); mxy = wave_max(mxy);
-    __shared__ float4 smn[4], smx[4];
-    int w = threadIdx.x >> 6;
+    __shared__ float4 smn[16], smx[16];
+    const int w = threadIdx.x >> 6, nw = (int)(blockDim.x >> 6);
     if (lane_id() == 0) { smn[w] = make_float4(mnx, mny, 0, 0); smx[w] = make_float4(mxx, mxy, 0, 0); }
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int k = 1; k < 4; ++k) {
+        for (int k = 1; k < nw; ++k) {
             mnx = fminf(mnx, smn[k].x); mny = fminf(mny, smn[k].y);
             mxx = fmaxf(mxx, smx[k].x); mxy = fmaxf(mxy, smx[k].y);
         }
@@ -805,7 +805,8 @@ hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
     const int n = c->p.n, B = c->p.morton_bits;
     const float2 *Y = c->Yi;
     const int nb = (n + 255) / 256;
-    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(256), 0, s, c->bbox_part, c->bbox_nparts, B, c->root, c->status);
+    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(c->bbox_nparts > 1024 ? 1024 : 256), 0, s, c->bbox_part, c->bbox_nparts, B,
+                       c->root, c->status);
     hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],
                        c->idx[0]);
     return launch_sort(c, 2 * B, s);

@@ -53,6 +53,7 @@ struct tsne_ctx {
     int num_cu;                    // compute units of the current device
     hipEvent_t ev_fork, ev_fork2, ev_join;
     int have_P, tree_valid;
+    int t_every, t_seen;           // timing: every t_every-th step is timed; steps seen since timing began
     // P in the caller's numbering (borrowed)
     const int32_t *user_row_ptr, *user_col;
     const float *user_val;
@@ -69,6 +70,8 @@ struct tsne_ctx {
     // (8 (column mod ATTRACT_RING)); far columns are slot numbers, col_far[j - rp_far[0]].
     int32_t *rp_near, *rp_far, *col_far, *len_near, *len_far;
     uint16_t *col_near;
+    uint32_t *far_rows, *far_count;   // the rows that have a far part (any order), and how many
+    float2 *Afar;                     // their far sums, by row
     float *val_s;
     float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
