@@ -157,7 +157,10 @@ int tsne_set_state(tsne_ctx *ctx, const float *d_velocity, const float *d_gains)
 int tsne_step(tsne_ctx *ctx, float *d_Y, int32_t iter);
 
 /* Alg. 1 lines 3-9: n_iter steps starting at iteration iter0; then synchronises and returns
- * TSNE_ENUM if the device reported trouble. */
+ * TSNE_ENUM if the device reported trouble.  The result equals n_iter calls of tsne_step bit for bit.
+ * Between the iterations of one call the library works from its own copy of the embedding, so d_Y is
+ * read at the start, holds the final embedding on return, and is unspecified in between (and after an
+ * error). */
 int tsne_run(tsne_ctx *ctx, float *d_Y, int32_t iter0, int32_t n_iter);
 
 /*

@@ -387,7 +387,10 @@ int step_impl(tsne_ctx *c, float *d_Y, int32_t iter, bool cached, bool keep)
     const float alpha = iter < c->p.exaggeration_iters ? c->p.exaggeration : 1.0f;
     const float mom = iter < c->p.momentum_switch_iter ? c->p.momentum_early : c->p.momentum_late;
     if (ev) (void)hipEventRecord(ev[8], c->stream);
-    hipError_t e = launch_update(c, d_Y, alpha, mom, keep ? 1 : 0, c->stream);
+    // an iteration whose successor reads the embedding from the library's own copy (keep) need not
+    // write the caller's array -- unless the slots are about to be renumbered, which starts from it
+    const bool renumber_next = c->reorder_on && c->p.reorder_every > 0 && c->steps_since_reorder + 1 >= c->p.reorder_every;
+    hipError_t e = launch_update(c, d_Y, alpha, mom, keep ? 1 : 0, (!keep || renumber_next) ? 1 : 0, c->stream);
     if (ev) { (void)hipEventRecord(ev[5], c->stream); c->t_used += 1; }
     if (e != hipSuccess) return fail_hip(c, e, "update");
     c->yi_fresh = keep ? 1 : 0;

@@ -373,7 +373,7 @@ __global__ __launch_bounds__(256) void update_k(float2 *__restrict__ Y, const ui
                                                 const float2 *__restrict__ A, const float2 *__restrict__ R,
                                                 const double *__restrict__ Z, int n, float alpha, float momentum,
                                                 float lr, float gain_inc, float gain_dec, float gain_min,
-                                                float4 *__restrict__ part, uint32_t *status)
+                                                float4 *__restrict__ part, uint32_t *status, int write_user)
 {
     const int s = blockIdx.x * blockDim.x + threadIdx.x;
     const bool live = s < n;
@@ -392,7 +392,8 @@ __global__ __launch_bounds__(256) void update_k(float2 *__restrict__ Y, const ui
         gains[s] = g;
         uY[s] = u;
         y.x += u.x; y.y += u.y;
-        Y[min(orig[s], (uint32_t)n - 1u)] = y;
+        // (inside a run of several iterations only the last one has to reach the caller's array)
+        if (write_user) Y[min(orig[s], (uint32_t)n - 1u)] = y;
     }
     if (!part) return;
     if (live) Yi[s] = y;
@@ -414,12 +415,13 @@ __global__ __launch_bounds__(256) void update_k(float2 *__restrict__ Y, const ui
     }
 }
 
-hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, hipStream_t s)
+hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, int write_user, hipStream_t s)
 {
     const int n = c->p.n, nb = (n + 255) / 256;
     hipLaunchKernelGGL(update_k, dim3(nb), dim3(256), 0, s, (float2 *)d_Y, c->orig[c->cur_state], c->Yi,
                        c->uYb[c->cur_state], c->gainsb[c->cur_state], c->A, c->R, c->Z, n, alpha, momentum, c->p.lr,
-                       c->p.gain_inc, c->p.gain_dec, c->p.gain_min, keep ? c->bbox_part : (float4 *)nullptr, c->status);
+                       c->p.gain_inc, c->p.gain_dec, c->p.gain_min, keep ? c->bbox_part : (float4 *)nullptr, c->status,
+                       write_user);
     if (keep) c->bbox_nparts = nb;
     return hipGetLastError();
 }

@@ -117,7 +117,8 @@ hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);
 hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s);
-hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, hipStream_t s);
+hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, int write_user,
+                         hipStream_t s);
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s);
 hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in idx[sorted_buf]
 hipError_t launch_sort(tsne_ctx *c, int nbits, hipStream_t s);  // sorts keys[0]/idx[0]; result in [sorted_buf]
