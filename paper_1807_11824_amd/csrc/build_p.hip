@@ -107,8 +107,9 @@ __device__ __forceinline__ void store_slab(float *__restrict__ S, const float4 v
 __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict__ X, int n, int d, int q0, int qend,
                                                      int j0, int jend, const float *__restrict__ norms,
                                                      const float *__restrict__ tau, int *__restrict__ cnt,
-                                                     uint64_t *__restrict__ cand, int cap)
+                                                     uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
 {
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *ccount = 0;   // for the compaction pass that follows
     __shared__ __align__(16) float As[TM * LDS_STRIDE];
     __shared__ __align__(16) float Bs[TN * LDS_STRIDE];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -174,7 +175,16 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict_
                     for (int i = 0; i < 16; ++i) { acc[a][b][i] += part[a][b][i]; part[a][b][i] = 0.f; }
         }
     }
-    // epilogue: lane holds column (lane % 32) and rows 8 (i / 4) + 4 (lane / 32) + i % 4 of each block
+    // epilogue: lane holds column (lane % 32) and rows 8 (i / 4) + 4 (lane / 32) + i % 4 of each block.
+    // The tile's query norms and cut-offs are staged once in LDS (the slabs are no longer needed).
+    __syncthreads();
+    float *qn = As, *qt = As + TM;
+    if (tid < TM) {
+        const int q = qa + tid;
+        qn[tid] = q < qend ? norms[q] : 0.f;
+        qt[tid] = q < qend ? tau[q - q0] : -INFINITY;     // rows past the end accept nothing
+    }
+    __syncthreads();
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int j = ja + wn * 64 + b * 32 + r32;
@@ -183,10 +193,11 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict_
         for (int a = 0; a < 2; ++a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int q = qa + wm * 64 + a * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-                if (q < qend && j < jend && j != q) {
-                    const float dist = (norms[q] + nj) - 2.0f * acc[a][b][i];
-                    if (dist < tau[q - q0]) {
+                const int ql = wm * 64 + a * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+                const int q = qa + ql;
+                if (j < jend && j != q) {
+                    const float dist = (qn[ql] + nj) - 2.0f * acc[a][b][i];
+                    if (dist < qt[ql]) {
                         const int pos = atomicAdd(&cnt[q - q0], 1);
                         if (pos < cap)
                             cand[(size_t)(q - q0) * cap + pos] = ((uint64_t)orderable(dist) << 32) | (uint32_t)j;
@@ -215,11 +226,13 @@ __device__ __forceinline__ void bitonic_sort(uint64_t *s, int size)
     }
 }
 
-__global__ __launch_bounds__(256) void knn_compact(float *__restrict__ tau, int *__restrict__ cnt,
-                                                   uint64_t *__restrict__ cand, int cap, int kp, int rows, int force)
+// Which rows of the query block need their candidates compacted now (one thread per row; the
+// compaction itself takes a workgroup per row, and on most slabs only a few rows need it).
+__global__ __launch_bounds__(256) void knn_compact_list(const float *__restrict__ tau, const int *__restrict__ cnt,
+                                                        int cap, int kp, int rows, int force, int *__restrict__ list,
+                                                        int *__restrict__ count)
 {
-    __shared__ uint64_t s[SORT_CAP];
-    const int row = blockIdx.x;
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= rows) return;
     int c = cnt[row];
     if (c > cap) c = cap;
@@ -227,6 +240,20 @@ __global__ __launch_bounds__(256) void knn_compact(float *__restrict__ tau, int 
     // sort only when enough new candidates have piled up to matter, when the next slab could
     // overflow the buffer, or at the end (force); in between the cut-off is merely a bit stale
     if (!force && tau[row] < INFINITY && c < kp + COMPACT_SLACK && c + DBC <= cap) return;
+    list[atomicAdd(count, 1)] = row;    // any order
+}
+
+__global__ __launch_bounds__(256) void knn_compact(float *__restrict__ tau, int *__restrict__ cnt,
+                                                   uint64_t *__restrict__ cand, int cap, int kp, int rows,
+                                                   const int *__restrict__ list, const int *__restrict__ count)
+{
+    __shared__ uint64_t s[SORT_CAP];
+    const int m = min(*count, rows);
+    for (int i = blockIdx.x; i < m; i += gridDim.x) {
+    const int row = min(max(list[i], 0), rows - 1);
+    int c = cnt[row];
+    if (c > cap) c = cap;
+    __syncthreads();                    // the previous row of this workgroup is out of s
     int size = 1;
     while (size < c) size <<= 1;
     uint64_t *buf = cand + (size_t)row * cap;
@@ -237,6 +264,7 @@ __global__ __launch_bounds__(256) void knn_compact(float *__restrict__ tau, int 
     if (threadIdx.x == 0) {
         cnt[row] = kp;
         tau[row] = unorderable((uint32_t)(s[kp - 1] >> 32));
+    }
     }
 }
 
@@ -581,6 +609,7 @@ struct Layout {
     float *norms, *norm_max, *tau;
     int *cnt, *fail_count, *fail_rows, *extra, *cursor, *unconv;
     uint64_t *cand, *okey, *sort_scratch;
+    int *clist, *ccount;     // rows of the current query block that need compaction, and how many
     int32_t *knn_idx;
     double *knn_d2, *cond;
     int kp, cap;
@@ -606,6 +635,8 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
     q = take(4); if (L) L->norm_max = (float *)q;
     q = take(4 * qb); if (L) L->tau = (float *)q;
     q = take(4 * qb); if (L) L->cnt = (int *)q;
+    q = take(4 * qb); if (L) L->clist = (int *)q;
+    q = take(4); if (L) L->ccount = (int *)q;
     q = take(4); if (L) L->fail_count = (int *)q;
     q = take(4 * (size_t)n); if (L) L->fail_rows = (int *)q;
     q = take(4 * (size_t)n); if (L) L->extra = (int *)q;
@@ -680,9 +711,11 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
             const int jend = j0 + DBC < n ? j0 + DBC : n;
             dim3 grid((rows + TM - 1) / TM, (jend - j0 + TN - 1) / TN);
             hipLaunchKernelGGL(knn_tile_mfma, grid, dim3(256), 0, s, d_X, n, d, q0, qend, j0, jend, L.norms, L.tau,
-                               L.cnt, L.cand, cap);
-            hipLaunchKernelGGL(knn_compact, dim3(rows), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows,
-                               jend >= n ? 1 : 0);
+                               L.cnt, L.cand, cap, L.ccount);
+            hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows,
+                               jend >= n ? 1 : 0, L.clist, L.ccount);
+            hipLaunchKernelGGL(knn_compact, dim3(rows < 4096 ? rows : 4096), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap,
+                               kp, rows, L.clist, L.ccount);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, q0, rows, k, kp, L.norms,
                            norm_max, L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
