@@ -104,7 +104,11 @@ __device__ __forceinline__ void store_slab(float *__restrict__ S, const float4 v
 }
 
 // One 128 x 128 tile of query rows [q0 + 128 bx, ..) against database rows [j0 + 128 by, ..).
-__global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict__ X, int n, int d, int q0, int qend,
+// TWO: two-level accumulation (needed once d exceeds KFLUSH); without it the kernel needs 64
+// registers less and a third workgroup fits on a compute unit, which matters at small d, where
+// the loads and the epilogue, not the matrix cores, set the pace.
+template <bool TWO>
+__global__ __launch_bounds__(256, TWO ? 2 : 3) void knn_tile_mfma(const float *__restrict__ X, int n, int d, int q0, int qend,
                                                      int j0, int jend, const float *__restrict__ norms,
                                                      const float *__restrict__ tau, int *__restrict__ cnt,
                                                      uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
@@ -120,13 +124,16 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict_
     // to `acc` and cleared.  The rounding error of a dot product of length d drops from order d to
     // order KFLUSH + d / KFLUSH units in the last place, which is what lets a small candidate
     // margin certify rows at D in the thousands.
-    floatx16 acc[2][2], part[2][2];
+    floatx16 acc[TWO ? 2 : 1][TWO ? 2 : 1], part[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { acc[a][b][i] = 0.f; part[a][b][i] = 0.f; }
+            for (int i = 0; i < 16; ++i) {
+                if (TWO) acc[TWO ? a : 0][TWO ? b : 0][i] = 0.f;
+                part[a][b][i] = 0.f;
+            }
     float4 ra[4], rb[4];
     load_slab(X, d, qa, qend, 0, vec, ra);
     load_slab(X, d, ja, jend, 0, vec, rb);
@@ -166,13 +173,16 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict_
                     for (int b = 0; b < 2; ++b)
                         part[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a][s], fb[b][s], part[a][b], 0, 0, 0);
         }
-        if (((k0 / BK) % (KFLUSH / BK)) == (KFLUSH / BK) - 1 || k0 + BK >= d) {
+        if (TWO && (((k0 / BK) % (KFLUSH / BK)) == (KFLUSH / BK) - 1 || k0 + BK >= d)) {
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) { acc[a][b][i] += part[a][b][i]; part[a][b][i] = 0.f; }
+                    for (int i = 0; i < 16; ++i) {
+                        acc[TWO ? a : 0][TWO ? b : 0][i] += part[a][b][i];
+                        part[a][b][i] = 0.f;
+                    }
         }
     }
     // epilogue: lane holds column (lane % 32) and rows 8 (i / 4) + 4 (lane / 32) + i % 4 of each block.
@@ -196,7 +206,8 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const float *__restrict_
                 const int ql = wm * 64 + a * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
                 const int q = qa + ql;
                 if (j < jend && j != q) {
-                    const float dist = (qn[ql] + nj) - 2.0f * acc[a][b][i];
+                    const float dot = TWO ? acc[TWO ? a : 0][TWO ? b : 0][i] : part[a][b][i];
+                    const float dist = (qn[ql] + nj) - 2.0f * dot;
                     if (dist < qt[ql]) {
                         const int pos = atomicAdd(&cnt[q - q0], 1);
                         if (pos < cap)
@@ -710,8 +721,12 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
         for (int j0 = 0; j0 < n; j0 += DBC) {
             const int jend = j0 + DBC < n ? j0 + DBC : n;
             dim3 grid((rows + TM - 1) / TM, (jend - j0 + TN - 1) / TN);
-            hipLaunchKernelGGL(knn_tile_mfma, grid, dim3(256), 0, s, d_X, n, d, q0, qend, j0, jend, L.norms, L.tau,
-                               L.cnt, L.cand, cap, L.ccount);
+            if (d > KFLUSH)
+                hipLaunchKernelGGL(knn_tile_mfma<true>, grid, dim3(256), 0, s, d_X, n, d, q0, qend, j0, jend, L.norms,
+                                   L.tau, L.cnt, L.cand, cap, L.ccount);
+            else   // one flush at the end is the same sum
+                hipLaunchKernelGGL(knn_tile_mfma<false>, grid, dim3(256), 0, s, d_X, n, d, q0, qend, j0, jend, L.norms,
+                                   L.tau, L.cnt, L.cand, cap, L.ccount);
             hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows,
                                jend >= n ? 1 : 0, L.clist, L.ccount);
             hipLaunchKernelGGL(knn_compact, dim3(rows < 4096 ? rows : 4096), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap,
