@@ -4,7 +4,7 @@
 A "step" is one full iteration of Alg. 1 lines 4-8 (tree build, walk + Z, attractive forces over
 the CSR P, update) through the C ABI, with X, P and Y resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg4|cfg2|cfg1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg4|cfg3|cfg2|cfg1]
 """
 import argparse
 import json
@@ -41,6 +41,9 @@ def workload_inputs(name):
         c["d_used"] = STANDIN_D
     elif name == "cfg4":
         X, _ = synth.config4()
+        c["d_used"] = c["d"]
+    elif name == "cfg3":
+        X, _ = synth.config3()
         c["d_used"] = c["d"]
     elif name == "cfg2":
         X, _ = synth.config2()
