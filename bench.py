@@ -67,6 +67,44 @@ def cpu_baseline(Y0, P_host, seconds_hint=20.0):
                 sample=f"{iters} full iterations (tree + walk + attraction + update) of the same N={n} workload from Y0")
 
 
+def sweep(dev, overlap, sizes, n_iter, reorder_every):
+    """Stand-in for the paper's scaling experiment (Sec. IV-B: simulated 50-d data in four clusters): time of a
+    whole run of n_iter iterations (exaggeration 12 for the first quarter), the phases of an iteration averaged
+    over the run, and the time of tsne_build_P, as N grows.  Perplexity 30, k = 90, theta = 0.5."""
+    import torch
+    from paper_1807_11824_amd import Tsne, build_P, synth
+    for n in sizes:
+        X, _ = synth.gaussian_mixture(n, 50, 4, 10.0, 1.0, seed=0)
+        Xd = torch.from_numpy(X).to(dev)
+        del X
+        torch.cuda.synchronize()
+        t0 = time.time()
+        P = build_P(Xd, 30.0, 90)
+        torch.cuda.synchronize()
+        t_build = time.time() - t0
+        del Xd
+        Yd = torch.from_numpy(synth.y0(n)).to(dev)
+        ts = Tsne(n, overlap=overlap, max_nnz=P["nnz"], reorder_every=reorder_every, exaggeration_iters=n_iter // 4)
+        t0 = time.time()
+        ts.set_P(P["row_ptr"], P["col"], P["val"])
+        torch.cuda.synchronize()
+        t_setp = time.time() - t0
+        ts.timing_begin((n_iter + 7) // 8, 8)
+        t0 = time.time()
+        ts.run(Yd, n_iter)
+        torch.cuda.synchronize()
+        dt = time.time() - t0
+        tm = ts.timing_end()
+        st = ts.status()
+        ts.close()
+        print(json.dumps({"workload": "50-d, 4 Gaussian clusters (means N(0, 10^2), sigma 1)", "n": n, "nnz": P["nnz"],
+                          "n_iter": n_iter, "reorder_every": reorder_every, "run_s": round(dt, 4),
+                          "ms_per_step": dt / n_iter * 1e3, "iterations_per_s": n_iter / dt,
+                          "phases_ms": {k[:-3]: round(v, 4) for k, v in tm.items() if k.endswith("_ms")},
+                          "build_P_s": round(t_build, 4), "set_P_s": round(t_setp, 4), "status": st}), flush=True)
+        del P, Yd
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +114,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap", type=int, default=2)
     ap.add_argument("--leaf-cap", type=int, default=8)
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark: the paper's synthetic scaling workload (50-d, 4 Gaussian clusters, "
+                         "Sec. IV-B) at N = 500 ... 5M, one JSON line per N")
+    ap.add_argument("--sweep-n", default="500,1000,2000,4000,8000,16000,32000,64000,128000,512000,2000000,5000000")
+    ap.add_argument("--sweep-iters", type=int, default=1000)
+    ap.add_argument("--reorder-every", type=int, default=0, help="--sweep only: tsne_params.reorder_every")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for the profiler's byte counters)")
     args = ap.parse_args()
@@ -87,6 +131,9 @@ def main():
     from paper_1807_11824_amd import Tsne, build_P, synth
 
     dev = torch.device("cuda:0")
+    if args.sweep:
+        sweep(dev, args.overlap, [int(v) for v in args.sweep_n.split(",")], args.sweep_iters, args.reorder_every)
+        return
     X, cfg = workload_inputs(args.workload)
     n, k, perp = cfg["n"], cfg["k"], cfg["perplexity"]
     Xd = torch.from_numpy(X).to(dev)

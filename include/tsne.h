@@ -126,6 +126,14 @@ void tsne_destroy(tsne_ctx *ctx);
  * Optional outputs (may be NULL): d_knn_idx[n*k] neighbour indices, d_knn_d2[n*k] squared distances.
  * *n_unconverged (host, may be NULL) receives the number of rows whose entropy could not be
  * brought within 1e-5 of the target (e.g. all neighbours equidistant).
+ * X must be finite with |x| < 1e38.  Candidate neighbours are found with reduced-precision products
+ * (each value as two bf16 parts), every row's list is then re-ranked in double precision and
+ * checked against a bound on the candidate search's error; a row that cannot be certified is redone
+ * exactly against all n rows, so the lists do not depend on the reduced precision.
+ * Workspace: about 4 n (d rounded up to 32) bytes for the split copy of X, 20 n k for neighbour
+ * lists and probabilities, 16 n k for sorting, and 8 * 65536 * (k' + 2112) with k' = k + max(k/2, 32)
+ * for the candidate buffers (tsne_build_P_workspace_bytes() gives the exact figure).
+ * Limits: k' <= 1920, d <= 4096, 2 n k < 2^31.
  * Synchronises the stream before returning.
  */
 int tsne_build_P_workspace_bytes(int32_t n, int32_t d, int32_t k, size_t *bytes);

@@ -1,17 +1,19 @@
 // Alg. 1 lines 1-2 of the paper on gfx950: the sparse affinity matrix P.
 //
 //   row_norms            |x_i|^2 in double, rounded to float
+//   split_bf16           every x as bf16 high part + bf16 low part
 //   knn_tile_mfma        Sec. III-B, exact reading: all-pairs squared distances
 //                        |q|^2 + |x|^2 - 2 q.x, the dot products on the matrix cores
-//                        (v_mfma_f32_32x32x2_f32, 128x128 tiles through LDS).  The N x N matrix is
-//                        never stored: the epilogue keeps a pair only if it beats the query row's
-//                        current cut-off and appends it to that row's candidate buffer.
+//                        (three v_mfma_f32_32x32x16_bf16 per step on the split values, 256x128 or
+//                        128x128 tiles through LDS).  The N x N matrix is never stored: the
+//                        epilogue keeps a pair only if it beats the query row's current cut-off
+//                        and appends it to that row's candidate buffer.
 //   knn_compact          per query row, sorts the buffer, keeps the best k' = k + margin and lowers
 //                        the cut-off to the k'-th distance
 //   knn_rerank           recomputes the k' candidate distances as sum_t (x_it - x_jt)^2 in double,
 //                        orders them by (distance, index), keeps k, and certifies the row: every
-//                        discarded pair had a single-precision distance >= cut-off, so it cannot
-//                        belong to the k nearest if cut-off - error bound > exact k-th distance
+//                        discarded pair had a tile distance >= cut-off, so it cannot belong to
+//                        the k nearest if cut-off - error bound > exact k-th distance
 //   knn_exact_dists / knn_exact_select   rows that fail the certificate: all n distances in
 //                        double, radix selection of the k-th smallest, ties by index
 //   perplexity_search    Eq. (1) on the k neighbours, beta by bracketing + bisection on the entropy
@@ -30,8 +32,9 @@ constexpr int QB = 65536;       // query rows per pass
 constexpr int DBC = 2048;       // database rows per launch (bounds what one launch can append per row)
 constexpr int MAX_KP = 1920;    // k' limit: k' + COMPACT_SLACK + DBC must fit the LDS sort
 constexpr int SORT_CAP = 4096;  // candidate buffer entries per row = LDS sort size
-constexpr int TM = 128, TN = 128, BK = 32, LDS_STRIDE = BK + 4;
-constexpr int COMPACT_SLACK = 128; // new candidates per row that trigger a re-sort of its buffer
+constexpr int TN = 128;         // database rows per tile
+constexpr int KNN_MB = 4;        // 32-row query blocks per wave of the general single-level tile kernel
+constexpr int COMPACT_SLACK = 64;  // new candidates per row that trigger a re-sort of its buffer
 constexpr int KFLUSH = 64;      // columns summed on the matrix cores before a flush into the running sum
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -68,65 +71,138 @@ __global__ void knn_reset(float *__restrict__ tau, int *__restrict__ cnt, int ro
     if (i < rows) { tau[i] = INFINITY; cnt[i] = 0; }
 }
 
-// Loads a 128 x 32 slab of X (rows r0.., columns k0..) into registers as 4 float4 per thread;
-// rows >= rend and columns >= d read as 0.
-__device__ __forceinline__ void load_slab(const float *__restrict__ X, int d, int r0, int rend, int k0, bool vec,
-                                          float4 v[4])
+// ---- the distance tiles
+// Candidates only have to be found, not ranked (knn_rerank does that in double), so the dot
+// products run on the bf16 matrix cores at sixteen times the rate of the fp32 ones: every value
+// is split as x = hi + lo + rest, hi = bf16(x), lo = bf16(x - hi), |rest| <= 2^-18 |x|, and
+// q.x is taken as sum hi.hi + hi.lo + lo.hi, accumulated in fp32.  What this leaves out, and
+// what the accumulation rounds away, is bounded in tile_error_coeff(); knn_rerank certifies
+// each row against that bound, so the neighbour lists stay exact.
+//
+// split_bf16 lays the two parts out for the tile kernel: row-major, the row padded to a multiple
+// of SLAB columns, and per SLAB columns the 32 high parts followed by the 32 low parts (128 bytes,
+// the piece of a row that one LDS slab holds).
+constexpr int SLAB = 32;                  // columns per LDS slab (two matrix-core steps of 16)
+constexpr int SLAB_ROW = 4 * SLAB;        // bytes of a row's piece of a slab
+constexpr int LDS_ROW = SLAB_ROW + 16;    // padded: 8 consecutive rows' 16-byte reads hit distinct banks
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ uint32_t bf16_rne(float x)
 {
-    const int kq = (threadIdx.x & 7) * 4;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int r = r0 + (threadIdx.x >> 3) + 32 * it;
-        const int k = k0 + kq;
-        float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r < rend) {
-            const float *p = X + (size_t)r * d + k;
-            if (vec && k + 3 < d) a = *reinterpret_cast<const float4 *>(p);
-            else {
-                if (k < d) a.x = p[0];
-                if (k + 1 < d) a.y = p[1];
-                if (k + 2 < d) a.z = p[2];
-                if (k + 3 < d) a.w = p[3];
-            }
-        }
-        v[it] = a;
-    }
+    uint32_t u = __float_as_uint(x);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-__device__ __forceinline__ void store_slab(float *__restrict__ S, const float4 v[4])
+__global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, int n, int d, int dp,
+                                                  uint16_t *__restrict__ Xs)
 {
-    const int kq = (threadIdx.x & 7) * 4;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int r = (threadIdx.x >> 3) + 32 * it;
-        *reinterpret_cast<float4 *>(S + r * LDS_STRIDE + kq) = v[it];
-    }
+    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (size_t)n * dp) return;
+    const size_t row = e / dp;
+    const int k = (int)(e % dp);
+    const float x = k < d ? X[row * d + k] : 0.f;
+    const uint32_t hi = bf16_rne(x);
+    const uint32_t lo = bf16_rne(x - __uint_as_float(hi << 16));      // the difference is exact in fp32
+    uint16_t *o = Xs + row * dp * 2 + (size_t)(k / SLAB) * (2 * SLAB) + (k % SLAB);
+    o[0] = (uint16_t)hi;
+    o[SLAB] = (uint16_t)lo;
 }
 
-// One 128 x 128 tile of query rows [q0 + 128 bx, ..) against database rows [j0 + 128 by, ..).
-// TWO: two-level accumulation (needed once d exceeds KFLUSH); without it the kernel needs 64
-// registers less and a third workgroup fits on a compute unit, which matters at small d, where
-// the loads and the epilogue, not the matrix cores, set the pace.
-template <bool TWO>
-__global__ __launch_bounds__(256, TWO ? 2 : 3) void knn_tile_mfma(const float *__restrict__ X, int n, int d, int q0, int qend,
-                                                     int j0, int jend, const float *__restrict__ norms,
-                                                     const float *__restrict__ tau, int *__restrict__ cnt,
-                                                     uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
+// Bound on |computed - exact| of one tile distance, as a multiple of |q|^2 + |x|^2.
+//   split: the products left out (lo.lo, rest.x, x.rest) are at most 3 (1 + 2^-18) 2^-18 |q_t x_t| each;
+//   accumulation: a sum reaches the result through at most R fp32 additions, R = 3 * (columns per
+//     flush) + number of flushes; each is taken to lose up to 2^-23 relative (one unit in the last
+//     place, which also covers truncating adders), so the sum is off by R 2^-23 / (1 - R 2^-23)
+//     times the sum of |terms| <= (1 + 2^-8)^2 sum |q_t x_t|;
+//   sum |q_t x_t| <= (|q|^2 + |x|^2) / 2, and the distance takes -2 times the dot product;
+//   norms (each a rounded double sum), their sum and the final fused multiply-add: 8 more roundings
+//   of quantities below 2 (|q|^2 + |x|^2).
+// 5 % on top for the norms themselves being rounded values.
+__host__ __device__ inline double tile_error_coeff(int d, bool two_level)
 {
+    const int dp = (d + SLAB - 1) / SLAB * SLAB;
+    const double R = two_level ? 3.0 * KFLUSH + (double)((dp + KFLUSH - 1) / KFLUSH) : 3.0 * dp;
+    const double u = 1.1920928955078125e-07;   // 2^-23
+    const double split = 3.0 * (1.0 + 3.814697265625e-06) * 3.814697265625e-06;
+    const double accum = 1.0079 * R * u / (1.0 - R * u);
+    return 1.05 * (split + accum + 16.0 * 5.9604644775390625e-08);
+}
+
+// A wave's queue of accepted pairs lives in LDS.
+typedef __attribute__((address_space(3))) uint64_t lds_u64;
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) float lds_f32;
+
+// A wave appends the `fill` pairs it has queued to their rows' candidate buffers.
+__device__ __forceinline__ void append_queue_inline(const lds_u32 *qrow, const lds_u64 *qkey, int fill, int *__restrict__ cnt,
+                                                    uint64_t *__restrict__ cand, int cap)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int e = (int)lane_id(); e < fill; e += WAVE) {
+        const uint32_t row = qrow[e];
+        const int pos = atomicAdd(&cnt[row], 1);
+        if (pos < cap) cand[(size_t)row * cap + pos] = qkey[e];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __noinline__ void append_queue(const lds_u32 *qrow, const lds_u64 *qkey, int fill, int *__restrict__ cnt,
+                                          uint64_t *__restrict__ cand, int cap)
+{
+    append_queue_inline(qrow, qkey, fill, cnt, cand, cap);
+}
+
+// The rare path of a tile's epilogue (some lane of the wave found a pair under its row's cut-off),
+// out of line so that the unrolled test loop stays a handful of instructions per pair.  Called
+// with all lanes active; queues the pairs (slots from a ballot) and returns the new fill level.
+// ql: the lane's query row within the tile (row qa + ql of X, row qa + ql - q0 of the block).
+// A leaf on purpose: a function that calls another one saves its return address through memory.
+__device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0, const lds_f32 *qn, float nj, float dot,
+                                        int fill, int qcap, lds_u64 *qkey, lds_u32 *qrow, int *__restrict__ cnt,
+                                        uint64_t *__restrict__ cand, int cap)
+{
+    const int q = qa + ql;
+    const bool take = near && j != q;
+    const uint64_t m = __ballot(take);
+    if (m == 0) return fill;
+    if (fill + WAVE > qcap) { append_queue_inline(qrow, qkey, fill, cnt, cand, cap); fill = 0; }
+    if (take) {
+        const int slot = fill + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        const float dist = (qn[ql] + nj) - 2.0f * dot;
+        qkey[slot] = ((uint64_t)orderable(dist) << 32) | (uint32_t)j;
+        qrow[slot] = (uint32_t)(q - q0);
+    }
+    return fill + __popcll(m);
+}
+
+// MB x 2 blocks of 32 x 32 per wave, 2 x 2 waves: 64 MB query rows [q0 + 64 MB bx, ..) against 128
+// database rows [j0 + 128 by, ..).  MB = 4 (256 x 128) halves the bytes loaded per product, which
+// is what bounds the kernel once the matrix cores run at the bf16 rate.
+// TWO: two-level accumulation, needed once d exceeds KFLUSH: the matrix cores sum KFLUSH columns
+// into `part`, which is then added to `acc` and cleared, so the accumulation error stays that of
+// a short sum.  It doubles the accumulator registers, hence MB = 2 there.
+template <int MB, bool TWO>
+__global__ __launch_bounds__(256, (MB == 2 && !TWO) ? 4 : 2) void knn_tile_mfma(const uint4 *__restrict__ Xs, int dp, int q0, int qend, int j0,
+                                                        int jend, const float *__restrict__ norms,
+                                                        const float *__restrict__ tau, int *__restrict__ cnt,
+                                                        uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
+{
+    static_assert(!TWO || MB == 2, "two-level accumulation has registers for 2 x 2 blocks only");
+    constexpr int TQ = 64 * MB;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *ccount = 0;   // for the compaction pass that follows
-    __shared__ __align__(16) float As[TM * LDS_STRIDE];
-    __shared__ __align__(16) float Bs[TN * LDS_STRIDE];
+    __shared__ __align__(16) unsigned char As[TQ * LDS_ROW];
+    __shared__ __align__(16) unsigned char Bs[TN * LDS_ROW];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wm = w >> 1, wn = w & 1;
-    const int qa = q0 + blockIdx.x * TM, ja = j0 + blockIdx.y * TN;
-    const bool vec = (d & 3) == 0;
-    // Two-level accumulation: the matrix cores sum KFLUSH columns into `part`, which is then added
-    // to `acc` and cleared.  The rounding error of a dot product of length d drops from order d to
-    // order KFLUSH + d / KFLUSH units in the last place, which is what lets a small candidate
-    // margin certify rows at D in the thousands.
-    floatx16 acc[TWO ? 2 : 1][TWO ? 2 : 1], part[2][2];
+    const int qa = q0 + blockIdx.x * TQ, ja = j0 + blockIdx.y * TN;
+    const int row16 = dp / 4;              // 16-byte pieces per row of Xs
+    const int piece = tid & 7, lrow = tid >> 3;
+    floatx16 acc[TWO ? MB : 1][TWO ? 2 : 1], part[MB][2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MB; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -134,48 +210,72 @@ __global__ __launch_bounds__(256, TWO ? 2 : 3) void knn_tile_mfma(const float *_
                 if (TWO) acc[TWO ? a : 0][TWO ? b : 0][i] = 0.f;
                 part[a][b][i] = 0.f;
             }
-    float4 ra[4], rb[4];
-    load_slab(X, d, qa, qend, 0, vec, ra);
-    load_slab(X, d, ja, jend, 0, vec, rb);
+    uint4 ra[2 * MB], rb[4];
+    auto load = [&](int slab) {
+#pragma unroll
+        for (int it = 0; it < 2 * MB; ++it) {
+            const int r = qa + lrow + 32 * it;
+            ra[it] = r < qend ? Xs[(size_t)r * row16 + slab * 8 + piece] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int r = ja + lrow + 32 * it;
+            rb[it] = r < jend ? Xs[(size_t)r * row16 + slab * 8 + piece] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    load(0);
     const int r32 = lane & 31, h = lane >> 5;
-    for (int k0 = 0; k0 < d; k0 += BK) {
+    const int nslab = dp / SLAB;
+    for (int slab = 0; slab < nslab; ++slab) {
         __syncthreads();
-        store_slab(As, ra);
-        store_slab(Bs, rb);
+#pragma unroll
+        for (int it = 0; it < 2 * MB; ++it)
+            *reinterpret_cast<uint4 *>(As + (lrow + 32 * it) * LDS_ROW + piece * 16) = ra[it];
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            *reinterpret_cast<uint4 *>(Bs + (lrow + 32 * it) * LDS_ROW + piece * 16) = rb[it];
         __syncthreads();
-        if (k0 + BK < d) {
-            load_slab(X, d, qa, qend, k0 + BK, vec, ra);
-            load_slab(X, d, ja, jend, k0 + BK, vec, rb);
+        if (slab + 1 < nslab) load(slab + 1);
+        // a lane holds 8 consecutive columns of its row for each step of 16: columns 8 h .. 8 h + 7.
+        // Both operands use the same assignment, so the products pair up whatever order the
+        // hardware sums them in.
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            // low.high, high.high, high.low, in that order so that at most three fragment sets are live
+            bf16x8 ah[MB], al[MB], bh[2], bl[2];
+            const unsigned char *pa = As + (wm * 32 * MB + r32) * LDS_ROW + ks * 32 + h * 16;
+            const unsigned char *pb = Bs + (wn * 64 + r32) * LDS_ROW + ks * 32 + h * 16;
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+                al[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW + 2 * SLAB));
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                bh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW));
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[a], bh[b], part[a][b], 0, 0, 0);
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+                ah[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW));
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], part[a][b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                bl[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW + 2 * SLAB));
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], part[a][b], 0, 0, 0);
         }
-        // each lane owns 16 of the slab's 32 columns (h selects the half); the same column
-        // assignment is used for both operands, so the products pair up correctly.  The 16
-        // columns are taken in two rounds of 8 to keep the fragment registers at 32.
+        if (TWO && ((slab % (KFLUSH / SLAB)) == (KFLUSH / SLAB) - 1 || slab + 1 == nslab)) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            float fa[2][8], fb[2][8];
-#pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                const float *pa = As + (wm * 64 + m * 32 + r32) * LDS_STRIDE + h * 16 + half * 8;
-                const float *pb = Bs + (wn * 64 + m * 32 + r32) * LDS_STRIDE + h * 16 + half * 8;
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    float4 va = *reinterpret_cast<const float4 *>(pa + 4 * q);
-                    float4 vb = *reinterpret_cast<const float4 *>(pb + 4 * q);
-                    fa[m][4 * q] = va.x; fa[m][4 * q + 1] = va.y; fa[m][4 * q + 2] = va.z; fa[m][4 * q + 3] = va.w;
-                    fb[m][4 * q] = vb.x; fb[m][4 * q + 1] = vb.y; fb[m][4 * q + 2] = vb.z; fb[m][4 * q + 3] = vb.w;
-                }
-            }
-#pragma unroll
-            for (int s = 0; s < 8; ++s)
-#pragma unroll
-                for (int a = 0; a < 2; ++a)
-#pragma unroll
-                    for (int b = 0; b < 2; ++b)
-                        part[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a][s], fb[b][s], part[a][b], 0, 0, 0);
-        }
-        if (TWO && (((k0 / BK) % (KFLUSH / BK)) == (KFLUSH / BK) - 1 || k0 + BK >= d)) {
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < MB; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -187,35 +287,249 @@ __global__ __launch_bounds__(256, TWO ? 2 : 3) void knn_tile_mfma(const float *_
     }
     // epilogue: lane holds column (lane % 32) and rows 8 (i / 4) + 4 (lane / 32) + i % 4 of each block.
     // The tile's query norms and cut-offs are staged once in LDS (the slabs are no longer needed).
+    // Accepted pairs are few (well under 1 % once the cut-offs have settled), but nearly every wave
+    // has some, and an append to a row's buffer is a returning atomic: done where the pair is found,
+    // each would stall the wave for a round trip to memory.  So the wave first collects its pairs in
+    // an LDS queue (slots from a ballot, no atomics) and appends them all at once, 64 at a time.
+    // The test itself is |x|^2 - 2 q.x < cut-off - |q|^2 (one fused multiply-add and one compare per
+    // pair); the distance as stored, (|q|^2 + |x|^2) - 2 q.x, is formed for accepted pairs only.
+    // Both are within tile_error_coeff() of the exact distance.
     __syncthreads();
-    float *qn = As, *qt = As + TM;
-    if (tid < TM) {
-        const int q = qa + tid;
-        qn[tid] = q < qend ? norms[q] : 0.f;
-        qt[tid] = q < qend ? tau[q - q0] : -INFINITY;     // rows past the end accept nothing
+    float *qn = reinterpret_cast<float *>(As), *qd = qn + TQ;
+    for (int t = tid; t < TQ; t += 256) {
+        const int q = qa + t;
+        const float nq = q < qend ? norms[q] : 0.f;
+        qn[t] = nq;
+        qd[t] = q < qend ? tau[q - q0] - nq : -INFINITY;     // rows past the end accept nothing
     }
     __syncthreads();
+    constexpr int QCAP = 320;
+    static_assert(4 * QCAP * 12 <= TN * LDS_ROW, "the queues live where the database slab was");
+    lds_u64 *qkey = (lds_u64 *)(Bs) + w * QCAP;
+    lds_u32 *qrow = (lds_u32 *)(Bs + 4 * QCAP * 8) + w * QCAP;
+    int fill = 0;       // wave-uniform
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int j = ja + wn * 64 + b * 32 + r32;
-        const float nj = j < jend ? norms[j] : 0.f;
+        const float nj = j < jend ? norms[j] : INFINITY;    // rows past the end are never closer than any cut-off
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
+        for (int a = 0; a < MB; ++a) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int ql = wm * 64 + a * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-                const int q = qa + ql;
-                if (j < jend && j != q) {
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int ql0 = wm * 32 * MB + a * 32 + 8 * i4 + 4 * h;
+                const float4 d4 = *reinterpret_cast<const float4 *>(qd + ql0);
+                const float dq[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii) {
+                    const int i = 4 * i4 + ii;
                     const float dot = TWO ? acc[TWO ? a : 0][TWO ? b : 0][i] : part[a][b][i];
-                    const float dist = (qn[ql] + nj) - 2.0f * dot;
-                    if (dist < qt[ql]) {
-                        const int pos = atomicAdd(&cnt[q - q0], 1);
-                        if (pos < cap)
-                            cand[(size_t)(q - q0) * cap + pos] = ((uint64_t)orderable(dist) << 32) | (uint32_t)j;
+                    const bool near = fmaf(-2.0f, dot, nj) < dq[ii];
+                    if (__ballot(near) != 0)
+                        fill = __builtin_amdgcn_readfirstlane(queue_pairs(near, j, ql0 + ii, qa, q0, (const lds_f32 *)qn, nj, dot, fill, QCAP,
+                                                                          qkey, qrow, cnt, cand, cap));
+                }
+            }
+        }
+    }
+    append_queue(qrow, qkey, fill, cnt, cand, cap);
+}
+
+// ---- d <= 64: the query tile stays in LDS
+// With two slabs at most, the kernel above spends its time waiting: a workgroup makes five
+// dependent round trips to memory (two slabs, norms and cut-offs, the appends) around 2 x 48 matrix
+// instructions.  Here a workgroup keeps its 256 query rows on chip for the whole launch (each
+// wave holds the fragments of its 64 rows in registers) and walks over the database rows; the
+// next rows are in flight (registers) while the current ones are multiplied and tested.  The
+// workgroup is the only one that appends to its rows' buffers during the launch, so the fill
+// counts live in LDS: an append is an LDS atomic and a store that nobody waits for.
+// Eight waves in two groups of four: each group takes every other tile of 128 database rows, in
+// two halves of 64; a wave holds 64 x 64 of its group's 256 x 64 products.  Group 0 multiplies a
+// half and then tests it, group 1 tests its previous half first and then multiplies the next, so
+// that on every SIMD one wave feeds the matrix cores while the other one runs the tests on the
+// vector unit.  (Two halves per trip: one half's work is shorter than a load takes to arrive.)
+// LDS rows are 128 bytes (32 high parts, 32 low parts), unpadded; the 16-byte piece c of row r sits
+// at position c ^ swz(r), chosen so that 16 consecutive rows' reads of one piece fall on 16
+// different 16-byte bank groups of a 256-byte LDS line (and 8 consecutive rows on 8 of a
+// 128-byte line), while the 8 pieces of a row stay a permutation of the row.
+constexpr int RQ = 256;          // query rows per workgroup
+constexpr int RT = 128;          // database rows per group and trip, taken in two halves
+constexpr int RESIDENT_MIN_ROWS = 64 * RQ;   // fewer query rows than this leave most compute units without a workgroup
+
+constexpr size_t resident_lds_bytes(int ns)
+{
+    return 2 * (size_t)ns * RT * SLAB_ROW + 3 * RQ * 4;
+}
+
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ ((row & 1) << 2)) & 7; }
+
+// A workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// store of the wave to complete, which would put the appends' trip to memory on the critical path.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <int NS>
+__global__ __launch_bounds__(512, 1) void knn_tile_resident(const uint4 *__restrict__ Xs, int q0, int qend, int j0, int jend,
+                                                            const float *__restrict__ norms,
+                                                            const float *__restrict__ tau, int *__restrict__ cnt,
+                                                            uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *Bs = smem;                                   // [2 groups][NS][RT] rows
+    float *qn = reinterpret_cast<float *>(Bs + 2 * NS * RT * SLAB_ROW), *qd = qn + RQ;
+    int *qc = reinterpret_cast<int *>(qd + RQ);                 // candidates in each row's buffer
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int g = w >> 2, wq = w & 3;
+    const int r32 = lane & 31, h = lane >> 5, sw = swz(r32);
+    const int qa = q0 + blockIdx.x * RQ;
+    constexpr int row16 = NS * 8;          // 16-byte pieces per row of Xs
+    if (blockIdx.x == 0 && tid == 0) *ccount = 0;   // for the compaction pass that follows
+    // the wave's query fragments: [block][slab][step] high and low parts, as the matrix cores take them
+    bf16x8 afh[2][NS][2], afl[2][NS][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        const int r = qa + wq * 64 + a * 32 + r32;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+                afh[a][sl][ks] = __builtin_bit_cast(bf16x8, r < qend ? Xs[(size_t)r * row16 + sl * 8 + 2 * ks + h] : z);
+                afl[a][sl][ks] = __builtin_bit_cast(bf16x8, r < qend ? Xs[(size_t)r * row16 + sl * 8 + 4 + 2 * ks + h] : z);
+            }
+    }
+    for (int t = tid; t < RQ; t += 512) {
+        const int q = qa + t;
+        const float nq = q < qend ? norms[q] : 0.f;
+        qn[t] = nq;
+        qd[t] = q < qend ? tau[q - q0] - nq : -INFINITY;     // rows past the end accept nothing
+        qc[t] = q < qend ? cnt[q - q0] : 0;
+    }
+    unsigned char *Bg = Bs + g * NS * RT * SLAB_ROW;
+    const int bpiece = tid & 7, blrow = (tid & 255) >> 3;
+    const int ntile = (jend - j0 + RT - 1) / RT, npair = (ntile + 1) / 2;
+    uint4 rb[4 * NS];
+    float njn[2][2];   // |x|^2 of this lane's two columns of each half of the tile in rb
+    auto load_tile = [&](int pair) {
+        const int ja = j0 + (2 * pair + g) * RT;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int r = ja + blrow + 32 * it;
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl)
+                rb[it * NS + sl] = r < jend ? Xs[(size_t)r * row16 + sl * 8 + bpiece] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int j = ja + hf * 64 + b * 32 + r32;
+                njn[hf][b] = j < jend ? norms[j] : INFINITY;    // rows past the end are never closer than any cut-off
+            }
+    };
+    floatx16 part[2][2];
+    float njc[2] = {INFINITY, INFINITY};   // the same for the half in `part`
+    int jac = j0;                          // first database row of that half
+    auto test_tile = [&]() {
+        // one base per lane, the rest compile-time offsets (and no addresses carried around the loop)
+        int lbase = wq * 64 + 4 * h;
+        asm volatile("" : "+v"(lbase));
+        const float *qd_l = qd + lbase, *qn_l = qn + lbase;
+        int *qc_l = qc + lbase;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int j = jac + b * 32 + r32;
+            const float nj = njc[b];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const float4 d4 = *reinterpret_cast<const float4 *>(qd_l + a * 32 + 8 * i4);
+                    const float dq[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii) {
+                        const float dot = part[a][b][4 * i4 + ii];
+                        const bool near = fmaf(-2.0f, dot, nj) < dq[ii];
+                        if (__builtin_expect(__ballot(near) != 0, 0)) {
+                            const int off = a * 32 + 8 * i4 + ii;
+                            const int q = qa + lbase + off;
+                            if (near && j != q) {
+                                const float dist = (qn_l[off] + nj) - 2.0f * dot;
+                                const int pos = atomicAdd(qc_l + off, 1);
+                                if (pos < cap)
+                                    cand[(size_t)(q - q0) * cap + pos] = ((uint64_t)orderable(dist) << 32) | (uint32_t)j;
+                            }
+                        }
                     }
                 }
             }
         }
+    };
+    if (npair > 0) load_tile(0);
+    const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bool have = false;      // group 1: `part` holds a half that has not been tested yet
+    for (int pair = 0; pair < npair; ++pair) {
+        lds_barrier();          // every wave is done with the tiles in LDS (first trip: the query rows are in)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int row = blrow + 32 * it;
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl)
+                *reinterpret_cast<uint4 *>(Bg + (sl * RT + row) * SLAB_ROW + ((bpiece ^ swz(row)) << 4)) = rb[it * NS + sl];
+        }
+        const float njl[2][2] = {{njn[0][0], njn[0][1]}, {njn[1][0], njn[1][1]}};
+        lds_barrier();
+        // the next rows are requested after the first tests of this trip: a wait for them (the counter
+        // is in order) then never covers stores made by tests, except those of the half in between
+        for (int hf = 0; hf < 2; ++hf) {
+            if (g == 1 && have) test_tile();
+            if (hf == 0 && pair + 1 < npair) load_tile(pair + 1);
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl) {
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    // low.high, high.low, high.high; piece index = 4 (low part) + 2 ks + h
+                    bf16x8 bh[2], bl[2];
+                    const unsigned char *pb = Bg + (sl * RT + hf * 64 + r32) * SLAB_ROW;
+                    const int ch = ((2 * ks + h) ^ sw) << 4, cl = ((4 + 2 * ks + h) ^ sw) << 4;
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) {
+                        bh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * SLAB_ROW + ch));
+                        bl[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * SLAB_ROW + cl));
+                    }
+#pragma unroll
+                    for (int a = 0; a < 2; ++a)
+#pragma unroll
+                        for (int b = 0; b < 2; ++b)
+                            part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afl[a][sl][ks], bh[b],
+                                                                                 (sl == 0 && ks == 0) ? zero16 : part[a][b], 0, 0, 0);
+#pragma unroll
+                    for (int a = 0; a < 2; ++a)
+#pragma unroll
+                        for (int b = 0; b < 2; ++b)
+                            part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afh[a][sl][ks], bl[b], part[a][b], 0, 0, 0);
+#pragma unroll
+                    for (int a = 0; a < 2; ++a)
+#pragma unroll
+                        for (int b = 0; b < 2; ++b)
+                            part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afh[a][sl][ks], bh[b], part[a][b], 0, 0, 0);
+                }
+            }
+            njc[0] = njl[hf][0];
+            njc[1] = njl[hf][1];
+            jac = j0 + (2 * pair + g) * RT + hf * 64;
+            have = true;
+            if (g == 0) test_tile();
+        }
+    }
+    if (g == 1 && have) test_tile();
+    lds_barrier();
+    for (int t = tid; t < RQ; t += 512) {
+        const int q = qa + t;
+        if (q < qend) cnt[q - q0] = qc[t];
     }
 }
 
@@ -335,11 +649,8 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
         // at most E, so they are farther than the exact k-th candidate if tau - E > D_k
         bool ok = c >= k;
         if (ok && c < n - 1) {
-            // error of the float distance: each product and each addition rounds once (2 KFLUSH per
-            // partial sum), d / KFLUSH additions of partial sums, a few for norms and the final
-            // combination; terms are bounded by (|q|^2 + |x|^2) / 2 in sum; the whole doubled for safety
-            const double roundings = 2.0 * KFLUSH + (double)((d + KFLUSH - 1) / KFLUSH) + 16.0;
-            const double E = roundings * 5.9604644775390625e-08 * ((double)norms[i] + (double)norm_max) * 2.0;
+            // (the additive term covers matrix cores that flush denormal bf16 parts to zero)
+            const double E = tile_error_coeff(d, d > KFLUSH) * ((double)norms[i] + (double)norm_max) + 1e-30 * d;
             const double Dk = dd[order[k - 1]];
             ok = (double)tau[row] - E > Dk;
         }
@@ -620,6 +931,7 @@ struct Layout {
     float *norms, *norm_max, *tau;
     int *cnt, *fail_count, *fail_rows, *extra, *cursor, *unconv;
     uint64_t *cand, *okey, *sort_scratch;
+    uint16_t *xs;            // the split copy of X
     int *clist, *ccount;     // rows of the current query block that need compaction, and how many
     int32_t *knn_idx;
     double *knn_d2, *cond;
@@ -635,7 +947,6 @@ int margin_kp(int n, int k)
 
 size_t carve(Layout *L, int n, int d, int k, char *base)
 {
-    (void)d;
     size_t off = 0;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up(bytes); return (void *)p; };
     const int kp = margin_kp(n, k);
@@ -659,6 +970,7 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
     q = take(4 * (size_t)n * k); if (L) L->knn_idx = (int32_t *)q;
     q = take(8 * (size_t)n * k); if (L) L->knn_d2 = (double *)q;
     q = take(8 * (size_t)n * k); if (L) L->cond = (double *)q;
+    q = take(4 * (size_t)n * ((d + SLAB - 1) / SLAB * SLAB)); if (L) L->xs = (uint16_t *)q;
     if (L) { L->kp = kp; L->cap = cap; }
     return off;
 }
@@ -705,7 +1017,9 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     carve(&L, n, d, k, (char *)d_workspace);
     const int kp = L.kp, cap = L.cap;
 
+    const int dp = (d + SLAB - 1) / SLAB * SLAB;
     hipLaunchKernelGGL(row_norms, dim3((n + 3) / 4), dim3(256), 0, s, d_X, n, d, L.norms);
+    hipLaunchKernelGGL(split_bf16, dim3((unsigned)(((size_t)n * dp + 255) / 256)), dim3(256), 0, s, d_X, n, d, dp, L.xs);
     hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms, n, L.norm_max);
     HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
     HIPCHK(hipMemsetAsync(L.unconv, 0, 4, s));
@@ -714,22 +1028,41 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     HIPCHK(hipMemcpyAsync(&norm_max, L.norm_max, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
 
+    // more LDS than a kernel may use by default
+    HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&knn_tile_resident<1>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)resident_lds_bytes(1)));
+    HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&knn_tile_resident<2>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)resident_lds_bytes(2)));
     const size_t rerank_smem = up((size_t)d * 4) + 8 * (size_t)MAX_KP;
     for (int q0 = 0; q0 < n; q0 += QB) {
         const int qend = q0 + QB < n ? q0 + QB : n, rows = qend - q0;
         hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows);
-        for (int j0 = 0; j0 < n; j0 += DBC) {
-            const int jend = j0 + DBC < n ? j0 + DBC : n;
-            dim3 grid((rows + TM - 1) / TM, (jend - j0 + TN - 1) / TN);
-            if (d > KFLUSH)
-                hipLaunchKernelGGL(knn_tile_mfma<true>, grid, dim3(256), 0, s, d_X, n, d, q0, qend, j0, jend, L.norms,
-                                   L.tau, L.cnt, L.cand, cap, L.ccount);
-            else   // one flush at the end is the same sum
-                hipLaunchKernelGGL(knn_tile_mfma<false>, grid, dim3(256), 0, s, d_X, n, d, q0, qend, j0, jend, L.norms,
-                                   L.tau, L.cnt, L.cand, cap, L.ccount);
+        // Until a row has k' candidates its cut-off is +inf and every pair is kept, and the pairs kept
+        // right after are still many (a fraction k' / j0 of them).  Short first slabs get the cut-offs
+        // down early: 256, 256, 512, 1024 rows, then DBC at a time.
+        int step = kp + 64 <= 256 ? 256 : DBC;
+        for (int j0 = 0, jend; j0 < n; j0 = jend) {
+            jend = j0 + step < n ? j0 + step : n;
+            if (jend > step && step < DBC) step *= 2;
+            const unsigned gy = (unsigned)((jend - j0 + TN - 1) / TN);
+            if (dp <= 2 * SLAB && rows >= RESIDENT_MIN_ROWS) {
+                if (dp == SLAB)
+                    hipLaunchKernelGGL(knn_tile_resident<1>, dim3((rows + RQ - 1) / RQ), dim3(512), resident_lds_bytes(1), s,
+                                       (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount);
+                else
+                    hipLaunchKernelGGL(knn_tile_resident<2>, dim3((rows + RQ - 1) / RQ), dim3(512), resident_lds_bytes(2), s,
+                                       (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount);
+            } else if (d > KFLUSH)
+                hipLaunchKernelGGL((knn_tile_mfma<2, true>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
+                                   (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap,
+                                   L.ccount);
+            else
+                hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false>), dim3((rows + 32 * KNN_MB * 2 - 1) / (64 * KNN_MB), gy), dim3(256), 0, s,
+                                   (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap,
+                                   L.ccount);
             hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows,
                                jend >= n ? 1 : 0, L.clist, L.ccount);
-            hipLaunchKernelGGL(knn_compact, dim3(rows < 4096 ? rows : 4096), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap,
+            hipLaunchKernelGGL(knn_compact, dim3(rows < 1024 ? rows : 1024), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap,
                                kp, rows, L.clist, L.ccount);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, q0, rows, k, kp, L.norms,

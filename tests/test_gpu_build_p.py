@@ -86,6 +86,17 @@ def test_config3_shape_sampled_rows():
     _check_against_oracle(X, 50.0, 150, rows=np.sort(rows))
 
 
+@pytest.mark.parametrize("n,d,k", [(40000, 50, 90), (20000, 20, 30), (16500, 64, 45)])
+def test_small_d_many_rows_sampled(n, d, k):
+    """Enough rows and few enough columns for the tile kernel that keeps the query rows in LDS
+    (one slab at d <= 32, two up to 64); clustered like the scaling workload of Sec. IV-B."""
+    X, _ = synth.gaussian_mixture(n, d, 4, 10.0, 1.0, seed=d)
+    rows = np.sort(np.random.default_rng(d).choice(n, 192, replace=False).astype(np.int32))
+    rows[:3] = [0, 255, 256]
+    rows[-2:] = [n - 2, n - 1]
+    _check_against_oracle(X, 30.0 if k >= 90 else 10.0, k, rows=np.unique(rows))
+
+
 def test_bad_arguments():
     import torch
     from paper_1807_11824_amd import build_P, TsneError
