@@ -97,6 +97,15 @@ def test_small_d_many_rows_sampled(n, d, k):
     _check_against_oracle(X, 30.0 if k >= 90 else 10.0, k, rows=np.unique(rows))
 
 
+@pytest.mark.parametrize("offset,sigma", [(30.0, 1.0), (300.0, 0.01)])
+def test_far_from_the_origin(offset, sigma):
+    """Norms much larger than the distances: the reduced-precision candidate search cannot certify
+    (some, then all) rows, which must then come out of the exact fall-back with the same lists."""
+    rng = np.random.default_rng(int(offset))
+    X = (offset + sigma * rng.standard_normal((3000, 20))).astype(np.float32)
+    _check_against_oracle(X, 10.0, 30)
+
+
 def test_bad_arguments():
     import torch
     from paper_1807_11824_amd import build_P, TsneError
