@@ -8,6 +8,8 @@
 //                        128x128 tiles through LDS).  The N x N matrix is never stored: the
 //                        epilogue keeps a pair only if it beats the query row's current cut-off
 //                        and appends it to that row's candidate buffer.
+//   knn_tile_resident    the same for d <= 64 and many query rows: a workgroup keeps 256 query rows
+//                        on chip for the whole launch and streams the database rows past them
 //   knn_compact          per query row, sorts the buffer, keeps the best k' = k + margin and lowers
 //                        the cut-off to the k'-th distance
 //   knn_rerank           recomputes the k' candidate distances as sum_t (x_it - x_jt)^2 in double,
@@ -185,7 +187,7 @@ __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0
 // into `part`, which is then added to `acc` and cleared, so the accumulation error stays that of
 // a short sum.  It doubles the accumulator registers, hence MB = 2 there.
 template <int MB, bool TWO>
-__global__ __launch_bounds__(256, (MB == 2 && !TWO) ? 4 : 2) void knn_tile_mfma(const uint4 *__restrict__ Xs, int dp, int q0, int qend, int j0,
+__global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict__ Xs, int dp, int q0, int qend, int j0,
                                                         int jend, const float *__restrict__ norms,
                                                         const float *__restrict__ tau, int *__restrict__ cnt,
                                                         uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
