@@ -92,8 +92,18 @@ typedef struct {
                                      kernels are latency-bound and slow down under any extra memory traffic
                                      (measured: 0.24 -> 0.33 ms at 20 percent), so only the small far part
                                      runs there by default.  (0) */
+    int32_t far_tiles;            /* how the entries of the renumbered P that lie far from the diagonal are
+                                     summed.  1: one row at a time, each entry fetching its neighbour's
+                                     position from memory.  2: from a copy bucketed by 4096-row x 2048-column
+                                     tiles, so that the positions fetched together share cache lines, with
+                                     the row sums kept in fixed point in LDS (integer-valued doubles: every
+                                     addition is exact, so the result does not depend on the order of the
+                                     entries).
+                                     0: chosen at tsne_set_P: tiles if the far part holds at least an eighth
+                                     of the entries and n >= 2^18, rows otherwise.  (0) */
     int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
-                                     10 bytes per entry plus 186 bytes per point (rows are padded).  0 disables
+                                     20 bytes per entry plus 202 bytes per point (rows are padded) plus 8 bytes
+                                     per pair of a 4096-row and a 2048-column tile (n^2 / 2^20).  0 disables
                                      renumbering; P is then only borrowed and a stop/resume is bitwise
                                      reproducible.  With renumbering a row of the attractive sum is added up
                                      as (entries near the diagonal) + (the others): deterministic, equal to

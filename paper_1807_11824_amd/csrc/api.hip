@@ -90,6 +90,18 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
         q = take(2 * ms);      if (c) c->col_near = (uint16_t *)q;
         q = take(4 * (m + ATTRACT_SLACK)); if (c) c->col_far = (int32_t *)q;
         q = take(4 * ms);      if (c) c->val_s = (float *)q;
+        if (c) c->ft_tiles = 0;
+        if (ft_possible(p)) {
+            const size_t nrt = (n + FT_ROWS - 1) / FT_ROWS, nct = (n + FT_COLS - 1) / FT_COLS;
+            if (c) { c->ft_tiles = (int64_t)(nrt * nct); c->ft_nct = (int)nct; }
+            q = take(4 * nrt * nct);       if (c) c->ft_cnt = (uint32_t *)q;
+            q = take(4 * (nrt * nct + 1)); if (c) c->ft_ptr = (int32_t *)q;
+            q = take(4 * m);               if (c) c->ft_col = (int32_t *)q;
+            q = take(2 * m);               if (c) c->ft_row = (uint16_t *)q;
+            q = take(4 * m);               if (c) c->ft_val = (float *)q;
+            q = take(16 * n);              if (c) c->ft_acc = (double *)q;
+            q = take(32);                  if (c) c->ft_meta = (uint32_t *)q;
+        }
     }
     q = take(4 * (ATTRACT_MAX_PARTS + 1));           if (c) c->arow = (int32_t *)q;
     q = take(8 * ngroups);                           if (c) c->zpart = (double *)q;
@@ -109,6 +121,7 @@ int check_params(const tsne_params *p)
     if (p->attract_resident < 0 || p->attract_resident > 64) return TSNE_EINVAL;
     if (p->walk_resident < 0 || p->walk_resident > 32) return TSNE_EINVAL;
     if (p->attract_early < 0 || p->attract_early > 90) return TSNE_EINVAL;
+    if (p->far_tiles < 0 || p->far_tiles > 2) return TSNE_EINVAL;
     if (p->max_nnz < 0 || p->max_nnz > 0x7FFFFFFFll) return TSNE_EINVAL;
     // the renumbered copy pads every row to whole chunks and is indexed with int32
     if (p->max_nnz > 0 && p->max_nnz + (ATTRACT_CHUNK - 1ll) * p->n + ATTRACT_SLACK > 0x7FFFFFFFll) return TSNE_EINVAL;
@@ -253,6 +266,7 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->attract_resident = 1;
     p->walk_resident = 14;
     p->attract_early = 0;
+    p->far_tiles = 0;
     p->max_nnz = 0;
     return TSNE_OK;
 }
@@ -301,6 +315,15 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
             return TSNE_EHIP;
         }
     }
+    if (c->ft_tiles > 0 &&
+        ((e = hipHostMalloc((void **)&c->ft_host, sizeof(uint32_t), hipHostMallocDefault)) != hipSuccess ||
+         (*c->ft_host = 0u, e = attract_far_tiled_prepare()) != hipSuccess ||
+         (e = hipMemsetAsync(c->ft_cnt, 0, 4 * (size_t)c->ft_tiles, c->stream)) != hipSuccess ||
+         (e = hipMemsetAsync(c->ft_acc, 0, 16 * (size_t)p->n, c->stream)) != hipSuccess ||
+         (e = hipMemsetAsync(c->ft_meta, 0, 32, c->stream)) != hipSuccess)) {
+        tsne_destroy(c);
+        return TSNE_EHIP;
+    }
     if ((e = hipMemsetAsync(c->status, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
         (e = hipMemsetAsync(c->ncells, 0, sizeof(uint32_t), c->stream)) != hipSuccess ||
         (e = launch_fill_state(c, c->stream)) != hipSuccess ||
@@ -321,6 +344,7 @@ void tsne_destroy(tsne_ctx *c)
     if (c->ev_fork2) (void)hipEventDestroy(c->ev_fork2);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     free_timing(c);
+    if (c->ft_host) (void)hipHostFree((void *)c->ft_host);
     delete c;
 }
 
@@ -338,7 +362,9 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     c->have_P = 1;
     if (c->reorder_on && c->p.graph_order_iters > 0 && nnz > 0) {
         hipError_t e;
-        if ((e = launch_graph_order(c, c->stream)) != hipSuccess || (e = launch_reorder(c, c->stream)) != hipSuccess)
+        if ((e = launch_graph_order(c, c->stream)) != hipSuccess || (e = launch_reorder(c, c->stream)) != hipSuccess ||
+            (c->ft_tiles > 0 && (e = hipMemcpyAsync((void *)c->ft_host, c->ft_meta, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                                                    c->stream)) != hipSuccess))
             return fail_hip(c, e, "graph order");
     }
     return TSNE_OK;
@@ -397,7 +423,10 @@ int step_impl(tsne_ctx *c, float *d_Y, int32_t iter, bool cached, bool keep)
     if (c->reorder_on && c->p.reorder_every > 0 && ++c->steps_since_reorder >= c->p.reorder_every) {
         c->steps_since_reorder = 0;
         c->yi_fresh = 0;      // the slots are renumbered: Yi is stale
-        if ((e = launch_reorder(c, c->stream)) != hipSuccess) return fail_hip(c, e, "reorder");
+        if ((e = launch_reorder(c, c->stream)) != hipSuccess ||
+            (c->ft_tiles > 0 && (e = hipMemcpyAsync((void *)c->ft_host, c->ft_meta, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                                                    c->stream)) != hipSuccess))
+            return fail_hip(c, e, "reorder");
     }
     return TSNE_OK;
 }

@@ -270,8 +270,10 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
 __global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
                                                    const float *__restrict__ val, const float2 *__restrict__ Y, int n,
                                                    const uint32_t *__restrict__ far_rows,
-                                                   const uint32_t *__restrict__ far_count, float2 *__restrict__ Afar)
+                                                   const uint32_t *__restrict__ far_count, float2 *__restrict__ Afar,
+                                                   const uint32_t *__restrict__ tiled)
 {
+    if (tiled && tiled[0]) return;      // the bucketed copy is in use (attract_far_tiled)
     const int sub = (int)(threadIdx.x % 16);
     const uint32_t m = min(*far_count, (uint32_t)n);
     const int far0 = rp[0];      // values sit behind the near part, columns start at 0
@@ -311,6 +313,148 @@ __global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ r
     }
 }
 
+// ---- the far part from its bucketed copy
+// An entry of the far part costs attract_far a cache line for 8 bytes of Y.  When the far part is
+// large (P without a band structure: one high-dimensional blob per cluster), the entries are taken
+// tile by tile instead: a workgroup owns FT_ROWS rows and streams through their entries, which are
+// stored by column tile of FT_COLS points, so that the positions fetched around the same time share
+// the 16 KB of one column tile and many are served by the first-level cache.  Row sums are kept in
+// fixed point -- doubles that only ever hold integers below 2^53, so every addition is exact --
+// in LDS while the workgroup runs and added to a global array at its end (several workgroups may
+// share a row tile, each taking a range of its entries): the result is exact for the terms as
+// computed and does not depend on any order.
+// The scale: a term is p w (y_i - y_j) with w <= 1, so a row sum is below
+// (largest p) x (extent of Y) x (longest far row) < 2^e; terms are multiplied by 2^(52 - e) and
+// truncated to integers, which keeps every sum below 2^52.
+__global__ __launch_bounds__(256) void ft_extent_k(const float4 *__restrict__ part, int nparts, uint32_t *meta)
+{
+    if (!meta[0]) return;
+    float mnx = INFINITY, mny = INFINITY, mxx = -INFINITY, mxy = -INFINITY;
+    for (int i = threadIdx.x; i < nparts; i += 256) {
+        const float4 a = part[2 * i], b = part[2 * i + 1];
+        mnx = fminf(mnx, a.x); mny = fminf(mny, a.y);
+        mxx = fmaxf(mxx, b.x); mxy = fmaxf(mxy, b.y);
+    }
+    float ext = fmaxf(mxx - mnx, mxy - mny);
+    ext = wave_max(ext);
+    __shared__ float sw[4];
+    if (lane_id() == 0) sw[threadIdx.x >> 6] = ext;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        ext = fmaxf(fmaxf(sw[0], sw[1]), fmaxf(sw[2], sw[3]));
+        meta[3] = __float_as_uint(ext >= 0.f && ext < INFINITY ? ext : 0.f);
+    }
+}
+
+__device__ __forceinline__ int ft_shift(const uint32_t *meta)
+{
+    const float bound = __uint_as_float(meta[1]) * __uint_as_float(meta[3]) * (float)meta[2];
+    if (!(bound > 0.f) || !(bound < INFINITY)) return 0;
+    int e;
+    (void)frexpf(bound, &e);       // bound < 2^e
+    return 52 - e;
+}
+
+constexpr int FT_THREADS = 512;
+constexpr int FT_UNROLL = 8;
+constexpr size_t FT_LDS = (size_t)FT_ROWS * 16;
+
+typedef __attribute__((address_space(3))) double ft_lds_f64;
+typedef __attribute__((address_space(1))) double ft_glb_f64;
+
+__global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *__restrict__ ptr, const int32_t *__restrict__ tcol,
+                                                                const uint16_t *__restrict__ trow,
+                                                                const float *__restrict__ tval, const float2 *__restrict__ Y,
+                                                                int n, int nct, const uint32_t *__restrict__ meta,
+                                                                double *__restrict__ gacc)
+{
+    if (!meta[0]) return;
+    extern __shared__ __align__(16) unsigned char ft_smem[];
+    // x sums, then y sums; row r of the tile at slot r ^ (r / 32 % 32): rows a fixed stride apart
+    // (entries arrive roughly in row order) would otherwise meet in the same LDS banks
+    double *acc = reinterpret_cast<double *>(ft_smem);
+    const uint32_t tid = threadIdx.x;
+    const int rt = blockIdx.x, row0 = rt * FT_ROWS;
+    // this workgroup's share of the row tile's entries
+    const int t0 = ptr[(int64_t)rt * nct], t1 = ptr[(int64_t)(rt + 1) * nct];
+    const int per = (int)(((int64_t)(t1 - t0) + gridDim.y - 1) / gridDim.y);
+    const int s0 = t0 + (int)blockIdx.y * per, s1 = min(t1, s0 + per);
+    if (s0 >= s1) return;                   // the same for every thread
+    const int shift = ft_shift(meta);
+    for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) acc[t] = 0.0;
+    __syncthreads();
+    // Entries past the end of the share are read as the share's last entry with weight 0 (they add 0).
+    // The entries of the next trip are requested before the gathers of this one.
+    const uint32_t last = (uint32_t)s1 - 1u;
+    uint32_t ncj[FT_UNROLL], nrl[FT_UNROLL];
+    float nv[FT_UNROLL];
+    auto fetch = [&](uint32_t e0) {
+#pragma unroll
+        for (int u = 0; u < FT_UNROLL; ++u) {
+            const uint32_t e = e0 + (uint32_t)u * FT_THREADS, ec = min(e, last);
+            // (read once: kept out of the way of the lines of Y in the first-level cache)
+            ncj[u] = (uint32_t)__builtin_nontemporal_load(tcol + ec);
+            nrl[u] = (uint32_t)__builtin_nontemporal_load(trow + ec);
+            const float val = __builtin_nontemporal_load(tval + ec);
+            nv[u] = e <= last ? val : 0.f;
+        }
+    };
+    fetch((uint32_t)s0 + tid);
+    for (uint32_t e0 = (uint32_t)s0 + tid; e0 <= last; e0 += FT_THREADS * FT_UNROLL) {
+        uint32_t rl[FT_UNROLL];
+        float v[FT_UNROLL];
+        float2 yi[FT_UNROLL], yj[FT_UNROLL];
+#pragma unroll
+        for (int u = 0; u < FT_UNROLL; ++u) {
+            rl[u] = min(nrl[u], (uint32_t)FT_ROWS - 1u);
+            v[u] = nv[u];
+            yj[u] = Y[min(ncj[u], (uint32_t)n - 1u)];
+            yi[u] = Y[min((uint32_t)row0 + rl[u], (uint32_t)n - 1u)];
+        }
+        fetch(e0 + FT_THREADS * FT_UNROLL);
+#pragma unroll
+        for (int u = 0; u < FT_UNROLL; ++u) {
+            const float dx = yi[u].x - yj[u].x, dy = yi[u].y - yj[u].y;
+            const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
+            const float pw = v[u] * w;
+            const double fx = trunc(ldexp((double)(pw * dx), shift)), fy = trunc(ldexp((double)(pw * dy), shift));
+            const uint32_t slot = rl[u] ^ ((rl[u] >> 5) & 31u);
+            (void)__builtin_amdgcn_ds_atomic_fadd_f64((ft_lds_f64 *)(acc + slot), fx);
+            (void)__builtin_amdgcn_ds_atomic_fadd_f64((ft_lds_f64 *)(acc + FT_ROWS + slot), fy);
+        }
+    }
+    __syncthreads();
+    for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) {
+        const uint32_t r = t / 2, slot = r ^ ((r >> 5) & 31u);
+        const double a = acc[(t & 1u) * FT_ROWS + slot];
+        if (a != 0.0 && row0 + (int)r < n)
+            (void)__builtin_amdgcn_global_atomic_fadd_f64((ft_glb_f64 *)(gacc + 2 * (size_t)row0 + t), a);
+    }
+}
+
+// fixed point -> float, and the accumulators back to zero for the next step
+__global__ __launch_bounds__(256) void ft_finish_k(const uint32_t *__restrict__ far_rows, const uint32_t *__restrict__ far_count,
+                                                   int n, const uint32_t *__restrict__ meta, double *__restrict__ gacc,
+                                                   float2 *__restrict__ Afar)
+{
+    if (!meta[0]) return;
+    const uint32_t m = min(*far_count, (uint32_t)n);
+    const int shift = ft_shift(meta);
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < m; i += gridDim.x * 256u) {
+        const uint32_t row = min(far_rows[i], (uint32_t)n - 1u);
+        const double ax = gacc[2 * (size_t)row], ay = gacc[2 * (size_t)row + 1];
+        gacc[2 * (size_t)row] = 0.0;
+        gacc[2 * (size_t)row + 1] = 0.0;
+        Afar[row] = make_float2((float)ldexp(ax, -shift), (float)ldexp(ay, -shift));
+    }
+}
+
+hipError_t attract_far_tiled_prepare()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attract_far_tiled), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)FT_LDS);
+}
+
 #ifndef FAR_BLOCKS
 #define FAR_BLOCKS 1024
 #endif
@@ -322,6 +466,21 @@ static void attract_shares(const tsne_ctx *c, int *k1, int *k2)
     const int tiles = (n + AN_ROWS - 1) / AN_ROWS;
     *k2 = max(1, min(min(per_cu * c->num_cu, ATTRACT_MAX_PARTS / 2), tiles));
     *k1 = c->p.attract_early > 0 ? max(1, min(c->num_cu / 4, tiles)) : 0;
+}
+
+// The far part from its tiles (the kernels return at once when the tiles are not in use).  A small
+// far part is summed beside the tree build; the tile kernels are heavy and go beside the walk.
+static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
+{
+    const int n = c->p.n;
+    // enough workgroups to fill the chip: a row tile's entries are shared out when there are few row tiles
+    const int nrt = (n + FT_ROWS - 1) / FT_ROWS;
+    const int split = max(1, min(64, (8 * c->num_cu + nrt - 1) / nrt));
+    hipLaunchKernelGGL(ft_extent_k, dim3(1), dim3(256), 0, s, c->bbox_part, c->bbox_nparts, c->ft_meta);
+    hipLaunchKernelGGL(attract_far_tiled, dim3((unsigned)nrt, (unsigned)split), dim3(FT_THREADS), FT_LDS, s, c->ft_ptr,
+                       c->ft_col, c->ft_row, c->ft_val, c->Yi, n, c->ft_nct, c->ft_meta, c->ft_acc);
+    hipLaunchKernelGGL(ft_finish_k, dim3((unsigned)min((n + 255) / 256, 1024)), dim3(256), 0, s, c->far_rows, c->far_count, n,
+                       c->ft_meta, c->ft_acc, c->Afar);
 }
 
 hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s)
@@ -336,7 +495,8 @@ hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s)
         c->arow_valid = 1;
     }
     hipLaunchKernelGGL(attract_far, dim3((unsigned)min((n + 15) / 16, FAR_BLOCKS)), dim3(256), 0, s, c->rp_far, c->col_far,
-                       c->val_s, c->Yi, n, c->far_rows, c->far_count, c->Afar);
+                       c->val_s, c->Yi, n, c->far_rows, c->far_count, c->Afar, c->ft_tiles > 0 ? c->ft_meta : nullptr);
+    if (c->ft_tiles > 0 && !*c->ft_host) launch_far_tiles(c, s);
     if (k1 > 0)
         hipLaunchKernelGGL(attract_near, dim3(k1), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
                            (const float4 *)c->val_s, c->Yi, n, c->arow, 0, c->rp_far, c->Afar, c->A);
@@ -349,6 +509,7 @@ hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s)
     if (c->reorder_on && !c->identity) {
         int k1, k2;
         attract_shares(c, &k1, &k2);
+        if (c->ft_tiles > 0 && *c->ft_host) launch_far_tiles(c, s);
         hipLaunchKernelGGL(attract_near, dim3(k2), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
                            (const float4 *)c->val_s, c->Yi, n, c->arow, k1, c->rp_far, c->Afar, c->A);
     } else {

@@ -11,6 +11,8 @@
 // order of the entries inside each part of a row are those of the caller's P.
 #include "tsne_internal.h"
 
+#include <algorithm>
+
 // position p of the new order takes over old slot s = perm[p]
 __global__ __launch_bounds__(256) void reorder_state_k(const uint32_t *__restrict__ perm, int n,
                                                        const uint32_t *__restrict__ orig_in, uint32_t *__restrict__ orig_out,
@@ -134,6 +136,75 @@ __global__ __launch_bounds__(256) void split_fill_k(const uint32_t *__restrict__
     }
 }
 
+
+// ---- the far part once more, bucketed by tiles (for attract_far_tiled)
+// meta: [0] tiles in use, [1] largest value of P (bits of a non-negative float), [2] longest far row.
+__global__ void ft_begin_k(uint32_t *meta) { meta[0] = 0u; meta[1] = 0u; meta[2] = 0u; }
+
+__global__ __launch_bounds__(256) void ft_stats_k(const float *__restrict__ uval, int64_t nnz,
+                                                  const int32_t *__restrict__ len_far, int n, uint32_t *meta)
+{
+    uint32_t pm = 0u, lm = 0u;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < nnz; e += stride) {
+        const float v = uval[e];
+        if (v > 0.f) pm = max(pm, __float_as_uint(v));
+    }
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) lm = max(lm, (uint32_t)len_far[i]);
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) {
+        pm = max(pm, (uint32_t)__shfl_xor((int)pm, o, WAVE));
+        lm = max(lm, (uint32_t)__shfl_xor((int)lm, o, WAVE));
+    }
+    if (lane_id() == 0) {
+        if (pm) atomicMax(meta + 1, pm);
+        if (lm) atomicMax(meta + 2, lm);
+    }
+}
+
+// mode: 0 = tiles if the far part is at least an eighth of the entries and there are at least 2^18 points
+// (below that all of Y stays in the second-level cache and the row-by-row kernel is as fast), 2 = always
+__global__ void ft_decide_k(const int32_t *__restrict__ rp_far, int n, int64_t nnz, int mode, uint32_t *meta)
+{
+    const int64_t far_total = (int64_t)rp_far[n] - rp_far[0];
+    meta[0] = far_total > 0 && (mode == 2 || (far_total * 8 >= nnz && n >= (1 << 18))) ? 1u : 0u;
+}
+
+__global__ __launch_bounds__(256) void ft_zero_k(uint32_t *__restrict__ cnt, int64_t tiles, const uint32_t *meta)
+{
+    if (!meta[0]) return;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < tiles; t += stride) cnt[t] = 0u;
+}
+
+// 16 lanes per row; FILL: place the entries (the counts of ft_count run down to 0 as positions are handed out)
+template <bool FILL>
+__global__ __launch_bounds__(256) void ft_scatter_k(const int32_t *__restrict__ rp_far, const int32_t *__restrict__ col_far,
+                                                    const float *__restrict__ val_s, int n, int nct,
+                                                    uint32_t *__restrict__ cnt, const int32_t *__restrict__ ptr,
+                                                    int32_t *__restrict__ tcol, uint16_t *__restrict__ trow,
+                                                    float *__restrict__ tval, const uint32_t *meta)
+{
+    if (!meta[0]) return;
+    const int p = (int)((blockIdx.x * 256u + threadIdx.x) / 16);
+    const int sub = (int)(threadIdx.x % 16);
+    if (p >= n) return;
+    const int far0 = rp_far[0];
+    const int64_t tile0 = (int64_t)(p / FT_ROWS) * nct;
+    for (int e = rp_far[p] + sub; e < rp_far[p + 1]; e += 16) {
+        const uint32_t cs = min((uint32_t)col_far[e - far0], (uint32_t)n - 1u);
+        const int64_t t = tile0 + cs / FT_COLS;
+        if (!FILL) atomicAdd(cnt + t, 1u);
+        else {
+            const uint32_t left = atomicSub(cnt + t, 1u);      // any order inside the tile
+            const int pos = ptr[t] + (int)left - 1;
+            tcol[pos] = (int32_t)cs;
+            trow[pos] = (uint16_t)(p % FT_ROWS);
+            tval[pos] = val_s[e];
+        }
+    }
+}
+
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s)
 {
     const int n = c->p.n;
@@ -149,6 +220,20 @@ hipError_t launch_reorder(tsne_ctx *c, hipStream_t s)
     hipLaunchKernelGGL(scan_len_k, dim3(1), dim3(1024), 0, s, c->len_far, n, (const int32_t *)(c->rp_near + n), c->rp_far);
     hipLaunchKernelGGL(split_fill_k, dim3(blocks), dim3(256), 0, s, c->orig[b], c->inv, n, c->user_row_ptr, c->user_col,
                        c->user_val, c->rp_near, c->rp_far, c->col_near, c->col_far, c->val_s);
+    if (c->ft_tiles > 0) {
+        const unsigned sblocks = (unsigned)std::min<int64_t>(4096, (std::max<int64_t>(c->nnz, n) + 255) / 256);
+        const unsigned zblocks = (unsigned)std::min<int64_t>(4096, (c->ft_tiles + 255) / 256);
+        hipLaunchKernelGGL(ft_begin_k, dim3(1), dim3(1), 0, s, c->ft_meta);
+        hipLaunchKernelGGL(ft_stats_k, dim3(sblocks), dim3(256), 0, s, c->user_val, c->nnz, c->len_far, n, c->ft_meta);
+        hipLaunchKernelGGL(ft_decide_k, dim3(1), dim3(1), 0, s, c->rp_far, n, c->nnz, c->p.far_tiles, c->ft_meta);
+        hipLaunchKernelGGL(ft_zero_k, dim3(zblocks), dim3(256), 0, s, c->ft_cnt, c->ft_tiles, c->ft_meta);
+        hipLaunchKernelGGL(ft_scatter_k<false>, dim3(blocks), dim3(256), 0, s, c->rp_far, c->col_far, c->val_s, n, c->ft_nct,
+                           c->ft_cnt, c->ft_ptr, c->ft_col, c->ft_row, c->ft_val, c->ft_meta);
+        hipLaunchKernelGGL(scan_len_k, dim3(1), dim3(1024), 0, s, (const int32_t *)c->ft_cnt, (int)c->ft_tiles,
+                           (const int32_t *)nullptr, c->ft_ptr);
+        hipLaunchKernelGGL(ft_scatter_k<true>, dim3(blocks), dim3(256), 0, s, c->rp_far, c->col_far, c->val_s, n, c->ft_nct,
+                           c->ft_cnt, c->ft_ptr, c->ft_col, c->ft_row, c->ft_val, c->ft_meta);
+    }
     hipError_t e = launch_iota(c->row_order, n, s);
     if (e != hipSuccess) return e;
     c->cur_state = b;

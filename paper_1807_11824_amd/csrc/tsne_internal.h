@@ -45,6 +45,9 @@ static_assert(ATTRACT_RING * 8 <= 65536, "ring offsets are stored in 16 bits");
 constexpr int ATTRACT_CHUNK = 32;        // near rows are padded to a multiple of this many entries
 constexpr int ATTRACT_SLACK = 64;        // entries readable past the end of col_s / val_s
 constexpr int ATTRACT_MAX_PARTS = 16384; // most resident workgroups of the attraction kernel
+constexpr int FT_ROWS = 4096;            // rows of a tile of the bucketed copy of the far part
+constexpr int FT_COLS = 2048;            // columns of such a tile
+constexpr int64_t FT_MAX_TILES = (int64_t)1 << 27;
 
 struct tsne_ctx {
     tsne_params p;
@@ -73,6 +76,19 @@ struct tsne_ctx {
     uint32_t *far_rows, *far_count;   // the rows that have a far part (any order), and how many
     float2 *Afar;                     // their far sums, by row
     float *val_s;
+    // the far part once more, bucketed by tiles of FT_ROWS x FT_COLS (row tile major); an entry is
+    // (column, row within the row tile, value), in any order inside its tile
+    int64_t ft_tiles;                 // number of tiles, 0 if the context has no room for them
+    int ft_nct;                       // column tiles per row
+    uint32_t *ft_cnt;                 // per tile: entries not yet placed (0 outside ft_fill_k)
+    int32_t *ft_ptr;                  // per tile: first entry (+ end)
+    int32_t *ft_col;
+    uint16_t *ft_row;
+    float *ft_val;
+    double *ft_acc;                   // row sums in fixed point (integer-valued doubles), (x, y) per row; zero between steps
+    volatile uint32_t *ft_host;       // pinned host copy of ft_meta[0], refreshed (asynchronously) after every renumbering;
+                                      // it only decides where in the step the tile kernels are launched
+    uint32_t *ft_meta;                // [0] tiles in use, [1] largest P value (bits), [2] longest far row, [3] extent of Y (bits)
     float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
     float4 *bbox_part;   // (min, max) pairs of the bounding box, one per workgroup of the kernel that made them
@@ -111,6 +127,12 @@ struct tsne_ctx {
 };
 
 // ---- launchers (each enqueues on the given stream and returns the launch error) ----
+inline bool ft_possible(const tsne_params *p)
+{
+    const int64_t nrt = ((int64_t)p->n + FT_ROWS - 1) / FT_ROWS, nct = ((int64_t)p->n + FT_COLS - 1) / FT_COLS;
+    return p->far_tiles != 1 && nrt * nct <= FT_MAX_TILES;
+}
+hipError_t attract_far_tiled_prepare();   // once per process, before the first launch
 hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s);
 hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);

@@ -241,6 +241,41 @@ def test_near_and_far_parts_against_the_oracle():
     assert np.array_equal(R, R2) or rel_l2(R, R2) <= 1e-6
 
 
+def _random_csr(n, k, seed):
+    """Symmetric CSR with k random columns per row anywhere in the matrix: no band under any numbering."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(seed)
+    rows = np.repeat(np.arange(n), k)
+    cols = rng.integers(0, n, size=n * k)
+    keep = cols != rows
+    w = rng.random(rows.size) + 0.1
+    M = sp.coo_matrix((w[keep], (rows[keep], cols[keep])), shape=(n, n)).tocsr()
+    M = M + M.T
+    M.sum_duplicates(); M.sort_indices()
+    M = M / M.sum()
+    return M.indptr.astype(np.int32), M.indices.astype(np.int32), M.data.astype(np.float32)
+
+
+@pytest.mark.parametrize("n,k", [(20_000, 12), (4097, 12), (270_000, 5)])
+def test_far_part_from_tiles(n, k):
+    """P without structure: nearly every entry is far from the diagonal.  The bucketed copy (tiles of 4096 rows
+    x 2048 columns, fixed-point row sums) against the oracle, against the row-by-row kernel, chosen automatically,
+    and the same bits on every run and stream layout."""
+    rp, col, val = _random_csr(n, k, seed=n)
+    Y = synth.clustered_embedding(n, n_clusters=40, seed=5)
+    Ao = oracle.attract(Y, rp, col, val.astype(np.float64))
+    A_rows, _, _, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, far_tiles=1)
+    assert st == 0 and rel_l2(A_rows, Ao) <= 1e-6
+    A_tiles, _, _, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, far_tiles=2)
+    assert st == 0 and rel_l2(A_tiles, Ao) <= 1e-6
+    assert rel_l2(A_tiles, A_rows) <= 1e-6
+    for params in (dict(far_tiles=2), dict(far_tiles=0), dict(far_tiles=2, overlap=0), dict(far_tiles=0, overlap=3)):
+        if params.get("far_tiles") == 0 and n < (1 << 18):
+            continue        # the automatic choice stays with the row-by-row kernel below 2^18 points
+        A, _, _, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, **params)
+        assert st == 0 and np.array_equal(A, A_tiles), params
+
+
 def test_launch_shapes_change_nothing():
     """Stream layout (overlap 0-3), resident or one-wave-per-group walk, share of the attraction started early:
     every output of tsne_gradient is bitwise the same."""
