@@ -386,17 +386,17 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     // Entries past the end of the share are read as the share's last entry with weight 0 (they add 0).
     // The entries of the next trip are requested before the gathers of this one.
     const uint32_t last = (uint32_t)s1 - 1u;
-    uint32_t ncj[FT_UNROLL], nrl[FT_UNROLL];
+    int32_t ncj[FT_UNROLL];
+    uint16_t nrl[FT_UNROLL];
     float nv[FT_UNROLL];
     auto fetch = [&](uint32_t e0) {
 #pragma unroll
         for (int u = 0; u < FT_UNROLL; ++u) {
             const uint32_t e = e0 + (uint32_t)u * FT_THREADS, ec = min(e, last);
             // (read once: kept out of the way of the lines of Y in the first-level cache)
-            ncj[u] = (uint32_t)__builtin_nontemporal_load(tcol + ec);
-            nrl[u] = (uint32_t)__builtin_nontemporal_load(trow + ec);
-            const float val = __builtin_nontemporal_load(tval + ec);
-            nv[u] = e <= last ? val : 0.f;
+            ncj[u] = __builtin_nontemporal_load(tcol + ec);
+            nrl[u] = __builtin_nontemporal_load(trow + ec);
+            nv[u] = __builtin_nontemporal_load(tval + ec);     // (nothing here uses what it loads)
         }
     };
     fetch((uint32_t)s0 + tid);
@@ -406,12 +406,16 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
         float2 yi[FT_UNROLL], yj[FT_UNROLL];
 #pragma unroll
         for (int u = 0; u < FT_UNROLL; ++u) {
-            rl[u] = min(nrl[u], (uint32_t)FT_ROWS - 1u);
-            v[u] = nv[u];
-            yj[u] = Y[min(ncj[u], (uint32_t)n - 1u)];
+            rl[u] = min((uint32_t)nrl[u], (uint32_t)FT_ROWS - 1u);
+            v[u] = e0 + (uint32_t)u * FT_THREADS <= last ? nv[u] : 0.f;
+            yj[u] = Y[min((uint32_t)ncj[u], (uint32_t)n - 1u)];
             yi[u] = Y[min((uint32_t)row0 + rl[u], (uint32_t)n - 1u)];
         }
+        // the memory counter is in order: all gathers go out before the next trip's entries are
+        // requested, so that waiting for the gathers does not wait for those as well
+        __builtin_amdgcn_sched_barrier(0);
         fetch(e0 + FT_THREADS * FT_UNROLL);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < FT_UNROLL; ++u) {
             const float dx = yi[u].x - yj[u].x, dy = yi[u].y - yj[u].y;
@@ -427,8 +431,10 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) {
         const uint32_t r = t / 2, slot = r ^ ((r >> 5) & 31u);
         const double a = acc[(t & 1u) * FT_ROWS + slot];
-        if (a != 0.0 && row0 + (int)r < n)
-            (void)__builtin_amdgcn_global_atomic_fadd_f64((ft_glb_f64 *)(gacc + 2 * (size_t)row0 + t), a);
+        if (a != 0.0 && row0 + (int)r < n) {
+            if (gridDim.y == 1) gacc[2 * (size_t)row0 + t] = a;      // the only workgroup of this row tile
+            else (void)__builtin_amdgcn_global_atomic_fadd_f64((ft_glb_f64 *)(gacc + 2 * (size_t)row0 + t), a);
+        }
     }
 }
 
