@@ -372,12 +372,17 @@ __global__ __attribute__((amdgpu_waves_per_eu(5))) __launch_bounds__(WAVE) void 
     }
 }
 
-// Z = sum of the per-group partial sums, in a fixed order (thread t takes groups t, t + 1024, ...).
+// Z = sum of the per-group partial sums, in a fixed order (thread t takes groups t, t + 1024, ...,
+// eight running sums so that eight loads are in flight, combined pairwise).
 __global__ __launch_bounds__(1024) void z_final(const double *__restrict__ zpart, int ngroups, double *__restrict__ Z)
 {
     __shared__ double ws[16];
-    double a = 0.0;
-    for (int i = (int)threadIdx.x; i < ngroups; i += 1024) a += zpart[i];
+    double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int i = (int)threadIdx.x; i < ngroups; i += 8 * 1024) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] += i + 1024 * k < ngroups ? zpart[i + 1024 * k] : 0.0;
+    }
+    double a = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
     a = wave_sum(a);
     if (lane_id() == 0) ws[threadIdx.x >> 6] = a;
     __syncthreads();
