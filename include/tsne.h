@@ -99,8 +99,9 @@ typedef struct {
                                      the row sums kept in fixed point in LDS (integer-valued doubles: every
                                      addition is exact, so the result does not depend on the order of the
                                      entries).
-                                     0: chosen at tsne_set_P: tiles if the far part holds at least an eighth
-                                     of the entries and n >= 2^18, rows otherwise.  (0) */
+                                     0: chosen at tsne_set_P: tiles if the far part holds at least half of
+                                     the entries and n >= 2^18, rows otherwise; the choice is kept through
+                                     later renumberings (reorder_every).  (0) */
     int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
                                      20 bytes per entry plus 202 bytes per point (rows are padded) plus 8 bytes
                                      per pair of a 4096-row and a 2048-column tile (n^2 / 2^20).  0 disables
@@ -155,7 +156,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
 /* Hands a CSR matrix P (n rows, int32 indices, float values, all on the device) to the context.
  * Borrowed: it must outlive every later call on the context (with renumbering on, the library works
  * from a relabelled private copy but still reads the original for tsne_kl).  With renumbering on,
- * nnz must not exceed max_nnz.  Column indices must lie in [0, n). */
+ * nnz must not exceed max_nnz.  Column indices must lie in [0, n).  With renumbering on and
+ * far_tiles = 0 or 2 the call waits for the stream (it reads back which kernel will take the far part). */
 int tsne_set_P(tsne_ctx *ctx, const int32_t *d_row_ptr, const int32_t *d_col, const float *d_val, int64_t nnz);
 
 /* Resets the optimiser state: velocity = 0, gains = 1 (enqueued). */

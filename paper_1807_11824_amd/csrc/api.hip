@@ -316,8 +316,7 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
         }
     }
     if (c->ft_tiles > 0 &&
-        ((e = hipHostMalloc((void **)&c->ft_host, sizeof(uint32_t), hipHostMallocDefault)) != hipSuccess ||
-         (*c->ft_host = 0u, e = attract_far_tiled_prepare()) != hipSuccess ||
+        ((e = attract_far_tiled_prepare()) != hipSuccess ||
          (e = hipMemsetAsync(c->ft_cnt, 0, 4 * (size_t)c->ft_tiles, c->stream)) != hipSuccess ||
          (e = hipMemsetAsync(c->ft_acc, 0, 16 * (size_t)p->n, c->stream)) != hipSuccess ||
          (e = hipMemsetAsync(c->ft_meta, 0, 32, c->stream)) != hipSuccess)) {
@@ -344,7 +343,6 @@ void tsne_destroy(tsne_ctx *c)
     if (c->ev_fork2) (void)hipEventDestroy(c->ev_fork2);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     free_timing(c);
-    if (c->ft_host) (void)hipHostFree((void *)c->ft_host);
     delete c;
 }
 
@@ -362,10 +360,21 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     c->have_P = 1;
     if (c->reorder_on && c->p.graph_order_iters > 0 && nnz > 0) {
         hipError_t e;
-        if ((e = launch_graph_order(c, c->stream)) != hipSuccess || (e = launch_reorder(c, c->stream)) != hipSuccess ||
-            (c->ft_tiles > 0 && (e = hipMemcpyAsync((void *)c->ft_host, c->ft_meta, sizeof(uint32_t), hipMemcpyDeviceToHost,
-                                                    c->stream)) != hipSuccess))
+        if ((e = launch_graph_order(c, c->stream)) != hipSuccess ||
+            (e = launch_reorder(c, c->stream, c->ft_tiles > 0 ? c->p.far_tiles : 1)) != hipSuccess)
             return fail_hip(c, e, "graph order");
+        // which kernel takes the far part is settled here, once per P, so that a run is reproducible:
+        // later renumberings keep the choice
+        c->ft_active = 0;
+        if (c->ft_tiles > 0) {
+            uint32_t in_use = 0u;
+            if ((e = hipMemcpyAsync(&in_use, c->ft_meta, sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream)) != hipSuccess ||
+                (e = hipStreamSynchronize(c->stream)) != hipSuccess)
+                return fail_hip(c, e, "graph order");
+            c->ft_active = in_use ? 1 : 0;
+        }
+    } else {
+        c->ft_active = c->ft_tiles > 0 && c->p.far_tiles == 2;
     }
     return TSNE_OK;
 }
@@ -423,10 +432,7 @@ int step_impl(tsne_ctx *c, float *d_Y, int32_t iter, bool cached, bool keep)
     if (c->reorder_on && c->p.reorder_every > 0 && ++c->steps_since_reorder >= c->p.reorder_every) {
         c->steps_since_reorder = 0;
         c->yi_fresh = 0;      // the slots are renumbered: Yi is stale
-        if ((e = launch_reorder(c, c->stream)) != hipSuccess ||
-            (c->ft_tiles > 0 && (e = hipMemcpyAsync((void *)c->ft_host, c->ft_meta, sizeof(uint32_t), hipMemcpyDeviceToHost,
-                                                    c->stream)) != hipSuccess))
-            return fail_hip(c, e, "reorder");
+        if ((e = launch_reorder(c, c->stream, c->ft_active ? 2 : 1)) != hipSuccess) return fail_hip(c, e, "reorder");
     }
     return TSNE_OK;
 }

@@ -270,10 +270,8 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
 __global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
                                                    const float *__restrict__ val, const float2 *__restrict__ Y, int n,
                                                    const uint32_t *__restrict__ far_rows,
-                                                   const uint32_t *__restrict__ far_count, float2 *__restrict__ Afar,
-                                                   const uint32_t *__restrict__ tiled)
+                                                   const uint32_t *__restrict__ far_count, float2 *__restrict__ Afar)
 {
-    if (tiled && tiled[0]) return;      // the bucketed copy is in use (attract_far_tiled)
     const int sub = (int)(threadIdx.x % 16);
     const uint32_t m = min(*far_count, (uint32_t)n);
     const int far0 = rp[0];      // values sit behind the near part, columns start at 0
@@ -474,8 +472,8 @@ static void attract_shares(const tsne_ctx *c, int *k1, int *k2)
     *k1 = c->p.attract_early > 0 ? max(1, min(c->num_cu / 4, tiles)) : 0;
 }
 
-// The far part from its tiles (the kernels return at once when the tiles are not in use).  A small
-// far part is summed beside the tree build; the tile kernels are heavy and go beside the walk.
+// The far part from its tiles.  A small far part is summed row by row beside the tree build; the
+// tile kernels are heavy and go beside the walk.
 static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
 {
     const int n = c->p.n;
@@ -500,9 +498,9 @@ hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s)
                            c->p.attract_early, c->arow);
         c->arow_valid = 1;
     }
-    hipLaunchKernelGGL(attract_far, dim3((unsigned)min((n + 15) / 16, FAR_BLOCKS)), dim3(256), 0, s, c->rp_far, c->col_far,
-                       c->val_s, c->Yi, n, c->far_rows, c->far_count, c->Afar, c->ft_tiles > 0 ? c->ft_meta : nullptr);
-    if (c->ft_tiles > 0 && !*c->ft_host) launch_far_tiles(c, s);
+    if (!c->ft_active)
+        hipLaunchKernelGGL(attract_far, dim3((unsigned)min((n + 15) / 16, FAR_BLOCKS)), dim3(256), 0, s, c->rp_far, c->col_far,
+                           c->val_s, c->Yi, n, c->far_rows, c->far_count, c->Afar);
     if (k1 > 0)
         hipLaunchKernelGGL(attract_near, dim3(k1), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
                            (const float4 *)c->val_s, c->Yi, n, c->arow, 0, c->rp_far, c->Afar, c->A);
@@ -515,7 +513,7 @@ hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s)
     if (c->reorder_on && !c->identity) {
         int k1, k2;
         attract_shares(c, &k1, &k2);
-        if (c->ft_tiles > 0 && *c->ft_host) launch_far_tiles(c, s);
+        if (c->ft_active) launch_far_tiles(c, s);
         hipLaunchKernelGGL(attract_near, dim3(k2), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
                            (const float4 *)c->val_s, c->Yi, n, c->arow, k1, c->rp_far, c->Afar, c->A);
     } else {

@@ -162,12 +162,14 @@ __global__ __launch_bounds__(256) void ft_stats_k(const float *__restrict__ uval
     }
 }
 
-// mode: 0 = tiles if the far part is at least an eighth of the entries and there are at least 2^18 points
-// (below that all of Y stays in the second-level cache and the row-by-row kernel is as fast), 2 = always
+// mode: 0 = tiles if the far part is at least half of the entries and there are at least 2^18 points
+// (below that all of Y stays in the second-level cache and the row-by-row kernel is as fast; a far part
+// that is a minority -- clusters a little wider than the band -- is quicker row by row beside the tree
+// build: measured on the 400,000-point, 200-cluster workload), 1 = never, 2 = always
 __global__ void ft_decide_k(const int32_t *__restrict__ rp_far, int n, int64_t nnz, int mode, uint32_t *meta)
 {
     const int64_t far_total = (int64_t)rp_far[n] - rp_far[0];
-    meta[0] = far_total > 0 && (mode == 2 || (far_total * 8 >= nnz && n >= (1 << 18))) ? 1u : 0u;
+    meta[0] = far_total > 0 && (mode == 2 || (mode == 0 && far_total * 2 >= nnz && n >= (1 << 18))) ? 1u : 0u;
 }
 
 __global__ __launch_bounds__(256) void ft_zero_k(uint32_t *__restrict__ cnt, int64_t tiles, const uint32_t *meta)
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(256) void ft_scatter_k(const int32_t *__restrict__ 
     }
 }
 
-hipError_t launch_reorder(tsne_ctx *c, hipStream_t s)
+hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode)
 {
     const int n = c->p.n;
     const uint32_t *perm = c->idx[c->sorted_buf];
@@ -225,7 +227,7 @@ hipError_t launch_reorder(tsne_ctx *c, hipStream_t s)
         const unsigned zblocks = (unsigned)std::min<int64_t>(4096, (c->ft_tiles + 255) / 256);
         hipLaunchKernelGGL(ft_begin_k, dim3(1), dim3(1), 0, s, c->ft_meta);
         hipLaunchKernelGGL(ft_stats_k, dim3(sblocks), dim3(256), 0, s, c->user_val, c->nnz, c->len_far, n, c->ft_meta);
-        hipLaunchKernelGGL(ft_decide_k, dim3(1), dim3(1), 0, s, c->rp_far, n, c->nnz, c->p.far_tiles, c->ft_meta);
+        hipLaunchKernelGGL(ft_decide_k, dim3(1), dim3(1), 0, s, c->rp_far, n, c->nnz, tiles_mode, c->ft_meta);
         hipLaunchKernelGGL(ft_zero_k, dim3(zblocks), dim3(256), 0, s, c->ft_cnt, c->ft_tiles, c->ft_meta);
         hipLaunchKernelGGL(ft_scatter_k<false>, dim3(blocks), dim3(256), 0, s, c->rp_far, c->col_far, c->val_s, n, c->ft_nct,
                            c->ft_cnt, c->ft_ptr, c->ft_col, c->ft_row, c->ft_val, c->ft_meta);

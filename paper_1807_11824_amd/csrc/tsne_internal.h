@@ -86,8 +86,7 @@ struct tsne_ctx {
     uint16_t *ft_row;
     float *ft_val;
     double *ft_acc;                   // row sums in fixed point (integer-valued doubles), (x, y) per row; zero between steps
-    volatile uint32_t *ft_host;       // pinned host copy of ft_meta[0], refreshed (asynchronously) after every renumbering;
-                                      // it only decides where in the step the tile kernels are launched
+    int ft_active;                    // the tiles are in use (decided at tsne_set_P, kept through later renumberings)
     uint32_t *ft_meta;                // [0] tiles in use, [1] largest P value (bits), [2] longest far row, [3] extent of Y (bits)
     float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
@@ -141,7 +140,7 @@ hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s);
 hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, int write_user,
                          hipStream_t s);
-hipError_t launch_reorder(tsne_ctx *c, hipStream_t s);
+hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode);   // tiles_mode: 0 decide, 1 rows, 2 tiles
 hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in idx[sorted_buf]
 hipError_t launch_sort(tsne_ctx *c, int nbits, hipStream_t s);  // sorts keys[0]/idx[0]; result in [sorted_buf]
 hipError_t launch_scatter2(const float2 *in, const uint32_t *orig, float2 *out, int n, hipStream_t s);
