@@ -67,10 +67,11 @@ __global__ __launch_bounds__(256) void row_norms(const float *__restrict__ X, in
     if (lane_id() == 0) norms[row] = (float)s;
 }
 
-__global__ void knn_reset(float *__restrict__ tau, int *__restrict__ cnt, int rows)
+__global__ void knn_reset(float *__restrict__ tau, int *__restrict__ cnt, int rows, int *__restrict__ ccount)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < rows) { tau[i] = INFINITY; cnt[i] = 0; }
+    if (i < 2) ccount[i] = 0;
 }
 
 // ---- the distance tiles
@@ -377,7 +378,9 @@ template <int NS>
 __global__ __launch_bounds__(512, 1) void knn_tile_resident(const uint4 *__restrict__ Xs, int q0, int qend, int j0, int jend,
                                                             const float *__restrict__ norms,
                                                             const float *__restrict__ tau, int *__restrict__ cnt,
-                                                            uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
+                                                            uint64_t *__restrict__ cand, int cap, int kp, int force,
+                                                            int *__restrict__ clist, int *__restrict__ ccount,
+                                                            int *__restrict__ ccount_next)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *Bs = smem;                                   // [2 groups][NS][RT] rows
@@ -388,7 +391,7 @@ __global__ __launch_bounds__(512, 1) void knn_tile_resident(const uint4 *__restr
     const int r32 = lane & 31, h = lane >> 5, sw = swz(r32);
     const int qa = q0 + blockIdx.x * RQ;
     constexpr int row16 = NS * 8;          // 16-byte pieces per row of Xs
-    if (blockIdx.x == 0 && tid == 0) *ccount = 0;   // for the compaction pass that follows
+    if (blockIdx.x == 0 && tid == 0) *ccount_next = 0;   // the list of the next launch (nobody reads it any more)
     // the wave's query fragments: [block][slab][step] high and low parts, as the matrix cores take them
     bf16x8 afh[2][NS][2], afl[2][NS][2];
 #pragma unroll
@@ -529,9 +532,17 @@ __global__ __launch_bounds__(512, 1) void knn_tile_resident(const uint4 *__restr
     }
     if (g == 1 && have) test_tile();
     lds_barrier();
+    // the fill counts go back, and the rows whose buffers are due for compaction go on the list (the
+    // rule of knn_compact_list, which this kernel makes unnecessary)
     for (int t = tid; t < RQ; t += 512) {
         const int q = qa + t;
-        if (q < qend) cnt[q - q0] = qc[t];
+        if (q < qend) {
+            const int c = qc[t];
+            cnt[q - q0] = c;
+            const int cc = min(c, cap);
+            if (cc >= kp && (force || !(qd[t] < INFINITY) || cc >= kp + COMPACT_SLACK || cc + DBC > cap))
+                clist[atomicAdd(ccount, 1)] = q - q0;    // any order
+        }
     }
 }
 
@@ -934,7 +945,7 @@ struct Layout {
     int *cnt, *fail_count, *fail_rows, *extra, *cursor, *unconv;
     uint64_t *cand, *okey, *sort_scratch;
     uint16_t *xs;            // the split copy of X
-    int *clist, *ccount;     // rows of the current query block that need compaction, and how many
+    int *clist, *ccount;     // rows of the current query block that need compaction, and how many (two counters take turns)
     int32_t *knn_idx;
     double *knn_d2, *cond;
     int kp, cap;
@@ -960,7 +971,7 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
     q = take(4 * qb); if (L) L->tau = (float *)q;
     q = take(4 * qb); if (L) L->cnt = (int *)q;
     q = take(4 * qb); if (L) L->clist = (int *)q;
-    q = take(4); if (L) L->ccount = (int *)q;
+    q = take(8); if (L) L->ccount = (int *)q;
     q = take(4); if (L) L->fail_count = (int *)q;
     q = take(4 * (size_t)n); if (L) L->fail_rows = (int *)q;
     q = take(4 * (size_t)n); if (L) L->extra = (int *)q;
@@ -1038,34 +1049,39 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     const size_t rerank_smem = up((size_t)d * 4) + 8 * (size_t)MAX_KP;
     for (int q0 = 0; q0 < n; q0 += QB) {
         const int qend = q0 + QB < n ? q0 + QB : n, rows = qend - q0;
-        hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows);
+        hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows, L.ccount);
         // Until a row has k' candidates its cut-off is +inf and every pair is kept, and the pairs kept
         // right after are still many (a fraction k' / j0 of them).  Short first slabs get the cut-offs
         // down early: 256, 256, 512, 1024 rows, then DBC at a time.
         int step = kp + 64 <= 256 ? 256 : DBC;
-        for (int j0 = 0, jend; j0 < n; j0 = jend) {
+        int launch = 0;
+        for (int j0 = 0, jend; j0 < n; j0 = jend, ++launch) {
             jend = j0 + step < n ? j0 + step : n;
             if (jend > step && step < DBC) step *= 2;
             const unsigned gy = (unsigned)((jend - j0 + TN - 1) / TN);
+            const int force = jend >= n ? 1 : 0;
+            int *cc = L.ccount + (launch & 1), *cc_next = L.ccount + ((launch + 1) & 1);   // two lists take turns
             if (dp <= 2 * SLAB && rows >= RESIDENT_MIN_ROWS) {
                 if (dp == SLAB)
                     hipLaunchKernelGGL(knn_tile_resident<1>, dim3((rows + RQ - 1) / RQ), dim3(512), resident_lds_bytes(1), s,
-                                       (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount);
+                                       (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, kp, force,
+                                       L.clist, cc, cc_next);
                 else
                     hipLaunchKernelGGL(knn_tile_resident<2>, dim3((rows + RQ - 1) / RQ), dim3(512), resident_lds_bytes(2), s,
-                                       (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount);
-            } else if (d > KFLUSH)
-                hipLaunchKernelGGL((knn_tile_mfma<2, true>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
-                                   (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap,
-                                   L.ccount);
-            else
-                hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false>), dim3((rows + 32 * KNN_MB * 2 - 1) / (64 * KNN_MB), gy), dim3(256), 0, s,
-                                   (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap,
-                                   L.ccount);
-            hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows,
-                               jend >= n ? 1 : 0, L.clist, L.ccount);
-            hipLaunchKernelGGL(knn_compact, dim3(rows < 1024 ? rows : 1024), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap,
-                               kp, rows, L.clist, L.ccount);
+                                       (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, kp, force,
+                                       L.clist, cc, cc_next);
+            } else {
+                if (d > KFLUSH)
+                    hipLaunchKernelGGL((knn_tile_mfma<2, true>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
+                                       (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc);
+                else
+                    hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
+                                       0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc);
+                hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
+                                   L.clist, cc);
+            }
+            hipLaunchKernelGGL(knn_compact, dim3(rows < 1024 ? rows : 1024), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows,
+                               L.clist, cc);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, q0, rows, k, kp, L.norms,
                            norm_max, L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
