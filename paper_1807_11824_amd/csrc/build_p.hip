@@ -581,28 +581,39 @@ __global__ __launch_bounds__(256) void knn_compact_list(const float *__restrict_
     list[atomicAdd(count, 1)] = row;    // any order
 }
 
-__global__ __launch_bounds__(256) void knn_compact(float *__restrict__ tau, int *__restrict__ cnt,
-                                                   uint64_t *__restrict__ cand, int cap, int kp, int rows,
-                                                   const int *__restrict__ list, const int *__restrict__ count)
+// One workgroup per listed row: keeps the best k' of the row's candidates, sorted, and lowers the
+// cut-off to the k'-th.  The LDS buffer is sized for the usual case (k' and a few hundred new
+// candidates), so that many rows are in flight per compute unit; a longer buffer (the first slabs
+// of a query block) goes through it in several rounds, each keeping the best k' so far.
+template <int BUF, int THREADS>
+__global__ __launch_bounds__(THREADS) void knn_compact(float *__restrict__ tau, int *__restrict__ cnt,
+                                                       uint64_t *__restrict__ cand, int cap, int kp, int rows,
+                                                       const int *__restrict__ list, const int *__restrict__ count)
 {
-    __shared__ uint64_t s[SORT_CAP];
+    __shared__ uint64_t s[BUF];
     const int m = min(*count, rows);
     for (int i = blockIdx.x; i < m; i += gridDim.x) {
-    const int row = min(max(list[i], 0), rows - 1);
-    int c = cnt[row];
-    if (c > cap) c = cap;
-    __syncthreads();                    // the previous row of this workgroup is out of s
-    int size = 1;
-    while (size < c) size <<= 1;
-    uint64_t *buf = cand + (size_t)row * cap;
-    for (int t = threadIdx.x; t < size; t += blockDim.x) s[t] = t < c ? buf[t] : ~0ull;
-    __syncthreads();
-    bitonic_sort(s, size);
-    for (int t = threadIdx.x; t < kp; t += blockDim.x) buf[t] = s[t];
-    if (threadIdx.x == 0) {
-        cnt[row] = kp;
-        tau[row] = unorderable((uint32_t)(s[kp - 1] >> 32));
-    }
+        const int row = min(max(list[i], 0), rows - 1);
+        int c = cnt[row];
+        if (c > cap) c = cap;
+        uint64_t *buf = cand + (size_t)row * cap;
+        int done = 0, have = 0;         // candidates read so far; sorted survivors in s[0 .. have)
+        while (done < c) {
+            __syncthreads();            // the previous round (or row) is out of s
+            const int take = min(BUF - have, c - done), total = have + take;
+            int size = 1;
+            while (size < total) size <<= 1;
+            for (int t = threadIdx.x; t < size - have; t += THREADS) s[have + t] = t < take ? buf[done + t] : ~0ull;
+            __syncthreads();
+            bitonic_sort(s, size);
+            done += take;
+            have = min(total, kp);
+        }
+        for (int t = threadIdx.x; t < have; t += THREADS) buf[t] = s[t];
+        if (threadIdx.x == 0 && have > 0) {
+            cnt[row] = have;
+            tau[row] = have >= kp ? unorderable((uint32_t)(s[kp - 1] >> 32)) : tau[row];
+        }
     }
 }
 
@@ -1080,8 +1091,13 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, cc);
             }
-            hipLaunchKernelGGL(knn_compact, dim3(rows < 1024 ? rows : 1024), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows,
-                               L.clist, cc);
+            const unsigned cg = (unsigned)(rows < 4096 ? rows : 4096);
+            if (kp <= 320)
+                hipLaunchKernelGGL((knn_compact<512, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
+            else if (kp <= 832)
+                hipLaunchKernelGGL((knn_compact<1024, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
+            else
+                hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, q0, rows, k, kp, L.norms,
                            norm_max, L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
