@@ -142,7 +142,7 @@ void tsne_destroy(tsne_ctx *ctx);
  * checked against a bound on the candidate search's error; a row that cannot be certified is redone
  * exactly against all n rows, so the lists do not depend on the reduced precision.
  * Workspace: about 4 n (d rounded up to 32) bytes for the split copy of X, 20 n k for neighbour
- * lists and probabilities, 16 n k for sorting, and 8 * 65536 * (k' + 2112) with k' = k + max(k/2, 32)
+ * lists and probabilities, 16 n k for sorting, and 8 * 65536 * (k' + 4160) with k' = k + max(k/2, 32)
  * for the candidate buffers (tsne_build_P_workspace_bytes() gives the exact figure).
  * Limits: k' <= 1920, d <= 4096, 2 n k < 2^31.
  * Synchronises the stream before returning.

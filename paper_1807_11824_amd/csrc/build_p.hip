@@ -32,11 +32,13 @@ __host__ __device__ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN 
 
 constexpr int QB = 65536;       // query rows per pass
 constexpr int DBC = 2048;       // database rows per launch (bounds what one launch can append per row)
-constexpr int MAX_KP = 1920;    // k' limit: k' + COMPACT_SLACK + DBC must fit the LDS sort
+constexpr int MAX_KP = 1920;    // k' limit (size of the re-rank's LDS arrays)
 constexpr int SORT_CAP = 4096;  // candidate buffer entries per row = LDS sort size
 constexpr int TN = 128;         // database rows per tile
 constexpr int KNN_MB = 4;        // 32-row query blocks per wave of the general single-level tile kernel
 constexpr int COMPACT_SLACK = 64;  // new candidates per row that trigger a re-sort of its buffer
+constexpr int COMPACT_EVERY = 2;   // a compaction pass follows every second slab (a pass costs as much as a third of a
+                                   // slab; cut-offs that are one slab older let a few more pairs through)
 constexpr int KFLUSH = 64;      // columns summed on the matrix cores before a flush into the running sum
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -540,7 +542,7 @@ __global__ __launch_bounds__(512, 1) void knn_tile_resident(const uint4 *__restr
             const int c = qc[t];
             cnt[q - q0] = c;
             const int cc = min(c, cap);
-            if (cc >= kp && (force || !(qd[t] < INFINITY) || cc >= kp + COMPACT_SLACK || cc + DBC > cap))
+            if (cc >= kp && (force || !(qd[t] < INFINITY) || cc >= kp + COMPACT_SLACK || cc + COMPACT_EVERY * DBC > cap))
                 clist[atomicAdd(ccount, 1)] = q - q0;    // any order
         }
     }
@@ -577,7 +579,7 @@ __global__ __launch_bounds__(256) void knn_compact_list(const float *__restrict_
     if (c < kp) return;                 // not yet k' candidates: the cut-off stays +inf
     // sort only when enough new candidates have piled up to matter, when the next slab could
     // overflow the buffer, or at the end (force); in between the cut-off is merely a bit stale
-    if (!force && tau[row] < INFINITY && c < kp + COMPACT_SLACK && c + DBC <= cap) return;
+    if (!force && tau[row] < INFINITY && c < kp + COMPACT_SLACK && c + COMPACT_EVERY * DBC <= cap) return;
     list[atomicAdd(count, 1)] = row;    // any order
 }
 
@@ -974,7 +976,7 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
     size_t off = 0;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up(bytes); return (void *)p; };
     const int kp = margin_kp(n, k);
-    const int cap = kp + COMPACT_SLACK + DBC;   // <= SORT_CAP because kp <= MAX_KP
+    const int cap = kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
     const size_t qb = (size_t)(n < QB ? n : QB);
     void *q;
     q = take(4 * (size_t)n); if (L) L->norms = (float *)q;
@@ -1092,6 +1094,7 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                                    L.clist, cc);
             }
             const unsigned cg = (unsigned)(rows < 4096 ? rows : 4096);
+            if (!force && step >= DBC && launch % COMPACT_EVERY != COMPACT_EVERY - 1) continue;   // (the rows stay listed)
             if (kp <= 320)
                 hipLaunchKernelGGL((knn_compact<512, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
             else if (kp <= 832)
