@@ -37,8 +37,8 @@ constexpr int SORT_CAP = 4096;  // candidate buffer entries per row = LDS sort s
 constexpr int TN = 128;         // database rows per tile
 constexpr int KNN_MB = 4;        // 32-row query blocks per wave of the general single-level tile kernel
 constexpr int COMPACT_SLACK = 64;  // new candidates per row that trigger a re-sort of its buffer
-constexpr int COMPACT_EVERY = 2;   // a compaction pass follows every second slab (a pass costs as much as a third of a
-                                   // slab; cut-offs that are one slab older let a few more pairs through)
+constexpr int COMPACT_EVERY = 2;   // after the resident tile kernel a compaction pass follows every second slab only (a pass
+                                   // costs a third of a slab; cut-offs one slab older let a few more pairs through)
 constexpr int KFLUSH = 64;      // columns summed on the matrix cores before a flush into the running sum
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -456,14 +456,20 @@ __global__ __launch_bounds__(512, 1) void knn_tile_resident(const uint4 *__restr
                 for (int i4 = 0; i4 < 4; ++i4) {
                     const float4 d4 = *reinterpret_cast<const float4 *>(qd_l + a * 32 + 8 * i4);
                     const float dq[4] = {d4.x, d4.y, d4.z, d4.w};
+                    // four pairs per branch: a branch on a vector compare waits for the compare, and that
+                    // wait, not the arithmetic, is what a test costs (sixteen per branch: slower again,
+                    // the rare path is entered too often)
+                    bool near[4];
 #pragma unroll
-                    for (int ii = 0; ii < 4; ++ii) {
-                        const float dot = part[a][b][4 * i4 + ii];
-                        const bool near = fmaf(-2.0f, dot, nj) < dq[ii];
-                        if (__builtin_expect(__ballot(near) != 0, 0)) {
+                    for (int ii = 0; ii < 4; ++ii) near[ii] = fmaf(-2.0f, part[a][b][4 * i4 + ii], nj) < dq[ii];
+                    if (__builtin_expect(__ballot(near[0] || near[1] || near[2] || near[3]) != 0, 0)) {
+#pragma unroll
+                        for (int ii = 0; ii < 4; ++ii) {
+                            if (__ballot(near[ii]) == 0) continue;
+                            const float dot = part[a][b][4 * i4 + ii];
                             const int off = a * 32 + 8 * i4 + ii;
                             const int q = qa + lbase + off;
-                            if (near && j != q) {
+                            if (near[ii] && j != q) {
                                 const float dist = (qn_l[off] + nj) - 2.0f * dot;
                                 const int pos = atomicAdd(qc_l + off, 1);
                                 if (pos < cap)
@@ -1074,7 +1080,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
             const unsigned gy = (unsigned)((jend - j0 + TN - 1) / TN);
             const int force = jend >= n ? 1 : 0;
             int *cc = L.ccount + (launch & 1), *cc_next = L.ccount + ((launch + 1) & 1);   // two lists take turns
-            if (dp <= 2 * SLAB && rows >= RESIDENT_MIN_ROWS) {
+            const bool resident = dp <= 2 * SLAB && rows >= RESIDENT_MIN_ROWS;
+            if (resident) {
                 if (dp == SLAB)
                     hipLaunchKernelGGL(knn_tile_resident<1>, dim3((rows + RQ - 1) / RQ), dim3(512), resident_lds_bytes(1), s,
                                        (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, kp, force,
@@ -1094,7 +1101,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                                    L.clist, cc);
             }
             const unsigned cg = (unsigned)(rows < 4096 ? rows : 4096);
-            if (!force && step >= DBC && launch % COMPACT_EVERY != COMPACT_EVERY - 1) continue;   // (the rows stay listed)
+            // (every second slab after the resident kernel, where accepted pairs are cheap; the rows stay listed)
+            if (resident && !force && step >= DBC && launch % COMPACT_EVERY != COMPACT_EVERY - 1) continue;
             if (kp <= 320)
                 hipLaunchKernelGGL((knn_compact<512, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
             else if (kp <= 832)
