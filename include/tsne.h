@@ -102,6 +102,12 @@ typedef struct {
                                      0: chosen at tsne_set_P: tiles if the far part holds at least half of
                                      the entries and n >= 2^18, rows otherwise; the choice is kept through
                                      later renumberings (reorder_every).  (0) */
+    int32_t graphs;               /* 1: inside tsne_run the iterations that neither start nor end the call (nor
+                                     carry timing events, nor precede a renumbering) are replayed from a HIP
+                                     graph captured once per (exaggeration, momentum) phase instead of being
+                                     launched kernel by kernel.  Same kernels, same results; measured slower
+                                     than plain stream launches on every size tried (0.72 -> 0.77 ms per
+                                     iteration at 1.28M points, 0.157 -> 0.181 ms at 2000), hence off.  (0) */
     int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
                                      20 bytes per entry plus 202 bytes per point (rows are padded) plus 8 bytes
                                      per pair of a 4096-row and a 2048-column tile (n^2 / 2^20).  0 disables

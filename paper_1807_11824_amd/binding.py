@@ -29,7 +29,7 @@ class TsneParams(C.Structure):
                 ("gain_min", C.c_float), ("morton_bits", C.c_int32), ("leaf_cap", C.c_int32),
                 ("overlap", C.c_int32), ("graph_order_iters", C.c_int32), ("reorder_every", C.c_int32),
                 ("attract_resident", C.c_int32), ("walk_resident", C.c_int32), ("attract_early", C.c_int32),
-                ("far_tiles", C.c_int32), ("max_nnz", C.c_int64)]
+                ("far_tiles", C.c_int32), ("graphs", C.c_int32), ("max_nnz", C.c_int64)]
 
 
 _lib = None

@@ -122,6 +122,7 @@ int check_params(const tsne_params *p)
     if (p->walk_resident < 0 || p->walk_resident > 32) return TSNE_EINVAL;
     if (p->attract_early < 0 || p->attract_early > 90) return TSNE_EINVAL;
     if (p->far_tiles < 0 || p->far_tiles > 2) return TSNE_EINVAL;
+    if (p->graphs < 0 || p->graphs > 1) return TSNE_EINVAL;
     if (p->max_nnz < 0 || p->max_nnz > 0x7FFFFFFFll) return TSNE_EINVAL;
     // the renumbered copy pads every row to whole chunks and is indexed with int32
     if (p->max_nnz > 0 && p->max_nnz + (ATTRACT_CHUNK - 1ll) * p->n + ATTRACT_SLACK > 0x7FFFFFFFll) return TSNE_EINVAL;
@@ -267,6 +268,7 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->walk_resident = 14;
     p->attract_early = 0;
     p->far_tiles = 0;
+    p->graphs = 0;
     p->max_nnz = 0;
     return TSNE_OK;
 }
@@ -335,9 +337,18 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
     return TSNE_OK;
 }
 
+// The captured iterations hold pointers and launch shapes: P, the slot order or Y changing makes them stale.
+static void drop_graphs(tsne_ctx *c)
+{
+    for (int k = 0; k < 4; ++k)
+        if (c->gexec[k]) { (void)hipGraphExecDestroy(c->gexec[k]); c->gexec[k] = nullptr; c->g_Y[k] = nullptr; }
+}
+
 void tsne_destroy(tsne_ctx *c)
 {
     if (!c) return;
+    drop_graphs(c);
+    if (c->gstream) (void)hipStreamDestroy(c->gstream);
     if (c->stream2) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_fork2) (void)hipEventDestroy(c->ev_fork2);
@@ -354,6 +365,7 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     if (c->reorder_on && nnz > c->p.max_nnz) return fail(c, TSNE_ENOSPC, "tsne_set_P: nnz exceeds max_nnz");
     int rc = reset_slot_order(c);
     if (rc != TSNE_OK) return rc;
+    drop_graphs(c);
     c->user_row_ptr = d_row_ptr; c->user_col = d_col; c->user_val = d_val;
     c->nnz = nnz;
     c->arow_valid = 0;
@@ -501,7 +513,45 @@ int tsne_run(tsne_ctx *c, float *d_Y, int32_t iter0, int32_t n_iter)
     // Between the iterations of one call nobody else touches Y, so every update hands the next
     // iteration the embedding in slot order and its bounding box.
     for (int32_t it = iter0; it < iter0 + n_iter; ++it) {
-        int rc = step_impl(c, d_Y, it, it > iter0, it + 1 < iter0 + n_iter);
+        const bool cached = it > iter0, keep = it + 1 < iter0 + n_iter;
+        const bool counted = c->tev && c->t_used < c->t_cap;                  // as in step_impl
+        const bool timed = counted && (c->t_seen % c->t_every) == 0;
+        if (c->p.graphs && cached && keep && c->yi_fresh && !timed && !(c->reorder_on && c->p.reorder_every > 0)) {
+            // a middle iteration: replayed from the graph of its phase (captured on first use)
+            const int cls = (it < c->p.exaggeration_iters ? 1 : 0) | (it < c->p.momentum_switch_iter ? 2 : 0);
+            if (c->gexec[cls] && c->g_Y[cls] != d_Y) { (void)hipGraphExecDestroy(c->gexec[cls]); c->gexec[cls] = nullptr; }
+            if (!c->gexec[cls]) {
+                hipGraph_t g = nullptr;
+                hipError_t e = hipSuccess;
+                if (!c->gstream) e = hipStreamCreateWithFlags(&c->gstream, hipStreamNonBlocking);
+                if (e == hipSuccess) e = hipStreamBeginCapture(c->gstream, hipStreamCaptureModeThreadLocal);
+                int rc = TSNE_OK;
+                if (e == hipSuccess) {
+                    hipEvent_t *saved = c->tev;
+                    hipStream_t caller = c->stream;
+                    c->tev = nullptr;                                         // no timing events in the graph
+                    c->stream = c->gstream;
+                    rc = step_impl(c, d_Y, it, true, true);
+                    c->stream = caller;
+                    c->tev = saved;
+                    e = hipStreamEndCapture(c->gstream, &g);
+                }
+                if (e == hipSuccess && rc == TSNE_OK) e = hipGraphInstantiate(&c->gexec[cls], g, nullptr, nullptr, 0);
+                if (g) (void)hipGraphDestroy(g);
+                if (e != hipSuccess || rc != TSNE_OK) {
+                    c->gexec[cls] = nullptr;
+                    c->yi_fresh = 0;
+                    return rc != TSNE_OK ? rc : fail_hip(c, e, "graph capture");
+                }
+                c->g_Y[cls] = d_Y;
+            }
+            hipError_t e = hipGraphLaunch(c->gexec[cls], c->stream);
+            if (e != hipSuccess) { c->yi_fresh = 0; return fail_hip(c, e, "graph launch"); }
+            if (counted) c->t_seen++;
+            c->yi_fresh = 1;
+            continue;
+        }
+        int rc = step_impl(c, d_Y, it, cached, keep);
         if (rc != TSNE_OK) { c->yi_fresh = 0; return rc; }
     }
     c->yi_fresh = 0;

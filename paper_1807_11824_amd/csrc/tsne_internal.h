@@ -119,6 +119,10 @@ struct tsne_ctx {
     double *zpart, *Z;
     double *kl_part;
     int sorted_buf;      // which of keys[]/idx[] holds the sorted result
+    // tsne_run: one captured iteration per (exaggerated?, early momentum?) phase, valid for one Y pointer
+    hipGraphExec_t gexec[4];
+    float *g_Y[4];
+    hipStream_t gstream;           // the stream the capture is made on (the caller's may be the default stream, which cannot capture)
     // optional per-phase timing: 6 events per armed step
     hipEvent_t *tev;
     int t_cap, t_used;

@@ -143,8 +143,12 @@ def test_run_equals_repeated_steps_bitwise():
     dev = torch.device("cuda:0")
     X, _ = synth.gaussian_mixture(6000, 16, 12, 6.0, 1.0, seed=3)
     P = build_P(torch.from_numpy(X).to(dev), 20.0, 60)
-    for kw in (dict(), dict(max_nnz=P["nnz"]), dict(max_nnz=P["nnz"], reorder_every=4)):
-        a = Tsne(6000, **kw); b = Tsne(6000, **kw)
+    # (graphs=1: the middle iterations of a run are replayed from a captured HIP graph, several replays with
+    # eager iterations around them; exaggeration_iters=6 and momentum_switch_iter=9 put three phases into 13 steps)
+    for kw in (dict(), dict(max_nnz=P["nnz"]), dict(max_nnz=P["nnz"], reorder_every=4),
+               dict(max_nnz=P["nnz"], graphs=1, exaggeration_iters=6, momentum_switch_iter=9),
+               dict(graphs=1, overlap=0)):
+        a = Tsne(6000, **kw); b = Tsne(6000, **dict(kw, graphs=0))
         for t in (a, b):
             t.set_P(P["row_ptr"], P["col"], P["val"])
         Ya = torch.from_numpy(synth.y0(6000, seed=9)).to(dev); Yb = Ya.clone()
