@@ -846,13 +846,17 @@ __device__ __forceinline__ int find_in_row(const int32_t *__restrict__ idx, int 
     return -1;
 }
 
-// extra[j] = number of rows i that list j while j does not list i
-__global__ __launch_bounds__(256) void sym_count(const int32_t *__restrict__ idx, int n, int k, int *__restrict__ extra)
+// extra[j] = number of rows i that list j while j does not list i; slot[e] = where i sits in j's list
+// (-1 if it does not), kept for sym_fill (k <= 1280 fits 16 bits)
+__global__ __launch_bounds__(256) void sym_count(const int32_t *__restrict__ idx, int n, int k, int *__restrict__ extra,
+                                                 int16_t *__restrict__ slot)
 {
     const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (size_t)n * k) return;
     const int i = (int)(e / k), j = idx[e];
-    if (find_in_row(idx, k, j, i) < 0) atomicAdd(&extra[j], 1);
+    const int sl = find_in_row(idx, k, j, i);
+    slot[e] = (int16_t)sl;
+    if (sl < 0) atomicAdd(&extra[j], 1);
 }
 
 // row_ptr[i] = sum_{r<i} (k + extra[r]); single block, n up to 2^30
@@ -885,13 +889,14 @@ __global__ __launch_bounds__(1024) void sym_scan(const int *__restrict__ extra, 
 
 __global__ __launch_bounds__(256) void sym_fill(const int32_t *__restrict__ idx, const double *__restrict__ cond, int n,
                                                 int k, const int32_t *__restrict__ row_ptr, int *__restrict__ cursor,
-                                                int32_t *__restrict__ col, float *__restrict__ val)
+                                                const int16_t *__restrict__ slots, int32_t *__restrict__ col,
+                                                float *__restrict__ val)
 {
     const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (size_t)n * k) return;
     const int i = (int)(e / k), a = (int)(e % k), j = idx[e];
     const double pji = cond[e];
-    const int slot = find_in_row(idx, k, j, i);
+    const int slot = slots[e];
     const double pij = slot >= 0 ? cond[(size_t)j * k + slot] : 0.0;
     const float v = (float)((pji + pij) / (2.0 * (double)n));
     col[row_ptr[i] + a] = j;
@@ -1133,14 +1138,17 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     const size_t nk = (size_t)n * k;
     hipLaunchKernelGGL(perplexity_search, dim3((n + 63) / 64), dim3(64), 0, s, L.knn_d2, n, k, log((double)perplexity),
                        1e-10, L.cond, L.unconv);
-    hipLaunchKernelGGL(sym_count, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, n, k, L.extra);
+    // (the candidate buffers are free by now and hold 2 n k bytes with room to spare: 2 n k < 2^31 <= 8 * 65536 * 4160
+    // for a full query block, and 2 k < 8 * 4160 for a short one)
+    int16_t *slots = reinterpret_cast<int16_t *>(L.cand);
+    hipLaunchKernelGGL(sym_count, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, n, k, L.extra, slots);
     hipLaunchKernelGGL(sym_scan, dim3(1), dim3(1024), 0, s, L.extra, n, k, d_row_ptr, L.cursor);
     int32_t total = 0;
     HIPCHK(hipMemcpyAsync(&total, d_row_ptr + n, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     if ((int64_t)total > cap_nnz) return TSNE_ENOSPC;
     hipLaunchKernelGGL(sym_fill, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, L.cond, n, k, d_row_ptr,
-                       L.cursor, d_col, d_val);
+                       L.cursor, slots, d_col, d_val);
     hipLaunchKernelGGL(sym_sort_rows, dim3(n), dim3(256), 0, s, d_row_ptr, n, d_col, d_val, L.sort_scratch);
     if (d_knn_idx) HIPCHK(hipMemcpyAsync(d_knn_idx, L.knn_idx, 4 * nk, hipMemcpyDeviceToDevice, s));
     if (d_knn_d2)
