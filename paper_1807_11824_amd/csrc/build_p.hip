@@ -813,13 +813,26 @@ __device__ __forceinline__ double row_entropy(const double *__restrict__ dd, int
     return log(S) + beta * T / S;
 }
 
+// One thread per row.  LDS: the workgroup's 64 rows of distances are staged in LDS (row stride k | 1
+// doubles, so that the 64 threads' reads of their m-th distance fall in different banks) when they
+// fit; the bisection re-reads them some forty times.
 __global__ __launch_bounds__(64) void perplexity_search(const double *__restrict__ d2, int n, int k, double target,
                                                         double tol, double *__restrict__ cond,
-                                                        int *__restrict__ unconverged)
+                                                        int *__restrict__ unconverged, int staged)
 {
+    extern __shared__ __align__(16) unsigned char ps_smem[];
+    double *sd = reinterpret_cast<double *>(ps_smem);
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int stride = k | 1;
+    const double *dd = d2 + (size_t)min(i, n - 1) * k;
+    if (staged) {
+        const int row0 = blockIdx.x * 64, nrows = min(64, n - row0);
+        const double *src = d2 + (size_t)row0 * k;
+        for (int t = threadIdx.x; t < nrows * k; t += 64) sd[(t / k) * stride + t % k] = src[t];
+        __syncthreads();
+        dd = sd + threadIdx.x * stride;
+    }
     if (i >= n) return;
-    const double *dd = d2 + (size_t)i * k;
     double dmin = dd[0];
     for (int m = 1; m < k; ++m) dmin = fmin(dmin, dd[m]);
     double lo = 0.0, hi = INFINITY, beta = 1.0;
@@ -1136,8 +1149,10 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
         HIPCHK(hipGetLastError());
     }
     const size_t nk = (size_t)n * k;
-    hipLaunchKernelGGL(perplexity_search, dim3((n + 63) / 64), dim3(64), 0, s, L.knn_d2, n, k, log((double)perplexity),
-                       1e-10, L.cond, L.unconv);
+    const size_t ps_bytes = 64 * (size_t)(k | 1) * 8;
+    const int ps_staged = ps_bytes <= 60 * 1024 ? 1 : 0;
+    hipLaunchKernelGGL(perplexity_search, dim3((n + 63) / 64), dim3(64), ps_staged ? ps_bytes : 0, s, L.knn_d2, n, k,
+                       log((double)perplexity), 1e-10, L.cond, L.unconv, ps_staged);
     // (the candidate buffers are free by now and hold 2 n k bytes with room to spare: 2 n k < 2^31 <= 8 * 65536 * 4160
     // for a full query block, and 2 k < 8 * 4160 for a short one)
     int16_t *slots = reinterpret_cast<int16_t *>(L.cand);
