@@ -269,10 +269,22 @@ __global__ __launch_bounds__(256) void graph_smooth_k(const int32_t *__restrict_
     float a = 0.f, w = 0.f;
     if (row < n) {
         const int s = row_ptr[row], e = row_ptr[row + 1];
-        for (int j = s + sub; j < e; j += 16) {
-            const float v = val[j];
-            a = fmaf(v, x[min((uint32_t)col[j], (uint32_t)n - 1u)], a);
-            w += v;
+        for (int j0 = s + sub; j0 < e; j0 += 64) {      // four entries per lane in flight
+            float v[4], xv[4];
+            int cj[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = j0 + 16 * q;
+                v[q] = j < e ? val[j] : 0.f;
+                cj[q] = j < e ? col[j] : row;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) xv[q] = x[min((uint32_t)cj[q], (uint32_t)n - 1u)];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                a = fmaf(v[q], xv[q], a);
+                w += v[q];
+            }
         }
     }
 #pragma unroll
