@@ -473,7 +473,8 @@ static void attract_shares(const tsne_ctx *c, int *k1, int *k2)
 }
 
 // The far part from its tiles.  A small far part is summed row by row beside the tree build; the
-// tile kernels are heavy and go beside the walk.
+// tile kernels are heavy and are launched where the walk starts.  Their 64 KB of LDS per workgroup
+// does not fit beside the walk's resident waves, so they take over the chip as the walk drains.
 static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
 {
     const int n = c->p.n;
