@@ -109,9 +109,11 @@ def test_deterministic():
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and a[2] == b[2]
 
 
-def test_renumbering_changes_nothing_but_the_layout():
+@pytest.mark.parametrize("far_tiles", [0, 2])
+def test_renumbering_changes_nothing_but_the_layout(far_tiles):
     """With periodic renumbering on, forces at a given Y equal those of a fresh context without it,
-    and the optimiser state maps back to the caller's point order."""
+    and the optimiser state maps back to the caller's point order.  (far_tiles = 2: the bucketed copy of the
+    far part is rebuilt at every renumbering.)"""
     import torch
     from paper_1807_11824_amd import Tsne
     dev = torch.device("cuda:0")
@@ -119,7 +121,7 @@ def test_renumbering_changes_nothing_but_the_layout():
     rp, col, val = random_symmetric_csr(n, 30, seed=3)
     P = [torch.from_numpy(a).to(dev) for a in (rp, col, val)]
     Y = torch.from_numpy(synth.y0(n, seed=2)).to(dev)
-    a = Tsne(n, reorder_every=7, max_nnz=len(col), exaggeration=4.0)
+    a = Tsne(n, reorder_every=7, max_nnz=len(col), exaggeration=4.0, far_tiles=far_tiles)
     a.set_P(*P)
     a.run(Y, 40)                     # renumbers five times
     assert a.status() == 0
