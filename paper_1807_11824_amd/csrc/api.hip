@@ -317,6 +317,10 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
             return TSNE_EHIP;
         }
     }
+    if (p->n <= SMALL_SORT_MAX && (e = small_sort_prepare()) != hipSuccess) {
+        tsne_destroy(c);
+        return TSNE_EHIP;
+    }
     if (c->ft_tiles > 0 &&
         ((e = attract_far_tiled_prepare()) != hipSuccess ||
          (e = hipMemsetAsync(c->ft_cnt, 0, 4 * (size_t)c->ft_tiles, c->stream)) != hipSuccess ||

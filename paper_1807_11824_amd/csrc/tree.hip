@@ -5,6 +5,7 @@
 //   bbox_partial / bbox_final   step 1   min/max reduction -> root square (power-of-two side)
 //   morton_encode               step 2a  16-bit grid coordinates, bit-interleaved key
 //   radix_hist / _scan / _scatter  step 4  stable LSD radix sort of (key, index), 8 bits a pass
+//   small_root_keys_sort        steps 1, 2a, 4 in one launch of one workgroup, for few points
 //   gather_levels               step 2b  which cells start at each sorted position
 //   scan_partials / downsweep   step 3   prefix sums: cell numbering and running coordinate sums
 //   write_cells                 steps 2c+3  cell records: members, count, centre of mass, children
@@ -53,6 +54,23 @@ __global__ __launch_bounds__(256) void bbox_partial(const float2 *__restrict__ Y
 
 // Root square: lower corner (min x, min y); side = smallest power of two >= the larger extent,
 // at least 2^-40; scale S = 2^bits / side (an exact power of two).
+__device__ __forceinline__ float4 root_square(float mnx, float mny, float mxx, float mxy, int bits, uint32_t *status)
+{
+    float ex = mxx - mnx, ey = mxy - mny;
+    float e = fmaxf(ex, ey);
+    float W = ldexpf(1.0f, -40);
+    if (!isfinite(e) || !isfinite(mnx) || !isfinite(mny)) {
+        atomicOr(status, TSNE_STATUS_NONFINITE);
+        mnx = 0.0f; mny = 0.0f; W = 1.0f;
+    } else if (e > W) {
+        int ex2;
+        float m = frexpf(e, &ex2);          // e = m 2^ex2, m in [0.5, 1)
+        W = (m == 0.5f) ? e : ldexpf(1.0f, ex2);
+    }
+    float S = ldexpf(1.0f, bits) / W;
+    return make_float4(mnx, mny, W, S);
+}
+
 __global__ __launch_bounds__(1024) void bbox_final(const float4 *__restrict__ part, int nparts, int bits,
                                                    float4 *__restrict__ root, uint32_t *status)
 {
@@ -72,19 +90,7 @@ __global__ __launch_bounds__(1024) void bbox_final(const float4 *__restrict__ pa
             mnx = fminf(mnx, smn[k].x); mny = fminf(mny, smn[k].y);
             mxx = fmaxf(mxx, smx[k].x); mxy = fmaxf(mxy, smx[k].y);
         }
-        float ex = mxx - mnx, ey = mxy - mny;
-        float e = fmaxf(ex, ey);
-        float W = ldexpf(1.0f, -40);
-        if (!isfinite(e) || !isfinite(mnx) || !isfinite(mny)) {
-            atomicOr(status, TSNE_STATUS_NONFINITE);
-            mnx = 0.0f; mny = 0.0f; W = 1.0f;
-        } else if (e > W) {
-            int ex2;
-            float m = frexpf(e, &ex2);          // e = m 2^ex2, m in [0.5, 1)
-            W = (m == 0.5f) ? e : ldexpf(1.0f, ex2);
-        }
-        float S = ldexpf(1.0f, bits) / W;
-        *root = make_float4(mnx, mny, W, S);
+        *root = root_square(mnx, mny, mxx, mxy, bits, status);
     }
 }
 
@@ -125,6 +131,135 @@ __global__ __launch_bounds__(256) void morton_encode(const float2 *__restrict__ 
     keys_orig[i] = key;
     keys[i] = key;
     idx[i] = (uint32_t)i;
+}
+
+// ------------------------------------------------------------------ few points: one workgroup does it all
+// Root square, keys and the sort of (key, index) in one launch, for n <= SMALL_SORT_MAX: the pairs
+// sit in LDS as key * 2^32 + index (all different, so any sorting network gives the order of a
+// stable sort by key), padded with all-ones to m, the power of two >= n.  Same root, same keys
+// and same order as bbox_final + morton_encode + the radix passes.
+//
+// The network is the bitonic one.  A thread holds E = 2^LOGE pairs that differ in LOGE
+// neighbouring index bits, so one trip through LDS serves LOGE exchange distances; one padding
+// slot after every eight keeps the lanes of a wave on different banks whichever bits they are.
+__device__ __forceinline__ int small_sort_slot(int i) { return i + (i >> 3); }
+
+template <int LOGE>
+__device__ __forceinline__ void bitonic_trip(unsigned long long *pairs, int t, int b_lo, int nsteps, int k)
+{
+    constexpr int E = 1 << LOGE;
+    const int base = ((t >> b_lo) << (b_lo + LOGE)) | (t & ((1 << b_lo) - 1));
+    unsigned long long v[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[e] = pairs[small_sort_slot(base | (e << b_lo))];
+    // direction of the run of length k a pair belongs to: one per thread unless k's bit is among the E's
+    if ((k >> (b_lo + LOGE)) != 0) {
+        const bool up = (base & k) == 0;
+#pragma unroll
+        for (int c = LOGE - 1; c >= 0; --c) {
+            if (c < nsteps) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    if (e & (1 << c)) continue;
+                    unsigned long long a = v[e], b = v[e | (1 << c)];
+                    const bool sw = (a > b) == up;
+                    v[e] = sw ? b : a;
+                    v[e | (1 << c)] = sw ? a : b;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int c = LOGE - 1; c >= 0; --c) {
+            if (c < nsteps) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    if (e & (1 << c)) continue;
+                    const bool up = ((e << b_lo) & k) == 0;
+                    unsigned long long a = v[e], b = v[e | (1 << c)];
+                    const bool sw = (a > b) == up;
+                    v[e] = sw ? b : a;
+                    v[e | (1 << c)] = sw ? a : b;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) pairs[small_sort_slot(base | (e << b_lo))] = v[e];
+}
+
+// blockDim.x = m >> LOGE
+template <int LOGE>
+__global__ __launch_bounds__(1024) void small_root_keys_sort(const float2 *__restrict__ Y, int n, int m,
+                                                             const float4 *__restrict__ part, int nparts, int bits,
+                                                             float4 *__restrict__ root, uint32_t *__restrict__ keys_orig,
+                                                             uint32_t *__restrict__ keys_out,
+                                                             uint32_t *__restrict__ idx_out, uint32_t *status)
+{
+    extern __shared__ unsigned long long pairs[];
+    __shared__ float4 smn[16], smx[16];
+    __shared__ float4 sroot;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    {
+        float mnx = INFINITY, mny = INFINITY, mxx = -INFINITY, mxy = -INFINITY;
+        for (int i = tid; i < nparts; i += nthr) {
+            float4 a = part[2 * i], b = part[2 * i + 1];
+            mnx = fminf(mnx, a.x); mny = fminf(mny, a.y);
+            mxx = fmaxf(mxx, b.x); mxy = fmaxf(mxy, b.y);
+        }
+        mnx = wave_min(mnx); mny = wave_min(mny); mxx = wave_max(mxx); mxy = wave_max(mxy);
+        const int w = tid >> 6, nw = nthr >> 6;
+        if (lane_id() == 0) { smn[w] = make_float4(mnx, mny, 0, 0); smx[w] = make_float4(mxx, mxy, 0, 0); }
+        __syncthreads();
+        if (tid == 0) {
+            for (int k = 1; k < nw; ++k) {
+                mnx = fminf(mnx, smn[k].x); mny = fminf(mny, smn[k].y);
+                mxx = fmaxf(mxx, smx[k].x); mxy = fmaxf(mxy, smx[k].y);
+            }
+            float4 r = root_square(mnx, mny, mxx, mxy, bits, status);
+            sroot = r;
+            *root = r;
+        }
+        __syncthreads();
+    }
+    const float4 r = sroot;
+    const uint32_t qmax = (1u << bits) - 1u;
+    for (int i = tid; i < m; i += nthr) {
+        unsigned long long v = ~0ull;
+        if (i < n) {
+            float2 y = Y[i];
+            uint32_t qx = grid_coord(y.x, r.x, r.w, qmax);
+            uint32_t qy = grid_coord(y.y, r.y, r.w, qmax);
+            uint32_t key = spread16(qx) | (spread16(qy) << 1);
+            keys_orig[i] = key;
+            v = ((unsigned long long)key << 32) | (uint32_t)i;
+        }
+        pairs[small_sort_slot(i)] = v;
+    }
+    __syncthreads();
+    // stage s makes sorted runs of length 2^s out of pairs of runs of opposite direction: exchanges at
+    // distances 2^(s-1) .. 1, taken LOGE at a time from the top
+    for (int st = 1; (1 << st) <= m; ++st) {
+        for (int rem = st; rem > 0;) {
+            const int ns = rem < LOGE ? rem : LOGE;
+            bitonic_trip<LOGE>(pairs, tid, rem - ns, ns, 1 << st);
+            rem -= ns;
+            __syncthreads();
+        }
+    }
+    for (int i = tid; i < n; i += nthr) {
+        unsigned long long v = pairs[small_sort_slot(i)];
+        keys_out[i] = (uint32_t)(v >> 32);
+        idx_out[i] = (uint32_t)v;
+    }
+}
+
+static size_t small_sort_lds(int m) { return 8 * (size_t)(m + (m >> 3)); }
+
+hipError_t small_sort_prepare()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&small_root_keys_sort<3>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_sort_lds(SMALL_SORT_MAX));
 }
 
 // ------------------------------------------------------------------ radix sort (stable, LSD, 8 bits)
@@ -805,6 +940,15 @@ hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
     const int n = c->p.n, B = c->p.morton_bits;
     const float2 *Y = c->Yi;
     const int nb = (n + 255) / 256;
+    if (n <= SMALL_SORT_MAX) {
+        int m = 512;
+        while (m < n) m <<= 1;
+        const int cur = ((2 * B + 7) / 8) & 1;     // where the radix passes would have left the result
+        hipLaunchKernelGGL(small_root_keys_sort<3>, dim3(1), dim3(m >> 3), small_sort_lds(m), s, Y, n, m, c->bbox_part,
+                           c->bbox_nparts, B, c->root, c->keys_orig, c->keys[cur], c->idx[cur], c->status);
+        c->sorted_buf = cur;
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(bbox_final, dim3(1), dim3(c->bbox_nparts > 1024 ? 1024 : 256), 0, s, c->bbox_part, c->bbox_nparts, B,
                        c->root, c->status);
     hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],

@@ -30,6 +30,7 @@ struct ScanPart {
 constexpr int SORT_THREADS = 256;
 constexpr int SORT_ITEMS = 8;
 constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
+constexpr int SMALL_SORT_MAX = 8192;  // up to here one workgroup finds root, keys and order in LDS
 constexpr int LEVEL_THREADS = 256;
 constexpr int LEVEL_ITEMS = 4;
 constexpr int LEVEL_TILE = LEVEL_THREADS * LEVEL_ITEMS;
@@ -136,6 +137,7 @@ inline bool ft_possible(const tsne_params *p)
     return p->far_tiles != 1 && nrt * nct <= FT_MAX_TILES;
 }
 hipError_t attract_far_tiled_prepare();   // once per process, before the first launch
+hipError_t small_sort_prepare();          // likewise
 hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s);
 hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);

@@ -34,6 +34,9 @@ def _rng_cases():
         "duplicates": np.repeat(r.random((50, 2)).astype(np.float32), 13, axis=0),
         "collinear": np.stack([np.linspace(-3, 5, 1000), np.full(1000, 2.0)], 1).astype(np.float32),
         "blob_5003": synth.y0(5003, seed=1),
+        # either side of the size up to which one workgroup sorts in LDS
+        "blob_8192": synth.clustered_embedding(8192, n_clusters=30, seed=5),
+        "blob_8193": synth.clustered_embedding(8193, n_clusters=30, seed=5),
         "outlier": np.vstack([r.random((4097, 2)) * 1e-3, [[100.0, -50.0]]]).astype(np.float32),
         "clusters_100k": synth.clustered_embedding(100_003, n_clusters=300, seed=2),
         "collapsed_clusters": synth.clustered_embedding(30_000, n_clusters=20, spread=5.0, sigma=1e-4, seed=3),
@@ -44,7 +47,7 @@ CASES = _rng_cases()
 
 
 @pytest.mark.parametrize("name", sorted(CASES))
-@pytest.mark.parametrize("bits,leaf_cap", [(16, 8), (16, 1), (7, 3), (16, 40)])
+@pytest.mark.parametrize("bits,leaf_cap", [(16, 8), (16, 1), (7, 3), (10, 8), (16, 40)])
 def test_tree_matches_oracle(name, bits, leaf_cap):
     Y = CASES[name]
     print(f"case={name} n={Y.shape[0]} bits={bits} leaf_cap={leaf_cap}", flush=True)
