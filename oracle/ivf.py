@@ -1,0 +1,104 @@
+"""CPU oracle for the approximate neighbour search of Sec. III-B (test infrastructure only).
+
+Inverted-file search with a flat second stage: the coarse quantiser q1 is the nearest of |C|
+centroids trained by k-means (the paper takes |C| = sqrt(N)); a query looks at the tau lists whose
+centroids are nearest to it (Eq. 10) and keeps the k nearest of the points stored there (Eq. 11 with
+q(y) = y, i.e. no second-stage code).  Everything below is the definition written out in numpy,
+in double precision, ties broken towards the lower index.  Nothing here is shared with the GPU code.
+"""
+import numpy as np
+
+__all__ = ["kmeans_init", "sq_dists", "assign", "kmeans_train", "probes", "ivf_lists", "ivf_knn", "recall"]
+
+
+def kmeans_init(X, nlist):
+    """Starting centroids: the rows floor(c n / nlist), c = 0 .. nlist-1."""
+    X = np.asarray(X, np.float32)
+    n = X.shape[0]
+    rows = (np.arange(nlist, dtype=np.int64) * n) // nlist
+    return X[rows].copy()
+
+
+def sq_dists(Xq, C):
+    """|x - c|^2 for every row of Xq against every row of C, in double."""
+    Xq = np.asarray(Xq, np.float64)
+    C = np.asarray(C, np.float64)
+    out = np.empty((Xq.shape[0], C.shape[0]), np.float64)
+    step = max(1, (1 << 24) // max(1, C.shape[0] * Xq.shape[1]))
+    for a in range(0, Xq.shape[0], step):
+        diff = Xq[a:a + step, None, :] - C[None, :, :]
+        out[a:a + step] = np.einsum("qcd,qcd->qc", diff, diff)
+    return out
+
+
+def assign(X, C):
+    """q1: index of the nearest centroid (lowest index among equals) and the squared distance to it."""
+    D = sq_dists(X, C)
+    a = np.argmin(D, axis=1)            # first minimum = lowest index
+    return a.astype(np.int32), D[np.arange(D.shape[0]), a]
+
+
+def kmeans_train(X, nlist, iters):
+    """Lloyd's algorithm from kmeans_init: assign every point to its nearest centroid, move every
+    centroid to the mean of its points (a centroid without points stays where it is).  Centroids are
+    kept as float between the iterations.  Returns (centroids float32, inertia before each update)."""
+    X = np.asarray(X, np.float32)
+    C = kmeans_init(X, nlist)
+    Xd = X.astype(np.float64)
+    inertia = []
+    for _ in range(iters):
+        a, dmin = assign(X, C)
+        inertia.append(float(dmin.sum()))
+        for c in range(nlist):
+            members = Xd[a == c]
+            if members.shape[0] > 0:
+                C[c] = members.mean(axis=0).astype(np.float32)
+    return C, inertia
+
+
+def probes(X, C, tau):
+    """Eq. (10): for every row of X the tau nearest centroids, ordered by (distance, index)."""
+    D = sq_dists(X, C)
+    ids = np.broadcast_to(np.arange(C.shape[0]), D.shape)
+    out = np.empty((X.shape[0], tau), np.int32)
+    for i in range(X.shape[0]):
+        out[i] = np.lexsort((ids[i], D[i]))[:tau]
+    return out
+
+
+def ivf_lists(X, C):
+    """The inverted file: for every centroid the indices (ascending) of the points whose q1 it is."""
+    a, _ = assign(X, C)
+    return [np.flatnonzero(a == c).astype(np.int32) for c in range(C.shape[0])]
+
+
+def ivf_knn(X, C, tau, k):
+    """Eq. (11) with a flat second stage: the k nearest (exact squared distance in double, then index)
+    among the points of the tau probed lists, the query itself left out.
+    Returns (idx int32 [n, k], d2 float64 [n, k]); raises if some query sees fewer than k points."""
+    X = np.asarray(X, np.float32)
+    n = X.shape[0]
+    Xd = X.astype(np.float64)
+    lists = ivf_lists(X, C)
+    pr = probes(X, C, tau)
+    idx = np.empty((n, k), np.int32)
+    d2 = np.empty((n, k), np.float64)
+    for i in range(n):
+        cand = np.concatenate([lists[c] for c in pr[i]])
+        cand = cand[cand != i]
+        if cand.shape[0] < k:
+            raise ValueError(f"row {i}: only {cand.shape[0]} candidates in its {tau} lists, need {k}")
+        diff = Xd[cand] - Xd[i]
+        dd = np.einsum("cd,cd->c", diff, diff)
+        order = np.lexsort((cand, dd))[:k]
+        idx[i] = cand[order]
+        d2[i] = dd[order]
+    return idx, d2
+
+
+def recall(idx, idx_exact):
+    """Fraction of the exact neighbours that the approximate lists contain (recall at k)."""
+    hit = 0
+    for a, b in zip(idx, idx_exact):
+        hit += np.intersect1d(a, b).shape[0]
+    return hit / idx_exact.size

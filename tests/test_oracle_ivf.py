@@ -1,0 +1,114 @@
+"""Pins for the oracle of the inverted-file neighbour search (Sec. III-B, Eq. 10-11, flat second stage)."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ivf
+from paper_1807_11824_amd import synth
+
+
+def test_all_lists_probed_is_the_exact_search():
+    """tau = |C|: every point is a candidate, so Eq. (11) is the exact k-argmin (the brute-force oracle)."""
+    X, _ = synth.gaussian_mixture(700, 12, 5, 4.0, 1.0, seed=2)
+    C, _ = ivf.kmeans_train(X, 9, 3)
+    idx, d2 = ivf.ivf_knn(X, C, 9, 15)
+    eidx, ed2 = oracle.knn(X, 15)
+    assert np.array_equal(idx, eidx)
+    assert np.allclose(d2, ed2, rtol=1e-12, atol=0)
+
+
+def test_line_example_by_hand():
+    """Twenty points on a line in two groups, one centroid per group, one list probed: neighbours never
+    cross to the other group; equal distances go to the lower index."""
+    X = np.concatenate([np.arange(10.0), 100.0 + np.arange(10.0)]).astype(np.float32)[:, None]
+    C = np.array([[4.5], [104.5]], np.float32)
+    idx, d2 = ivf.ivf_knn(X, C, 1, 3)
+    assert idx[0].tolist() == [1, 2, 3] and d2[0].tolist() == [1.0, 4.0, 9.0]
+    assert idx[5].tolist() == [4, 6, 3] and d2[5].tolist() == [1.0, 1.0, 4.0]
+    assert idx[9].tolist() == [8, 7, 6]
+    assert idx[10].tolist() == [11, 12, 13]
+    assert idx[19].tolist() == [18, 17, 16] and d2[19].tolist() == [1.0, 4.0, 9.0]
+    # both lists probed: point 9 still has 8, 7, 6 (the other group is 91 away), with k = 9 it needs all of its group
+    idx2, _ = ivf.ivf_knn(X, C, 2, 10)
+    assert idx2[9].tolist() == [8, 7, 6, 5, 4, 3, 2, 1, 0, 10]
+    with pytest.raises(ValueError):
+        ivf.ivf_knn(X, C, 1, 10)         # nine other points in the list, ten asked for
+
+
+def test_probe_order_and_ties():
+    """Eq. (10) by hand: distances 1, 1, 4, 0 to four centroids -> order 3, 0, 1, 2; a copy of a centroid
+    never wins against the original."""
+    X = np.array([[0.0, 0.0]], np.float32)
+    C = np.array([[1, 0], [0, -1], [2, 0], [0, 0]], np.float32)
+    assert ivf.probes(X, C, 4)[0].tolist() == [3, 0, 1, 2]
+    assert ivf.probes(X, C, 2)[0].tolist() == [3, 0]
+    a, dmin = ivf.assign(np.array([[1.0, 0.1]], np.float32), np.array([[1, 0], [1, 0], [5, 5]], np.float32))
+    assert a.tolist() == [0] and abs(dmin[0] - np.float64(np.float32(0.1)) ** 2) < 1e-15
+
+
+def test_sq_dists_against_plain_loops():
+    r = np.random.default_rng(0)
+    X = r.standard_normal((7, 5)).astype(np.float32)
+    C = r.standard_normal((4, 5)).astype(np.float32)
+    D = ivf.sq_dists(X, C)
+    for i in range(7):
+        for c in range(4):
+            s = 0.0
+            for t in range(5):
+                s += (float(X[i, t]) - float(C[c, t])) ** 2
+            assert abs(D[i, c] - s) <= 1e-14 * s
+
+
+def test_kmeans_separated_groups_reach_the_group_means_in_one_step():
+    """Three groups far apart, stored one after the other: the starting rows 0, n/3, 2n/3 fall one into each,
+    every point's nearest centroid is its own group's, and one update gives the three means."""
+    r = np.random.default_rng(3)
+    groups = [r.standard_normal((40, 6)) + 100.0 * g for g in range(3)]
+    X = np.concatenate(groups).astype(np.float32)
+    C, inertia = ivf.kmeans_train(X, 3, 2)
+    want = np.stack([X[40 * g:40 * g + 40].astype(np.float64).mean(axis=0) for g in range(3)])
+    assert np.allclose(C, want, rtol=0, atol=1e-5)
+    assert inertia[1] < inertia[0]
+    # a fixed point: another pass changes nothing
+    C2, _ = ivf.kmeans_train(X, 3, 5)
+    assert np.array_equal(C, C2)
+
+
+def test_kmeans_inertia_never_rises_and_empty_cells_stay():
+    X, _ = synth.gaussian_mixture(900, 8, 4, 5.0, 1.0, seed=5)
+    C, inertia = ivf.kmeans_train(X, 30, 8)
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(inertia, inertia[1:]))   # (centroids are rounded to float)
+    # two copies of one point as starting centroids: the second never gets a point and must not move
+    Xd = np.concatenate([np.zeros((2, 3), np.float32), np.ones((2, 3), np.float32)])   # rows 0, 1 equal; n=4, nlist=4
+    C, _ = ivf.kmeans_train(Xd, 4, 3)
+    assert np.array_equal(C[1], Xd[1]) and np.array_equal(C[3], Xd[3])
+
+
+def test_more_lists_never_hurt():
+    """The candidate sets are nested in tau, so the distance to the k-th neighbour cannot grow and the recall
+    cannot fall; at tau = |C| the recall is 1."""
+    X, _ = synth.gaussian_mixture(1200, 10, 6, 3.0, 1.0, seed=7)
+    C, _ = ivf.kmeans_train(X, 20, 5)
+    eidx, _ = oracle.knn(X, 10)
+    last_d, last_r = None, 0.0
+    for tau in (2, 4, 8, 20):
+        idx, d2 = ivf.ivf_knn(X, C, tau, 10)
+        assert np.all(np.diff(d2, axis=1) >= 0)
+        assert not np.any(idx == np.arange(1200)[:, None])
+        if last_d is not None:
+            assert np.all(d2 <= last_d)
+        rec = ivf.recall(idx, eidx)
+        assert rec >= last_r
+        last_d, last_r = d2, rec
+    assert last_r == 1.0
+
+
+def test_lists_partition_the_points():
+    X, _ = synth.gaussian_mixture(500, 6, 3, 3.0, 1.0, seed=1)
+    C = ivf.kmeans_init(X, 11)
+    lists = ivf.ivf_lists(X, C)
+    allp = np.sort(np.concatenate(lists))
+    assert np.array_equal(allp, np.arange(500))
+    a, _ = ivf.assign(X, C)
+    for c, l in enumerate(lists):
+        assert np.all(a[l] == c)
