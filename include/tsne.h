@@ -159,6 +159,48 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                  int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged,
                  void *d_workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Sec. III-B, Eq. (8)-(11): approximate neighbours from an inverted file.  The coarse quantiser q1 is the
+ * nearest of nlist centroids (index of the lowest among equals); a query looks at the tau lists whose
+ * centroids are nearest to it (Eq. 10) and keeps the k nearest of the points stored in them (Eq. 11).
+ * The second-stage code q2 of Eq. (8) is left out: list entries are compared by their exact squared
+ * distance (a "flat" inverted file), so the only approximation is in which lists are looked at.
+ * All decisions are taken on squared distances accumulated in double precision from the float inputs,
+ * ties towards the lower index; the lists returned are those of the definition.
+ *
+ * tsne_ivf_train: k-means (Lloyd) for the centroids, as the paper trains them: start from the rows
+ *   floor(c n / nlist), then `iters` rounds of (assign every row to its nearest centroid, move every
+ *   centroid to the mean of its rows; a centroid without rows stays).  d_centroids: nlist x d floats
+ *   (device, caller-owned, written).  X must be finite with |x| < 1e38.
+ * tsne_ivf_knn: neighbour lists of every row of X (self excluded, ordered by (distance, index)) from
+ *   given centroids.  d_knn_idx: n x k int32, d_knn_d2: n x k doubles (device, caller-owned).
+ *   Returns TSNE_ENUM if some row finds fewer than k other points in its tau lists (raise tau or lower
+ *   nlist), TSNE_ENOSPC if one row's candidates do not fit the workspace's distance scratch.
+ * Workspace (tsne_ivf_workspace_bytes; use the figure for the largest tau to be passed): 8 n d bytes for
+ *   the copy of X grouped by list, 4 n tau, and a distance scratch of min(8 GiB, 8 n min(n, 4096)) bytes;
+ *   more workspace than asked for is used (up to 8 GiB of scratch) to take more queries per pass.
+ * Limits: nlist <= min(n, 65536), tau <= min(nlist, 32), k <= 1920, d <= 4096, n tau < 2^31.
+ * Both calls synchronise the stream before returning.
+ */
+int tsne_ivf_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes);
+int tsne_ivf_train(const float *d_X, int32_t n, int32_t d, int32_t nlist, int32_t iters, float *d_centroids,
+                   void *d_workspace, size_t workspace_bytes, void *stream);
+int tsne_ivf_knn(const float *d_X, int32_t n, int32_t d, const float *d_centroids, int32_t nlist, int32_t tau,
+                 int32_t k, int32_t *d_knn_idx, double *d_knn_d2, void *d_workspace, size_t workspace_bytes,
+                 void *stream);
+
+/*
+ * tsne_build_P with the neighbours of Sec. III-B's approximate search instead of the exact ones:
+ * tsne_ivf_train (nlist centroids, kmeans_iters rounds; nlist = 0 takes the paper's sqrt(n)), tsne_ivf_knn
+ * (tau lists per query), then Eq. (1) and the symmetric CSR exactly as in tsne_build_P.  Same outputs,
+ * same limits as both; errors as tsne_ivf_knn.
+ */
+int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes);
+int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k, int32_t nlist,
+                        int32_t tau, int32_t kmeans_iters, int32_t *d_row_ptr, int32_t *d_col, float *d_val,
+                        int64_t cap_nnz, int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged,
+                        void *d_workspace, size_t workspace_bytes, void *stream);
+
 /* Hands a CSR matrix P (n rows, int32 indices, float values, all on the device) to the context.
  * Borrowed: it must outlive every later call on the context (with renumbering on, the library works
  * from a relabelled private copy but still reads the original for tsne_kl).  With renumbering on,

@@ -72,27 +72,28 @@ def ivf_lists(X, C):
     return [np.flatnonzero(a == c).astype(np.int32) for c in range(C.shape[0])]
 
 
-def ivf_knn(X, C, tau, k):
+def ivf_knn(X, C, tau, k, rows=None):
     """Eq. (11) with a flat second stage: the k nearest (exact squared distance in double, then index)
-    among the points of the tau probed lists, the query itself left out.
-    Returns (idx int32 [n, k], d2 float64 [n, k]); raises if some query sees fewer than k points."""
+    among the points of the tau probed lists, the query itself left out; for the queries `rows` (all).
+    Returns (idx int32 [len(rows), k], d2 float64 [len(rows), k]); raises if a query sees fewer than k points."""
     X = np.asarray(X, np.float32)
     n = X.shape[0]
     Xd = X.astype(np.float64)
     lists = ivf_lists(X, C)
-    pr = probes(X, C, tau)
-    idx = np.empty((n, k), np.int32)
-    d2 = np.empty((n, k), np.float64)
-    for i in range(n):
-        cand = np.concatenate([lists[c] for c in pr[i]])
+    rows = np.arange(n) if rows is None else np.asarray(rows)
+    pr = probes(X[rows], C, tau)
+    idx = np.empty((rows.shape[0], k), np.int32)
+    d2 = np.empty((rows.shape[0], k), np.float64)
+    for o, i in enumerate(rows):
+        cand = np.concatenate([lists[c] for c in pr[o]])
         cand = cand[cand != i]
         if cand.shape[0] < k:
             raise ValueError(f"row {i}: only {cand.shape[0]} candidates in its {tau} lists, need {k}")
         diff = Xd[cand] - Xd[i]
         dd = np.einsum("cd,cd->c", diff, diff)
         order = np.lexsort((cand, dd))[:k]
-        idx[i] = cand[order]
-        d2[i] = dd[order]
+        idx[o] = cand[order]
+        d2[o] = dd[order]
     return idx, d2
 
 

@@ -54,6 +54,12 @@ def lib():
         "tsne_build_P_workspace_bytes": (C.c_int, [i32, i32, i32, C.POINTER(C.c_size_t)]),
         "tsne_build_P": (C.c_int, [vp, i32, i32, f32, i32, vp, vp, vp, i64, C.POINTER(i64), vp, vp,
                                    C.POINTER(i32), vp, C.c_size_t, vp]),
+        "tsne_ivf_workspace_bytes": (C.c_int, [i32, i32, i32, i32, i32, C.POINTER(C.c_size_t)]),
+        "tsne_ivf_train": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, C.c_size_t, vp]),
+        "tsne_ivf_knn": (C.c_int, [vp, i32, i32, vp, i32, i32, i32, vp, vp, vp, C.c_size_t, vp]),
+        "tsne_build_P_approx_workspace_bytes": (C.c_int, [i32, i32, i32, i32, i32, C.POINTER(C.c_size_t)]),
+        "tsne_build_P_approx": (C.c_int, [vp, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, i64, C.POINTER(i64), vp, vp,
+                                          C.POINTER(i32), vp, C.c_size_t, vp]),
         "tsne_set_P": (C.c_int, [vp, vp, vp, vp, i64]),
         "tsne_init_state": (C.c_int, [vp]),
         "tsne_get_state": (C.c_int, [vp, vp, vp]),
@@ -132,6 +138,74 @@ def build_P(X, perplexity, k, stream=None, want_knn=False):
                         _ptr(knn_idx), _ptr(knn_d2), C.byref(bad), _ptr(work), wb, _stream_ptr(stream))
     if rc:
         raise TsneError(rc, "tsne_build_P", L.tsne_strerror(rc).decode())
+    m = nnz.value
+    return dict(row_ptr=row_ptr, col=col[:m], val=val[:m], nnz=m, unconverged=bad.value,
+                knn_idx=knn_idx, knn_d2=knn_d2)
+
+
+def _ivf_workspace(n, d, k, nlist, tau, device, extra_bytes=0):
+    b = C.c_size_t(0)
+    rc = lib().tsne_ivf_workspace_bytes(n, d, k, nlist, tau, C.byref(b))
+    if rc:
+        raise TsneError(rc, "tsne_ivf_workspace_bytes", lib().tsne_strerror(rc).decode())
+    return torch.empty(b.value + extra_bytes, dtype=torch.uint8, device=device)
+
+
+def ivf_train(X, nlist, iters, stream=None):
+    """tsne_ivf_train on a device tensor X (n x d float32): the nlist x d centroids (device float32)."""
+    _dev(X, torch.float32, "X")
+    n, d = X.shape
+    L = lib()
+    work = _ivf_workspace(n, d, 1, nlist, 1, X.device)
+    cent = torch.empty((nlist, d), dtype=torch.float32, device=X.device)
+    rc = L.tsne_ivf_train(_ptr(X), n, d, nlist, iters, _ptr(cent), _ptr(work), work.numel(), _stream_ptr(stream))
+    if rc:
+        raise TsneError(rc, "tsne_ivf_train", L.tsne_strerror(rc).decode())
+    return cent
+
+
+def ivf_knn(X, centroids, tau, k, stream=None, extra_workspace_bytes=0):
+    """tsne_ivf_knn: (idx int32 n x k, squared distances float64 n x k), device tensors."""
+    _dev(X, torch.float32, "X")
+    _dev(centroids, torch.float32, "centroids")
+    n, d = X.shape
+    nlist = centroids.shape[0]
+    if centroids.shape[1] != d:
+        raise ValueError("centroids: wrong width")
+    L = lib()
+    work = _ivf_workspace(n, d, k, nlist, tau, X.device, extra_workspace_bytes)
+    idx = torch.empty((n, k), dtype=torch.int32, device=X.device)
+    d2 = torch.empty((n, k), dtype=torch.float64, device=X.device)
+    rc = L.tsne_ivf_knn(_ptr(X), n, d, _ptr(centroids), nlist, tau, k, _ptr(idx), _ptr(d2), _ptr(work), work.numel(),
+                        _stream_ptr(stream))
+    if rc:
+        raise TsneError(rc, "tsne_ivf_knn", L.tsne_strerror(rc).decode())
+    return idx, d2
+
+
+def build_P_approx(X, perplexity, k, tau, nlist=0, kmeans_iters=10, stream=None, want_knn=False):
+    """tsne_build_P_approx on a device tensor X (n x d float32).  Returns a dict of device tensors."""
+    _dev(X, torch.float32, "X")
+    n, d = X.shape
+    L = lib()
+    b = C.c_size_t(0)
+    rc = L.tsne_build_P_approx_workspace_bytes(n, d, k, nlist, tau, C.byref(b))
+    if rc:
+        raise TsneError(rc, "tsne_build_P_approx_workspace_bytes", L.tsne_strerror(rc).decode())
+    work = torch.empty(b.value, dtype=torch.uint8, device=X.device)
+    cap = 2 * n * k
+    row_ptr = torch.empty(n + 1, dtype=torch.int32, device=X.device)
+    col = torch.empty(cap, dtype=torch.int32, device=X.device)
+    val = torch.empty(cap, dtype=torch.float32, device=X.device)
+    knn_idx = torch.empty((n, k), dtype=torch.int32, device=X.device) if want_knn else None
+    knn_d2 = torch.empty((n, k), dtype=torch.float32, device=X.device) if want_knn else None
+    nnz = C.c_int64(0)
+    bad = C.c_int32(0)
+    rc = L.tsne_build_P_approx(_ptr(X), n, d, perplexity, k, nlist, tau, kmeans_iters, _ptr(row_ptr), _ptr(col),
+                               _ptr(val), cap, C.byref(nnz), _ptr(knn_idx), _ptr(knn_d2), C.byref(bad), _ptr(work),
+                               b.value, _stream_ptr(stream))
+    if rc:
+        raise TsneError(rc, "tsne_build_P_approx", L.tsne_strerror(rc).decode())
     m = nnz.value
     return dict(row_ptr=row_ptr, col=col[:m], val=val[:m], nnz=m, unconverged=bad.value,
                 knn_idx=knn_idx, knn_d2=knn_d2)

@@ -1053,6 +1053,40 @@ int tsne_build_P_workspace_bytes(int32_t n, int32_t d, int32_t k, size_t *bytes)
         }                                                 \
     } while (0)
 
+// Alg. 1 line 2 from finished neighbour lists (L.knn_idx, L.knn_d2): Eq. (1) per row, then the symmetric CSR.
+static int finish_P(const Layout &L, int32_t n, int32_t k, float perplexity, int32_t *d_row_ptr, int32_t *d_col,
+                    float *d_val, int64_t cap_nnz, int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2,
+                    int32_t *n_unconverged, hipStream_t s)
+{
+    const size_t nk = (size_t)n * k;
+    const size_t ps_bytes = 64 * (size_t)(k | 1) * 8;
+    const int ps_staged = ps_bytes <= 60 * 1024 ? 1 : 0;
+    hipLaunchKernelGGL(perplexity_search, dim3((n + 63) / 64), dim3(64), ps_staged ? ps_bytes : 0, s, L.knn_d2, n, k,
+                       log((double)perplexity), 1e-10, L.cond, L.unconv, ps_staged);
+    // (the candidate buffers are free by now and hold 2 n k bytes with room to spare: 2 n k < 2^31 <= 8 * 65536 * 4160
+    // for a full query block, and 2 k < 8 * 4160 for a short one)
+    int16_t *slots = reinterpret_cast<int16_t *>(L.cand);
+    hipLaunchKernelGGL(sym_count, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, n, k, L.extra, slots);
+    hipLaunchKernelGGL(sym_scan, dim3(1), dim3(1024), 0, s, L.extra, n, k, d_row_ptr, L.cursor);
+    int32_t total = 0;
+    HIPCHK(hipMemcpyAsync(&total, d_row_ptr + n, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    if ((int64_t)total > cap_nnz) return TSNE_ENOSPC;
+    hipLaunchKernelGGL(sym_fill, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, L.cond, n, k, d_row_ptr,
+                       L.cursor, slots, d_col, d_val);
+    hipLaunchKernelGGL(sym_sort_rows, dim3(n), dim3(256), 0, s, d_row_ptr, n, d_col, d_val, L.sort_scratch);
+    if (d_knn_idx) HIPCHK(hipMemcpyAsync(d_knn_idx, L.knn_idx, 4 * nk, hipMemcpyDeviceToDevice, s));
+    if (d_knn_d2)
+        hipLaunchKernelGGL(d2_to_float, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_d2, d_knn_d2, nk);
+    int unconv = 0;
+    HIPCHK(hipMemcpyAsync(&unconv, L.unconv, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipGetLastError());
+    *nnz = total;
+    if (n_unconverged) *n_unconverged = unconv;
+    return TSNE_OK;
+}
+
 int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k, int32_t *d_row_ptr,
                  int32_t *d_col, float *d_val, int64_t cap_nnz, int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2,
                  int32_t *n_unconverged, void *d_workspace, size_t workspace_bytes, void *stream)
@@ -1148,33 +1182,55 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
         free(rows_h);
         HIPCHK(hipGetLastError());
     }
-    const size_t nk = (size_t)n * k;
-    const size_t ps_bytes = 64 * (size_t)(k | 1) * 8;
-    const int ps_staged = ps_bytes <= 60 * 1024 ? 1 : 0;
-    hipLaunchKernelGGL(perplexity_search, dim3((n + 63) / 64), dim3(64), ps_staged ? ps_bytes : 0, s, L.knn_d2, n, k,
-                       log((double)perplexity), 1e-10, L.cond, L.unconv, ps_staged);
-    // (the candidate buffers are free by now and hold 2 n k bytes with room to spare: 2 n k < 2^31 <= 8 * 65536 * 4160
-    // for a full query block, and 2 k < 8 * 4160 for a short one)
-    int16_t *slots = reinterpret_cast<int16_t *>(L.cand);
-    hipLaunchKernelGGL(sym_count, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, n, k, L.extra, slots);
-    hipLaunchKernelGGL(sym_scan, dim3(1), dim3(1024), 0, s, L.extra, n, k, d_row_ptr, L.cursor);
-    int32_t total = 0;
-    HIPCHK(hipMemcpyAsync(&total, d_row_ptr + n, 4, hipMemcpyDeviceToHost, s));
-    HIPCHK(hipStreamSynchronize(s));
-    if ((int64_t)total > cap_nnz) return TSNE_ENOSPC;
-    hipLaunchKernelGGL(sym_fill, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, L.cond, n, k, d_row_ptr,
-                       L.cursor, slots, d_col, d_val);
-    hipLaunchKernelGGL(sym_sort_rows, dim3(n), dim3(256), 0, s, d_row_ptr, n, d_col, d_val, L.sort_scratch);
-    if (d_knn_idx) HIPCHK(hipMemcpyAsync(d_knn_idx, L.knn_idx, 4 * nk, hipMemcpyDeviceToDevice, s));
-    if (d_knn_d2)
-        hipLaunchKernelGGL(d2_to_float, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_d2, d_knn_d2, nk);
-    int unconv = 0;
-    HIPCHK(hipMemcpyAsync(&unconv, L.unconv, 4, hipMemcpyDeviceToHost, s));
-    HIPCHK(hipStreamSynchronize(s));
-    HIPCHK(hipGetLastError());
-    *nnz = total;
-    if (n_unconverged) *n_unconverged = unconv;
+    return finish_P(L, n, k, perplexity, d_row_ptr, d_col, d_val, cap_nnz, nnz, d_knn_idx, d_knn_d2, n_unconverged, s);
+}
+
+static int approx_lists(int32_t n, int32_t nlist)
+{
+    if (nlist > 0) return nlist;
+    int v = (int)llround(sqrt((double)n));     // Sec. III-B: |C| = sqrt(N)
+    if (v < 1) v = 1;
+    if (v > 65536) v = 65536;
+    return v;
+}
+
+int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes)
+{
+    if (!bytes || check_args(n, d, k) != TSNE_OK) return TSNE_EINVAL;
+    nlist = approx_lists(n, nlist);
+    size_t ivf = 0;
+    if (tsne_ivf_workspace_bytes(n, d, k, nlist, tau, &ivf) != TSNE_OK) return TSNE_EINVAL;
+    *bytes = carve(nullptr, n, d, k, nullptr) + up(4 * (size_t)nlist * d) + ivf;
     return TSNE_OK;
+}
+
+int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k, int32_t nlist, int32_t tau,
+                        int32_t kmeans_iters, int32_t *d_row_ptr, int32_t *d_col, float *d_val, int64_t cap_nnz,
+                        int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged, void *d_workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    if (!d_X || !d_row_ptr || !d_col || !d_val || !nnz || !d_workspace || kmeans_iters < 0) return TSNE_EINVAL;
+    if (check_args(n, d, k) != TSNE_OK) return TSNE_EINVAL;
+    if (!(perplexity > 0.0f) || !(perplexity <= (float)k)) return TSNE_EINVAL;
+    if (((uintptr_t)d_workspace % ALIGN) != 0) return TSNE_EINVAL;
+    nlist = approx_lists(n, nlist);
+    size_t need = 0;
+    if (tsne_build_P_approx_workspace_bytes(n, d, k, nlist, tau, &need) != TSNE_OK) return TSNE_EINVAL;
+    if (workspace_bytes < need) return TSNE_ENOSPC;
+    hipStream_t s = (hipStream_t)stream;
+    Layout L;
+    size_t off = carve(&L, n, d, k, (char *)d_workspace);
+    float *centroids = (float *)((char *)d_workspace + off);
+    off += up(4 * (size_t)nlist * d);
+    void *ivf_ws = (char *)d_workspace + off;
+    const size_t ivf_bytes = workspace_bytes - off;
+    HIPCHK(hipMemsetAsync(L.unconv, 0, 4, s));
+    HIPCHK(hipMemsetAsync(L.extra, 0, 4 * (size_t)n, s));
+    int rc = ivf_train_device(d_X, n, d, nlist, kmeans_iters, centroids, ivf_ws, ivf_bytes, s);
+    if (rc != TSNE_OK) return rc;
+    rc = ivf_knn_device(d_X, n, d, centroids, nlist, tau, k, L.knn_idx, L.knn_d2, ivf_ws, ivf_bytes, s);
+    if (rc != TSNE_OK) return rc;
+    return finish_P(L, n, k, perplexity, d_row_ptr, d_col, d_val, cap_nnz, nnz, d_knn_idx, d_knn_d2, n_unconverged, s);
 }
 
 }  // extern "C"

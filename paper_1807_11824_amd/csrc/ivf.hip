@@ -1,0 +1,743 @@
+// Approximate neighbour search of Sec. III-B: inverted file over a k-means coarse quantiser, flat
+// second stage (Eq. 10-11 with q(y) = y).
+//
+//   ivf_probe        Eq. (10): for every point the tau nearest centroids (tau = 1: the quantiser q1)
+//   kmeans_accum / kmeans_finish   Lloyd update: centroid = mean of its points
+//   cell_hist / scan_cells / cell_scatter / gather_double   the inverted file: points grouped by list
+//   pair_hist / scan_pairs / pair_scatter   (query, probed list) pairs grouped by list
+//   ivf_score        squared distances of a list's points to the 64 queries of a tile that probe it
+//   ivf_select       Eq. (11): the k smallest of a query's distances, ordered by (distance, index)
+//
+// Every decision (nearest centroid, probed lists, the k nearest of the candidates) is taken on
+// squared distances summed in double precision from the float inputs, ties towards the lower
+// index, so the result is the definition's and does not depend on how the work is tiled.
+//
+// Distances are not a matrix product here: the work is N * tau * (points per list) * d, two
+// orders of magnitude below the exact search, and its cost is in moving and selecting the
+// distances, not in forming them.  A tile is 64 queries (one per lane, the chunk of their
+// coordinates transposed in LDS) against the rows of one list, which are the same for every lane
+// and come through scalar loads; each lane keeps eight running sums.
+#include "tsne_internal.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+namespace {
+
+constexpr size_t IVF_ALIGN = 256;
+inline size_t up256(size_t v) { return (v + IVF_ALIGN - 1) / IVF_ALIGN * IVF_ALIGN; }
+
+constexpr int IVF_DC = 64;       // coordinates per staged chunk
+constexpr int IVF_XS = 65;       // LDS pitch of a chunk row (odd: lanes writing one query column hit different banks)
+constexpr int IVF_CB = 8;        // list rows per register block
+constexpr int IVF_ECAP = 1024;   // distances equal (as floats) to the k-th that are ranked in LDS
+constexpr int IVF_LDS_KEYS = 16384;   // float keys of one query kept in LDS
+constexpr size_t IVF_D_MAX = (size_t)8 << 30;   // bytes of distance scratch used at most
+
+// ------------------------------------------------------------------ small helpers
+__global__ void to_double_k(const float *__restrict__ in, double *__restrict__ out, size_t m)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m) out[i] = (double)in[i];
+}
+
+__global__ void fill_i32_k(int *__restrict__ a, int v, size_t m)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m) a[i] = v;
+}
+
+__global__ void fill_u64_k(unsigned long long *__restrict__ a, size_t m)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m) a[i] = 0ull;
+}
+
+// starting centroids: rows floor(c n / nlist)
+__global__ void kmeans_init_k(const float *__restrict__ X, int n, int d, int nlist, float *__restrict__ C)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)nlist * d) return;
+    const int c = (int)(i / d), t = (int)(i % d);
+    const long long row = ((long long)c * n) / nlist;
+    C[i] = X[(size_t)row * d + t];
+}
+
+__global__ void max_abs_k(const float *__restrict__ X, size_t m, unsigned int *__restrict__ out)
+{
+    float v = 0.f;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < m; i += (size_t)gridDim.x * blockDim.x)
+        v = fmaxf(v, fabsf(X[i]));
+    v = wave_max(v);
+    if (lane_id() == 0) atomicMax(out, __float_as_uint(v));   // non-negative floats order like their bits
+}
+
+// ------------------------------------------------------------------ the distance tile
+// The chunk [t0, t0 + tl) of the coordinates of up to 64 rows of X, transposed: xs[t][row slot].
+__device__ __forceinline__ void stage_chunk(float *xs, const float *__restrict__ X, int d, int myrow, int nrows, int t0,
+                                            int tl)
+{
+    const int lane = lane_id();
+    for (int rr = 0; rr < nrows; ++rr) {
+        const int row = __shfl(myrow, rr);
+        xs[lane * IVF_XS + rr] = lane < tl ? X[(size_t)row * d + t0 + lane] : 0.0f;
+    }
+}
+
+// acc[j] += sum over the chunk of (x_lane[t] - Y[row0 + j][t0 + t])^2, rows past row_last read row_last
+__device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], const float *xs, const double *__restrict__ Y, int d,
+                                           int row0, int row_last, int t0, int tl)
+{
+    const int lane = lane_id();
+    const double *y[IVF_CB];
+#pragma unroll
+    for (int j = 0; j < IVF_CB; ++j) {
+        const int r = __builtin_amdgcn_readfirstlane(row0 + j < row_last ? row0 + j : row_last);
+        y[j] = Y + (size_t)r * d + t0;
+    }
+    int t = 0;
+    for (; t + 4 <= tl; t += 4) {     // four coordinates a trip: one wide scalar load per list row
+        double xv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) xv[u] = (double)xs[(t + u) * IVF_XS + lane];
+#pragma unroll
+        for (int j = 0; j < IVF_CB; ++j) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const double df = xv[u] - y[j][t + u];
+                acc[j] = fma(df, df, acc[j]);
+            }
+        }
+    }
+    for (; t < tl; ++t) {
+        const double xv = (double)xs[t * IVF_XS + lane];
+#pragma unroll
+        for (int j = 0; j < IVF_CB; ++j) {
+            const double df = xv - y[j][t];
+            acc[j] = fma(df, df, acc[j]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ Eq. (10)
+// One wave per 64 consecutive points, one point per lane; the lane's tau best (distance, centroid)
+// so far sit in LDS, ordered; centroids come in ascending index, so "strictly smaller" keeps the
+// lower index among equals.
+__global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int n, int d, const double *__restrict__ Cd,
+                                                int nlist, int tau, int32_t *__restrict__ probe)
+{
+    __shared__ float xs[IVF_DC * IVF_XS];
+    extern __shared__ __align__(16) unsigned char probe_dyn[];
+    double *pd = reinterpret_cast<double *>(probe_dyn);
+    int *pi = reinterpret_cast<int *>(probe_dyn + 8 * (size_t)WAVE * tau);
+    const int lane = lane_id();
+    const int i0 = blockIdx.x * WAVE, nrows = min(WAVE, n - i0);
+    const int i = min(i0 + lane, n - 1);
+    const bool single = d <= IVF_DC;
+    if (single) {
+        stage_chunk(xs, X, d, i, nrows, 0, d);
+        __syncthreads();
+    }
+    int have = 0;
+    double worst = INFINITY;
+    for (int c0 = 0; c0 < nlist; c0 += IVF_CB) {
+        double acc[IVF_CB];
+#pragma unroll
+        for (int j = 0; j < IVF_CB; ++j) acc[j] = 0.0;
+        for (int t0 = 0; t0 < d; t0 += IVF_DC) {
+            const int tl = min(IVF_DC, d - t0);
+            if (!single) {
+                __syncthreads();
+                stage_chunk(xs, X, d, i, nrows, t0, tl);
+                __syncthreads();
+            }
+            accumulate(acc, xs, Cd, d, c0, nlist - 1, t0, tl);
+        }
+#pragma unroll
+        for (int j = 0; j < IVF_CB; ++j) {
+            const int c = c0 + j;
+            const double v = acc[j];
+            if (c < nlist && (have < tau || v < worst)) {
+                int s = have < tau ? have : tau - 1;
+                while (s > 0 && pd[(s - 1) * WAVE + lane] > v) {
+                    pd[s * WAVE + lane] = pd[(s - 1) * WAVE + lane];
+                    pi[s * WAVE + lane] = pi[(s - 1) * WAVE + lane];
+                    --s;
+                }
+                pd[s * WAVE + lane] = v;
+                pi[s * WAVE + lane] = c;
+                if (have < tau) ++have;
+                if (have == tau) worst = pd[(tau - 1) * WAVE + lane];
+            }
+        }
+    }
+    if (i0 + lane < n)
+        for (int r = 0; r < tau; ++r) probe[(size_t)i * tau + r] = pi[r * WAVE + lane];
+}
+
+// ------------------------------------------------------------------ Lloyd update
+// Sums in fixed point (value * scale as a 64-bit integer): integer addition is associative, so the
+// mean does not depend on the order in which the atomics land.
+__global__ void kmeans_accum(const float *__restrict__ X, int n, int d, const int32_t *__restrict__ probe, int tau,
+                             double scale, unsigned long long *__restrict__ sums, int *__restrict__ counts)
+{
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)n * d) return;
+    const int i = (int)(idx / d), t = (int)(idx % d);
+    const int c = probe[(size_t)i * tau];
+    atomicAdd(&sums[(size_t)c * d + t], (unsigned long long)llrint((double)X[idx] * scale));
+    if (t == 0) atomicAdd(&counts[c], 1);
+}
+
+__global__ void kmeans_finish(const unsigned long long *__restrict__ sums, const int *__restrict__ counts, int nlist,
+                              int d, double inv_scale, float *__restrict__ C)
+{
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)nlist * d) return;
+    const int cnt = counts[idx / d];
+    if (cnt > 0) C[idx] = (float)((double)(long long)sums[idx] * inv_scale / (double)cnt);   // an empty cell keeps its centroid
+}
+
+// ------------------------------------------------------------------ grouping by list
+__global__ void cell_hist(const int32_t *__restrict__ probe, int n, int tau, int *__restrict__ cnt)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) atomicAdd(&cnt[probe[(size_t)i * tau]], 1);
+}
+
+// out[0] = 0, out[i + 1] = in[0] + .. + in[i]; with tiles != null also the same for ceil(in / 64).  One workgroup.
+__global__ __launch_bounds__(1024) void scan_counts(const int *__restrict__ in, int m, long long *__restrict__ out64,
+                                                    int *__restrict__ out32, int *__restrict__ tiles)
+{
+    __shared__ long long part[1024], tpart[1024];
+    const int tid = threadIdx.x;
+    const int chunk = (m + 1023) / 1024;
+    const int b = min(tid * chunk, m), e = min(b + chunk, m);
+    long long s = 0, ts = 0;
+    for (int i = b; i < e; ++i) { s += in[i]; ts += (in[i] + WAVE - 1) / WAVE; }
+    part[tid] = s;
+    tpart[tid] = ts;
+    __syncthreads();
+    if (tid == 0) {
+        long long a = 0, ta = 0;
+        for (int q = 0; q < 1024; ++q) {
+            const long long v = part[q], tv = tpart[q];
+            part[q] = a; tpart[q] = ta;
+            a += v; ta += tv;
+        }
+        if (out64) out64[m] = a;
+        if (out32) out32[m] = (int)a;
+        if (tiles) tiles[m] = (int)ta;
+    }
+    __syncthreads();
+    s = part[tid];
+    ts = tpart[tid];
+    for (int i = b; i < e; ++i) {
+        if (out64) out64[i] = s;
+        if (out32) out32[i] = (int)s;
+        if (tiles) tiles[i] = (int)ts;
+        s += in[i];
+        ts += (in[i] + WAVE - 1) / WAVE;
+    }
+}
+
+__global__ void cell_scatter(const int32_t *__restrict__ probe, int n, int tau, const int *__restrict__ cellptr,
+                             int *__restrict__ cursor, int *__restrict__ lorder)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int c = probe[(size_t)i * tau];
+    lorder[cellptr[c] + atomicAdd(&cursor[c], 1)] = i;   // the order inside a list does not matter to any result
+}
+
+__global__ void gather_double(const float *__restrict__ X, int n, int d, const int *__restrict__ lorder,
+                              double *__restrict__ Xl)
+{
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)n * d) return;
+    const size_t pos = idx / d, t = idx % d;
+    Xl[idx] = (double)X[(size_t)lorder[pos] * d + t];
+}
+
+// candidates a query sees: the sizes of its tau lists
+__global__ void msize_k(const int32_t *__restrict__ probe, int n, int tau, const int *__restrict__ cellptr,
+                        int *__restrict__ msize)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    int m = 0;
+    for (int r = 0; r < tau; ++r) {
+        const int c = probe[(size_t)i * tau + r];
+        m += cellptr[c + 1] - cellptr[c];
+    }
+    msize[i] = m;
+}
+
+__global__ void pair_hist(const int32_t *__restrict__ probe, int qb, int rows, int tau, int *__restrict__ bcnt)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < (size_t)rows * tau) atomicAdd(&bcnt[probe[(size_t)qb * tau + p]], 1);
+}
+
+__global__ void pair_scatter(const int32_t *__restrict__ probe, int qb, int rows, int tau,
+                             const int *__restrict__ pairptr, int *__restrict__ bcur, int *__restrict__ pairq,
+                             unsigned char *__restrict__ pairr)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= (size_t)rows * tau) return;
+    const int B = probe[(size_t)qb * tau + p];
+    const int pos = pairptr[B] + atomicAdd(&bcur[B], 1);
+    pairq[pos] = qb + (int)(p / tau);
+    pairr[pos] = (unsigned char)(p % tau);
+}
+
+// ------------------------------------------------------------------ distances of one list to the queries probing it
+// Workgroup = one wave = one tile: up to 64 (query, list) pairs of one list.  Lane's query q, the
+// list its r-th: the distances go to the query's row of the scratch, after the sizes of its lists
+// 0 .. r-1, in the list's order.  The query itself gets +inf.
+__global__ __launch_bounds__(64) void ivf_score(const float *__restrict__ X, int d, const double *__restrict__ Xl,
+                                                const int *__restrict__ lorder, const int *__restrict__ cellptr,
+                                                const int32_t *__restrict__ probe, int tau, int nlist,
+                                                const int *__restrict__ pairptr, const int *__restrict__ tileptr,
+                                                const int *__restrict__ pairq, const unsigned char *__restrict__ pairr,
+                                                const long long *__restrict__ mprefix, long long base0,
+                                                double *__restrict__ D)
+{
+    __shared__ float xs[IVF_DC * IVF_XS];
+    const int tile = blockIdx.x;
+    if (tile >= tileptr[nlist]) return;
+    int lo = 0, hi = nlist;            // last list whose first tile is <= tile and that has tiles
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tileptr[mid] <= tile) lo = mid; else hi = mid;
+    }
+    const int B = lo;
+    const int lane = lane_id();
+    const int p0 = pairptr[B] + WAVE * (tile - tileptr[B]);
+    const int np = min(WAVE, pairptr[B + 1] - p0);
+    const int p = p0 + min(lane, np - 1);
+    const int q = pairq[p], r = pairr[p];
+    long long off = mprefix[q] - base0;
+    for (int rr = 0; rr < r; ++rr) {
+        const int c = probe[(size_t)q * tau + rr];
+        off += cellptr[c + 1] - cellptr[c];
+    }
+    double *dst = D + off;
+    const int cb = cellptr[B], ce = cellptr[B + 1];
+    const bool single = d <= IVF_DC;
+    if (single) {
+        stage_chunk(xs, X, d, q, np, 0, d);
+        __syncthreads();
+    }
+    for (int c0 = cb; c0 < ce; c0 += IVF_CB) {
+        double acc[IVF_CB];
+#pragma unroll
+        for (int j = 0; j < IVF_CB; ++j) acc[j] = 0.0;
+        for (int t0 = 0; t0 < d; t0 += IVF_DC) {
+            const int tl = min(IVF_DC, d - t0);
+            if (!single) {
+                __syncthreads();
+                stage_chunk(xs, X, d, q, np, t0, tl);
+                __syncthreads();
+            }
+            accumulate(acc, xs, Xl, d, c0, ce - 1, t0, tl);
+        }
+        if (lane < np) {
+#pragma unroll
+            for (int j = 0; j < IVF_CB; ++j)
+                if (c0 + j < ce) dst[c0 - cb + j] = lorder[c0 + j] == q ? INFINITY : acc[j];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ Eq. (11): the k smallest of a row
+__device__ __forceinline__ uint32_t float_key(double v) { return __float_as_uint(__double2float_rz(v)); }
+__device__ __forceinline__ bool pair_less(double da, int ia, double db, int ib) { return da < db || (da == db && ia < ib); }
+
+// One workgroup per query.  The distances are non-negative, so a float rounded towards zero orders
+// like the double it came from (weakly): the k-th smallest float key bounds the set that can hold
+// the k smallest doubles.  Keys below it are in; the ones equal to it are ranked by (double, index).
+__global__ __launch_bounds__(256) void ivf_select(const double *__restrict__ D, const long long *__restrict__ mprefix,
+                                                  long long base0, int qb, int tau, int k,
+                                                  const int32_t *__restrict__ probe, const int *__restrict__ cellptr,
+                                                  const int *__restrict__ lorder, int lds_keys,
+                                                  int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2)
+{
+    extern __shared__ __align__(16) unsigned char sel_dyn[];
+    double *wd = reinterpret_cast<double *>(sel_dyn);                       // k winners, then IVF_ECAP equals
+    int *wi = reinterpret_cast<int *>(sel_dyn + 8 * (size_t)(k + IVF_ECAP));
+    uint32_t *fk = reinterpret_cast<uint32_t *>(sel_dyn + 12 * (size_t)(k + IVF_ECAP) + 8);
+    __shared__ uint32_t hist[256];
+    __shared__ int segoff[33], segbase[32];
+    __shared__ int sh_bucket, sh_need, sh_equal, wcount, ecount;
+    const int tid = threadIdx.x;
+    const int q = qb + blockIdx.x;
+    const double *src = D + (mprefix[q] - base0);
+    const int M = (int)(mprefix[q + 1] - mprefix[q]);
+    if (tid < tau) {
+        const int c = probe[(size_t)q * tau + tid];
+        segbase[tid] = cellptr[c];
+        segoff[tid + 1] = cellptr[c + 1] - cellptr[c];
+    }
+    if (tid == 0) { segoff[0] = 0; wcount = 0; ecount = 0; }
+    __syncthreads();
+    if (tid == 0)
+        for (int r = 0; r < tau; ++r) segoff[r + 1] += segoff[r];
+    const bool in_lds = M <= lds_keys;
+    if (in_lds)
+        for (int pos = tid; pos < M; pos += 256) fk[pos] = float_key(src[pos]);
+    __syncthreads();
+    auto key_at = [&](int pos) -> uint32_t { return in_lds ? fk[pos] : float_key(src[pos]); };
+    auto id_at = [&](int pos) -> int {
+        int r = 0;
+        while (r + 1 < tau && pos >= segoff[r + 1]) ++r;
+        return lorder[segbase[r] + pos - segoff[r]];
+    };
+    // the k-th smallest float key, a byte at a time from the top
+    uint32_t prefix = 0, mask = 0;
+    int need = k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        for (int pos = tid; pos < M; pos += 256) {
+            const uint32_t kk = key_at(pos);
+            if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int acc = 0, b = 0;
+            for (; b < 255; ++b) {
+                if (acc + (int)hist[b] >= need) break;
+                acc += (int)hist[b];
+            }
+            sh_bucket = b;
+            sh_need = need - acc;
+            sh_equal = (int)hist[b];
+        }
+        __syncthreads();
+        prefix |= (uint32_t)sh_bucket << shift;
+        mask |= 255u << shift;
+        need = sh_need;
+        __syncthreads();
+    }
+    const uint32_t Tf = prefix;
+    const int equal = sh_equal, less = k - need;     // keys == Tf; keys < Tf (all of them winners)
+    const bool small = equal <= IVF_ECAP;
+    for (int pos = tid; pos < M; pos += 256) {
+        const uint32_t kk = key_at(pos);
+        if (kk < Tf) {
+            const int s = atomicAdd(&wcount, 1);
+            wd[s] = src[pos];
+            wi[s] = id_at(pos);
+        } else if (kk == Tf && small) {
+            const int s = k + atomicAdd(&ecount, 1);
+            wd[s] = src[pos];
+            wi[s] = id_at(pos);
+        }
+    }
+    __syncthreads();
+    if (small) {
+        // the `need` first of the equals by (double, index)
+        for (int a = tid; a < equal; a += 256) {
+            const double da = wd[k + a];
+            const int ia = wi[k + a];
+            int rank = 0;
+            for (int b = 0; b < equal; ++b) rank += pair_less(wd[k + b], wi[k + b], da, ia);
+            if (rank < need) { wd[less + rank] = da; wi[less + rank] = ia; }
+        }
+    } else {
+        // (thousands of candidates at one float distance: duplicates.)  Select among them on the double's
+        // bits, then on the index, a byte at a time.
+        unsigned long long p64 = 0, m64 = 0;
+        int nd = need;
+        for (int shift = 56; shift >= 0; shift -= 8) {
+            hist[tid] = 0;
+            __syncthreads();
+            for (int pos = tid; pos < M; pos += 256) {
+                if (key_at(pos) != Tf) continue;
+                const unsigned long long db = (unsigned long long)__double_as_longlong(src[pos]);
+                if ((db & m64) == p64) atomicAdd(&hist[(unsigned)(db >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int acc = 0, b = 0;
+                for (; b < 255; ++b) {
+                    if (acc + (int)hist[b] >= nd) break;
+                    acc += (int)hist[b];
+                }
+                sh_bucket = b;
+                sh_need = nd - acc;
+                sh_equal = (int)hist[b];
+            }
+            __syncthreads();
+            p64 |= (unsigned long long)sh_bucket << shift;
+            m64 |= 255ull << shift;
+            nd = sh_need;
+            __syncthreads();
+        }
+        const int eq64 = sh_equal;
+        uint32_t pid = 0, mid = 0;
+        uint32_t Tid = 0xFFFFFFFFu;
+        if (nd < eq64) {
+            int ni = nd;
+            for (int shift = 24; shift >= 0; shift -= 8) {
+                hist[tid] = 0;
+                __syncthreads();
+                for (int pos = tid; pos < M; pos += 256) {
+                    if (key_at(pos) != Tf) continue;
+                    if ((unsigned long long)__double_as_longlong(src[pos]) != p64) continue;
+                    const uint32_t id = (uint32_t)id_at(pos);
+                    if ((id & mid) == pid) atomicAdd(&hist[(id >> shift) & 255u], 1u);
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    int acc = 0, b = 0;
+                    for (; b < 255; ++b) {
+                        if (acc + (int)hist[b] >= ni) break;
+                        acc += (int)hist[b];
+                    }
+                    sh_bucket = b;
+                    sh_need = ni - acc;
+                }
+                __syncthreads();
+                pid |= (uint32_t)sh_bucket << shift;
+                mid |= 255u << shift;
+                ni = sh_need;
+                __syncthreads();
+            }
+            Tid = pid;
+        }
+        for (int pos = tid; pos < M; pos += 256) {
+            if (key_at(pos) != Tf) continue;
+            const double v = src[pos];
+            const unsigned long long db = (unsigned long long)__double_as_longlong(v);
+            if (db > p64) continue;
+            const int id = id_at(pos);
+            if (db == p64 && (uint32_t)id > Tid) continue;
+            const int s = atomicAdd(&wcount, 1);
+            wd[s] = v;
+            wi[s] = id;
+        }
+    }
+    __syncthreads();
+    // final order by (distance, index)
+    for (int a = tid; a < k; a += 256) {
+        const double da = wd[a];
+        const int ia = wi[a];
+        int rank = 0;
+        for (int b = 0; b < k; ++b) rank += pair_less(wd[b], wi[b], da, ia);
+        knn_idx[(size_t)q * k + rank] = ia;
+        knn_d2[(size_t)q * k + rank] = da;
+    }
+}
+
+size_t select_lds(int k, int lds_keys) { return 12 * (size_t)(k + IVF_ECAP) + 8 + 4 * (size_t)lds_keys; }
+
+#define IVFCHK(call)                                      \
+    do {                                                  \
+        hipError_t e_ = (call);                           \
+        if (e_ != hipSuccess) {                           \
+            fprintf(stderr, "tsne ivf: %s failed: %s\n", #call, hipGetErrorString(e_)); \
+            return TSNE_EHIP;                             \
+        }                                                 \
+    } while (0)
+
+inline unsigned blocks(size_t m, int per = 256) { return (unsigned)((m + per - 1) / per); }
+
+struct IvfLayout {
+    double *Cd, *Xl, *D;
+    int32_t *probe;
+    int *cnt, *cellptr, *cursor, *lorder, *msize, *bcnt, *pairptr, *tileptr, *bcur, *pairq;
+    unsigned char *pairr;
+    long long *mprefix;
+    unsigned long long *sums;
+    unsigned int *maxabs;
+    size_t d_bytes;
+};
+
+constexpr int IVF_BATCH_ROWS = 1 << 17;
+
+size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, size_t avail)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up256(bytes); return (void *)p; };
+    const size_t rows = (size_t)(n < IVF_BATCH_ROWS ? n : IVF_BATCH_ROWS);
+    void *q;
+    q = take(8 * (size_t)nlist * d); if (L) L->Cd = (double *)q;
+    q = take(8 * (size_t)n * d); if (L) L->Xl = (double *)q;
+    q = take(4 * (size_t)n * tau); if (L) L->probe = (int32_t *)q;
+    q = take(4 * (size_t)(nlist + 1)); if (L) L->cnt = (int *)q;
+    q = take(4 * (size_t)(nlist + 1)); if (L) L->cellptr = (int *)q;
+    q = take(4 * (size_t)(nlist + 1)); if (L) L->cursor = (int *)q;
+    q = take(4 * (size_t)n); if (L) L->lorder = (int *)q;
+    q = take(4 * (size_t)n); if (L) L->msize = (int *)q;
+    q = take(8 * (size_t)(n + 1)); if (L) L->mprefix = (long long *)q;
+    q = take(4 * (size_t)(nlist + 1)); if (L) L->bcnt = (int *)q;
+    q = take(4 * (size_t)(nlist + 1)); if (L) L->pairptr = (int *)q;
+    q = take(4 * (size_t)(nlist + 1)); if (L) L->tileptr = (int *)q;
+    q = take(4 * (size_t)(nlist + 1)); if (L) L->bcur = (int *)q;
+    q = take(4 * rows * tau); if (L) L->pairq = (int *)q;
+    q = take(rows * tau); if (L) L->pairr = (unsigned char *)q;
+    q = take(8 * (size_t)nlist * d); if (L) L->sums = (unsigned long long *)q;
+    q = take(4); if (L) L->maxabs = (unsigned int *)q;
+    // distance scratch: whatever is left, at least one row of n distances, at most IVF_D_MAX
+    size_t want = 8 * (size_t)n * (size_t)(n < 4096 ? n : 4096);
+    if (want > IVF_D_MAX) want = IVF_D_MAX;
+    if (want < 8 * (size_t)n) want = 8 * (size_t)n;
+    if (!base) return off + up256(want);
+    size_t have = avail > off ? avail - off : 0;
+    if (have > IVF_D_MAX) have = IVF_D_MAX;
+    if (L) { L->D = (double *)(base + off); L->d_bytes = have / 8 * 8; }
+    return off + up256(want);
+}
+
+int ivf_check(int n, int d, int k, int nlist, int tau)
+{
+    if (n < 2 || d < 1 || d > 4096 || k < 1 || k >= n || k > 1920) return TSNE_EINVAL;
+    if (nlist < 1 || nlist > n || nlist > 65536 || tau < 1 || tau > 32 || tau > nlist) return TSNE_EINVAL;
+    if ((int64_t)n * tau > 0x7FFFFFFFll) return TSNE_EINVAL;
+    return TSNE_OK;
+}
+
+}  // namespace
+
+size_t ivf_workspace(int n, int d, int k, int nlist, int tau)
+{
+    (void)k;
+    return ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0);
+}
+
+// Lloyd's algorithm: `iters` rounds of (nearest centroid, mean of the members) from the rows floor(c n / nlist).
+int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *C, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    IvfLayout L;
+    if (ws_bytes < ivf_carve(nullptr, n, d, nlist, 1, nullptr, 0)) return TSNE_ENOSPC;
+    ivf_carve(&L, n, d, nlist, 1, (char *)ws, ws_bytes);
+    const size_t cd = (size_t)nlist * d, nd = (size_t)n * d;
+    hipLaunchKernelGGL(kmeans_init_k, dim3(blocks(cd)), dim3(256), 0, s, X, n, d, nlist, C);
+    IVFCHK(hipMemsetAsync(L.maxabs, 0, 4, s));
+    hipLaunchKernelGGL(max_abs_k, dim3(1024), dim3(256), 0, s, X, nd, L.maxabs);
+    unsigned int bits = 0;
+    IVFCHK(hipMemcpyAsync(&bits, L.maxabs, 4, hipMemcpyDeviceToHost, s));
+    IVFCHK(hipStreamSynchronize(s));
+    float xmax;
+    memcpy(&xmax, &bits, 4);
+    if (!(xmax < 1e38f)) return TSNE_EINVAL;
+    // |sum| < n * xmax < 2^(ln + e): scale by 2^(62 - ln - e)
+    int e = 0, ln = 0;
+    if (xmax > 0.f) frexpf(xmax, &e);
+    while ((1ll << ln) < (long long)n) ++ln;
+    const double scale = ldexp(1.0, 62 - ln - e), inv_scale = ldexp(1.0, -(62 - ln - e));
+    for (int it = 0; it < iters; ++it) {
+        hipLaunchKernelGGL(to_double_k, dim3(blocks(cd)), dim3(256), 0, s, C, L.Cd, cd);
+        hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE, s, X, n, d, L.Cd, nlist, 1,
+                           L.probe);
+        hipLaunchKernelGGL(fill_u64_k, dim3(blocks(cd)), dim3(256), 0, s, L.sums, cd);
+        hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist);
+        hipLaunchKernelGGL(kmeans_accum, dim3(blocks(nd)), dim3(256), 0, s, X, n, d, L.probe, 1, scale, L.sums, L.cnt);
+        hipLaunchKernelGGL(kmeans_finish, dim3(blocks(cd)), dim3(256), 0, s, L.sums, L.cnt, nlist, d, inv_scale, C);
+    }
+    IVFCHK(hipGetLastError());
+    return TSNE_OK;
+}
+
+// Eq. (10)-(11): neighbour lists of every row of X from the inverted file over the centroids C.
+int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int tau, int k, int32_t *knn_idx,
+                   double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    IvfLayout L;
+    if (ws_bytes < ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0)) return TSNE_ENOSPC;
+    ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes);
+    const size_t cd = (size_t)nlist * d, nd = (size_t)n * d;
+    hipLaunchKernelGGL(to_double_k, dim3(blocks(cd)), dim3(256), 0, s, C, L.Cd, cd);
+    hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE * tau, s, X, n, d, L.Cd, nlist,
+                       tau, L.probe);
+    hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist + 1);
+    hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cursor, 0, (size_t)nlist + 1);
+    hipLaunchKernelGGL(cell_hist, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cnt);
+    hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.cnt, nlist, (long long *)nullptr, L.cellptr, (int *)nullptr);
+    hipLaunchKernelGGL(cell_scatter, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.cursor, L.lorder);
+    hipLaunchKernelGGL(gather_double, dim3(blocks(nd)), dim3(256), 0, s, X, n, d, L.lorder, L.Xl);
+    hipLaunchKernelGGL(msize_k, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.msize);
+    hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.msize, n, L.mprefix, (int *)nullptr, (int *)nullptr);
+    long long *mp = (long long *)malloc(8 * ((size_t)n + 1));
+    if (!mp) return TSNE_ENOSPC;
+    hipError_t e = hipMemcpyAsync(mp, L.mprefix, 8 * ((size_t)n + 1), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) { free(mp); return TSNE_EHIP; }
+    long long mmax = 0;
+    int rc = TSNE_OK;
+    for (int i = 0; i < n; ++i) {
+        const long long m = mp[i + 1] - mp[i];
+        if (m - 1 < k) rc = TSNE_ENUM;            // fewer than k other points in the probed lists
+        if (m > mmax) mmax = m;
+    }
+    const long long d_cap = (long long)(L.d_bytes / 8);
+    if (rc == TSNE_OK && mmax > d_cap) rc = TSNE_ENOSPC;
+    if (rc != TSNE_OK) { free(mp); return rc; }
+    int lds_keys = (int)(mmax < IVF_LDS_KEYS ? mmax : IVF_LDS_KEYS);
+    lds_keys = (lds_keys + 63) / 64 * 64;
+    const size_t sel_bytes = select_lds(k, lds_keys);
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_select), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)select_lds(1920, IVF_LDS_KEYS));
+    if (e != hipSuccess) { free(mp); return TSNE_EHIP; }
+    for (int qb = 0; qb < n;) {
+        int qe = qb;
+        while (qe < n && qe - qb < IVF_BATCH_ROWS && mp[qe + 1] - mp[qb] <= d_cap) ++qe;
+        const int rows = qe - qb;
+        const size_t pairs = (size_t)rows * tau;
+        hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcnt, 0, (size_t)nlist + 1);
+        hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcur, 0, (size_t)nlist + 1);
+        hipLaunchKernelGGL(pair_hist, dim3(blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.bcnt);
+        hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.bcnt, nlist, (long long *)nullptr, L.pairptr, L.tileptr);
+        hipLaunchKernelGGL(pair_scatter, dim3(blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.pairptr, L.bcur,
+                           L.pairq, L.pairr);
+        const unsigned tiles = (unsigned)(pairs / WAVE + (size_t)nlist);
+        hipLaunchKernelGGL(ivf_score, dim3(tiles), dim3(WAVE), 0, s, X, d, L.Xl, L.lorder, L.cellptr, L.probe, tau, nlist,
+                           L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
+        hipLaunchKernelGGL(ivf_select, dim3(rows), dim3(256), sel_bytes, s, L.D, L.mprefix, mp[qb], qb, tau, k, L.probe,
+                           L.cellptr, L.lorder, lds_keys, knn_idx, knn_d2);
+        qb = qe;
+    }
+    free(mp);
+    IVFCHK(hipGetLastError());
+    return TSNE_OK;
+}
+
+extern "C" {
+
+int tsne_ivf_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes)
+{
+    if (!bytes || ivf_check(n, d, k, nlist, tau) != TSNE_OK) return TSNE_EINVAL;
+    *bytes = ivf_workspace(n, d, k, nlist, tau);
+    return TSNE_OK;
+}
+
+int tsne_ivf_train(const float *d_X, int32_t n, int32_t d, int32_t nlist, int32_t iters, float *d_centroids,
+                   void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d_X || !d_centroids || !d_workspace || iters < 0) return TSNE_EINVAL;
+    if (n < 1 || d < 1 || d > 4096 || nlist < 1 || nlist > n || nlist > 65536) return TSNE_EINVAL;
+    if (((uintptr_t)d_workspace % IVF_ALIGN) != 0) return TSNE_EINVAL;
+    int rc = ivf_train_device(d_X, n, d, nlist, iters, d_centroids, d_workspace, workspace_bytes, (hipStream_t)stream);
+    if (rc != TSNE_OK) return rc;
+    IVFCHK(hipStreamSynchronize((hipStream_t)stream));
+    return TSNE_OK;
+}
+
+int tsne_ivf_knn(const float *d_X, int32_t n, int32_t d, const float *d_centroids, int32_t nlist, int32_t tau, int32_t k,
+                 int32_t *d_knn_idx, double *d_knn_d2, void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d_X || !d_centroids || !d_knn_idx || !d_knn_d2 || !d_workspace) return TSNE_EINVAL;
+    if (ivf_check(n, d, k, nlist, tau) != TSNE_OK) return TSNE_EINVAL;
+    if (((uintptr_t)d_workspace % IVF_ALIGN) != 0) return TSNE_EINVAL;
+    int rc = ivf_knn_device(d_X, n, d, d_centroids, nlist, tau, k, d_knn_idx, d_knn_d2, d_workspace, workspace_bytes,
+                            (hipStream_t)stream);
+    if (rc != TSNE_OK) return rc;
+    IVFCHK(hipStreamSynchronize((hipStream_t)stream));
+    return TSNE_OK;
+}
+
+}  // extern "C"

@@ -138,6 +138,12 @@ inline bool ft_possible(const tsne_params *p)
 }
 hipError_t attract_far_tiled_prepare();   // once per process, before the first launch
 hipError_t small_sort_prepare();          // likewise
+
+// inverted-file neighbour search (ivf.hip); return a tsne_error
+size_t ivf_workspace(int n, int d, int k, int nlist, int tau);
+int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *C, void *ws, size_t ws_bytes, hipStream_t s);
+int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int tau, int k, int32_t *knn_idx,
+                   double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s);
 hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s);
 hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);

@@ -1,0 +1,115 @@
+"""GPU vs oracle: the inverted-file neighbour search (Sec. III-B, Eq. 10-11), its k-means and the P built on it.
+
+Both sides take every decision on squared distances in double precision with ties towards the lower index,
+so neighbour indices must agree exactly; distances differ only by the order of the summation."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ivf
+from paper_1807_11824_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _case(name):
+    r = np.random.default_rng(11)
+    if name == "blobs_50d":
+        X, _ = synth.gaussian_mixture(3000, 50, 4, 10.0, 1.0, seed=0)
+        return X, 40, 5, 30
+    if name == "two_chunks_and_tail":        # d = 130: two full chunks of 64 coordinates and two left over
+        X, _ = synth.gaussian_mixture(2500, 130, 6, 3.0, 1.0, seed=1)
+        return X, 50, 8, 90
+    if name == "all_lists":                  # tau = nlist: the exact search
+        X, _ = synth.gaussian_mixture(2000, 7, 3, 2.0, 1.0, seed=2)
+        return X, 10, 10, 60
+    if name == "every_row_five_times":       # ties at every distance, decided by index
+        base = r.standard_normal((500, 9)).astype(np.float32)
+        return np.repeat(base, 5, axis=0), 12, 4, 23
+    if name == "one_point_many_times":       # thousands of candidates at distance 0: selection by index alone
+        X = np.concatenate([np.tile(r.standard_normal((1, 6)).astype(np.float32), (2600, 1)),
+                            r.standard_normal((400, 6)).astype(np.float32)])
+        return X[r.permutation(3000)], 4, 2, 20
+    if name == "k_one":
+        X = r.standard_normal((700, 3)).astype(np.float32)
+        return X, 26, 3, 1
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("name", ["blobs_50d", "two_chunks_and_tail", "all_lists", "every_row_five_times",
+                                  "one_point_many_times", "k_one"])
+def test_ivf_knn_matches_oracle(name):
+    from paper_1807_11824_amd import ivf_knn
+    X, nlist, tau, k = _case(name)
+    print(f"case={name} n={X.shape[0]} d={X.shape[1]} nlist={nlist} tau={tau} k={k}", flush=True)
+    C, _ = ivf.kmeans_train(X, nlist, 4)
+    want_idx, want_d2 = ivf.ivf_knn(X, C, tau, k)
+    idx, d2 = ivf_knn(_dev(X), _dev(C), tau, k)
+    idx, d2 = idx.cpu().numpy(), d2.cpu().numpy()
+    assert np.array_equal(idx, want_idx)
+    assert np.allclose(d2, want_d2, rtol=1e-13, atol=1e-300)
+
+
+def test_several_passes_and_rows_longer_than_the_lds_keys():
+    """Large lists: a query sees about 30,000 candidates (more than the float keys kept in LDS) and the
+    distance scratch of the minimum workspace holds a fraction of the rows, so the search runs in passes."""
+    from paper_1807_11824_amd import ivf_knn
+    X, _ = synth.gaussian_mixture(40_000, 4, 5, 3.0, 1.0, seed=4)
+    C, _ = ivf.kmeans_train(X[::10], 4, 3)
+    rows = np.random.default_rng(0).choice(40_000, 300, replace=False)
+    want_idx, want_d2 = ivf.ivf_knn(X, C, 3, 40, rows=rows)
+    idx, d2 = ivf_knn(_dev(X), _dev(C), 3, 40)
+    assert np.array_equal(idx.cpu().numpy()[rows], want_idx)
+    assert np.allclose(d2.cpu().numpy()[rows], want_d2, rtol=1e-13, atol=1e-300)
+
+
+def test_too_few_candidates_is_reported():
+    from paper_1807_11824_amd import ivf_knn, TsneError
+    X = np.random.default_rng(1).standard_normal((200, 5)).astype(np.float32)
+    C = ivf.kmeans_init(X, 50)
+    with pytest.raises(TsneError) as e:
+        ivf_knn(_dev(X), _dev(C), 1, 30)
+    assert e.value.code == -5
+
+
+@pytest.mark.parametrize("n,d,nlist,iters", [(4000, 20, 30, 5), (1500, 70, 12, 3), (300, 3, 300, 2)])
+def test_kmeans_matches_oracle(n, d, nlist, iters):
+    """Same start, same rule; the means are exact sums here and double sums there, both rounded to float."""
+    from paper_1807_11824_amd import ivf_train
+    X, _ = synth.gaussian_mixture(n, d, 5, 4.0, 1.0, seed=6)
+    want, _ = ivf.kmeans_train(X, nlist, iters)
+    got = ivf_train(_dev(X), nlist, iters).cpu().numpy()
+    scale = np.abs(X).max()
+    assert np.abs(got - want).max() <= 1e-6 * scale
+    print("centroids equal bit for bit:", float(np.mean(got == want)), flush=True)
+
+
+def test_P_from_approximate_neighbours():
+    """tsne_build_P_approx against the oracle's pieces in the same order: k-means, search, Eq. (1), symmetric CSR."""
+    from paper_1807_11824_amd import build_P_approx
+    X, _ = synth.gaussian_mixture(3000, 50, 4, 10.0, 1.0, seed=0)
+    nlist, tau, k, perp, iters = 55, 6, 45, 15.0, 6            # nlist = round(sqrt(3000))
+    C, _ = ivf.kmeans_train(X, nlist, iters)
+    idx, d2 = ivf.ivf_knn(X, C, tau, k)
+    cond, _, bad = oracle.cond_p(d2, perp)
+    rp, col, val = oracle.symmetrise(idx, cond)
+    P = build_P_approx(_dev(X), perp, k, tau, nlist=0, kmeans_iters=iters, want_knn=True)
+    got_idx = P["knn_idx"].cpu().numpy()
+    same_rows = np.mean(np.all(got_idx == idx, axis=1))
+    print(f"rows with identical neighbour lists: {same_rows:.4f}", flush=True)
+    # the centroids of the two k-means may differ in the last bit of a float, which can move a point that
+    # sits on a cell border: allow a handful of rows
+    assert same_rows >= 0.995
+    if same_rows == 1.0:
+        assert np.array_equal(P["row_ptr"].cpu().numpy(), rp)
+        assert np.array_equal(P["col"].cpu().numpy(), col)
+        assert np.allclose(P["val"].cpu().numpy(), val, rtol=2e-6, atol=1e-30)
+        assert P["unconverged"] == bad
+    exact_idx, _ = oracle.knn(X, k)
+    print(f"recall at k = {k}: {ivf.recall(got_idx, exact_idx):.4f} (oracle's own lists: {ivf.recall(idx, exact_idx):.4f})",
+          flush=True)
