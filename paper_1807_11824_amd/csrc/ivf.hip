@@ -30,17 +30,21 @@ constexpr size_t IVF_ALIGN = 256;
 inline size_t up256(size_t v) { return (v + IVF_ALIGN - 1) / IVF_ALIGN * IVF_ALIGN; }
 
 constexpr int IVF_DC = 64;       // coordinates per staged chunk
-constexpr int IVF_XS = 65;       // LDS pitch of a chunk row (odd: lanes writing one query column hit different banks)
 constexpr int IVF_CB = 8;        // list rows per register block
-constexpr int IVF_ECAP = 1024;   // distances equal (as floats) to the k-th that are ranked in LDS
-constexpr int IVF_LDS_KEYS = 16384;   // float keys of one query kept in LDS
-constexpr size_t IVF_D_MAX = (size_t)8 << 30;   // bytes of distance scratch used at most
+constexpr int IVF_SAMPLE = 2048;      // keys of a row sampled for the cut
+constexpr int IVF_BUF_MIN = 1024, IVF_BUF_MAX = 4096;   // keys that may pass the cut (3 k within these bounds)
+constexpr int IVF_CCH = 256;          // list rows per tile of the distance kernel
+constexpr size_t IVF_D_MAX = (size_t)8 << 30;   // bytes of key scratch used at most
 
 // ------------------------------------------------------------------ small helpers
-__global__ void to_double_k(const float *__restrict__ in, double *__restrict__ out, size_t m)
+// rows of d floats -> rows of dp doubles (dp = d rounded up to a multiple of four, the rest zero)
+__global__ void to_double_k(const float *__restrict__ in, size_t rows, int d, int dp, double *__restrict__ out)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < m) out[i] = (double)in[i];
+    if (i >= rows * dp) return;
+    const size_t r = i / dp;
+    const int t = (int)(i % dp);
+    out[i] = t < d ? (double)in[r * d + t] : 0.0;
 }
 
 __global__ void fill_i32_k(int *__restrict__ a, int v, size_t m)
@@ -75,48 +79,37 @@ __global__ void max_abs_k(const float *__restrict__ X, size_t m, unsigned int *_
 }
 
 // ------------------------------------------------------------------ the distance tile
-// The chunk [t0, t0 + tl) of the coordinates of up to 64 rows of X, transposed: xs[t][row slot].
-__device__ __forceinline__ void stage_chunk(float *xs, const float *__restrict__ X, int d, int myrow, int nrows, int t0,
-                                            int tl)
+// A lane keeps a chunk of IVF_DC coordinates of its own row in registers (zero past the end of the row).
+__device__ __forceinline__ void load_chunk(float (&xr)[IVF_DC], const float *__restrict__ X, int d, int row, int t0, int tl)
 {
-    const int lane = lane_id();
-    for (int rr = 0; rr < nrows; ++rr) {
-        const int row = __shfl(myrow, rr);
-        xs[lane * IVF_XS + rr] = lane < tl ? X[(size_t)row * d + t0 + lane] : 0.0f;
-    }
+    const float *src = X + (size_t)row * d + t0;
+#pragma unroll
+    for (int t = 0; t < IVF_DC; ++t) xr[t] = t < tl ? src[t] : 0.0f;
 }
 
-// acc[j] += sum over the chunk of (x_lane[t] - Y[row0 + j][t0 + t])^2, rows past row_last read row_last
-__device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], const float *xs, const double *__restrict__ Y, int d,
-                                           int row0, int row_last, int t0, int tl)
+// acc[j] += sum over the chunk of (x_lane[t] - Y[row0 + j][t0 + t])^2; rows past row_last read row_last.
+// Y has rows of dp doubles, dp a multiple of four with zeros past d, so whole groups of four can be taken;
+// the rows are the same for every lane and arrive through scalar loads.
+__device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], const float (&xr)[IVF_DC], const double *__restrict__ Y,
+                                           int dp, int row0, int row_last, int t0, int tl)
 {
-    const int lane = lane_id();
     const double *y[IVF_CB];
 #pragma unroll
     for (int j = 0; j < IVF_CB; ++j) {
         const int r = __builtin_amdgcn_readfirstlane(row0 + j < row_last ? row0 + j : row_last);
-        y[j] = Y + (size_t)r * d + t0;
+        y[j] = Y + (size_t)r * dp + t0;
     }
-    int t = 0;
-    for (; t + 4 <= tl; t += 4) {     // four coordinates a trip: one wide scalar load per list row
-        double xv[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) xv[u] = (double)xs[(t + u) * IVF_XS + lane];
+    for (int t4 = 0; t4 < IVF_DC; t4 += 4) {
+        if (t4 < tl) {
 #pragma unroll
-        for (int j = 0; j < IVF_CB; ++j) {
+            for (int j = 0; j < IVF_CB; ++j) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const double df = xv[u] - y[j][t + u];
-                acc[j] = fma(df, df, acc[j]);
+                for (int u = 0; u < 4; ++u) {
+                    const double df = (double)xr[t4 + u] - y[j][t4 + u];
+                    acc[j] = fma(df, df, acc[j]);
+                }
             }
-        }
-    }
-    for (; t < tl; ++t) {
-        const double xv = (double)xs[t * IVF_XS + lane];
-#pragma unroll
-        for (int j = 0; j < IVF_CB; ++j) {
-            const double df = xv - y[j][t];
-            acc[j] = fma(df, df, acc[j]);
         }
     }
 }
@@ -125,21 +118,19 @@ __device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], const float *x
 // One wave per 64 consecutive points, one point per lane; the lane's tau best (distance, centroid)
 // so far sit in LDS, ordered; centroids come in ascending index, so "strictly smaller" keeps the
 // lower index among equals.
-__global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int n, int d, const double *__restrict__ Cd,
-                                                int nlist, int tau, int32_t *__restrict__ probe)
+__global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int n, int d, int dp,
+                                                const double *__restrict__ Cd, int nlist, int tau,
+                                                int32_t *__restrict__ probe)
 {
-    __shared__ float xs[IVF_DC * IVF_XS];
     extern __shared__ __align__(16) unsigned char probe_dyn[];
     double *pd = reinterpret_cast<double *>(probe_dyn);
     int *pi = reinterpret_cast<int *>(probe_dyn + 8 * (size_t)WAVE * tau);
     const int lane = lane_id();
-    const int i0 = blockIdx.x * WAVE, nrows = min(WAVE, n - i0);
+    const int i0 = blockIdx.x * WAVE;
     const int i = min(i0 + lane, n - 1);
     const bool single = d <= IVF_DC;
-    if (single) {
-        stage_chunk(xs, X, d, i, nrows, 0, d);
-        __syncthreads();
-    }
+    float xr[IVF_DC];
+    if (single) load_chunk(xr, X, d, i, 0, d);
     int have = 0;
     double worst = INFINITY;
     for (int c0 = 0; c0 < nlist; c0 += IVF_CB) {
@@ -148,12 +139,8 @@ __global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int
         for (int j = 0; j < IVF_CB; ++j) acc[j] = 0.0;
         for (int t0 = 0; t0 < d; t0 += IVF_DC) {
             const int tl = min(IVF_DC, d - t0);
-            if (!single) {
-                __syncthreads();
-                stage_chunk(xs, X, d, i, nrows, t0, tl);
-                __syncthreads();
-            }
-            accumulate(acc, xs, Cd, d, c0, nlist - 1, t0, tl);
+            if (!single) load_chunk(xr, X, d, i, t0, tl);
+            accumulate(acc, xr, Cd, dp, c0, nlist - 1, t0, tl);
         }
 #pragma unroll
         for (int j = 0; j < IVF_CB; ++j) {
@@ -207,16 +194,21 @@ __global__ void cell_hist(const int32_t *__restrict__ probe, int n, int tau, int
     if (i < n) atomicAdd(&cnt[probe[(size_t)i * tau]], 1);
 }
 
-// out[0] = 0, out[i + 1] = in[0] + .. + in[i]; with tiles != null also the same for ceil(in / 64).  One workgroup.
+// out[0] = 0, out[i + 1] = in[0] + .. + in[i]; with tiles != null also the same for the tiles of the distance
+// kernel, ceil(in[i] / 64) * ceil(length of list i / IVF_CCH).  One workgroup.
 __global__ __launch_bounds__(1024) void scan_counts(const int *__restrict__ in, int m, long long *__restrict__ out64,
-                                                    int *__restrict__ out32, int *__restrict__ tiles)
+                                                    int *__restrict__ out32, int *__restrict__ tiles,
+                                                    const int *__restrict__ cellptr)
 {
     __shared__ long long part[1024], tpart[1024];
     const int tid = threadIdx.x;
     const int chunk = (m + 1023) / 1024;
     const int b = min(tid * chunk, m), e = min(b + chunk, m);
+    auto ntiles = [&](int i) -> long long {
+        return (long long)((in[i] + WAVE - 1) / WAVE) * ((cellptr[i + 1] - cellptr[i] + IVF_CCH - 1) / IVF_CCH);
+    };
     long long s = 0, ts = 0;
-    for (int i = b; i < e; ++i) { s += in[i]; ts += (in[i] + WAVE - 1) / WAVE; }
+    for (int i = b; i < e; ++i) { s += in[i]; if (tiles) ts += ntiles(i); }
     part[tid] = s;
     tpart[tid] = ts;
     __syncthreads();
@@ -229,7 +221,7 @@ __global__ __launch_bounds__(1024) void scan_counts(const int *__restrict__ in, 
         }
         if (out64) out64[m] = a;
         if (out32) out32[m] = (int)a;
-        if (tiles) tiles[m] = (int)ta;
+        if (tiles) tiles[m] = (int)(ta < 0x7FFFFFFFll ? ta : 0x7FFFFFFFll);
     }
     __syncthreads();
     s = part[tid];
@@ -237,9 +229,8 @@ __global__ __launch_bounds__(1024) void scan_counts(const int *__restrict__ in, 
     for (int i = b; i < e; ++i) {
         if (out64) out64[i] = s;
         if (out32) out32[i] = (int)s;
-        if (tiles) tiles[i] = (int)ts;
+        if (tiles) { tiles[i] = (int)ts; ts += ntiles(i); }
         s += in[i];
-        ts += (in[i] + WAVE - 1) / WAVE;
     }
 }
 
@@ -252,13 +243,14 @@ __global__ void cell_scatter(const int32_t *__restrict__ probe, int n, int tau, 
     lorder[cellptr[c] + atomicAdd(&cursor[c], 1)] = i;   // the order inside a list does not matter to any result
 }
 
-__global__ void gather_double(const float *__restrict__ X, int n, int d, const int *__restrict__ lorder,
+__global__ void gather_double(const float *__restrict__ X, int n, int d, int dp, const int *__restrict__ lorder,
                               double *__restrict__ Xl)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)n * d) return;
-    const size_t pos = idx / d, t = idx % d;
-    Xl[idx] = (double)X[(size_t)lorder[pos] * d + t];
+    if (idx >= (size_t)n * dp) return;
+    const size_t pos = idx / dp;
+    const int t = (int)(idx % dp);
+    Xl[idx] = t < d ? (double)X[(size_t)lorder[pos] * d + t] : 0.0;
 }
 
 // candidates a query sees: the sizes of its tau lists
@@ -293,19 +285,21 @@ __global__ void pair_scatter(const int32_t *__restrict__ probe, int qb, int rows
     pairr[pos] = (unsigned char)(p % tau);
 }
 
+// what is kept of a distance for the selection: the nearest float, finite (so that +inf can mark the query itself)
+__device__ __forceinline__ float distance_key(double v) { return fminf((float)v, 3.4028234663852886e38f); }
+
 // ------------------------------------------------------------------ distances of one list to the queries probing it
 // Workgroup = one wave = one tile: up to 64 (query, list) pairs of one list.  Lane's query q, the
 // list its r-th: the distances go to the query's row of the scratch, after the sizes of its lists
 // 0 .. r-1, in the list's order.  The query itself gets +inf.
-__global__ __launch_bounds__(64) void ivf_score(const float *__restrict__ X, int d, const double *__restrict__ Xl,
+__global__ __launch_bounds__(64) void ivf_score(const float *__restrict__ X, int d, int dp, const double *__restrict__ Xl,
                                                 const int *__restrict__ lorder, const int *__restrict__ cellptr,
                                                 const int32_t *__restrict__ probe, int tau, int nlist,
                                                 const int *__restrict__ pairptr, const int *__restrict__ tileptr,
                                                 const int *__restrict__ pairq, const unsigned char *__restrict__ pairr,
                                                 const long long *__restrict__ mprefix, long long base0,
-                                                double *__restrict__ D)
+                                                float *__restrict__ D)
 {
-    __shared__ float xs[IVF_DC * IVF_XS];
     const int tile = blockIdx.x;
     if (tile >= tileptr[nlist]) return;
     int lo = 0, hi = nlist;            // last list whose first tile is <= tile and that has tiles
@@ -315,7 +309,11 @@ __global__ __launch_bounds__(64) void ivf_score(const float *__restrict__ X, int
     }
     const int B = lo;
     const int lane = lane_id();
-    const int p0 = pairptr[B] + WAVE * (tile - tileptr[B]);
+    // the list's tiles: query groups of 64 (fast index) times chunks of IVF_CCH of its rows
+    const int qgroups = (pairptr[B + 1] - pairptr[B] + WAVE - 1) / WAVE;
+    const int within = tile - tileptr[B];
+    const int chunk = within / qgroups;
+    const int p0 = pairptr[B] + WAVE * (within - chunk * qgroups);
     const int np = min(WAVE, pairptr[B + 1] - p0);
     const int p = p0 + min(lane, np - 1);
     const int q = pairq[p], r = pairr[p];
@@ -324,122 +322,204 @@ __global__ __launch_bounds__(64) void ivf_score(const float *__restrict__ X, int
         const int c = probe[(size_t)q * tau + rr];
         off += cellptr[c + 1] - cellptr[c];
     }
-    double *dst = D + off;
-    const int cb = cellptr[B], ce = cellptr[B + 1];
+    float *dst = D + off;
+    const int cb = cellptr[B], ce = min(cellptr[B + 1], cb + (chunk + 1) * IVF_CCH);
     const bool single = d <= IVF_DC;
-    if (single) {
-        stage_chunk(xs, X, d, q, np, 0, d);
-        __syncthreads();
-    }
-    for (int c0 = cb; c0 < ce; c0 += IVF_CB) {
+    float xr[IVF_DC];
+    if (single) load_chunk(xr, X, d, q, 0, d);
+    for (int c0 = cb + chunk * IVF_CCH; c0 < ce; c0 += IVF_CB) {
         double acc[IVF_CB];
 #pragma unroll
         for (int j = 0; j < IVF_CB; ++j) acc[j] = 0.0;
         for (int t0 = 0; t0 < d; t0 += IVF_DC) {
             const int tl = min(IVF_DC, d - t0);
-            if (!single) {
-                __syncthreads();
-                stage_chunk(xs, X, d, q, np, t0, tl);
-                __syncthreads();
-            }
-            accumulate(acc, xs, Xl, d, c0, ce - 1, t0, tl);
+            if (!single) load_chunk(xr, X, d, q, t0, tl);
+            accumulate(acc, xr, Xl, dp, c0, ce - 1, t0, tl);
         }
         if (lane < np) {
 #pragma unroll
             for (int j = 0; j < IVF_CB; ++j)
-                if (c0 + j < ce) dst[c0 - cb + j] = lorder[c0 + j] == q ? INFINITY : acc[j];
+                if (c0 + j < ce) dst[c0 - cb + j] = lorder[c0 + j] == q ? INFINITY : distance_key(acc[j]);
         }
     }
 }
 
 // ------------------------------------------------------------------ Eq. (11): the k smallest of a row
-__device__ __forceinline__ uint32_t float_key(double v) { return __float_as_uint(__double2float_rz(v)); }
+// What the distance kernel leaves per (query, candidate) is a float: the double sum rounded to nearest
+// (monotone, so it orders like the sum, weakly) and kept finite, +inf standing for the query itself.
+// The selection works on these keys and forms the sums again, with the same operations in the same
+// order, for the few candidates whose exact value decides something.
+__device__ __forceinline__ uint32_t key_bits(float f) { return __float_as_uint(f); }   // non-negative: ordered like the float
 __device__ __forceinline__ bool pair_less(double da, int ia, double db, int ib) { return da < db || (da == db && ia < ib); }
 
-// One workgroup per query.  The distances are non-negative, so a float rounded towards zero orders
-// like the double it came from (weakly): the k-th smallest float key bounds the set that can hold
-// the k smallest doubles.  Keys below it are in; the ones equal to it are ranked by (double, index).
-__global__ __launch_bounds__(256) void ivf_select(const double *__restrict__ D, const long long *__restrict__ mprefix,
+// |x_q - y|^2 for row q of X and row lp of the list-ordered copy, summed like accumulate() does
+__device__ __forceinline__ double exact_d2(const float *__restrict__ X, int d, int dp, const double *__restrict__ Xl, int q,
+                                           int lp)
+{
+    const float *x = X + (size_t)q * d;
+    const double *y = Xl + (size_t)lp * dp;
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) {
+        const double df = (double)x[t] - y[t];
+        acc = fma(df, df, acc);
+    }
+    return acc;
+}
+
+// The bucket of a 256-bin histogram that holds the need-th smallest element (1-based), how many of the
+// elements wanted fall inside it, and its count.  All 256 threads call it after the histogram is complete.
+__device__ __forceinline__ void find_bucket(const uint32_t *hist, int need, int *wtot, int *bucket, int *need_in,
+                                            int *count)
+{
+    const int tid = threadIdx.x;
+    const int h = (int)hist[tid];
+    int tot;
+    const int ex = wave_excl_scan(h, &tot);
+    if (lane_id() == 0) wtot[tid >> 6] = tot;
+    __syncthreads();
+    int before = ex;
+    for (int w = 0; w < (tid >> 6); ++w) before += wtot[w];
+    if (before < need && need <= before + h) { *bucket = tid; *need_in = need - before; *count = h; }
+    __syncthreads();
+}
+
+struct SelectShared {
+    uint32_t hist[256];
+    int wtot[4];
+    int bucket, need, count;
+};
+
+// The rank-th smallest (1-based) of count 32-bit keys read through key(i); all 256 threads.  Returns the key;
+// *need_in = how many of the rank smallest equal it, *equal = how many keys equal it.
+template <typename KeyFn>
+__device__ __forceinline__ uint32_t radix_kth(KeyFn key, int count, int rank, SelectShared &sh, int *need_in, int *equal)
+{
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, mask = 0;
+    int need = rank;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        sh.hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < count; i += 256) {
+            const uint32_t kk = key(i);
+            if ((kk & mask) == prefix) atomicAdd(&sh.hist[(kk >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        find_bucket(sh.hist, need, sh.wtot, &sh.bucket, &sh.need, &sh.count);
+        prefix |= (uint32_t)sh.bucket << shift;
+        mask |= 255u << shift;
+        need = sh.need;
+        __syncthreads();
+    }
+    *need_in = need;
+    *equal = sh.count;
+    return prefix;
+}
+
+// One workgroup per query.  A strided sample of the row's keys gives a cut that, almost always, a few
+// hundred keys pass, the k smallest among them: one sweep over the row collects those into LDS and the
+// rest happens there.  If the cut fails (fewer than k keys, or more than the buffer holds) the k-th
+// smallest key is found by sweeps over the whole row instead.  Keys below the k-th are in; the ones
+// equal to it are ranked by (exact sum, index).
+__global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, const long long *__restrict__ mprefix,
                                                   long long base0, int qb, int tau, int k,
                                                   const int32_t *__restrict__ probe, const int *__restrict__ cellptr,
-                                                  const int *__restrict__ lorder, int lds_keys,
+                                                  const int *__restrict__ lorder, const float *__restrict__ X, int d, int dp,
+                                                  const double *__restrict__ Xl, int buf,
                                                   int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2)
 {
     extern __shared__ __align__(16) unsigned char sel_dyn[];
-    double *wd = reinterpret_cast<double *>(sel_dyn);                       // k winners, then IVF_ECAP equals
-    int *wi = reinterpret_cast<int *>(sel_dyn + 8 * (size_t)(k + IVF_ECAP));
-    uint32_t *fk = reinterpret_cast<uint32_t *>(sel_dyn + 12 * (size_t)(k + IVF_ECAP) + 8);
-    __shared__ uint32_t hist[256];
+    double *wd = reinterpret_cast<double *>(sel_dyn);          // k winners, then up to buf equals
+    int *wi = reinterpret_cast<int *>(wd + (k + buf));         // their indices; before that, their positions in the row
+    uint32_t *bk = reinterpret_cast<uint32_t *>(wi + (k + buf));   // keys that passed the cut
+    int *bp = reinterpret_cast<int *>(bk + buf);               // and their positions in the row
+    uint32_t *sk = reinterpret_cast<uint32_t *>(wd + k);       // the sample (gone before the equals are written)
+    __shared__ SelectShared sh;
     __shared__ int segoff[33], segbase[32];
-    __shared__ int sh_bucket, sh_need, sh_equal, wcount, ecount;
+    __shared__ int bcount, wcount, ecount;
     const int tid = threadIdx.x;
     const int q = qb + blockIdx.x;
-    const double *src = D + (mprefix[q] - base0);
+    const float *src = F + (mprefix[q] - base0);
     const int M = (int)(mprefix[q + 1] - mprefix[q]);
     if (tid < tau) {
         const int c = probe[(size_t)q * tau + tid];
         segbase[tid] = cellptr[c];
         segoff[tid + 1] = cellptr[c + 1] - cellptr[c];
     }
-    if (tid == 0) { segoff[0] = 0; wcount = 0; ecount = 0; }
+    if (tid == 0) { segoff[0] = 0; bcount = 0; wcount = 0; ecount = 0; }
     __syncthreads();
     if (tid == 0)
         for (int r = 0; r < tau; ++r) segoff[r + 1] += segoff[r];
-    const bool in_lds = M <= lds_keys;
-    if (in_lds)
-        for (int pos = tid; pos < M; pos += 256) fk[pos] = float_key(src[pos]);
     __syncthreads();
-    auto key_at = [&](int pos) -> uint32_t { return in_lds ? fk[pos] : float_key(src[pos]); };
-    auto id_at = [&](int pos) -> int {
+    auto list_pos = [&](int pos) -> int {       // row position -> position in the list-ordered copy
         int r = 0;
         while (r + 1 < tau && pos >= segoff[r + 1]) ++r;
-        return lorder[segbase[r] + pos - segoff[r]];
+        return segbase[r] + pos - segoff[r];
     };
-    // the k-th smallest float key, a byte at a time from the top
-    uint32_t prefix = 0, mask = 0;
-    int need = k;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        hist[tid] = 0;
+    int cnt = 0;
+    bool direct;
+    if (M <= buf) {
+        for (int pos = tid; pos < M; pos += 256) { bk[pos] = key_bits(src[pos]); bp[pos] = pos; }
+        cnt = M;
+        direct = true;
         __syncthreads();
-        for (int pos = tid; pos < M; pos += 256) {
-            const uint32_t kk = key_at(pos);
-            if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1u);
-        }
+    } else {
+        for (int j = tid; j < IVF_SAMPLE; j += 256) sk[j] = key_bits(src[(long long)j * M / IVF_SAMPLE]);
         __syncthreads();
-        if (tid == 0) {
-            int acc = 0, b = 0;
-            for (; b < 255; ++b) {
-                if (acc + (int)hist[b] >= need) break;
-                acc += (int)hist[b];
+        // about k S / M of the sample lie below the k-th key of the row; twice that and a dozen more is
+        // more than three standard deviations above
+        int r = 2 * (int)(((long long)k * IVF_SAMPLE + M - 1) / M) + 12;
+        if (r > IVF_SAMPLE) r = IVF_SAMPLE;
+        int dummy_need, dummy_equal;
+        const uint32_t cut = radix_kth([&](int i) { return sk[i]; }, IVF_SAMPLE, r, sh, &dummy_need, &dummy_equal);
+        for (int base = 0; base < M; base += 8 * 256) {     // eight loads in flight per thread
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int pos = base + u * 256 + tid;
+                v[u] = pos < M ? src[pos] : INFINITY;
             }
-            sh_bucket = b;
-            sh_need = need - acc;
-            sh_equal = (int)hist[b];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int pos = base + u * 256 + tid;
+                const uint32_t kk = key_bits(v[u]);
+                if (pos < M && kk <= cut) {
+                    const int slot = atomicAdd(&bcount, 1);
+                    if (slot < buf) { bk[slot] = kk; bp[slot] = pos; }
+                }
+            }
         }
         __syncthreads();
-        prefix |= (uint32_t)sh_bucket << shift;
-        mask |= 255u << shift;
-        need = sh_need;
-        __syncthreads();
+        cnt = bcount;
+        direct = cnt >= k && cnt <= buf;
     }
-    const uint32_t Tf = prefix;
-    const int equal = sh_equal, less = k - need;     // keys == Tf; keys < Tf (all of them winners)
-    const bool small = equal <= IVF_ECAP;
-    for (int pos = tid; pos < M; pos += 256) {
-        const uint32_t kk = key_at(pos);
-        if (kk < Tf) {
-            const int s = atomicAdd(&wcount, 1);
-            wd[s] = src[pos];
-            wi[s] = id_at(pos);
-        } else if (kk == Tf && small) {
-            const int s = k + atomicAdd(&ecount, 1);
-            wd[s] = src[pos];
-            wi[s] = id_at(pos);
-        }
+    int need, equal;
+    uint32_t Tf;
+    if (direct) {
+        Tf = radix_kth([&](int i) { return bk[i]; }, cnt, k, sh, &need, &equal);
+    } else {
+        Tf = radix_kth([&](int i) { return key_bits(src[i]); }, M, k, sh, &need, &equal);
+        cnt = M;
+    }
+    const int less = k - need;                  // keys < Tf: all of them winners; keys == Tf: `equal` of them
+    const bool small = equal <= buf;
+    // positions of the winners (wi[0 .. less)) and of the equals (wi[k .. k + equal))
+    for (int i = tid; i < cnt; i += 256) {
+        const uint32_t kk = direct ? bk[i] : key_bits(src[i]);
+        const int pos = direct ? bp[i] : i;
+        if (kk < Tf) wi[atomicAdd(&wcount, 1)] = pos;
+        else if (kk == Tf && small) wi[k + atomicAdd(&ecount, 1)] = pos;
+    }
+    __syncthreads();
+    for (int a = tid; a < less + (small ? equal : 0); a += 256) {
+        const int slot = a < less ? a : k + (a - less);
+        const int lp = list_pos(wi[slot]);
+        wd[slot] = exact_d2(X, d, dp, Xl, q, lp);
+        wi[slot] = lorder[lp];
     }
     __syncthreads();
     if (small) {
-        // the `need` first of the equals by (double, index)
+        // the `need` first of the equals by (sum, index)
         for (int a = tid; a < equal; a += 256) {
             const double da = wd[k + a];
             const int ia = wi[k + a];
@@ -448,77 +528,61 @@ __global__ __launch_bounds__(256) void ivf_select(const double *__restrict__ D, 
             if (rank < need) { wd[less + rank] = da; wi[less + rank] = ia; }
         }
     } else {
-        // (thousands of candidates at one float distance: duplicates.)  Select among them on the double's
-        // bits, then on the index, a byte at a time.
+        // (More candidates at one float distance than the buffer holds: copies of one point.)  Among them
+        // select on the bits of the exact sum, then on the index, a byte at a time, with sweeps over the row.
         unsigned long long p64 = 0, m64 = 0;
         int nd = need;
         for (int shift = 56; shift >= 0; shift -= 8) {
-            hist[tid] = 0;
+            sh.hist[tid] = 0;
             __syncthreads();
             for (int pos = tid; pos < M; pos += 256) {
-                if (key_at(pos) != Tf) continue;
-                const unsigned long long db = (unsigned long long)__double_as_longlong(src[pos]);
-                if ((db & m64) == p64) atomicAdd(&hist[(unsigned)(db >> shift) & 255u], 1u);
+                if (key_bits(src[pos]) != Tf) continue;
+                const unsigned long long db =
+                    (unsigned long long)__double_as_longlong(exact_d2(X, d, dp, Xl, q, list_pos(pos)));
+                if ((db & m64) == p64) atomicAdd(&sh.hist[(unsigned)(db >> shift) & 255u], 1u);
             }
             __syncthreads();
-            if (tid == 0) {
-                int acc = 0, b = 0;
-                for (; b < 255; ++b) {
-                    if (acc + (int)hist[b] >= nd) break;
-                    acc += (int)hist[b];
-                }
-                sh_bucket = b;
-                sh_need = nd - acc;
-                sh_equal = (int)hist[b];
-            }
-            __syncthreads();
-            p64 |= (unsigned long long)sh_bucket << shift;
+            find_bucket(sh.hist, nd, sh.wtot, &sh.bucket, &sh.need, &sh.count);
+            p64 |= (unsigned long long)sh.bucket << shift;
             m64 |= 255ull << shift;
-            nd = sh_need;
+            nd = sh.need;
             __syncthreads();
         }
-        const int eq64 = sh_equal;
+        const int eq64 = sh.count;
         uint32_t pid = 0, mid = 0;
         uint32_t Tid = 0xFFFFFFFFu;
         if (nd < eq64) {
             int ni = nd;
             for (int shift = 24; shift >= 0; shift -= 8) {
-                hist[tid] = 0;
+                sh.hist[tid] = 0;
                 __syncthreads();
                 for (int pos = tid; pos < M; pos += 256) {
-                    if (key_at(pos) != Tf) continue;
-                    if ((unsigned long long)__double_as_longlong(src[pos]) != p64) continue;
-                    const uint32_t id = (uint32_t)id_at(pos);
-                    if ((id & mid) == pid) atomicAdd(&hist[(id >> shift) & 255u], 1u);
+                    if (key_bits(src[pos]) != Tf) continue;
+                    const int lp = list_pos(pos);
+                    if ((unsigned long long)__double_as_longlong(exact_d2(X, d, dp, Xl, q, lp)) != p64) continue;
+                    const uint32_t id = (uint32_t)lorder[lp];
+                    if ((id & mid) == pid) atomicAdd(&sh.hist[(id >> shift) & 255u], 1u);
                 }
                 __syncthreads();
-                if (tid == 0) {
-                    int acc = 0, b = 0;
-                    for (; b < 255; ++b) {
-                        if (acc + (int)hist[b] >= ni) break;
-                        acc += (int)hist[b];
-                    }
-                    sh_bucket = b;
-                    sh_need = ni - acc;
-                }
-                __syncthreads();
-                pid |= (uint32_t)sh_bucket << shift;
+                find_bucket(sh.hist, ni, sh.wtot, &sh.bucket, &sh.need, &sh.count);
+                pid |= (uint32_t)sh.bucket << shift;
                 mid |= 255u << shift;
-                ni = sh_need;
+                ni = sh.need;
                 __syncthreads();
             }
             Tid = pid;
         }
         for (int pos = tid; pos < M; pos += 256) {
-            if (key_at(pos) != Tf) continue;
-            const double v = src[pos];
+            if (key_bits(src[pos]) != Tf) continue;
+            const int lp = list_pos(pos);
+            const double v = exact_d2(X, d, dp, Xl, q, lp);
             const unsigned long long db = (unsigned long long)__double_as_longlong(v);
             if (db > p64) continue;
-            const int id = id_at(pos);
+            const int id = lorder[lp];
             if (db == p64 && (uint32_t)id > Tid) continue;
-            const int s = atomicAdd(&wcount, 1);
-            wd[s] = v;
-            wi[s] = id;
+            const int slot = atomicAdd(&wcount, 1);
+            wd[slot] = v;
+            wi[slot] = id;
         }
     }
     __syncthreads();
@@ -533,7 +597,14 @@ __global__ __launch_bounds__(256) void ivf_select(const double *__restrict__ D, 
     }
 }
 
-size_t select_lds(int k, int lds_keys) { return 12 * (size_t)(k + IVF_ECAP) + 8 + 4 * (size_t)lds_keys; }
+int select_buf(int k)
+{
+    int b = 3 * k;
+    if (b < IVF_BUF_MIN) b = IVF_BUF_MIN;
+    if (b > IVF_BUF_MAX) b = IVF_BUF_MAX;
+    return (b + 63) / 64 * 64;
+}
+size_t select_lds(int k, int buf) { return 12 * (size_t)(k + buf) + 8 * (size_t)buf; }
 
 #define IVFCHK(call)                                      \
     do {                                                  \
@@ -547,7 +618,8 @@ size_t select_lds(int k, int lds_keys) { return 12 * (size_t)(k + IVF_ECAP) + 8 
 inline unsigned blocks(size_t m, int per = 256) { return (unsigned)((m + per - 1) / per); }
 
 struct IvfLayout {
-    double *Cd, *Xl, *D;
+    double *Cd, *Xl;
+    float *D;
     int32_t *probe;
     int *cnt, *cellptr, *cursor, *lorder, *msize, *bcnt, *pairptr, *tileptr, *bcur, *pairq;
     unsigned char *pairr;
@@ -565,8 +637,9 @@ size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, siz
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up256(bytes); return (void *)p; };
     const size_t rows = (size_t)(n < IVF_BATCH_ROWS ? n : IVF_BATCH_ROWS);
     void *q;
-    q = take(8 * (size_t)nlist * d); if (L) L->Cd = (double *)q;
-    q = take(8 * (size_t)n * d); if (L) L->Xl = (double *)q;
+    const size_t dp = ((size_t)d + 3) / 4 * 4;
+    q = take(8 * (size_t)nlist * dp); if (L) L->Cd = (double *)q;
+    q = take(8 * (size_t)n * dp); if (L) L->Xl = (double *)q;
     q = take(4 * (size_t)n * tau); if (L) L->probe = (int32_t *)q;
     q = take(4 * (size_t)(nlist + 1)); if (L) L->cnt = (int *)q;
     q = take(4 * (size_t)(nlist + 1)); if (L) L->cellptr = (int *)q;
@@ -583,13 +656,13 @@ size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, siz
     q = take(8 * (size_t)nlist * d); if (L) L->sums = (unsigned long long *)q;
     q = take(4); if (L) L->maxabs = (unsigned int *)q;
     // distance scratch: whatever is left, at least one row of n distances, at most IVF_D_MAX
-    size_t want = 8 * (size_t)n * (size_t)(n < 4096 ? n : 4096);
+    size_t want = 4 * (size_t)n * (size_t)(n < 4096 ? n : 4096);
     if (want > IVF_D_MAX) want = IVF_D_MAX;
-    if (want < 8 * (size_t)n) want = 8 * (size_t)n;
+    if (want < 4 * (size_t)n) want = 4 * (size_t)n;
     if (!base) return off + up256(want);
     size_t have = avail > off ? avail - off : 0;
     if (have > IVF_D_MAX) have = IVF_D_MAX;
-    if (L) { L->D = (double *)(base + off); L->d_bytes = have / 8 * 8; }
+    if (L) { L->D = (float *)(base + off); L->d_bytes = have / 8 * 8; }
     return off + up256(want);
 }
 
@@ -616,6 +689,7 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     if (ws_bytes < ivf_carve(nullptr, n, d, nlist, 1, nullptr, 0)) return TSNE_ENOSPC;
     ivf_carve(&L, n, d, nlist, 1, (char *)ws, ws_bytes);
     const size_t cd = (size_t)nlist * d, nd = (size_t)n * d;
+    const int dp = (d + 3) / 4 * 4;
     hipLaunchKernelGGL(kmeans_init_k, dim3(blocks(cd)), dim3(256), 0, s, X, n, d, nlist, C);
     IVFCHK(hipMemsetAsync(L.maxabs, 0, 4, s));
     hipLaunchKernelGGL(max_abs_k, dim3(1024), dim3(256), 0, s, X, nd, L.maxabs);
@@ -631,8 +705,8 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     while ((1ll << ln) < (long long)n) ++ln;
     const double scale = ldexp(1.0, 62 - ln - e), inv_scale = ldexp(1.0, -(62 - ln - e));
     for (int it = 0; it < iters; ++it) {
-        hipLaunchKernelGGL(to_double_k, dim3(blocks(cd)), dim3(256), 0, s, C, L.Cd, cd);
-        hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE, s, X, n, d, L.Cd, nlist, 1,
+        hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
+        hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE, s, X, n, d, dp, L.Cd, nlist, 1,
                            L.probe);
         hipLaunchKernelGGL(fill_u64_k, dim3(blocks(cd)), dim3(256), 0, s, L.sums, cd);
         hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist);
@@ -650,18 +724,20 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
     IvfLayout L;
     if (ws_bytes < ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0)) return TSNE_ENOSPC;
     ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes);
-    const size_t cd = (size_t)nlist * d, nd = (size_t)n * d;
-    hipLaunchKernelGGL(to_double_k, dim3(blocks(cd)), dim3(256), 0, s, C, L.Cd, cd);
-    hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE * tau, s, X, n, d, L.Cd, nlist,
-                       tau, L.probe);
+    const int dp = (d + 3) / 4 * 4;
+    hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
+    hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE * tau, s, X, n, d, dp, L.Cd,
+                       nlist, tau, L.probe);
     hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cursor, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(cell_hist, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cnt);
-    hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.cnt, nlist, (long long *)nullptr, L.cellptr, (int *)nullptr);
+    hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.cnt, nlist, (long long *)nullptr, L.cellptr, (int *)nullptr,
+                       (const int *)nullptr);
     hipLaunchKernelGGL(cell_scatter, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.cursor, L.lorder);
-    hipLaunchKernelGGL(gather_double, dim3(blocks(nd)), dim3(256), 0, s, X, n, d, L.lorder, L.Xl);
+    hipLaunchKernelGGL(gather_double, dim3(blocks((size_t)n * dp)), dim3(256), 0, s, X, n, d, dp, L.lorder, L.Xl);
     hipLaunchKernelGGL(msize_k, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.msize);
-    hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.msize, n, L.mprefix, (int *)nullptr, (int *)nullptr);
+    hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.msize, n, L.mprefix, (int *)nullptr, (int *)nullptr,
+                       (const int *)nullptr);
     long long *mp = (long long *)malloc(8 * ((size_t)n + 1));
     if (!mp) return TSNE_ENOSPC;
     hipError_t e = hipMemcpyAsync(mp, L.mprefix, 8 * ((size_t)n + 1), hipMemcpyDeviceToHost, s);
@@ -674,14 +750,13 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
         if (m - 1 < k) rc = TSNE_ENUM;            // fewer than k other points in the probed lists
         if (m > mmax) mmax = m;
     }
-    const long long d_cap = (long long)(L.d_bytes / 8);
+    const long long d_cap = (long long)(L.d_bytes / 4);
     if (rc == TSNE_OK && mmax > d_cap) rc = TSNE_ENOSPC;
     if (rc != TSNE_OK) { free(mp); return rc; }
-    int lds_keys = (int)(mmax < IVF_LDS_KEYS ? mmax : IVF_LDS_KEYS);
-    lds_keys = (lds_keys + 63) / 64 * 64;
-    const size_t sel_bytes = select_lds(k, lds_keys);
+    const int buf = select_buf(k);
+    const size_t sel_bytes = select_lds(k, buf);
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_select), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)select_lds(1920, IVF_LDS_KEYS));
+                            (int)select_lds(1920, IVF_BUF_MAX));
     if (e != hipSuccess) { free(mp); return TSNE_EHIP; }
     for (int qb = 0; qb < n;) {
         int qe = qb;
@@ -691,14 +766,18 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
         hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcnt, 0, (size_t)nlist + 1);
         hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcur, 0, (size_t)nlist + 1);
         hipLaunchKernelGGL(pair_hist, dim3(blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.bcnt);
-        hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.bcnt, nlist, (long long *)nullptr, L.pairptr, L.tileptr);
+        hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.bcnt, nlist, (long long *)nullptr, L.pairptr, L.tileptr,
+                           L.cellptr);
         hipLaunchKernelGGL(pair_scatter, dim3(blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.pairptr, L.bcur,
                            L.pairq, L.pairr);
-        const unsigned tiles = (unsigned)(pairs / WAVE + (size_t)nlist);
-        hipLaunchKernelGGL(ivf_score, dim3(tiles), dim3(WAVE), 0, s, X, d, L.Xl, L.lorder, L.cellptr, L.probe, tau, nlist,
+        int tiles = 0;
+        e = hipMemcpyAsync(&tiles, L.tileptr + nlist, 4, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess || tiles <= 0 || tiles == 0x7FFFFFFF) { free(mp); return e != hipSuccess ? TSNE_EHIP : TSNE_ENOSPC; }
+        hipLaunchKernelGGL(ivf_score, dim3(tiles), dim3(WAVE), 0, s, X, d, dp, L.Xl, L.lorder, L.cellptr, L.probe, tau, nlist,
                            L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
         hipLaunchKernelGGL(ivf_select, dim3(rows), dim3(256), sel_bytes, s, L.D, L.mprefix, mp[qb], qb, tau, k, L.probe,
-                           L.cellptr, L.lorder, lds_keys, knn_idx, knn_d2);
+                           L.cellptr, L.lorder, X, d, dp, L.Xl, buf, knn_idx, knn_d2);
         qb = qe;
     }
     free(mp);
