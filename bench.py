@@ -120,6 +120,9 @@ def main():
     ap.add_argument("--sweep-n", default="500,1000,2000,4000,8000,16000,32000,64000,128000,512000,2000000,5000000")
     ap.add_argument("--sweep-iters", type=int, default=1000)
     ap.add_argument("--reorder-every", type=int, default=0, help="--sweep only: tsne_params.reorder_every")
+    ap.add_argument("--approx-tau", type=int, default=4,
+                    help="also time tsne_build_P_approx (inverted-file neighbour search, sqrt(N) lists, this many "
+                         "probed per query) on the same X and report its recall against the exact lists; 0 = skip")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for the profiler's byte counters)")
     args = ap.parse_args()
@@ -139,11 +142,26 @@ def main():
     Xd = torch.from_numpy(X).to(dev)
     torch.cuda.synchronize()
     t0 = time.time()
-    P = build_P(Xd, perp, k)
+    P = build_P(Xd, perp, k, want_knn=args.approx_tau > 0)
     torch.cuda.synchronize()
     t_build = time.time() - t0
-    del Xd
     nnz = P["nnz"]
+    approx = None
+    if args.approx_tau > 0:
+        # (not part of the timed steps, which use the exact P: the alternative first phase, timed beside it)
+        from paper_1807_11824_amd import build_P_approx
+        t0 = time.time()
+        Pa = build_P_approx(Xd, perp, k, args.approx_tau, nlist=0, kmeans_iters=10, want_knn=True)
+        torch.cuda.synchronize()
+        t_approx = time.time() - t0
+        rows = torch.randperm(n, device=dev, generator=torch.Generator(device=dev).manual_seed(0))[:20000]
+        hit = (Pa["knn_idx"][rows].long()[:, :, None] == P["knn_idx"][rows].long()[:, None, :]).any(-1)
+        approx = {"tau": args.approx_tau, "nlist": int(round(n ** 0.5)), "kmeans_iters": 10, "build_P_approx_s": t_approx,
+                  "recall_at_k": float(hit.float().mean().item()), "rows_sampled": int(rows.numel()), "nnz": Pa["nnz"]}
+        del Pa, hit
+    P["knn_idx"] = P["knn_d2"] = None
+    del Xd
+    torch.cuda.empty_cache()
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -229,6 +247,8 @@ def main():
                                     "tree_ms": tms["tree_ms"], "update_ms": tms["update_ms"]}},
     }
     out["end_to_end_s_1000_iters"] = t_build + t_setp + ms_step  # ms/step * 1000 steps / 1000 ms
+    if approx is not None:
+        out["approx_P"] = approx
     if not args.no_cpu_baseline:
         P_host = dict(row_ptr=P["row_ptr"].cpu().numpy(), col=P["col"].cpu().numpy(),
                       val=P["val"].cpu().numpy().astype(np.float64))

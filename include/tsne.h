@@ -177,8 +177,9 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
  *   Returns TSNE_ENUM if some row finds fewer than k other points in its tau lists (raise tau or lower
  *   nlist), TSNE_ENOSPC if one row's candidates do not fit the workspace's distance scratch.
  * Workspace (tsne_ivf_workspace_bytes; use the figure for the largest tau to be passed): 8 n d bytes for
- *   the copy of X grouped by list, 4 n tau, and a distance scratch of min(8 GiB, 8 n min(n, 4096)) bytes;
- *   more workspace than asked for is used (up to 8 GiB of scratch) to take more queries per pass.
+ *   the copy of X grouped by list, 4 n tau, and a scratch of min(8 GiB, 4 n min(n, 4096)) bytes for one
+ *   float per (query, candidate); more workspace than asked for is used (up to 8 GiB of scratch) to take
+ *   more queries per pass.
  * Limits: nlist <= min(n, 65536), tau <= min(nlist, 32), k <= 1920, d <= 4096, n tau < 2^31.
  * Both calls synchronise the stream before returning.
  */
