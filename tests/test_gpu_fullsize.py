@@ -79,3 +79,38 @@ def test_forces_in_bench_configuration(full):
     assert np.array_equal(want["keys"][perm], want["sorted_keys"])
     assert np.array_equal(np.sort(perm), np.arange(n))
     ts.close()
+
+
+def test_inverted_file_search_on_sampled_rows(full):
+    """tsne_ivf_knn at full size (1132 lists, 4 probed).  The oracle cannot assign 1.28M points to their lists in
+    reasonable time, so for each sampled query it walks all points in exact (distance, index) order and assigns
+    only the ones it meets: the first k whose list is among the query's probed lists are Eq. (11)'s answer."""
+    import torch
+    from oracle import ivf
+    from paper_1807_11824_amd import ivf_knn
+    X, cfg = full["X"], full["cfg"]
+    n, k, tau = cfg["n"], cfg["k"], 4
+    nlist = int(round(n ** 0.5))
+    C = ivf.kmeans_init(X, nlist)
+    dev = torch.device("cuda:0")
+    idx, d2 = ivf_knn(torch.from_numpy(X).to(dev), torch.from_numpy(C).to(dev), tau, k)
+    rows = np.sort(np.random.default_rng(1).choice(n, 16, replace=False))
+    got_idx = idx[rows.tolist()].cpu().numpy()
+    got_d2 = d2[rows.tolist()].cpu().numpy()
+    Xd = X.astype(np.float64)
+    for r, q in enumerate(rows):
+        probed = set(ivf.probes(X[q:q + 1], C, tau)[0].tolist())
+        diff = Xd - Xd[q]
+        dd = np.einsum("nd,nd->n", diff, diff)
+        order = np.lexsort((np.arange(n), dd))
+        want, want_d = [], []
+        for a in range(0, n, 512):
+            block = order[a:a + 512]
+            cells, _ = ivf.assign(X[block], C)
+            for j, c in zip(block, cells):
+                if j != q and int(c) in probed:
+                    want.append(int(j)); want_d.append(dd[j])
+            if len(want) >= k:
+                break
+        assert got_idx[r].tolist() == want[:k], f"row {q}"
+        assert np.allclose(got_d2[r], want_d[:k], rtol=1e-13, atol=1e-300)
