@@ -34,6 +34,7 @@ constexpr int IVF_CB = 8;        // list rows per register block
 constexpr int IVF_SAMPLE = 2048;      // keys of a row sampled for the cut
 constexpr int IVF_BUF_MIN = 1024, IVF_BUF_MAX = 4096;   // keys that may pass the cut (3 k within these bounds)
 constexpr int IVF_CCH = 256;          // list rows per tile of the distance kernel
+constexpr int IVF_QW = 4;             // query groups of 64 (waves) per tile: they read the same list rows at about the same time
 constexpr size_t IVF_D_MAX = (size_t)8 << 30;   // bytes of key scratch used at most
 
 // ------------------------------------------------------------------ small helpers
@@ -195,7 +196,7 @@ __global__ void cell_hist(const int32_t *__restrict__ probe, int n, int tau, int
 }
 
 // out[0] = 0, out[i + 1] = in[0] + .. + in[i]; with tiles != null also the same for the tiles of the distance
-// kernel, ceil(in[i] / 64) * ceil(length of list i / IVF_CCH).  One workgroup.
+// kernel, ceil(in[i] / (64 IVF_QW)) * ceil(length of list i / IVF_CCH).  One workgroup.
 __global__ __launch_bounds__(1024) void scan_counts(const int *__restrict__ in, int m, long long *__restrict__ out64,
                                                     int *__restrict__ out32, int *__restrict__ tiles,
                                                     const int *__restrict__ cellptr)
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(1024) void scan_counts(const int *__restrict__ in, 
     const int chunk = (m + 1023) / 1024;
     const int b = min(tid * chunk, m), e = min(b + chunk, m);
     auto ntiles = [&](int i) -> long long {
-        return (long long)((in[i] + WAVE - 1) / WAVE) * ((cellptr[i + 1] - cellptr[i] + IVF_CCH - 1) / IVF_CCH);
+        return (long long)((in[i] + IVF_QW * WAVE - 1) / (IVF_QW * WAVE)) * ((cellptr[i + 1] - cellptr[i] + IVF_CCH - 1) / IVF_CCH);
     };
     long long s = 0, ts = 0;
     for (int i = b; i < e; ++i) { s += in[i]; if (tiles) ts += ntiles(i); }
@@ -289,10 +290,10 @@ __global__ void pair_scatter(const int32_t *__restrict__ probe, int qb, int rows
 __device__ __forceinline__ float distance_key(double v) { return fminf((float)v, 3.4028234663852886e38f); }
 
 // ------------------------------------------------------------------ distances of one list to the queries probing it
-// Workgroup = one wave = one tile: up to 64 (query, list) pairs of one list.  Lane's query q, the
+// A wave takes up to 64 (query, list) pairs of one list.  Lane's query q, the
 // list its r-th: the distances go to the query's row of the scratch, after the sizes of its lists
 // 0 .. r-1, in the list's order.  The query itself gets +inf.
-__global__ __launch_bounds__(64) void ivf_score(const float *__restrict__ X, int d, int dp, const double *__restrict__ Xl,
+__global__ __launch_bounds__(IVF_QW * 64) void ivf_score(const float *__restrict__ X, int d, int dp, const double *__restrict__ Xl,
                                                 const int *__restrict__ lorder, const int *__restrict__ cellptr,
                                                 const int32_t *__restrict__ probe, int tau, int nlist,
                                                 const int *__restrict__ pairptr, const int *__restrict__ tileptr,
@@ -309,11 +310,12 @@ __global__ __launch_bounds__(64) void ivf_score(const float *__restrict__ X, int
     }
     const int B = lo;
     const int lane = lane_id();
-    // the list's tiles: query groups of 64 (fast index) times chunks of IVF_CCH of its rows
-    const int qgroups = (pairptr[B + 1] - pairptr[B] + WAVE - 1) / WAVE;
+    // the list's tiles: IVF_QW query groups of 64, one per wave (fast index), times chunks of IVF_CCH of its rows
+    const int qtiles = (pairptr[B + 1] - pairptr[B] + IVF_QW * WAVE - 1) / (IVF_QW * WAVE);
     const int within = tile - tileptr[B];
-    const int chunk = within / qgroups;
-    const int p0 = pairptr[B] + WAVE * (within - chunk * qgroups);
+    const int chunk = within / qtiles;
+    const int p0 = pairptr[B] + WAVE * (IVF_QW * (within - chunk * qtiles) + (int)(threadIdx.x >> 6));
+    if (p0 >= pairptr[B + 1]) return;
     const int np = min(WAVE, pairptr[B + 1] - p0);
     const int p = p0 + min(lane, np - 1);
     const int q = pairq[p], r = pairr[p];
@@ -774,7 +776,7 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
         e = hipMemcpyAsync(&tiles, L.tileptr + nlist, 4, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess || tiles <= 0 || tiles == 0x7FFFFFFF) { free(mp); return e != hipSuccess ? TSNE_EHIP : TSNE_ENOSPC; }
-        hipLaunchKernelGGL(ivf_score, dim3(tiles), dim3(WAVE), 0, s, X, d, dp, L.Xl, L.lorder, L.cellptr, L.probe, tau, nlist,
+        hipLaunchKernelGGL(ivf_score, dim3(tiles), dim3(IVF_QW * WAVE), 0, s, X, d, dp, L.Xl, L.lorder, L.cellptr, L.probe, tau, nlist,
                            L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
         hipLaunchKernelGGL(ivf_select, dim3(rows), dim3(256), sel_bytes, s, L.D, L.mprefix, mp[qb], qb, tau, k, L.probe,
                            L.cellptr, L.lorder, X, d, dp, L.Xl, buf, knn_idx, knn_d2);
