@@ -67,19 +67,24 @@ def cpu_baseline(Y0, P_host, seconds_hint=20.0):
                 sample=f"{iters} full iterations (tree + walk + attraction + update) of the same N={n} workload from Y0")
 
 
-def sweep(dev, overlap, sizes, n_iter, reorder_every):
+def sweep(dev, overlap, sizes, n_iter, reorder_every, approx_tau=0):
     """Stand-in for the paper's scaling experiment (Sec. IV-B: simulated 50-d data in four clusters): time of a
     whole run of n_iter iterations (exaggeration 12 for the first quarter), the phases of an iteration averaged
-    over the run, and the time of tsne_build_P, as N grows.  Perplexity 30, k = 90, theta = 0.5."""
+    over the run, and the time of tsne_build_P, as N grows.  Perplexity 30, k = 90, theta = 0.5.  With approx_tau > 0
+    P comes from the inverted-file search (sqrt(N) lists, approx_tau probed), which is the paper's own first phase;
+    the final KL divergence against that run's P and the objective's value are then not comparable between the two."""
     import torch
-    from paper_1807_11824_amd import Tsne, build_P, synth
+    from paper_1807_11824_amd import Tsne, build_P, build_P_approx, synth
     for n in sizes:
         X, _ = synth.gaussian_mixture(n, 50, 4, 10.0, 1.0, seed=0)
         Xd = torch.from_numpy(X).to(dev)
         del X
         torch.cuda.synchronize()
         t0 = time.time()
-        P = build_P(Xd, 30.0, 90)
+        if approx_tau > 0 and n > 90 * 8:
+            P = build_P_approx(Xd, 30.0, 90, min(approx_tau, int(round(n ** 0.5))))
+        else:
+            P = build_P(Xd, 30.0, 90)
         torch.cuda.synchronize()
         t_build = time.time() - t0
         del Xd
@@ -98,7 +103,7 @@ def sweep(dev, overlap, sizes, n_iter, reorder_every):
         st = ts.status()
         ts.close()
         print(json.dumps({"workload": "50-d, 4 Gaussian clusters (means N(0, 10^2), sigma 1)", "n": n, "nnz": P["nnz"],
-                          "n_iter": n_iter, "reorder_every": reorder_every, "run_s": round(dt, 4),
+                          "n_iter": n_iter, "reorder_every": reorder_every, "approx_tau": approx_tau, "run_s": round(dt, 4),
                           "ms_per_step": dt / n_iter * 1e3, "iterations_per_s": n_iter / dt,
                           "phases_ms": {k[:-3]: round(v, 4) for k, v in tm.items() if k.endswith("_ms")},
                           "build_P_s": round(t_build, 4), "set_P_s": round(t_setp, 4), "status": st}), flush=True)
@@ -120,6 +125,8 @@ def main():
     ap.add_argument("--sweep-n", default="500,1000,2000,4000,8000,16000,32000,64000,128000,512000,2000000,5000000")
     ap.add_argument("--sweep-iters", type=int, default=1000)
     ap.add_argument("--reorder-every", type=int, default=0, help="--sweep only: tsne_params.reorder_every")
+    ap.add_argument("--sweep-approx-tau", type=int, default=0,
+                    help="--sweep only: build P with tsne_build_P_approx, this many lists probed (0 = exact)")
     ap.add_argument("--approx-tau", type=int, default=4,
                     help="also time tsne_build_P_approx (inverted-file neighbour search, sqrt(N) lists, this many "
                          "probed per query) on the same X and report its recall against the exact lists; 0 = skip")
@@ -135,7 +142,8 @@ def main():
 
     dev = torch.device("cuda:0")
     if args.sweep:
-        sweep(dev, args.overlap, [int(v) for v in args.sweep_n.split(",")], args.sweep_iters, args.reorder_every)
+        sweep(dev, args.overlap, [int(v) for v in args.sweep_n.split(",")], args.sweep_iters, args.reorder_every,
+              args.sweep_approx_tau)
         return
     X, cfg = workload_inputs(args.workload)
     n, k, perp = cfg["n"], cfg["k"], cfg["perplexity"]
