@@ -3,20 +3,20 @@
 //
 //   ivf_probe        Eq. (10): for every point the tau nearest centroids (tau = 1: the quantiser q1)
 //   kmeans_accum / kmeans_finish   Lloyd update: centroid = mean of its points
-//   cell_hist / scan_cells / cell_scatter / gather_double   the inverted file: points grouped by list
-//   pair_hist / scan_pairs / pair_scatter   (query, probed list) pairs grouped by list
-//   ivf_score        squared distances of a list's points to the 64 queries of a tile that probe it
-//   ivf_select       Eq. (11): the k smallest of a query's distances, ordered by (distance, index)
+//   cell_hist / scan_counts / cell_scatter / gather_double   the inverted file: points grouped by list
+//   pair_hist / scan_counts / pair_scatter   (query, probed list) pairs grouped by list
+//   ivf_score        squared distances of a list's points to the queries that probe it, kept as float keys
+//   ivf_select       Eq. (11): the k smallest of a query's candidates, ordered by (distance, index)
 //
 // Every decision (nearest centroid, probed lists, the k nearest of the candidates) is taken on
 // squared distances summed in double precision from the float inputs, ties towards the lower
 // index, so the result is the definition's and does not depend on how the work is tiled.
 //
-// Distances are not a matrix product here: the work is N * tau * (points per list) * d, two
-// orders of magnitude below the exact search, and its cost is in moving and selecting the
-// distances, not in forming them.  A tile is 64 queries (one per lane, the chunk of their
-// coordinates transposed in LDS) against the rows of one list, which are the same for every lane
-// and come through scalar loads; each lane keeps eight running sums.
+// Distances are not a matrix product here: the work is N * tau * (points per list) * d, a percent
+// or two of the exact search's, and its cost is in moving and selecting the distances as much as
+// in forming them.  A wave takes 64 queries, one per lane, their coordinates in registers, against
+// the rows of one list, which are the same for every lane and come through scalar loads; each lane
+// keeps eight running sums.
 #include "tsne_internal.h"
 
 #include <math.h>
