@@ -38,11 +38,21 @@ def _case(name):
     if name == "k_one":
         X = r.standard_normal((700, 3)).astype(np.float32)
         return X, 26, 3, 1
+    if name == "one_list_all_but_self":      # a single list and k = n - 1: every candidate is a neighbour
+        X = r.standard_normal((130, 3)).astype(np.float32)
+        return X, 1, 1, 129
+    if name == "large_k":                    # k = 1500 of 5000 candidates: the cut lets about 3000 keys pass
+        X = r.standard_normal((5000, 5)).astype(np.float32)
+        return X, 7, 7, 1500
+    if name == "largest_k_cut_fails":        # k = 1900 of 9000: more keys pass the cut than the buffer holds
+        X = r.standard_normal((9000, 4)).astype(np.float32)
+        return X, 3, 3, 1900
     raise KeyError(name)
 
 
 @pytest.mark.parametrize("name", ["blobs_50d", "two_chunks_and_tail", "all_lists", "every_row_five_times",
-                                  "one_point_many_times", "k_one"])
+                                  "one_point_many_times", "k_one", "one_list_all_but_self", "large_k",
+                                  "largest_k_cut_fails"])
 def test_ivf_knn_matches_oracle(name):
     from paper_1807_11824_amd import ivf_knn
     X, nlist, tau, k = _case(name)
