@@ -851,25 +851,30 @@ __global__ __launch_bounds__(64) void perplexity_search(const double *__restrict
 }
 
 // ---- symmetrisation
-// slot of i in row j's neighbour list, or -1
-__device__ __forceinline__ int find_in_row(const int32_t *__restrict__ idx, int k, int j, int i)
-{
-    const int32_t *r = idx + (size_t)j * k;
-    for (int a = 0; a < k; ++a) if (r[a] == i) return a;
-    return -1;
-}
-
 // extra[j] = number of rows i that list j while j does not list i; slot[e] = where i sits in j's list
-// (-1 if it does not), kept for sym_fill (k <= 1280 fits 16 bits)
+// (-1 if it does not), kept for sym_fill (k <= 1280 fits 16 bits).  Sixteen lanes look one edge up: they
+// read 64 contiguous bytes of row j at a time, so a row costs its three or four cache lines once.
 __global__ __launch_bounds__(256) void sym_count(const int32_t *__restrict__ idx, int n, int k, int *__restrict__ extra,
                                                  int16_t *__restrict__ slot)
 {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (size_t)n * k) return;
-    const int i = (int)(e / k), j = idx[e];
-    const int sl = find_in_row(idx, k, j, i);
-    slot[e] = (int16_t)sl;
-    if (sl < 0) atomicAdd(&extra[j], 1);
+    const size_t e = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int sub = (int)(threadIdx.x & 15u), grp = (int)((threadIdx.x & 63u) >> 4);
+    const bool live = e < (size_t)n * k;
+    const size_t ee = live ? e : 0;
+    const int i = (int)(ee / k), j = idx[ee];
+    const int32_t *r = idx + (size_t)j * k;
+    int found = -1;
+    for (int a0 = 0; a0 < k; a0 += 16) {
+        const int a = a0 + sub;
+        const bool hit = a < k && r[a] == i;
+        const unsigned m = (unsigned)(__ballot(hit) >> (16 * grp)) & 0xFFFFu;
+        if (m != 0u && found < 0) found = a0 + __builtin_ctz(m);
+        if (__all(found >= 0)) break;
+    }
+    if (live && sub == 0) {
+        slot[e] = (int16_t)found;
+        if (found < 0) atomicAdd(&extra[j], 1);
+    }
 }
 
 // row_ptr[i] = sum_{r<i} (k + extra[r]); single block, n up to 2^30
@@ -1066,7 +1071,7 @@ static int finish_P(const Layout &L, int32_t n, int32_t k, float perplexity, int
     // (the candidate buffers are free by now and hold 2 n k bytes with room to spare: 2 n k < 2^31 <= 8 * 65536 * 4160
     // for a full query block, and 2 k < 8 * 4160 for a short one)
     int16_t *slots = reinterpret_cast<int16_t *>(L.cand);
-    hipLaunchKernelGGL(sym_count, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, n, k, L.extra, slots);
+    hipLaunchKernelGGL(sym_count, dim3((unsigned)((nk * 16 + 255) / 256)), dim3(256), 0, s, L.knn_idx, n, k, L.extra, slots);
     hipLaunchKernelGGL(sym_scan, dim3(1), dim3(1024), 0, s, L.extra, n, k, d_row_ptr, L.cursor);
     int32_t total = 0;
     HIPCHK(hipMemcpyAsync(&total, d_row_ptr + n, 4, hipMemcpyDeviceToHost, s));
