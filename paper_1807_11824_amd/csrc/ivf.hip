@@ -88,10 +88,33 @@ __device__ __forceinline__ void load_chunk(float (&xr)[IVF_DC], const float *__r
     for (int t = 0; t < IVF_DC; ++t) xr[t] = t < tl ? src[t] : 0.0f;
 }
 
+// The same for rows longer than one chunk, where the chunk is fetched again for every block of list rows:
+// lane t reads coordinate t0 + t of each of the wave's 64 rows (contiguous across the lanes), the values go
+// through this wave's 64 x 64 floats of LDS (slot of row r in line t: r ^ t) and come back one row per lane.
+__device__ __forceinline__ void load_chunk_lds(float (&xr)[IVF_DC], float *xs, const float *__restrict__ X, int d,
+                                               int myrow, int t0, int tl)
+{
+    const int lane = lane_id();
+    __builtin_amdgcn_wave_barrier();      // (the reads of the previous chunk come first)
+    for (int r0 = 0; r0 < WAVE; r0 += 16) {       // sixteen row loads in flight
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int row = __shfl(myrow, r0 + u);
+            v[u] = lane < tl ? X[(size_t)row * d + t0 + lane] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) xs[lane * IVF_DC + ((r0 + u) ^ lane)] = v[u];
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int t = 0; t < IVF_DC; ++t) xr[t] = xs[t * IVF_DC + (lane ^ t)];
+}
+
 // acc[j] += sum over the chunk of (x_lane[t] - Y[row0 + j][t0 + t])^2; rows past row_last read row_last.
 // Y has rows of dp doubles, dp a multiple of four with zeros past d, so whole groups of four can be taken;
 // the rows are the same for every lane and arrive through scalar loads.
-__device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], const float (&xr)[IVF_DC], const double *__restrict__ Y,
+__device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], float (&xr)[IVF_DC], const double *__restrict__ Y,
                                            int dp, int row0, int row_last, int t0, int tl)
 {
     const double *y[IVF_CB];
@@ -100,6 +123,10 @@ __device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], const float (&
         const int r = __builtin_amdgcn_readfirstlane(row0 + j < row_last ? row0 + j : row_last);
         y[j] = Y + (size_t)r * dp + t0;
     }
+    // (The coordinates stay floats between the calls: widened once outside the caller's loop they would
+    // take twice the registers and a wave slot per SIMD with them.)
+#pragma unroll
+    for (int t = 0; t < IVF_DC; ++t) asm volatile("" : "+v"(xr[t]));
 #pragma unroll
     for (int t4 = 0; t4 < IVF_DC; t4 += 4) {
         if (t4 < tl) {
@@ -119,6 +146,8 @@ __device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], const float (&
 // One wave per 64 consecutive points, one point per lane; the lane's tau best (distance, centroid)
 // so far sit in LDS, ordered; centroids come in ascending index, so "strictly smaller" keeps the
 // lower index among equals.
+// LONG: rows longer than one chunk (the chunk buffer in LDS is there)
+template <bool LONG>
 __global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int n, int d, int dp,
                                                 const double *__restrict__ Cd, int nlist, int tau,
                                                 int32_t *__restrict__ probe)
@@ -126,38 +155,47 @@ __global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int
     extern __shared__ __align__(16) unsigned char probe_dyn[];
     double *pd = reinterpret_cast<double *>(probe_dyn);
     int *pi = reinterpret_cast<int *>(probe_dyn + 8 * (size_t)WAVE * tau);
+    float *xs = reinterpret_cast<float *>(probe_dyn + 12 * (size_t)WAVE * tau);   // present when d > IVF_DC
     const int lane = lane_id();
     const int i0 = blockIdx.x * WAVE;
     const int i = min(i0 + lane, n - 1);
-    const bool single = d <= IVF_DC;
     float xr[IVF_DC];
-    if (single) load_chunk(xr, X, d, i, 0, d);
+    if (!LONG) load_chunk(xr, X, d, i, 0, d);
     int have = 0;
     double worst = INFINITY;
-    for (int c0 = 0; c0 < nlist; c0 += IVF_CB) {
-        double acc[IVF_CB];
+    // Long rows: a chunk of the coordinates serves four blocks of eight centroids before the next is fetched.
+    constexpr int NSUB = LONG ? 4 : 1;
+    for (int c0 = 0; c0 < nlist; c0 += NSUB * IVF_CB) {
+        double acc[NSUB][IVF_CB];
 #pragma unroll
-        for (int j = 0; j < IVF_CB; ++j) acc[j] = 0.0;
+        for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+            for (int j = 0; j < IVF_CB; ++j) acc[u][j] = 0.0;
         for (int t0 = 0; t0 < d; t0 += IVF_DC) {
             const int tl = min(IVF_DC, d - t0);
-            if (!single) load_chunk(xr, X, d, i, t0, tl);
-            accumulate(acc, xr, Cd, dp, c0, nlist - 1, t0, tl);
+            if (LONG) load_chunk_lds(xr, xs, X, d, i, t0, tl);
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u)
+                if (c0 + u * IVF_CB < nlist) accumulate(acc[u], xr, Cd, dp, c0 + u * IVF_CB, nlist - 1, t0, tl);
         }
 #pragma unroll
-        for (int j = 0; j < IVF_CB; ++j) {
-            const int c = c0 + j;
-            const double v = acc[j];
-            if (c < nlist && (have < tau || v < worst)) {
-                int s = have < tau ? have : tau - 1;
-                while (s > 0 && pd[(s - 1) * WAVE + lane] > v) {
-                    pd[s * WAVE + lane] = pd[(s - 1) * WAVE + lane];
-                    pi[s * WAVE + lane] = pi[(s - 1) * WAVE + lane];
-                    --s;
+        for (int u = 0; u < NSUB; ++u) {
+#pragma unroll
+            for (int j = 0; j < IVF_CB; ++j) {
+                const int c = c0 + u * IVF_CB + j;
+                const double v = acc[u][j];
+                if (c < nlist && (have < tau || v < worst)) {
+                    int s = have < tau ? have : tau - 1;
+                    while (s > 0 && pd[(s - 1) * WAVE + lane] > v) {
+                        pd[s * WAVE + lane] = pd[(s - 1) * WAVE + lane];
+                        pi[s * WAVE + lane] = pi[(s - 1) * WAVE + lane];
+                        --s;
+                    }
+                    pd[s * WAVE + lane] = v;
+                    pi[s * WAVE + lane] = c;
+                    if (have < tau) ++have;
+                    if (have == tau) worst = pd[(tau - 1) * WAVE + lane];
                 }
-                pd[s * WAVE + lane] = v;
-                pi[s * WAVE + lane] = c;
-                if (have < tau) ++have;
-                if (have == tau) worst = pd[(tau - 1) * WAVE + lane];
             }
         }
     }
@@ -293,6 +331,7 @@ __device__ __forceinline__ float distance_key(double v) { return fminf((float)v,
 // A wave takes up to 64 (query, list) pairs of one list.  Lane's query q, the
 // list its r-th: the distances go to the query's row of the scratch, after the sizes of its lists
 // 0 .. r-1, in the list's order.  The query itself gets +inf.
+template <bool LONG>
 __global__ __launch_bounds__(IVF_QW * 64) void ivf_score(const float *__restrict__ X, int d, int dp, const double *__restrict__ Xl,
                                                 const int *__restrict__ lorder, const int *__restrict__ cellptr,
                                                 const int32_t *__restrict__ probe, int tau, int nlist,
@@ -301,6 +340,7 @@ __global__ __launch_bounds__(IVF_QW * 64) void ivf_score(const float *__restrict
                                                 const long long *__restrict__ mprefix, long long base0,
                                                 float *__restrict__ D)
 {
+    extern __shared__ __align__(16) float score_dyn[];     // a chunk buffer per wave, present when d > IVF_DC
     const int tile = blockIdx.x;
     if (tile >= tileptr[nlist]) return;
     int lo = 0, hi = nlist;            // last list whose first tile is <= tile and that has tiles
@@ -326,22 +366,30 @@ __global__ __launch_bounds__(IVF_QW * 64) void ivf_score(const float *__restrict
     }
     float *dst = D + off;
     const int cb = cellptr[B], ce = min(cellptr[B + 1], cb + (chunk + 1) * IVF_CCH);
-    const bool single = d <= IVF_DC;
     float xr[IVF_DC];
-    if (single) load_chunk(xr, X, d, q, 0, d);
-    for (int c0 = cb + chunk * IVF_CCH; c0 < ce; c0 += IVF_CB) {
-        double acc[IVF_CB];
+    if (!LONG) load_chunk(xr, X, d, q, 0, d);
+    constexpr int NSUB = LONG ? 4 : 1;     // blocks of eight list rows served by one fetch of a chunk
+    for (int c0 = cb + chunk * IVF_CCH; c0 < ce; c0 += NSUB * IVF_CB) {
+        double acc[NSUB][IVF_CB];
 #pragma unroll
-        for (int j = 0; j < IVF_CB; ++j) acc[j] = 0.0;
+        for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+            for (int j = 0; j < IVF_CB; ++j) acc[u][j] = 0.0;
         for (int t0 = 0; t0 < d; t0 += IVF_DC) {
             const int tl = min(IVF_DC, d - t0);
-            if (!single) load_chunk(xr, X, d, q, t0, tl);
-            accumulate(acc, xr, Xl, dp, c0, ce - 1, t0, tl);
+            if (LONG) load_chunk_lds(xr, score_dyn + (threadIdx.x >> 6) * (IVF_DC * WAVE), X, d, q, t0, tl);
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u)
+                if (c0 + u * IVF_CB < ce) accumulate(acc[u], xr, Xl, dp, c0 + u * IVF_CB, ce - 1, t0, tl);
         }
         if (lane < np) {
 #pragma unroll
-            for (int j = 0; j < IVF_CB; ++j)
-                if (c0 + j < ce) dst[c0 - cb + j] = lorder[c0 + j] == q ? INFINITY : distance_key(acc[j]);
+            for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                for (int j = 0; j < IVF_CB; ++j) {
+                    const int c = c0 + u * IVF_CB + j;
+                    if (c < ce) dst[c - cb] = lorder[c] == q ? INFINITY : distance_key(acc[u][j]);
+                }
         }
     }
 }
@@ -599,6 +647,20 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
     }
 }
 
+// LDS for the chunk buffers of the distance kernels: none while a row fits one chunk
+size_t chunk_lds(int d, int waves) { return d > IVF_DC ? 4 * (size_t)IVF_DC * WAVE * waves : 0; }
+
+void launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nlist, int tau, int32_t *probe, hipStream_t s)
+{
+    const size_t lists = 12 * (size_t)WAVE * tau;
+    if (d > IVF_DC)
+        hipLaunchKernelGGL(ivf_probe<true>, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), lists + chunk_lds(d, 1), s, X, n, d, dp, Cd,
+                           nlist, tau, probe);
+    else
+        hipLaunchKernelGGL(ivf_probe<false>, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), lists, s, X, n, d, dp, Cd, nlist, tau,
+                           probe);
+}
+
 int select_buf(int k)
 {
     int b = 3 * k;
@@ -708,8 +770,7 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     const double scale = ldexp(1.0, 62 - ln - e), inv_scale = ldexp(1.0, -(62 - ln - e));
     for (int it = 0; it < iters; ++it) {
         hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
-        hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE, s, X, n, d, dp, L.Cd, nlist, 1,
-                           L.probe);
+        launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, s);
         hipLaunchKernelGGL(fill_u64_k, dim3(blocks(cd)), dim3(256), 0, s, L.sums, cd);
         hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist);
         hipLaunchKernelGGL(kmeans_accum, dim3(blocks(nd)), dim3(256), 0, s, X, n, d, L.probe, 1, scale, L.sums, L.cnt);
@@ -728,8 +789,7 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
     ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes);
     const int dp = (d + 3) / 4 * 4;
     hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
-    hipLaunchKernelGGL(ivf_probe, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), 12 * (size_t)WAVE * tau, s, X, n, d, dp, L.Cd,
-                       nlist, tau, L.probe);
+    launch_probe(X, n, d, dp, L.Cd, nlist, tau, L.probe, s);
     hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cursor, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(cell_hist, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cnt);
@@ -755,6 +815,9 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
     const long long d_cap = (long long)(L.d_bytes / 4);
     if (rc == TSNE_OK && mmax > d_cap) rc = TSNE_ENOSPC;
     if (rc != TSNE_OK) { free(mp); return rc; }
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_score<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)chunk_lds(IVF_DC + 1, IVF_QW));
+    if (e != hipSuccess) { free(mp); return TSNE_EHIP; }
     const int buf = select_buf(k);
     const size_t sel_bytes = select_lds(k, buf);
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_select), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -776,8 +839,12 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
         e = hipMemcpyAsync(&tiles, L.tileptr + nlist, 4, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess || tiles <= 0 || tiles == 0x7FFFFFFF) { free(mp); return e != hipSuccess ? TSNE_EHIP : TSNE_ENOSPC; }
-        hipLaunchKernelGGL(ivf_score, dim3(tiles), dim3(IVF_QW * WAVE), 0, s, X, d, dp, L.Xl, L.lorder, L.cellptr, L.probe, tau, nlist,
-                           L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
+        if (d > IVF_DC)
+            hipLaunchKernelGGL(ivf_score<true>, dim3(tiles), dim3(IVF_QW * WAVE), chunk_lds(d, IVF_QW), s, X, d, dp, L.Xl, L.lorder,
+                               L.cellptr, L.probe, tau, nlist, L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
+        else
+            hipLaunchKernelGGL(ivf_score<false>, dim3(tiles), dim3(IVF_QW * WAVE), 0, s, X, d, dp, L.Xl, L.lorder,
+                               L.cellptr, L.probe, tau, nlist, L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
         hipLaunchKernelGGL(ivf_select, dim3(rows), dim3(256), sel_bytes, s, L.D, L.mprefix, mp[qb], qb, tau, k, L.probe,
                            L.cellptr, L.lorder, X, d, dp, L.Xl, buf, knn_idx, knn_d2);
         qb = qe;
