@@ -28,13 +28,20 @@ def workload_inputs(name):
     """Synthetic X for the named configuration (recipes in paper_1807_11824_amd/synth.py).
 
     cfg5 is the headline N = 1,281,167.  Its P is built by tsne_build_P from a 1000-cluster
-    ReLU-Gaussian mixture drawn in D' = 64 dimensions instead of 2048: the exact brute-force kNN
-    at D = 2048 costs 6.7e15 flop and does not fit a benchmark run, while the per-iteration step
-    only sees P.  At D = 2048 the between-cluster squared distances exceed the within-cluster
+    ReLU-Gaussian mixture drawn in D' = 64 dimensions instead of 2048: drawing 10.5 GB on the host
+    and the exact brute-force kNN at D = 2048 take three quarters of a minute ("cfg5_nominal" runs
+    exactly that), while the per-iteration step only sees P.  At D = 2048 the between-cluster squared distances exceed the within-cluster
     ones by many standard deviations, so every point's neighbours lie in its own cluster; at
     D' = 64 the same is obtained by drawing the cluster means with scale 2 instead of 1.
     """
     from paper_1807_11824_amd import synth
+    if name == "cfg5_nominal":
+        # the recipe as stated, D = 2048: 10.5 GB of X, about 20 s to draw on the host and 25 s for the exact
+        # tsne_build_P; not the default because of that, the iterations only see P
+        c = dict(synth.CONFIGS["cfg5"])
+        X, _ = synth.config5()
+        c["d_used"] = c["d"]
+        return X, c
     c = dict(synth.CONFIGS[name])
     if name == "cfg5":
         X, _ = synth.gaussian_mixture(c["n"], STANDIN_D, 1000, STANDIN_MEAN_SCALE, 1.0, seed=0, relu=True)
@@ -230,7 +237,7 @@ def main():
     del Ys
     solo_achieved = attract_bytes / (tms["attract_ms"] * 1e-3) / 1e9 if tms["attract_ms"] > 0 else 0.0
     out = {
-        "metric": "BH t-SNE gradient iterations/sec at N=1.28M" if args.workload == "cfg5"
+        "metric": "BH t-SNE gradient iterations/sec at N=1.28M" if args.workload in ("cfg5", "cfg5_nominal")
                   else f"BH t-SNE gradient iterations/sec ({args.workload})",
         "value": args.steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
