@@ -12,11 +12,23 @@ __all__ = ["kmeans_init", "sq_dists", "assign", "kmeans_train", "probes", "ivf_l
 
 
 def kmeans_init(X, nlist):
-    """Starting centroids: the rows floor(c n / nlist), c = 0 .. nlist-1."""
+    """Starting centroids, spread out: from the sample of m = min(n, 8 nlist) rows floor(j n / m) take the
+    first, then nlist - 1 times the sample row farthest (squared distance in double, lowest j among equals)
+    from the ones taken so far."""
     X = np.asarray(X, np.float32)
     n = X.shape[0]
-    rows = (np.arange(nlist, dtype=np.int64) * n) // nlist
-    return X[rows].copy()
+    m = min(n, 8 * nlist)
+    rows = (np.arange(m, dtype=np.int64) * n) // m
+    S = X[rows].astype(np.float64)
+    chosen = [0]
+    diff = S - S[0]
+    mind = np.einsum("md,md->m", diff, diff)
+    for _ in range(1, nlist):
+        j = int(np.argmax(mind))            # first maximum = lowest j
+        chosen.append(j)
+        diff = S - S[j]
+        mind = np.minimum(mind, np.einsum("md,md->m", diff, diff))
+    return X[rows[chosen]].copy()
 
 
 def sq_dists(Xq, C):
@@ -39,7 +51,7 @@ def assign(X, C):
 
 
 def kmeans_train(X, nlist, iters):
-    """Lloyd's algorithm from kmeans_init: assign every point to its nearest centroid, move every
+    """Lloyd's algorithm from kmeans_init (which see): assign every point to its nearest centroid, move every
     centroid to the mean of its points (a centroid without points stays where it is).  Centroids are
     kept as float between the iterations.  Returns (centroids float32, inertia before each update)."""
     X = np.asarray(X, np.float32)

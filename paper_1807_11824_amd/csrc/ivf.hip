@@ -60,14 +60,59 @@ __global__ void fill_u64_k(unsigned long long *__restrict__ a, size_t m)
     if (i < m) a[i] = 0ull;
 }
 
-// starting centroids: rows floor(c n / nlist)
-__global__ void kmeans_init_k(const float *__restrict__ X, int n, int d, int nlist, float *__restrict__ C)
+// ---- starting centroids, spread out: from the sample of m rows floor(j n / m) the first, then again and
+// again the one farthest from those taken so far (squared distance in double, lowest j among equals)
+__device__ __forceinline__ long long sample_row(int j, int n, int m) { return ((long long)j * n) / m; }
+
+// mind[j] = min(mind[j], |sample j - sample sel[c]|^2); one wave per sample row
+__global__ __launch_bounds__(256) void fps_update(const float *__restrict__ X, int n, int d, int m,
+                                                  const int *__restrict__ sel, int c, double *__restrict__ mind, int first)
+{
+    const int j = blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+    if (j >= m) return;
+    const float *x = X + (size_t)sample_row(j, n, m) * d;
+    const float *y = X + (size_t)sample_row(sel[c], n, m) * d;
+    double acc = 0.0;
+    for (int t = lane_id(); t < d; t += WAVE) {
+        const double df = (double)x[t] - (double)y[t];
+        acc = fma(df, df, acc);
+    }
+    acc = wave_sum(acc);
+    if (lane_id() == 0) mind[j] = first ? acc : fmin(mind[j], acc);
+}
+
+// sel[c] = argmax_j mind[j], lowest j among equals; one workgroup
+__global__ __launch_bounds__(1024) void fps_argmax(const double *__restrict__ mind, int m, int *__restrict__ sel, int c)
+{
+    __shared__ double bv[1024];
+    __shared__ int bi[1024];
+    double v = -1.0;
+    int idx = 0x7FFFFFFF;
+    for (int j = threadIdx.x; j < m; j += 1024) {
+        const double w = mind[j];
+        if (w > v) { v = w; idx = j; }         // ascending j: a later equal value does not replace
+    }
+    bv[threadIdx.x] = v;
+    bi[threadIdx.x] = idx;
+    __syncthreads();
+    for (int o = 512; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            const double w = bv[threadIdx.x + o];
+            const int wi = bi[threadIdx.x + o];
+            if (w > bv[threadIdx.x] || (w == bv[threadIdx.x] && wi < bi[threadIdx.x])) { bv[threadIdx.x] = w; bi[threadIdx.x] = wi; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) sel[c] = bi[0];
+}
+
+__global__ void fps_gather(const float *__restrict__ X, int n, int d, int m, int nlist, const int *__restrict__ sel,
+                           float *__restrict__ C)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)nlist * d) return;
     const int c = (int)(i / d), t = (int)(i % d);
-    const long long row = ((long long)c * n) / nlist;
-    C[i] = X[(size_t)row * d + t];
+    C[i] = X[(size_t)sample_row(sel[c], n, m) * d + t];
 }
 
 __global__ void max_abs_k(const float *__restrict__ X, size_t m, unsigned int *__restrict__ out)
@@ -690,6 +735,8 @@ struct IvfLayout {
     long long *mprefix;
     unsigned long long *sums;
     unsigned int *maxabs;
+    double *mind;
+    int *sel;
     size_t d_bytes;
 };
 
@@ -719,6 +766,8 @@ size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, siz
     q = take(rows * tau); if (L) L->pairr = (unsigned char *)q;
     q = take(8 * (size_t)nlist * d); if (L) L->sums = (unsigned long long *)q;
     q = take(4); if (L) L->maxabs = (unsigned int *)q;
+    q = take(8 * 8 * (size_t)nlist); if (L) L->mind = (double *)q;
+    q = take(4 * (size_t)nlist); if (L) L->sel = (int *)q;
     // distance scratch: whatever is left, at least one row of n distances, at most IVF_D_MAX
     size_t want = 4 * (size_t)n * (size_t)(n < 4096 ? n : 4096);
     if (want > IVF_D_MAX) want = IVF_D_MAX;
@@ -746,7 +795,7 @@ size_t ivf_workspace(int n, int d, int k, int nlist, int tau)
     return ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0);
 }
 
-// Lloyd's algorithm: `iters` rounds of (nearest centroid, mean of the members) from the rows floor(c n / nlist).
+// Lloyd's algorithm: `iters` rounds of (nearest centroid, mean of the members) from a spread-out start.
 int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *C, void *ws, size_t ws_bytes, hipStream_t s)
 {
     IvfLayout L;
@@ -754,7 +803,15 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     ivf_carve(&L, n, d, nlist, 1, (char *)ws, ws_bytes);
     const size_t cd = (size_t)nlist * d, nd = (size_t)n * d;
     const int dp = (d + 3) / 4 * 4;
-    hipLaunchKernelGGL(kmeans_init_k, dim3(blocks(cd)), dim3(256), 0, s, X, n, d, nlist, C);
+    {
+        const int m = (long long)n < 8ll * nlist ? n : 8 * nlist;
+        hipLaunchKernelGGL(fill_i32_k, dim3(1), dim3(256), 0, s, L.sel, 0, (size_t)1);       // the first sample row
+        for (int c = 1; c < nlist; ++c) {
+            hipLaunchKernelGGL(fps_update, dim3((m + 3) / 4), dim3(256), 0, s, X, n, d, m, L.sel, c - 1, L.mind, c == 1 ? 1 : 0);
+            hipLaunchKernelGGL(fps_argmax, dim3(1), dim3(1024), 0, s, L.mind, m, L.sel, c);
+        }
+        hipLaunchKernelGGL(fps_gather, dim3(blocks(cd)), dim3(256), 0, s, X, n, d, m, nlist, L.sel, C);
+    }
     IVFCHK(hipMemsetAsync(L.maxabs, 0, 4, s));
     hipLaunchKernelGGL(max_abs_k, dim3(1024), dim3(256), 0, s, X, nd, L.maxabs);
     unsigned int bits = 0;

@@ -59,15 +59,29 @@ def test_sq_dists_against_plain_loops():
             assert abs(D[i, c] - s) <= 1e-14 * s
 
 
+def test_start_is_spread_out_by_hand():
+    """Eight points on a line, three centroids, all eight in the sample: the first row, then the farthest
+    from it, then the farthest from both (ties to the lower row)."""
+    X = np.array([0, 1, 2, 3, 10, 11, 20, 21], np.float32)[:, None]
+    assert ivf.kmeans_init(X, 3)[:, 0].tolist() == [0.0, 21.0, 10.0]     # 10 and 11 are both 10 away: the lower row
+    assert ivf.kmeans_init(X, 1)[:, 0].tolist() == [0.0]
+    # copies only: every distance is zero and the first sample row is taken again and again
+    assert ivf.kmeans_init(np.ones((5, 2), np.float32), 3).tolist() == [[1.0, 1.0]] * 3
+    # the sample: m = min(n, 8 nlist) rows floor(j n / m); with n = 100, nlist = 2 these are rows 0, 6, 12, 18, ...
+    Y = np.arange(100, dtype=np.float32)[:, None]
+    assert ivf.kmeans_init(Y, 2)[:, 0].tolist() == [0.0, float((15 * 100) // 16)]
+
+
 def test_kmeans_separated_groups_reach_the_group_means_in_one_step():
-    """Three groups far apart, stored one after the other: the starting rows 0, n/3, 2n/3 fall one into each,
-    every point's nearest centroid is its own group's, and one update gives the three means."""
+    """Three groups far apart: the spread-out start puts one centroid into each, every point's nearest centroid
+    is its own group's, and one update gives the three means."""
     r = np.random.default_rng(3)
     groups = [r.standard_normal((40, 6)) + 100.0 * g for g in range(3)]
     X = np.concatenate(groups).astype(np.float32)
     C, inertia = ivf.kmeans_train(X, 3, 2)
     want = np.stack([X[40 * g:40 * g + 40].astype(np.float64).mean(axis=0) for g in range(3)])
-    assert np.allclose(C, want, rtol=0, atol=1e-5)
+    order = np.argsort(C[:, 0])
+    assert np.allclose(C[order], want, rtol=0, atol=1e-5)
     assert inertia[1] < inertia[0]
     # a fixed point: another pass changes nothing
     C2, _ = ivf.kmeans_train(X, 3, 5)
@@ -78,10 +92,11 @@ def test_kmeans_inertia_never_rises_and_empty_cells_stay():
     X, _ = synth.gaussian_mixture(900, 8, 4, 5.0, 1.0, seed=5)
     C, inertia = ivf.kmeans_train(X, 30, 8)
     assert all(b <= a * (1 + 1e-6) for a, b in zip(inertia, inertia[1:]))   # (centroids are rounded to float)
-    # two copies of one point as starting centroids: the second never gets a point and must not move
-    Xd = np.concatenate([np.zeros((2, 3), np.float32), np.ones((2, 3), np.float32)])   # rows 0, 1 equal; n=4, nlist=4
+    # two points, each twice, four centroids: the start is (0,0,0), (1,1,1) and twice more (0,0,0); the copies
+    # never win a point against the first (ties go to the lower index) and must not move
+    Xd = np.concatenate([np.zeros((2, 3), np.float32), np.ones((2, 3), np.float32)])
     C, _ = ivf.kmeans_train(Xd, 4, 3)
-    assert np.array_equal(C[1], Xd[1]) and np.array_equal(C[3], Xd[3])
+    assert C.tolist() == [[0.0] * 3, [1.0] * 3, [0.0] * 3, [0.0] * 3]
 
 
 def test_more_lists_never_hurt():
