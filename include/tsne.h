@@ -196,13 +196,15 @@ int tsne_ivf_knn(const float *d_X, int32_t n, int32_t d, const float *d_centroid
  * tsne_build_P with the neighbours of Sec. III-B's approximate search instead of the exact ones:
  * tsne_ivf_train (nlist centroids, kmeans_iters rounds; nlist = 0 takes the paper's sqrt(n)), tsne_ivf_knn
  * (tau lists per query), then Eq. (1) and the symmetric CSR exactly as in tsne_build_P.  Same outputs,
- * same limits as both; errors as tsne_ivf_knn.
+ * same limits as both.  If some row finds fewer than k other points in its tau lists the search is
+ * repeated for all rows with twice the lists, up to min(32, nlist), before TSNE_ENUM is returned;
+ * *tau_used (host, may be NULL) receives the number of lists the result was built with.
  */
 int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes);
 int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k, int32_t nlist,
                         int32_t tau, int32_t kmeans_iters, int32_t *d_row_ptr, int32_t *d_col, float *d_val,
                         int64_t cap_nnz, int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged,
-                        void *d_workspace, size_t workspace_bytes, void *stream);
+                        int32_t *tau_used, void *d_workspace, size_t workspace_bytes, void *stream);
 
 /* Hands a CSR matrix P (n rows, int32 indices, float values, all on the device) to the context.
  * Borrowed: it must outlive every later call on the context (with renumbering on, the library works

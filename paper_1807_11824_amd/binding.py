@@ -59,7 +59,7 @@ def lib():
         "tsne_ivf_knn": (C.c_int, [vp, i32, i32, vp, i32, i32, i32, vp, vp, vp, C.c_size_t, vp]),
         "tsne_build_P_approx_workspace_bytes": (C.c_int, [i32, i32, i32, i32, i32, C.POINTER(C.c_size_t)]),
         "tsne_build_P_approx": (C.c_int, [vp, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, i64, C.POINTER(i64), vp, vp,
-                                          C.POINTER(i32), vp, C.c_size_t, vp]),
+                                          C.POINTER(i32), C.POINTER(i32), vp, C.c_size_t, vp]),
         "tsne_set_P": (C.c_int, [vp, vp, vp, vp, i64]),
         "tsne_init_state": (C.c_int, [vp]),
         "tsne_get_state": (C.c_int, [vp, vp, vp]),
@@ -201,14 +201,15 @@ def build_P_approx(X, perplexity, k, tau, nlist=0, kmeans_iters=10, stream=None,
     knn_d2 = torch.empty((n, k), dtype=torch.float32, device=X.device) if want_knn else None
     nnz = C.c_int64(0)
     bad = C.c_int32(0)
+    used = C.c_int32(0)
     rc = L.tsne_build_P_approx(_ptr(X), n, d, perplexity, k, nlist, tau, kmeans_iters, _ptr(row_ptr), _ptr(col),
-                               _ptr(val), cap, C.byref(nnz), _ptr(knn_idx), _ptr(knn_d2), C.byref(bad), _ptr(work),
-                               b.value, _stream_ptr(stream))
+                               _ptr(val), cap, C.byref(nnz), _ptr(knn_idx), _ptr(knn_d2), C.byref(bad), C.byref(used),
+                               _ptr(work), b.value, _stream_ptr(stream))
     if rc:
         raise TsneError(rc, "tsne_build_P_approx", L.tsne_strerror(rc).decode())
     m = nnz.value
     return dict(row_ptr=row_ptr, col=col[:m], val=val[:m], nnz=m, unconverged=bad.value,
-                knn_idx=knn_idx, knn_d2=knn_d2)
+                knn_idx=knn_idx, knn_d2=knn_d2, tau_used=used.value)
 
 
 class Tsne:

@@ -1203,16 +1203,18 @@ int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t
 {
     if (!bytes || check_args(n, d, k) != TSNE_OK) return TSNE_EINVAL;
     nlist = approx_lists(n, nlist);
-    size_t ivf = 0;
+    size_t ivf = 0, ivf_max = 0;
     if (tsne_ivf_workspace_bytes(n, d, k, nlist, tau, &ivf) != TSNE_OK) return TSNE_EINVAL;
-    *bytes = carve(nullptr, n, d, k, nullptr) + up(4 * (size_t)nlist * d) + ivf;
+    // (room for the search to be repeated with more lists, see tsne_build_P_approx)
+    if (tsne_ivf_workspace_bytes(n, d, k, nlist, nlist < 32 ? nlist : 32, &ivf_max) != TSNE_OK) return TSNE_EINVAL;
+    *bytes = carve(nullptr, n, d, k, nullptr) + up(4 * (size_t)nlist * d) + (ivf_max > ivf ? ivf_max : ivf);
     return TSNE_OK;
 }
 
 int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k, int32_t nlist, int32_t tau,
                         int32_t kmeans_iters, int32_t *d_row_ptr, int32_t *d_col, float *d_val, int64_t cap_nnz,
-                        int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged, void *d_workspace,
-                        size_t workspace_bytes, void *stream)
+                        int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged, int32_t *tau_used,
+                        void *d_workspace, size_t workspace_bytes, void *stream)
 {
     if (!d_X || !d_row_ptr || !d_col || !d_val || !nnz || !d_workspace || kmeans_iters < 0) return TSNE_EINVAL;
     if (check_args(n, d, k) != TSNE_OK) return TSNE_EINVAL;
@@ -1233,8 +1235,15 @@ int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity
     HIPCHK(hipMemsetAsync(L.extra, 0, 4 * (size_t)n, s));
     int rc = ivf_train_device(d_X, n, d, nlist, kmeans_iters, centroids, ivf_ws, ivf_bytes, s);
     if (rc != TSNE_OK) return rc;
-    rc = ivf_knn_device(d_X, n, d, centroids, nlist, tau, k, L.knn_idx, L.knn_d2, ivf_ws, ivf_bytes, s);
+    // a row that finds fewer than k other points in its tau lists: twice the lists for everybody, and again
+    const int tau_max = nlist < 32 ? nlist : 32;
+    for (;;) {
+        rc = ivf_knn_device(d_X, n, d, centroids, nlist, tau, k, L.knn_idx, L.knn_d2, ivf_ws, ivf_bytes, s);
+        if (rc != TSNE_ENUM || tau >= tau_max) break;
+        tau = 2 * tau < tau_max ? 2 * tau : tau_max;
+    }
     if (rc != TSNE_OK) return rc;
+    if (tau_used) *tau_used = tau;
     return finish_P(L, n, k, perplexity, d_row_ptr, d_col, d_val, cap_nnz, nnz, d_knn_idx, d_knn_d2, n_unconverged, s);
 }
 

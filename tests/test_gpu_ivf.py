@@ -123,3 +123,18 @@ def test_P_from_approximate_neighbours():
     exact_idx, _ = oracle.knn(X, k)
     print(f"recall at k = {k}: {ivf.recall(got_idx, exact_idx):.4f} (oracle's own lists: {ivf.recall(idx, exact_idx):.4f})",
           flush=True)
+
+
+def test_P_build_takes_more_lists_when_a_row_runs_short():
+    """200 points in 50 lists of about four, k = 30: one list never holds 30 other points, nor do two, four, ... ;
+    tsne_build_P_approx doubles tau until every row has its k candidates and says how far it went."""
+    from paper_1807_11824_amd import build_P_approx
+    X = np.random.default_rng(1).standard_normal((200, 5)).astype(np.float32)
+    P = build_P_approx(_dev(X), 10.0, 30, 1, nlist=50, kmeans_iters=3, want_knn=True)
+    tau = P["tau_used"]
+    assert tau in (16, 32)
+    C, _ = ivf.kmeans_train(X, 50, 3)
+    idx, d2 = ivf.ivf_knn(X, C, tau, 30)
+    assert np.array_equal(P["knn_idx"].cpu().numpy(), idx)
+    with pytest.raises(ValueError):
+        ivf.ivf_knn(X, C, tau // 2, 30)
