@@ -171,7 +171,8 @@ def main():
         t_approx = time.time() - t0
         rows = torch.randperm(n, device=dev, generator=torch.Generator(device=dev).manual_seed(0))[:20000]
         hit = (Pa["knn_idx"][rows].long()[:, :, None] == P["knn_idx"][rows].long()[:, None, :]).any(-1)
-        approx = {"tau": args.approx_tau, "nlist": int(round(n ** 0.5)), "kmeans_iters": 10, "build_P_approx_s": t_approx,
+        approx = {"tau": args.approx_tau, "tau_used": Pa["tau_used"], "nlist": int(round(n ** 0.5)), "kmeans_iters": 10,
+                  "build_P_approx_s": t_approx,
                   "recall_at_k": float(hit.float().mean().item()), "rows_sampled": int(rows.numel()), "nnz": Pa["nnz"]}
         del Pa, hit
     P["knn_idx"] = P["knn_d2"] = None
