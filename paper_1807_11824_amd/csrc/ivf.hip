@@ -447,15 +447,15 @@ __global__ __launch_bounds__(IVF_QW * 64) void ivf_score(const float *__restrict
 __device__ __forceinline__ uint32_t key_bits(float f) { return __float_as_uint(f); }   // non-negative: ordered like the float
 __device__ __forceinline__ bool pair_less(double da, int ia, double db, int ib) { return da < db || (da == db && ia < ib); }
 
-// |x_q - y|^2 for row q of X and row lp of the list-ordered copy, summed like accumulate() does
-__device__ __forceinline__ double exact_d2(const float *__restrict__ X, int d, int dp, const double *__restrict__ Xl, int q,
-                                           int lp)
+// |x_q - x_j|^2 for rows q and j of X, summed like accumulate() does (which reads row j from the double
+// copy: the same values, twice the bytes)
+__device__ __forceinline__ double exact_d2(const float *__restrict__ X, int d, int q, int j)
 {
     const float *x = X + (size_t)q * d;
-    const double *y = Xl + (size_t)lp * dp;
+    const float *y = X + (size_t)j * d;
     double acc = 0.0;
     for (int t = 0; t < d; ++t) {
-        const double df = (double)x[t] - y[t];
+        const double df = (double)x[t] - (double)y[t];
         acc = fma(df, df, acc);
     }
     return acc;
@@ -519,8 +519,7 @@ __device__ __forceinline__ uint32_t radix_kth(KeyFn key, int count, int rank, Se
 __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, const long long *__restrict__ mprefix,
                                                   long long base0, int qb, int tau, int k,
                                                   const int32_t *__restrict__ probe, const int *__restrict__ cellptr,
-                                                  const int *__restrict__ lorder, const float *__restrict__ X, int d, int dp,
-                                                  const double *__restrict__ Xl, int buf,
+                                                  const int *__restrict__ lorder, const float *__restrict__ X, int d, int buf,
                                                   int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2)
 {
     extern __shared__ __align__(16) unsigned char sel_dyn[];
@@ -608,9 +607,9 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
     __syncthreads();
     for (int a = tid; a < less + (small ? equal : 0); a += 256) {
         const int slot = a < less ? a : k + (a - less);
-        const int lp = list_pos(wi[slot]);
-        wd[slot] = exact_d2(X, d, dp, Xl, q, lp);
-        wi[slot] = lorder[lp];
+        const int id = lorder[list_pos(wi[slot])];
+        wd[slot] = exact_d2(X, d, q, id);
+        wi[slot] = id;
     }
     __syncthreads();
     if (small) {
@@ -633,7 +632,7 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
             for (int pos = tid; pos < M; pos += 256) {
                 if (key_bits(src[pos]) != Tf) continue;
                 const unsigned long long db =
-                    (unsigned long long)__double_as_longlong(exact_d2(X, d, dp, Xl, q, list_pos(pos)));
+                    (unsigned long long)__double_as_longlong(exact_d2(X, d, q, lorder[list_pos(pos)]));
                 if ((db & m64) == p64) atomicAdd(&sh.hist[(unsigned)(db >> shift) & 255u], 1u);
             }
             __syncthreads();
@@ -653,9 +652,8 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
                 __syncthreads();
                 for (int pos = tid; pos < M; pos += 256) {
                     if (key_bits(src[pos]) != Tf) continue;
-                    const int lp = list_pos(pos);
-                    if ((unsigned long long)__double_as_longlong(exact_d2(X, d, dp, Xl, q, lp)) != p64) continue;
-                    const uint32_t id = (uint32_t)lorder[lp];
+                    const uint32_t id = (uint32_t)lorder[list_pos(pos)];
+                    if ((unsigned long long)__double_as_longlong(exact_d2(X, d, q, (int)id)) != p64) continue;
                     if ((id & mid) == pid) atomicAdd(&sh.hist[(id >> shift) & 255u], 1u);
                 }
                 __syncthreads();
@@ -669,11 +667,10 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
         }
         for (int pos = tid; pos < M; pos += 256) {
             if (key_bits(src[pos]) != Tf) continue;
-            const int lp = list_pos(pos);
-            const double v = exact_d2(X, d, dp, Xl, q, lp);
+            const int id = lorder[list_pos(pos)];
+            const double v = exact_d2(X, d, q, id);
             const unsigned long long db = (unsigned long long)__double_as_longlong(v);
             if (db > p64) continue;
-            const int id = lorder[lp];
             if (db == p64 && (uint32_t)id > Tid) continue;
             const int slot = atomicAdd(&wcount, 1);
             wd[slot] = v;
@@ -903,7 +900,7 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
             hipLaunchKernelGGL(ivf_score<false>, dim3(tiles), dim3(IVF_QW * WAVE), 0, s, X, d, dp, L.Xl, L.lorder,
                                L.cellptr, L.probe, tau, nlist, L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
         hipLaunchKernelGGL(ivf_select, dim3(rows), dim3(256), sel_bytes, s, L.D, L.mprefix, mp[qb], qb, tau, k, L.probe,
-                           L.cellptr, L.lorder, X, d, dp, L.Xl, buf, knn_idx, knn_d2);
+                           L.cellptr, L.lorder, X, d, buf, knn_idx, knn_d2);
         qb = qe;
     }
     free(mp);
