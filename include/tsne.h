@@ -171,8 +171,9 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
  * tsne_ivf_train: k-means (Lloyd) for the centroids, as the paper trains them.  Start: of the sample of
  *   m = min(n, 8 nlist) rows floor(j n / m) the first, then nlist - 1 times the sample row farthest from
  *   those taken so far (lowest j among equals), which puts a centroid into every well separated cluster
- *   before any gets a second one.  Then `iters` rounds of (assign every row to its nearest centroid, move
- *   every centroid to the mean of its rows; a centroid without rows stays).  d_centroids: nlist x d floats
+ *   before any gets a second one.  Then `iters` rounds, on the min(n, 256 nlist) rows floor(i n / m), of
+ *   (assign every row to its nearest centroid, move every centroid to the mean of its rows; a centroid
+ *   without rows stays).  d_centroids: nlist x d floats
  *   (device, caller-owned, written).  X must be finite with |x| < 1e38.
  * tsne_ivf_knn: neighbour lists of every row of X (self excluded, ordered by (distance, index)) from
  *   given centroids.  d_knn_idx: n x k int32, d_knn_d2: n x k doubles (device, caller-owned).

@@ -51,11 +51,15 @@ def assign(X, C):
 
 
 def kmeans_train(X, nlist, iters):
-    """Lloyd's algorithm from kmeans_init (which see): assign every point to its nearest centroid, move every
-    centroid to the mean of its points (a centroid without points stays where it is).  Centroids are
-    kept as float between the iterations.  Returns (centroids float32, inertia before each update)."""
+    """Lloyd's algorithm from kmeans_init (which see) on the sample of min(n, 256 nlist) rows floor(i n / m):
+    assign every sample point to its nearest centroid, move every centroid to the mean of its points (a
+    centroid without points stays where it is).  Centroids are kept as float between the iterations.
+    Returns (centroids float32, inertia of the sample before each update)."""
     X = np.asarray(X, np.float32)
     C = kmeans_init(X, nlist)
+    n = X.shape[0]
+    m = min(n, 256 * nlist)
+    X = X[(np.arange(m, dtype=np.int64) * n) // m]
     Xd = X.astype(np.float64)
     inertia = []
     for _ in range(iters):

@@ -195,15 +195,18 @@ __device__ __forceinline__ void accumulate(double (&acc)[IVF_CB], float (&xr)[IV
 template <bool LONG>
 __global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int n, int d, int dp,
                                                 const double *__restrict__ Cd, int nlist, int tau,
-                                                int32_t *__restrict__ probe)
+                                                int32_t *__restrict__ probe, int m)
 {
     extern __shared__ __align__(16) unsigned char probe_dyn[];
     double *pd = reinterpret_cast<double *>(probe_dyn);
     int *pi = reinterpret_cast<int *>(probe_dyn + 8 * (size_t)WAVE * tau);
     float *xs = reinterpret_cast<float *>(probe_dyn + 12 * (size_t)WAVE * tau);   // present when d > IVF_DC
     const int lane = lane_id();
+    // entry i of the output belongs to row floor(i n / m) of X: the m evenly spaced rows k-means works on,
+    // or every row (m = n)
     const int i0 = blockIdx.x * WAVE;
-    const int i = min(i0 + lane, n - 1);
+    const int slot = min(i0 + lane, m - 1);
+    const int i = (int)(((long long)slot * n) / m);
     float xr[IVF_DC];
     if (!LONG) load_chunk(xr, X, d, i, 0, d);
     int have = 0;
@@ -244,21 +247,22 @@ __global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int
             }
         }
     }
-    if (i0 + lane < n)
-        for (int r = 0; r < tau; ++r) probe[(size_t)i * tau + r] = pi[r * WAVE + lane];
+    if (i0 + lane < m)
+        for (int r = 0; r < tau; ++r) probe[(size_t)slot * tau + r] = pi[r * WAVE + lane];
 }
 
 // ------------------------------------------------------------------ Lloyd update
 // Sums in fixed point (value * scale as a 64-bit integer): integer addition is associative, so the
 // mean does not depend on the order in which the atomics land.
 __global__ void kmeans_accum(const float *__restrict__ X, int n, int d, const int32_t *__restrict__ probe, int tau,
-                             double scale, unsigned long long *__restrict__ sums, int *__restrict__ counts)
+                             double scale, unsigned long long *__restrict__ sums, int *__restrict__ counts, int m)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)n * d) return;
+    if (idx >= (size_t)m * d) return;
     const int i = (int)(idx / d), t = (int)(idx % d);
     const int c = probe[(size_t)i * tau];
-    atomicAdd(&sums[(size_t)c * d + t], (unsigned long long)llrint((double)X[idx] * scale));
+    const size_t row = (size_t)(((long long)i * n) / m);       // the sample's i-th row
+    atomicAdd(&sums[(size_t)c * d + t], (unsigned long long)llrint((double)X[row * d + t] * scale));
     if (t == 0) atomicAdd(&counts[c], 1);
 }
 
@@ -692,15 +696,16 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
 // LDS for the chunk buffers of the distance kernels: none while a row fits one chunk
 size_t chunk_lds(int d, int waves) { return d > IVF_DC ? 4 * (size_t)IVF_DC * WAVE * waves : 0; }
 
-void launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nlist, int tau, int32_t *probe, hipStream_t s)
+void launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nlist, int tau, int32_t *probe, int m,
+                  hipStream_t s)
 {
     const size_t lists = 12 * (size_t)WAVE * tau;
     if (d > IVF_DC)
-        hipLaunchKernelGGL(ivf_probe<true>, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), lists + chunk_lds(d, 1), s, X, n, d, dp, Cd,
-                           nlist, tau, probe);
+        hipLaunchKernelGGL(ivf_probe<true>, dim3((m + WAVE - 1) / WAVE), dim3(WAVE), lists + chunk_lds(d, 1), s, X, n, d, dp, Cd,
+                           nlist, tau, probe, m);
     else
-        hipLaunchKernelGGL(ivf_probe<false>, dim3((n + WAVE - 1) / WAVE), dim3(WAVE), lists, s, X, n, d, dp, Cd, nlist, tau,
-                           probe);
+        hipLaunchKernelGGL(ivf_probe<false>, dim3((m + WAVE - 1) / WAVE), dim3(WAVE), lists, s, X, n, d, dp, Cd, nlist, tau,
+                           probe, m);
 }
 
 int select_buf(int k)
@@ -792,7 +797,8 @@ size_t ivf_workspace(int n, int d, int k, int nlist, int tau)
     return ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0);
 }
 
-// Lloyd's algorithm: `iters` rounds of (nearest centroid, mean of the members) from a spread-out start.
+// Lloyd's algorithm: `iters` rounds of (nearest centroid, mean of the members) from a spread-out start, on a sample
+// of 256 rows per centroid.
 int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *C, void *ws, size_t ws_bytes, hipStream_t s)
 {
     IvfLayout L;
@@ -822,12 +828,15 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     if (xmax > 0.f) frexpf(xmax, &e);
     while ((1ll << ln) < (long long)n) ++ln;
     const double scale = ldexp(1.0, 62 - ln - e), inv_scale = ldexp(1.0, -(62 - ln - e));
+    // the rounds work on min(n, 256 nlist) evenly spaced rows
+    const int ms = (long long)n < 256ll * nlist ? n : 256 * nlist;
     for (int it = 0; it < iters; ++it) {
         hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
-        launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, s);
+        launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, ms, s);
         hipLaunchKernelGGL(fill_u64_k, dim3(blocks(cd)), dim3(256), 0, s, L.sums, cd);
         hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist);
-        hipLaunchKernelGGL(kmeans_accum, dim3(blocks(nd)), dim3(256), 0, s, X, n, d, L.probe, 1, scale, L.sums, L.cnt);
+        hipLaunchKernelGGL(kmeans_accum, dim3(blocks((size_t)ms * d)), dim3(256), 0, s, X, n, d, L.probe, 1, scale, L.sums, L.cnt,
+                           ms);
         hipLaunchKernelGGL(kmeans_finish, dim3(blocks(cd)), dim3(256), 0, s, L.sums, L.cnt, nlist, d, inv_scale, C);
     }
     IVFCHK(hipGetLastError());
@@ -843,7 +852,7 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
     ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes);
     const int dp = (d + 3) / 4 * 4;
     hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
-    launch_probe(X, n, d, dp, L.Cd, nlist, tau, L.probe, s);
+    launch_probe(X, n, d, dp, L.Cd, nlist, tau, L.probe, n, s);
     hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cursor, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(cell_hist, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cnt);

@@ -87,7 +87,8 @@ def test_too_few_candidates_is_reported():
     assert e.value.code == -5
 
 
-@pytest.mark.parametrize("n,d,nlist,iters", [(4000, 20, 30, 5), (1500, 70, 12, 3), (300, 3, 300, 2)])
+# (the last: 8 centroids, so the rounds run on a sample of 2048 of the 6000 rows)
+@pytest.mark.parametrize("n,d,nlist,iters", [(4000, 20, 30, 5), (1500, 70, 12, 3), (300, 3, 300, 2), (6000, 10, 8, 4)])
 def test_kmeans_matches_oracle(n, d, nlist, iters):
     """Same start, same rule; the means are exact sums here and double sums there, both rounded to float."""
     from paper_1807_11824_amd import ivf_train

@@ -99,6 +99,17 @@ def test_kmeans_inertia_never_rises_and_empty_cells_stay():
     assert C.tolist() == [[0.0] * 3, [1.0] * 3, [0.0] * 3, [0.0] * 3]
 
 
+def test_kmeans_rounds_see_only_the_sample():
+    """One centroid, 1000 rows: the rounds use the 256 rows floor(i 1000 / 256); the other rows can hold anything."""
+    r = np.random.default_rng(8)
+    X = r.standard_normal((1000, 4)).astype(np.float32)
+    rows = (np.arange(256) * 1000) // 256
+    other = np.setdiff1d(np.arange(1000), rows)
+    X[other] = 1e6
+    C, _ = ivf.kmeans_train(X, 1, 2)
+    assert np.allclose(C[0], X[rows].astype(np.float64).mean(axis=0), rtol=0, atol=1e-6)
+
+
 def test_more_lists_never_hurt():
     """The candidate sets are nested in tau, so the distance to the k-th neighbour cannot grow and the recall
     cannot fall; at tau = |C| the recall is 1."""
