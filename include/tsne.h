@@ -63,51 +63,31 @@ typedef struct {
     float gain_min;               /* 0.01 */
     int32_t morton_bits;          /* grid bits per axis = maximum tree depth, 1..16 (16) */
     int32_t leaf_cap;             /* a cell with at most this many points is a leaf, >= 1 (8) */
-    int32_t overlap;              /* the attractive forces run on a second stream: 2 = beside the tree walk
-                                     (arithmetic-bound walk and memory-bound attraction share the compute
-                                     units), 1 = from the start of the tree build, 3 = from the end of the sort;
-                                     0 = everything on one stream.  (2) */
+    int32_t overlap;              /* 1: the attractive forces run on a second stream, the entries far from the
+                                     diagonal beside the tree build and the streaming part beside the tree walk;
+                                     0: everything on one stream.  (1) */
     int32_t graph_order_iters;    /* > 0 (and max_nnz > 0): at tsne_set_P the library renumbers its private
                                      copy of the points and of P so that points that are neighbours in P get
                                      nearby numbers: a seeded pseudo-random value per point is averaged over
                                      the P-neighbourhood this many times and the points are sorted by it.
                                      The sparsity pattern becomes banded, so the y_j gathers of Eq. (5) stay
-                                     cache-resident.  Nothing the method computes changes except float
-                                     rounding and the order of points with equal grid keys.  (64) */
+                                     on chip.  Nothing the method computes changes except float rounding and
+                                     the order of points with equal grid keys.  (64) */
     int32_t reorder_every;        /* > 0 (and max_nnz > 0): additionally renumber along the current spatial
-                                     order of the embedding every this many steps; pays off once neighbours
-                                     in P are neighbours in the plane.  (0 = never) */
-    int32_t attract_resident;     /* resident workgroups (512 lanes) of the attraction kernel per compute unit
-                                     when the points are renumbered; each works through a contiguous share of
-                                     the rows.  A small number keeps HBM busy and leaves the rest of every
-                                     compute unit to the tree walk.  0 = library's choice.  (1) */
+                                     order of the embedding every this many steps.  (0 = never) */
+    int32_t attract_resident;     /* resident workgroups (512 lanes) of the streaming attraction kernel per
+                                     compute unit; each works through a contiguous share of the rows.
+                                     0 = library's choice.  (1) */
     int32_t walk_resident;        /* > 0: the tree walk runs as this many resident waves per compute unit that
-                                     take groups of points from a counter, instead of one wave per group, so
-                                     that walk and attraction hold fixed shares of every compute unit; used
-                                     when there are more groups than resident waves.  0 = one wave per group.
-                                     (14) */
-    int32_t attract_early;        /* percent (0..90) of the attraction's streaming work that is started beside
-                                     the tree build by a quarter as many workgroups as there are compute
-                                     units; the rest runs beside the walk.  Only with overlap = 2.  The tree
-                                     kernels are latency-bound and slow down under any extra memory traffic
-                                     (measured: 0.24 -> 0.33 ms at 20 percent), so only the small far part
-                                     runs there by default.  (0) */
+                                     take groups of points from a counter, so that walk and attraction hold
+                                     fixed shares of every compute unit; used when there are more groups than
+                                     resident waves.  0 = one wave per group.  (14) */
     int32_t far_tiles;            /* how the entries of the renumbered P that lie far from the diagonal are
-                                     summed.  1: one row at a time, each entry fetching its neighbour's
-                                     position from memory.  2: from a copy bucketed by 4096-row x 2048-column
-                                     tiles, so that the positions fetched together share cache lines, with
-                                     the row sums kept in fixed point in LDS (integer-valued doubles: every
-                                     addition is exact, so the result does not depend on the order of the
-                                     entries).
-                                     0: chosen at tsne_set_P: tiles if the far part holds at least half of
-                                     the entries and n >= 2^18, rows otherwise; the choice is kept through
-                                     later renumberings (reorder_every).  (0) */
-    int32_t graphs;               /* 1: inside tsne_run the iterations that neither start nor end the call (nor
-                                     carry timing events, nor precede a renumbering) are replayed from a HIP
-                                     graph captured once per (exaggeration, momentum) phase instead of being
-                                     launched kernel by kernel.  Same kernels, same results; measured slower
-                                     than plain stream launches on every size tried (0.72 -> 0.77 ms per
-                                     iteration at 1.28M points, 0.157 -> 0.181 ms at 2000), hence off.  (0) */
+                                     summed.  1: one row at a time.  2: from a copy bucketed by 4096-row x
+                                     2048-column tiles, row sums kept in fixed point (every addition exact, so
+                                     the result does not depend on the order of the entries).  0: chosen at
+                                     tsne_set_P: tiles if the far part holds at least half of the entries and
+                                     n >= 2^18, rows otherwise; kept through later renumberings.  (0) */
     int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
                                      20 bytes per entry plus 202 bytes per point (rows are padded) plus 8 bytes
                                      per pair of a 4096-row and a 2048-column tile (n^2 / 2^20).  0 disables

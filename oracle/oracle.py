@@ -158,7 +158,7 @@ def tree(Y, bits=16, leaf_cap=8):
     root, keys = morton(Y, bits)
     sk, perm = sort_keys(keys)
     Ys = np.ascontiguousarray(Y[perm])
-    cap = min(n * (bits + 1) + 1, 4 * n + 4096)
+    cap = n * (bits + 1) + 1        # every level holds at most n cells
     depth = np.empty(cap, np.int32); lo = np.empty(cap, np.int32); hi = np.empty(cap, np.int32)
     leaf = np.empty(cap, np.int32); child = np.empty((cap, 4), np.int32)
     prefix = np.empty(cap, np.uint32); com = np.empty((cap, 2), np.float32)

@@ -487,10 +487,11 @@ int32_t oracle_repulse_bh(const float *Y, int32_t n, float theta, int32_t leaf_c
                           int32_t bits, double *R, double *z, double *Zout, int64_t *stats)
 {
     if (!Y || n < 1 || group < 1 || !(theta >= 0.0f)) return -1;
-    /* a chain of single-child cells can sit above every leaf, so the cell count
-     * is bounded by n (bits + 1); real inputs stay far below 4n */
-    int64_t cap64 = (int64_t)n * (bits + 1) + 1;
-    if (cap64 > (int64_t)4 * n + 4096) cap64 = (int64_t)4 * n + 4096;
+    /* leaves are disjoint and non-empty (at most n of them); an inner cell holds more than
+     * leaf_cap points, so every level above the deepest has at most n / (leaf_cap + 1) */
+    if (leaf_cap < 1 || bits < 1) return -1;
+    int64_t cap64 = (int64_t)n + (int64_t)bits * (n / ((int64_t)leaf_cap + 1)) + 1;
+    if (cap64 > 0x7FFFFFFF) return -1;
     int32_t cap = (int32_t)cap64;
     uint32_t *keys = malloc((size_t)n * 4), *skeys = malloc((size_t)n * 4);
     int32_t *perm = malloc((size_t)n * 4);

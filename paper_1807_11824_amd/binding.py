@@ -28,8 +28,8 @@ class TsneParams(C.Structure):
                 ("momentum_switch_iter", C.c_int32), ("gain_inc", C.c_float), ("gain_dec", C.c_float),
                 ("gain_min", C.c_float), ("morton_bits", C.c_int32), ("leaf_cap", C.c_int32),
                 ("overlap", C.c_int32), ("graph_order_iters", C.c_int32), ("reorder_every", C.c_int32),
-                ("attract_resident", C.c_int32), ("walk_resident", C.c_int32), ("attract_early", C.c_int32),
-                ("far_tiles", C.c_int32), ("graphs", C.c_int32), ("max_nnz", C.c_int64)]
+                ("attract_resident", C.c_int32), ("walk_resident", C.c_int32),
+                ("far_tiles", C.c_int32), ("max_nnz", C.c_int64)]
 
 
 _lib = None
@@ -288,7 +288,7 @@ class Tsne:
 
     def export_tree(self, cap_cells=None):
         n = self.n
-        cap = cap_cells if cap_cells is not None else 4 * n + 4096
+        cap = cap_cells if cap_cells is not None else n + self.params.morton_bits * (n // (self.params.leaf_cap + 1)) + 1
         dev = self.device
         keys = torch.empty(n, dtype=torch.int32, device=dev)
         perm = torch.empty(n, dtype=torch.int32, device=dev)

@@ -18,14 +18,12 @@ constexpr int KL_PART_DOUBLES = 3 * 1024;
 
 size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
-int32_t cell_capacity(int32_t n, int32_t bits)
+// Most cells a tree over n points can have: its leaves are disjoint and non-empty (at most n), and an
+// inner cell holds more than leaf_cap points, so each of the `bits` levels above the deepest has at
+// most n / (leaf_cap + 1) of them.
+int64_t cell_capacity(int64_t n, int bits, int64_t leaf_cap)
 {
-    // Every cell but the root has a parent with more than leaf_cap >= 1 points, and each level
-    // holds at most n cells, so n (bits + 1) + 1 always suffices; ordinary embeddings need well
-    // under n cells, and 4n + 4096 covers chains of one-child cells over clumps of duplicates.
-    int64_t worst = (int64_t)n * (bits + 1) + 1;
-    int64_t want = (int64_t)4 * n + 4096;
-    return (int32_t)(worst < want ? worst : want);
+    return n + (int64_t)bits * (n / (leaf_cap + 1)) + 1;
 }
 
 // Walks the workspace layout; with base == nullptr it only measures.
@@ -38,7 +36,7 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
         off += up(bytes);
         return (void *)ptr;
     };
-    const int32_t cap = cell_capacity(p->n, p->morton_bits);
+    const int32_t cap = (int32_t)cell_capacity(p->n, p->morton_bits, p->leaf_cap);   // < 2^31: check_params
     const size_t nblk_sort = (n + SORT_TILE - 1) / SORT_TILE;
     const size_t nblk_lev = (n + LEVEL_TILE - 1) / LEVEL_TILE;
     const size_t ngroups = (n + WAVE - 1) / WAVE;
@@ -117,12 +115,12 @@ int check_params(const tsne_params *p)
     if (!(p->theta >= 0.0f) || p->theta > 0.7f) return TSNE_EINVAL;
     if (p->morton_bits < 1 || p->morton_bits > 16) return TSNE_EINVAL;
     if (p->leaf_cap < 1) return TSNE_EINVAL;
+    if (p->overlap < 0 || p->overlap > 1) return TSNE_EINVAL;
+    if (cell_capacity(p->n, p->morton_bits, p->leaf_cap) > 0x7FFFFFFFll) return TSNE_EINVAL;   // cells are numbered in 32 bits
     if (p->reorder_every < 0 || p->graph_order_iters < 0 || p->graph_order_iters > 1000) return TSNE_EINVAL;
     if (p->attract_resident < 0 || p->attract_resident > 64) return TSNE_EINVAL;
     if (p->walk_resident < 0 || p->walk_resident > 32) return TSNE_EINVAL;
-    if (p->attract_early < 0 || p->attract_early > 90) return TSNE_EINVAL;
     if (p->far_tiles < 0 || p->far_tiles > 2) return TSNE_EINVAL;
-    if (p->graphs < 0 || p->graphs > 1) return TSNE_EINVAL;
     if (p->max_nnz < 0 || p->max_nnz > 0x7FFFFFFFll) return TSNE_EINVAL;
     // the renumbered copy pads every row to whole chunks and is indexed with int32
     if (p->max_nnz > 0 && p->max_nnz + (ATTRACT_CHUNK - 1ll) * p->n + ATTRACT_SLACK > 0x7FFFFFFFll) return TSNE_EINVAL;
@@ -144,29 +142,27 @@ int fail(tsne_ctx *c, int code, const char *msg)
     return code;
 }
 
-// Events of one timed step: 0 start, 1 tree built, 2 walk done, 3 / 4 main part of the attraction,
-// 5 update done, 6 / 7 early part of the attraction, 8 update started.
+// Events of one timed step: 0 start, 1 tree built, 2 walk done, 3 / 4 streaming part of the attraction,
+// 5 update done, 6 / 7 far part of the attraction, 8 update started.
 constexpr int NEV = 9;
 
 // Forces at d_Y into c->A, c->R, c->Z.  The attraction only needs Y and P, so with overlap it runs
-// on the second stream: overlap 1 from the gather on, 3 from the end of the sort, 2 (default) in
-// two pieces -- a small early piece beside the tree build (the tree kernels are short and
-// latency-bound, a few streaming workgroups do not slow them much) and the main piece beside the
-// walk, whose arithmetic and the attraction's memory traffic use different parts of the chip.
+// on the second stream: the small far part beside the tree build (the tree kernels are short and
+// latency-bound; a few gathering workgroups do not slow them much) and the streaming part beside
+// the walk, whose arithmetic and the attraction's memory traffic use different parts of the chip.
 int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev, bool cached = false)
 {
     hipError_t e;
     const bool two = c->p.overlap && c->stream2;
-    const int mode = c->p.overlap;
     hipStream_t sa = two ? c->stream2 : c->stream;   // where the attraction runs
     auto fork = [&](hipEvent_t evt) -> int {
         if ((e = hipEventRecord(evt, c->stream)) != hipSuccess) return fail_hip(c, e, "event record");
         if ((e = hipStreamWaitEvent(c->stream2, evt, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
         return TSNE_OK;
     };
-    auto early = [&]() -> int {
+    auto farpart = [&]() -> int {
         if (ev) (void)hipEventRecord(ev[6], sa);
-        if ((e = launch_attract_early(c, sa)) != hipSuccess) return fail_hip(c, e, "attract (early part)");
+        if ((e = launch_attract_far(c, sa)) != hipSuccess) return fail_hip(c, e, "attract (far part)");
         if (ev) (void)hipEventRecord(ev[7], sa);
         return TSNE_OK;
     };
@@ -181,26 +177,17 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev, bool cached = 
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     // (inside tsne_run the previous update has already left Y in slot order and its bounding box)
     if (!cached && (e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
-    if (two && (mode == 1 || mode == 2)) {
-        if ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = early()) != TSNE_OK) return rc;
-        if (mode == 1 && (rc = mainpart()) != TSNE_OK) return rc;
-    }
+    if (two && ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = farpart()) != TSNE_OK)) return rc;
     if ((e = launch_tree_sort(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree sort");
-    if (two && mode == 3 && ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = early()) != TSNE_OK || (rc = mainpart()) != TSNE_OK))
-        return rc;
     if ((e = launch_tree_cells(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree cells");
     if (ev) (void)hipEventRecord(ev[1], c->stream);
-    if (two && mode != 1 && mode != 3) {
-        if (mode != 2 && ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = early()) != TSNE_OK)) return rc;
-        if (mode == 2 && (rc = fork(c->ev_fork2)) != TSNE_OK) return rc;
-        if ((rc = mainpart()) != TSNE_OK) return rc;
-    }
+    if (two && ((rc = fork(c->ev_fork2)) != TSNE_OK || (rc = mainpart()) != TSNE_OK)) return rc;
     if ((e = launch_walk(c, c->stream)) != hipSuccess) return fail_hip(c, e, "walk");
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     if (two) {
         if ((e = hipStreamWaitEvent(c->stream, c->ev_join, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
     } else {
-        if ((rc = early()) != TSNE_OK || (rc = mainpart()) != TSNE_OK) return rc;
+        if ((rc = farpart()) != TSNE_OK || (rc = mainpart()) != TSNE_OK) return rc;
     }
     // Without renumbering, the attractive kernel of the NEXT call visits rows in this call's
     // spatial order (the kernel has finished by now on either stream, so the array is free to
@@ -261,14 +248,12 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->gain_min = 0.01f;
     p->morton_bits = 16;
     p->leaf_cap = 8;
-    p->overlap = 2;
+    p->overlap = 1;
     p->graph_order_iters = 64;
     p->reorder_every = 0;
     p->attract_resident = 1;
     p->walk_resident = 14;
-    p->attract_early = 0;
     p->far_tiles = 0;
-    p->graphs = 0;
     p->max_nnz = 0;
     return TSNE_OK;
 }
@@ -341,18 +326,9 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
     return TSNE_OK;
 }
 
-// The captured iterations hold pointers and launch shapes: P, the slot order or Y changing makes them stale.
-static void drop_graphs(tsne_ctx *c)
-{
-    for (int k = 0; k < 4; ++k)
-        if (c->gexec[k]) { (void)hipGraphExecDestroy(c->gexec[k]); c->gexec[k] = nullptr; c->g_Y[k] = nullptr; }
-}
-
 void tsne_destroy(tsne_ctx *c)
 {
     if (!c) return;
-    drop_graphs(c);
-    if (c->gstream) (void)hipStreamDestroy(c->gstream);
     if (c->stream2) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_fork2) (void)hipEventDestroy(c->ev_fork2);
@@ -369,7 +345,6 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     if (c->reorder_on && nnz > c->p.max_nnz) return fail(c, TSNE_ENOSPC, "tsne_set_P: nnz exceeds max_nnz");
     int rc = reset_slot_order(c);
     if (rc != TSNE_OK) return rc;
-    drop_graphs(c);
     c->user_row_ptr = d_row_ptr; c->user_col = d_col; c->user_val = d_val;
     c->nnz = nnz;
     c->arow_valid = 0;
@@ -518,43 +493,6 @@ int tsne_run(tsne_ctx *c, float *d_Y, int32_t iter0, int32_t n_iter)
     // iteration the embedding in slot order and its bounding box.
     for (int32_t it = iter0; it < iter0 + n_iter; ++it) {
         const bool cached = it > iter0, keep = it + 1 < iter0 + n_iter;
-        const bool counted = c->tev && c->t_used < c->t_cap;                  // as in step_impl
-        const bool timed = counted && (c->t_seen % c->t_every) == 0;
-        if (c->p.graphs && cached && keep && c->yi_fresh && !timed && !(c->reorder_on && c->p.reorder_every > 0)) {
-            // a middle iteration: replayed from the graph of its phase (captured on first use)
-            const int cls = (it < c->p.exaggeration_iters ? 1 : 0) | (it < c->p.momentum_switch_iter ? 2 : 0);
-            if (c->gexec[cls] && c->g_Y[cls] != d_Y) { (void)hipGraphExecDestroy(c->gexec[cls]); c->gexec[cls] = nullptr; }
-            if (!c->gexec[cls]) {
-                hipGraph_t g = nullptr;
-                hipError_t e = hipSuccess;
-                if (!c->gstream) e = hipStreamCreateWithFlags(&c->gstream, hipStreamNonBlocking);
-                if (e == hipSuccess) e = hipStreamBeginCapture(c->gstream, hipStreamCaptureModeThreadLocal);
-                int rc = TSNE_OK;
-                if (e == hipSuccess) {
-                    hipEvent_t *saved = c->tev;
-                    hipStream_t caller = c->stream;
-                    c->tev = nullptr;                                         // no timing events in the graph
-                    c->stream = c->gstream;
-                    rc = step_impl(c, d_Y, it, true, true);
-                    c->stream = caller;
-                    c->tev = saved;
-                    e = hipStreamEndCapture(c->gstream, &g);
-                }
-                if (e == hipSuccess && rc == TSNE_OK) e = hipGraphInstantiate(&c->gexec[cls], g, nullptr, nullptr, 0);
-                if (g) (void)hipGraphDestroy(g);
-                if (e != hipSuccess || rc != TSNE_OK) {
-                    c->gexec[cls] = nullptr;
-                    c->yi_fresh = 0;
-                    return rc != TSNE_OK ? rc : fail_hip(c, e, "graph capture");
-                }
-                c->g_Y[cls] = d_Y;
-            }
-            hipError_t e = hipGraphLaunch(c->gexec[cls], c->stream);
-            if (e != hipSuccess) { c->yi_fresh = 0; return fail_hip(c, e, "graph launch"); }
-            if (counted) c->t_seen++;
-            c->yi_fresh = 1;
-            continue;
-        }
         int rc = step_impl(c, d_Y, it, cached, keep);
         if (rc != TSNE_OK) { c->yi_fresh = 0; return rc; }
     }

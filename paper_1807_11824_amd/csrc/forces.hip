@@ -77,35 +77,29 @@ constexpr int AW_LPR = 16, AW_U = 4;
 // runs beside it (the kernel is held to 64 registers for the same reason).  Within one window
 // step the rows are handed to the groups longest first through a counter in LDS, one row
 // ahead; a row's sum does not depend on which group takes it or when.
-#ifndef AN_PD_N
-#define AN_PD_N 2
-#endif
 constexpr int AN_THREADS = 512, AN_ROWS = ATTRACT_ROWS, AN_S = ATTRACT_RING, AN_LPR = 4, AN_CH = ATTRACT_CHUNK;
 static_assert(AN_CH == 8 * AN_LPR, "a lane takes two quads of a chunk");
-constexpr int AN_PD = AN_PD_N, AN_GROUPS = AN_THREADS / AN_LPR;
+constexpr int AN_PD = 2, AN_GROUPS = AN_THREADS / AN_LPR;
 
-// Shares of the rows for the resident workgroups: the first k1 workgroups (the part that runs
-// beside the tree build) split the first `early` percent of the work evenly, the other k2 split
-// the rest.  Work of rows [0, r) = their entries plus a fixed cost per row.
-__global__ void attract_partition(const int32_t *__restrict__ rp_near, int n, int k1, int k2, int early,
-                                  int32_t *__restrict__ arow)
+// Shares of the rows for the k resident workgroups: equal work each, the work of rows [0, r)
+// being their entries plus a fixed cost per row.
+__global__ void attract_partition(const int32_t *__restrict__ rp_near, int n, int k, int32_t *__restrict__ arow)
 {
     const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (b > k1 + k2) return;
+    if (b > k) return;
     const int64_t total = (int64_t)rp_near[n] + 16ll * n;
-    const int64_t cut = k1 > 0 ? total * early / 100 : 0;
-    const int64_t target = b < k1 ? cut * b / k1 : cut + (total - cut) * (b - k1) / k2;
+    const int64_t target = total * b / k;
     int lo = 0, hi = n;   // smallest r with work(r) >= target
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
         if ((int64_t)rp_near[mid] + 16ll * mid >= target) hi = mid; else lo = mid + 1;
     }
-    arow[b] = b == k1 + k2 ? n : lo;
+    arow[b] = b == k ? n : lo;
 }
 
 __global__ __attribute__((amdgpu_waves_per_eu(8))) __launch_bounds__(AN_THREADS) void
 attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, const float4 *__restrict__ val4,
-             const float2 *__restrict__ Y, int n, const int32_t *__restrict__ arow, int share0,
+             const float2 *__restrict__ Y, int n, const int32_t *__restrict__ arow,
              const int32_t *__restrict__ rp_far, const float2 *__restrict__ Afar, float2 *__restrict__ A)
 {
     __shared__ float2 ring[AN_S];
@@ -116,7 +110,7 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
     __shared__ uint16_t order[AN_ROWS];
     static_assert(AN_ROWS <= 65536, "rows per step");
     constexpr int KPT = (AN_ROWS + AN_THREADS - 1) / AN_THREADS;
-    const int share = share0 + (int)blockIdx.x;
+    const int share = (int)blockIdx.x;
     const int rb = min(max(arow[share], 0), n), re = min(max(arow[share + 1], rb), n);
     if (rb >= re) return;
     const int tid = (int)threadIdx.x, sub = tid % AN_LPR, grp = tid / AN_LPR;
@@ -459,17 +453,13 @@ hipError_t attract_far_tiled_prepare()
                                (int)FT_LDS);
 }
 
-#ifndef FAR_BLOCKS
-#define FAR_BLOCKS 1024
-#endif
-// share-out of the rows (once per P), then the part of the attraction that may run early
-static void attract_shares(const tsne_ctx *c, int *k1, int *k2)
+constexpr int FAR_BLOCKS = 1024;
+// number of resident workgroups of attract_near
+static int attract_shares(const tsne_ctx *c)
 {
-    const int n = c->p.n;
     const int per_cu = c->p.attract_resident > 0 ? c->p.attract_resident : 1;
-    const int tiles = (n + AN_ROWS - 1) / AN_ROWS;
-    *k2 = max(1, min(min(per_cu * c->num_cu, ATTRACT_MAX_PARTS / 2), tiles));
-    *k1 = c->p.attract_early > 0 ? max(1, min(c->num_cu / 4, tiles)) : 0;
+    const int tiles = (c->p.n + AN_ROWS - 1) / AN_ROWS;
+    return max(1, min(min(per_cu * c->num_cu, ATTRACT_MAX_PARTS / 2), tiles));
 }
 
 // The far part from its tiles.  A small far part is summed row by row beside the tree build; the
@@ -488,23 +478,20 @@ static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
                        c->ft_meta, c->ft_acc, c->Afar);
 }
 
-hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s)
+// The far part of the renumbered P when it is summed row by row (also shares the rows of the
+// streaming part out, once per P).
+hipError_t launch_attract_far(tsne_ctx *c, hipStream_t s)
 {
     const int n = c->p.n;
     if (!(c->reorder_on && !c->identity)) return hipSuccess;
-    int k1, k2;
-    attract_shares(c, &k1, &k2);
     if (!c->arow_valid) {   // P changed since the rows were shared out
-        hipLaunchKernelGGL(attract_partition, dim3((k1 + k2 + 256) / 256), dim3(256), 0, s, c->rp_near, n, k1, k2,
-                           c->p.attract_early, c->arow);
+        const int k = attract_shares(c);
+        hipLaunchKernelGGL(attract_partition, dim3((k + 256) / 256), dim3(256), 0, s, c->rp_near, n, k, c->arow);
         c->arow_valid = 1;
     }
     if (!c->ft_active)
         hipLaunchKernelGGL(attract_far, dim3((unsigned)min((n + 15) / 16, FAR_BLOCKS)), dim3(256), 0, s, c->rp_far, c->col_far,
                            c->val_s, c->Yi, n, c->far_rows, c->far_count, c->Afar);
-    if (k1 > 0)
-        hipLaunchKernelGGL(attract_near, dim3(k1), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
-                           (const float4 *)c->val_s, c->Yi, n, c->arow, 0, c->rp_far, c->Afar, c->A);
     return hipGetLastError();
 }
 
@@ -512,11 +499,9 @@ hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s)
 {
     const int n = c->p.n;
     if (c->reorder_on && !c->identity) {
-        int k1, k2;
-        attract_shares(c, &k1, &k2);
         if (c->ft_active) launch_far_tiles(c, s);
-        hipLaunchKernelGGL(attract_near, dim3(k2), dim3(AN_THREADS), 0, s, c->rp_near, (const uint4 *)c->col_near,
-                           (const float4 *)c->val_s, c->Yi, n, c->arow, k1, c->rp_far, c->Afar, c->A);
+        hipLaunchKernelGGL(attract_near, dim3(attract_shares(c)), dim3(AN_THREADS), 0, s, c->rp_near,
+                           (const uint4 *)c->col_near, (const float4 *)c->val_s, c->Yi, n, c->arow, c->rp_far, c->Afar, c->A);
     } else {
         const unsigned blocks = (unsigned)(((int64_t)n * AW_LPR + 255) / 256);
         hipLaunchKernelGGL((attract_csr<AW_LPR, AW_U>), dim3(blocks), dim3(256), 0, s, c->user_row_ptr, c->user_col,
@@ -543,12 +528,16 @@ __global__ __launch_bounds__(256) void update_k(float2 *__restrict__ Y, const ui
 {
     const int s = blockIdx.x * blockDim.x + threadIdx.x;
     const bool live = s < n;
+    // Once the device has reported trouble (a non-finite coordinate, a tree or a walk that did not
+    // fit) the forces of this step are not to be trusted: embedding and optimiser state stay as they are.
+    const bool frozen = *status != 0u;
     float2 y = make_float2(0.f, 0.f);
-    if (live) {
-        const float invZ = (float)(1.0 / *Z);
+    if (live) y = Yi[s];
+    if (live && !frozen) {
+        const double Zd = *Z;
+        const float invZ = Zd > 0.0 ? (float)(1.0 / Zd) : 0.f;    // a single point has no pairs: Z = 0, R = 0
         const float2 a = A[s], r = R[s];
         float2 g = gains[s], u = uY[s];
-        y = Yi[s];
         const float gx = 4.0f * (alpha * a.x - r.x * invZ), gy = 4.0f * (alpha * a.y - r.y * invZ);
         g.x = (sign3(gx) != sign3(u.x)) ? g.x + gain_inc : g.x * gain_dec;
         g.y = (sign3(gy) != sign3(u.y)) ? g.y + gain_inc : g.y * gain_dec;

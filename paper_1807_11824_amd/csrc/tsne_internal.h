@@ -37,10 +37,7 @@ constexpr int LEVEL_TILE = LEVEL_THREADS * LEVEL_ITEMS;
 constexpr int BBOX_MAX_BLOCKS = 1024;
 constexpr int WALK_COUNTERS = 16;        // work counters of the resident walk (a power of two)
 constexpr int ATTRACT_BAND = 1280;       // half width of the near part of the renumbered P
-#ifndef ATTRACT_ROWS_N
-#define ATTRACT_ROWS_N 512
-#endif
-constexpr int ATTRACT_ROWS = ATTRACT_ROWS_N;        // rows the attraction kernel's window of Y advances by
+constexpr int ATTRACT_ROWS = 512;        // rows the attraction kernel's window of Y advances by
 constexpr int ATTRACT_RING = ATTRACT_ROWS + 2 * ATTRACT_BAND;   // points in that window (a ring in LDS)
 static_assert(ATTRACT_RING * 8 <= 65536, "ring offsets are stored in 16 bits");
 constexpr int ATTRACT_CHUNK = 32;        // near rows are padded to a multiple of this many entries
@@ -120,11 +117,7 @@ struct tsne_ctx {
     double *zpart, *Z;
     double *kl_part;
     int sorted_buf;      // which of keys[]/idx[] holds the sorted result
-    // tsne_run: one captured iteration per (exaggerated?, early momentum?) phase, valid for one Y pointer
-    hipGraphExec_t gexec[4];
-    float *g_Y[4];
-    hipStream_t gstream;           // the stream the capture is made on (the caller's may be the default stream, which cannot capture)
-    // optional per-phase timing: 6 events per armed step
+    // optional per-phase timing: 9 events per armed step
     hipEvent_t *tev;
     int t_cap, t_used;
     char err[256];
@@ -148,7 +141,7 @@ hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s);
 hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);
 hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
-hipError_t launch_attract_early(tsne_ctx *c, hipStream_t s);
+hipError_t launch_attract_far(tsne_ctx *c, hipStream_t s);    // the far part of the renumbered P (no-op otherwise)
 hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, int write_user,
                          hipStream_t s);

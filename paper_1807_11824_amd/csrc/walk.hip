@@ -31,36 +31,13 @@
 
 #include <math.h>
 
-#ifndef WALK_STACK_N
-#define WALK_STACK_N 512
-#endif
-constexpr int WALK_STACK = WALK_STACK_N;   // stack entries
+constexpr int WALK_STACK = 512;      // stack entries
 constexpr int WALK_SLACK = 48;       // head room for a depth-first descent (3 entries per level, 16 levels)
 constexpr int WALK_PEND = 128;       // pending list entries
 constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied by their own lane
-#ifndef WALK_CLIST_N
-#define WALK_CLIST_N 96
-#endif
-#ifndef WALK_PLIST_N
-#define WALK_PLIST_N 512
-#endif
-constexpr int WALK_CLIST = WALK_CLIST_N;     // accepted cells waiting for the drain (16 B each), >= 64
-constexpr int WALK_PLIST = WALK_PLIST_N;     // points of opened leaves waiting (8 B each), >= 64 * WALK_FAST_LEAF
+constexpr int WALK_CLIST = 96;       // accepted cells waiting for the drain (16 B each), >= 64
+constexpr int WALK_PLIST = 512;      // points of opened leaves waiting (8 B each), >= 64 * WALK_FAST_LEAF
 static_assert(WALK_CLIST >= WAVE && WALK_PLIST >= WAVE * WALK_FAST_LEAF, "one round must fit");
-
-#ifdef WALK_STATS
-// instrumentation for tuning builds only: sums and maxima over all waves of one launch
-__device__ unsigned long long g_walk_stats[16];
-extern "C" int tsne_debug_walk_stats(unsigned long long *out, int reset)
-{
-    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_walk_stats), sizeof(g_walk_stats)) != hipSuccess) return -1;
-    if (reset) { unsigned long long z[16] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(g_walk_stats), z, sizeof(z)); }
-    return 0;
-}
-#define WSTAT(stmt) stmt
-#else
-#define WSTAT(stmt)
-#endif
 
 // side^2 < theta^2 * d2, with d2 = fma(dy, dy, dx*dx): one rounding per operation.
 __device__ __forceinline__ float dist2_rounded(float dx, float dy)
@@ -173,8 +150,6 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
     int sp = 1, np = 0, icc = 0, icp = 0;   // wave-uniform; kept in scalar registers via readfirstlane
     bool overflow = false;
     uint32_t rounds = 0;
-    WSTAT(unsigned st_sift = 0; unsigned st_settle = 0; unsigned st_press = 0; unsigned st_maxsp = 0; unsigned st_inter = 0;
-          unsigned st_sifted = 0; unsigned st_settled = 0;)
     if (lane == 0) stack[0] = 0u;
     __syncthreads();
     // four members of the group used as quick witnesses: if Eq. (14) fails for one of them the
@@ -202,11 +177,9 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
             take = min(min(np, WAVE), room >> 2);            // pending cells free no stack entry
             id = lane < take ? pend[np - take + lane] : 0u;
             np -= take;
-            WSTAT(st_settle++; st_settled += take;)
         } else {
             take = pressure ? 1 : min(min(sp, WAVE), room / 3);   // a popped cell nets at most +3
             id = lane < take ? stack[sp - take + lane] : 0u;
-            WSTAT(st_sift++; st_sifted += take; if ((unsigned)sp > st_maxsp) st_maxsp = sp; if (pressure) st_press++;)
             sp -= take;
         }
         const bool act = lane < take;
@@ -319,12 +292,6 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
     }
     drain_cells(clist, icc, x, y, fx, fy, z);
     drain_points(plist, icp, x, y, fx, fy, z);
-    WSTAT(if (lane == 0) {
-        atomicAdd(&g_walk_stats[0], 1ull); atomicAdd(&g_walk_stats[1], (unsigned long long)st_sift);
-        atomicAdd(&g_walk_stats[2], (unsigned long long)st_settle); atomicAdd(&g_walk_stats[3], (unsigned long long)st_press);
-        atomicAdd(&g_walk_stats[4], (unsigned long long)st_sifted); atomicAdd(&g_walk_stats[5], (unsigned long long)st_settled);
-        atomicMax(&g_walk_stats[6], (unsigned long long)st_maxsp); atomicAdd(&g_walk_stats[7], (unsigned long long)st_maxsp);
-    })
     if (valid) R[min(perm[p], (uint32_t)n - 1u)] = make_float2(fx, fy);
     double zd = wave_sum(valid ? (double)z : 0.0);
     if (lane == 0) zpart[g] = zd;

@@ -271,7 +271,7 @@ def test_far_part_from_tiles(n, k):
     A_tiles, _, _, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, far_tiles=2)
     assert st == 0 and rel_l2(A_tiles, Ao) <= 1e-6
     assert rel_l2(A_tiles, A_rows) <= 1e-6
-    for params in (dict(far_tiles=2), dict(far_tiles=0), dict(far_tiles=2, overlap=0), dict(far_tiles=0, overlap=3)):
+    for params in (dict(far_tiles=2), dict(far_tiles=0), dict(far_tiles=2, overlap=0), dict(far_tiles=0, overlap=0)):
         if params.get("far_tiles") == 0 and n < (1 << 18):
             continue        # the automatic choice stays with the row-by-row kernel below 2^18 points
         A, _, _, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, **params)
@@ -279,15 +279,15 @@ def test_far_part_from_tiles(n, k):
 
 
 def test_launch_shapes_change_nothing():
-    """Stream layout (overlap 0-3), resident or one-wave-per-group walk, share of the attraction started early:
-    every output of tsne_gradient is bitwise the same."""
+    """One or two streams, resident or one-wave-per-group walk, one or two resident workgroups of the attraction
+    per compute unit: every output of tsne_gradient is bitwise the same."""
     import torch
     n = 300_007            # more groups than 14 resident waves on each of 256 compute units
     rp, col, val = _banded_csr(n, 12, 700, 11, seed=21)
     Y = synth.clustered_embedding(n, n_clusters=300, seed=22)
     ref = None
-    for params in (dict(overlap=0, walk_resident=0), dict(overlap=2), dict(overlap=1, walk_resident=0),
-                   dict(overlap=3, walk_resident=6), dict(overlap=2, attract_early=35, attract_resident=2)):
+    for params in (dict(overlap=0, walk_resident=0), dict(overlap=1), dict(overlap=1, walk_resident=0),
+                   dict(overlap=0, walk_resident=6), dict(overlap=1, attract_resident=2)):
         A, R, Z, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, **params)
         assert st == 0
         if ref is None:

@@ -54,7 +54,7 @@ def test_forces_in_bench_configuration(full):
     cfg, P = full["cfg"], full["P"]
     n = cfg["n"]
     dev = torch.device("cuda:0")
-    ts = Tsne(n, overlap=2, leaf_cap=8, max_nnz=P["nnz"])   # bench.py's defaults
+    ts = Tsne(n, overlap=1, leaf_cap=8, max_nnz=P["nnz"])   # bench.py's defaults
     ts.set_P(P["row_ptr"], P["col"], P["val"])
     Y = torch.from_numpy(synth.y0(n)).to(dev)
     ts.run(Y, 30)

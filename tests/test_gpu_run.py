@@ -143,12 +143,11 @@ def test_run_equals_repeated_steps_bitwise():
     dev = torch.device("cuda:0")
     X, _ = synth.gaussian_mixture(6000, 16, 12, 6.0, 1.0, seed=3)
     P = build_P(torch.from_numpy(X).to(dev), 20.0, 60)
-    # (graphs=1: the middle iterations of a run are replayed from a captured HIP graph, several replays with
-    # eager iterations around them; exaggeration_iters=6 and momentum_switch_iter=9 put three phases into 13 steps)
+    # (exaggeration_iters=6 and momentum_switch_iter=9 put three phases into 13 steps)
     for kw in (dict(), dict(max_nnz=P["nnz"]), dict(max_nnz=P["nnz"], reorder_every=4),
-               dict(max_nnz=P["nnz"], graphs=1, exaggeration_iters=6, momentum_switch_iter=9),
-               dict(graphs=1, overlap=0)):
-        a = Tsne(6000, **kw); b = Tsne(6000, **dict(kw, graphs=0))
+               dict(max_nnz=P["nnz"], exaggeration_iters=6, momentum_switch_iter=9),
+               dict(overlap=0)):
+        a = Tsne(6000, **kw); b = Tsne(6000, **kw)
         for t in (a, b):
             t.set_P(P["row_ptr"], P["col"], P["val"])
         Ya = torch.from_numpy(synth.y0(6000, seed=9)).to(dev); Yb = Ya.clone()
@@ -166,3 +165,48 @@ def test_run_equals_repeated_steps_bitwise():
         assert torch.equal(Ya, Yb), kw
         assert a.status() == 0 and b.status() == 0
         a.close(); b.close()
+
+
+def test_single_point():
+    """n = 1: no pairs, Z = 0, zero gradient -- the point stays where it is and nothing is flagged."""
+    import torch
+    from paper_1807_11824_amd import Tsne
+    dev = torch.device("cuda:0")
+    t = Tsne(1)
+    t.set_P(torch.zeros(2, dtype=torch.int32, device=dev), torch.zeros(0, dtype=torch.int32, device=dev),
+            torch.zeros(0, dtype=torch.float32, device=dev))
+    Y = torch.tensor([[0.25, -3.0]], dtype=torch.float32, device=dev)
+    A, R, Z = t.gradient(Y)
+    assert float(Z[0]) == 0.0 and not A.any() and not R.any()
+    t.step(Y, 0)
+    t.run(Y, 3, iter0=1)
+    assert t.status() == 0
+    assert Y.cpu().tolist() == [[0.25, -3.0]]
+    u, g = t.get_state()
+    assert not u.any() and torch.isfinite(g).all()
+    t.close()
+
+
+def test_device_trouble_freezes_embedding_and_state():
+    """A non-finite coordinate is flagged by the tree build; from then on the update leaves the embedding and
+    the optimiser state as they are (no NaN spreads), and tsne_run reports it."""
+    import torch
+    from paper_1807_11824_amd import Tsne, TsneError, STATUS_NONFINITE
+    from helpers import random_symmetric_csr
+    dev = torch.device("cuda:0")
+    n = 3000
+    rp, col, val = random_symmetric_csr(n, 10, seed=4)
+    for kw in (dict(), dict(max_nnz=len(col))):
+        t = Tsne(n, **kw)
+        t.set_P(*[torch.from_numpy(a).to(dev) for a in (rp, col, val)])
+        Y0 = synth.y0(n, seed=3)
+        Y0[1234, 0] = np.inf
+        Y = torch.from_numpy(Y0).to(dev)
+        with pytest.raises(TsneError) as ei:
+            t.run(Y, 4)
+        assert ei.value.code == -5
+        assert t.status() & STATUS_NONFINITE
+        assert np.array_equal(Y.cpu().numpy(), Y0)
+        u, g = t.get_state()
+        assert not u.any() and (g == 1).all()
+        t.close()

@@ -40,6 +40,9 @@ def _rng_cases():
         "outlier": np.vstack([r.random((4097, 2)) * 1e-3, [[100.0, -50.0]]]).astype(np.float32),
         "clusters_100k": synth.clustered_embedding(100_003, n_clusters=300, seed=2),
         "collapsed_clusters": synth.clustered_embedding(30_000, n_clusters=20, spread=5.0, sigma=1e-4, seed=3),
+        # every point twice: with leaf_cap = 1 a chain of one-child cells runs to the deepest level under each pair
+        # (about 4.7 cells per point, more than any other case here)
+        "pairs_20000": np.repeat(r.random((10_000, 2)).astype(np.float32), 2, axis=0),
     }
 
 
