@@ -244,6 +244,22 @@ int tsne_export_tree(tsne_ctx *ctx, uint32_t *d_keys, int32_t *d_perm, int32_t c
 int tsne_kl(tsne_ctx *ctx, const float *d_Y, double *kl);
 
 /*
+ * tsne_kl for callers that cannot allocate or hold a context: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same kernels and the same result as tsne_kl on the same P and Y;
+ * the partial sums live in a 24 KB array inside the library's device image (one copy per GPU, kept until the
+ * process ends) instead of a context's workspace.  The call allocates nothing, creates nothing and does not
+ * synchronise: it enqueues four kernels on `stream`.
+ * d_Y: n x 2 floats; P: CSR with n rows (d_col / d_val may be NULL only if the matrix has no entries);
+ * d_out (device, caller-owned): d_out[0] = KL(P||Q), d_out[1] = the exact Z of Eq. (4).
+ * n > TSNE_KL_STATIC_MAX_N returns TSNE_EINVAL (the all-pairs sum is O(n^2); beyond this size use a context).
+ * All calls on one GPU share the one array: calls that overlap on the same GPU (two streams, two threads)
+ * race and give wrong results; calls on one stream are ordered and safe.
+ */
+#define TSNE_KL_STATIC_MAX_N (1 << 22)
+int tsne_kl_static(const float *d_Y, int32_t n, const int32_t *d_row_ptr, const int32_t *d_col, const float *d_val,
+                   double *d_out, void *stream);
+
+/*
  * Per-phase GPU time of tsne_step, measured with HIP events recorded on the streams the kernels
  * run on.  tsne_timing_begin() arms the next max_steps calls of tsne_step (9 events per step);
  * tsne_timing_end() synchronises, and returns the number of steps timed plus the mean milliseconds

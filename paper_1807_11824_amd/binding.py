@@ -69,6 +69,7 @@ def lib():
         "tsne_gradient": (C.c_int, [vp, vp, vp, vp, vp]),
         "tsne_export_tree": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, C.POINTER(i32)]),
         "tsne_kl": (C.c_int, [vp, vp, C.POINTER(C.c_double)]),
+        "tsne_kl_static": (C.c_int, [vp, i32, vp, vp, vp, vp, vp]),
         "tsne_status": (C.c_int, [vp, C.POINTER(C.c_uint32)]),
         "tsne_timing_begin": (C.c_int, [vp, i32]),
         "tsne_timing_begin_every": (C.c_int, [vp, i32, i32]),
@@ -210,6 +211,18 @@ def build_P_approx(X, perplexity, k, tau, nlist=0, kmeans_iters=10, stream=None,
     m = nnz.value
     return dict(row_ptr=row_ptr, col=col[:m], val=val[:m], nnz=m, unconverged=bad.value,
                 knn_idx=knn_idx, knn_d2=knn_d2, tau_used=used.value)
+
+
+def kl_static(Y, row_ptr, col, val, out, stream=None):
+    """tsne_kl_static: KL(P||Q) and the exact Z into the caller's device tensor `out` (2 doubles).  Enqueues only;
+    allocates nothing."""
+    _dev(Y, torch.float32, "Y"); _dev(row_ptr, torch.int32, "row_ptr"); _dev(out, torch.float64, "out")
+    if out.numel() < 2:
+        raise ValueError("out: need two doubles")
+    L = lib()
+    rc = L.tsne_kl_static(_ptr(Y), Y.shape[0], _ptr(row_ptr), _ptr(col), _ptr(val), _ptr(out), _stream_ptr(stream))
+    if rc:
+        raise TsneError(rc, "tsne_kl_static", L.tsne_strerror(rc).decode())
 
 
 class Tsne:

@@ -678,6 +678,11 @@ __global__ void kl_final_k(double *__restrict__ part, int nb)
     part[1] = Z;
 }
 
+__global__ void kl_copy_out_k(const double *__restrict__ part, double *__restrict__ out)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) { out[0] = part[0]; out[1] = part[1]; }
+}
+
 hipError_t launch_kl(tsne_ctx *c, const float *d_Y, hipStream_t s)
 {
     const int n = c->p.n;
@@ -687,4 +692,36 @@ hipError_t launch_kl(tsne_ctx *c, const float *d_Y, hipStream_t s)
                        c->kl_part + KL_BLOCKS, c->kl_part + 2 * KL_BLOCKS);
     hipLaunchKernelGGL(kl_final_k, dim3(1), dim3(64), 0, s, c->kl_part, KL_BLOCKS);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ the same utility for callers that cannot allocate
+// tsne_kl_static: the three kernels above with their partial sums in a file-scope device array
+// instead of a context's workspace, so that no context (and no allocation of any kind) is needed.
+// Every GPU holds its own copy of the array at its own address, looked up once per device.
+static __device__ __align__(256) double scratch[3 * KL_BLOCKS];
+constexpr int KL_STATIC_MAX_DEVICES = 64;
+static double *scratch_ptr[KL_STATIC_MAX_DEVICES];     // device address of `scratch`, by device ordinal
+
+extern "C" int tsne_kl_static(const float *d_Y, int32_t n, const int32_t *d_row_ptr, const int32_t *d_col,
+                              const float *d_val, double *d_out, void *stream)
+{
+    if (!d_Y || !d_row_ptr || !d_out || n < 1 || n > TSNE_KL_STATIC_MAX_N) return TSNE_EINVAL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return TSNE_EHIP;
+    if (dev < 0 || dev >= KL_STATIC_MAX_DEVICES) return TSNE_EINVAL;
+    if (!scratch_ptr[dev]) {
+        double *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TSNE_EHIP;
+        scratch_ptr[dev] = ptr;
+    }
+    double *part = scratch_ptr[dev];
+    hipStream_t s = (hipStream_t)stream;
+    const float2 *Y = (const float2 *)d_Y;
+    // every launch writes all of its KL_BLOCKS partial sums, so nothing of an earlier call is read
+    hipLaunchKernelGGL(exact_z_k, dim3(KL_BLOCKS), dim3(256), 0, s, Y, n, part);
+    hipLaunchKernelGGL(kl_terms_k, dim3(KL_BLOCKS), dim3(256), 0, s, d_row_ptr, d_col, d_val, Y, n, part + KL_BLOCKS,
+                       part + 2 * KL_BLOCKS);
+    hipLaunchKernelGGL(kl_final_k, dim3(1), dim3(64), 0, s, part, KL_BLOCKS);
+    hipLaunchKernelGGL(kl_copy_out_k, dim3(1), dim3(64), 0, s, part, d_out);
+    return hipGetLastError() == hipSuccess ? TSNE_OK : TSNE_EHIP;
 }
