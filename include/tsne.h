@@ -61,7 +61,11 @@ typedef struct {
     float gain_inc;               /* 0.2 */
     float gain_dec;               /* 0.8 */
     float gain_min;               /* 0.01 */
-    int32_t morton_bits;          /* grid bits per axis = maximum tree depth, 1..16 (16) */
+    int32_t morton_bits;          /* grid bits per axis = maximum tree depth, 1..24, and
+                                     2 morton_bits + ceil(log2 n) <= 64 (a point's grid key and its number share a
+                                     64-bit word in the sort).  (the smaller of 22 and (64 - ceil(log2 n)) / 2:
+                                     21 at n = 1.28M; late in a run whole clusters are smaller than 2^-16 of the
+                                     embedding's extent and only a deeper grid splits them) */
     int32_t leaf_cap;             /* a cell with at most this many points is a leaf, >= 1 (8) */
     int32_t overlap;              /* 1: the attractive forces run on a second stream, the entries far from the
                                      diagonal beside the tree build and the streaming part beside the tree walk;
@@ -228,14 +232,14 @@ int tsne_gradient(tsne_ctx *ctx, const float *d_Y, float *d_attr, float *d_rep, 
 
 /*
  * Copies out the tree of the last tsne_step / tsne_gradient (device arrays, any may be NULL):
- * d_keys[n]   interleaved grid key of every point (x in even bits), original order
+ * d_keys[n]   interleaved grid key of every point (x in even bits, 2 morton_bits bits), original order
  * d_perm[n]   spatial order: position p holds original index d_perm[p]
  * cells in depth-first pre-order, children in quadrant order, cap_cells entries each:
  * d_depth, d_lo, d_hi (member positions [lo,hi)), d_leaf (0/1), d_com (2 floats per cell)
  * d_root[3]   lower corner x, y and side of the root square
  * *n_cells (host) receives the cell count.  Synchronises.
  */
-int tsne_export_tree(tsne_ctx *ctx, uint32_t *d_keys, int32_t *d_perm, int32_t cap_cells,
+int tsne_export_tree(tsne_ctx *ctx, uint64_t *d_keys, int32_t *d_perm, int32_t cap_cells,
                      int32_t *d_depth, int32_t *d_lo, int32_t *d_hi, int32_t *d_leaf, float *d_com,
                      float *d_root, int32_t *n_cells);
 

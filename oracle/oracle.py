@@ -134,19 +134,19 @@ def morton(Y, bits=16):
     Y = _f32(Y)
     n = Y.shape[0]
     root = np.empty(3, np.float32)
-    keys = np.empty(n, np.uint32)
-    rc = _L().oracle_morton(_p(Y, C.c_float), n, bits, _p(root, C.c_float), _p(keys, C.c_uint32))
+    keys = np.empty(n, np.uint64)
+    rc = _L().oracle_morton(_p(Y, C.c_float), n, bits, _p(root, C.c_float), _p(keys, C.c_uint64))
     if rc != 0:
         raise ValueError("oracle_morton: bad arguments or non-finite coordinate")
     return root, keys
 
 
 def sort_keys(keys):
-    keys = np.ascontiguousarray(keys, np.uint32)
+    keys = np.ascontiguousarray(keys, np.uint64)
     n = keys.shape[0]
-    sk = np.empty(n, np.uint32)
+    sk = np.empty(n, np.uint64)
     perm = np.empty(n, np.int32)
-    if _L().oracle_sort(_p(keys, C.c_uint32), n, _p(sk, C.c_uint32), _p(perm, C.c_int32)) != 0:
+    if _L().oracle_sort(_p(keys, C.c_uint64), n, _p(sk, C.c_uint64), _p(perm, C.c_int32)) != 0:
         raise MemoryError
     return sk, perm
 
@@ -161,9 +161,9 @@ def tree(Y, bits=16, leaf_cap=8):
     cap = n * (bits + 1) + 1        # every level holds at most n cells
     depth = np.empty(cap, np.int32); lo = np.empty(cap, np.int32); hi = np.empty(cap, np.int32)
     leaf = np.empty(cap, np.int32); child = np.empty((cap, 4), np.int32)
-    prefix = np.empty(cap, np.uint32); com = np.empty((cap, 2), np.float32)
-    m = _L().oracle_tree(_p(sk, C.c_uint32), _p(Ys, C.c_float), n, bits, leaf_cap, cap,
-                         _p(depth, C.c_int32), _p(prefix, C.c_uint32), _p(lo, C.c_int32),
+    prefix = np.empty(cap, np.uint64); com = np.empty((cap, 2), np.float32)
+    m = _L().oracle_tree(_p(sk, C.c_uint64), _p(Ys, C.c_float), n, bits, leaf_cap, cap,
+                         _p(depth, C.c_int32), _p(prefix, C.c_uint64), _p(lo, C.c_int32),
                          _p(hi, C.c_int32), _p(leaf, C.c_int32), _p(child, C.c_int32),
                          _p(com, C.c_float))
     if m < 0:

@@ -293,11 +293,13 @@ double oracle_kl(const double *Y, int32_t n, const int32_t *row_ptr, const int32
 /* of two >= max(extent x, extent y), never below 2^-40.  Each coordinate   */
 /* is quantised to `bits` bits in SINGLE precision, one rounding per        */
 /* operation; the key interleaves x into the even and y into the odd bits.  */
+/* bits <= 24: a float has 24 significant bits, a finer grid cannot tell    */
+/* two different coordinates apart any better.                              */
 /* root[0..2] = x0, y0, W.  Returns -1 if a coordinate is not finite.       */
 /* ------------------------------------------------------------------------ */
-int oracle_morton(const float *Y, int32_t n, int32_t bits, float *root, uint32_t *keys)
+int oracle_morton(const float *Y, int32_t n, int32_t bits, float *root, uint64_t *keys)
 {
-    if (!Y || !root || !keys || n < 1 || bits < 1 || bits > 16) return -1;
+    if (!Y || !root || !keys || n < 1 || bits < 1 || bits > 24) return -1;
     float minx = Y[0], maxx = Y[0], miny = Y[1], maxy = Y[1];
     for (int32_t i = 0; i < n; ++i) {
         float x = Y[2 * i], y = Y[2 * i + 1];
@@ -320,10 +322,10 @@ int oracle_morton(const float *Y, int32_t n, int32_t bits, float *root, uint32_t
         float fx = floorf(sx), fy = floorf(sy);
         uint32_t qx = fx >= (float)qmax ? qmax : (uint32_t)fx;
         uint32_t qy = fy >= (float)qmax ? qmax : (uint32_t)fy;
-        uint32_t key = 0;
+        uint64_t key = 0;
         for (int32_t b = 0; b < bits; ++b) {
-            key |= ((qx >> b) & 1u) << (2 * b);
-            key |= ((qy >> b) & 1u) << (2 * b + 1);
+            key |= (uint64_t)((qx >> b) & 1u) << (2 * b);
+            key |= (uint64_t)((qy >> b) & 1u) << (2 * b + 1);
         }
         keys[i] = key;
     }
@@ -331,7 +333,7 @@ int oracle_morton(const float *Y, int32_t n, int32_t bits, float *root, uint32_t
 }
 
 /* Sec. III-C step 4: order points along the curve; ties by original index. */
-typedef struct { uint32_t key; int32_t idx; } keyidx_t;
+typedef struct { uint64_t key; int32_t idx; } keyidx_t;
 
 static int cmp_keyidx(const void *a, const void *b)
 {
@@ -341,7 +343,7 @@ static int cmp_keyidx(const void *a, const void *b)
     return 0;
 }
 
-int oracle_sort(const uint32_t *keys, int32_t n, uint32_t *sorted_keys, int32_t *perm)
+int oracle_sort(const uint64_t *keys, int32_t n, uint64_t *sorted_keys, int32_t *perm)
 {
     keyidx_t *t = (keyidx_t *)malloc((size_t)n * sizeof(keyidx_t));
     if (!t) return -1;
@@ -362,16 +364,16 @@ int oracle_sort(const uint32_t *keys, int32_t n, uint32_t *sorted_keys, int32_t 
 /* mean of its points (summed in double in sorted order, rounded to float). */
 /* ------------------------------------------------------------------------ */
 typedef struct {
-    const uint32_t *keys;   /* sorted */
+    const uint64_t *keys;   /* sorted */
     const float *Ys;        /* points in sorted order, n x 2 */
     int32_t bits, leaf_cap, cap, m;
     int32_t *depth, *lo, *hi, *leaf, *child; /* child: 4 per node, -1 = none */
-    uint32_t *prefix;
+    uint64_t *prefix;
     float *com;             /* 2 per node */
     int overflow;
 } treeb_t;
 
-static int32_t tree_rec(treeb_t *T, int32_t lo, int32_t hi, int32_t depth, uint32_t prefix)
+static int32_t tree_rec(treeb_t *T, int32_t lo, int32_t hi, int32_t depth, uint64_t prefix)
 {
     if (T->m >= T->cap) { T->overflow = 1; return -1; }
     int32_t id = T->m++;
@@ -386,7 +388,7 @@ static int32_t tree_rec(treeb_t *T, int32_t lo, int32_t hi, int32_t depth, uint3
     if (is_leaf) return id;
     int shift = 2 * (T->bits - depth - 1);
     int32_t p = lo;
-    for (uint32_t q = 0; q < 4; ++q) {
+    for (uint64_t q = 0; q < 4; ++q) {
         int32_t s = p;
         while (p < hi && ((T->keys[p] >> shift) & 3u) == q) ++p;
         if (p > s) T->child[4 * id + q] = tree_rec(T, s, p, depth + 1, (prefix << 2) | q);
@@ -394,12 +396,12 @@ static int32_t tree_rec(treeb_t *T, int32_t lo, int32_t hi, int32_t depth, uint3
     return id;
 }
 
-int32_t oracle_tree(const uint32_t *sorted_keys, const float *Ys, int32_t n, int32_t bits,
+int32_t oracle_tree(const uint64_t *sorted_keys, const float *Ys, int32_t n, int32_t bits,
                     int32_t leaf_cap, int32_t cap,
-                    int32_t *depth, uint32_t *prefix, int32_t *lo, int32_t *hi, int32_t *leaf,
+                    int32_t *depth, uint64_t *prefix, int32_t *lo, int32_t *hi, int32_t *leaf,
                     int32_t *child, float *com)
 {
-    if (n < 1 || bits < 1 || bits > 16 || leaf_cap < 1) return -1;
+    if (n < 1 || bits < 1 || bits > 24 || leaf_cap < 1) return -1;
     treeb_t T = { sorted_keys, Ys, bits, leaf_cap, cap, 0, depth, lo, hi, leaf, child, prefix, com, 0 };
     tree_rec(&T, 0, n, 0, 0u);
     return T.overflow ? -1 : T.m;
@@ -493,12 +495,12 @@ int32_t oracle_repulse_bh(const float *Y, int32_t n, float theta, int32_t leaf_c
     int64_t cap64 = (int64_t)n + (int64_t)bits * (n / ((int64_t)leaf_cap + 1)) + 1;
     if (cap64 > 0x7FFFFFFF) return -1;
     int32_t cap = (int32_t)cap64;
-    uint32_t *keys = malloc((size_t)n * 4), *skeys = malloc((size_t)n * 4);
+    uint64_t *keys = malloc((size_t)n * 8), *skeys = malloc((size_t)n * 8);
     int32_t *perm = malloc((size_t)n * 4);
     float *Ys = malloc((size_t)n * 8);
     int32_t *depth = malloc((size_t)cap * 4), *lo = malloc((size_t)cap * 4), *hi = malloc((size_t)cap * 4);
     int32_t *leaf = malloc((size_t)cap * 4), *child = malloc((size_t)cap * 16);
-    uint32_t *prefix = malloc((size_t)cap * 4);
+    uint64_t *prefix = malloc((size_t)cap * 8);
     float *com = malloc((size_t)cap * 8);
     float root[3];
     int32_t m = -1;

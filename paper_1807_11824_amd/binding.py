@@ -303,7 +303,7 @@ class Tsne:
         n = self.n
         cap = cap_cells if cap_cells is not None else n + self.params.morton_bits * (n // (self.params.leaf_cap + 1)) + 1
         dev = self.device
-        keys = torch.empty(n, dtype=torch.int32, device=dev)
+        keys = torch.empty(n, dtype=torch.int64, device=dev)
         perm = torch.empty(n, dtype=torch.int32, device=dev)
         depth = torch.empty(cap, dtype=torch.int32, device=dev)
         lo = torch.empty(cap, dtype=torch.int32, device=dev)

@@ -46,14 +46,11 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     q = take(sizeof(float4));                        if (c) c->root = (float4 *)q;
     q = take(sizeof(uint32_t));                      if (c) c->status = (uint32_t *)q;
     q = take(sizeof(uint32_t));                      if (c) c->ncells = (uint32_t *)q;
-    for (int k = 0; k < 2; ++k) {
-        q = take(4 * n); if (c) c->keys[k] = (uint32_t *)q;
-        q = take(4 * n); if (c) c->idx[k] = (uint32_t *)q;
-    }
-    q = take(4 * n);                                 if (c) c->keys_orig = (uint32_t *)q;
+    for (int k = 0; k < 2; ++k) { q = take(8 * n); if (c) c->words[k] = (uint64_t *)q; }
+    q = take(4 * n);                                 if (c) c->perm = (uint32_t *)q;
     q = take(4 * n);                                 if (c) c->row_order = (uint32_t *)q;
-    q = take(4 * 256 * nblk_sort);                   if (c) c->hist = (uint32_t *)q;
-    q = take(4 * 256);                               if (c) c->dtot = (uint32_t *)q;
+    q = take(4 * (size_t)RADIX * nblk_sort);         if (c) c->hist = (uint32_t *)q;
+    q = take(4 * (size_t)RADIX);                     if (c) c->dtot = (uint32_t *)q;
     q = take(8 * n);                                 if (c) c->Ys = (float2 *)q;
     q = take(2 * n);                                 if (c) c->lev = (uint16_t *)q;
     q = take(sizeof(ScanPart) * nblk_lev);           if (c) c->part = (ScanPart *)q;
@@ -108,12 +105,22 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
     return off;
 }
 
+// bits needed for the numbers 0 .. n-1
+int index_bits(int64_t n)
+{
+    int b = 0;
+    while (((int64_t)1 << b) < n) ++b;
+    return b;
+}
+
 int check_params(const tsne_params *p)
 {
     if (!p) return TSNE_EINVAL;
     if (p->n < 1 || p->n > (1 << 30)) return TSNE_EINVAL;
     if (!(p->theta >= 0.0f) || p->theta > 0.7f) return TSNE_EINVAL;
-    if (p->morton_bits < 1 || p->morton_bits > 16) return TSNE_EINVAL;
+    if (p->morton_bits < 1 || p->morton_bits > MAX_GRID_BITS) return TSNE_EINVAL;
+    // a point's grid key and its number share one 64-bit word in the sort
+    if (2 * p->morton_bits + index_bits(p->n) > 64) return TSNE_EINVAL;
     if (p->leaf_cap < 1) return TSNE_EINVAL;
     if (p->overlap < 0 || p->overlap > 1) return TSNE_EINVAL;
     if (cell_capacity(p->n, p->morton_bits, p->leaf_cap) > 0x7FFFFFFFll) return TSNE_EINVAL;   // cells are numbered in 32 bits
@@ -193,7 +200,7 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev, bool cached = 
     // spatial order (the kernel has finished by now on either stream, so the array is free to
     // overwrite).  With renumbering the slots themselves are ordered and rows go in slot order.
     if (!c->reorder_on &&
-        (e = hipMemcpyAsync(c->row_order, c->idx[c->sorted_buf], 4 * (size_t)c->p.n, hipMemcpyDeviceToDevice,
+        (e = hipMemcpyAsync(c->row_order, c->perm, 4 * (size_t)c->p.n, hipMemcpyDeviceToDevice,
                             c->stream)) != hipSuccess)
         return fail_hip(c, e, "copy row order");
     c->tree_valid = 1;
@@ -246,7 +253,7 @@ int tsne_default_params(tsne_params *p, int32_t n)
     p->gain_inc = 0.2f;
     p->gain_dec = 0.8f;
     p->gain_min = 0.01f;
-    p->morton_bits = 16;
+    p->morton_bits = n >= 1 ? std::min(22, (64 - index_bits(n)) / 2) : 22;
     p->leaf_cap = 8;
     p->overlap = 1;
     p->graph_order_iters = 64;
@@ -280,6 +287,7 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
     c->p = *p;
     c->stream = (hipStream_t)stream;
     carve(c, p, (char *)d_workspace);
+    c->key_shift = 64 - 2 * p->morton_bits;
     c->reorder_on = (p->reorder_every > 0 || p->graph_order_iters > 0) && p->max_nnz > 0;
     c->identity = 1;
     hipError_t e;
@@ -521,7 +529,7 @@ int tsne_gradient(tsne_ctx *c, const float *d_Y, float *d_attr, float *d_rep, do
     return e == hipSuccess ? TSNE_OK : fail_hip(c, e, "copy forces");
 }
 
-int tsne_export_tree(tsne_ctx *c, uint32_t *d_keys, int32_t *d_perm, int32_t cap_cells, int32_t *d_depth,
+int tsne_export_tree(tsne_ctx *c, uint64_t *d_keys, int32_t *d_perm, int32_t cap_cells, int32_t *d_depth,
                      int32_t *d_lo, int32_t *d_hi, int32_t *d_leaf, float *d_com, float *d_root, int32_t *n_cells)
 {
     if (!c || cap_cells < 0) return TSNE_EINVAL;

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void ft_scatter_k(const int32_t *__restrict__ 
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode)
 {
     const int n = c->p.n;
-    const uint32_t *perm = c->idx[c->sorted_buf];
+    const uint32_t *perm = c->perm;
     const int a = c->cur_state, b = a ^ 1;
     hipLaunchKernelGGL(reorder_state_k, dim3((n + 255) / 256), dim3(256), 0, s, perm, n, c->orig[a], c->orig[b],
                        c->uYb[a], c->uYb[b], c->gainsb[a], c->gainsb[b], c->inv);
@@ -292,14 +292,12 @@ __global__ __launch_bounds__(256) void graph_smooth_k(const int32_t *__restrict_
     if (row < n && sub == 0) xo[row] = w > 0.f ? a / w : x[row];
 }
 
-__global__ __launch_bounds__(256) void graph_keys_k(const float *__restrict__ x, int n, uint32_t *__restrict__ keys,
-                                                    uint32_t *__restrict__ idx)
+__global__ __launch_bounds__(256) void graph_keys_k(const float *__restrict__ x, int n, uint64_t *__restrict__ words)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const uint32_t u = __float_as_uint(x[i]);     // x >= 0: the bit pattern is already ordered
-    keys[i] = u;
-    idx[i] = (uint32_t)i;
+    words[i] = ((uint64_t)u << 32) | (uint32_t)i;
 }
 
 hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s)
@@ -312,8 +310,9 @@ hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s)
         hipLaunchKernelGGL(graph_smooth_k, dim3(blocks), dim3(256), 0, s, c->user_row_ptr, c->user_col, c->user_val, xa, n, xb);
         float *tmp = xa; xa = xb; xb = tmp;
     }
-    hipLaunchKernelGGL(graph_keys_k, dim3((n + 255) / 256), dim3(256), 0, s, xa, n, c->keys[0], c->idx[0]);
-    return launch_sort(c, 32, s);
+    hipLaunchKernelGGL(graph_keys_k, dim3((n + 255) / 256), dim3(256), 0, s, xa, n, c->words[0]);
+    hipError_t e = launch_sort(c, 32, 32, false, s);
+    return e != hipSuccess ? e : launch_unpack_perm(c, s);
 }
 
 // out[orig[s]] = in[s] and its inverse (copies between slot order and the caller's order)
@@ -340,24 +339,5 @@ hipError_t launch_scatter2(const float2 *in, const uint32_t *orig, float2 *out, 
 hipError_t launch_gather2(const float2 *in, const uint32_t *orig, float2 *out, int n, hipStream_t s)
 {
     hipLaunchKernelGGL(gather2_k, dim3((n + 255) / 256), dim3(256), 0, s, in, orig, out, n);
-    return hipGetLastError();
-}
-
-// keys and spatial order in the caller's numbering (tests only)
-__global__ __launch_bounds__(256) void export_order_k(const uint32_t *__restrict__ keys_slot, const uint32_t *__restrict__ perm,
-                                                      const uint32_t *__restrict__ orig, int n, uint32_t *__restrict__ keys_out,
-                                                      int32_t *__restrict__ perm_out)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    if (keys_out) keys_out[min(orig[i], (uint32_t)n - 1u)] = keys_slot[i];
-    if (perm_out) perm_out[i] = (int32_t)orig[min(perm[i], (uint32_t)n - 1u)];
-}
-
-hipError_t launch_export_order(tsne_ctx *c, uint32_t *d_keys, int32_t *d_perm, hipStream_t s)
-{
-    const int n = c->p.n;
-    hipLaunchKernelGGL(export_order_k, dim3((n + 255) / 256), dim3(256), 0, s, c->keys_orig, c->idx[c->sorted_buf],
-                       c->orig[c->cur_state], n, d_keys, d_perm);
     return hipGetLastError();
 }

@@ -3,12 +3,16 @@
 // the tree is read off the sorted keys.
 //
 //   bbox_partial / bbox_final   step 1   min/max reduction -> root square (power-of-two side)
-//   morton_encode               step 2a  16-bit grid coordinates, bit-interleaved key
-//   radix_hist / _scan / _scatter  step 4  stable LSD radix sort of (key, index), 8 bits a pass
+//   morton_encode_hist          step 2a  grid coordinates (up to 24 bits per axis), bit-interleaved key
+//   radix_hist / _scan / _scatter  step 4  stable LSD radix sort, 11 bits a pass
 //   small_root_keys_sort        steps 1, 2a, 4 in one launch of one workgroup, for few points
 //   gather_levels               step 2b  which cells start at each sorted position
-//   scan_partials / downsweep   step 3   prefix sums: cell numbering and running coordinate sums
+//   downsweep                   step 3   prefix sums: cell numbering and running coordinate sums
 //   write_cells                 steps 2c+3  cell records: members, count, centre of mass, children
+//
+// The sort works on one 64-bit word per point, (key << key_shift) | slot with key_shift = 64 - 2 bits:
+// the order of the words is the order by (key, slot), which is the stable order the tree is defined
+// on, and no index array travels through the passes.
 //
 // A cell at depth t is the run of sorted positions sharing the top 2t key bits.  A position p
 // opens cells at depths tmin(p).. where tmin is fixed by the first digit in which key[p] differs
@@ -95,13 +99,15 @@ __global__ __launch_bounds__(1024) void bbox_final(const float4 *__restrict__ pa
 }
 
 // ------------------------------------------------------------------ grid keys
-__device__ __forceinline__ uint32_t spread16(uint32_t v)
+// bits of v (up to 24) to the even positions
+__device__ __forceinline__ uint64_t spread24(uint32_t q)
 {
-    v &= 0xFFFFu;
-    v = (v | (v << 8)) & 0x00FF00FFu;
-    v = (v | (v << 4)) & 0x0F0F0F0Fu;
-    v = (v | (v << 2)) & 0x33333333u;
-    v = (v | (v << 1)) & 0x55555555u;
+    uint64_t v = q & 0xFFFFFFu;
+    v = (v | (v << 16)) & 0x0000FFFF0000FFFFull;
+    v = (v | (v << 8)) & 0x00FF00FF00FF00FFull;
+    v = (v | (v << 4)) & 0x0F0F0F0F0F0F0F0Full;
+    v = (v | (v << 2)) & 0x3333333333333333ull;
+    v = (v | (v << 1)) & 0x5555555555555555ull;
     return v;
 }
 
@@ -115,29 +121,16 @@ __device__ __forceinline__ uint32_t grid_coord(float v, float origin, float S, u
     return f >= (float)qmax ? qmax : (f > 0.0f ? (uint32_t)f : 0u);
 }
 
-__global__ __launch_bounds__(256) void morton_encode(const float2 *__restrict__ Y, int n,
-                                                     const float4 *__restrict__ root, int bits,
-                                                     uint32_t *__restrict__ keys_orig,
-                                                     uint32_t *__restrict__ keys, uint32_t *__restrict__ idx)
+__device__ __forceinline__ uint64_t grid_key(float2 y, float4 r, uint32_t qmax)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    float4 r = *root;
-    float2 y = Y[i];
-    uint32_t qmax = (1u << bits) - 1u;
-    uint32_t qx = grid_coord(y.x, r.x, r.w, qmax);
-    uint32_t qy = grid_coord(y.y, r.y, r.w, qmax);
-    uint32_t key = spread16(qx) | (spread16(qy) << 1);
-    keys_orig[i] = key;
-    keys[i] = key;
-    idx[i] = (uint32_t)i;
+    return spread24(grid_coord(y.x, r.x, r.w, qmax)) | (spread24(grid_coord(y.y, r.y, r.w, qmax)) << 1);
 }
 
 // ------------------------------------------------------------------ few points: one workgroup does it all
-// Root square, keys and the sort of (key, index) in one launch, for n <= SMALL_SORT_MAX: the pairs
-// sit in LDS as key * 2^32 + index (all different, so any sorting network gives the order of a
-// stable sort by key), padded with all-ones to m, the power of two >= n.  Same root, same keys
-// and same order as bbox_final + morton_encode + the radix passes.
+// Root square, keys and the sort in one launch, for n <= SMALL_SORT_MAX: the words (key, slot) sit
+// in LDS (all different, so any sorting network gives the order of a stable sort by key), padded
+// with all-ones to m, the power of two >= n.  Same root, same keys and same order as bbox_final +
+// morton_encode_hist + the radix passes.
 //
 // The network is the bitonic one.  A thread holds E = 2^LOGE pairs that differ in LOGE
 // neighbouring index bits, so one trip through LDS serves LOGE exchange distances; one padding
@@ -192,9 +185,8 @@ __device__ __forceinline__ void bitonic_trip(unsigned long long *pairs, int t, i
 template <int LOGE>
 __global__ __launch_bounds__(1024) void small_root_keys_sort(const float2 *__restrict__ Y, int n, int m,
                                                              const float4 *__restrict__ part, int nparts, int bits,
-                                                             float4 *__restrict__ root, uint32_t *__restrict__ keys_orig,
-                                                             uint32_t *__restrict__ keys_out,
-                                                             uint32_t *__restrict__ idx_out, uint32_t *status)
+                                                             int ks, float4 *__restrict__ root,
+                                                             uint64_t *__restrict__ words_out, uint32_t *status)
 {
     extern __shared__ unsigned long long pairs[];
     __shared__ float4 smn[16], smx[16];
@@ -226,14 +218,7 @@ __global__ __launch_bounds__(1024) void small_root_keys_sort(const float2 *__res
     const uint32_t qmax = (1u << bits) - 1u;
     for (int i = tid; i < m; i += nthr) {
         unsigned long long v = ~0ull;
-        if (i < n) {
-            float2 y = Y[i];
-            uint32_t qx = grid_coord(y.x, r.x, r.w, qmax);
-            uint32_t qy = grid_coord(y.y, r.y, r.w, qmax);
-            uint32_t key = spread16(qx) | (spread16(qy) << 1);
-            keys_orig[i] = key;
-            v = ((unsigned long long)key << 32) | (uint32_t)i;
-        }
+        if (i < n) v = (grid_key(Y[i], r, qmax) << ks) | (uint32_t)i;
         pairs[small_sort_slot(i)] = v;
     }
     __syncthreads();
@@ -247,11 +232,7 @@ __global__ __launch_bounds__(1024) void small_root_keys_sort(const float2 *__res
             __syncthreads();
         }
     }
-    for (int i = tid; i < n; i += nthr) {
-        unsigned long long v = pairs[small_sort_slot(i)];
-        keys_out[i] = (uint32_t)(v >> 32);
-        idx_out[i] = (uint32_t)v;
-    }
+    for (int i = tid; i < n; i += nthr) words_out[i] = pairs[small_sort_slot(i)];
 }
 
 static size_t small_sort_lds(int m) { return 8 * (size_t)(m + (m >> 3)); }
@@ -262,132 +243,216 @@ hipError_t small_sort_prepare()
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_sort_lds(SMALL_SORT_MAX));
 }
 
-// ------------------------------------------------------------------ radix sort (stable, LSD, 8 bits)
-// hist layout: hist[digit * nblk + block].
-__global__ __launch_bounds__(SORT_THREADS) void radix_hist(const uint32_t *__restrict__ keys, int n, int shift,
-                                                           uint32_t *__restrict__ hist, int nblk)
+// ------------------------------------------------------------------ radix sort (stable, LSD, 11 bits a pass)
+// Three kernels a pass: digit counts per tile (hist[tile][digit]; the first pass gets them from
+// the kernel that wrote the words), their prefix over the tiles, and the scatter.
+__device__ __forceinline__ uint32_t digit_of(uint64_t w, int lo, uint32_t mask) { return (uint32_t)(w >> lo) & mask; }
+
+// Root square (already reduced), grid key and word of every point, and the digit counts of the
+// first radix pass.
+__global__ __launch_bounds__(SORT_THREADS) void morton_encode_hist(const float2 *__restrict__ Y, int n,
+                                                                   const float4 *__restrict__ root, int bits, int ks,
+                                                                   uint32_t mask, uint64_t *__restrict__ words,
+                                                                   uint32_t *__restrict__ hist)
 {
-    __shared__ uint32_t h[256];
-    h[threadIdx.x] = 0;
+    __shared__ uint32_t h[RADIX];
+    for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) h[d] = 0u;
     __syncthreads();
-    int base = blockIdx.x * SORT_TILE;
+    const float4 r = *root;
+    const uint32_t qmax = (1u << bits) - 1u;
+    const int base = blockIdx.x * SORT_TILE;
 #pragma unroll
-    for (int r = 0; r < SORT_ITEMS; ++r) {
-        int e = base + r * SORT_THREADS + threadIdx.x;
-        if (e < n) atomicAdd(&h[(keys[e] >> shift) & 0xFFu], 1u);
+    for (int k = 0; k < SORT_ITEMS; ++k) {
+        const int e = base + k * SORT_THREADS + (int)threadIdx.x;
+        if (e < n) {
+            const uint64_t w = (grid_key(Y[e], r, qmax) << ks) | (uint32_t)e;
+            words[e] = w;
+            atomicAdd(&h[digit_of(w, ks, mask)], 1u);
+        }
     }
     __syncthreads();
-    hist[threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+    for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) hist[(size_t)blockIdx.x * RADIX + d] = h[d];
 }
 
-// Block d turns hist[d][0..nblk) into its exclusive prefix and stores the digit total.
-__global__ __launch_bounds__(256) void radix_scan(uint32_t *__restrict__ hist, int nblk, uint32_t *__restrict__ dtot)
+__global__ __launch_bounds__(SORT_THREADS) void radix_hist(const uint64_t *__restrict__ words, int n, int lo, uint32_t mask,
+                                                           uint32_t *__restrict__ hist)
 {
-    __shared__ uint32_t wsum[4];
-    uint32_t *row = hist + (size_t)blockIdx.x * nblk;
-    uint32_t carry = 0;
-    int w = threadIdx.x >> 6;
-    for (int b0 = 0; b0 < nblk; b0 += 256) {
-        int b = b0 + threadIdx.x;
-        int v = b < nblk ? (int)row[b] : 0;
-        int tot;
-        int ex = wave_excl_scan(v, &tot);
-        if (lane_id() == 0) wsum[w] = (uint32_t)tot;
-        __syncthreads();
-        uint32_t wbase = 0, all = 0;
-        for (int k = 0; k < 4; ++k) { if (k < w) wbase += wsum[k]; all += wsum[k]; }
-        if (b < nblk) row[b] = carry + wbase + (uint32_t)ex;
-        carry += all;
-        __syncthreads();
+    __shared__ uint32_t h[RADIX];
+    for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) h[d] = 0u;
+    __syncthreads();
+    const int base = blockIdx.x * SORT_TILE;
+#pragma unroll
+    for (int k = 0; k < SORT_ITEMS; ++k) {
+        const int e = base + k * SORT_THREADS + (int)threadIdx.x;
+        if (e < n) atomicAdd(&h[digit_of(words[e], lo, mask)], 1u);
     }
-    if (threadIdx.x == 0) dtot[blockIdx.x] = carry;
+    __syncthreads();
+    for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) hist[(size_t)blockIdx.x * RADIX + d] = h[d];
 }
 
-__global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint32_t *__restrict__ keys_in,
-                                                              const uint32_t *__restrict__ idx_in,
-                                                              uint32_t *__restrict__ keys_out,
-                                                              uint32_t *__restrict__ idx_out, int n, int shift,
+// hist[t][d] becomes the number of words with digit d in tiles before t; dtot[d] the digit's total.
+// A workgroup takes 32 digits; 16 threads share a digit, each a segment of the tiles.
+constexpr int SCAN_DIGITS = 32, SCAN_SEGS = 16;
+__global__ __launch_bounds__(SCAN_DIGITS * SCAN_SEGS) void radix_scan(uint32_t *__restrict__ hist, int nblk,
+                                                                      uint32_t *__restrict__ dtot)
+{
+    __shared__ uint32_t ssum[SCAN_SEGS][SCAN_DIGITS];
+    const int dl = (int)threadIdx.x % SCAN_DIGITS, sg = (int)threadIdx.x / SCAN_DIGITS;
+    const int d = blockIdx.x * SCAN_DIGITS + dl;
+    const int len = (nblk + SCAN_SEGS - 1) / SCAN_SEGS;
+    const int t0 = min(nblk, sg * len), t1 = min(nblk, t0 + len);
+    uint32_t sum = 0;
+    for (int t = t0; t < t1; ++t) sum += hist[(size_t)t * RADIX + d];
+    ssum[sg][dl] = sum;
+    __syncthreads();
+    uint32_t run = 0, all = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_SEGS; ++k) {
+        const uint32_t v = ssum[k][dl];
+        if (k < sg) run += v;
+        all += v;
+    }
+    if (sg == 0) dtot[d] = all;
+    for (int t = t0; t < t1; ++t) {
+        const uint32_t v = hist[(size_t)t * RADIX + d];
+        hist[(size_t)t * RADIX + d] = run;
+        run += v;
+    }
+}
+
+// Exclusive prefix over the workgroup of one value per thread (SORT_THREADS threads); all threads call.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wsum /* SORT_THREADS / 64 */)
+{
+    int tot;
+    const int ex = wave_excl_scan((int)v, &tot);
+    const int w = (int)threadIdx.x >> 6;
+    __syncthreads();
+    if (lane_id() == 0) wsum[w] = (uint32_t)tot;
+    __syncthreads();
+    uint32_t wb = 0;
+    for (int k = 0; k < w; ++k) wb += wsum[k];
+    return wb + (uint32_t)ex;
+}
+
+// Workgroups reach the eight XCDs in turn.  Tile numbers are dealt so that each XCD works on a
+// contiguous range of tiles: the pieces of one digit's output run that neighbouring tiles write
+// are adjacent in memory, and this way they meet in one second-level cache and leave it as whole lines.
+__device__ __forceinline__ int scatter_tile(int block, int nblk)
+{
+    const int per = (nblk + 7) / 8;
+    return (block % 8) * per + block / 8;
+}
+
+__global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
+                                                              int n, int lo, uint32_t mask,
                                                               const uint32_t *__restrict__ hist,
                                                               const uint32_t *__restrict__ dtot, int nblk)
 {
-    __shared__ uint32_t whist[4][256];   // per-wave running digit counts, later per-wave starts
-    __shared__ uint32_t gbase[256];      // global start of (digit, this block)
-    __shared__ uint32_t lstart[256];     // start of the digit inside the locally sorted tile
-    __shared__ uint32_t dscan[4];
-    __shared__ uint32_t skey[SORT_TILE], sidx[SORT_TILE];
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-    for (int k = 0; k < 4; ++k) whist[k][tid] = 0;
-    // exclusive scan of the 256 digit totals
+    constexpr int NW = SORT_THREADS / WAVE, DPT = RADIX / SORT_THREADS;   // digits per thread
+    // per-wave running digit counts, later per-wave starts; once every word knows its place in the
+    // locally sorted tile the same memory holds that tile
+    __shared__ __align__(16) unsigned char overlay[SORT_TILE * 8];
+    static_assert(sizeof(uint16_t) * NW * RADIX <= sizeof(overlay), "the counts fit the tile's space");
+    uint16_t (*whist)[RADIX] = reinterpret_cast<uint16_t (*)[RADIX]>(overlay);
+    uint64_t *sorted = reinterpret_cast<uint64_t *>(overlay);
+    __shared__ uint32_t gbase[RADIX];       // global start of (digit, this tile)
+    __shared__ uint16_t lstart[RADIX];      // start of the digit inside the locally sorted tile
+    __shared__ uint32_t wsum[NW];
+    const int tile = scatter_tile((int)blockIdx.x, nblk);
+    if (tile >= nblk) return;               // the same for every thread of the workgroup
+    const int tid = (int)threadIdx.x, w = tid >> 6, lane = tid & 63;
     {
-        int v = (int)dtot[tid], tot;
-        int ex = wave_excl_scan(v, &tot);
-        if (lane == 0) dscan[w] = (uint32_t)tot;
-        __syncthreads();
-        uint32_t wb = 0;
-        for (int k = 0; k < w; ++k) wb += dscan[k];
-        gbase[tid] = wb + (uint32_t)ex + hist[tid * nblk + blockIdx.x];
+        uint32_t *z = reinterpret_cast<uint32_t *>(overlay);
+        for (int i = tid; i < NW * RADIX / 2; i += SORT_THREADS) z[i] = 0u;
     }
-    __syncthreads();
-    const int tile0 = blockIdx.x * SORT_TILE;
+    // where every digit's run starts in the output: digits before it, then tiles before this one
+    {
+        uint32_t t[DPT], sum = 0;
+#pragma unroll
+        for (int j = 0; j < DPT; ++j) { t[j] = dtot[tid * DPT + j]; sum += t[j]; }
+        uint32_t run = block_excl_scan(sum, wsum);      // (its barriers also cover the zeroing above)
+#pragma unroll
+        for (int j = 0; j < DPT; ++j) {
+            gbase[tid * DPT + j] = run + hist[(size_t)tile * RADIX + tid * DPT + j];
+            run += t[j];
+        }
+    }
+    const int tile0 = tile * SORT_TILE;
     const int base = tile0 + w * (WAVE * SORT_ITEMS);
-    uint32_t key[SORT_ITEMS], val[SORT_ITEMS], rank[SORT_ITEMS];
+    uint64_t word[SORT_ITEMS];
+    uint32_t rank[SORT_ITEMS];
 #pragma unroll
     for (int r = 0; r < SORT_ITEMS; ++r) {
-        int e = base + r * WAVE + lane;
-        bool valid = e < n;
-        key[r] = valid ? keys_in[e] : 0u;
-        val[r] = valid ? idx_in[e] : 0u;
-        uint32_t d = (key[r] >> shift) & 0xFFu;
-        // lanes of this round holding the same digit
+        const int e = base + r * WAVE + lane;
+        word[r] = e < n ? in[e] : 0ull;
+    }
+    // Rank inside the wave's share, one item of every lane at a time: lanes with the same digit are
+    // found with one ballot per digit bit.  whist[w] is touched by wave w alone, whose LDS
+    // instructions execute in program order, so the rounds need no barrier between them.
+    volatile uint16_t *mine = whist[w];
+#pragma unroll
+    for (int r = 0; r < SORT_ITEMS; ++r) {
+        const bool valid = base + r * WAVE + lane < n;
+        const uint32_t d = digit_of(word[r], lo, mask);
         uint64_t peers = __ballot(valid);
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            uint64_t bal = __ballot((d >> b) & 1u);
+        for (int b = 0; b < RADIX_BITS; ++b) {
+            const uint64_t bal = __ballot((d >> b) & 1u);
             peers &= ((d >> b) & 1u) ? bal : ~bal;
         }
-        uint32_t before = (uint32_t)__popcll(peers & lanemask_lt());
-        uint32_t pre = whist[w][d];
+        const uint32_t before = (uint32_t)__popcll(peers & lanemask_lt());
+        const uint32_t pre = mine[d];
         rank[r] = pre + before;
-        __syncthreads();
-        if (valid && before == 0) whist[w][d] = pre + (uint32_t)__popcll(peers);
-        __syncthreads();
+        if (valid && before == 0) mine[d] = (uint16_t)(pre + (uint32_t)__popcll(peers));
     }
-    // per digit: where each wave's share starts inside the block's run, and where the run starts
+    __syncthreads();
+    // per digit: where each wave's share starts inside the tile's run, and where the run starts
     // inside the locally sorted tile
     {
-        const uint32_t c0 = whist[0][tid], c1 = whist[1][tid], c2 = whist[2][tid], c3 = whist[3][tid];
-        int tot;
-        const int ex = wave_excl_scan((int)(c0 + c1 + c2 + c3), &tot);
-        __syncthreads();
-        if (lane == 0) dscan[w] = (uint32_t)tot;
-        whist[0][tid] = 0; whist[1][tid] = c0; whist[2][tid] = c0 + c1; whist[3][tid] = c0 + c1 + c2;
-        __syncthreads();
-        uint32_t wb = 0;
-        for (int k = 0; k < w; ++k) wb += dscan[k];
-        lstart[tid] = wb + (uint32_t)ex;
+        uint32_t tot[DPT], sum = 0;
+#pragma unroll
+        for (int j = 0; j < DPT; ++j) {
+            uint32_t acc = 0;
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                const uint32_t c = whist[k][tid * DPT + j];
+                whist[k][tid * DPT + j] = (uint16_t)acc;
+                acc += c;
+            }
+            tot[j] = acc;
+            sum += acc;
+        }
+        uint32_t run = block_excl_scan(sum, wsum);
+#pragma unroll
+        for (int j = 0; j < DPT; ++j) { lstart[tid * DPT + j] = (uint16_t)run; run += tot[j]; }
     }
     __syncthreads();
     // stable local sort through LDS ...
 #pragma unroll
     for (int r = 0; r < SORT_ITEMS; ++r) {
-        int e = base + r * WAVE + lane;
-        if (e < n) {
-            uint32_t d = (key[r] >> shift) & 0xFFu;
-            uint32_t lp = lstart[d] + whist[w][d] + rank[r];
-            skey[lp] = key[r];
-            sidx[lp] = val[r];
-        }
+        const uint32_t d = digit_of(word[r], lo, mask);
+        rank[r] += (uint32_t)lstart[d] + (uint32_t)whist[w][d];
     }
+    __syncthreads();      // the counts are no longer needed: their memory becomes the sorted tile
+#pragma unroll
+    for (int r = 0; r < SORT_ITEMS; ++r)
+        if (base + r * WAVE + lane < n) sorted[min(rank[r], (uint32_t)SORT_TILE - 1u)] = word[r];
     __syncthreads();
     // ... so that consecutive threads write consecutive addresses within each digit's run
     const int cnt = min(SORT_TILE, n - tile0);
     for (int j = tid; j < cnt; j += SORT_THREADS) {
-        const uint32_t k = skey[j];
-        const uint32_t d = (k >> shift) & 0xFFu;
-        const uint32_t pos = gbase[d] + ((uint32_t)j - lstart[d]);
-        keys_out[pos] = k;
-        idx_out[pos] = sidx[j];
+        const uint64_t v = sorted[j];
+        const uint32_t d = digit_of(v, lo, mask);
+        const uint32_t pos = gbase[d] + ((uint32_t)j - (uint32_t)lstart[d]);
+        if (pos < (uint32_t)n) out[pos] = v;
     }
+}
+
+// the low 32 bits of every word
+__global__ __launch_bounds__(256) void unpack_perm_k(const uint64_t *__restrict__ words, int n, uint32_t *__restrict__ perm)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n) perm[p] = (uint32_t)words[p];
 }
 
 // ------------------------------------------------------------------ cells opened at each position
@@ -397,32 +462,34 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint32_t *__
 constexpr int KEY_HALO = 256;
 
 struct KeyWindow {
-    const uint32_t *__restrict__ keys;   // sorted keys in memory
-    const uint32_t *lds;                 // keys[lo, lo + len)
+    const uint64_t *__restrict__ words;  // sorted words in memory (key << ks | slot)
+    const uint64_t *lds;                 // keys of positions [lo, lo + len)
     uint32_t lo, len;
-    __device__ __forceinline__ uint32_t operator[](uint32_t q) const
+    int ks;
+    __device__ __forceinline__ uint64_t operator[](uint32_t q) const
     {
         const uint32_t off = q - lo;
-        return off < len ? lds[off] : keys[q];
+        return off < len ? lds[off] : words[q] >> ks;
     }
 };
 
 // Cooperative fill; the caller synchronises the workgroup afterwards.
-__device__ __forceinline__ KeyWindow key_window_fill(const uint32_t *__restrict__ keys, uint32_t n, uint32_t first,
-                                                     uint32_t count, uint32_t *lds)
+__device__ __forceinline__ KeyWindow key_window_fill(const uint64_t *__restrict__ words, int ks, uint32_t n, uint32_t first,
+                                                     uint32_t count, uint64_t *lds)
 {
     KeyWindow w;
-    w.keys = keys;
+    w.words = words;
     w.lds = lds;
+    w.ks = ks;
     w.lo = first > (uint32_t)KEY_HALO ? first - KEY_HALO : 0u;
     const uint32_t hi = min(n, first + count + KEY_HALO);
     w.len = hi > w.lo ? hi - w.lo : 0u;
-    for (uint32_t t = threadIdx.x; t < w.len; t += blockDim.x) lds[t] = keys[w.lo + t];
+    for (uint32_t t = threadIdx.x; t < w.len; t += blockDim.x) lds[t] = words[w.lo + t] >> ks;
     return w;
 }
 
 // Sorted keys: the positions whose key shifted right by sh equals pre form one contiguous run.
-__device__ __forceinline__ uint32_t run_end(const KeyWindow &keys, uint32_t n, uint32_t p, int sh, uint32_t pre)
+__device__ __forceinline__ uint32_t run_end(const KeyWindow &keys, uint32_t n, uint32_t p, int sh, uint64_t pre)
 {
     uint32_t lo = p, hi, step = 1;
     for (;;) {
@@ -439,7 +506,7 @@ __device__ __forceinline__ uint32_t run_end(const KeyWindow &keys, uint32_t n, u
     return hi;
 }
 
-__device__ __forceinline__ uint32_t run_begin(const KeyWindow &keys, uint32_t p, int sh, uint32_t pre)
+__device__ __forceinline__ uint32_t run_begin(const KeyWindow &keys, uint32_t p, int sh, uint64_t pre)
 {
     int64_t lo, hi = p, step = 1;
     for (;;) {
@@ -460,12 +527,12 @@ __device__ __forceinline__ uint32_t run_begin(const KeyWindow &keys, uint32_t p,
 __device__ __forceinline__ void levels_at(const KeyWindow &keys, uint32_t n, uint32_t p, int B,
                                           uint32_t C, int *tmin_out, int *tend_out)
 {
-    uint32_t key = keys[p];
+    uint64_t key = keys[p];
     int tmin;
     if (p == 0) tmin = 0;
     else {
-        uint32_t x = key ^ keys[p - 1];
-        tmin = x ? B - ((31 - __clz((int)x)) >> 1) : B + 1;
+        uint64_t x = key ^ keys[p - 1];
+        tmin = x ? B - ((63 - __clzll((long long)x)) >> 1) : B + 1;
     }
     int tend = tmin;
     if (tmin <= B) {
@@ -474,7 +541,7 @@ __device__ __forceinline__ void levels_at(const KeyWindow &keys, uint32_t n, uin
         else if (tmin == 1) pc = n;
         else {
             int sh = 2 * (B - (tmin - 1));
-            uint32_t pre = key >> sh;
+            uint64_t pre = key >> sh;
             pc = run_end(keys, n, p, sh, pre) - run_begin(keys, p, sh, pre);
         }
         int t = tmin;
@@ -497,10 +564,10 @@ __device__ __forceinline__ void levels_at(const KeyWindow &keys, uint32_t n, uin
 // top s digits (L[j], R[j]: number of leading digits p shares with positions p-j, p+j).
 constexpr int LEVELS_WINDOW_MAXC = 16;
 
-__device__ __forceinline__ int common_digits(uint32_t a, uint32_t b, int B)
+__device__ __forceinline__ int common_digits(uint64_t a, uint64_t b, int B)
 {
-    const uint32_t x = a ^ b;
-    return x ? B - 1 - ((31 - __clz((int)x)) >> 1) : B;
+    const uint64_t x = a ^ b;
+    return x ? B - 1 - ((63 - __clzll((long long)x)) >> 1) : B;
 }
 
 // CT > 0: leaf_cap known at compile time (all indices static, no bisection); CT = 0: any
@@ -509,7 +576,7 @@ template <int CT>
 __device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n, uint32_t p, int B, int C,
                                               int *tmin_out, int *tend_out)
 {
-    const uint32_t key = keys[p];
+    const uint64_t key = keys[p];
     const int tmin = p == 0 ? 0 : (key == keys[p - 1] ? B + 1 : common_digits(key, keys[p - 1], B) + 1);
     int smax;
     if (CT > 0) {
@@ -551,27 +618,36 @@ __device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n,
     *tend_out = tend;
 }
 
-// Also moves the points into spatial order (step 4) and reduces each tile's (cells, sum x, sum y).
+// Also moves the points into spatial order (step 4), writes the order itself (position -> slot)
+// and reduces each tile's (cells, sum x, sum y).
 template <int CT>
 __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__restrict__ Y,
-                                                               const uint32_t *__restrict__ keys,
-                                                               const uint32_t *__restrict__ perm, int n, int B, int C,
-                                                               float2 *__restrict__ Ys, uint16_t *__restrict__ lev,
-                                                               ScanPart *__restrict__ part)
+                                                               const uint64_t *__restrict__ words, int ks, int n, int B,
+                                                               int C, float2 *__restrict__ Ys,
+                                                               uint32_t *__restrict__ perm, uint16_t *__restrict__ lev,
+                                                               ScanPart *__restrict__ part,
+                                                               uint32_t *__restrict__ counters)
 {
     __shared__ double sx[4], sy[4];
     __shared__ uint32_t sc[4];
-    __shared__ uint32_t kwin[LEVEL_TILE + 2 * KEY_HALO];
-    const KeyWindow kw = key_window_fill(keys, (uint32_t)n, blockIdx.x * LEVEL_TILE, LEVEL_TILE, kwin);
-    __syncthreads();
+    __shared__ uint64_t kwin[LEVEL_TILE + 2 * KEY_HALO];
+    // the list of large cells (write_cells) and the work counters of the walk start at zero
+    if (blockIdx.x == 0 && threadIdx.x < 1 + WALK_COUNTERS) counters[threadIdx.x] = 0u;
+    const KeyWindow kw = key_window_fill(words, ks, (uint32_t)n, blockIdx.x * LEVEL_TILE, LEVEL_TILE, kwin);
     double ax = 0.0, ay = 0.0;
     uint32_t ac = 0;
     float2 y[LEVEL_ITEMS];
 #pragma unroll
     for (int k = 0; k < LEVEL_ITEMS; ++k) {
         const int p = blockIdx.x * LEVEL_TILE + k * LEVEL_THREADS + threadIdx.x;
-        y[k] = p < n ? Y[min(perm[p], (uint32_t)n - 1u)] : make_float2(0.f, 0.f);
+        y[k] = make_float2(0.f, 0.f);
+        if (p < n) {
+            const uint32_t slot = min((uint32_t)(words[p] & ((1ull << ks) - 1ull)), (uint32_t)n - 1u);
+            perm[p] = slot;
+            y[k] = Y[slot];
+        }
     }
+    __syncthreads();
 #pragma unroll
     for (int k = 0; k < LEVEL_ITEMS; ++k) {
         const int p = blockIdx.x * LEVEL_TILE + k * LEVEL_THREADS + threadIdx.x;
@@ -599,65 +675,32 @@ __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__r
     }
 }
 
-// One block: exclusive prefix over the tile partials; total cell count to *ncells.
-__global__ __launch_bounds__(1024) void scan_partials(ScanPart *__restrict__ part, int nparts,
-                                                      uint32_t *__restrict__ ncells, uint32_t cap_cells,
-                                                      uint32_t *status, uint32_t *__restrict__ big_count)
-{
-    if (threadIdx.x == 0) {
-        big_count[0] = 0u;    // list of large cells filled by write_cells
-    }
-    if (threadIdx.x < WALK_COUNTERS) big_count[1 + threadIdx.x] = 0u;    // work counters of the walk
-    __shared__ double wx[16], wy[16];
-    __shared__ uint32_t wc[16];
-    const int tid = threadIdx.x, w = tid >> 6;
-    const int per = (nparts + 1023) / 1024;
-    const int s = tid * per, e = min(nparts, s + per);
-    double ax = 0.0, ay = 0.0;
-    uint32_t ac = 0;
-    for (int i = s; i < e; ++i) { ax += part[i].sx; ay += part[i].sy; ac += part[i].cnt; }
-    // inclusive scan across the wave, then across the 16 waves
-    double ix = ax, iy = ay;
-    uint32_t icn = ac;
-#pragma unroll
-    for (int o = 1; o < WAVE; o <<= 1) {
-        double tx = __shfl_up(ix, o, WAVE), ty = __shfl_up(iy, o, WAVE);
-        uint32_t tc = __shfl_up(icn, o, WAVE);
-        if (lane_id() >= o) { ix += tx; iy += ty; icn += tc; }
-    }
-    if (lane_id() == WAVE - 1) { wx[w] = ix; wy[w] = iy; wc[w] = icn; }
-    __syncthreads();
-    double bx = 0.0, by = 0.0;
-    uint32_t bc = 0;
-    for (int k = 0; k < w; ++k) { bx += wx[k]; by += wy[k]; bc += wc[k]; }
-    double px = bx + (ix - ax), py = by + (iy - ay);   // exclusive prefix of this thread's first item
-    uint32_t pc = bc + (icn - ac);
-    for (int i = s; i < e; ++i) {
-        ScanPart q = part[i];
-        ScanPart o;
-        o.sx = px; o.sy = py; o.cnt = pc; o.pad = 0;
-        part[i] = o;
-        px += q.sx; py += q.sy; pc += q.cnt;
-    }
-    if (tid == 1023) {
-        // thread 1023 holds the grand total whether or not it owned items
-        *ncells = pc;
-        if (pc > cap_cells) atomicOr(status, TSNE_STATUS_CELL_OVERFLOW);
-    }
-}
-
 // Per position: index of the first cell opened there, and the running sums of the sorted
-// coordinates (ps[p] = sum of Ys[0..p), ps[n] = total).
+// coordinates (ps[p] = sum of Ys[0..p), ps[n] = total).  Every workgroup first adds up the tile
+// sums before its own tile (in a fixed order, so a run is reproducible; a few KB from the
+// second-level cache instead of one more kernel); the last one also knows the number of cells.
 __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restrict__ Ys,
                                                            const uint16_t *__restrict__ lev, int n,
                                                            const ScanPart *__restrict__ part,
                                                            uint32_t *__restrict__ cellseq, double2 *__restrict__ ps,
                                                            uint32_t *__restrict__ cell_p, uint8_t *__restrict__ cell_t,
-                                                           uint32_t cap_cells)
+                                                           uint32_t cap_cells, uint32_t *__restrict__ ncells,
+                                                           uint32_t *status)
 {
     __shared__ double wx[4], wy[4];
     __shared__ uint32_t wc[4];
+    __shared__ double bx[4], by[4];
+    __shared__ uint32_t bc[4];
     const int tid = threadIdx.x, w = tid >> 6;
+    // tiles before this one
+    double qx = 0.0, qy = 0.0;
+    uint32_t qc = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += LEVEL_THREADS) {
+        const ScanPart q = part[i];
+        qx += q.sx; qy += q.sy; qc += q.cnt;
+    }
+    qx = wave_sum(qx); qy = wave_sum(qy); qc = wave_sum(qc);
+    if (lane_id() == 0) { bx[w] = qx; by[w] = qy; bc[w] = qc; }
     int p0 = blockIdx.x * LEVEL_TILE + tid * LEVEL_ITEMS;
     float2 y[LEVEL_ITEMS];
     uint32_t c[LEVEL_ITEMS], t0[LEVEL_ITEMS];
@@ -684,9 +727,8 @@ __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restr
     }
     if (lane_id() == WAVE - 1) { wx[w] = ix; wy[w] = iy; wc[w] = icn; }
     __syncthreads();
-    ScanPart b = part[blockIdx.x];
-    double px = b.sx, py = b.sy;
-    uint32_t pc = b.cnt;
+    double px = ((bx[0] + bx[1]) + bx[2]) + bx[3], py = ((by[0] + by[1]) + by[2]) + by[3];
+    uint32_t pc = bc[0] + bc[1] + bc[2] + bc[3];
     for (int k = 0; k < w; ++k) { px += wx[k]; py += wy[k]; pc += wc[k]; }
     px += ix - ax; py += iy - ay; pc += icn - ac;
 #pragma unroll
@@ -698,7 +740,12 @@ __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restr
             for (uint32_t q = 0; q < c[k]; ++q)
                 if (pc + q < cap_cells) { cell_p[pc + q] = (uint32_t)p; cell_t[pc + q] = (uint8_t)(t0[k] + q); }
             px += (double)y[k].x; py += (double)y[k].y; pc += c[k];
-            if (p == n - 1) { cellseq[n] = pc; ps[n] = make_double2(px, py); }
+            if (p == n - 1) {
+                cellseq[n] = pc;
+                ps[n] = make_double2(px, py);
+                *ncells = pc;
+                if (pc > cap_cells) atomicOr(status, TSNE_STATUS_CELL_OVERFLOW);
+            }
         }
     }
 }
@@ -709,7 +756,7 @@ __device__ __forceinline__ uint32_t digit_lower_bound(const KeyWindow &keys, uin
 {
     while (s < e) {
         uint32_t mid = s + ((e - s) >> 1);
-        if (((keys[mid] >> sh) & 3u) < q) s = mid + 1; else e = mid;
+        if (((uint32_t)(keys[mid] >> sh) & 3u) < q) s = mid + 1; else e = mid;
     }
     return s;
 }
@@ -718,10 +765,10 @@ __device__ __forceinline__ uint32_t digit_lower_bound(const KeyWindow &keys, uin
 // non-decreasing positions and the keys they search sit in one short stretch, staged in LDS).
 // A cell whose run of positions ends inside that stretch is finished on the spot.  The few large
 // cells near the top of the tree would each be a chain of dozens of dependent memory reads in a
-// single lane; they are put on a list instead and finished by write_big_cells, four lanes per cell.
+// single lane; they are put on a list instead and finished by write_big_cells, one wave per search.
 constexpr int CELL_WINDOW = 4096;
 
-__global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ keys,
+__global__ __launch_bounds__(256) void write_cells(const uint64_t *__restrict__ words, int ks,
                                                    const uint32_t *__restrict__ cellseq,
                                                    const double2 *__restrict__ ps,
                                                    const uint32_t *__restrict__ cell_p, const uint8_t *__restrict__ cell_t,
@@ -730,24 +777,25 @@ __global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ 
                                                    uint32_t *__restrict__ big_count, uint2 *__restrict__ big_list,
                                                    uint32_t big_cap)
 {
-    __shared__ uint32_t kwin[CELL_WINDOW];
+    __shared__ uint64_t kwin[CELL_WINDOW];
     const uint32_t m = min(*ncells, cap_cells);
     for (uint32_t base = blockIdx.x * 256u; base < m; base += gridDim.x * 256u) {
         const uint32_t id = base + threadIdx.x;
         const bool live = id < m;
         const uint32_t p_first = cell_p[base], p_last = cell_p[min(base + 255u, m - 1u)];
         KeyWindow kw;
-        kw.keys = keys;
+        kw.words = words;
         kw.lds = kwin;
+        kw.ks = ks;
         kw.lo = p_first;
         kw.len = min(min((uint32_t)n, p_last + 1u + (uint32_t)KEY_HALO) - p_first, (uint32_t)CELL_WINDOW);
         __syncthreads();                    // previous round's readers are done with the window
-        for (uint32_t q = threadIdx.x; q < kw.len; q += 256u) kwin[q] = keys[p_first + q];
+        for (uint32_t q = threadIdx.x; q < kw.len; q += 256u) kwin[q] = words[p_first + q] >> ks;
         __syncthreads();
         if (!live) continue;
         const uint32_t p = cell_p[id];
         const int t = (int)cell_t[id];
-        const uint32_t key = kw[p];
+        const uint64_t key = kw[p];
         const uint32_t wend = kw.lo + kw.len;                  // one past the last position in the window
         if (p < wend && wend < (uint32_t)n &&
             (t == 0 || (kwin[kw.len - 1] >> (2 * (B - t))) == (key >> (2 * (B - t))))) {
@@ -772,10 +820,10 @@ __global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ 
             uint32_t kids[3];
             int nk = 0;
             uint32_t s = p;
-            const uint32_t qfirst = (key >> sh) & 3u;
+            const uint32_t qfirst = (uint32_t)(key >> sh) & 3u;
             for (uint32_t q = qfirst + 1; q < 4; ++q) {
                 const uint32_t b = digit_lower_bound(kw, s, e, sh, q);
-                if (b < e && ((kw[b] >> sh) & 3u) == q) kids[nk++] = cellseq[b];
+                if (b < e && ((uint32_t)(kw[b] >> sh) & 3u) == q) kids[nk++] = cellseq[b];
                 s = b;
             }
             if (nk > 0) c.c1 = kids[0];
@@ -786,13 +834,12 @@ __global__ __launch_bounds__(256) void write_cells(const uint32_t *__restrict__ 
     }
 }
 
-// First position x in [lo, n) with (keys[x] >> sh) >= target, n if none (keys sorted).
-// First position i in [lo, n) with (keys[i] >> sh) >= target (n if there is none), found by the
+// First position i in [lo, n) with (key[i] >> sh) >= target (n if there is none), found by the
 // whole wave: every round the 64 lanes probe 64 evenly spaced positions of the remaining range,
-// which shrinks 64-fold, so four rounds cover any n.  All lanes must call with the same
+// which shrinks 64-fold, so five rounds cover any n.  All lanes must call with the same
 // arguments; every probed index lies inside [lo, n) whatever the keys hold.
-__device__ __forceinline__ uint32_t wave_shifted_lower_bound(const uint32_t *__restrict__ keys, uint32_t lo, uint32_t n,
-                                                             int sh, uint64_t target)
+__device__ __forceinline__ uint32_t wave_shifted_lower_bound(const uint64_t *__restrict__ words, int ks, uint32_t lo,
+                                                             uint32_t n, int sh, uint64_t target)
 {
     uint32_t hi = n;
     const uint32_t lane = (uint32_t)lane_id();
@@ -800,7 +847,7 @@ __device__ __forceinline__ uint32_t wave_shifted_lower_bound(const uint32_t *__r
         const uint32_t step = (hi - lo + 63u) >> 6;
         const uint64_t probe = (uint64_t)lo + (uint64_t)(lane + 1u) * step - 1ull;
         bool below = false;
-        if (probe < (uint64_t)hi) below = (uint64_t)(keys[probe] >> sh) < target;
+        if (probe < (uint64_t)hi) below = ((words[probe] >> ks) >> sh) < target;
         const uint32_t c = (uint32_t)__popcll(__ballot(below));   // the keys are sorted: lanes 0..c-1
         const uint64_t top = (uint64_t)lo + (uint64_t)(c + 1u) * step - 1ull;
         lo += c * step;
@@ -812,7 +859,8 @@ __device__ __forceinline__ uint32_t wave_shifted_lower_bound(const uint32_t *__r
 // One workgroup per listed cell, one wave per search: wave 0 finds the end of the cell, waves
 // 1-3 the first position of quadrants 1-3 among its points (all four are lower bounds in the
 // globally sorted keys).
-__global__ __launch_bounds__(256) void write_big_cells(const uint32_t *__restrict__ keys, const uint16_t *__restrict__ lev,
+__global__ __launch_bounds__(256) void write_big_cells(const uint64_t *__restrict__ words, int ks,
+                                                       const uint16_t *__restrict__ lev,
                                                        const uint32_t *__restrict__ cellseq,
                                                        const double2 *__restrict__ ps, int n, int B, int C,
                                                        Cell *__restrict__ cells, uint32_t cap_cells,
@@ -826,17 +874,17 @@ __global__ __launch_bounds__(256) void write_big_cells(const uint32_t *__restric
         const uint2 it = big_list[item];
         const uint32_t p = min(it.x, (uint32_t)n - 1u);
         const int t = min((int)it.y, B);
-        const uint32_t key = keys[p];
+        const uint64_t key = words[p] >> ks;
         uint32_t found = (uint32_t)n;
         if (role == 0) {
             if (t > 0) {
                 const int sh = 2 * (B - t);
-                found = wave_shifted_lower_bound(keys, p, (uint32_t)n, sh, (uint64_t)(key >> sh) + 1ull);
+                found = wave_shifted_lower_bound(words, ks, p, (uint32_t)n, sh, (key >> sh) + 1ull);
             }
         } else if (t < B) {
             const int sh = 2 * (B - t - 1);
-            const uint64_t parent = t > 0 ? (uint64_t)(key >> (2 * (B - t))) : 0ull;
-            found = wave_shifted_lower_bound(keys, p, (uint32_t)n, sh, (parent << 2) + (uint64_t)role);
+            const uint64_t parent = t > 0 ? (key >> (2 * (B - t))) : 0ull;
+            found = wave_shifted_lower_bound(words, ks, p, (uint32_t)n, sh, (parent << 2) + (uint64_t)role);
         }
         if (lane_id() == 0) found_s[role] = found;
         __syncthreads();
@@ -858,7 +906,7 @@ __global__ __launch_bounds__(256) void write_big_cells(const uint32_t *__restric
                 c.c1 = c.c2 = c.c3 = TSNE_NONE;
                 if (!leaf) {
                     // quadrant q > first quadrant exists iff its first position precedes the next boundary
-                    const uint32_t qfirst = (key >> (2 * (B - t - 1))) & 3u;
+                    const uint32_t qfirst = (uint32_t)(key >> (2 * (B - t - 1))) & 3u;
                     const uint32_t bnd[5] = {p, b1, b2, b3, e};
                     uint32_t kids[3];
                     int nk = 0;
@@ -900,6 +948,27 @@ hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t
     return hipGetLastError();
 }
 
+// keys and spatial order in the caller's numbering
+__global__ __launch_bounds__(256) void export_order_k(const uint64_t *__restrict__ words, int ks,
+                                                      const uint32_t *__restrict__ orig, int n, uint64_t *__restrict__ keys_out,
+                                                      int32_t *__restrict__ perm_out)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    const uint64_t w = words[p];
+    const uint32_t o = orig[min((uint32_t)(w & ((1ull << ks) - 1ull)), (uint32_t)n - 1u)];
+    if (keys_out) keys_out[min(o, (uint32_t)n - 1u)] = w >> ks;
+    if (perm_out) perm_out[p] = (int32_t)o;
+}
+
+hipError_t launch_export_order(tsne_ctx *c, uint64_t *d_keys, int32_t *d_perm, hipStream_t s)
+{
+    const int n = c->p.n;
+    hipLaunchKernelGGL(export_order_k, dim3((n + 255) / 256), dim3(256), 0, s, c->words[c->sorted_buf], c->key_shift,
+                       c->orig[c->cur_state], n, d_keys, d_perm);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ host: enqueue the whole build
 static int bbox_blocks(int n)
 {
@@ -907,20 +976,32 @@ static int bbox_blocks(int n)
     return nb < BBOX_MAX_BLOCKS ? nb : BBOX_MAX_BLOCKS;
 }
 
-// Stable LSD radix sort of (keys[0], idx[0]) on the low nbits bits, 8 bits a pass.
-hipError_t launch_sort(tsne_ctx *c, int nbits, hipStream_t s)
+// Stable LSD radix sort of words[0] on bits [lo, lo + nbits), RADIX_BITS a pass.
+hipError_t launch_sort(tsne_ctx *c, int lo, int nbits, bool hist0, hipStream_t s)
 {
     const int n = c->p.n;
     const int nblk = (n + SORT_TILE - 1) / SORT_TILE;
+    const int grid = 8 * ((nblk + 7) / 8);       // scatter_tile() deals the tiles to the XCDs
     int cur = 0;
-    for (int shift = 0; shift < nbits; shift += 8) {
-        hipLaunchKernelGGL(radix_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, c->keys[cur], n, shift, c->hist, nblk);
-        hipLaunchKernelGGL(radix_scan, dim3(256), dim3(256), 0, s, c->hist, nblk, c->dtot);
-        hipLaunchKernelGGL(radix_scatter, dim3(nblk), dim3(SORT_THREADS), 0, s, c->keys[cur], c->idx[cur],
-                           c->keys[cur ^ 1], c->idx[cur ^ 1], n, shift, c->hist, c->dtot, nblk);
+    for (int plo = lo; plo < lo + nbits; plo += RADIX_BITS) {
+        const int width = lo + nbits - plo < RADIX_BITS ? lo + nbits - plo : RADIX_BITS;
+        const uint32_t mask = (1u << width) - 1u;
+        if (!(hist0 && plo == lo))
+            hipLaunchKernelGGL(radix_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, c->words[cur], n, plo, mask, c->hist);
+        hipLaunchKernelGGL(radix_scan, dim3(RADIX / SCAN_DIGITS), dim3(SCAN_DIGITS * SCAN_SEGS), 0, s, c->hist, nblk,
+                           c->dtot);
+        hipLaunchKernelGGL(radix_scatter, dim3(grid), dim3(SORT_THREADS), 0, s, c->words[cur], c->words[cur ^ 1], n, plo,
+                           mask, c->hist, c->dtot, nblk);
         cur ^= 1;
     }
     c->sorted_buf = cur;
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_perm(tsne_ctx *c, hipStream_t s)
+{
+    const int n = c->p.n;
+    hipLaunchKernelGGL(unpack_perm_k, dim3((n + 255) / 256), dim3(256), 0, s, c->words[c->sorted_buf], n, c->perm);
     return hipGetLastError();
 }
 
@@ -937,48 +1018,46 @@ hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s)
 // Step 1 second half, step 2a and step 4: root square, keys, spatial sort.
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
 {
-    const int n = c->p.n, B = c->p.morton_bits;
+    const int n = c->p.n, B = c->p.morton_bits, ks = c->key_shift;
     const float2 *Y = c->Yi;
-    const int nb = (n + 255) / 256;
     if (n <= SMALL_SORT_MAX) {
         int m = 512;
         while (m < n) m <<= 1;
-        const int cur = ((2 * B + 7) / 8) & 1;     // where the radix passes would have left the result
         hipLaunchKernelGGL(small_root_keys_sort<3>, dim3(1), dim3(m >> 3), small_sort_lds(m), s, Y, n, m, c->bbox_part,
-                           c->bbox_nparts, B, c->root, c->keys_orig, c->keys[cur], c->idx[cur], c->status);
-        c->sorted_buf = cur;
+                           c->bbox_nparts, B, ks, c->root, c->words[0], c->status);
+        c->sorted_buf = 0;
         return hipGetLastError();
     }
     hipLaunchKernelGGL(bbox_final, dim3(1), dim3(c->bbox_nparts > 1024 ? 1024 : 256), 0, s, c->bbox_part, c->bbox_nparts, B,
                        c->root, c->status);
-    hipLaunchKernelGGL(morton_encode, dim3(nb), dim3(256), 0, s, Y, n, c->root, B, c->keys_orig, c->keys[0],
-                       c->idx[0]);
-    return launch_sort(c, 2 * B, s);
+    const int nblk = (n + SORT_TILE - 1) / SORT_TILE;
+    const int width0 = 2 * B < RADIX_BITS ? 2 * B : RADIX_BITS;
+    hipLaunchKernelGGL(morton_encode_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, Y, n, c->root, B, ks, (1u << width0) - 1u,
+                       c->words[0], c->hist);
+    return launch_sort(c, ks, 2 * B, true, s);
 }
 
 // Steps 2b, 2c and 3: cells, counts, centres of mass from the sorted keys.
 hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s)
 {
-    const int n = c->p.n, B = c->p.morton_bits, C = c->p.leaf_cap;
+    const int n = c->p.n, B = c->p.morton_bits, C = c->p.leaf_cap, ks = c->key_shift;
     const float2 *Y = c->Yi;
     const int nb = (n + 255) / 256;
-    const int cur = c->sorted_buf;
+    const uint64_t *words = c->words[c->sorted_buf];
     int nl = (n + LEVEL_TILE - 1) / LEVEL_TILE;
     if (C == 8)
-        hipLaunchKernelGGL(gather_levels<8>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B,
-                           C, c->Ys, c->lev, c->part);
+        hipLaunchKernelGGL(gather_levels<8>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, words, ks, n, B, C, c->Ys, c->perm,
+                           c->lev, c->part, c->big_count);
     else
-        hipLaunchKernelGGL(gather_levels<0>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, c->keys[cur], c->idx[cur], n, B,
-                           C, c->Ys, c->lev, c->part);
-    hipLaunchKernelGGL(scan_partials, dim3(1), dim3(1024), 0, s, c->part, nl, c->ncells, (uint32_t)c->cap_cells,
-                       c->status, c->big_count);
+        hipLaunchKernelGGL(gather_levels<0>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, words, ks, n, B, C, c->Ys, c->perm,
+                           c->lev, c->part, c->big_count);
     hipLaunchKernelGGL(downsweep, dim3(nl), dim3(LEVEL_THREADS), 0, s, c->Ys, c->lev, n, c->part, c->cellseq, c->ps,
-                       c->cell_p, c->cell_t, (uint32_t)c->cap_cells);
+                       c->cell_p, c->cell_t, (uint32_t)c->cap_cells, c->ncells, c->status);
     // grid sized for n cells (a typical tree has about n / 3); the kernel strides if there are more
-    hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, c->keys[cur], c->cellseq, c->ps, c->cell_p, c->cell_t,
+    hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, words, ks, c->cellseq, c->ps, c->cell_p, c->cell_t,
                        c->ncells, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
                        (uint32_t)c->big_cap);
-    hipLaunchKernelGGL(write_big_cells, dim3(4096), dim3(256), 0, s, c->keys[cur], c->lev,
+    hipLaunchKernelGGL(write_big_cells, dim3(4096), dim3(256), 0, s, words, ks, c->lev,
                        c->cellseq, c->ps, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
                        (uint32_t)c->big_cap);
     return hipGetLastError();

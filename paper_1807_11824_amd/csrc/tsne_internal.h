@@ -27,9 +27,12 @@ struct ScanPart {
 };
 
 // Tiling constants that host and device must agree on.
-constexpr int SORT_THREADS = 256;
+constexpr int RADIX_BITS = 11;           // digit width of the radix sort
+constexpr int RADIX = 1 << RADIX_BITS;
+constexpr int SORT_THREADS = 512;
 constexpr int SORT_ITEMS = 8;
 constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
+constexpr int MAX_GRID_BITS = 24;        // a float has 24 significant bits
 constexpr int SMALL_SORT_MAX = 8192;  // up to here one workgroup finds root, keys and order in LDS
 constexpr int LEVEL_THREADS = 256;
 constexpr int LEVEL_ITEMS = 4;
@@ -94,8 +97,11 @@ struct tsne_ctx {
     float4 *root;        // x0, y0, W, S
     uint32_t *status;    // device status word
     uint32_t *ncells;    // device cell count
-    uint32_t *keys[2], *idx[2];
-    uint32_t *keys_orig; // keys in original order (kept for export)
+    // the sort works on one 64-bit word per point: (grid key << key_shift) | slot, key_shift = 64 - 2 morton_bits,
+    // so that the order of the words is the order by (key, slot) and no separate index array travels along
+    uint64_t *words[2];
+    int key_shift;
+    uint32_t *perm;      // spatial order: position p holds slot perm[p] (written with the sorted points)
     int32_t *arow;              // first row of each resident workgroup of the attraction kernel (+ end)
     int arow_valid;             // arow matches the current near part
     uint32_t *row_order; // order in which the attractive kernel visits the rows (an earlier spatial order)
@@ -116,7 +122,7 @@ struct tsne_ctx {
     float2 *R, *A;
     double *zpart, *Z;
     double *kl_part;
-    int sorted_buf;      // which of keys[]/idx[] holds the sorted result
+    int sorted_buf;      // which of words[] holds the sorted result
     // optional per-phase timing: 9 events per armed step
     hipEvent_t *tev;
     int t_cap, t_used;
@@ -146,11 +152,14 @@ hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, int write_user,
                          hipStream_t s);
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode);   // tiles_mode: 0 decide, 1 rows, 2 tiles
-hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in idx[sorted_buf]
-hipError_t launch_sort(tsne_ctx *c, int nbits, hipStream_t s);  // sorts keys[0]/idx[0]; result in [sorted_buf]
+hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in c->perm
+// stable sort of words[0] on bits [lo, lo + nbits); result in words[sorted_buf].  hist0: the digit counts of the
+// first pass are already in c->hist (left by the kernel that wrote the words)
+hipError_t launch_sort(tsne_ctx *c, int lo, int nbits, bool hist0, hipStream_t s);
+hipError_t launch_unpack_perm(tsne_ctx *c, hipStream_t s);   // c->perm = low 32 bits of words[sorted_buf] (the graph order's words)
 hipError_t launch_scatter2(const float2 *in, const uint32_t *orig, float2 *out, int n, hipStream_t s);
 hipError_t launch_gather2(const float2 *in, const uint32_t *orig, float2 *out, int n, hipStream_t s);
-hipError_t launch_export_order(tsne_ctx *c, uint32_t *d_keys, int32_t *d_perm, hipStream_t s);
+hipError_t launch_export_order(tsne_ctx *c, uint64_t *d_keys, int32_t *d_perm, hipStream_t s);
 hipError_t launch_fill_state(tsne_ctx *c, hipStream_t s);
 hipError_t launch_iota(uint32_t *a, int n, hipStream_t s);
 hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t *lo, int32_t *hi,

@@ -32,7 +32,7 @@
 #include <math.h>
 
 constexpr int WALK_STACK = 512;      // stack entries
-constexpr int WALK_SLACK = 48;       // head room for a depth-first descent (3 entries per level, 16 levels)
+constexpr int WALK_SLACK = 3 * MAX_GRID_BITS;   // head room for a depth-first descent (3 entries per level)
 constexpr int WALK_PEND = 128;       // pending list entries
 constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied by their own lane
 constexpr int WALK_CLIST = 96;       // accepted cells waiting for the drain (16 B each), >= 64
@@ -164,7 +164,7 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
         // cells as still leave WALK_SLACK entries free afterwards whatever they push; when not
         // even one cell fits that rule the wave takes the single top cell per round -- plain
         // depth-first search, which adds at most 3 entries per level below the popped cell
-        // (<= 45 for 16 levels) before it shrinks again.  So sp never passes WALK_STACK - 3.
+        // (<= 69 for 24 levels) before it shrinks again.  So sp never passes WALK_STACK - 3.
         const int room = WALK_STACK - WALK_SLACK - sp;
         const bool pressure = room < 3;
         const bool from_pending = room >= 4 && (np >= WAVE || sp == 0);
@@ -370,7 +370,7 @@ hipError_t launch_walk(tsne_ctx *c, hipStream_t s)
     const bool resident = c->p.walk_resident > 0 && ngroups > c->p.walk_resident * c->num_cu &&
                           c->p.walk_resident * c->num_cu >= WALK_COUNTERS;
     const int grid = resident ? c->p.walk_resident * c->num_cu / WALK_COUNTERS * WALK_COUNTERS : ngroups;
-    hipLaunchKernelGGL(bh_walk, dim3(grid), dim3(WAVE), 0, s, c->cells, c->Ys, c->idx[c->sorted_buf], n, c->root,
+    hipLaunchKernelGGL(bh_walk, dim3(grid), dim3(WAVE), 0, s, c->cells, c->Ys, c->perm, n, c->root,
                        theta2, c->ncells, (uint32_t)c->cap_cells, c->R, c->zpart, c->status,
                        resident ? c->walk_counter : (uint32_t *)nullptr);
     hipLaunchKernelGGL(z_final, dim3(1), dim3(1024), 0, s, c->zpart, ngroups, c->Z);

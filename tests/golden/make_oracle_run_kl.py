@@ -29,13 +29,15 @@ def run(name):
     P = oracle.build_P(X, cfg["perplexity"], cfg["k"])
     t_p = time.time() - t0
     Y0 = synth.y0(cfg["n"])
-    pr = oracle.RunParams.default()          # theta 0.5, leaf_cap 8, group 64, lr 200, exaggeration 12 x 250
+    # theta 0.5, leaf_cap 8, group 64, lr 200, exaggeration 12 x 250; grid depth: what the library takes for this n
+    bits = min(22, (64 - (cfg["n"] - 1).bit_length()) // 2)
+    pr = oracle.RunParams.default(bits=bits)
     t0 = time.time()
     Y, _, _ = oracle.run(Y0, P["row_ptr"], P["col"], P["val"], pr, 1000)
     t_run = time.time() - t0
     kl = oracle.kl(Y, P["row_ptr"], P["col"], P["val"])
     kl0 = oracle.kl(Y0.astype(np.float64), P["row_ptr"], P["col"], P["val"])
-    return dict(n=cfg["n"], d=cfg["d"], perplexity=cfg["perplexity"], k=cfg["k"], iterations=1000,
+    return dict(n=cfg["n"], d=cfg["d"], bits=bits, perplexity=cfg["perplexity"], k=cfg["k"], iterations=1000,
                 nnz=int(len(P["col"])), kl_start=kl0, kl_final=kl, seconds_build_P=t_p, seconds_run=t_run,
                 threads=oracle.threads())
 

@@ -2,6 +2,12 @@
 import numpy as np
 
 
+def grid_bits(n):
+    """Grid bits per axis the library takes by default for n points (include/tsne.h, morton_bits): the oracle's
+    tree takes the depth as a parameter, and a comparison has to build both trees to the same depth."""
+    return min(22, (64 - max(0, int(n) - 1).bit_length()) // 2)
+
+
 def rel_l2(a, b):
     a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))

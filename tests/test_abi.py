@@ -46,14 +46,14 @@ def test_host_side_validation(L):
     from paper_1807_11824_amd.binding import TsneParams
     p = TsneParams()
     assert L.tsne_default_params(C.byref(p), 1000) == 0
-    assert (p.n, p.morton_bits, p.leaf_cap, p.exaggeration_iters) == (1000, 16, 8, 250)
+    assert (p.n, p.morton_bits, p.leaf_cap, p.exaggeration_iters) == (1000, 22, 8, 250)
     assert abs(p.theta - 0.5) < 1e-7 and p.lr == 200.0 and p.exaggeration == 12.0
     b = C.c_size_t(0)
     assert L.tsne_workspace_bytes(C.byref(p), C.byref(b)) == 0 and b.value > 1000 * 100
     small = b.value
     p.n = 2000
     assert L.tsne_workspace_bytes(C.byref(p), C.byref(b)) == 0 and b.value > small
-    for field, bad in (("n", 0), ("theta", 0.8), ("theta", -0.1), ("theta", float("nan")), ("morton_bits", 17),
+    for field, bad in (("n", 0), ("theta", 0.8), ("theta", -0.1), ("theta", float("nan")), ("morton_bits", 25),
                        ("morton_bits", 0), ("leaf_cap", 0), ("lr", float("inf"))):
         q = TsneParams()
         L.tsne_default_params(C.byref(q), 1000)
@@ -62,6 +62,19 @@ def test_host_side_validation(L):
         ctx = C.c_void_p()
         assert L.tsne_create(C.byref(ctx), C.byref(q), None, C.c_void_p(256), 1 << 40) == -1
         assert not ctx.value
+    # the grid key and the point's number share a 64-bit word: 2 bits + ceil(log2 n) <= 64
+    q = TsneParams()
+    L.tsne_default_params(C.byref(q), 1281167)
+    assert q.morton_bits == 21 and L.tsne_workspace_bytes(C.byref(q), C.byref(b)) == 0
+    q.morton_bits = 22
+    assert L.tsne_workspace_bytes(C.byref(q), C.byref(b)) == -1
+    L.tsne_default_params(C.byref(q), 1 << 20)
+    assert q.morton_bits == 22
+    L.tsne_default_params(C.byref(q), 1 << 29)
+    assert q.morton_bits == 17 and L.tsne_workspace_bytes(C.byref(q), C.byref(b)) == 0
+    # the call for callers that cannot allocate refuses sizes beyond its limit before touching the GPU
+    assert L.tsne_kl_static(C.c_void_p(256), (1 << 22) + 1, C.c_void_p(256), None, None, C.c_void_p(256), None) == -1
+    assert L.tsne_kl_static(C.c_void_p(256), 0, C.c_void_p(256), None, None, C.c_void_p(256), None) == -1
     # null / misaligned / too small workspace
     q = TsneParams()
     L.tsne_default_params(C.byref(q), 1000)

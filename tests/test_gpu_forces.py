@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import random_symmetric_csr, rel_l2
+from helpers import grid_bits, random_symmetric_csr, rel_l2
 from paper_1807_11824_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -32,7 +32,8 @@ def _gpu_forces(Y, rp, col, val, **params):
 def _compare(Y, rp, col, val, theta, leaf_cap, alpha=12.0):
     A, R, Z, st = _gpu_forces(Y, rp, col, val, theta=theta, leaf_cap=leaf_cap)
     assert st == 0
-    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=theta, leaf_cap=leaf_cap, group=64, alpha=alpha)
+    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=theta, leaf_cap=leaf_cap, group=64, alpha=alpha,
+                       bits=grid_bits(Y.shape[0]))
     g = 4.0 * (alpha * A.astype(np.float64) - R.astype(np.float64) / Z)
     errs = dict(A=rel_l2(A, o["A"]), R=rel_l2(R, o["R"]), Z=abs(Z - o["Z"]) / o["Z"], grad=rel_l2(g, o["grad"]))
     print("parity", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
@@ -77,7 +78,7 @@ def test_small_and_ragged_sizes(n):
         rp = np.zeros(n + 1, np.int32); col = np.zeros(0, np.int32); val = np.zeros(0, np.float32)
     A, R, Z, st = _gpu_forces(Y, rp, col, val, theta=0.5, leaf_cap=8)
     assert st == 0
-    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=0.5, leaf_cap=8, group=64)
+    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=0.5, leaf_cap=8, group=64, bits=grid_bits(n))
     assert np.abs(A - o["A"]).max() <= 1e-6 * max(1e-30, np.abs(o["A"]).max())
     assert np.abs(R - o["R"]).max() <= 1e-5 * max(1e-30, np.abs(o["R"]).max())
     assert abs(Z - o["Z"]) <= 1e-5 * max(o["Z"], 1e-30)
@@ -146,7 +147,8 @@ def test_renumbering_changes_nothing_but_the_layout(far_tiles):
     a.close(); b.close()
 
 
-@pytest.mark.parametrize("leaf_cap,bits,theta", [(40, 16, 0.5), (3, 6, 0.5), (8, 16, 0.7), (16, 16, 0.3), (200, 16, 0.5)])
+@pytest.mark.parametrize("leaf_cap,bits,theta", [(40, 16, 0.5), (3, 6, 0.5), (8, 16, 0.7), (16, 16, 0.3), (200, 16, 0.5),
+                                                 (8, 24, 0.5), (2, 19, 0.6)])
 def test_other_tree_parameters(leaf_cap, bits, theta):
     """Large leaves (lane-serial leaf path), a coarse grid with crowded deepest cells, the largest theta."""
     import torch

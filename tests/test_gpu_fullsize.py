@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import rel_l2
+from helpers import grid_bits, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -62,16 +62,17 @@ def test_forces_in_bench_configuration(full):
     assert ts.status() == 0
     Yh = Y.cpu().numpy()
     o = oracle.grad_bh(Yh, P["row_ptr"].cpu().numpy(), P["col"].cpu().numpy(),
-                       P["val"].cpu().numpy().astype(np.float64), theta=0.5, leaf_cap=8, group=64, alpha=12.0)
+                       P["val"].cpu().numpy().astype(np.float64), theta=0.5, leaf_cap=8, group=64, alpha=12.0,
+                       bits=grid_bits(n))
     g = 4.0 * (12.0 * A.cpu().numpy().astype(np.float64) - R.cpu().numpy().astype(np.float64) / float(Z[0]))
     errs = dict(A=rel_l2(A.cpu().numpy(), o["A"]), R=rel_l2(R.cpu().numpy(), o["R"]),
                 Z=abs(float(Z[0]) - o["Z"]) / o["Z"], grad=rel_l2(g, o["grad"]))
     print("full-size parity", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     assert errs["grad"] <= 1e-4 and errs["A"] <= 1e-4 and errs["R"] <= 1e-4 and errs["Z"] <= 1e-5
     t = ts.export_tree()
-    want = oracle.tree(Yh, bits=16, leaf_cap=8)
+    want = oracle.tree(Yh, bits=grid_bits(n), leaf_cap=8)
     assert t["m"] == want["m"]
-    assert np.array_equal(t["keys"].cpu().numpy().view(np.uint32), want["keys"])
+    assert np.array_equal(t["keys"].cpu().numpy().view(np.uint64), want["keys"])
     assert np.array_equal(t["depth"].cpu().numpy(), want["depth"])
     assert np.array_equal(t["lo"].cpu().numpy(), want["lo"]) and np.array_equal(t["hi"].cpu().numpy(), want["hi"])
     # order of equal keys is the one thing renumbering may change: compare the key sequence, check a permutation

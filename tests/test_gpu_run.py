@@ -95,7 +95,7 @@ def test_step_equals_oracle_update():
     """One tsne_step from a known state against the oracle's gradient + update in double."""
     import torch
     from paper_1807_11824_amd import Tsne
-    from helpers import random_symmetric_csr, rel_l2
+    from helpers import grid_bits, random_symmetric_csr, rel_l2
     dev = torch.device("cuda:0")
     n = 3000
     rp, col, val = random_symmetric_csr(n, 15, seed=5)
@@ -109,7 +109,8 @@ def test_step_equals_oracle_update():
     Yd = torch.from_numpy(Y).to(dev)
     t.step(Yd, 300)                                   # past exaggeration: alpha = 1, momentum 0.8
     u1, g1 = t.get_state()
-    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=0.5, leaf_cap=8, group=64, alpha=1.0)
+    o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=0.5, leaf_cap=8, group=64, alpha=1.0,
+                       bits=grid_bits(Y.shape[0]))
     Yo, uo, go = Y.astype(np.float64), u0.astype(np.float64), g0.astype(np.float64)
     oracle.update(Yo, uo, go, o["grad"], momentum=0.8, lr=200.0)
     # gains switch on the sign of the gradient: compare where the gradient is not within rounding of 0

@@ -56,11 +56,14 @@ CASES = {
     "two": lambda r: np.array([[0, 0], [1, 3]], np.float32),
     "one": lambda r: np.array([[0.5, -2]], np.float32),
     "far_outlier": lambda r: np.vstack([r.random((64, 2)) * 1e-3, [[100.0, -50.0]]]).astype(np.float32),
+    # tight clumps far apart: only a grid finer than 2^16 cells per axis separates the members of a clump
+    "tiny_clumps": lambda r: (np.repeat(r.random((6, 2)) * 50.0, 40, axis=0)
+                              + 2e-4 * r.standard_normal((240, 2))).astype(np.float32),
 }
 
 
 @pytest.mark.parametrize("name", sorted(CASES))
-@pytest.mark.parametrize("bits,leaf_cap", [(16, 1), (16, 8), (5, 2), (1, 1)])
+@pytest.mark.parametrize("bits,leaf_cap", [(16, 1), (16, 8), (5, 2), (1, 1), (17, 2), (22, 4), (24, 1)])
 def test_tree_equals_geometric_construction(name, bits, leaf_cap):
     Y = CASES[name](np.random.default_rng(11))
     n = Y.shape[0]
@@ -124,3 +127,21 @@ def test_non_finite_is_rejected():
     Y[2, 1] = np.nan
     with pytest.raises(ValueError):
         oracle.morton(Y)
+
+
+def test_deep_grid_splits_what_16_levels_cannot():
+    """Clumps much smaller than 2^-16 of the extent: at 16 levels their members share deepest cells, at 22 they
+    are split down to the leaf size."""
+    rng = np.random.default_rng(2)
+    Y = (np.repeat(rng.random((30, 2)) * 40.0, 200, axis=0) + 1e-4 * rng.standard_normal((6000, 2))).astype(np.float32)
+    a = oracle.tree(Y, bits=16, leaf_cap=8)
+    b = oracle.tree(Y, bits=22, leaf_cap=8)
+    size_a = (a["hi"] - a["lo"])[a["leaf"] == 1]
+    size_b = (b["hi"] - b["lo"])[b["leaf"] == 1]
+    assert size_a.max() > 50 and size_b.max() <= 8
+    assert b["depth"].max() > 16
+    # the first 16 levels are the same tree: same cells above depth 16, same order of the points up to ties
+    top = a["depth"] < 16
+    topb = b["depth"] < 16
+    assert np.array_equal(a["lo"][top], b["lo"][topb]) and np.array_equal(a["hi"][top], b["hi"][topb])
+    assert np.array_equal(b["sorted_keys"] >> np.uint64(12), a["sorted_keys"])
