@@ -20,32 +20,28 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 STANDIN_D = 64                 # see workload_inputs()
 STANDIN_MEAN_SCALE = 2.0
-# HBM bytes per launch of the attraction kernel from the committed counter runs, keyed by (workload, nnz)
-MEASURED_TRAFFIC = {("cfg5", 176122426): 1.282e9}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "attract_cfg5_hbm_traffic.md")
 
 
 def workload_inputs(name):
     """Synthetic X for the named configuration (recipes in paper_1807_11824_amd/synth.py).
 
-    cfg5 is the headline N = 1,281,167.  Its P is built by tsne_build_P from a 1000-cluster
-    ReLU-Gaussian mixture drawn in D' = 64 dimensions instead of 2048: drawing 10.5 GB on the host
-    and the exact brute-force kNN at D = 2048 take three quarters of a minute ("cfg5_nominal" runs
-    exactly that), while the per-iteration step only sees P.  At D = 2048 the between-cluster squared distances exceed the within-cluster
-    ones by many standard deviations, so every point's neighbours lie in its own cluster; at
-    D' = 64 the same is obtained by drawing the cluster means with scale 2 instead of 1.
+    cfg5 is the headline configuration as stated: N = 1,281,167, D = 2048 (10.5 GB of X, about 20 s to draw on
+    the host and 25 s for the exact tsne_build_P).  cfg5_standin is a quick substitute for kernel work: the same
+    1000-cluster ReLU-Gaussian mixture drawn in D' = 64 dimensions with the cluster means at scale 2, which gives
+    the same neighbourhood structure (every point's neighbours lie in its own cluster) in a second; it is never
+    what the default run reports.
     """
     from paper_1807_11824_amd import synth
-    if name == "cfg5_nominal":
-        # the recipe as stated, D = 2048: 10.5 GB of X, about 20 s to draw on the host and 25 s for the exact
-        # tsne_build_P; not the default because of that, the iterations only see P
+    if name == "cfg5_standin":
         c = dict(synth.CONFIGS["cfg5"])
-        X, _ = synth.config5()
-        c["d_used"] = c["d"]
+        X, _ = synth.gaussian_mixture(c["n"], STANDIN_D, 1000, STANDIN_MEAN_SCALE, 1.0, seed=0, relu=True)
+        c["d_used"] = STANDIN_D
         return X, c
     c = dict(synth.CONFIGS[name])
     if name == "cfg5":
-        X, _ = synth.gaussian_mixture(c["n"], STANDIN_D, 1000, STANDIN_MEAN_SCALE, 1.0, seed=0, relu=True)
-        c["d_used"] = STANDIN_D
+        X, _ = synth.config5()
+        c["d_used"] = c["d"]
     elif name == "cfg4":
         X, _ = synth.config4()
         c["d_used"] = c["d"]
@@ -61,17 +57,41 @@ def workload_inputs(name):
     return X, c
 
 
-def cpu_baseline(Y0, P_host, seconds_hint=20.0):
-    """The CPU oracle as it stands, timed on this host for a few iterations of the same workload."""
+def cpu_baseline(Y0, P_host, bits, X=None, cfg=None, P_gpu_seconds=None):
+    """The CPU oracle as it stands, timed on this host: a few whole iterations of the same workload, and the
+    construction of P (kNN in double precision, Eq. (1)) on a sample of rows, extrapolated to all rows."""
     import oracle
-    pr = oracle.RunParams.default()
+    pr = oracle.RunParams.default(bits=bits)
     n = Y0.shape[0]
     iters = 3 if n > 200_000 else 10
     t0 = time.time()
     oracle.run(Y0, P_host["row_ptr"], P_host["col"], P_host["val"], pr, iters)
     dt = time.time() - t0
-    return dict(value=iters / dt, unit="iterations/s", cores=oracle.threads(), kind="oracle",
-                sample=f"{iters} full iterations (tree + walk + attraction + update) of the same N={n} workload from Y0")
+    out = dict(value=iters / dt, unit="iterations/s", cores=oracle.threads(), kind="oracle",
+               sample=f"{iters} full iterations (tree + walk + attraction + update) of the same N={n} workload from Y0")
+    if X is not None:
+        # neighbour search and Eq. (1) for a sample of query rows against all n rows; the symmetric CSR (a sort of
+        # all n k entries) is not sampled
+        k, perp = cfg["k"], cfg["perplexity"]
+        rng = np.random.default_rng(0)
+        probe = np.sort(rng.choice(n, 16, replace=False)).astype(np.int32)
+        t0 = time.time()
+        oracle.knn(X, k, rows=probe)
+        t16 = time.time() - t0
+        rows = int(min(256, max(16, 12.0 / max(t16 / 16, 1e-9))))      # about 12 s of work
+        sample = np.sort(rng.choice(n, rows, replace=False)).astype(np.int32)
+        t0 = time.time()
+        _, d2 = oracle.knn(X, k, rows=sample)
+        t_knn = time.time() - t0
+        t0 = time.time()
+        oracle.cond_p(d2, perp)
+        t_cond = time.time() - t0
+        est = (t_knn + t_cond) / rows * n
+        out["build_P"] = dict(rows_sampled=rows, knn_s=t_knn, cond_p_s=t_cond, extrapolated_s_all_rows=est,
+                              note="oracle kNN (sequential double-precision sums) + Eq. (1) on the sampled rows against "
+                                   "all rows, scaled by n / rows; symmetrisation not included",
+                              gpu_build_P_s=P_gpu_seconds)
+    return out
 
 
 def sweep(dev, overlap, sizes, n_iter, reorder_every, approx_tau=0):
@@ -117,15 +137,41 @@ def sweep(dev, overlap, sizes, n_iter, reorder_every, approx_tau=0):
         del P, Yd
 
 
+def step_bytes(n, m_cells, near, far, radix_passes):
+    """Bytes one iteration has to move, kernel by kernel as implemented (N points, M tree cells; every array
+    counted once per kernel that streams it, gathers that stay in cache not counted)."""
+    b = {}
+    b["sort"] = (8 + 8) * n + 8 * n * (radix_passes - 1) + 16 * n * radix_passes    # words written, digit counts, passes
+    b["cells"] = (8 + 8 + 8 + 4 + 2) * n + (8 + 2 + 4 + 16) * n + 5 * m_cells + 8 * n + (5 + 32 + 32) * m_cells
+    b["walk"] = (8 + 8 + 4) * n + 32 * m_cells
+    b["attract"] = 6 * near + 8 * far + (4 + 4 + 8 + 8) * n
+    b["update"] = 64 * n
+    return b
+
+
+def traffic_from_profile(nnz):
+    """HBM bytes per step of the attraction kernels as counted by rocprofv3 (profiles/attract_cfg5_hbm_traffic.md
+    holds a line 'TRAFFIC nnz=<entries of P> bytes=<bytes per step>'); None if no line matches this P."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            f = line.split()
+            if len(f) >= 3 and f[0] == "TRAFFIC" and f[1] == f"nnz={nnz}":
+                return float(f[2].split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--workload", default="cfg5", help="cfg5 (as stated, D = 2048) | cfg5_standin | cfg4 | cfg3 | cfg2 | cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--overlap", type=int, default=2)
+    ap.add_argument("--overlap", type=int, default=1)
     ap.add_argument("--leaf-cap", type=int, default=8)
+    ap.add_argument("--no-full-run", action="store_true", help="skip the separate 1000-iteration run (profiling)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark: the paper's synthetic scaling workload (50-d, 4 Gaussian clusters, "
                          "Sec. IV-B) at N = 500 ... 5M, one JSON line per N")
@@ -191,26 +237,30 @@ def main():
         del src, dst
 
     Y0 = synth.y0(n)
-    Yd = torch.from_numpy(Y0).to(dev)
+    Y0d = torch.from_numpy(Y0).to(dev)
     ts = Tsne(n, overlap=args.overlap, leaf_cap=args.leaf_cap, max_nnz=nnz)
+    bits = ts.params.morton_bits
     torch.cuda.synchronize()
     t0 = time.time()
     ts.set_P(P["row_ptr"], P["col"], P["val"])      # renumbers the points and lays the private copy of P out
     torch.cuda.synchronize()
     t_setp = time.time() - t0
-    # one tsne_run call per region: inside a run the library keeps the embedding in its own order
-    # from one iteration to the next (the caller's Y is still written every iteration)
-    it = 0
+    near, far = ts.P_layout()
+
+    # Warm-up: W steps on a scratch copy of Y0, then the optimiser state is reset, so that the timed region is
+    # iterations 0 .. K-1 of a real run from Y0 (the state of the embedding decides what an iteration costs).
     if args.warmup:
-        ts.run(Yd, args.warmup, iter0=it)
-        it += args.warmup
+        scratch = Y0d.clone()
+        ts.run(scratch, args.warmup)
+        ts.init_state()
+        del scratch
+    Yd = Y0d.clone()
     torch.cuda.synchronize()
-    # every 16th step carries the HIP events of the phase timing (they cost about 30 us per timed step)
+    # every 16th step carries the HIP events of the phase timing (nine event records cost about 30 us)
     every = 16 if args.steps >= 64 else 1
     ts.timing_begin((args.steps + every - 1) // every, every)
     t0 = time.time()
-    ts.run(Yd, args.steps, iter0=it)
-    it += args.steps
+    ts.run(Yd, args.steps)
     torch.cuda.synchronize()
     dt = time.time() - t0
     tm = ts.timing_end()
@@ -219,18 +269,47 @@ def main():
         print(f"bench.py: device status 0x{status:x}", file=sys.stderr)
         sys.exit(1)
     ms_step = dt / args.steps * 1e3
+    m_cells = ts.n_cells()
 
-    # roofline of the dominant HBM kernel: the attraction streams P once (algorithmically col + val,
-    # 8 B per entry, plus row_ptr), reads Y once and writes A once.  In the timed region it shares the
-    # compute units with the walk (overlap), which stretches its launches; the same kernels are
-    # timed once more on their own below (30 serial steps) and reported as "standalone".
-    attract_bytes = 8.0 * nnz + 4.0 * (n + 1) + 8.0 * n + 8.0 * n
+    # A whole run of 1000 iterations from Y0 (no timing events), in chunks of 50 iterations with a host
+    # synchronisation between them: what an iteration costs at the start, while the clusters are exaggerated
+    # (iteration 100), late (iteration 900), and on average; end to end = build_P + set_P + this run.
+    full = None
+    if not args.no_full_run:
+        ts.init_state()
+        Yr = Y0d.clone()
+        torch.cuda.synchronize()
+        chunk_ms = []
+        t_run0 = time.time()
+        for c0 in range(0, 1000, 50):
+            t0 = time.time()
+            ts.run(Yr, 50, iter0=c0)
+            torch.cuda.synchronize()
+            chunk_ms.append((time.time() - t0) / 50 * 1e3)
+        t_run = time.time() - t_run0
+        st = ts.status()
+        full = {"iterations": 1000, "run_s": t_run, "status": st,
+                "iterations_per_s_at_Y0": 1e3 / chunk_ms[0], "iterations_per_s_at_iter_100": 1e3 / chunk_ms[2],
+                "iterations_per_s_at_iter_900": 1e3 / chunk_ms[18], "iterations_per_s_whole_run": 1000.0 / t_run,
+                "ms_per_iteration_by_chunk_of_50": [round(v, 4) for v in chunk_ms],
+                "cells_at_end": ts.n_cells(),
+                "end_to_end_s": t_build + t_setp + t_run}
+        del Yr
+
+    # roofline of the dominant HBM kernels: the attraction streams its private copy of P once (6 bytes per stored
+    # entry of the near part, rows padded to 32 entries; 8 bytes per far entry), reads Y once and writes A once.
+    # In the timed region it shares the compute units with the walk (overlap), which stretches its launches; the
+    # same kernels are timed once more on their own below (30 serial steps) and reported as "standalone".
+    radix_passes = (2 * bits + 10) // 11
+    sb = step_bytes(n, m_cells, near, far, radix_passes)
+    attract_bytes = float(sb["attract"])
+    csr_bytes = 8.0 * nnz + 4.0 * (n + 1) + 8.0 * n + 8.0 * n
     phases = dict(tree=tm["tree_ms"], walk=tm["walk_ms"], attract=tm["attract_ms"], update=tm["update_ms"])
     achieved = attract_bytes / (tm["attract_ms"] * 1e-3) / 1e9 if tm["attract_ms"] > 0 else 0.0
-    step_bytes = attract_bytes + 8.0 * n + 100.0 * n + 60.0 * n + 40.0 * n + 80.0 * n + 64.0 * n
+    total_bytes = float(sum(sb.values()))
     solo = Tsne(n, overlap=0, walk_resident=0, leaf_cap=args.leaf_cap, max_nnz=nnz)
     solo.set_P(P["row_ptr"], P["col"], P["val"])
-    Ys = torch.from_numpy(Y0).to(dev)
+    Ys = Y0d.clone()
     for i in range(5):
         solo.step(Ys, i)
     solo.timing_begin(30)
@@ -240,38 +319,51 @@ def main():
     solo.close()
     del Ys
     solo_achieved = attract_bytes / (tms["attract_ms"] * 1e-3) / 1e9 if tms["attract_ms"] > 0 else 0.0
+    headline = args.workload == "cfg5"
     out = {
-        "metric": "BH t-SNE gradient iterations/sec at N=1.28M" if args.workload in ("cfg5", "cfg5_nominal")
+        "metric": "BH t-SNE gradient iterations/sec at N=1.28M" if headline
                   else f"BH t-SNE gradient iterations/sec ({args.workload})",
         "value": args.steps / dt, "unit": "iterations/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: N={n}, k={k}, perplexity={perp}, theta=0.5, "
-                               f"P built by tsne_build_P from the D={cfg['d_used']} draw of the recipe "
-                               f"(nominal D={cfg['d']}), nnz={nnz}, steps from Y0 with exaggeration 12 for 250",
-                   "n": n, "nnz": nnz, "leaf_cap": args.leaf_cap, "overlap": args.overlap},
+        "config": {"workload": f"{args.workload}: N={n}, D={cfg['d_used']}, k={k}, perplexity={perp}, theta=0.5, "
+                               f"P built by tsne_build_P (exact kNN), nnz={nnz}; timed steps = iterations 0..{args.steps - 1} "
+                               f"of a run from Y0 (exaggeration 12 for the first 250)"
+                               + ("" if args.workload != "cfg5_standin" else
+                                  f" -- STAND-IN: X drawn at D'={STANDIN_D}, not the stated D={cfg['d']}"),
+                   "n": n, "d": cfg["d_used"], "nnz": nnz, "leaf_cap": args.leaf_cap, "morton_bits": bits,
+                   "overlap": args.overlap, "cells": m_cells},
         "phases_ms": phases,
         "build_P_s": t_build,
         "set_P_s": t_setp,
-        "end_to_end_s_1000_iters": t_build + t_setp + ms_step,
-        "step_algorithmic_GB": step_bytes / 1e9,
-        "step_hbm_frac": step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"kernel": "attract_near (+ attract_far)", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "step_bytes": {k_: round(v / 1e6, 2) for k_, v in sb.items()},
+        "step_bytes_total_GB": total_bytes / 1e9,
+        "step_hbm_frac": total_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"kernel": "attract_near + attract_far", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     # measured with rocprofv3 FETCH_SIZE / WRITE_SIZE on this workload, scaled by a 1 GiB copy
-                     # (profiles/attract_cfg5_hbm_traffic.md); bytes per step, both kernels
-                     "traffic": MEASURED_TRAFFIC.get((args.workload, nnz)),
+                     # what rocprofv3's FETCH_SIZE / WRITE_SIZE counted for these kernels on this P, scaled by a
+                     # 1 GiB copy (profiles/attract_cfg5_hbm_traffic.md); bytes per step, both kernels
+                     "traffic": traffic_from_profile(nnz),
+                     "bytes_per_launch": attract_bytes,
+                     "bytes_note": "6 B per stored near entry (rows padded to 32) + 8 B per far entry + 24 B per point; "
+                                   "a plain CSR of the same P would be csr_bytes",
+                     "csr_bytes": csr_bytes,
                      "standalone": {"ms": tms["attract_ms"], "achieved": solo_achieved,
                                     "frac": solo_achieved / HBM_PEAK_GBS, "walk_ms": tms["walk_ms"],
                                     "tree_ms": tms["tree_ms"], "update_ms": tms["update_ms"]}},
     }
-    out["end_to_end_s_1000_iters"] = t_build + t_setp + ms_step  # ms/step * 1000 steps / 1000 ms
+    if full is not None:
+        out["run_1000"] = full
+        out["end_to_end_s"] = full["end_to_end_s"]
+        out["step_hbm_frac_whole_run"] = total_bytes / (full["run_s"] / 1000.0) / 1e9 / HBM_PEAK_GBS
     if approx is not None:
         out["approx_P"] = approx
+        if full is not None and "build_P_approx_s" in approx:
+            out["end_to_end_s_approx_P"] = approx["build_P_approx_s"] + t_setp + full["run_s"]
     if not args.no_cpu_baseline:
         P_host = dict(row_ptr=P["row_ptr"].cpu().numpy(), col=P["col"].cpu().numpy(),
                       val=P["val"].cpu().numpy().astype(np.float64))
-        out["cpu_baseline"] = cpu_baseline(Y0, P_host)
+        out["cpu_baseline"] = cpu_baseline(Y0, P_host, bits, X=X, cfg=cfg, P_gpu_seconds=t_build)
     print(json.dumps(out))
 
 

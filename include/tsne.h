@@ -198,6 +198,12 @@ int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity
  * far_tiles = 0 or 2 the call waits for the stream (it reads back which kernel will take the far part). */
 int tsne_set_P(tsne_ctx *ctx, const int32_t *d_row_ptr, const int32_t *d_col, const float *d_val, int64_t nnz);
 
+/* How the context holds P after tsne_set_P, for byte accounting: with renumbering on, *near_entries is the
+ * number of stored entries of the part near the diagonal (rows padded to multiples of 32 entries; 6 bytes each:
+ * a float and a 16-bit column) and *far_entries that of the rest (8 bytes each); without renumbering
+ * *near_entries = 0 and *far_entries = nnz (the caller's CSR, 8 bytes each).  Synchronises. */
+int tsne_P_layout(tsne_ctx *ctx, int64_t *near_entries, int64_t *far_entries);
+
 /* Resets the optimiser state: velocity = 0, gains = 1 (enqueued). */
 int tsne_init_state(tsne_ctx *ctx);
 

@@ -61,6 +61,7 @@ def lib():
         "tsne_build_P_approx": (C.c_int, [vp, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, i64, C.POINTER(i64), vp, vp,
                                           C.POINTER(i32), C.POINTER(i32), vp, C.c_size_t, vp]),
         "tsne_set_P": (C.c_int, [vp, vp, vp, vp, i64]),
+        "tsne_P_layout": (C.c_int, [vp, C.POINTER(i64), C.POINTER(i64)]),
         "tsne_init_state": (C.c_int, [vp]),
         "tsne_get_state": (C.c_int, [vp, vp, vp]),
         "tsne_set_state": (C.c_int, [vp, vp, vp]),
@@ -269,6 +270,11 @@ class Tsne:
         self._P = (row_ptr, col, val)            # keep the borrowed arrays alive
         self._check(self.L.tsne_set_P(self._ctx, _ptr(row_ptr), _ptr(col), _ptr(val), col.numel()), "tsne_set_P")
 
+    def P_layout(self):
+        near, far = C.c_int64(0), C.c_int64(0)
+        self._check(self.L.tsne_P_layout(self._ctx, C.byref(near), C.byref(far)), "tsne_P_layout")
+        return near.value, far.value
+
     def init_state(self):
         self._check(self.L.tsne_init_state(self._ctx), "tsne_init_state")
 
@@ -317,6 +323,13 @@ class Tsne:
         m = m.value
         return dict(keys=keys, perm=perm, m=m, depth=depth[:m], lo=lo[:m], hi=hi[:m], leaf=leaf[:m], com=com[:m],
                     root=root)
+
+    def n_cells(self):
+        """Cell count of the last tree (tsne_export_tree with no arrays)."""
+        m = C.c_int32(0)
+        self._check(self.L.tsne_export_tree(self._ctx, None, None, 0, None, None, None, None, None, None, C.byref(m)),
+                    "tsne_export_tree")
+        return m.value
 
     def kl(self, Y):
         _dev(Y, torch.float32, "Y")

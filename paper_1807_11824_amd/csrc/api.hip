@@ -378,6 +378,26 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     return TSNE_OK;
 }
 
+int tsne_P_layout(tsne_ctx *c, int64_t *near_entries, int64_t *far_entries)
+{
+    if (!c) return TSNE_EINVAL;
+    if (!c->have_P) return fail(c, TSNE_ESTATE, "tsne_P_layout: no P");
+    int64_t near = 0, far = c->nnz;
+    if (c->reorder_on && !c->identity) {
+        int32_t a = 0, b0 = 0, b1 = 0;
+        hipError_t e = hipMemcpyAsync(&a, c->rp_near + c->p.n, 4, hipMemcpyDeviceToHost, c->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(&b0, c->rp_far, 4, hipMemcpyDeviceToHost, c->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(&b1, c->rp_far + c->p.n, 4, hipMemcpyDeviceToHost, c->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+        if (e != hipSuccess) return fail_hip(c, e, "P layout");
+        near = a;
+        far = (int64_t)b1 - b0;
+    }
+    if (near_entries) *near_entries = near;
+    if (far_entries) *far_entries = far;
+    return TSNE_OK;
+}
+
 int tsne_init_state(tsne_ctx *c)
 {
     if (!c) return TSNE_EINVAL;
