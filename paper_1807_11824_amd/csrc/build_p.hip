@@ -58,13 +58,45 @@ __device__ __forceinline__ uint64_t orderable64(double d)
     return (u & 0x8000000000000000ull) ? ~u : (u | 0x8000000000000000ull);
 }
 
-__global__ __launch_bounds__(256) void row_norms(const float *__restrict__ X, int n, int d, float *__restrict__ norms)
+// Squared distances do not change when every row is moved by the same vector, while the error of
+// the candidate search grows with the rows' norms: the search therefore works on X - mu, mu the
+// column means (only the split copy and the norms are centred; the re-rank reads the caller's X).
+// Any mu gives correct lists; this one is computed in a fixed order so that a build is reproducible.
+constexpr int MEAN_CHUNKS = 256;     // row chunks of the first stage
+__global__ __launch_bounds__(256) void col_mean_part(const float *__restrict__ X, int n, int d, int rows_per_chunk,
+                                                     double *__restrict__ part)
+{
+    __shared__ double acc[4][64];
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63), rg = threadIdx.x >> 6;
+    const int r0 = blockIdx.y * rows_per_chunk, r1 = min(n, r0 + rows_per_chunk);
+    double s = 0.0;
+    if (c < d)
+        for (int r = r0 + rg; r < r1; r += 4) s += (double)X[(size_t)r * d + c];
+    acc[rg][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (rg == 0 && c < d) part[(size_t)blockIdx.y * d + c] = ((acc[0][threadIdx.x] + acc[1][threadIdx.x]) + acc[2][threadIdx.x]) + acc[3][threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void col_mean_final(const double *__restrict__ part, int nchunks, int n, int d, int dp,
+                                                      float *__restrict__ mu)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= dp) return;
+    double s = 0.0;
+    if (c < d)
+        for (int q = 0; q < nchunks; ++q) s += part[(size_t)q * d + c];
+    mu[c] = c < d ? (float)(s / (double)n) : 0.f;
+}
+
+// |x - mu|^2 of the centred row as the tiles see it (each x_t - mu_t rounded to float)
+__global__ __launch_bounds__(256) void row_norms(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
+                                                 float *__restrict__ norms)
 {
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= n) return;
     const float *x = X + (size_t)row * d;
     double s = 0.0;
-    for (int t = lane_id(); t < d; t += WAVE) { double v = (double)x[t]; s += v * v; }
+    for (int t = lane_id(); t < d; t += WAVE) { double v = (double)(x[t] - mu[t]); s += v * v; }
     s = wave_sum(s);
     if (lane_id() == 0) norms[row] = (float)s;
 }
@@ -99,14 +131,14 @@ __device__ __forceinline__ uint32_t bf16_rne(float x)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-__global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, int n, int d, int dp,
-                                                  uint16_t *__restrict__ Xs)
+__global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
+                                                  int dp, uint16_t *__restrict__ Xs)
 {
     const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (size_t)n * dp) return;
     const size_t row = e / dp;
     const int k = (int)(e % dp);
-    const float x = k < d ? X[row * d + k] : 0.f;
+    const float x = k < d ? X[row * d + k] - mu[k] : 0.f;
     const uint32_t hi = bf16_rne(x);
     const uint32_t lo = bf16_rne(x - __uint_as_float(hi << 16));      // the difference is exact in fp32
     uint16_t *o = Xs + row * dp * 2 + (size_t)(k / SLAB) * (2 * SLAB) + (k % SLAB);
@@ -122,8 +154,10 @@ __global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, i
 //     times the sum of |terms| <= (1 + 2^-8)^2 sum |q_t x_t|;
 //   sum |q_t x_t| <= (|q|^2 + |x|^2) / 2, and the distance takes -2 times the dot product;
 //   norms (each a rounded double sum), their sum and the final fused multiply-add: 8 more roundings
-//   of quantities below 2 (|q|^2 + |x|^2).
-// 5 % on top for the norms themselves being rounded values.
+//   of quantities below 2 (|q|^2 + |x|^2);
+//   centring: q' = fl(q - mu), x' = fl(x - mu) are off by 2^-24 relative per coordinate, which moves
+//   |q' - x'|^2 by at most 2 |q - x| 2^-24 (|q'| + |x'|) <= 4 2^-24 (|q'|^2 + |x'|^2) (and a second-order term).
+// 5 % on top for the norms themselves being rounded values.  q, x here are the centred rows.
 __host__ __device__ inline double tile_error_coeff(int d, bool two_level)
 {
     const int dp = (d + SLAB - 1) / SLAB * SLAB;
@@ -131,7 +165,7 @@ __host__ __device__ inline double tile_error_coeff(int d, bool two_level)
     const double u = 1.1920928955078125e-07;   // 2^-23
     const double split = 3.0 * (1.0 + 3.814697265625e-06) * 3.814697265625e-06;
     const double accum = 1.0079 * R * u / (1.0 - R * u);
-    return 1.05 * (split + accum + 16.0 * 5.9604644775390625e-08);
+    return 1.05 * (split + accum + (16.0 + 4.2) * 5.9604644775390625e-08);
 }
 
 // A wave's queue of accepted pairs lives in LDS.
@@ -691,16 +725,37 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
 }
 
 // ---- rows that failed the certificate: exact distances to every row, then selection
-__global__ __launch_bounds__(256) void knn_exact_dists(const float *__restrict__ X, int n, int d, int i,
-                                                       uint64_t *__restrict__ okey)
+// A batch of `nb` failed rows rows[0..nb) at a time: okey[f * n + j] = ordered key of the exact distance
+// between rows[f] and j.  A wave holds one database row in registers and meets every failed row
+// (which come from the second-level cache), so X is read from memory once per batch.
+constexpr int EXACT_MAX_D = 4096;
+__global__ __launch_bounds__(256) void knn_exact_dists(const float *__restrict__ X, int n, int d,
+                                                       const int *__restrict__ rows, int nb, uint64_t *__restrict__ okey)
 {
     const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (j >= n) return;
-    const float *x = X + (size_t)i * d, *y = X + (size_t)j * d;
-    double s = 0.0;
-    for (int t = lane_id(); t < d; t += WAVE) { double df = (double)x[t] - (double)y[t]; s += df * df; }
-    s = wave_sum(s);
-    if (lane_id() == 0) okey[j] = (j == i) ? ~0ull : orderable64(s);
+    const float *y = X + (size_t)j * d;
+    float yr[EXACT_MAX_D / WAVE];
+#pragma unroll
+    for (int q = 0; q < EXACT_MAX_D / WAVE; ++q) {
+        const int t = q * WAVE + lane_id();
+        yr[q] = (q * WAVE < d && t < d) ? y[t] : 0.f;
+    }
+    for (int f = 0; f < nb; ++f) {
+        const int i = min(max(rows[f], 0), n - 1);
+        const float *x = X + (size_t)i * d;
+        double s = 0.0;
+#pragma unroll
+        for (int q = 0; q < EXACT_MAX_D / WAVE; ++q) {
+            if (q * WAVE < d) {
+                const int t = q * WAVE + lane_id();
+                const double df = t < d ? (double)x[t] - (double)yr[q] : 0.0;
+                s += df * df;
+            }
+        }
+        s = wave_sum(s);
+        if (lane_id() == 0) okey[(size_t)f * n + j] = (j == i) ? ~0ull : orderable64(s);
+    }
 }
 
 // One block: 8 radix passes over the ordered 64-bit keys find the k-th smallest distance; then
@@ -713,9 +768,13 @@ __device__ __forceinline__ double key_to_double(uint64_t v)
     return __longlong_as_double((long long)u);
 }
 
-__global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restrict__ okey, int n, int k, int i,
+// One workgroup per failed row of the batch.
+__global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restrict__ okey_all, int n, int k,
+                                                         const int *__restrict__ rows,
                                                          int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2)
 {
+    const uint64_t *okey = okey_all + (size_t)blockIdx.x * n;
+    const int i = min(max(rows[blockIdx.x], 0), n - 1);
     __shared__ uint32_t hist[256];
     __shared__ uint64_t prefix_s;
     __shared__ int want_s, nsel, ntie;
@@ -985,7 +1044,9 @@ __global__ void d2_to_float(const double *__restrict__ in, float *__restrict__ o
 struct Layout {
     float *norms, *norm_max, *tau;
     int *cnt, *fail_count, *fail_rows, *extra, *cursor, *unconv;
-    uint64_t *cand, *okey, *sort_scratch;
+    float *mu;               // column means (d rounded up to SLAB)
+    double *mu_part;         // their partial sums, MEAN_CHUNKS x d
+    uint64_t *cand, *sort_scratch;
     uint16_t *xs;            // the split copy of X
     int *clist, *ccount;     // rows of the current query block that need compaction, and how many (two counters take turns)
     int32_t *knn_idx;
@@ -1019,8 +1080,9 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
     q = take(4 * (size_t)n); if (L) L->extra = (int *)q;
     q = take(4 * (size_t)n); if (L) L->cursor = (int *)q;
     q = take(4); if (L) L->unconv = (int *)q;
+    q = take(4 * (size_t)((d + SLAB - 1) / SLAB * SLAB)); if (L) L->mu = (float *)q;
+    q = take(8 * (size_t)MEAN_CHUNKS * d); if (L) L->mu_part = (double *)q;
     q = take(8 * qb * cap); if (L) L->cand = (uint64_t *)q;
-    q = take(8 * (size_t)n); if (L) L->okey = (uint64_t *)q;
     q = take(8 * (size_t)2 * n * k); if (L) L->sort_scratch = (uint64_t *)q;
     q = take(4 * (size_t)n * k); if (L) L->knn_idx = (int32_t *)q;
     q = take(8 * (size_t)n * k); if (L) L->knn_d2 = (double *)q;
@@ -1107,8 +1169,11 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     const int kp = L.kp, cap = L.cap;
 
     const int dp = (d + SLAB - 1) / SLAB * SLAB;
-    hipLaunchKernelGGL(row_norms, dim3((n + 3) / 4), dim3(256), 0, s, d_X, n, d, L.norms);
-    hipLaunchKernelGGL(split_bf16, dim3((unsigned)(((size_t)n * dp + 255) / 256)), dim3(256), 0, s, d_X, n, d, dp, L.xs);
+    const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks = (n + rows_per_chunk - 1) / rows_per_chunk;
+    hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks), dim3(256), 0, s, d_X, n, d, rows_per_chunk, L.mu_part);
+    hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks, n, d, dp, L.mu);
+    hipLaunchKernelGGL(row_norms, dim3((n + 3) / 4), dim3(256), 0, s, d_X, L.mu, n, d, L.norms);
+    hipLaunchKernelGGL(split_bf16, dim3((unsigned)(((size_t)n * dp + 255) / 256)), dim3(256), 0, s, d_X, L.mu, n, d, dp, L.xs);
     hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms, n, L.norm_max);
     HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
     HIPCHK(hipMemsetAsync(L.unconv, 0, 4, s));
@@ -1174,17 +1239,14 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     int nfail = 0;
     HIPCHK(hipMemcpyAsync(&nfail, L.fail_count, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
-    if (nfail > 0) {
-        int *rows_h = (int *)malloc(sizeof(int) * (size_t)nfail);
-        if (!rows_h) return TSNE_ENOSPC;
-        HIPCHK(hipMemcpyAsync(rows_h, L.fail_rows, 4 * (size_t)nfail, hipMemcpyDeviceToHost, s));
-        HIPCHK(hipStreamSynchronize(s));
-        for (int f = 0; f < nfail; ++f) {
-            hipLaunchKernelGGL(knn_exact_dists, dim3((n + 3) / 4), dim3(256), 0, s, d_X, n, d, rows_h[f], L.okey);
-            hipLaunchKernelGGL(knn_exact_select, dim3(1), dim3(1024), 0, s, L.okey, n, k, rows_h[f], L.knn_idx,
-                               L.knn_d2);
-        }
-        free(rows_h);
+    // Rows without a certificate (ties at the k-th distance, duplicates): exact distances to every row, 2k failed
+    // rows a launch (their n keys each fit the space the symmetrisation sorts in later, 2 n k words).
+    for (int f0 = 0; f0 < nfail; f0 += 2 * k) {
+        const int nb = nfail - f0 < 2 * k ? nfail - f0 : 2 * k;
+        hipLaunchKernelGGL(knn_exact_dists, dim3((n + 3) / 4), dim3(256), 0, s, d_X, n, d, L.fail_rows + f0, nb,
+                           L.sort_scratch);
+        hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, L.sort_scratch, n, k, L.fail_rows + f0, L.knn_idx,
+                           L.knn_d2);
         HIPCHK(hipGetLastError());
     }
     return finish_P(L, n, k, perplexity, d_row_ptr, d_col, d_val, cap_nnz, nnz, d_knn_idx, d_knn_d2, n_unconverged, s);

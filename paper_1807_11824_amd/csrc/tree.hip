@@ -253,7 +253,7 @@ __device__ __forceinline__ uint32_t digit_of(uint64_t w, int lo, uint32_t mask) 
 __global__ __launch_bounds__(SORT_THREADS) void morton_encode_hist(const float2 *__restrict__ Y, int n,
                                                                    const float4 *__restrict__ root, int bits, int ks,
                                                                    uint32_t mask, uint64_t *__restrict__ words,
-                                                                   uint32_t *__restrict__ hist)
+                                                                   uint32_t *__restrict__ hist, int nblk)
 {
     __shared__ uint32_t h[RADIX];
     for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) h[d] = 0u;
@@ -275,24 +275,29 @@ __global__ __launch_bounds__(SORT_THREADS) void morton_encode_hist(const float2 
 }
 
 __global__ __launch_bounds__(SORT_THREADS) void radix_hist(const uint64_t *__restrict__ words, int n, int lo, uint32_t mask,
-                                                           uint32_t *__restrict__ hist)
+                                                           uint32_t *__restrict__ hist, int nblk)
 {
     __shared__ uint32_t h[RADIX];
     for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) h[d] = 0u;
     __syncthreads();
     const int base = blockIdx.x * SORT_TILE;
+    uint64_t w[SORT_ITEMS];
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k) {
+    for (int k = 0; k < SORT_ITEMS; ++k) {          // all loads in flight before the first count
         const int e = base + k * SORT_THREADS + (int)threadIdx.x;
-        if (e < n) atomicAdd(&h[digit_of(words[e], lo, mask)], 1u);
+        w[k] = e < n ? words[e] : 0ull;
     }
+#pragma unroll
+    for (int k = 0; k < SORT_ITEMS; ++k)
+        if (base + k * SORT_THREADS + (int)threadIdx.x < n) atomicAdd(&h[digit_of(w[k], lo, mask)], 1u);
     __syncthreads();
     for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) hist[(size_t)blockIdx.x * RADIX + d] = h[d];
 }
 
 // hist[t][d] becomes the number of words with digit d in tiles before t; dtot[d] the digit's total.
-// A workgroup takes 32 digits; 16 threads share a digit, each a segment of the tiles.
-constexpr int SCAN_DIGITS = 32, SCAN_SEGS = 16;
+// A workgroup takes SCAN_DIGITS neighbouring digits; SCAN_SEGS threads share a digit, each a segment of
+// the tiles, whose counts it loads in batches (so that its loads are in flight together).
+constexpr int SCAN_DIGITS = 16, SCAN_SEGS = 64, SCAN_BATCH = 8;
 __global__ __launch_bounds__(SCAN_DIGITS * SCAN_SEGS) void radix_scan(uint32_t *__restrict__ hist, int nblk,
                                                                       uint32_t *__restrict__ dtot)
 {
@@ -302,21 +307,31 @@ __global__ __launch_bounds__(SCAN_DIGITS * SCAN_SEGS) void radix_scan(uint32_t *
     const int len = (nblk + SCAN_SEGS - 1) / SCAN_SEGS;
     const int t0 = min(nblk, sg * len), t1 = min(nblk, t0 + len);
     uint32_t sum = 0;
-    for (int t = t0; t < t1; ++t) sum += hist[(size_t)t * RADIX + d];
+    for (int tb = t0; tb < t1; tb += SCAN_BATCH) {
+        uint32_t v[SCAN_BATCH];
+#pragma unroll
+        for (int k = 0; k < SCAN_BATCH; ++k) v[k] = tb + k < t1 ? hist[(size_t)(tb + k) * RADIX + d] : 0u;
+#pragma unroll
+        for (int k = 0; k < SCAN_BATCH; ++k) sum += v[k];
+    }
     ssum[sg][dl] = sum;
     __syncthreads();
     uint32_t run = 0, all = 0;
-#pragma unroll
     for (int k = 0; k < SCAN_SEGS; ++k) {
         const uint32_t v = ssum[k][dl];
-        if (k < sg) run += v;
+        run += k < sg ? v : 0u;
         all += v;
     }
     if (sg == 0) dtot[d] = all;
-    for (int t = t0; t < t1; ++t) {
-        const uint32_t v = hist[(size_t)t * RADIX + d];
-        hist[(size_t)t * RADIX + d] = run;
-        run += v;
+    for (int tb = t0; tb < t1; tb += SCAN_BATCH) {
+        uint32_t v[SCAN_BATCH];
+#pragma unroll
+        for (int k = 0; k < SCAN_BATCH; ++k) v[k] = tb + k < t1 ? hist[(size_t)(tb + k) * RADIX + d] : 0u;
+#pragma unroll
+        for (int k = 0; k < SCAN_BATCH; ++k) {
+            if (tb + k < t1) hist[(size_t)(tb + k) * RADIX + d] = run;
+            run += v[k];
+        }
     }
 }
 
@@ -361,30 +376,34 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint64_t *__
     const int tile = scatter_tile((int)blockIdx.x, nblk);
     if (tile >= nblk) return;               // the same for every thread of the workgroup
     const int tid = (int)threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int tile0 = tile * SORT_TILE;
+    const int base = tile0 + w * (WAVE * SORT_ITEMS);
+    uint64_t word[SORT_ITEMS];
+    uint32_t rank[SORT_ITEMS];
+#pragma unroll
+    for (int r = 0; r < SORT_ITEMS; ++r) {       // requested first: they arrive while the offsets below are worked out
+        const int e = base + r * WAVE + lane;
+        word[r] = e < n ? in[e] : 0ull;
+    }
     {
         uint32_t *z = reinterpret_cast<uint32_t *>(overlay);
         for (int i = tid; i < NW * RADIX / 2; i += SORT_THREADS) z[i] = 0u;
     }
     // where every digit's run starts in the output: digits before it, then tiles before this one
     {
-        uint32_t t[DPT], sum = 0;
+        uint32_t t[DPT], before[DPT], sum = 0;
 #pragma unroll
-        for (int j = 0; j < DPT; ++j) { t[j] = dtot[tid * DPT + j]; sum += t[j]; }
+        for (int j = 0; j < DPT; ++j) {
+            t[j] = dtot[tid * DPT + j];
+            before[j] = hist[(size_t)tile * RADIX + tid * DPT + j];
+            sum += t[j];
+        }
         uint32_t run = block_excl_scan(sum, wsum);      // (its barriers also cover the zeroing above)
 #pragma unroll
         for (int j = 0; j < DPT; ++j) {
-            gbase[tid * DPT + j] = run + hist[(size_t)tile * RADIX + tid * DPT + j];
+            gbase[tid * DPT + j] = run + before[j];
             run += t[j];
         }
-    }
-    const int tile0 = tile * SORT_TILE;
-    const int base = tile0 + w * (WAVE * SORT_ITEMS);
-    uint64_t word[SORT_ITEMS];
-    uint32_t rank[SORT_ITEMS];
-#pragma unroll
-    for (int r = 0; r < SORT_ITEMS; ++r) {
-        const int e = base + r * WAVE + lane;
-        word[r] = e < n ? in[e] : 0ull;
     }
     // Rank inside the wave's share, one item of every lane at a time: lanes with the same digit are
     // found with one ballot per digit bit.  whist[w] is touched by wave w alone, whose LDS
@@ -570,14 +589,18 @@ __device__ __forceinline__ int common_digits(uint64_t a, uint64_t b, int B)
     return x ? B - 1 - ((63 - __clzll((long long)x)) >> 1) : B;
 }
 
+// The keys are sorted, so the digits p shares with p+j are the fewest shared by any two
+// neighbours in between: with adj[q] = digits shared by positions q and q+1 (-1 beyond either end
+// of the array), R[j] = min(adj[p], .., adj[p+j-1]) and L[j] = min(adj[p-1], .., adj[p-j]).  Every
+// workgroup works adj out once for its positions and a margin (one 64-bit comparison per position),
+// after which a position needs 2C byte reads and minima.
 // CT > 0: leaf_cap known at compile time (all indices static, no bisection); CT = 0: any
-// leaf_cap <= LEVELS_WINDOW_MAXC at run time.
+// leaf_cap <= LEVELS_WINDOW_MAXC at run time.  adj points at the entry of position p.
 template <int CT>
-__device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n, uint32_t p, int B, int C,
-                                              int *tmin_out, int *tend_out)
+__device__ __forceinline__ void levels_window(const signed char *adj, int B, int C, int *tmin_out, int *tend_out)
 {
-    const uint64_t key = keys[p];
-    const int tmin = p == 0 ? 0 : (key == keys[p - 1] ? B + 1 : common_digits(key, keys[p - 1], B) + 1);
+    const int prev = adj[-1];
+    const int tmin = prev == B ? B + 1 : prev + 1;       // (position 0: adj[-1] = -1, depth 0)
     int smax;
     if (CT > 0) {
         // C-th largest of the two non-increasing lists: max over k of min(L[k], R[CT - k]), with
@@ -586,18 +609,21 @@ __device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n,
         L[0] = R[0] = B;
 #pragma unroll
         for (int j = 1; j <= CT; ++j) {
-            L[j] = p >= (uint32_t)j ? common_digits(key, keys[p - j], B) : -1;
-            R[j] = p + j < n ? common_digits(key, keys[p + j], B) : -1;
+            L[j] = min(L[j - 1], (int)adj[-j]);
+            R[j] = min(R[j - 1], (int)adj[j - 1]);
         }
         smax = -1;
 #pragma unroll
         for (int k = 0; k <= CT; ++k) smax = max(smax, min(L[k], R[CT - k]));
     } else {
         int L[LEVELS_WINDOW_MAXC], R[LEVELS_WINDOW_MAXC];
+        int l = B, r = B;
 #pragma unroll
         for (int j = 1; j <= LEVELS_WINDOW_MAXC; ++j) {
-            L[j - 1] = (j <= C && p >= (uint32_t)j) ? common_digits(key, keys[p - j], B) : -1;
-            R[j - 1] = (j <= C && p + j < n) ? common_digits(key, keys[p + j], B) : -1;
+            l = min(l, (int)adj[-j]);
+            r = min(r, (int)adj[j - 1]);
+            L[j - 1] = j <= C ? l : -1;
+            R[j - 1] = j <= C ? r : -1;
         }
         // deepest s in [0, B] with at least C of the 2C neighbours sharing s digits (-1 if none):
         // the count is non-increasing in s, so bisect
@@ -619,7 +645,7 @@ __device__ __forceinline__ void levels_window(const KeyWindow &keys, uint32_t n,
 }
 
 // Also moves the points into spatial order (step 4), writes the order itself (position -> slot)
-// and reduces each tile's (cells, sum x, sum y).
+// and reduces each tile's (cells, sum x, sum y).  CT < 0: any leaf_cap, by searching the keys.
 template <int CT>
 __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__restrict__ Y,
                                                                const uint64_t *__restrict__ words, int ks, int n, int B,
@@ -630,16 +656,29 @@ __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__r
 {
     __shared__ double sx[4], sy[4];
     __shared__ uint32_t sc[4];
-    __shared__ uint64_t kwin[LEVEL_TILE + 2 * KEY_HALO];
+    constexpr int MARGIN = LEVELS_WINDOW_MAXC + 1;
+    __shared__ uint64_t kwin[CT < 0 ? LEVEL_TILE + 2 * KEY_HALO : 1];
+    __shared__ signed char adjw[CT < 0 ? 1 : LEVEL_TILE + 2 * MARGIN];
     // the list of large cells (write_cells) and the work counters of the walk start at zero
     if (blockIdx.x == 0 && threadIdx.x < 1 + WALK_COUNTERS) counters[threadIdx.x] = 0u;
-    const KeyWindow kw = key_window_fill(words, ks, (uint32_t)n, blockIdx.x * LEVEL_TILE, LEVEL_TILE, kwin);
+    const int first = blockIdx.x * LEVEL_TILE;
+    KeyWindow kw;
+    if (CT < 0) {
+        kw = key_window_fill(words, ks, (uint32_t)n, (uint32_t)first, LEVEL_TILE, kwin);
+    } else {
+        // adjw[i]: digits shared by positions q = first - MARGIN + i and q + 1
+        for (int i = threadIdx.x; i < LEVEL_TILE + 2 * MARGIN; i += LEVEL_THREADS) {
+            const int q = first - MARGIN + i;
+            adjw[i] = (q < 0 || q + 1 >= n) ? (signed char)-1
+                                            : (signed char)common_digits(words[q] >> ks, words[q + 1] >> ks, B);
+        }
+    }
     double ax = 0.0, ay = 0.0;
     uint32_t ac = 0;
     float2 y[LEVEL_ITEMS];
 #pragma unroll
     for (int k = 0; k < LEVEL_ITEMS; ++k) {
-        const int p = blockIdx.x * LEVEL_TILE + k * LEVEL_THREADS + threadIdx.x;
+        const int p = first + k * LEVEL_THREADS + threadIdx.x;
         y[k] = make_float2(0.f, 0.f);
         if (p < n) {
             const uint32_t slot = min((uint32_t)(words[p] & ((1ull << ks) - 1ull)), (uint32_t)n - 1u);
@@ -650,13 +689,13 @@ __global__ __launch_bounds__(LEVEL_THREADS) void gather_levels(const float2 *__r
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < LEVEL_ITEMS; ++k) {
-        const int p = blockIdx.x * LEVEL_TILE + k * LEVEL_THREADS + threadIdx.x;
+        const int p = first + k * LEVEL_THREADS + threadIdx.x;
         if (p < n) {
             Ys[p] = y[k];
             ax += (double)y[k].x; ay += (double)y[k].y;
             int tmin, tend;
-            if (CT > 0 || C <= LEVELS_WINDOW_MAXC) levels_window<CT>(kw, (uint32_t)n, (uint32_t)p, B, C, &tmin, &tend);
-            else levels_at(kw, (uint32_t)n, (uint32_t)p, B, (uint32_t)C, &tmin, &tend);
+            if constexpr (CT < 0) levels_at(kw, (uint32_t)n, (uint32_t)p, B, (uint32_t)C, &tmin, &tend);
+            else levels_window<CT>(adjw + MARGIN + (p - first), B, C, &tmin, &tend);
             lev[p] = (uint16_t)(tmin | (tend << 8));
             ac += (uint32_t)(tend - tmin);
         }
@@ -766,7 +805,7 @@ __device__ __forceinline__ uint32_t digit_lower_bound(const KeyWindow &keys, uin
 // A cell whose run of positions ends inside that stretch is finished on the spot.  The few large
 // cells near the top of the tree would each be a chain of dozens of dependent memory reads in a
 // single lane; they are put on a list instead and finished by write_big_cells, one wave per search.
-constexpr int CELL_WINDOW = 4096;
+constexpr int CELL_WINDOW = 2048;
 
 __global__ __launch_bounds__(256) void write_cells(const uint64_t *__restrict__ words, int ks,
                                                    const uint32_t *__restrict__ cellseq,
@@ -987,7 +1026,7 @@ hipError_t launch_sort(tsne_ctx *c, int lo, int nbits, bool hist0, hipStream_t s
         const int width = lo + nbits - plo < RADIX_BITS ? lo + nbits - plo : RADIX_BITS;
         const uint32_t mask = (1u << width) - 1u;
         if (!(hist0 && plo == lo))
-            hipLaunchKernelGGL(radix_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, c->words[cur], n, plo, mask, c->hist);
+            hipLaunchKernelGGL(radix_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, c->words[cur], n, plo, mask, c->hist, nblk);
         hipLaunchKernelGGL(radix_scan, dim3(RADIX / SCAN_DIGITS), dim3(SCAN_DIGITS * SCAN_SEGS), 0, s, c->hist, nblk,
                            c->dtot);
         hipLaunchKernelGGL(radix_scatter, dim3(grid), dim3(SORT_THREADS), 0, s, c->words[cur], c->words[cur ^ 1], n, plo,
@@ -1033,7 +1072,7 @@ hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
     const int nblk = (n + SORT_TILE - 1) / SORT_TILE;
     const int width0 = 2 * B < RADIX_BITS ? 2 * B : RADIX_BITS;
     hipLaunchKernelGGL(morton_encode_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, Y, n, c->root, B, ks, (1u << width0) - 1u,
-                       c->words[0], c->hist);
+                       c->words[0], c->hist, nblk);
     return launch_sort(c, ks, 2 * B, true, s);
 }
 
@@ -1048,8 +1087,11 @@ hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s)
     if (C == 8)
         hipLaunchKernelGGL(gather_levels<8>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, words, ks, n, B, C, c->Ys, c->perm,
                            c->lev, c->part, c->big_count);
-    else
+    else if (C <= LEVELS_WINDOW_MAXC)
         hipLaunchKernelGGL(gather_levels<0>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, words, ks, n, B, C, c->Ys, c->perm,
+                           c->lev, c->part, c->big_count);
+    else
+        hipLaunchKernelGGL(gather_levels<-1>, dim3(nl), dim3(LEVEL_THREADS), 0, s, Y, words, ks, n, B, C, c->Ys, c->perm,
                            c->lev, c->part, c->big_count);
     hipLaunchKernelGGL(downsweep, dim3(nl), dim3(LEVEL_THREADS), 0, s, c->Ys, c->lev, n, c->part, c->cellseq, c->ps,
                        c->cell_p, c->cell_t, (uint32_t)c->cap_cells, c->ncells, c->status);

@@ -13,6 +13,14 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
+def worst_point(g, o):
+    """max over points i of |g_i - o_i| / (|o_i| + median_j |o_j|): a per-point companion of the relative L2 norm,
+    which a large error confined to a few of a million points would pass."""
+    g = np.asarray(g, np.float64); o = np.asarray(o, np.float64)
+    mag = np.linalg.norm(o, axis=1)
+    return float((np.linalg.norm(g - o, axis=1) / (mag + np.median(mag) + 1e-300)).max())
+
+
 def random_symmetric_csr(n, deg, seed=0):
     """A symmetric sparsity pattern with about 2*deg entries per row and positive values summing to 1.
 

@@ -99,11 +99,25 @@ def test_small_d_many_rows_sampled(n, d, k):
 
 @pytest.mark.parametrize("offset,sigma", [(30.0, 1.0), (300.0, 0.01)])
 def test_far_from_the_origin(offset, sigma):
-    """Norms much larger than the distances: the reduced-precision candidate search cannot certify
-    (some, then all) rows, which must then come out of the exact fall-back with the same lists."""
+    """Norms much larger than the distances.  The candidate search works on X minus its column means
+    (distances do not change), so the rows certify as they would around the origin and the lists are the oracle's."""
+    import time
     rng = np.random.default_rng(int(offset))
-    X = (offset + sigma * rng.standard_normal((3000, 20))).astype(np.float32)
-    _check_against_oracle(X, 10.0, 30)
+    n = 50_000
+    X = (offset + sigma * rng.standard_normal((n, 20))).astype(np.float32)
+    rows = np.sort(rng.choice(n, 256, replace=False).astype(np.int32))
+    _gpu_P(X[:4000], 10.0, 30)          # (first call: kernels are loaded)
+    t0 = time.time()
+    _check_against_oracle(X, 10.0, 30, rows=rows)
+    print(f"offset {offset}: tsne_build_P + oracle on 256 rows {time.time() - t0:.2f} s", flush=True)
+
+
+def test_many_rows_without_certificate():
+    """Lattice points with heavy duplication: nearly every row has ties at its k-th distance, cannot be certified
+    and goes through the exact fall-back, which takes the failed rows 2k at a time."""
+    X = synth.lattice(20_000, 6, span=3, seed=3)
+    rows = np.sort(np.random.default_rng(5).choice(20_000, 256, replace=False).astype(np.int32))
+    _check_against_oracle(X, 5.0, 17, rows=rows)
 
 
 def test_bad_arguments():

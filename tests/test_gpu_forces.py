@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import grid_bits, random_symmetric_csr, rel_l2
+from helpers import grid_bits, random_symmetric_csr, rel_l2, worst_point
 from paper_1807_11824_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -35,9 +35,11 @@ def _compare(Y, rp, col, val, theta, leaf_cap, alpha=12.0):
     o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=theta, leaf_cap=leaf_cap, group=64, alpha=alpha,
                        bits=grid_bits(Y.shape[0]))
     g = 4.0 * (alpha * A.astype(np.float64) - R.astype(np.float64) / Z)
-    errs = dict(A=rel_l2(A, o["A"]), R=rel_l2(R, o["R"]), Z=abs(Z - o["Z"]) / o["Z"], grad=rel_l2(g, o["grad"]))
+    errs = dict(A=rel_l2(A, o["A"]), R=rel_l2(R, o["R"]), Z=abs(Z - o["Z"]) / o["Z"], grad=rel_l2(g, o["grad"]),
+                worst_point=worst_point(g, o["grad"]))
     print("parity", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     assert errs["grad"] <= TOL and errs["A"] <= TOL and errs["R"] <= TOL and errs["Z"] <= 1e-5
+    assert errs["worst_point"] <= 1e-3
     return o, g
 
 
