@@ -138,3 +138,81 @@ def test_lists_partition_the_points():
     a, _ = ivf.assign(X, C)
     for c, l in enumerate(lists):
         assert np.all(a[l] == c)
+
+
+# ---------------------------------------------------------------------------- product-quantised second stage
+def test_pq_hand_example():
+    """Eq. (8) and (11) by hand.  One list (centroid at the origin), five points in the plane, two sub-vectors of
+    one coordinate each, two centroids per sub-quantiser."""
+    X = np.array([[1.0, 10.0], [3.0, 10.0], [1.0, 20.0], [3.0, 20.0], [2.0, 16.0]], np.float32)
+    C = np.array([[0.0, 0.0]], np.float32)
+    cb = np.array([[[1.0], [3.0]], [[10.0], [20.0]]], np.float32)       # x-codebook {1, 3}, y-codebook {10, 20}
+    codes, a = ivf.pq_encode(X, C, cb)
+    assert a.tolist() == [0] * 5
+    assert codes.tolist() == [[0, 0], [1, 0], [0, 1], [1, 1], [0, 1]]     # x = 2 is equally far from 1 and 3: lower index
+    Q = ivf.pq_decode(C, cb, codes, a)
+    assert Q.tolist() == [[1, 10], [3, 10], [1, 20], [3, 20], [1, 20]]
+    # query 4 = (2, 16): |x - q(y)|^2 to the codes of points 0..3 = 1 + 36, 1 + 36, 1 + 16, 1 + 16
+    idx, d2 = ivf.ivfpq_knn(X, C, cb, 1, 4, rows=[4])
+    assert idx[0].tolist() == [2, 3, 0, 1] and d2[0].tolist() == [17.0, 17.0, 37.0, 37.0]
+    # query 0 = (1, 10) sees point 4 through its code (1, 20): 100 away, behind point 1 (4) and level with point 2
+    idx, d2 = ivf.ivfpq_knn(X, C, cb, 1, 4, rows=[0])
+    assert idx[0].tolist() == [1, 2, 4, 3] and d2[0].tolist() == [4.0, 100.0, 100.0, 104.0]
+
+
+def test_pq_with_enough_centroids_is_the_flat_search():
+    """When every residual sub-vector is one of its sub-quantiser's centroids, q(y) = y and Eq. (11) compares exact
+    distances: the lists are those of the flat second stage.  Lattice data (three values a coordinate), one list
+    at the origin, codebooks holding all nine pairs of values."""
+    X = synth.lattice(600, 6, span=3, seed=4)
+    C = np.zeros((1, 6), np.float32)                       # one list at the origin: residual = the point itself
+    vals = np.array([0.0, 1.0, 2.0], np.float32)
+    pairs = np.array([[u, v] for u in vals for v in vals], np.float32)          # every possible sub-vector of two
+    cb = np.stack([pairs, pairs, pairs])                   # m = 3 sub-vectors, 9 centroids each
+    idx, d2 = ivf.ivfpq_knn(X, C, cb, 1, 12)
+    fidx, fd2 = ivf.ivf_knn(X, C, 1, 12)
+    assert np.array_equal(idx, fidx) and np.array_equal(d2, fd2)
+    eidx, _ = oracle.knn(X, 12)
+    assert np.array_equal(idx, eidx)
+
+
+def test_pq_codes_are_the_nearest_reconstruction():
+    """q2 takes each sub-vector to its nearest centroid, so no other code reconstructs a point better; the
+    distance of Eq. (11) is the distance to the decoded point; and the trained codebooks have the stated shape."""
+    X, _ = synth.gaussian_mixture(900, 8, 6, 3.0, 1.0, seed=7)
+    C, _ = ivf.kmeans_train(X, 12, 4)
+    cb = ivf.pq_train(X, C, 4, 16, 5)
+    assert cb.shape == (4, 16, 2) and cb.dtype == np.float32
+    codes, a = ivf.pq_encode(X, C, cb)
+    Q = ivf.pq_decode(C, cb, codes, a)
+    err = ((X.astype(np.float64) - Q) ** 2).sum(1)
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        other = codes.copy()
+        j = rng.integers(0, 4)
+        other[:, j] = (other[:, j] + rng.integers(1, 16)) % 16
+        worse = ((X.astype(np.float64) - ivf.pq_decode(C, cb, other, a)) ** 2).sum(1)
+        assert np.all(worse >= err - 1e-12)
+    # quantising the residual loses less than dropping it: the code is closer to the point than its list's centroid
+    _, dcoarse = ivf.assign(X, C)
+    assert err.mean() < 0.5 * dcoarse.mean()
+    idx, d2 = ivf.ivfpq_knn(X, C, cb, 3, 10, rows=[5, 77, 400])
+    for o, i in enumerate([5, 77, 400]):
+        direct = ((X[i].astype(np.float64)[None, :] - Q[idx[o]]) ** 2).sum(1)
+        assert np.allclose(d2[o], direct, rtol=1e-12, atol=1e-12)
+        assert np.all(np.diff(d2[o]) >= 0) and i not in idx[o]
+
+
+def test_pq_recall_grows_with_the_code():
+    """A finer second stage (more centroids per sub-quantiser) finds more of the true neighbours; with tau = |C|
+    the only approximation left is the code."""
+    X, _ = synth.gaussian_mixture(1200, 8, 5, 4.0, 1.0, seed=9)
+    C, _ = ivf.kmeans_train(X, 10, 4)
+    eidx, _ = oracle.knn(X, 10)
+    rows = np.arange(0, 1200, 7)
+    rec = []
+    for ksub in (2, 16, 128):
+        cb = ivf.pq_train(X, C, 4, ksub, 6)
+        idx, _ = ivf.ivfpq_knn(X, C, cb, 10, 10, rows=rows)
+        rec.append(ivf.recall(idx, eidx[rows]))
+    assert rec[0] < rec[1] < rec[2] and rec[2] > 0.6
