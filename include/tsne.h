@@ -148,8 +148,9 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
  * Sec. III-B, Eq. (8)-(11): approximate neighbours from an inverted file.  The coarse quantiser q1 is the
  * nearest of nlist centroids (index of the lowest among equals); a query looks at the tau lists whose
  * centroids are nearest to it (Eq. 10) and keeps the k nearest of the points stored in them (Eq. 11).
- * The second-stage code q2 of Eq. (8) is left out: list entries are compared by their exact squared
- * distance (a "flat" inverted file), so the only approximation is in which lists are looked at.
+ * Here the second-stage code q2 of Eq. (8) is the identity: list entries are compared by their exact squared
+ * distance (a "flat" inverted file), so the only approximation is in which lists are looked at
+ * (tsne_ivfpq_* below: the product-quantised second stage).
  * All decisions are taken on squared distances accumulated in double precision from the float inputs,
  * ties towards the lower index; the lists returned are those of the definition.
  *
@@ -179,16 +180,45 @@ int tsne_ivf_knn(const float *d_X, int32_t n, int32_t d, const float *d_centroid
                  void *stream);
 
 /*
+ * Sec. III-B, Eq. (8) and (11): the product-quantised second stage.  A point y of list c = q1(y) is stored as m code
+ * bytes: its residual y - c (one float subtraction per coordinate) is cut into m sub-vectors of d / m coordinates
+ * and each is replaced by the index of the nearest of ksub centroids of that sub-vector's own quantiser (squared
+ * distance in double, lowest index among equals); q(y) = c + the m centroids.  A query compares itself with the
+ * codes of the points in its tau lists: |x - q(y)|^2 = sum over the sub-vectors j, in order, of
+ * sum_t ((x_t - c_t) - codebook[j][code_j][t])^2, every operation in double and none fused; the k smallest by
+ * (that value, index) are returned together with those values.
+ *
+ * tsne_ivfpq_train: the m codebooks.  Sub-quantiser j is tsne_ivf_train's k-means (same start, same sample
+ *   rule, `iters` rounds) with ksub centroids on the j-th sub-vectors of the residuals of all rows.
+ *   d_codebooks: m x ksub x (d / m) floats (device, caller-owned, written).
+ * tsne_ivfpq_knn: codes of all rows, then the search.  d_knn_idx: n x k int32, d_knn_d2: n x k doubles (the
+ *   distances to the codes).  Errors as tsne_ivf_knn.
+ * Limits: those of tsne_ivf_knn; d a multiple of m; ksub <= min(n, 256).
+ * Both calls synchronise the stream before returning.
+ */
+int tsne_ivfpq_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, int32_t m, int32_t ksub,
+                               size_t *bytes);
+int tsne_ivfpq_train(const float *d_X, int32_t n, int32_t d, const float *d_centroids, int32_t nlist, int32_t m,
+                     int32_t ksub, int32_t iters, float *d_codebooks, void *d_workspace, size_t workspace_bytes,
+                     void *stream);
+int tsne_ivfpq_knn(const float *d_X, int32_t n, int32_t d, const float *d_centroids, int32_t nlist,
+                   const float *d_codebooks, int32_t m, int32_t ksub, int32_t tau, int32_t k, int32_t *d_knn_idx,
+                   double *d_knn_d2, void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * tsne_build_P with the neighbours of Sec. III-B's approximate search instead of the exact ones:
  * tsne_ivf_train (nlist centroids, kmeans_iters rounds; nlist = 0 takes the paper's sqrt(n)), tsne_ivf_knn
- * (tau lists per query), then Eq. (1) and the symmetric CSR exactly as in tsne_build_P.  Same outputs,
- * same limits as both.  If some row finds fewer than k other points in its tau lists the search is
+ * (tau lists per query), then Eq. (1) and the symmetric CSR exactly as in tsne_build_P.  pq_m > 0 takes the
+ * product-quantised second stage instead (tsne_ivfpq_train with pq_m sub-vectors of d / pq_m coordinates, 256
+ * centroids each, kmeans_iters rounds; tsne_ivfpq_knn), and Eq. (1) is then fed the distances to the codes, which
+ * is what such a search returns.  Same outputs, same limits as the calls it makes.  If some row finds fewer than k other points in its tau lists the search is
  * repeated for all rows with twice the lists, up to min(32, nlist), before TSNE_ENUM is returned;
  * *tau_used (host, may be NULL) receives the number of lists the result was built with.
  */
-int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes);
+int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, int32_t pq_m,
+                                        size_t *bytes);
 int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k, int32_t nlist,
-                        int32_t tau, int32_t kmeans_iters, int32_t *d_row_ptr, int32_t *d_col, float *d_val,
+                        int32_t tau, int32_t kmeans_iters, int32_t pq_m, int32_t *d_row_ptr, int32_t *d_col, float *d_val,
                         int64_t cap_nnz, int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged,
                         int32_t *tau_used, void *d_workspace, size_t workspace_bytes, void *stream);
 

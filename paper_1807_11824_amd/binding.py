@@ -57,8 +57,11 @@ def lib():
         "tsne_ivf_workspace_bytes": (C.c_int, [i32, i32, i32, i32, i32, C.POINTER(C.c_size_t)]),
         "tsne_ivf_train": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, C.c_size_t, vp]),
         "tsne_ivf_knn": (C.c_int, [vp, i32, i32, vp, i32, i32, i32, vp, vp, vp, C.c_size_t, vp]),
-        "tsne_build_P_approx_workspace_bytes": (C.c_int, [i32, i32, i32, i32, i32, C.POINTER(C.c_size_t)]),
-        "tsne_build_P_approx": (C.c_int, [vp, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, i64, C.POINTER(i64), vp, vp,
+        "tsne_ivfpq_workspace_bytes": (C.c_int, [i32, i32, i32, i32, i32, i32, i32, C.POINTER(C.c_size_t)]),
+        "tsne_ivfpq_train": (C.c_int, [vp, i32, i32, vp, i32, i32, i32, i32, vp, vp, C.c_size_t, vp]),
+        "tsne_ivfpq_knn": (C.c_int, [vp, i32, i32, vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, C.c_size_t, vp]),
+        "tsne_build_P_approx_workspace_bytes": (C.c_int, [i32, i32, i32, i32, i32, i32, C.POINTER(C.c_size_t)]),
+        "tsne_build_P_approx": (C.c_int, [vp, i32, i32, f32, i32, i32, i32, i32, i32, vp, vp, vp, i64, C.POINTER(i64), vp, vp,
                                           C.POINTER(i32), C.POINTER(i32), vp, C.c_size_t, vp]),
         "tsne_set_P": (C.c_int, [vp, vp, vp, vp, i64]),
         "tsne_P_layout": (C.c_int, [vp, C.POINTER(i64), C.POINTER(i64)]),
@@ -185,13 +188,55 @@ def ivf_knn(X, centroids, tau, k, stream=None, extra_workspace_bytes=0):
     return idx, d2
 
 
-def build_P_approx(X, perplexity, k, tau, nlist=0, kmeans_iters=10, stream=None, want_knn=False):
-    """tsne_build_P_approx on a device tensor X (n x d float32).  Returns a dict of device tensors."""
+def _ivfpq_workspace(n, d, k, nlist, tau, m, ksub, device):
+    b = C.c_size_t(0)
+    rc = lib().tsne_ivfpq_workspace_bytes(n, d, k, nlist, tau, m, ksub, C.byref(b))
+    if rc:
+        raise TsneError(rc, "tsne_ivfpq_workspace_bytes", lib().tsne_strerror(rc).decode())
+    return torch.empty(b.value, dtype=torch.uint8, device=device)
+
+
+def ivfpq_train(X, centroids, m, ksub, iters, stream=None):
+    """tsne_ivfpq_train: the m x ksub x (d / m) codebooks of the product quantiser (device float32)."""
+    _dev(X, torch.float32, "X"); _dev(centroids, torch.float32, "centroids")
+    n, d = X.shape
+    L = lib()
+    work = _ivfpq_workspace(n, d, 1, centroids.shape[0], 1, m, ksub, X.device)
+    cb = torch.empty((m, ksub, d // max(m, 1)), dtype=torch.float32, device=X.device)
+    rc = L.tsne_ivfpq_train(_ptr(X), n, d, _ptr(centroids), centroids.shape[0], m, ksub, iters, _ptr(cb), _ptr(work),
+                            work.numel(), _stream_ptr(stream))
+    if rc:
+        raise TsneError(rc, "tsne_ivfpq_train", L.tsne_strerror(rc).decode())
+    return cb
+
+
+def ivfpq_knn(X, centroids, codebooks, tau, k, stream=None):
+    """tsne_ivfpq_knn: (idx int32 n x k, distances to the codes float64 n x k), device tensors."""
+    _dev(X, torch.float32, "X"); _dev(centroids, torch.float32, "centroids"); _dev(codebooks, torch.float32, "codebooks")
+    n, d = X.shape
+    m, ksub, ds = codebooks.shape
+    if m * ds != d or centroids.shape[1] != d:
+        raise ValueError("codebooks / centroids: wrong shape")
+    L = lib()
+    nlist = centroids.shape[0]
+    work = _ivfpq_workspace(n, d, k, nlist, tau, m, ksub, X.device)
+    idx = torch.empty((n, k), dtype=torch.int32, device=X.device)
+    d2 = torch.empty((n, k), dtype=torch.float64, device=X.device)
+    rc = L.tsne_ivfpq_knn(_ptr(X), n, d, _ptr(centroids), nlist, _ptr(codebooks), m, ksub, tau, k, _ptr(idx), _ptr(d2),
+                          _ptr(work), work.numel(), _stream_ptr(stream))
+    if rc:
+        raise TsneError(rc, "tsne_ivfpq_knn", L.tsne_strerror(rc).decode())
+    return idx, d2
+
+
+def build_P_approx(X, perplexity, k, tau, nlist=0, kmeans_iters=10, stream=None, want_knn=False, pq_m=0):
+    """tsne_build_P_approx on a device tensor X (n x d float32); pq_m > 0: product-quantised second stage with
+    pq_m sub-vectors.  Returns a dict of device tensors."""
     _dev(X, torch.float32, "X")
     n, d = X.shape
     L = lib()
     b = C.c_size_t(0)
-    rc = L.tsne_build_P_approx_workspace_bytes(n, d, k, nlist, tau, C.byref(b))
+    rc = L.tsne_build_P_approx_workspace_bytes(n, d, k, nlist, tau, pq_m, C.byref(b))
     if rc:
         raise TsneError(rc, "tsne_build_P_approx_workspace_bytes", L.tsne_strerror(rc).decode())
     work = torch.empty(b.value, dtype=torch.uint8, device=X.device)
@@ -204,7 +249,7 @@ def build_P_approx(X, perplexity, k, tau, nlist=0, kmeans_iters=10, stream=None,
     nnz = C.c_int64(0)
     bad = C.c_int32(0)
     used = C.c_int32(0)
-    rc = L.tsne_build_P_approx(_ptr(X), n, d, perplexity, k, nlist, tau, kmeans_iters, _ptr(row_ptr), _ptr(col),
+    rc = L.tsne_build_P_approx(_ptr(X), n, d, perplexity, k, nlist, tau, kmeans_iters, pq_m, _ptr(row_ptr), _ptr(col),
                                _ptr(val), cap, C.byref(nnz), _ptr(knn_idx), _ptr(knn_d2), C.byref(bad), C.byref(used),
                                _ptr(work), b.value, _stream_ptr(stream))
     if rc:

@@ -1261,20 +1261,31 @@ static int approx_lists(int32_t n, int32_t nlist)
     return v;
 }
 
-int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes)
+constexpr int PQ_KSUB = 256;     // centroids per sub-quantiser: one code byte per sub-vector
+
+int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, int32_t pq_m,
+                                        size_t *bytes)
 {
-    if (!bytes || check_args(n, d, k) != TSNE_OK) return TSNE_EINVAL;
+    if (!bytes || check_args(n, d, k) != TSNE_OK || pq_m < 0) return TSNE_EINVAL;
     nlist = approx_lists(n, nlist);
+    const int tau_max = nlist < 32 ? nlist : 32;
     size_t ivf = 0, ivf_max = 0;
-    if (tsne_ivf_workspace_bytes(n, d, k, nlist, tau, &ivf) != TSNE_OK) return TSNE_EINVAL;
     // (room for the search to be repeated with more lists, see tsne_build_P_approx)
-    if (tsne_ivf_workspace_bytes(n, d, k, nlist, nlist < 32 ? nlist : 32, &ivf_max) != TSNE_OK) return TSNE_EINVAL;
-    *bytes = carve(nullptr, n, d, k, nullptr) + up(4 * (size_t)nlist * d) + (ivf_max > ivf ? ivf_max : ivf);
+    if (pq_m > 0) {
+        const int ksub = n < PQ_KSUB ? n : PQ_KSUB;
+        if (tsne_ivfpq_workspace_bytes(n, d, k, nlist, tau, pq_m, ksub, &ivf) != TSNE_OK) return TSNE_EINVAL;
+        if (tsne_ivfpq_workspace_bytes(n, d, k, nlist, tau_max, pq_m, ksub, &ivf_max) != TSNE_OK) return TSNE_EINVAL;
+    } else {
+        if (tsne_ivf_workspace_bytes(n, d, k, nlist, tau, &ivf) != TSNE_OK) return TSNE_EINVAL;
+        if (tsne_ivf_workspace_bytes(n, d, k, nlist, tau_max, &ivf_max) != TSNE_OK) return TSNE_EINVAL;
+    }
+    *bytes = carve(nullptr, n, d, k, nullptr) + up(4 * (size_t)nlist * d) + up(4 * (size_t)PQ_KSUB * d) +
+             (ivf_max > ivf ? ivf_max : ivf);
     return TSNE_OK;
 }
 
 int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity, int32_t k, int32_t nlist, int32_t tau,
-                        int32_t kmeans_iters, int32_t *d_row_ptr, int32_t *d_col, float *d_val, int64_t cap_nnz,
+                        int32_t kmeans_iters, int32_t pq_m, int32_t *d_row_ptr, int32_t *d_col, float *d_val, int64_t cap_nnz,
                         int64_t *nnz, int32_t *d_knn_idx, float *d_knn_d2, int32_t *n_unconverged, int32_t *tau_used,
                         void *d_workspace, size_t workspace_bytes, void *stream)
 {
@@ -1284,23 +1295,32 @@ int tsne_build_P_approx(const float *d_X, int32_t n, int32_t d, float perplexity
     if (((uintptr_t)d_workspace % ALIGN) != 0) return TSNE_EINVAL;
     nlist = approx_lists(n, nlist);
     size_t need = 0;
-    if (tsne_build_P_approx_workspace_bytes(n, d, k, nlist, tau, &need) != TSNE_OK) return TSNE_EINVAL;
+    if (tsne_build_P_approx_workspace_bytes(n, d, k, nlist, tau, pq_m, &need) != TSNE_OK) return TSNE_EINVAL;
     if (workspace_bytes < need) return TSNE_ENOSPC;
     hipStream_t s = (hipStream_t)stream;
     Layout L;
     size_t off = carve(&L, n, d, k, (char *)d_workspace);
     float *centroids = (float *)((char *)d_workspace + off);
     off += up(4 * (size_t)nlist * d);
+    float *codebooks = (float *)((char *)d_workspace + off);
+    off += up(4 * (size_t)PQ_KSUB * d);
+    const int ksub = n < PQ_KSUB ? n : PQ_KSUB;
     void *ivf_ws = (char *)d_workspace + off;
     const size_t ivf_bytes = workspace_bytes - off;
     HIPCHK(hipMemsetAsync(L.unconv, 0, 4, s));
     HIPCHK(hipMemsetAsync(L.extra, 0, 4 * (size_t)n, s));
     int rc = ivf_train_device(d_X, n, d, nlist, kmeans_iters, centroids, ivf_ws, ivf_bytes, s);
     if (rc != TSNE_OK) return rc;
+    if (pq_m > 0) {     // Eq. (8): the second-stage codebooks, one code byte per sub-vector
+        rc = tsne_ivfpq_train(d_X, n, d, centroids, nlist, pq_m, ksub, kmeans_iters, codebooks, ivf_ws, ivf_bytes, s);
+        if (rc != TSNE_OK) return rc;
+    }
     // a row that finds fewer than k other points in its tau lists: twice the lists for everybody, and again
     const int tau_max = nlist < 32 ? nlist : 32;
     for (;;) {
-        rc = ivf_knn_device(d_X, n, d, centroids, nlist, tau, k, L.knn_idx, L.knn_d2, ivf_ws, ivf_bytes, s);
+        rc = pq_m > 0 ? tsne_ivfpq_knn(d_X, n, d, centroids, nlist, codebooks, pq_m, ksub, tau, k, L.knn_idx, L.knn_d2, ivf_ws,
+                                       ivf_bytes, s)
+                      : ivf_knn_device(d_X, n, d, centroids, nlist, tau, k, L.knn_idx, L.knn_d2, ivf_ws, ivf_bytes, s);
         if (rc != TSNE_ENUM || tau >= tau_max) break;
         tau = 2 * tau < tau_max ? 2 * tau : tau_max;
     }

@@ -1,5 +1,6 @@
-// Approximate neighbour search of Sec. III-B: inverted file over a k-means coarse quantiser, flat
-// second stage (Eq. 10-11 with q(y) = y).
+// Approximate neighbour search of Sec. III-B: inverted file over a k-means coarse quantiser, with a
+// flat second stage (Eq. 10-11 with q(y) = y) or the product-quantised one of Eq. (8): q(y) = q1(y) +
+// q2(y - q1(y)), q2 = m sub-quantisers of ksub centroids over the sub-vectors of the residual.
 //
 //   ivf_probe        Eq. (10): for every point the tau nearest centroids (tau = 1: the quantiser q1)
 //   kmeans_accum / kmeans_finish   Lloyd update: centroid = mean of its points
@@ -7,6 +8,8 @@
 //   pair_hist / scan_counts / pair_scatter   (query, probed list) pairs grouped by list
 //   ivf_score        squared distances of a list's points to the queries that probe it, kept as float keys
 //   ivf_select       Eq. (11): the k smallest of a query's candidates, ordered by (distance, index)
+//   residual_sub / pack_codes / ivfpq_score   the product quantiser: residual sub-vectors (training and
+//                    encoding reuse the k-means and nearest-centroid kernels), codes, distances to the codes
 //
 // Every decision (nearest centroid, probed lists, the k nearest of the candidates) is taken on
 // squared distances summed in double precision from the float inputs, ties towards the lower
@@ -465,6 +468,107 @@ __device__ __forceinline__ double exact_d2(const float *__restrict__ X, int d, i
     return acc;
 }
 
+// The product-quantised second stage (Eq. 8): row id is stored as its list (q1) and m code bytes; codes == nullptr
+// means the flat second stage.
+struct PqView {
+    const unsigned char *codes;   // n x m
+    const float *cb;              // m x ksub x ds
+    const float *C;               // the coarse centroids, nlist x d
+    int m, ds, ksub;
+};
+
+// Eq. (11), |x_q - q(y)|^2 for y = row id stored in `list`: the query's residual to that list against the
+// code's sub-vector centroids, every operation in double and none fused, each sub-vector's sum accumulated
+// coordinate by coordinate and the m sums added in order.  The one function serves the distance kernel and
+// the selection, so a candidate's value is the same bits wherever it is formed.
+__device__ __forceinline__ double pq_d2(const float *__restrict__ X, int d, int q, int id, int list, const PqView &pq)
+{
+#pragma clang fp contract(off)
+    const float *x = X + (size_t)q * d;
+    const float *c = pq.C + (size_t)list * d;
+    const unsigned char *code = pq.codes + (size_t)id * pq.m;
+    double total = 0.0;
+    for (int j = 0; j < pq.m; ++j) {
+        const float *r = pq.cb + ((size_t)j * pq.ksub + min((int)code[j], pq.ksub - 1)) * pq.ds;
+        double sub = 0.0;
+        for (int t = 0; t < pq.ds; ++t) {
+            const double rq = (double)x[j * pq.ds + t] - (double)c[j * pq.ds + t];
+            const double df = rq - (double)r[t];
+            const double sq = df * df;          // (a product and an addition: two roundings)
+            sub = sub + sq;
+        }
+        total = total + sub;
+    }
+    return total;
+}
+
+// distance of candidate id to query q under the second stage in use (id's list is its nearest centroid,
+// the first of its probes)
+__device__ __forceinline__ double cand_d2(const float *__restrict__ X, int d, int q, int id,
+                                          const int32_t *__restrict__ probe, int tau, const PqView &pq)
+{
+    return pq.codes ? pq_d2(X, d, q, id, probe[(size_t)id * tau], pq) : exact_d2(X, d, q, id);
+}
+
+// ------------------------------------------------------------------ product quantiser: residuals, codes, distances
+// R[i][t] = x_i[j ds + t] - c[j ds + t], c the centroid of i's list: the j-th sub-vector of the residual (one
+// float subtraction per coordinate), rows contiguous so that the k-means and nearest-centroid kernels take it as data
+__global__ void residual_sub(const float *__restrict__ X, int n, int d, const float *__restrict__ C,
+                             const int32_t *__restrict__ list, int j, int ds, float *__restrict__ R)
+{
+    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (size_t)n * ds) return;
+    const size_t i = e / ds;
+    const int t = (int)(e % ds);
+    R[e] = X[i * d + (size_t)j * ds + t] - C[(size_t)list[i] * d + (size_t)j * ds + t];
+}
+
+__global__ void pack_codes(const int32_t *__restrict__ nearest, int n, int j, int m, unsigned char *__restrict__ codes)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) codes[(size_t)i * m + j] = (unsigned char)nearest[i];
+}
+
+// The distance kernel of the product-quantised second stage: same tiles and same places in the scratch as
+// ivf_score; a lane's query against the codes of the list's rows, which are the same for every lane.
+__global__ __launch_bounds__(IVF_QW * 64) void ivfpq_score(const float *__restrict__ X, int d, const int *__restrict__ lorder,
+                                                  const int *__restrict__ cellptr, const int32_t *__restrict__ probe, int tau,
+                                                  int nlist, const int *__restrict__ pairptr, const int *__restrict__ tileptr,
+                                                  const int *__restrict__ pairq, const unsigned char *__restrict__ pairr,
+                                                  const long long *__restrict__ mprefix, long long base0,
+                                                  float *__restrict__ D, PqView pq)
+{
+    const int tile = blockIdx.x;
+    if (tile >= tileptr[nlist]) return;
+    int lo = 0, hi = nlist;            // last list whose first tile is <= tile and that has tiles
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tileptr[mid] <= tile) lo = mid; else hi = mid;
+    }
+    const int B = lo;
+    const int lane = lane_id();
+    const int qtiles = (pairptr[B + 1] - pairptr[B] + IVF_QW * WAVE - 1) / (IVF_QW * WAVE);
+    const int within = tile - tileptr[B];
+    const int chunk = within / qtiles;
+    const int p0 = pairptr[B] + WAVE * (IVF_QW * (within - chunk * qtiles) + (int)(threadIdx.x >> 6));
+    if (p0 >= pairptr[B + 1]) return;
+    const int np = min(WAVE, pairptr[B + 1] - p0);
+    const int p = p0 + min(lane, np - 1);
+    const int q = pairq[p], r = pairr[p];
+    long long off = mprefix[q] - base0;
+    for (int rr = 0; rr < r; ++rr) {
+        const int c = probe[(size_t)q * tau + rr];
+        off += cellptr[c + 1] - cellptr[c];
+    }
+    float *dst = D + off;
+    const int cb = cellptr[B], ce = min(cellptr[B + 1], cb + (chunk + 1) * IVF_CCH);
+    for (int c = cb + chunk * IVF_CCH; c < ce; ++c) {
+        const int id = lorder[c];
+        const double v = pq_d2(X, d, q, id, B, pq);
+        if (lane < np) dst[c - cb] = id == q ? INFINITY : distance_key(v);
+    }
+}
+
 // The bucket of a 256-bin histogram that holds the need-th smallest element (1-based), how many of the
 // elements wanted fall inside it, and its count.  All 256 threads call it after the histogram is complete.
 __device__ __forceinline__ void find_bucket(const uint32_t *hist, int need, int *wtot, int *bucket, int *need_in,
@@ -524,7 +628,7 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
                                                   long long base0, int qb, int tau, int k,
                                                   const int32_t *__restrict__ probe, const int *__restrict__ cellptr,
                                                   const int *__restrict__ lorder, const float *__restrict__ X, int d, int buf,
-                                                  int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2)
+                                                  int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2, PqView pq)
 {
     extern __shared__ __align__(16) unsigned char sel_dyn[];
     double *wd = reinterpret_cast<double *>(sel_dyn);          // k winners, then up to buf equals
@@ -612,7 +716,7 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
     for (int a = tid; a < less + (small ? equal : 0); a += 256) {
         const int slot = a < less ? a : k + (a - less);
         const int id = lorder[list_pos(wi[slot])];
-        wd[slot] = exact_d2(X, d, q, id);
+        wd[slot] = cand_d2(X, d, q, id, probe, tau, pq);
         wi[slot] = id;
     }
     __syncthreads();
@@ -636,7 +740,7 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
             for (int pos = tid; pos < M; pos += 256) {
                 if (key_bits(src[pos]) != Tf) continue;
                 const unsigned long long db =
-                    (unsigned long long)__double_as_longlong(exact_d2(X, d, q, lorder[list_pos(pos)]));
+                    (unsigned long long)__double_as_longlong(cand_d2(X, d, q, lorder[list_pos(pos)], probe, tau, pq));
                 if ((db & m64) == p64) atomicAdd(&sh.hist[(unsigned)(db >> shift) & 255u], 1u);
             }
             __syncthreads();
@@ -657,7 +761,7 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
                 for (int pos = tid; pos < M; pos += 256) {
                     if (key_bits(src[pos]) != Tf) continue;
                     const uint32_t id = (uint32_t)lorder[list_pos(pos)];
-                    if ((unsigned long long)__double_as_longlong(exact_d2(X, d, q, (int)id)) != p64) continue;
+                    if ((unsigned long long)__double_as_longlong(cand_d2(X, d, q, (int)id, probe, tau, pq)) != p64) continue;
                     if ((id & mid) == pid) atomicAdd(&sh.hist[(id >> shift) & 255u], 1u);
                 }
                 __syncthreads();
@@ -672,7 +776,7 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
         for (int pos = tid; pos < M; pos += 256) {
             if (key_bits(src[pos]) != Tf) continue;
             const int id = lorder[list_pos(pos)];
-            const double v = exact_d2(X, d, q, id);
+            const double v = cand_d2(X, d, q, id, probe, tau, pq);
             const unsigned long long db = (unsigned long long)__double_as_longlong(v);
             if (db > p64) continue;
             if (db == p64 && (uint32_t)id > Tid) continue;
@@ -844,8 +948,8 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
 }
 
 // Eq. (10)-(11): neighbour lists of every row of X from the inverted file over the centroids C.
-int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int tau, int k, int32_t *knn_idx,
-                   double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s)
+static int ivf_knn_impl(const float *X, int n, int d, const float *C, int nlist, int tau, int k, int32_t *knn_idx,
+                        double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s, PqView pq)
 {
     IvfLayout L;
     if (ws_bytes < ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0)) return TSNE_ENOSPC;
@@ -902,14 +1006,17 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
         e = hipMemcpyAsync(&tiles, L.tileptr + nlist, 4, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess || tiles <= 0 || tiles == 0x7FFFFFFF) { free(mp); return e != hipSuccess ? TSNE_EHIP : TSNE_ENOSPC; }
-        if (d > IVF_DC)
+        if (pq.codes)
+            hipLaunchKernelGGL(ivfpq_score, dim3(tiles), dim3(IVF_QW * WAVE), 0, s, X, d, L.lorder, L.cellptr, L.probe, tau, nlist,
+                               L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D, pq);
+        else if (d > IVF_DC)
             hipLaunchKernelGGL(ivf_score<true>, dim3(tiles), dim3(IVF_QW * WAVE), chunk_lds(d, IVF_QW), s, X, d, dp, L.Xl, L.lorder,
                                L.cellptr, L.probe, tau, nlist, L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
         else
             hipLaunchKernelGGL(ivf_score<false>, dim3(tiles), dim3(IVF_QW * WAVE), 0, s, X, d, dp, L.Xl, L.lorder,
                                L.cellptr, L.probe, tau, nlist, L.pairptr, L.tileptr, L.pairq, L.pairr, L.mprefix, mp[qb], L.D);
         hipLaunchKernelGGL(ivf_select, dim3(rows), dim3(256), sel_bytes, s, L.D, L.mprefix, mp[qb], qb, tau, k, L.probe,
-                           L.cellptr, L.lorder, X, d, buf, knn_idx, knn_d2);
+                           L.cellptr, L.lorder, X, d, buf, knn_idx, knn_d2, pq);
         qb = qe;
     }
     free(mp);
@@ -917,7 +1024,122 @@ int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int 
     return TSNE_OK;
 }
 
+int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int tau, int k, int32_t *knn_idx,
+                   double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    PqView none;
+    memset(&none, 0, sizeof(none));
+    return ivf_knn_impl(X, n, d, C, nlist, tau, k, knn_idx, knn_d2, ws, ws_bytes, s, none);
+}
+
+// ---- product-quantised second stage
+namespace {
+struct PqLayout {
+    int32_t *list, *nearest;      // q1 of every row; nearest sub-centroid of every row (one sub-quantiser at a time)
+    float *R;                     // residual sub-vectors, n x ds
+    double *cbd;                  // one sub-quantiser's centroids as doubles, ksub x (ds rounded up to 4)
+    double *Cd;                   // the coarse centroids as doubles
+    unsigned char *codes;         // n x m
+    void *inner;                  // workspace of the calls made from here (k-means, the search)
+    size_t inner_bytes;
+};
+
+int pq_check(int n, int d, int nlist, int m, int ksub)
+{
+    if (m < 1 || m > d || d % m != 0 || ksub < 1 || ksub > 256 || ksub > n) return TSNE_EINVAL;
+    if (n < 1 || d < 1 || d > 4096 || nlist < 1 || nlist > n || nlist > 65536) return TSNE_EINVAL;
+    return TSNE_OK;
+}
+
+size_t pq_carve(PqLayout *L, int n, int d, int k, int nlist, int tau, int m, int ksub, char *base, size_t avail)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up256(bytes); return (void *)p; };
+    const int ds = d / m, dsp = (ds + 3) / 4 * 4, dp = (d + 3) / 4 * 4;
+    void *q;
+    q = take(4 * (size_t)n); if (L) L->list = (int32_t *)q;
+    q = take(4 * (size_t)n); if (L) L->nearest = (int32_t *)q;
+    q = take(4 * (size_t)n * ds); if (L) L->R = (float *)q;
+    q = take(8 * (size_t)ksub * dsp); if (L) L->cbd = (double *)q;
+    q = take(8 * (size_t)nlist * dp); if (L) L->Cd = (double *)q;
+    q = take((size_t)n * m); if (L) L->codes = (unsigned char *)q;
+    size_t a = ivf_carve(nullptr, n, ds, ksub, 1, nullptr, 0);            // training a sub-quantiser
+    size_t b = tau > 0 ? ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0) : 0;   // the search
+    (void)k;
+    if (L) { L->inner = base + off; L->inner_bytes = avail > off ? avail - off : 0; }
+    return off + (a > b ? a : b);
+}
+
+// q1 of every row into L.list
+void pq_lists(const float *X, int n, int d, const float *C, int nlist, PqLayout &L, hipStream_t s)
+{
+    const int dp = (d + 3) / 4 * 4;
+    hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
+    launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.list, n, s);
+}
+}  // namespace
+
 extern "C" {
+
+int tsne_ivfpq_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, int32_t m, int32_t ksub,
+                               size_t *bytes)
+{
+    if (!bytes || pq_check(n, d, nlist, m, ksub) != TSNE_OK || ivf_check(n, d, k, nlist, tau) != TSNE_OK) return TSNE_EINVAL;
+    *bytes = pq_carve(nullptr, n, d, k, nlist, tau, m, ksub, nullptr, 0);
+    return TSNE_OK;
+}
+
+int tsne_ivfpq_train(const float *d_X, int32_t n, int32_t d, const float *d_centroids, int32_t nlist, int32_t m,
+                     int32_t ksub, int32_t iters, float *d_codebooks, void *d_workspace, size_t workspace_bytes,
+                     void *stream)
+{
+    if (!d_X || !d_centroids || !d_codebooks || !d_workspace || iters < 0) return TSNE_EINVAL;
+    if (pq_check(n, d, nlist, m, ksub) != TSNE_OK) return TSNE_EINVAL;
+    if (((uintptr_t)d_workspace % IVF_ALIGN) != 0) return TSNE_EINVAL;
+    if (workspace_bytes < pq_carve(nullptr, n, d, 1, nlist, 0, m, ksub, nullptr, 0)) return TSNE_ENOSPC;
+    hipStream_t s = (hipStream_t)stream;
+    PqLayout L;
+    pq_carve(&L, n, d, 1, nlist, 0, m, ksub, (char *)d_workspace, workspace_bytes);
+    const int ds = d / m;
+    pq_lists(d_X, n, d, d_centroids, nlist, L, s);
+    for (int j = 0; j < m; ++j) {
+        hipLaunchKernelGGL(residual_sub, dim3(blocks((size_t)n * ds)), dim3(256), 0, s, d_X, n, d, d_centroids, L.list, j, ds, L.R);
+        const int rc = ivf_train_device(L.R, n, ds, ksub, iters, d_codebooks + (size_t)j * ksub * ds, L.inner, L.inner_bytes, s);
+        if (rc != TSNE_OK) return rc;
+    }
+    IVFCHK(hipStreamSynchronize(s));
+    IVFCHK(hipGetLastError());
+    return TSNE_OK;
+}
+
+int tsne_ivfpq_knn(const float *d_X, int32_t n, int32_t d, const float *d_centroids, int32_t nlist,
+                   const float *d_codebooks, int32_t m, int32_t ksub, int32_t tau, int32_t k, int32_t *d_knn_idx,
+                   double *d_knn_d2, void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!d_X || !d_centroids || !d_codebooks || !d_knn_idx || !d_knn_d2 || !d_workspace) return TSNE_EINVAL;
+    if (pq_check(n, d, nlist, m, ksub) != TSNE_OK || ivf_check(n, d, k, nlist, tau) != TSNE_OK) return TSNE_EINVAL;
+    if (((uintptr_t)d_workspace % IVF_ALIGN) != 0) return TSNE_EINVAL;
+    if (workspace_bytes < pq_carve(nullptr, n, d, k, nlist, tau, m, ksub, nullptr, 0)) return TSNE_ENOSPC;
+    hipStream_t s = (hipStream_t)stream;
+    PqLayout L;
+    pq_carve(&L, n, d, k, nlist, tau, m, ksub, (char *)d_workspace, workspace_bytes);
+    const int ds = d / m, dsp = (ds + 3) / 4 * 4;
+    // codes: for every sub-vector of the residual the nearest centroid of its sub-quantiser
+    pq_lists(d_X, n, d, d_centroids, nlist, L, s);
+    for (int j = 0; j < m; ++j) {
+        hipLaunchKernelGGL(residual_sub, dim3(blocks((size_t)n * ds)), dim3(256), 0, s, d_X, n, d, d_centroids, L.list, j, ds, L.R);
+        hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)ksub * dsp)), dim3(256), 0, s, d_codebooks + (size_t)j * ksub * ds,
+                           (size_t)ksub, ds, dsp, L.cbd);
+        launch_probe(L.R, n, ds, dsp, L.cbd, ksub, 1, L.nearest, n, s);
+        hipLaunchKernelGGL(pack_codes, dim3(blocks((size_t)n)), dim3(256), 0, s, L.nearest, n, j, m, L.codes);
+    }
+    PqView pq;
+    pq.codes = L.codes; pq.cb = d_codebooks; pq.C = d_centroids; pq.m = m; pq.ds = ds; pq.ksub = ksub;
+    const int rc = ivf_knn_impl(d_X, n, d, d_centroids, nlist, tau, k, d_knn_idx, d_knn_d2, L.inner, L.inner_bytes, s, pq);
+    if (rc != TSNE_OK) return rc;
+    IVFCHK(hipStreamSynchronize(s));
+    return TSNE_OK;
+}
 
 int tsne_ivf_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t nlist, int32_t tau, size_t *bytes)
 {

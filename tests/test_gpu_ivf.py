@@ -138,3 +138,84 @@ def test_P_build_takes_more_lists_when_a_row_runs_short():
     assert np.array_equal(P["knn_idx"].cpu().numpy(), idx)
     with pytest.raises(ValueError):
         ivf.ivf_knn(X, C, tau // 2, 30)
+
+
+# ---------------------------------------------------------------------------- product-quantised second stage
+def _pq_case(name):
+    r = np.random.default_rng(3)
+    if name == "blobs_32d_m8":
+        X, _ = synth.gaussian_mixture(4000, 32, 6, 4.0, 1.0, seed=3)
+        return X, 40, 6, 30, 8, 64, 4
+    if name == "full_codebooks":             # 256 centroids a sub-quantiser, sub-vectors of 5
+        X, _ = synth.gaussian_mixture(6000, 20, 5, 3.0, 1.0, seed=5)
+        return X, 25, 5, 40, 4, 256, 3
+    if name == "one_subvector":              # m = 1: q2 is a plain vector quantiser of the residual
+        X = r.standard_normal((1500, 6)).astype(np.float32)
+        return X, 12, 4, 15, 1, 32, 3
+    if name == "scalar_subvectors":          # m = d: one coordinate per sub-quantiser
+        X = r.standard_normal((2000, 8)).astype(np.float32)
+        return X, 10, 10, 20, 8, 16, 3
+    if name == "many_equal_codes":           # few centroids: many candidates share a code and tie exactly (index decides)
+        X, _ = synth.gaussian_mixture(3000, 12, 4, 5.0, 1.0, seed=8)
+        return X, 8, 3, 50, 2, 4, 2
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("name", ["blobs_32d_m8", "full_codebooks", "one_subvector", "scalar_subvectors",
+                                  "many_equal_codes"])
+def test_ivfpq_matches_oracle(name):
+    """Codebooks (k-means per sub-vector of the residuals), codes and the search of Eq. (11) on the codes: the
+    GPU's distances are formed by the same double-precision operations in the same order as the oracle's, so
+    indices and distances must be the oracle's."""
+    from paper_1807_11824_amd import ivfpq_train, ivfpq_knn
+    X, nlist, tau, k, m, ksub, iters = _pq_case(name)
+    print(f"case={name} n={X.shape[0]} d={X.shape[1]} nlist={nlist} tau={tau} k={k} m={m} ksub={ksub}", flush=True)
+    C, _ = ivf.kmeans_train(X, nlist, 4)
+    want_cb = ivf.pq_train(X, C, m, ksub, iters)
+    cb = ivfpq_train(_dev(X), _dev(C), m, ksub, iters)
+    got_cb = cb.cpu().numpy()
+    print("codebooks equal bit for bit:", float(np.mean(got_cb == want_cb)), flush=True)
+    assert np.abs(got_cb - want_cb).max() <= 1e-6 * np.abs(X).max()
+    # the search from the oracle's codebooks (so that a last-bit difference of a centroid cannot move a code)
+    rows = np.arange(0, X.shape[0], 5)
+    want_idx, want_d2 = ivf.ivfpq_knn(X, C, want_cb, tau, k, rows=rows)
+    idx, d2 = ivfpq_knn(_dev(X), _dev(C), _dev(want_cb), tau, k)
+    idx, d2 = idx.cpu().numpy()[rows], d2.cpu().numpy()[rows]
+    assert np.array_equal(idx, want_idx)
+    assert np.array_equal(d2, want_d2)          # same operations, same order: the same bits
+    exact_idx, _ = oracle.knn(X, k, rows=rows.astype(np.int32))
+    print(f"recall at k = {k} against the exact lists: {ivf.recall(idx, exact_idx):.4f}", flush=True)
+
+
+def test_ivfpq_bad_arguments():
+    from paper_1807_11824_amd import ivfpq_train, TsneError
+    X = _dev(np.zeros((100, 6), np.float32))
+    C = _dev(np.zeros((4, 6), np.float32))
+    with pytest.raises(TsneError):
+        ivfpq_train(X, C, 4, 16, 2)           # 6 coordinates do not split into 4 sub-vectors
+    with pytest.raises(TsneError):
+        ivfpq_train(X, C, 2, 300, 2)          # more than 256 centroids
+
+
+def test_P_from_product_quantised_neighbours():
+    """tsne_build_P_approx with pq_m > 0 against the oracle's pieces in the same order: coarse k-means, codebooks,
+    codes and search (Eq. (8), (11)), Eq. (1) on the distances to the codes, symmetric CSR."""
+    from paper_1807_11824_amd import build_P_approx
+    X, _ = synth.gaussian_mixture(3000, 48, 4, 10.0, 1.0, seed=1)
+    nlist, tau, k, perp, iters, m = 55, 8, 45, 15.0, 5, 12
+    C, _ = ivf.kmeans_train(X, nlist, iters)
+    cb = ivf.pq_train(X, C, m, 256, iters)
+    idx, d2 = ivf.ivfpq_knn(X, C, cb, tau, k)
+    cond, _, bad = oracle.cond_p(d2, perp)
+    rp, col, val = oracle.symmetrise(idx, cond)
+    P = build_P_approx(_dev(X), perp, k, tau, nlist=0, kmeans_iters=iters, want_knn=True, pq_m=m)
+    got_idx = P["knn_idx"].cpu().numpy()
+    same_rows = np.mean(np.all(got_idx == idx, axis=1))
+    print(f"rows with identical neighbour lists: {same_rows:.4f}", flush=True)
+    assert same_rows == 1.0
+    assert np.array_equal(P["row_ptr"].cpu().numpy(), rp)
+    assert np.array_equal(P["col"].cpu().numpy(), col)
+    assert np.allclose(P["val"].cpu().numpy(), val, rtol=2e-6, atol=1e-30)
+    assert P["unconverged"] == bad
+    exact_idx, _ = oracle.knn(X, k)
+    print(f"recall at k = {k} against the exact lists: {ivf.recall(got_idx, exact_idx):.4f}", flush=True)
