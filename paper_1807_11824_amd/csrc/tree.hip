@@ -366,8 +366,9 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint64_t *__
     constexpr int NW = SORT_THREADS / WAVE, DPT = RADIX / SORT_THREADS;   // digits per thread
     // per-wave running digit counts, later per-wave starts; once every word knows its place in the
     // locally sorted tile the same memory holds that tile
-    __shared__ __align__(16) unsigned char overlay[SORT_TILE * 8];
-    static_assert(sizeof(uint16_t) * NW * RADIX <= sizeof(overlay), "the counts fit the tile's space");
+    constexpr size_t OVERLAY = sizeof(uint16_t) * NW * RADIX > (size_t)SORT_TILE * 8 ? sizeof(uint16_t) * NW * RADIX
+                                                                                   : (size_t)SORT_TILE * 8;
+    __shared__ __align__(16) unsigned char overlay[OVERLAY];
     uint16_t (*whist)[RADIX] = reinterpret_cast<uint16_t (*)[RADIX]>(overlay);
     uint64_t *sorted = reinterpret_cast<uint64_t *>(overlay);
     __shared__ uint32_t gbase[RADIX];       // global start of (digit, this tile)

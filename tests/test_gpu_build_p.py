@@ -128,3 +128,14 @@ def test_bad_arguments():
         build_P(X, 3.0, 10)        # k must be < n
     with pytest.raises(TsneError):
         build_P(X, 9.0, 5)         # perplexity must be <= k
+
+
+@pytest.mark.parametrize("clusters,scale", [(300, 3.0), (1, 0.0)])
+def test_many_long_rows_sampled(clusters, scale):
+    """200,001 rows of 96 coordinates (the general tile kernel, several query blocks, a ragged last tile):
+    clustered data and a single Gaussian blob, sampled rows against the oracle."""
+    n, d, k = 200_001, 96, 60
+    X, _ = synth.gaussian_mixture(n, d, clusters, scale, 1.0, seed=11)
+    rows = np.sort(np.random.default_rng(2).choice(n, 192, replace=False).astype(np.int32))
+    rows[0], rows[-1] = 0, n - 1
+    _check_against_oracle(X, 20.0, k, rows=np.unique(rows))
