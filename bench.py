@@ -172,6 +172,9 @@ def main():
     ap.add_argument("--overlap", type=int, default=1)
     ap.add_argument("--leaf-cap", type=int, default=8)
     ap.add_argument("--no-full-run", action="store_true", help="skip the separate 1000-iteration run (profiling)")
+    ap.add_argument("--P-cache", default="",
+                    help="profiling aid: a path prefix; if <prefix>.npz exists P is loaded from it (X is neither drawn "
+                         "nor searched, build_P_s is reported as null), otherwise P is built as usual and saved there")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark: the paper's synthetic scaling workload (50-d, 4 Gaussian clusters, "
                          "Sec. IV-B) at N = 500 ... 5M, one JSON line per N")
@@ -198,35 +201,51 @@ def main():
         sweep(dev, args.overlap, [int(v) for v in args.sweep_n.split(",")], args.sweep_iters, args.reorder_every,
               args.sweep_approx_tau)
         return
-    X, cfg = workload_inputs(args.workload)
-    n, k, perp = cfg["n"], cfg["k"], cfg["perplexity"]
-    Xd = torch.from_numpy(X).to(dev)
-    torch.cuda.synchronize()
-    t0 = time.time()
-    P = build_P(Xd, perp, k, want_knn=args.approx_tau > 0)
-    torch.cuda.synchronize()
-    t_build = time.time() - t0
-    nnz = P["nnz"]
+    cache = args.P_cache + ".npz" if args.P_cache else ""
     approx = None
-    if args.approx_tau > 0:
-        # (not part of the timed steps, which use the exact P: the alternative first phase, timed beside it)
-        from paper_1807_11824_amd import build_P_approx
-        try:
-            t0 = time.time()
-            Pa = build_P_approx(Xd, perp, k, args.approx_tau, nlist=0, kmeans_iters=10, want_knn=True)
-            torch.cuda.synchronize()
-            t_approx = time.time() - t0
-            rows = torch.randperm(n, device=dev, generator=torch.Generator(device=dev).manual_seed(0))[:20000]
-            hit = (Pa["knn_idx"][rows].long()[:, :, None] == P["knn_idx"][rows].long()[:, None, :]).any(-1)
-            approx = {"tau": args.approx_tau, "tau_used": Pa["tau_used"], "nlist": int(round(n ** 0.5)), "kmeans_iters": 10,
-                      "build_P_approx_s": t_approx,
-                      "recall_at_k": float(hit.float().mean().item()), "rows_sampled": int(rows.numel()), "nnz": Pa["nnz"]}
-            del Pa, hit
-        except Exception as e:      # the side measurement must not take the benchmark down with it
-            approx = {"tau": args.approx_tau, "error": repr(e)}
-    P["knn_idx"] = P["knn_d2"] = None
-    del Xd
-    torch.cuda.empty_cache()
+    if cache and os.path.exists(cache):
+        from paper_1807_11824_amd import synth as _synth
+        cfg = dict(_synth.CONFIGS["cfg5" if args.workload == "cfg5_standin" else args.workload])
+        cfg["d_used"] = STANDIN_D if args.workload == "cfg5_standin" else cfg["d"]
+        n, k, perp = cfg["n"], cfg["k"], cfg["perplexity"]
+        with np.load(cache) as z:
+            P = dict(row_ptr=torch.from_numpy(z["row_ptr"]).to(dev), col=torch.from_numpy(z["col"]).to(dev),
+                     val=torch.from_numpy(z["val"]).to(dev))
+        P["nnz"] = int(P["col"].numel())
+        X, t_build = None, None
+        nnz = P["nnz"]
+    else:
+        X, cfg = workload_inputs(args.workload)
+        n, k, perp = cfg["n"], cfg["k"], cfg["perplexity"]
+        Xd = torch.from_numpy(X).to(dev)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        P = build_P(Xd, perp, k, want_knn=args.approx_tau > 0)
+        torch.cuda.synchronize()
+        t_build = time.time() - t0
+        nnz = P["nnz"]
+        if cache:
+            np.savez(cache, row_ptr=P["row_ptr"].cpu().numpy(), col=P["col"].cpu().numpy(), val=P["val"].cpu().numpy())
+        if args.approx_tau > 0:
+            # (not part of the timed steps, which use the exact P: the alternative first phase, timed beside it)
+            from paper_1807_11824_amd import build_P_approx
+            try:
+                t0 = time.time()
+                Pa = build_P_approx(Xd, perp, k, args.approx_tau, nlist=0, kmeans_iters=10, want_knn=True)
+                torch.cuda.synchronize()
+                t_approx = time.time() - t0
+                rows = torch.randperm(n, device=dev, generator=torch.Generator(device=dev).manual_seed(0))[:20000]
+                hit = (Pa["knn_idx"][rows].long()[:, :, None] == P["knn_idx"][rows].long()[:, None, :]).any(-1)
+                approx = {"tau": args.approx_tau, "tau_used": Pa["tau_used"], "nlist": int(round(n ** 0.5)),
+                          "kmeans_iters": 10, "second_stage": "flat", "build_P_approx_s": t_approx,
+                          "recall_at_k": float(hit.float().mean().item()), "rows_sampled": int(rows.numel()),
+                          "nnz": Pa["nnz"]}
+                del Pa, hit
+            except Exception as e:      # the side measurement must not take the benchmark down with it
+                approx = {"tau": args.approx_tau, "error": repr(e)}
+        P["knn_idx"] = P["knn_d2"] = None
+        del Xd
+        torch.cuda.empty_cache()
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -293,7 +312,7 @@ def main():
                 "iterations_per_s_at_iter_900": 1e3 / chunk_ms[18], "iterations_per_s_whole_run": 1000.0 / t_run,
                 "ms_per_iteration_by_chunk_of_50": [round(v, 4) for v in chunk_ms],
                 "cells_at_end": ts.n_cells(),
-                "end_to_end_s": t_build + t_setp + t_run}
+                "end_to_end_s": (t_build + t_setp + t_run) if t_build is not None else None}
         del Yr
 
     # roofline of the dominant HBM kernels: the attraction streams its private copy of P once (6 bytes per stored

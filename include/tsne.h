@@ -50,7 +50,7 @@ typedef enum {
 #define TSNE_GROUP 64
 
 typedef struct {
-    int32_t n;                    /* number of points, >= 1 */
+    int32_t n;                    /* number of points, 1 .. 2^27 */
     float theta;                  /* Eq. (14) threshold; 0 <= theta <= 0.7; 0 = all pairs */
     float lr;                     /* learning rate (200) */
     float exaggeration;           /* factor on the attractive term early on (12) */

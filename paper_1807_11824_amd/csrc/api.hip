@@ -116,7 +116,8 @@ int index_bits(int64_t n)
 int check_params(const tsne_params *p)
 {
     if (!p) return TSNE_EINVAL;
-    if (p->n < 1 || p->n > (1 << 30)) return TSNE_EINVAL;
+    // (several kernels run 16 lanes per point in one launch, and a launch axis holds fewer than 2^32 work-items)
+    if (p->n < 1 || p->n > (1 << 27)) return TSNE_EINVAL;
     if (!(p->theta >= 0.0f) || p->theta > 0.7f) return TSNE_EINVAL;
     if (p->morton_bits < 1 || p->morton_bits > MAX_GRID_BITS) return TSNE_EINVAL;
     // a point's grid key and its number share one 64-bit word in the sort

@@ -92,8 +92,9 @@ __global__ __launch_bounds__(256) void col_mean_final(const double *__restrict__
 __global__ __launch_bounds__(256) void row_norms(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
                                                  float *__restrict__ norms)
 {
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= n) return;
+    const size_t w = global_index() >> 6;
+    if (w >= (size_t)n) return;
+    const int row = (int)w;
     const float *x = X + (size_t)row * d;
     double s = 0.0;
     for (int t = lane_id(); t < d; t += WAVE) { double v = (double)(x[t] - mu[t]); s += v * v; }
@@ -134,7 +135,7 @@ __device__ __forceinline__ uint32_t bf16_rne(float x)
 __global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
                                                   int dp, uint16_t *__restrict__ Xs)
 {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t e = global_index();
     if (e >= (size_t)n * dp) return;
     const size_t row = e / dp;
     const int k = (int)(e % dp);
@@ -732,8 +733,9 @@ constexpr int EXACT_MAX_D = 4096;
 __global__ __launch_bounds__(256) void knn_exact_dists(const float *__restrict__ X, int n, int d,
                                                        const int *__restrict__ rows, int nb, uint64_t *__restrict__ okey)
 {
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= n) return;
+    const size_t w = global_index() >> 6;
+    if (w >= (size_t)n) return;
+    const int j = (int)w;
     const float *y = X + (size_t)j * d;
     float yr[EXACT_MAX_D / WAVE];
 #pragma unroll
@@ -916,7 +918,7 @@ __global__ __launch_bounds__(64) void perplexity_search(const double *__restrict
 __global__ __launch_bounds__(256) void sym_count(const int32_t *__restrict__ idx, int n, int k, int *__restrict__ extra,
                                                  int16_t *__restrict__ slot)
 {
-    const size_t e = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const size_t e = global_index() >> 4;
     const int sub = (int)(threadIdx.x & 15u), grp = (int)((threadIdx.x & 63u) >> 4);
     const bool live = e < (size_t)n * k;
     const size_t ee = live ? e : 0;
@@ -969,7 +971,7 @@ __global__ __launch_bounds__(256) void sym_fill(const int32_t *__restrict__ idx,
                                                 const int16_t *__restrict__ slots, int32_t *__restrict__ col,
                                                 float *__restrict__ val)
 {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t e = global_index();
     if (e >= (size_t)n * k) return;
     const int i = (int)(e / k), a = (int)(e % k), j = idx[e];
     const double pji = cond[e];
@@ -991,8 +993,8 @@ __global__ __launch_bounds__(256) void sym_sort_rows(const int32_t *__restrict__
                                                      float *__restrict__ val, uint64_t *__restrict__ scratch)
 {
     __shared__ uint64_t s[SORT_CAP];
-    const int row = blockIdx.x;
-    if (row >= n) return;
+    if (global_block() >= (size_t)n) return;
+    const int row = (int)global_block();
     const int b = row_ptr[row], len = row_ptr[row + 1] - b;
     if (len <= 1) return;
     if (len <= SORT_CAP) {
@@ -1037,7 +1039,7 @@ __global__ void max_norm_k(const float *__restrict__ norms, int n, float *__rest
 
 __global__ void d2_to_float(const double *__restrict__ in, float *__restrict__ out, size_t m)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t i = global_index();
     if (i < m) out[i] = (float)in[i];
 }
 
@@ -1133,18 +1135,18 @@ static int finish_P(const Layout &L, int32_t n, int32_t k, float perplexity, int
     // (the candidate buffers are free by now and hold 2 n k bytes with room to spare: 2 n k < 2^31 <= 8 * 65536 * 4160
     // for a full query block, and 2 k < 8 * 4160 for a short one)
     int16_t *slots = reinterpret_cast<int16_t *>(L.cand);
-    hipLaunchKernelGGL(sym_count, dim3((unsigned)((nk * 16 + 255) / 256)), dim3(256), 0, s, L.knn_idx, n, k, L.extra, slots);
+    hipLaunchKernelGGL(sym_count, wide_grid(nk * 16), dim3(256), 0, s, L.knn_idx, n, k, L.extra, slots);
     hipLaunchKernelGGL(sym_scan, dim3(1), dim3(1024), 0, s, L.extra, n, k, d_row_ptr, L.cursor);
     int32_t total = 0;
     HIPCHK(hipMemcpyAsync(&total, d_row_ptr + n, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     if ((int64_t)total > cap_nnz) return TSNE_ENOSPC;
-    hipLaunchKernelGGL(sym_fill, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_idx, L.cond, n, k, d_row_ptr,
+    hipLaunchKernelGGL(sym_fill, wide_grid(nk), dim3(256), 0, s, L.knn_idx, L.cond, n, k, d_row_ptr,
                        L.cursor, slots, d_col, d_val);
-    hipLaunchKernelGGL(sym_sort_rows, dim3(n), dim3(256), 0, s, d_row_ptr, n, d_col, d_val, L.sort_scratch);
+    hipLaunchKernelGGL(sym_sort_rows, wide_grid((size_t)n * 256), dim3(256), 0, s, d_row_ptr, n, d_col, d_val, L.sort_scratch);
     if (d_knn_idx) HIPCHK(hipMemcpyAsync(d_knn_idx, L.knn_idx, 4 * nk, hipMemcpyDeviceToDevice, s));
     if (d_knn_d2)
-        hipLaunchKernelGGL(d2_to_float, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, L.knn_d2, d_knn_d2, nk);
+        hipLaunchKernelGGL(d2_to_float, wide_grid(nk), dim3(256), 0, s, L.knn_d2, d_knn_d2, nk);
     int unconv = 0;
     HIPCHK(hipMemcpyAsync(&unconv, L.unconv, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
@@ -1172,8 +1174,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks = (n + rows_per_chunk - 1) / rows_per_chunk;
     hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks), dim3(256), 0, s, d_X, n, d, rows_per_chunk, L.mu_part);
     hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks, n, d, dp, L.mu);
-    hipLaunchKernelGGL(row_norms, dim3((n + 3) / 4), dim3(256), 0, s, d_X, L.mu, n, d, L.norms);
-    hipLaunchKernelGGL(split_bf16, dim3((unsigned)(((size_t)n * dp + 255) / 256)), dim3(256), 0, s, d_X, L.mu, n, d, dp, L.xs);
+    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, L.mu, n, d, L.norms);
+    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, d_X, L.mu, n, d, dp, L.xs);
     hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms, n, L.norm_max);
     HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
     HIPCHK(hipMemsetAsync(L.unconv, 0, 4, s));
@@ -1243,7 +1245,7 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     // rows a launch (their n keys each fit the space the symmetrisation sorts in later, 2 n k words).
     for (int f0 = 0; f0 < nfail; f0 += 2 * k) {
         const int nb = nfail - f0 < 2 * k ? nfail - f0 : 2 * k;
-        hipLaunchKernelGGL(knn_exact_dists, dim3((n + 3) / 4), dim3(256), 0, s, d_X, n, d, L.fail_rows + f0, nb,
+        hipLaunchKernelGGL(knn_exact_dists, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, n, d, L.fail_rows + f0, nb,
                            L.sort_scratch);
         hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, L.sort_scratch, n, k, L.fail_rows + f0, L.knn_idx,
                            L.knn_d2);

@@ -206,7 +206,7 @@ attract_near(const int32_t *__restrict__ rp, const uint4 *__restrict__ col8, con
         // one interaction; o = byte offset of y_j in the ring
 #define AN_ONE(o, p)                                                                     \
         {                                                                                \
-            const float2 yj_ = *reinterpret_cast<const float2 *>(ringb + min((o), (unsigned)(AN_S - 1) * 8u)); \
+            const float2 yj_ = *reinterpret_cast<const float2 *>(ringb + (o));   /* 8 (column mod ring) < 8 AN_S by construction */ \
             const float dx = yi.x - yj_.x, dy = yi.y - yj_.y;                            \
             const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));     \
             const float pw = (p) * w;                                                    \

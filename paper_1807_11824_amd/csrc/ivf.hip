@@ -44,7 +44,7 @@ constexpr size_t IVF_D_MAX = (size_t)8 << 30;   // bytes of key scratch used at 
 // rows of d floats -> rows of dp doubles (dp = d rounded up to a multiple of four, the rest zero)
 __global__ void to_double_k(const float *__restrict__ in, size_t rows, int d, int dp, double *__restrict__ out)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t i = global_index();
     if (i >= rows * dp) return;
     const size_t r = i / dp;
     const int t = (int)(i % dp);
@@ -53,13 +53,13 @@ __global__ void to_double_k(const float *__restrict__ in, size_t rows, int d, in
 
 __global__ void fill_i32_k(int *__restrict__ a, int v, size_t m)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t i = global_index();
     if (i < m) a[i] = v;
 }
 
 __global__ void fill_u64_k(unsigned long long *__restrict__ a, size_t m)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t i = global_index();
     if (i < m) a[i] = 0ull;
 }
 
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(1024) void fps_argmax(const double *__restrict__ mi
 __global__ void fps_gather(const float *__restrict__ X, int n, int d, int m, int nlist, const int *__restrict__ sel,
                            float *__restrict__ C)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t i = global_index();
     if (i >= (size_t)nlist * d) return;
     const int c = (int)(i / d), t = (int)(i % d);
     C[i] = X[(size_t)sample_row(sel[c], n, m) * d + t];
@@ -121,7 +121,7 @@ __global__ void fps_gather(const float *__restrict__ X, int n, int d, int m, int
 __global__ void max_abs_k(const float *__restrict__ X, size_t m, unsigned int *__restrict__ out)
 {
     float v = 0.f;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < m; i += (size_t)gridDim.x * blockDim.x)
+    for (size_t i = global_index(); i < m; i += (size_t)gridDim.x * blockDim.x)
         v = fmaxf(v, fabsf(X[i]));
     v = wave_max(v);
     if (lane_id() == 0) atomicMax(out, __float_as_uint(v));   // non-negative floats order like their bits
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(64) void ivf_probe(const float *__restrict__ X, int
 __global__ void kmeans_accum(const float *__restrict__ X, int n, int d, const int32_t *__restrict__ probe, int tau,
                              double scale, unsigned long long *__restrict__ sums, int *__restrict__ counts, int m)
 {
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t idx = global_index();
     if (idx >= (size_t)m * d) return;
     const int i = (int)(idx / d), t = (int)(idx % d);
     const int c = probe[(size_t)i * tau];
@@ -272,7 +272,7 @@ __global__ void kmeans_accum(const float *__restrict__ X, int n, int d, const in
 __global__ void kmeans_finish(const unsigned long long *__restrict__ sums, const int *__restrict__ counts, int nlist,
                               int d, double inv_scale, float *__restrict__ C)
 {
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t idx = global_index();
     if (idx >= (size_t)nlist * d) return;
     const int cnt = counts[idx / d];
     if (cnt > 0) C[idx] = (float)((double)(long long)sums[idx] * inv_scale / (double)cnt);   // an empty cell keeps its centroid
@@ -337,7 +337,7 @@ __global__ void cell_scatter(const int32_t *__restrict__ probe, int n, int tau, 
 __global__ void gather_double(const float *__restrict__ X, int n, int d, int dp, const int *__restrict__ lorder,
                               double *__restrict__ Xl)
 {
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t idx = global_index();
     if (idx >= (size_t)n * dp) return;
     const size_t pos = idx / dp;
     const int t = (int)(idx % dp);
@@ -360,7 +360,7 @@ __global__ void msize_k(const int32_t *__restrict__ probe, int n, int tau, const
 
 __global__ void pair_hist(const int32_t *__restrict__ probe, int qb, int rows, int tau, int *__restrict__ bcnt)
 {
-    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t p = global_index();
     if (p < (size_t)rows * tau) atomicAdd(&bcnt[probe[(size_t)qb * tau + p]], 1);
 }
 
@@ -368,7 +368,7 @@ __global__ void pair_scatter(const int32_t *__restrict__ probe, int qb, int rows
                              const int *__restrict__ pairptr, int *__restrict__ bcur, int *__restrict__ pairq,
                              unsigned char *__restrict__ pairr)
 {
-    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t p = global_index();
     if (p >= (size_t)rows * tau) return;
     const int B = probe[(size_t)qb * tau + p];
     const int pos = pairptr[B] + atomicAdd(&bcur[B], 1);
@@ -516,7 +516,7 @@ __device__ __forceinline__ double cand_d2(const float *__restrict__ X, int d, in
 __global__ void residual_sub(const float *__restrict__ X, int n, int d, const float *__restrict__ C,
                              const int32_t *__restrict__ list, int j, int ds, float *__restrict__ R)
 {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t e = global_index();
     if (e >= (size_t)n * ds) return;
     const size_t i = e / ds;
     const int t = (int)(e % ds);
@@ -830,7 +830,7 @@ size_t select_lds(int k, int buf) { return 12 * (size_t)(k + buf) + 8 * (size_t)
         }                                                 \
     } while (0)
 
-inline unsigned blocks(size_t m, int per = 256) { return (unsigned)((m + per - 1) / per); }
+inline dim3 blocks(size_t m) { return wide_grid(m); }
 
 struct IvfLayout {
     double *Cd, *Xl;
@@ -917,7 +917,7 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
             hipLaunchKernelGGL(fps_update, dim3((m + 3) / 4), dim3(256), 0, s, X, n, d, m, L.sel, c - 1, L.mind, c == 1 ? 1 : 0);
             hipLaunchKernelGGL(fps_argmax, dim3(1), dim3(1024), 0, s, L.mind, m, L.sel, c);
         }
-        hipLaunchKernelGGL(fps_gather, dim3(blocks(cd)), dim3(256), 0, s, X, n, d, m, nlist, L.sel, C);
+        hipLaunchKernelGGL(fps_gather, (blocks(cd)), dim3(256), 0, s, X, n, d, m, nlist, L.sel, C);
     }
     IVFCHK(hipMemsetAsync(L.maxabs, 0, 4, s));
     hipLaunchKernelGGL(max_abs_k, dim3(1024), dim3(256), 0, s, X, nd, L.maxabs);
@@ -935,13 +935,13 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     // the rounds work on min(n, 256 nlist) evenly spaced rows
     const int ms = (long long)n < 256ll * nlist ? n : 256 * nlist;
     for (int it = 0; it < iters; ++it) {
-        hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
+        hipLaunchKernelGGL(to_double_k, (blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
         launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, ms, s);
-        hipLaunchKernelGGL(fill_u64_k, dim3(blocks(cd)), dim3(256), 0, s, L.sums, cd);
-        hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist);
-        hipLaunchKernelGGL(kmeans_accum, dim3(blocks((size_t)ms * d)), dim3(256), 0, s, X, n, d, L.probe, 1, scale, L.sums, L.cnt,
+        hipLaunchKernelGGL(fill_u64_k, (blocks(cd)), dim3(256), 0, s, L.sums, cd);
+        hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist);
+        hipLaunchKernelGGL(kmeans_accum, (blocks((size_t)ms * d)), dim3(256), 0, s, X, n, d, L.probe, 1, scale, L.sums, L.cnt,
                            ms);
-        hipLaunchKernelGGL(kmeans_finish, dim3(blocks(cd)), dim3(256), 0, s, L.sums, L.cnt, nlist, d, inv_scale, C);
+        hipLaunchKernelGGL(kmeans_finish, (blocks(cd)), dim3(256), 0, s, L.sums, L.cnt, nlist, d, inv_scale, C);
     }
     IVFCHK(hipGetLastError());
     return TSNE_OK;
@@ -955,16 +955,16 @@ static int ivf_knn_impl(const float *X, int n, int d, const float *C, int nlist,
     if (ws_bytes < ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0)) return TSNE_ENOSPC;
     ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes);
     const int dp = (d + 3) / 4 * 4;
-    hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
+    hipLaunchKernelGGL(to_double_k, (blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
     launch_probe(X, n, d, dp, L.Cd, nlist, tau, L.probe, n, s);
-    hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist + 1);
-    hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cursor, 0, (size_t)nlist + 1);
-    hipLaunchKernelGGL(cell_hist, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cnt);
+    hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist + 1);
+    hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cursor, 0, (size_t)nlist + 1);
+    hipLaunchKernelGGL(cell_hist, (blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cnt);
     hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.cnt, nlist, (long long *)nullptr, L.cellptr, (int *)nullptr,
                        (const int *)nullptr);
-    hipLaunchKernelGGL(cell_scatter, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.cursor, L.lorder);
-    hipLaunchKernelGGL(gather_double, dim3(blocks((size_t)n * dp)), dim3(256), 0, s, X, n, d, dp, L.lorder, L.Xl);
-    hipLaunchKernelGGL(msize_k, dim3(blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.msize);
+    hipLaunchKernelGGL(cell_scatter, (blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.cursor, L.lorder);
+    hipLaunchKernelGGL(gather_double, (blocks((size_t)n * dp)), dim3(256), 0, s, X, n, d, dp, L.lorder, L.Xl);
+    hipLaunchKernelGGL(msize_k, (blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cellptr, L.msize);
     hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.msize, n, L.mprefix, (int *)nullptr, (int *)nullptr,
                        (const int *)nullptr);
     long long *mp = (long long *)malloc(8 * ((size_t)n + 1));
@@ -995,12 +995,12 @@ static int ivf_knn_impl(const float *X, int n, int d, const float *C, int nlist,
         while (qe < n && qe - qb < IVF_BATCH_ROWS && mp[qe + 1] - mp[qb] <= d_cap) ++qe;
         const int rows = qe - qb;
         const size_t pairs = (size_t)rows * tau;
-        hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcnt, 0, (size_t)nlist + 1);
-        hipLaunchKernelGGL(fill_i32_k, dim3(blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcur, 0, (size_t)nlist + 1);
-        hipLaunchKernelGGL(pair_hist, dim3(blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.bcnt);
+        hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcnt, 0, (size_t)nlist + 1);
+        hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist + 1)), dim3(256), 0, s, L.bcur, 0, (size_t)nlist + 1);
+        hipLaunchKernelGGL(pair_hist, (blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.bcnt);
         hipLaunchKernelGGL(scan_counts, dim3(1), dim3(1024), 0, s, L.bcnt, nlist, (long long *)nullptr, L.pairptr, L.tileptr,
                            L.cellptr);
-        hipLaunchKernelGGL(pair_scatter, dim3(blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.pairptr, L.bcur,
+        hipLaunchKernelGGL(pair_scatter, (blocks(pairs)), dim3(256), 0, s, L.probe, qb, rows, tau, L.pairptr, L.bcur,
                            L.pairq, L.pairr);
         int tiles = 0;
         e = hipMemcpyAsync(&tiles, L.tileptr + nlist, 4, hipMemcpyDeviceToHost, s);
@@ -1074,7 +1074,7 @@ size_t pq_carve(PqLayout *L, int n, int d, int k, int nlist, int tau, int m, int
 void pq_lists(const float *X, int n, int d, const float *C, int nlist, PqLayout &L, hipStream_t s)
 {
     const int dp = (d + 3) / 4 * 4;
-    hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
+    hipLaunchKernelGGL(to_double_k, (blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
     launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.list, n, s);
 }
 }  // namespace
@@ -1103,7 +1103,7 @@ int tsne_ivfpq_train(const float *d_X, int32_t n, int32_t d, const float *d_cent
     const int ds = d / m;
     pq_lists(d_X, n, d, d_centroids, nlist, L, s);
     for (int j = 0; j < m; ++j) {
-        hipLaunchKernelGGL(residual_sub, dim3(blocks((size_t)n * ds)), dim3(256), 0, s, d_X, n, d, d_centroids, L.list, j, ds, L.R);
+        hipLaunchKernelGGL(residual_sub, (blocks((size_t)n * ds)), dim3(256), 0, s, d_X, n, d, d_centroids, L.list, j, ds, L.R);
         const int rc = ivf_train_device(L.R, n, ds, ksub, iters, d_codebooks + (size_t)j * ksub * ds, L.inner, L.inner_bytes, s);
         if (rc != TSNE_OK) return rc;
     }
@@ -1127,11 +1127,11 @@ int tsne_ivfpq_knn(const float *d_X, int32_t n, int32_t d, const float *d_centro
     // codes: for every sub-vector of the residual the nearest centroid of its sub-quantiser
     pq_lists(d_X, n, d, d_centroids, nlist, L, s);
     for (int j = 0; j < m; ++j) {
-        hipLaunchKernelGGL(residual_sub, dim3(blocks((size_t)n * ds)), dim3(256), 0, s, d_X, n, d, d_centroids, L.list, j, ds, L.R);
-        hipLaunchKernelGGL(to_double_k, dim3(blocks((size_t)ksub * dsp)), dim3(256), 0, s, d_codebooks + (size_t)j * ksub * ds,
+        hipLaunchKernelGGL(residual_sub, (blocks((size_t)n * ds)), dim3(256), 0, s, d_X, n, d, d_centroids, L.list, j, ds, L.R);
+        hipLaunchKernelGGL(to_double_k, (blocks((size_t)ksub * dsp)), dim3(256), 0, s, d_codebooks + (size_t)j * ksub * ds,
                            (size_t)ksub, ds, dsp, L.cbd);
         launch_probe(L.R, n, ds, dsp, L.cbd, ksub, 1, L.nearest, n, s);
-        hipLaunchKernelGGL(pack_codes, dim3(blocks((size_t)n)), dim3(256), 0, s, L.nearest, n, j, m, L.codes);
+        hipLaunchKernelGGL(pack_codes, (blocks((size_t)n)), dim3(256), 0, s, L.nearest, n, j, m, L.codes);
     }
     PqView pq;
     pq.codes = L.codes; pq.cb = d_codebooks; pq.C = d_centroids; pq.m = m; pq.ds = ds; pq.ksub = ksub;

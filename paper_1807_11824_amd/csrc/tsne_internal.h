@@ -167,6 +167,22 @@ hipError_t launch_export_cells(tsne_ctx *c, int32_t cap, int32_t *depth, int32_t
 hipError_t launch_kl(tsne_ctx *c, const float *d_Y, hipStream_t s);  // result in c->kl_part[0]
 
 // ---- wave helpers ----
+// One axis of a launch holds fewer than 2^32 work-items: the dispatch packet counts them in 32 bits, and a larger
+// product of workgroups and workgroup size wraps without any error.  Launches with one work-item (or a few) per
+// element of a large array therefore spread their workgroups over two axes, and the kernel takes its element
+// number from global_index().  Along x at most 2^23 workgroups of at most 256, so any count below 2^31 stays on x.
+inline dim3 wide_grid(size_t items, int per = 256)
+{
+    const size_t nb = (items + (size_t)per - 1) / (size_t)per, gx = (size_t)1 << 23;
+    if (nb <= gx) return dim3((unsigned)(nb > 0 ? nb : 1));
+    return dim3((unsigned)gx, (unsigned)((nb + gx - 1) / gx));
+}
+__device__ __forceinline__ size_t global_block() { return (size_t)blockIdx.y * gridDim.x + blockIdx.x; }
+__device__ __forceinline__ size_t global_index()
+{
+    return ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+}
+
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
 
 __device__ __forceinline__ uint64_t lanemask_lt()

@@ -70,8 +70,10 @@ def test_host_side_validation(L):
     assert L.tsne_workspace_bytes(C.byref(q), C.byref(b)) == -1
     L.tsne_default_params(C.byref(q), 1 << 20)
     assert q.morton_bits == 22
-    L.tsne_default_params(C.byref(q), 1 << 29)
-    assert q.morton_bits == 17 and L.tsne_workspace_bytes(C.byref(q), C.byref(b)) == 0
+    L.tsne_default_params(C.byref(q), 1 << 27)
+    assert q.morton_bits == 18 and L.tsne_workspace_bytes(C.byref(q), C.byref(b)) == 0
+    L.tsne_default_params(C.byref(q), (1 << 27) + 1)      # more points than one launch axis holds at 16 lanes each
+    assert L.tsne_workspace_bytes(C.byref(q), C.byref(b)) == -1
     # the call for callers that cannot allocate refuses sizes beyond its limit before touching the GPU
     assert L.tsne_kl_static(C.c_void_p(256), (1 << 22) + 1, C.c_void_p(256), None, None, C.c_void_p(256), None) == -1
     assert L.tsne_kl_static(C.c_void_p(256), 0, C.c_void_p(256), None, None, C.c_void_p(256), None) == -1

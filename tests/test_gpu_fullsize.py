@@ -38,8 +38,8 @@ def _check_rows(built, n_rows, seed):
     assert bad == 0 and P["unconverged"] == 0
     rp = P["row_ptr"].cpu().numpy(); col = P["col"].cpu().numpy(); val = P["val"].cpu().numpy()
     assert n * k <= P["nnz"] <= 2 * n * k and rp[-1] == P["nnz"]
-    assert abs(val.astype(np.float64).sum() - 1.0) < 1e-4
-    assert np.all(np.diff(rp) >= k)
+    assert abs(val.astype(np.float64).sum() - 1.0) < 1e-4 and val.min() > 0
+    assert np.all(np.diff(rp) >= k) and col.min() >= 0 and col.max() < n
     # sampled rows: columns ascending, value = (p_j|i + p_i|j) / 2N for the oracle's conditionals, symmetric partner
     for r, i in enumerate(rows):
         c = col[rp[i]:rp[i + 1]]; v = val[rp[i]:rp[i + 1]]
@@ -62,6 +62,19 @@ def test_knn_rows_and_P_invariants_as_stated():
     neighbour lists of sampled rows against the oracle's double-precision search over all rows, and P's invariants."""
     built = _build("cfg5")
     _check_rows(built, 40, 3)
+
+
+def test_P_where_one_launch_axis_is_too_short():
+    """N k = 2.9e8 edges: at sixteen lanes an edge the symmetrisation needs more than 2^32 work-items, which one
+    axis of a launch cannot hold (the count would wrap silently and leave most edges out).  Sampled rows against
+    the oracle, the sum of P, positive values and bitwise symmetric partners."""
+    import torch
+    from paper_1807_11824_amd import build_P, synth
+    n, d, k = 3_200_000, 16, 90
+    assert n * k * 16 > 2 ** 32
+    X, _ = synth.gaussian_mixture(n, d, 4, 10.0, 1.0, seed=5)
+    P = build_P(torch.from_numpy(X).to("cuda:0"), 30.0, k, want_knn=True)
+    _check_rows(dict(X=X, cfg=dict(n=n, k=k, perplexity=30.0), P=P), 24, 7)
 
 
 def test_forces_in_bench_configuration(full):
