@@ -89,13 +89,14 @@ __global__ __launch_bounds__(256) void col_mean_final(const double *__restrict__
 }
 
 // |x - mu|^2 of the centred row as the tiles see it (each x_t - mu_t rounded to float)
+// (rowmap: row r of the result is row rowmap[r] of X; null = the same rows)
 __global__ __launch_bounds__(256) void row_norms(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
-                                                 float *__restrict__ norms)
+                                                 const int *__restrict__ rowmap, float *__restrict__ norms)
 {
     const size_t w = global_index() >> 6;
     if (w >= (size_t)n) return;
     const int row = (int)w;
-    const float *x = X + (size_t)row * d;
+    const float *x = X + (size_t)(rowmap ? min(max(rowmap[row], 0), n - 1) : row) * d;
     double s = 0.0;
     for (int t = lane_id(); t < d; t += WAVE) { double v = (double)(x[t] - mu[t]); s += v * v; }
     s = wave_sum(s);
@@ -133,13 +134,14 @@ __device__ __forceinline__ uint32_t bf16_rne(float x)
 }
 
 __global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
-                                                  int dp, uint16_t *__restrict__ Xs)
+                                                  int dp, const int *__restrict__ rowmap, uint16_t *__restrict__ Xs)
 {
     const size_t e = global_index();
     if (e >= (size_t)n * dp) return;
     const size_t row = e / dp;
     const int k = (int)(e % dp);
-    const float x = k < d ? X[row * d + k] - mu[k] : 0.f;
+    const size_t src = rowmap ? (size_t)min(max(rowmap[row], 0), n - 1) : row;
+    const float x = k < d ? X[src * d + k] - mu[k] : 0.f;
     const uint32_t hi = bf16_rne(x);
     const uint32_t lo = bf16_rne(x - __uint_as_float(hi << 16));      // the difference is exact in fp32
     uint16_t *o = Xs + row * dp * 2 + (size_t)(k / SLAB) * (2 * SLAB) + (k % SLAB);
@@ -200,11 +202,12 @@ __device__ __noinline__ void append_queue(const lds_u32 *qrow, const lds_u64 *qk
 // with all lanes active; queues the pairs (slots from a ballot) and returns the new fill level.
 // ql: the lane's query row within the tile (row qa + ql of X, row qa + ql - q0 of the block).
 // A leaf on purpose: a function that calls another one saves its return address through memory.
+// qid (or null): the tile's query rows are not consecutive; qid[ql] is the row of the lane's query.
 __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0, const lds_f32 *qn, float nj, float dot,
                                         int fill, int qcap, lds_u64 *qkey, lds_u32 *qrow, int *__restrict__ cnt,
-                                        uint64_t *__restrict__ cand, int cap)
+                                        uint64_t *__restrict__ cand, int cap, const lds_u32 *qid)
 {
-    const int q = qa + ql;
+    const int q = qid ? (int)qid[ql] : qa + ql;
     const bool take = near && j != q;
     const uint64_t m = __ballot(take);
     if (m == 0) return fill;
@@ -224,11 +227,19 @@ __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0
 // TWO: two-level accumulation, needed once d exceeds KFLUSH: the matrix cores sum KFLUSH columns
 // into `part`, which is then added to `acc` and cleared, so the accumulation error stays that of
 // a short sum.  It doubles the accumulator registers, hence MB = 2 there.
-template <int MB, bool TWO>
+// GATHER: the tiles of an inverted-file search (Eq. (11)) instead of a rectangle of the all-pairs matrix.  The
+// rows are in list order (cellptr[L] .. cellptr[L+1] hold list L); the queries of the pass that probe list L at
+// the current rank are pairq[pairptr[L] .. pairptr[L+1]) (row numbers, any order); a launch takes the rows
+// chunk * DBC .. of every list.  Workgroup t < tptr[nlist] belongs to the list L with tptr[L] <= t < tptr[L+1] and
+// is tile (a, b) of its ceil(queries / TQ) x ceil(rows of the chunk / TN) tiles; workgroups past the end leave.
+template <int MB, bool TWO, bool GATHER>
 __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict__ Xs, int dp, int q0, int qend, int j0,
                                                         int jend, const float *__restrict__ norms,
                                                         const float *__restrict__ tau, int *__restrict__ cnt,
-                                                        uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount)
+                                                        uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount,
+                                                        const int *__restrict__ tptr, int nlist,
+                                                        const int *__restrict__ pairptr, const int *__restrict__ pairq,
+                                                        const int *__restrict__ cellptr, int chunk)
 {
     static_assert(!TWO || MB == 2, "two-level accumulation has registers for 2 x 2 blocks only");
     constexpr int TQ = 64 * MB;
@@ -237,7 +248,26 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
     __shared__ __align__(16) unsigned char Bs[TN * LDS_ROW];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wm = w >> 1, wn = w & 1;
-    const int qa = q0 + blockIdx.x * TQ, ja = j0 + blockIdx.y * TN;
+    int qa = q0 + blockIdx.x * TQ, ja = j0 + blockIdx.y * TN;
+    int po = 0, nq = TQ;            // GATHER: first entry of pairq and number of queries of this tile
+    if (GATHER) {
+        const int t = (int)blockIdx.x;
+        if (t >= tptr[nlist]) return;
+        int lo = 0, hi = nlist;     // tptr[lo] <= t < tptr[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (tptr[mid] <= t) lo = mid; else hi = mid;
+        }
+        const int nql = pairptr[lo + 1] - pairptr[lo];
+        const int rs = min(cellptr[lo] + chunk * DBC, cellptr[lo + 1]), re = min(cellptr[lo + 1], rs + DBC);
+        const int tr = max((re - rs + TN - 1) / TN, 1);
+        const int a = (t - tptr[lo]) / tr, b = (t - tptr[lo]) % tr;
+        po = pairptr[lo] + a * TQ;
+        nq = max(min(TQ, nql - a * TQ), 0);
+        ja = rs + b * TN;
+        jend = min(re, ja + TN);
+        qa = 0;
+    }
     const int row16 = dp / 4;              // 16-byte pieces per row of Xs
     const int piece = tid & 7, lrow = tid >> 3;
     floatx16 acc[TWO ? MB : 1][TWO ? 2 : 1], part[MB][2];
@@ -251,12 +281,17 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
                 part[a][b][i] = 0.f;
             }
     uint4 ra[2 * MB], rb[4];
+    int arow[2 * MB];               // the query rows this thread loads (-1: none)
+#pragma unroll
+    for (int it = 0; it < 2 * MB; ++it) {
+        const int lr = lrow + 32 * it;
+        if (GATHER) arow[it] = lr < nq ? max(pairq[po + lr], 0) : -1;
+        else arow[it] = qa + lr < qend ? qa + lr : -1;
+    }
     auto load = [&](int slab) {
 #pragma unroll
-        for (int it = 0; it < 2 * MB; ++it) {
-            const int r = qa + lrow + 32 * it;
-            ra[it] = r < qend ? Xs[(size_t)r * row16 + slab * 8 + piece] : make_uint4(0u, 0u, 0u, 0u);
-        }
+        for (int it = 0; it < 2 * MB; ++it)
+            ra[it] = arow[it] >= 0 ? Xs[(size_t)arow[it] * row16 + slab * 8 + piece] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int r = ja + lrow + 32 * it;
@@ -336,11 +371,13 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
     // Both are within tile_error_coeff() of the exact distance.
     __syncthreads();
     float *qn = reinterpret_cast<float *>(As), *qd = qn + TQ;
+    uint32_t *qid = reinterpret_cast<uint32_t *>(qd + TQ);
     for (int t = tid; t < TQ; t += 256) {
-        const int q = qa + t;
-        const float nq = q < qend ? norms[q] : 0.f;
-        qn[t] = nq;
-        qd[t] = q < qend ? tau[q - q0] - nq : -INFINITY;     // rows past the end accept nothing
+        const int q = GATHER ? (t < nq ? max(pairq[po + t], q0) : -1) : (qa + t < qend ? qa + t : -1);
+        const float nrm = q >= 0 ? norms[q] : 0.f;
+        qn[t] = nrm;
+        qd[t] = q >= 0 ? tau[q - q0] - nrm : -INFINITY;     // rows past the end accept nothing
+        if (GATHER) qid[t] = (uint32_t)max(q, 0);
     }
     __syncthreads();
     constexpr int QCAP = 320;
@@ -366,7 +403,8 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
                     const bool near = fmaf(-2.0f, dot, nj) < dq[ii];
                     if (__ballot(near) != 0)
                         fill = __builtin_amdgcn_readfirstlane(queue_pairs(near, j, ql0 + ii, qa, q0, (const lds_f32 *)qn, nj, dot, fill, QCAP,
-                                                                          qkey, qrow, cnt, cand, cap));
+                                                                          qkey, qrow, cnt, cand, cap,
+                                                                          GATHER ? (const lds_u32 *)qid : (const lds_u32 *)nullptr));
                 }
             }
         }
@@ -638,6 +676,9 @@ __global__ __launch_bounds__(THREADS) void knn_compact(float *__restrict__ tau, 
     for (int i = blockIdx.x; i < m; i += gridDim.x) {
         const int row = min(max(list[i], 0), rows - 1);
         int c = cnt[row];
+        // (more pairs than the buffer holds cannot arrive between two passes as the launches are sized; should it
+        // happen all the same, pairs were dropped: the cut-off goes to -inf for good, which fails the row's certificate)
+        const bool lost = c > cap || tau[row] == -INFINITY;
         if (c > cap) c = cap;
         uint64_t *buf = cand + (size_t)row * cap;
         int done = 0, have = 0;         // candidates read so far; sorted survivors in s[0 .. have)
@@ -655,16 +696,18 @@ __global__ __launch_bounds__(THREADS) void knn_compact(float *__restrict__ tau, 
         for (int t = threadIdx.x; t < have; t += THREADS) buf[t] = s[t];
         if (threadIdx.x == 0 && have > 0) {
             cnt[row] = have;
-            tau[row] = have >= kp ? unorderable((uint32_t)(s[kp - 1] >> 32)) : tau[row];
+            tau[row] = lost ? -INFINITY : have >= kp ? unorderable((uint32_t)(s[kp - 1] >> 32)) : tau[row];
         }
     }
 }
 
 // Exact distances of the candidates, final order, certificate.  One block per query row.
+// idmap (or null): the search ran on a reordered copy, row r of which is row idmap[r] of X; distances are
+// taken from X, equal distances are ordered by the rows' numbers in X, and the lists are written in X's numbering.
 __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, int n, int d, int q0, int rows, int k,
                                                   int kp, const float *__restrict__ norms, float norm_max,
                                                   const float *__restrict__ tau, const int *__restrict__ cnt,
-                                                  const uint64_t *__restrict__ cand, int cap,
+                                                  const uint64_t *__restrict__ cand, int cap, const int *__restrict__ idmap,
                                                   int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2,
                                                   int *__restrict__ fail_count, int *__restrict__ fail_rows)
 {
@@ -678,13 +721,19 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
     const int i = q0 + row;
     int c = cnt[row];
     if (c > kp) c = kp;
-    const float *x = X + (size_t)i * d;
+    __shared__ int cid[MAX_KP];          // the candidates' row numbers in X
+    const int iu = idmap ? min(max(idmap[i], 0), n - 1) : i;
+    const float *x = X + (size_t)iu * d;
     for (int t = threadIdx.x; t < d; t += blockDim.x) xi[t] = x[t];
-    __syncthreads();
     const uint64_t *buf = cand + (size_t)row * cap;
+    for (int a = threadIdx.x; a < c; a += blockDim.x) {
+        const int j = min((int)(uint32_t)buf[a], n - 1);
+        cid[a] = idmap ? min(max(idmap[j], 0), n - 1) : j;
+    }
+    __syncthreads();
     const int w = threadIdx.x >> 6;
     for (int cidx = w; cidx < c; cidx += 4) {
-        const int j = (int)(uint32_t)buf[cidx];
+        const int j = cid[cidx];
         const float *y = X + (size_t)j * d;
         double s = 0.0;
         for (int t = lane_id(); t < d; t += WAVE) { double df = (double)xi[t] - (double)y[t]; s += df * df; }
@@ -697,19 +746,19 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
     __syncthreads();
     for (int a = threadIdx.x; a < c; a += blockDim.x) {
         const uint64_t ka = key[a];
-        const uint32_t ja = (uint32_t)buf[a];
+        const int ja = cid[a];
         int r = 0;
         for (int b = 0; b < c; ++b) {
             const uint64_t kb = key[b];
-            r += (kb < ka) || (kb == ka && (uint32_t)buf[b] < ja);
+            r += (kb < ka) || (kb == ka && cid[b] < ja);
         }
         order[r] = a;
     }
     __syncthreads();
     for (int r = threadIdx.x; r < k && r < c; r += blockDim.x) {
         const int a = order[r];
-        knn_idx[(size_t)i * k + r] = (int32_t)(uint32_t)buf[a];
-        knn_d2[(size_t)i * k + r] = dd[a];
+        knn_idx[(size_t)iu * k + r] = (int32_t)cid[a];
+        knn_d2[(size_t)iu * k + r] = dd[a];
     }
     if (threadIdx.x == 0) {
         // pairs never kept had single-precision distance >= tau; the error of that distance is
@@ -770,16 +819,22 @@ __device__ __forceinline__ double key_to_double(uint64_t v)
     return __longlong_as_double((long long)u);
 }
 
-// One workgroup per failed row of the batch.
-__global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restrict__ okey_all, int n, int k,
-                                                         const int *__restrict__ rows,
-                                                         int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2)
+// One workgroup per failed row of the batch.  Row f of the batch has its keys at okey_all + f * stride: n of them,
+// or counts[f] if counts is given; key j belongs to point j, or to point ids[f * stride + j] if ids is given
+// (equal distances are ordered by that number); the list goes to row rows[f] of the output, or rowmap[rows[f]].
+__global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restrict__ okey_all, size_t stride, int n,
+                                                         const int *__restrict__ counts, const int *__restrict__ ids,
+                                                         int k, const int *__restrict__ rows, const int *__restrict__ rowmap,
+                                                         int nrows, int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2)
 {
-    const uint64_t *okey = okey_all + (size_t)blockIdx.x * n;
-    const int i = min(max(rows[blockIdx.x], 0), n - 1);
+    const uint64_t *okey = okey_all + (size_t)blockIdx.x * stride;
+    const int *id = ids ? ids + (size_t)blockIdx.x * stride : nullptr;
+    if (counts) n = min(counts[blockIdx.x], (int)stride);
+    int i = min(max(rows[blockIdx.x], 0), nrows - 1);
+    if (rowmap) i = min(max(rowmap[i], 0), nrows - 1);
     __shared__ uint32_t hist[256];
     __shared__ uint64_t prefix_s;
-    __shared__ int want_s, nsel, ntie;
+    __shared__ int want_s, nsel, ntie, best;
     __shared__ uint64_t selk[MAX_KP];
     __shared__ int selj[MAX_KP];
     __shared__ uint64_t tie[TIE_CAP];
@@ -816,10 +871,10 @@ __global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restr
         const uint64_t v = okey[j];
         if (v < prefix) {
             const int p = atomicAdd(&nsel, 1);
-            if (p < MAX_KP) { selk[p] = v; selj[p] = j; }
+            if (p < MAX_KP) { selk[p] = v; selj[p] = id ? id[j] : j; }
         } else if (v == prefix) {
             const int p = atomicAdd(&ntie, 1);
-            if (p < TIE_CAP) tie[p] = (uint64_t)(uint32_t)j;
+            if (p < TIE_CAP) tie[p] = (uint64_t)(uint32_t)(id ? id[j] : j);
         }
     }
     __syncthreads();
@@ -853,11 +908,25 @@ __global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restr
             knn_idx[(size_t)i * k + below + t] = (int32_t)tie[t];
             knn_d2[(size_t)i * k + below + t] = dk;
         }
-    } else if (threadIdx.x == 0) {
-        // more equidistant rows than the tie buffer holds: take them in index order, serially
-        int out = below;
-        for (int j = 0; j < n && out < k; ++j)
-            if (okey[j] == prefix) { knn_idx[(size_t)i * k + out] = j; knn_d2[(size_t)i * k + out] = dk; ++out; }
+    } else {
+        // more equidistant rows than the tie buffer holds: the lowest number above the last one taken, `want` times
+        int last = -1;
+        for (int out = below; out < k; ++out) {
+            __syncthreads();
+            if (threadIdx.x == 0) best = 0x7FFFFFFF;
+            __syncthreads();
+            int mine = 0x7FFFFFFF;
+            for (int j = threadIdx.x; j < n; j += blockDim.x)
+                if (okey[j] == prefix) {
+                    const int v = id ? id[j] : j;
+                    if (v > last && v < mine) mine = v;
+                }
+            if (mine != 0x7FFFFFFF) atomicMin(&best, mine);
+            __syncthreads();
+            last = best;
+            if (last == 0x7FFFFFFF) break;
+            if (threadIdx.x == 0) { knn_idx[(size_t)i * k + out] = last; knn_d2[(size_t)i * k + out] = dk; }
+        }
     }
 }
 
@@ -1043,6 +1112,114 @@ __global__ void d2_to_float(const double *__restrict__ in, float *__restrict__ o
     if (i < m) out[i] = (float)in[i];
 }
 
+// ---- Eq. (10)-(11) for long rows on the same tiles: helpers of ivf_search_tiles() below
+// the probed lists of every row, rows in list order
+__global__ void probe_gather(const int32_t *__restrict__ probe, const int *__restrict__ lorder, int n, int tau, int nlist,
+                             int32_t *__restrict__ probe_l)
+{
+    const size_t e = global_index();
+    if (e >= (size_t)n * tau) return;
+    const size_t pos = e / tau;
+    const int r = (int)(e % tau);
+    const int row = min(max(lorder[pos], 0), n - 1);
+    probe_l[e] = min(max(probe[(size_t)row * tau + r], 0), nlist - 1);
+}
+
+// queries q0 .. q0 + rows of the pass, grouped by the list they probe at rank r
+__global__ void rank_hist(const int32_t *__restrict__ probe_l, int q0, int rows, int tau, int r, int *__restrict__ bcnt)
+{
+    const size_t i = global_index();
+    if (i < (size_t)rows) atomicAdd(&bcnt[probe_l[((size_t)q0 + i) * tau + r]], 1);
+}
+
+__global__ void rank_scatter(const int32_t *__restrict__ probe_l, int q0, int rows, int tau, int r,
+                             const int *__restrict__ pairptr, int *__restrict__ bcur, int *__restrict__ pairq)
+{
+    const size_t i = global_index();
+    if (i >= (size_t)rows) return;
+    const int L = probe_l[((size_t)q0 + i) * tau + r];
+    pairq[pairptr[L] + atomicAdd(&bcur[L], 1)] = q0 + (int)i;     // any order inside a list
+}
+
+// tiles of list L in the launch that takes rows chunk * DBC .. of every list
+__global__ void tile_count(const int *__restrict__ pairptr, const int *__restrict__ cellptr, int nlist, int chunk, int tq,
+                           int *__restrict__ tcnt)
+{
+    const int L = blockIdx.x * blockDim.x + threadIdx.x;
+    if (L >= nlist) return;
+    const int nq = pairptr[L + 1] - pairptr[L];
+    const int rs = min(cellptr[L] + chunk * DBC, cellptr[L + 1]), re = min(cellptr[L + 1], rs + DBC);
+    tcnt[L] = ((nq + tq - 1) / tq) * ((re - rs + TN - 1) / TN);
+}
+
+// out[i] = in[0] + .. + in[i-1], i = 0 .. m (one workgroup; the sums stay below 2^31 as the callers size things)
+__global__ __launch_bounds__(1024) void excl_scan_k(const int *__restrict__ in, int m, int *__restrict__ out)
+{
+    __shared__ int ws[16];
+    const int per = (m + 1023) / 1024;
+    const int b = min((int)threadIdx.x * per, m), e = min(b + per, m);
+    int a = 0;
+    for (int i = b; i < e; ++i) a += in[i];
+    int inc = a;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        const int t = __shfl_up(inc, o, WAVE);
+        if (lane_id() >= o) inc += t;
+    }
+    if (lane_id() == WAVE - 1) ws[threadIdx.x >> 6] = inc;
+    __syncthreads();
+    int base = 0;
+    for (int q = 0; q < (int)(threadIdx.x >> 6); ++q) base += ws[q];
+    int pre = base + inc - a;
+    for (int i = b; i < e; ++i) { const int v = in[i]; out[i] = pre; pre += v; }
+    if (threadIdx.x == 1023) out[m] = pre;
+}
+
+__global__ void fill_int_k(int *__restrict__ a, int v, int m)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m) a[i] = v;
+}
+
+// Queries without a certificate: exact distances to every row of their tau lists.  One workgroup per failed
+// query f (row rows[f] of the list order): key t of its `stride` slots is the ordered distance to the t-th row
+// of its lists taken in probe order, ids[t] that row's number in X; counts[f] = how many there are.
+__global__ __launch_bounds__(256) void ivf_exact_keys(const float *__restrict__ X, int n, int d, const int *__restrict__ rows,
+                                                      const int32_t *__restrict__ probe_l, int tau,
+                                                      const int *__restrict__ cellptr, const int *__restrict__ lorder,
+                                                      size_t stride, uint64_t *__restrict__ okey, int *__restrict__ ids,
+                                                      int *__restrict__ counts)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *xi = reinterpret_cast<float *>(smem);
+    const int f = blockIdx.x;
+    const int pos = min(max(rows[f], 0), n - 1);
+    const float *x = X + (size_t)min(max(lorder[pos], 0), n - 1) * d;
+    for (int t = threadIdx.x; t < d; t += blockDim.x) xi[t] = x[t];
+    __syncthreads();
+    const int w = threadIdx.x >> 6;
+    size_t off = 0;
+    for (int r = 0; r < tau; ++r) {
+        const int L = probe_l[(size_t)pos * tau + r];
+        const int rs = cellptr[L], m = cellptr[L + 1] - rs;
+        for (int u = w; u < m; u += 4) {
+            if (off + u >= stride) break;
+            const int row = min(max(lorder[rs + u], 0), n - 1);
+            const float *y = X + (size_t)row * d;
+            double sum = 0.0;
+            for (int t = lane_id(); t < d; t += WAVE) { const double df = (double)xi[t] - (double)y[t]; sum += df * df; }
+            sum = wave_sum(sum);
+            if (lane_id() == 0) {
+                okey[(size_t)f * stride + off + u] = rs + u == pos ? ~0ull : orderable64(sum);
+                ids[(size_t)f * stride + off + u] = row;
+            }
+        }
+        off += (size_t)m;
+    }
+    if (threadIdx.x == 0) counts[f] = (int)(off < stride ? off : stride);
+}
+
+
 struct Layout {
     float *norms, *norm_max, *tau;
     int *cnt, *fail_count, *fail_rows, *extra, *cursor, *unconv;
@@ -1104,6 +1281,157 @@ int check_args(int32_t n, int32_t d, int32_t k)
 
 }  // namespace
 
+#define HIPCHK(call)                                      \
+    do {                                                  \
+        hipError_t e_ = (call);                           \
+        if (e_ != hipSuccess) {                           \
+            fprintf(stderr, "tsne_build_P: %s failed: %s\n", #call, hipGetErrorString(e_)); \
+            return TSNE_EHIP;                             \
+        }                                                 \
+    } while (0)
+
+// ---- Eq. (10)-(11) with a flat second stage, rows longer than the double-precision kernels like
+// The k nearest of the points in a query's tau probed lists, found the way tsne_build_P finds neighbours among all
+// points: candidates from bf16 matrix-core tiles on the centred rows (here the tiles of (queries probing a list) x
+// (rows of the list), queries grouped by list once per probe rank), exact distances in double for the k' best,
+// a certificate per query, and an exact pass over its lists for a query without one.  The result is Eq. (11)'s by
+// (distance in double, row number).  probe: n x tau list numbers (Eq. (10)), lorder: the rows in list order,
+// cellptr: where each list starts in it; max_list and max_cand (longest list, most rows in one query's lists) from the caller.
+namespace {
+struct TileSearchLayout {
+    float *norms, *norm_max, *tau, *mu;
+    double *mu_part;
+    int *cnt, *clist, *ccount, *fail_count, *fail_rows, *bcnt, *bcur, *pairptr, *tcnt, *tptr, *pairq, *fcnt;
+    int32_t *probe_l;
+    uint64_t *cand;
+    uint16_t *xs;
+    size_t cand_bytes;
+};
+constexpr int TS_ROWS = 1 << 17;     // queries per pass
+
+size_t ts_carve(TileSearchLayout *L, int n, int d, int k, int nlist, int tau, char *base)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up(bytes); return (void *)p; };
+    const int kp = margin_kp(n, k);
+    const size_t cap = (size_t)kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
+    const size_t qb = (size_t)(n < TS_ROWS ? n : TS_ROWS);
+    const size_t dp = ((size_t)d + SLAB - 1) / SLAB * SLAB;
+    void *q;
+    q = take(4 * (size_t)n); if (L) L->norms = (float *)q;
+    q = take(4); if (L) L->norm_max = (float *)q;
+    q = take(4 * qb); if (L) L->tau = (float *)q;
+    q = take(4 * dp); if (L) L->mu = (float *)q;
+    q = take(8 * (size_t)MEAN_CHUNKS * d); if (L) L->mu_part = (double *)q;
+    q = take(4 * qb); if (L) L->cnt = (int *)q;
+    q = take(4 * qb); if (L) L->clist = (int *)q;
+    q = take(8); if (L) L->ccount = (int *)q;
+    q = take(4); if (L) L->fail_count = (int *)q;
+    q = take(4 * (size_t)n); if (L) L->fail_rows = (int *)q;
+    q = take(4 * ((size_t)nlist + 1)); if (L) L->bcnt = (int *)q;
+    q = take(4 * ((size_t)nlist + 1)); if (L) L->bcur = (int *)q;
+    q = take(4 * ((size_t)nlist + 1)); if (L) L->pairptr = (int *)q;
+    q = take(4 * ((size_t)nlist + 1)); if (L) L->tcnt = (int *)q;
+    q = take(4 * ((size_t)nlist + 1)); if (L) L->tptr = (int *)q;
+    q = take(4 * qb); if (L) L->pairq = (int *)q;
+    q = take(4 * (size_t)(2 * k > 1 ? 2 * k : 1)); if (L) L->fcnt = (int *)q;
+    q = take(4 * (size_t)n * tau); if (L) L->probe_l = (int32_t *)q;
+    q = take(4 * (size_t)n * dp); if (L) L->xs = (uint16_t *)q;
+    // candidate buffers; afterwards the keys and row numbers of the exact pass (12 bytes a slot, at least one query's n slots)
+    size_t cb = 8 * qb * cap;
+    if (cb < 12 * (size_t)n) cb = 12 * (size_t)n;
+    q = take(cb); if (L) { L->cand = (uint64_t *)q; L->cand_bytes = cb; }
+    return off;
+}
+}  // namespace
+
+// (0: these sizes are beyond the tile search; the caller keeps to its double-precision kernels)
+size_t ivf_search_tiles_workspace(int n, int d, int k, int nlist, int tau)
+{
+    if (check_args(n, d, k) != TSNE_OK) return 0;
+    return ts_carve(nullptr, n, d, k, nlist, tau, nullptr);
+}
+
+int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, const int32_t *probe, const int *lorder,
+                     const int *cellptr, int max_list, long long max_cand, int32_t *knn_idx, double *knn_d2, void *ws,
+                     size_t ws_bytes, hipStream_t s)
+{
+    if (check_args(n, d, k) != TSNE_OK || nlist < 1 || tau < 1 || max_list < 1 || max_cand < 1) return TSNE_EINVAL;
+    if (ws_bytes < ts_carve(nullptr, n, d, k, nlist, tau, nullptr)) return TSNE_ENOSPC;
+    TileSearchLayout L;
+    ts_carve(&L, n, d, k, nlist, tau, (char *)ws);
+    const int kp = margin_kp(n, k), cap = kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
+    const int dp = (d + SLAB - 1) / SLAB * SLAB;
+    const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks_mu = (n + rows_per_chunk - 1) / rows_per_chunk;
+    hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks_mu), dim3(256), 0, s, X, n, d, rows_per_chunk, L.mu_part);
+    hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks_mu, n, d, dp, L.mu);
+    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, X, L.mu, n, d, lorder, L.norms);
+    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, X, L.mu, n, d, dp, lorder, L.xs);
+    hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms, n, L.norm_max);
+    hipLaunchKernelGGL(probe_gather, wide_grid((size_t)n * tau), dim3(256), 0, s, probe, lorder, n, tau, nlist, L.probe_l);
+    HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
+    float norm_max = 0.f;
+    HIPCHK(hipMemcpyAsync(&norm_max, L.norm_max, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    const size_t rerank_smem = up((size_t)d * 4) + 8 * (size_t)MAX_KP;
+    const int nchunks = (max_list + DBC - 1) / DBC;
+    const unsigned lb = (unsigned)((nlist + 1 + 255) / 256);
+    for (int q0 = 0; q0 < n; q0 += TS_ROWS) {
+        const int rows = n - q0 < TS_ROWS ? n - q0 : TS_ROWS;
+        hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows, L.ccount);
+        // an upper bound of the tiles of one launch: sum over the lists of ceil(queries / 128) x (DBC / TN)
+        const unsigned bound = (unsigned)(((size_t)rows / 128 + (size_t)nlist + 1) * (DBC / TN));
+        for (int r = 0; r < tau; ++r) {
+            hipLaunchKernelGGL(fill_int_k, dim3(lb), dim3(256), 0, s, L.bcnt, 0, nlist + 1);
+            hipLaunchKernelGGL(fill_int_k, dim3(lb), dim3(256), 0, s, L.bcur, 0, nlist + 1);
+            hipLaunchKernelGGL(rank_hist, wide_grid((size_t)rows), dim3(256), 0, s, L.probe_l, q0, rows, tau, r, L.bcnt);
+            hipLaunchKernelGGL(excl_scan_k, dim3(1), dim3(1024), 0, s, L.bcnt, nlist, L.pairptr);
+            hipLaunchKernelGGL(rank_scatter, wide_grid((size_t)rows), dim3(256), 0, s, L.probe_l, q0, rows, tau, r, L.pairptr,
+                               L.bcur, L.pairq);
+            for (int c = 0; c < nchunks; ++c) {
+                hipLaunchKernelGGL(tile_count, dim3(lb), dim3(256), 0, s, L.pairptr, cellptr, nlist, c, 128, L.tcnt);
+                hipLaunchKernelGGL(excl_scan_k, dim3(1), dim3(1024), 0, s, L.tcnt, nlist, L.tptr);
+                hipLaunchKernelGGL((knn_tile_mfma<2, true, true>), dim3(bound), dim3(256), 0, s, (const uint4 *)L.xs, dp, q0,
+                                   q0 + rows, 0, 0, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount, L.tptr, nlist, L.pairptr,
+                                   L.pairq, cellptr, c);
+                const int force = r == tau - 1 && c == nchunks - 1 ? 1 : 0;
+                hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
+                                   L.clist, L.ccount);
+                const unsigned cg = (unsigned)(rows < 4096 ? rows : 4096);
+                if (kp <= 320)
+                    hipLaunchKernelGGL((knn_compact<512, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, L.ccount);
+                else if (kp <= 832)
+                    hipLaunchKernelGGL((knn_compact<1024, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, L.ccount);
+                else
+                    hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, L.ccount);
+            }
+        }
+        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, q0, rows, k, kp, L.norms, norm_max, L.tau,
+                           L.cnt, L.cand, cap, lorder, knn_idx, knn_d2, L.fail_count, L.fail_rows);
+        HIPCHK(hipGetLastError());
+    }
+    int nfail = 0;
+    HIPCHK(hipMemcpyAsync(&nfail, L.fail_count, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    if (nfail > 0) {
+        const size_t stride = (size_t)max_cand;
+        size_t nb_max = L.cand_bytes / (12 * stride);
+        if (nb_max > (size_t)(2 * k)) nb_max = (size_t)(2 * k);
+        if (nb_max < 1) return TSNE_ENOSPC;
+        uint64_t *okey = L.cand;
+        int *ids = reinterpret_cast<int *>(okey + nb_max * stride);
+        for (int f0 = 0; f0 < nfail; f0 += (int)nb_max) {
+            const int nb = nfail - f0 < (int)nb_max ? nfail - f0 : (int)nb_max;
+            hipLaunchKernelGGL(ivf_exact_keys, dim3(nb), dim3(256), up((size_t)d * 4), s, X, n, d, L.fail_rows + f0, L.probe_l, tau,
+                               cellptr, lorder, stride, okey, ids, L.fcnt);
+            hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, okey, stride, 0, L.fcnt, ids, k, L.fail_rows + f0,
+                               lorder, n, knn_idx, knn_d2);
+            HIPCHK(hipGetLastError());
+        }
+    }
+    return TSNE_OK;
+}
+
 extern "C" {
 
 int tsne_build_P_workspace_bytes(int32_t n, int32_t d, int32_t k, size_t *bytes)
@@ -1113,14 +1441,6 @@ int tsne_build_P_workspace_bytes(int32_t n, int32_t d, int32_t k, size_t *bytes)
     return TSNE_OK;
 }
 
-#define HIPCHK(call)                                      \
-    do {                                                  \
-        hipError_t e_ = (call);                           \
-        if (e_ != hipSuccess) {                           \
-            fprintf(stderr, "tsne_build_P: %s failed: %s\n", #call, hipGetErrorString(e_)); \
-            return TSNE_EHIP;                             \
-        }                                                 \
-    } while (0)
 
 // Alg. 1 line 2 from finished neighbour lists (L.knn_idx, L.knn_d2): Eq. (1) per row, then the symmetric CSR.
 static int finish_P(const Layout &L, int32_t n, int32_t k, float perplexity, int32_t *d_row_ptr, int32_t *d_col,
@@ -1174,8 +1494,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks = (n + rows_per_chunk - 1) / rows_per_chunk;
     hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks), dim3(256), 0, s, d_X, n, d, rows_per_chunk, L.mu_part);
     hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks, n, d, dp, L.mu);
-    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, L.mu, n, d, L.norms);
-    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, d_X, L.mu, n, d, dp, L.xs);
+    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, L.mu, n, d, (const int *)nullptr, L.norms);
+    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, d_X, L.mu, n, d, dp, (const int *)nullptr, L.xs);
     hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms, n, L.norm_max);
     HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
     HIPCHK(hipMemsetAsync(L.unconv, 0, 4, s));
@@ -1216,11 +1536,15 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                                        L.clist, cc, cc_next);
             } else {
                 if (d > KFLUSH)
-                    hipLaunchKernelGGL((knn_tile_mfma<2, true>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
-                                       (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc);
+                    hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
+                                       (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
+                                       (const int *)nullptr, 0, (const int *)nullptr, (const int *)nullptr,
+                                       (const int *)nullptr, 0);
                 else
-                    hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
-                                       0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc);
+                    hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
+                                       0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
+                                       (const int *)nullptr, 0, (const int *)nullptr, (const int *)nullptr,
+                                       (const int *)nullptr, 0);
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, cc);
             }
@@ -1235,7 +1559,7 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                 hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, q0, rows, k, kp, L.norms,
-                           norm_max, L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
+                           norm_max, L.tau, L.cnt, L.cand, cap, (const int *)nullptr, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
         HIPCHK(hipGetLastError());
     }
     int nfail = 0;
@@ -1247,8 +1571,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
         const int nb = nfail - f0 < 2 * k ? nfail - f0 : 2 * k;
         hipLaunchKernelGGL(knn_exact_dists, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, n, d, L.fail_rows + f0, nb,
                            L.sort_scratch);
-        hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, L.sort_scratch, n, k, L.fail_rows + f0, L.knn_idx,
-                           L.knn_d2);
+        hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, L.sort_scratch, (size_t)n, n, (const int *)nullptr,
+                           (const int *)nullptr, k, L.fail_rows + f0, (const int *)nullptr, n, L.knn_idx, L.knn_d2);
         HIPCHK(hipGetLastError());
     }
     return finish_P(L, n, k, perplexity, d_row_ptr, d_col, d_val, cap_nnz, nnz, d_knn_idx, d_knn_d2, n_unconverged, s);

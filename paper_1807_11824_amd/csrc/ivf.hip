@@ -843,12 +843,15 @@ struct IvfLayout {
     unsigned int *maxabs;
     double *mind;
     int *sel;
+    void *tiles_ws;          // workspace of the matrix-core search (long rows, flat second stage)
+    size_t tiles_bytes;
     size_t d_bytes;
 };
 
 constexpr int IVF_BATCH_ROWS = 1 << 17;
 
-size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, size_t avail)
+// k_tiles: the k of a search that may go through ivf_search_tiles (0: no such search with this workspace)
+size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, size_t avail, int k_tiles = 0)
 {
     size_t off = 0;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up256(bytes); return (void *)p; };
@@ -874,6 +877,10 @@ size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, siz
     q = take(4); if (L) L->maxabs = (unsigned int *)q;
     q = take(8 * 8 * (size_t)nlist); if (L) L->mind = (double *)q;
     q = take(4 * (size_t)nlist); if (L) L->sel = (int *)q;
+    {
+        const size_t tb = k_tiles > 0 && d > IVF_DC ? ivf_search_tiles_workspace(n, d, k_tiles, nlist, tau) : 0;
+        q = take(tb); if (L) { L->tiles_ws = q; L->tiles_bytes = tb; }
+    }
     // distance scratch: whatever is left, at least one row of n distances, at most IVF_D_MAX
     size_t want = 4 * (size_t)n * (size_t)(n < 4096 ? n : 4096);
     if (want > IVF_D_MAX) want = IVF_D_MAX;
@@ -897,8 +904,7 @@ int ivf_check(int n, int d, int k, int nlist, int tau)
 
 size_t ivf_workspace(int n, int d, int k, int nlist, int tau)
 {
-    (void)k;
-    return ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0);
+    return ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0, k);
 }
 
 // Lloyd's algorithm: `iters` rounds of (nearest centroid, mean of the members) from a spread-out start, on a sample
@@ -952,8 +958,9 @@ static int ivf_knn_impl(const float *X, int n, int d, const float *C, int nlist,
                         double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s, PqView pq)
 {
     IvfLayout L;
-    if (ws_bytes < ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0)) return TSNE_ENOSPC;
-    ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes);
+    const int k_tiles = pq.codes ? 0 : k;
+    if (ws_bytes < ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0, k_tiles)) return TSNE_ENOSPC;
+    ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes, k_tiles);
     const int dp = (d + 3) / 4 * 4;
     hipLaunchKernelGGL(to_double_k, (blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
     launch_probe(X, n, d, dp, L.Cd, nlist, tau, L.probe, n, s);
@@ -978,6 +985,20 @@ static int ivf_knn_impl(const float *X, int n, int d, const float *C, int nlist,
         const long long m = mp[i + 1] - mp[i];
         if (m - 1 < k) rc = TSNE_ENUM;            // fewer than k other points in the probed lists
         if (m > mmax) mmax = m;
+    }
+    if (rc == TSNE_OK && !pq.codes && d > IVF_DC && L.tiles_bytes > 0) {
+        // long rows, flat second stage: the distances of Eq. (11) on the matrix-core tiles of the exact search
+        free(mp);
+        int *cp = (int *)malloc(4 * ((size_t)nlist + 1));
+        if (!cp) return TSNE_ENOSPC;
+        e = hipMemcpyAsync(cp, L.cellptr, 4 * ((size_t)nlist + 1), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        int max_list = 1;
+        for (int c = 0; c < nlist; ++c) if (cp[c + 1] - cp[c] > max_list) max_list = cp[c + 1] - cp[c];
+        free(cp);
+        if (e != hipSuccess) return TSNE_EHIP;
+        return ivf_search_tiles(X, n, d, k, nlist, tau, L.probe, L.lorder, L.cellptr, max_list, mmax, knn_idx, knn_d2,
+                                L.tiles_ws, L.tiles_bytes, s);
     }
     const long long d_cap = (long long)(L.d_bytes / 4);
     if (rc == TSNE_OK && mmax > d_cap) rc = TSNE_ENOSPC;

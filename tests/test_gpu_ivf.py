@@ -47,12 +47,34 @@ def _case(name):
     if name == "largest_k_cut_fails":        # k = 1900 of 9000: more keys pass the cut than the buffer holds
         X = r.standard_normal((9000, 4)).astype(np.float32)
         return X, 3, 3, 1900
+    # rows longer than 64 coordinates: candidates from the matrix-core tiles, exact re-rank, certificate
+    if name == "long_rows_ties":             # every row five times: no certificate for anybody, decided by index
+        base = r.standard_normal((400, 100)).astype(np.float32)
+        return np.repeat(base, 5, axis=0), 10, 3, 23
+    if name == "long_rows_one_point_many_times":   # more equal distances than the tie buffer of the exact pass holds
+        X = np.concatenate([np.tile(r.standard_normal((1, 70)).astype(np.float32), (5000, 1)),
+                            r.standard_normal((600, 70)).astype(np.float32)])
+        return X[r.permutation(5600)], 4, 2, 20
+    if name == "long_rows_long_lists":       # lists of about 3000 rows: two launches per list and rank
+        X, _ = synth.gaussian_mixture(9000, 80, 3, 4.0, 1.0, seed=9)
+        return X, 3, 2, 50
+    if name == "long_rows_all_but_self":
+        X = r.standard_normal((130, 66)).astype(np.float32)
+        return X, 1, 1, 129
+    if name == "long_rows_far_from_origin":  # the search works on centred rows
+        X, _ = synth.gaussian_mixture(3000, 96, 5, 3.0, 1.0, seed=10)
+        return X + np.float32(200.0), 30, 4, 40
+    if name == "long_rows_k_one":
+        X = r.standard_normal((900, 65)).astype(np.float32)
+        return X, 20, 3, 1
     raise KeyError(name)
 
 
 @pytest.mark.parametrize("name", ["blobs_50d", "two_chunks_and_tail", "all_lists", "every_row_five_times",
                                   "one_point_many_times", "k_one", "one_list_all_but_self", "large_k",
-                                  "largest_k_cut_fails"])
+                                  "largest_k_cut_fails", "long_rows_ties", "long_rows_one_point_many_times",
+                                  "long_rows_long_lists", "long_rows_all_but_self", "long_rows_far_from_origin",
+                                  "long_rows_k_one"])
 def test_ivf_knn_matches_oracle(name):
     from paper_1807_11824_amd import ivf_knn
     X, nlist, tau, k = _case(name)
@@ -76,6 +98,21 @@ def test_several_passes_and_rows_longer_than_the_lds_keys():
     idx, d2 = ivf_knn(_dev(X), _dev(C), 3, 40)
     assert np.array_equal(idx.cpu().numpy()[rows], want_idx)
     assert np.allclose(d2.cpu().numpy()[rows], want_d2, rtol=1e-13, atol=1e-300)
+
+
+def test_long_rows_in_several_passes():
+    """140,000 queries of 72 coordinates: two passes of the tile search; sampled rows against the oracle."""
+    from paper_1807_11824_amd import ivf_knn
+    n, d, nlist, tau, k = 140_000, 72, 374, 3, 10
+    X, _ = synth.gaussian_mixture(n, d, 40, 4.0, 1.0, seed=12)
+    C = ivf.kmeans_init(X, nlist)
+    rows = np.sort(np.random.default_rng(2).choice(n, 96, replace=False))
+    want_idx, want_d2 = ivf.ivf_knn(X, C, tau, k, rows=rows)
+    idx, d2 = ivf_knn(_dev(X), _dev(C), tau, k)
+    assert np.array_equal(idx[rows.tolist()].cpu().numpy(), want_idx)
+    assert np.allclose(d2[rows.tolist()].cpu().numpy(), want_d2, rtol=1e-13, atol=1e-300)
+    idx = idx.cpu().numpy()
+    assert idx.min() >= 0 and idx.max() < n and not np.any(idx == np.arange(n)[:, None])
 
 
 def test_too_few_candidates_is_reported():
