@@ -89,14 +89,14 @@ __global__ __launch_bounds__(256) void col_mean_final(const double *__restrict__
 }
 
 // |x - mu|^2 of the centred row as the tiles see it (each x_t - mu_t rounded to float)
-// (rowmap: row r of the result is row rowmap[r] of X; null = the same rows)
+// (rowmap: row r of the result is row rowmap[r] of the nsrc rows of X; null = the same rows)
 __global__ __launch_bounds__(256) void row_norms(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
-                                                 const int *__restrict__ rowmap, float *__restrict__ norms)
+                                                 const int *__restrict__ rowmap, int nsrc, float *__restrict__ norms)
 {
     const size_t w = global_index() >> 6;
     if (w >= (size_t)n) return;
     const int row = (int)w;
-    const float *x = X + (size_t)(rowmap ? min(max(rowmap[row], 0), n - 1) : row) * d;
+    const float *x = X + (size_t)(rowmap ? min(max(rowmap[row], 0), nsrc - 1) : row) * d;
     double s = 0.0;
     for (int t = lane_id(); t < d; t += WAVE) { double v = (double)(x[t] - mu[t]); s += v * v; }
     s = wave_sum(s);
@@ -134,13 +134,14 @@ __device__ __forceinline__ uint32_t bf16_rne(float x)
 }
 
 __global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
-                                                  int dp, const int *__restrict__ rowmap, uint16_t *__restrict__ Xs)
+                                                  int dp, const int *__restrict__ rowmap, int nsrc,
+                                                  uint16_t *__restrict__ Xs)
 {
     const size_t e = global_index();
     if (e >= (size_t)n * dp) return;
     const size_t row = e / dp;
     const int k = (int)(e % dp);
-    const size_t src = rowmap ? (size_t)min(max(rowmap[row], 0), n - 1) : row;
+    const size_t src = rowmap ? (size_t)min(max(rowmap[row], 0), nsrc - 1) : row;
     const float x = k < d ? X[src * d + k] - mu[k] : 0.f;
     const uint32_t hi = bf16_rne(x);
     const uint32_t lo = bf16_rne(x - __uint_as_float(hi << 16));      // the difference is exact in fp32
@@ -205,10 +206,10 @@ __device__ __noinline__ void append_queue(const lds_u32 *qrow, const lds_u64 *qk
 // qid (or null): the tile's query rows are not consecutive; qid[ql] is the row of the lane's query.
 __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0, const lds_f32 *qn, float nj, float dot,
                                         int fill, int qcap, lds_u64 *qkey, lds_u32 *qrow, int *__restrict__ cnt,
-                                        uint64_t *__restrict__ cand, int cap, const lds_u32 *qid)
+                                        uint64_t *__restrict__ cand, int cap, const lds_u32 *qid, int exclude_self)
 {
     const int q = qid ? (int)qid[ql] : qa + ql;
-    const bool take = near && j != q;
+    const bool take = near && (j != q || !exclude_self);
     const uint64_t m = __ballot(take);
     if (m == 0) return fill;
     if (fill + WAVE > qcap) { append_queue_inline(qrow, qkey, fill, cnt, cand, cap); fill = 0; }
@@ -227,6 +228,8 @@ __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0
 // TWO: two-level accumulation, needed once d exceeds KFLUSH: the matrix cores sum KFLUSH columns
 // into `part`, which is then added to `acc` and cleared, so the accumulation error stays that of
 // a short sum.  It doubles the accumulator registers, hence MB = 2 there.
+// Xb, norms_b: the database rows and their norms (Xs and norms again when the rows are searched among themselves,
+// exclude_self = 1: a row is not its own neighbour).
 // GATHER: the tiles of an inverted-file search (Eq. (11)) instead of a rectangle of the all-pairs matrix.  The
 // rows are in list order (cellptr[L] .. cellptr[L+1] hold list L); the queries of the pass that probe list L at
 // the current rank are pairq[pairptr[L] .. pairptr[L+1]) (row numbers, any order); a launch takes the rows
@@ -237,7 +240,8 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
                                                         int jend, const float *__restrict__ norms,
                                                         const float *__restrict__ tau, int *__restrict__ cnt,
                                                         uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount,
-                                                        const int *__restrict__ tptr, int nlist,
+                                                        const uint4 *__restrict__ Xb, const float *__restrict__ norms_b,
+                                                        int exclude_self, const int *__restrict__ tptr, int nlist,
                                                         const int *__restrict__ pairptr, const int *__restrict__ pairq,
                                                         const int *__restrict__ cellptr, int chunk)
 {
@@ -295,7 +299,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int r = ja + lrow + 32 * it;
-            rb[it] = r < jend ? Xs[(size_t)r * row16 + slab * 8 + piece] : make_uint4(0u, 0u, 0u, 0u);
+            rb[it] = r < jend ? Xb[(size_t)r * row16 + slab * 8 + piece] : make_uint4(0u, 0u, 0u, 0u);
         }
     };
     load(0);
@@ -388,7 +392,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int j = ja + wn * 64 + b * 32 + r32;
-        const float nj = j < jend ? norms[j] : INFINITY;    // rows past the end are never closer than any cut-off
+        const float nj = j < jend ? norms_b[j] : INFINITY;    // rows past the end are never closer than any cut-off
 #pragma unroll
         for (int a = 0; a < MB; ++a) {
 #pragma unroll
@@ -404,7 +408,8 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
                     if (__ballot(near) != 0)
                         fill = __builtin_amdgcn_readfirstlane(queue_pairs(near, j, ql0 + ii, qa, q0, (const lds_f32 *)qn, nj, dot, fill, QCAP,
                                                                           qkey, qrow, cnt, cand, cap,
-                                                                          GATHER ? (const lds_u32 *)qid : (const lds_u32 *)nullptr));
+                                                                          GATHER ? (const lds_u32 *)qid : (const lds_u32 *)nullptr,
+                                                                          exclude_self));
                 }
             }
         }
@@ -701,13 +706,17 @@ __global__ __launch_bounds__(THREADS) void knn_compact(float *__restrict__ tau, 
     }
 }
 
-// Exact distances of the candidates, final order, certificate.  One block per query row.
-// idmap (or null): the search ran on a reordered copy, row r of which is row idmap[r] of X; distances are
-// taken from X, equal distances are ordered by the rows' numbers in X, and the lists are written in X's numbering.
-__global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, int n, int d, int q0, int rows, int k,
-                                                  int kp, const float *__restrict__ norms, float norm_max,
+// Exact distances of the candidates, final order, certificate.  One block per query.
+// Query number i = q0 + block is row qmap[i] of X (row i if qmap is null); candidate number j is row cmap[j] of Y
+// (row j); distances are taken from those rows, equal distances are ordered by the candidates' row numbers, which
+// are also what is written, to row omap[i] (row i) of the result.  n_all: how many candidates a query can have at
+// all (one that has them all needs no certificate).  norms_q by query number, norm_max over the database.
+__global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, int nx, int d, const int *__restrict__ qmap,
+                                                  const float *__restrict__ Y, int ny, const int *__restrict__ cmap,
+                                                  const int *__restrict__ omap, int q0, int rows, int k, int kp, int n_all,
+                                                  const float *__restrict__ norms_q, float norm_max,
                                                   const float *__restrict__ tau, const int *__restrict__ cnt,
-                                                  const uint64_t *__restrict__ cand, int cap, const int *__restrict__ idmap,
+                                                  const uint64_t *__restrict__ cand, int cap,
                                                   int32_t *__restrict__ knn_idx, double *__restrict__ knn_d2,
                                                   int *__restrict__ fail_count, int *__restrict__ fail_rows)
 {
@@ -716,25 +725,24 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
     double *dd = reinterpret_cast<double *>(smem + up((size_t)d * 4)); // MAX_KP doubles
     __shared__ uint64_t key[MAX_KP];
     __shared__ int order[MAX_KP];
+    __shared__ int cid[MAX_KP];          // the candidates' row numbers in Y
     const int row = blockIdx.x;
     if (row >= rows) return;
     const int i = q0 + row;
     int c = cnt[row];
     if (c > kp) c = kp;
-    __shared__ int cid[MAX_KP];          // the candidates' row numbers in X
-    const int iu = idmap ? min(max(idmap[i], 0), n - 1) : i;
+    const int iu = min(max(qmap ? qmap[i] : i, 0), nx - 1);
     const float *x = X + (size_t)iu * d;
     for (int t = threadIdx.x; t < d; t += blockDim.x) xi[t] = x[t];
     const uint64_t *buf = cand + (size_t)row * cap;
     for (int a = threadIdx.x; a < c; a += blockDim.x) {
-        const int j = min((int)(uint32_t)buf[a], n - 1);
-        cid[a] = idmap ? min(max(idmap[j], 0), n - 1) : j;
+        const int j = (int)(uint32_t)buf[a];
+        cid[a] = min(max(cmap ? cmap[min(j, ny - 1)] : j, 0), ny - 1);
     }
     __syncthreads();
     const int w = threadIdx.x >> 6;
     for (int cidx = w; cidx < c; cidx += 4) {
-        const int j = cid[cidx];
-        const float *y = X + (size_t)j * d;
+        const float *y = Y + (size_t)cid[cidx] * d;
         double s = 0.0;
         for (int t = lane_id(); t < d; t += WAVE) { double df = (double)xi[t] - (double)y[t]; s += df * df; }
         s = wave_sum(s);
@@ -755,18 +763,19 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
         order[r] = a;
     }
     __syncthreads();
+    const size_t orow = (size_t)(omap ? min(max(omap[i], 0), nx - 1) : i);
     for (int r = threadIdx.x; r < k && r < c; r += blockDim.x) {
         const int a = order[r];
-        knn_idx[(size_t)iu * k + r] = (int32_t)cid[a];
-        knn_d2[(size_t)iu * k + r] = dd[a];
+        knn_idx[orow * k + r] = (int32_t)cid[a];
+        if (knn_d2) knn_d2[orow * k + r] = dd[a];
     }
     if (threadIdx.x == 0) {
         // pairs never kept had single-precision distance >= tau; the error of that distance is
         // at most E, so they are farther than the exact k-th candidate if tau - E > D_k
         bool ok = c >= k;
-        if (ok && c < n - 1) {
+        if (ok && c < n_all) {
             // (the additive term covers matrix cores that flush denormal bf16 parts to zero)
-            const double E = tile_error_coeff(d, d > KFLUSH) * ((double)norms[i] + (double)norm_max) + 1e-30 * d;
+            const double E = tile_error_coeff(d, d > KFLUSH) * ((double)norms_q[i] + (double)norm_max) + 1e-30 * d;
             const double Dk = dd[order[k - 1]];
             ok = (double)tau[row] - E > Dk;
         }
@@ -779,13 +788,16 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
 // between rows[f] and j.  A wave holds one database row in registers and meets every failed row
 // (which come from the second-level cache), so X is read from memory once per batch.
 constexpr int EXACT_MAX_D = 4096;
-__global__ __launch_bounds__(256) void knn_exact_dists(const float *__restrict__ X, int n, int d,
-                                                       const int *__restrict__ rows, int nb, uint64_t *__restrict__ okey)
+// (queries: rows qmap[rows[f]] of X, or rows[f]; database: the ny rows of Y; exclude_self: X and Y are the same rows)
+__global__ __launch_bounds__(256) void knn_exact_dists(const float *__restrict__ X, int nx, const int *__restrict__ qmap,
+                                                       const float *__restrict__ Y, int ny, int d,
+                                                       const int *__restrict__ rows, int nb, int exclude_self,
+                                                       uint64_t *__restrict__ okey)
 {
     const size_t w = global_index() >> 6;
-    if (w >= (size_t)n) return;
+    if (w >= (size_t)ny) return;
     const int j = (int)w;
-    const float *y = X + (size_t)j * d;
+    const float *y = Y + (size_t)j * d;
     float yr[EXACT_MAX_D / WAVE];
 #pragma unroll
     for (int q = 0; q < EXACT_MAX_D / WAVE; ++q) {
@@ -793,7 +805,9 @@ __global__ __launch_bounds__(256) void knn_exact_dists(const float *__restrict__
         yr[q] = (q * WAVE < d && t < d) ? y[t] : 0.f;
     }
     for (int f = 0; f < nb; ++f) {
-        const int i = min(max(rows[f], 0), n - 1);
+        int i = rows[f];
+        if (qmap) i = qmap[i];
+        i = min(max(i, 0), nx - 1);
         const float *x = X + (size_t)i * d;
         double s = 0.0;
 #pragma unroll
@@ -805,7 +819,7 @@ __global__ __launch_bounds__(256) void knn_exact_dists(const float *__restrict__
             }
         }
         s = wave_sum(s);
-        if (lane_id() == 0) okey[(size_t)f * n + j] = (j == i) ? ~0ull : orderable64(s);
+        if (lane_id() == 0) okey[(size_t)f * ny + j] = (exclude_self && j == i) ? ~0ull : orderable64(s);
     }
 }
 
@@ -885,7 +899,7 @@ __global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restr
         int r = 0;
         for (int b = 0; b < below; ++b) r += (selk[b] < ka) || (selk[b] == ka && selj[b] < ja);
         knn_idx[(size_t)i * k + r] = ja;
-        knn_d2[(size_t)i * k + r] = key_to_double(ka);
+        if (knn_d2) knn_d2[(size_t)i * k + r] = key_to_double(ka);
     }
     const double dk = key_to_double(prefix);
     if (ntie <= TIE_CAP) {
@@ -906,7 +920,7 @@ __global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restr
             }
         for (int t = threadIdx.x; t < want && t < ntie; t += blockDim.x) {
             knn_idx[(size_t)i * k + below + t] = (int32_t)tie[t];
-            knn_d2[(size_t)i * k + below + t] = dk;
+            if (knn_d2) knn_d2[(size_t)i * k + below + t] = dk;
         }
     } else {
         // more equidistant rows than the tie buffer holds: the lowest number above the last one taken, `want` times
@@ -925,7 +939,7 @@ __global__ __launch_bounds__(1024) void knn_exact_select(const uint64_t *__restr
             __syncthreads();
             last = best;
             if (last == 0x7FFFFFFF) break;
-            if (threadIdx.x == 0) { knn_idx[(size_t)i * k + out] = last; knn_d2[(size_t)i * k + out] = dk; }
+            if (threadIdx.x == 0) { knn_idx[(size_t)i * k + out] = last; if (knn_d2) knn_d2[(size_t)i * k + out] = dk; }
         }
     }
 }
@@ -1175,6 +1189,13 @@ __global__ __launch_bounds__(1024) void excl_scan_k(const int *__restrict__ in, 
     if (threadIdx.x == 1023) out[m] = pre;
 }
 
+// the evenly spaced sample of m of n rows: floor(i n / m)
+__global__ void sample_rows_k(int *__restrict__ rows, int n, int m)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m) rows[i] = (int)(((long long)i * n) / m);
+}
+
 __global__ void fill_int_k(int *__restrict__ a, int v, int m)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1345,13 +1366,6 @@ size_t ts_carve(TileSearchLayout *L, int n, int d, int k, int nlist, int tau, ch
 }
 }  // namespace
 
-// (0: these sizes are beyond the tile search; the caller keeps to its double-precision kernels)
-size_t ivf_search_tiles_workspace(int n, int d, int k, int nlist, int tau)
-{
-    if (check_args(n, d, k) != TSNE_OK) return 0;
-    return ts_carve(nullptr, n, d, k, nlist, tau, nullptr);
-}
-
 int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, const int32_t *probe, const int *lorder,
                      const int *cellptr, int max_list, long long max_cand, int32_t *knn_idx, double *knn_d2, void *ws,
                      size_t ws_bytes, hipStream_t s)
@@ -1365,8 +1379,8 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
     const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks_mu = (n + rows_per_chunk - 1) / rows_per_chunk;
     hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks_mu), dim3(256), 0, s, X, n, d, rows_per_chunk, L.mu_part);
     hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks_mu, n, d, dp, L.mu);
-    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, X, L.mu, n, d, lorder, L.norms);
-    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, X, L.mu, n, d, dp, lorder, L.xs);
+    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, X, L.mu, n, d, lorder, n, L.norms);
+    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, X, L.mu, n, d, dp, lorder, n, L.xs);
     hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms, n, L.norm_max);
     hipLaunchKernelGGL(probe_gather, wide_grid((size_t)n * tau), dim3(256), 0, s, probe, lorder, n, tau, nlist, L.probe_l);
     HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
@@ -1392,8 +1406,8 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
                 hipLaunchKernelGGL(tile_count, dim3(lb), dim3(256), 0, s, L.pairptr, cellptr, nlist, c, 128, L.tcnt);
                 hipLaunchKernelGGL(excl_scan_k, dim3(1), dim3(1024), 0, s, L.tcnt, nlist, L.tptr);
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, true>), dim3(bound), dim3(256), 0, s, (const uint4 *)L.xs, dp, q0,
-                                   q0 + rows, 0, 0, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount, L.tptr, nlist, L.pairptr,
-                                   L.pairq, cellptr, c);
+                                   q0 + rows, 0, 0, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount, (const uint4 *)L.xs, L.norms, 1, L.tptr,
+                                   nlist, L.pairptr, L.pairq, cellptr, c);
                 const int force = r == tau - 1 && c == nchunks - 1 ? 1 : 0;
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, L.ccount);
@@ -1406,8 +1420,9 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
                     hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, L.ccount);
             }
         }
-        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, q0, rows, k, kp, L.norms, norm_max, L.tau,
-                           L.cnt, L.cand, cap, lorder, knn_idx, knn_d2, L.fail_count, L.fail_rows);
+        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, lorder, X, n, lorder, lorder, q0, rows, k,
+                           kp, 0x7FFFFFFF, L.norms, norm_max, L.tau, L.cnt, L.cand, cap, knn_idx, knn_d2, L.fail_count,
+                           L.fail_rows);
         HIPCHK(hipGetLastError());
     }
     int nfail = 0;
@@ -1426,6 +1441,142 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
                                cellptr, lorder, stride, okey, ids, L.fcnt);
             hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, okey, stride, 0, L.fcnt, ids, k, L.fail_rows + f0,
                                lorder, n, knn_idx, knn_d2);
+            HIPCHK(hipGetLastError());
+        }
+    }
+    return TSNE_OK;
+}
+
+// ---- Eq. (10) for long rows: the tau nearest centroids of m rows of X (all rows, or the evenly spaced sample
+// floor(i n / m) that k-means works on), by (distance in double, centroid number).  The same scheme once more:
+// candidates from the tiles (queries against centroids, both centred on X's column means), the tau + 32 best
+// re-ranked in double, a certificate, and all centroids in double for a query without one.
+namespace {
+struct TileProbeLayout {
+    float *norms_q, *norms_c, *norm_max, *tau, *mu;
+    double *mu_part;
+    int *cnt, *clist, *ccount, *fail_count, *fail_rows, *qrows;
+    uint64_t *cand;
+    uint16_t *xs, *cs;
+    size_t cand_bytes;
+};
+
+int probe_kp(int nlist, int tau) { return tau + 32 < nlist ? tau + 32 : nlist; }
+
+size_t tp_carve(TileProbeLayout *L, int n, int d, int nlist, int tau, char *base)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up(bytes); return (void *)p; };
+    const size_t cap = (size_t)probe_kp(nlist, tau) + COMPACT_SLACK + COMPACT_EVERY * DBC;
+    const size_t qb = (size_t)(n < TS_ROWS ? n : TS_ROWS);
+    const size_t dp = ((size_t)d + SLAB - 1) / SLAB * SLAB;
+    void *q;
+    q = take(4 * (size_t)n); if (L) L->norms_q = (float *)q;
+    q = take(4 * (size_t)nlist); if (L) L->norms_c = (float *)q;
+    q = take(4); if (L) L->norm_max = (float *)q;
+    q = take(4 * qb); if (L) L->tau = (float *)q;
+    q = take(4 * dp); if (L) L->mu = (float *)q;
+    q = take(8 * (size_t)MEAN_CHUNKS * d); if (L) L->mu_part = (double *)q;
+    q = take(4 * qb); if (L) L->cnt = (int *)q;
+    q = take(4 * qb); if (L) L->clist = (int *)q;
+    q = take(8); if (L) L->ccount = (int *)q;
+    q = take(4); if (L) L->fail_count = (int *)q;
+    q = take(4 * (size_t)n); if (L) L->fail_rows = (int *)q;
+    q = take(4 * (size_t)n); if (L) L->qrows = (int *)q;
+    q = take(4 * (size_t)n * dp); if (L) L->xs = (uint16_t *)q;
+    q = take(4 * (size_t)nlist * dp); if (L) L->cs = (uint16_t *)q;
+    size_t cb = 8 * qb * cap;
+    if (cb < 8 * (size_t)nlist) cb = 8 * (size_t)nlist;      // the exact pass: at least one query's keys
+    q = take(cb); if (L) { L->cand = (uint64_t *)q; L->cand_bytes = cb; }
+    return off;
+}
+}  // namespace
+
+// workspace of ivf_probe_tiles and, if k > 0, of ivf_search_tiles, which run one after the other (0: not for these sizes)
+size_t ivf_tiles_workspace(int n, int d, int k, int nlist, int tau)
+{
+    if (n < 2 || d < 1 || d > 4096 || nlist < 1 || tau < 1 || tau > nlist) return 0;
+    size_t a = tp_carve(nullptr, n, d, nlist, tau, nullptr), b = 0;
+    if (k > 0) {
+        if (check_args(n, d, k) != TSNE_OK) return 0;
+        b = ts_carve(nullptr, n, d, k, nlist, tau, nullptr);
+    }
+    return a > b ? a : b;
+}
+
+int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int tau, int m, int32_t *probe, void *ws,
+                    size_t ws_bytes, hipStream_t s)
+{
+    if (n < 2 || d < 1 || d > 4096 || nlist < 1 || tau < 1 || tau > nlist || m < 1 || m > n) return TSNE_EINVAL;
+    if (ws_bytes < tp_carve(nullptr, n, d, nlist, tau, nullptr)) return TSNE_ENOSPC;
+    TileProbeLayout L;
+    tp_carve(&L, n, d, nlist, tau, (char *)ws);
+    const int kp = probe_kp(nlist, tau), cap = kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
+    const int dp = (d + SLAB - 1) / SLAB * SLAB;
+    const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks_mu = (n + rows_per_chunk - 1) / rows_per_chunk;
+    hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks_mu), dim3(256), 0, s, X, n, d, rows_per_chunk, L.mu_part);
+    hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks_mu, n, d, dp, L.mu);
+    const int *rowmap = nullptr;
+    if (m < n) {
+        hipLaunchKernelGGL(sample_rows_k, dim3((m + 255) / 256), dim3(256), 0, s, L.qrows, n, m);
+        rowmap = L.qrows;
+    }
+    hipLaunchKernelGGL(row_norms, wide_grid((size_t)m * WAVE), dim3(256), 0, s, X, L.mu, m, d, rowmap, n, L.norms_q);
+    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)m * dp), dim3(256), 0, s, X, L.mu, m, d, dp, rowmap, n, L.xs);
+    hipLaunchKernelGGL(row_norms, wide_grid((size_t)nlist * WAVE), dim3(256), 0, s, C, L.mu, nlist, d, (const int *)nullptr, nlist,
+                       L.norms_c);
+    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)nlist * dp), dim3(256), 0, s, C, L.mu, nlist, d, dp, (const int *)nullptr,
+                       nlist, L.cs);
+    hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms_c, nlist, L.norm_max);
+    HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
+    float norm_max = 0.f;
+    HIPCHK(hipMemcpyAsync(&norm_max, L.norm_max, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    const size_t rerank_smem = up((size_t)d * 4) + 8 * (size_t)MAX_KP;
+    for (int q0 = 0; q0 < m; q0 += TS_ROWS) {
+        const int rows = m - q0 < TS_ROWS ? m - q0 : TS_ROWS;
+        hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows, L.ccount);
+        // short first slabs bring the cut-offs down early (until a query has kp candidates it keeps every pair)
+        int step = kp + 64 <= 256 ? 256 : DBC;
+        for (int j0 = 0, jend; j0 < nlist; j0 = jend) {
+            jend = j0 + step < nlist ? j0 + step : nlist;
+            if (jend > step && step < DBC) step *= 2;
+            const unsigned gy = (unsigned)((jend - j0 + TN - 1) / TN);
+            const int force = jend >= nlist ? 1 : 0;
+            if (d > KFLUSH)
+                hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
+                                   (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap, L.ccount,
+                                   (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 0, (const int *)nullptr,
+                                   (const int *)nullptr, (const int *)nullptr, 0);
+            else
+                hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
+                                   0, s, (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap,
+                                   L.ccount, (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 0, (const int *)nullptr,
+                                   (const int *)nullptr, (const int *)nullptr, 0);
+            hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
+                               L.clist, L.ccount);
+            const unsigned cg = (unsigned)(rows < 4096 ? rows : 4096);
+            hipLaunchKernelGGL((knn_compact<512, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist,
+                               L.ccount);
+        }
+        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, rowmap, C, nlist, (const int *)nullptr,
+                           (const int *)nullptr, q0, rows, tau, kp, nlist, L.norms_q, norm_max, L.tau, L.cnt, L.cand, cap, probe,
+                           (double *)nullptr, L.fail_count, L.fail_rows);
+        HIPCHK(hipGetLastError());
+    }
+    int nfail = 0;
+    HIPCHK(hipMemcpyAsync(&nfail, L.fail_count, 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    if (nfail > 0) {
+        size_t nb_max = L.cand_bytes / (8 * (size_t)nlist);
+        if (nb_max > 4096) nb_max = 4096;
+        if (nb_max < 1) return TSNE_ENOSPC;
+        for (int f0 = 0; f0 < nfail; f0 += (int)nb_max) {
+            const int nb = nfail - f0 < (int)nb_max ? nfail - f0 : (int)nb_max;
+            hipLaunchKernelGGL(knn_exact_dists, wide_grid((size_t)nlist * WAVE), dim3(256), 0, s, X, n, rowmap, C, nlist, d,
+                               L.fail_rows + f0, nb, 0, L.cand);
+            hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, L.cand, (size_t)nlist, nlist, (const int *)nullptr,
+                               (const int *)nullptr, tau, L.fail_rows + f0, (const int *)nullptr, m, probe, (double *)nullptr);
             HIPCHK(hipGetLastError());
         }
     }
@@ -1494,8 +1645,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks = (n + rows_per_chunk - 1) / rows_per_chunk;
     hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks), dim3(256), 0, s, d_X, n, d, rows_per_chunk, L.mu_part);
     hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks, n, d, dp, L.mu);
-    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, L.mu, n, d, (const int *)nullptr, L.norms);
-    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, d_X, L.mu, n, d, dp, (const int *)nullptr, L.xs);
+    hipLaunchKernelGGL(row_norms, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, L.mu, n, d, (const int *)nullptr, n, L.norms);
+    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)n * dp), dim3(256), 0, s, d_X, L.mu, n, d, dp, (const int *)nullptr, n, L.xs);
     hipLaunchKernelGGL(max_norm_k, dim3(1), dim3(1024), 0, s, L.norms, n, L.norm_max);
     HIPCHK(hipMemsetAsync(L.fail_count, 0, 4, s));
     HIPCHK(hipMemsetAsync(L.unconv, 0, 4, s));
@@ -1538,13 +1689,13 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                 if (d > KFLUSH)
                     hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                        (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const int *)nullptr, 0, (const int *)nullptr, (const int *)nullptr,
-                                       (const int *)nullptr, 0);
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 0, (const int *)nullptr,
+                                       (const int *)nullptr, (const int *)nullptr, 0);
                 else
                     hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
                                        0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const int *)nullptr, 0, (const int *)nullptr, (const int *)nullptr,
-                                       (const int *)nullptr, 0);
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 0, (const int *)nullptr,
+                                       (const int *)nullptr, (const int *)nullptr, 0);
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, cc);
             }
@@ -1558,8 +1709,9 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
             else
                 hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
         }
-        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, q0, rows, k, kp, L.norms,
-                           norm_max, L.tau, L.cnt, L.cand, cap, (const int *)nullptr, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
+        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, (const int *)nullptr, d_X, n,
+                           (const int *)nullptr, (const int *)nullptr, q0, rows, k, kp, n - 1, L.norms,
+                           norm_max, L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
         HIPCHK(hipGetLastError());
     }
     int nfail = 0;
@@ -1569,8 +1721,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     // rows a launch (their n keys each fit the space the symmetrisation sorts in later, 2 n k words).
     for (int f0 = 0; f0 < nfail; f0 += 2 * k) {
         const int nb = nfail - f0 < 2 * k ? nfail - f0 : 2 * k;
-        hipLaunchKernelGGL(knn_exact_dists, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, n, d, L.fail_rows + f0, nb,
-                           L.sort_scratch);
+        hipLaunchKernelGGL(knn_exact_dists, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, n, (const int *)nullptr, d_X, n, d,
+                           L.fail_rows + f0, nb, 1, L.sort_scratch);
         hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, L.sort_scratch, (size_t)n, n, (const int *)nullptr,
                            (const int *)nullptr, k, L.fail_rows + f0, (const int *)nullptr, n, L.knn_idx, L.knn_d2);
         HIPCHK(hipGetLastError());

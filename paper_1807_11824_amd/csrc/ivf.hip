@@ -800,9 +800,12 @@ __global__ __launch_bounds__(256) void ivf_select(const float *__restrict__ F, c
 // LDS for the chunk buffers of the distance kernels: none while a row fits one chunk
 size_t chunk_lds(int d, int waves) { return d > IVF_DC ? 4 * (size_t)IVF_DC * WAVE * waves : 0; }
 
-void launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nlist, int tau, int32_t *probe, int m,
-                  hipStream_t s)
+// Eq. (10) for the rows floor(i n / m), i < m, of X.  Long rows go through the matrix-core tiles when the caller has
+// their workspace (C: the centroids as floats); Cd: the centroids as doubles, rows padded to dp.
+int launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nlist, int tau, int32_t *probe, int m,
+                 hipStream_t s, const float *C = nullptr, void *tiles_ws = nullptr, size_t tiles_bytes = 0)
 {
+    if (d > IVF_DC && C && tiles_bytes > 0) return ivf_probe_tiles(X, n, d, C, nlist, tau, m, probe, tiles_ws, tiles_bytes, s);
     const size_t lists = 12 * (size_t)WAVE * tau;
     if (d > IVF_DC)
         hipLaunchKernelGGL(ivf_probe<true>, dim3((m + WAVE - 1) / WAVE), dim3(WAVE), lists + chunk_lds(d, 1), s, X, n, d, dp, Cd,
@@ -810,6 +813,7 @@ void launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nl
     else
         hipLaunchKernelGGL(ivf_probe<false>, dim3((m + WAVE - 1) / WAVE), dim3(WAVE), lists, s, X, n, d, dp, Cd, nlist, tau,
                            probe, m);
+    return TSNE_OK;
 }
 
 int select_buf(int k)
@@ -850,8 +854,9 @@ struct IvfLayout {
 
 constexpr int IVF_BATCH_ROWS = 1 << 17;
 
-// k_tiles: the k of a search that may go through ivf_search_tiles (0: no such search with this workspace)
-size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, size_t avail, int k_tiles = 0)
+// k_tiles: -1 none of the tile kernels is used with this workspace; 0 the probe only (k-means); > 0 the probe and a
+// search for this k
+size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, size_t avail, int k_tiles = -1)
 {
     size_t off = 0;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up256(bytes); return (void *)p; };
@@ -878,7 +883,7 @@ size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, siz
     q = take(8 * 8 * (size_t)nlist); if (L) L->mind = (double *)q;
     q = take(4 * (size_t)nlist); if (L) L->sel = (int *)q;
     {
-        const size_t tb = k_tiles > 0 && d > IVF_DC ? ivf_search_tiles_workspace(n, d, k_tiles, nlist, tau) : 0;
+        const size_t tb = k_tiles >= 0 && d > IVF_DC ? ivf_tiles_workspace(n, d, k_tiles, nlist, tau) : 0;
         q = take(tb); if (L) { L->tiles_ws = q; L->tiles_bytes = tb; }
     }
     // distance scratch: whatever is left, at least one row of n distances, at most IVF_D_MAX
@@ -912,8 +917,8 @@ size_t ivf_workspace(int n, int d, int k, int nlist, int tau)
 int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *C, void *ws, size_t ws_bytes, hipStream_t s)
 {
     IvfLayout L;
-    if (ws_bytes < ivf_carve(nullptr, n, d, nlist, 1, nullptr, 0)) return TSNE_ENOSPC;
-    ivf_carve(&L, n, d, nlist, 1, (char *)ws, ws_bytes);
+    if (ws_bytes < ivf_carve(nullptr, n, d, nlist, 1, nullptr, 0, 0)) return TSNE_ENOSPC;
+    ivf_carve(&L, n, d, nlist, 1, (char *)ws, ws_bytes, 0);
     const size_t cd = (size_t)nlist * d, nd = (size_t)n * d;
     const int dp = (d + 3) / 4 * 4;
     {
@@ -942,7 +947,10 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     const int ms = (long long)n < 256ll * nlist ? n : 256 * nlist;
     for (int it = 0; it < iters; ++it) {
         hipLaunchKernelGGL(to_double_k, (blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
-        launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, ms, s);
+        {
+            const int rc = launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, ms, s, C, L.tiles_ws, L.tiles_bytes);
+            if (rc != TSNE_OK) return rc;
+        }
         hipLaunchKernelGGL(fill_u64_k, (blocks(cd)), dim3(256), 0, s, L.sums, cd);
         hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist);
         hipLaunchKernelGGL(kmeans_accum, (blocks((size_t)ms * d)), dim3(256), 0, s, X, n, d, L.probe, 1, scale, L.sums, L.cnt,
@@ -958,12 +966,15 @@ static int ivf_knn_impl(const float *X, int n, int d, const float *C, int nlist,
                         double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s, PqView pq)
 {
     IvfLayout L;
-    const int k_tiles = pq.codes ? 0 : k;
+    const int k_tiles = pq.codes ? -1 : k;
     if (ws_bytes < ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0, k_tiles)) return TSNE_ENOSPC;
     ivf_carve(&L, n, d, nlist, tau, (char *)ws, ws_bytes, k_tiles);
     const int dp = (d + 3) / 4 * 4;
     hipLaunchKernelGGL(to_double_k, (blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
-    launch_probe(X, n, d, dp, L.Cd, nlist, tau, L.probe, n, s);
+    {
+        const int rc = launch_probe(X, n, d, dp, L.Cd, nlist, tau, L.probe, n, s, C, L.tiles_ws, L.tiles_bytes);
+        if (rc != TSNE_OK) return rc;
+    }
     hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cnt, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(fill_i32_k, (blocks((size_t)nlist + 1)), dim3(256), 0, s, L.cursor, 0, (size_t)nlist + 1);
     hipLaunchKernelGGL(cell_hist, (blocks((size_t)n)), dim3(256), 0, s, L.probe, n, tau, L.cnt);
@@ -1084,7 +1095,7 @@ size_t pq_carve(PqLayout *L, int n, int d, int k, int nlist, int tau, int m, int
     q = take(8 * (size_t)ksub * dsp); if (L) L->cbd = (double *)q;
     q = take(8 * (size_t)nlist * dp); if (L) L->Cd = (double *)q;
     q = take((size_t)n * m); if (L) L->codes = (unsigned char *)q;
-    size_t a = ivf_carve(nullptr, n, ds, ksub, 1, nullptr, 0);            // training a sub-quantiser
+    size_t a = ivf_carve(nullptr, n, ds, ksub, 1, nullptr, 0, 0);         // training a sub-quantiser
     size_t b = tau > 0 ? ivf_carve(nullptr, n, d, nlist, tau, nullptr, 0) : 0;   // the search
     (void)k;
     if (L) { L->inner = base + off; L->inner_bytes = avail > off ? avail - off : 0; }

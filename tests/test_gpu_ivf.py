@@ -125,7 +125,8 @@ def test_too_few_candidates_is_reported():
 
 
 # (the last: 8 centroids, so the rounds run on a sample of 2048 of the 6000 rows)
-@pytest.mark.parametrize("n,d,nlist,iters", [(4000, 20, 30, 5), (1500, 70, 12, 3), (300, 3, 300, 2), (6000, 10, 8, 4)])
+@pytest.mark.parametrize("n,d,nlist,iters", [(4000, 20, 30, 5), (1500, 70, 12, 3), (300, 3, 300, 2), (6000, 10, 8, 4),
+                                             (20000, 96, 700, 3), (400, 65, 400, 2)])
 def test_kmeans_matches_oracle(n, d, nlist, iters):
     """Same start, same rule; the means are exact sums here and double sums there, both rounded to float."""
     from paper_1807_11824_amd import ivf_train
@@ -192,13 +193,16 @@ def _pq_case(name):
     if name == "scalar_subvectors":          # m = d: one coordinate per sub-quantiser
         X = r.standard_normal((2000, 8)).astype(np.float32)
         return X, 10, 10, 20, 8, 16, 3
+    if name == "long_subvectors":            # sub-vectors of 70 coordinates: the sub-quantisers train through the tiles
+        X, _ = synth.gaussian_mixture(2500, 140, 5, 3.0, 1.0, seed=13)
+        return X, 20, 4, 25, 2, 32, 3
     if name == "many_equal_codes":           # few centroids: many candidates share a code and tie exactly (index decides)
         X, _ = synth.gaussian_mixture(3000, 12, 4, 5.0, 1.0, seed=8)
         return X, 8, 3, 50, 2, 4, 2
     raise KeyError(name)
 
 
-@pytest.mark.parametrize("name", ["blobs_32d_m8", "full_codebooks", "one_subvector", "scalar_subvectors",
+@pytest.mark.parametrize("name", ["blobs_32d_m8", "full_codebooks", "one_subvector", "scalar_subvectors", "long_subvectors",
                                   "many_equal_codes"])
 def test_ivfpq_matches_oracle(name):
     """Codebooks (k-means per sub-vector of the residuals), codes and the search of Eq. (11) on the codes: the
