@@ -741,12 +741,43 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
     }
     __syncthreads();
     const int w = threadIdx.x >> 6;
-    for (int cidx = w; cidx < c; cidx += 4) {
-        const float *y = Y + (size_t)cid[cidx] * d;
-        double s = 0.0;
-        for (int t = lane_id(); t < d; t += WAVE) { double df = (double)xi[t] - (double)y[t]; s += df * df; }
-        s = wave_sum(s);
-        if (lane_id() == 0) dd[cidx] = s;
+    if (d % 4 == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0) {
+        // rows of whole 16-byte pieces: a lane takes four coordinates a load and keeps four partial sums; a wave
+        // has two candidates' rows in flight
+        const float4 *x4 = reinterpret_cast<const float4 *>(xi);
+        const int d4 = d / 4;
+        for (int cidx = w; cidx < c; cidx += 8) {
+            const bool two = cidx + 4 < c;
+            const float4 *ya = reinterpret_cast<const float4 *>(Y + (size_t)cid[cidx] * d);
+            const float4 *yb = reinterpret_cast<const float4 *>(Y + (size_t)cid[two ? cidx + 4 : cidx] * d);
+            double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0, b0 = 0.0, b1 = 0.0, b2 = 0.0, b3 = 0.0;
+#pragma unroll 2
+            for (int t = lane_id(); t < d4; t += WAVE) {
+                const float4 q = x4[t], u = ya[t], v = yb[t];
+                double df;
+                df = (double)q.x - (double)u.x; a0 += df * df;
+                df = (double)q.y - (double)u.y; a1 += df * df;
+                df = (double)q.z - (double)u.z; a2 += df * df;
+                df = (double)q.w - (double)u.w; a3 += df * df;
+                df = (double)q.x - (double)v.x; b0 += df * df;
+                df = (double)q.y - (double)v.y; b1 += df * df;
+                df = (double)q.z - (double)v.z; b2 += df * df;
+                df = (double)q.w - (double)v.w; b3 += df * df;
+            }
+            const double sa = wave_sum((a0 + a1) + (a2 + a3)), sb = wave_sum((b0 + b1) + (b2 + b3));
+            if (lane_id() == 0) {
+                dd[cidx] = sa;
+                if (two) dd[cidx + 4] = sb;
+            }
+        }
+    } else {
+        for (int cidx = w; cidx < c; cidx += 4) {
+            const float *y = Y + (size_t)cid[cidx] * d;
+            double s = 0.0;
+            for (int t = lane_id(); t < d; t += WAVE) { double df = (double)xi[t] - (double)y[t]; s += df * df; }
+            s = wave_sum(s);
+            if (lane_id() == 0) dd[cidx] = s;
+        }
     }
     __syncthreads();
     // rank by (distance, index): c <= 2048, plain counting rank is enough
@@ -1319,6 +1350,9 @@ int check_args(int32_t n, int32_t d, int32_t k)
 // (distance in double, row number).  probe: n x tau list numbers (Eq. (10)), lorder: the rows in list order,
 // cellptr: where each list starts in it; max_list and max_cand (longest list, most rows in one query's lists) from the caller.
 namespace {
+// (the k-th and the (k + 16)-th neighbour of a point are much farther apart than the error of a tile distance)
+int search_kp(int n, int k) { return k + 16 < n - 1 ? k + 16 : n - 1; }
+
 struct TileSearchLayout {
     float *norms, *norm_max, *tau, *mu;
     double *mu_part;
@@ -1334,7 +1368,7 @@ size_t ts_carve(TileSearchLayout *L, int n, int d, int k, int nlist, int tau, ch
 {
     size_t off = 0;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += up(bytes); return (void *)p; };
-    const int kp = margin_kp(n, k);
+    const int kp = search_kp(n, k);
     const size_t cap = (size_t)kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
     const size_t qb = (size_t)(n < TS_ROWS ? n : TS_ROWS);
     const size_t dp = ((size_t)d + SLAB - 1) / SLAB * SLAB;
@@ -1374,7 +1408,7 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
     if (ws_bytes < ts_carve(nullptr, n, d, k, nlist, tau, nullptr)) return TSNE_ENOSPC;
     TileSearchLayout L;
     ts_carve(&L, n, d, k, nlist, tau, (char *)ws);
-    const int kp = margin_kp(n, k), cap = kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
+    const int kp = search_kp(n, k), cap = kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
     const int dp = (d + SLAB - 1) / SLAB * SLAB;
     const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks_mu = (n + rows_per_chunk - 1) / rows_per_chunk;
     hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks_mu), dim3(256), 0, s, X, n, d, rows_per_chunk, L.mu_part);
@@ -1461,7 +1495,8 @@ struct TileProbeLayout {
     size_t cand_bytes;
 };
 
-int probe_kp(int nlist, int tau) { return tau + 32 < nlist ? tau + 32 : nlist; }
+// (centroids are far apart against the error of a tile distance: eight spare candidates certify nearly every query)
+int probe_kp(int nlist, int tau) { return tau + 8 < nlist ? tau + 8 : nlist; }
 
 size_t tp_carve(TileProbeLayout *L, int n, int d, int nlist, int tau, char *base)
 {
