@@ -18,6 +18,8 @@
 //                        the k nearest if cut-off - error bound > exact k-th distance
 //   knn_exact_dists / knn_exact_select   rows that fail the certificate: all n distances in
 //                        double, radix selection of the k-th smallest, ties by index
+//   ivf_probe_tiles / ivf_search_tiles   Eq. (10) and (11) of the approximate search for rows longer than 64
+//                        coordinates, on the same tiles, re-rank and certificate (called from ivf.hip)
 //   perplexity_search    Eq. (1) on the k neighbours, beta by bracketing + bisection on the entropy
 //   sym_count / sym_fill / sym_sort_rows   p_ij = (p_j|i + p_i|j) / 2N as CSR, columns ascending
 #include "tsne_internal.h"
