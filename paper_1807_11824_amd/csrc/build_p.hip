@@ -42,6 +42,7 @@ constexpr int COMPACT_SLACK = 64;  // new candidates per row that trigger a re-s
 constexpr int COMPACT_EVERY = 2;   // after the resident tile kernel a compaction pass follows every second slab only (a pass
                                    // costs a third of a slab; cut-offs one slab older let a few more pairs through)
 constexpr int KFLUSH = 64;      // columns summed on the matrix cores before a flush into the running sum
+constexpr int HIGH_FIRST_MIN_D = 256;   // from this many columns on the exact search sweeps with the high parts first
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -152,6 +153,17 @@ __global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, c
     o[SLAB] = (uint16_t)lo;
 }
 
+// The high parts alone, for the first sweep over long rows: row-major, rows padded to a multiple of 64 columns.
+__global__ __launch_bounds__(256) void split_high(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
+                                                  int dph, uint16_t *__restrict__ Xh)
+{
+    const size_t e = global_index();
+    if (e >= (size_t)n * dph) return;
+    const size_t row = e / dph;
+    const int k = (int)(e % dph);
+    Xh[e] = (uint16_t)(k < d ? bf16_rne(X[row * d + k] - mu[k]) : 0u);
+}
+
 // Bound on |computed - exact| of one tile distance, as a multiple of |q|^2 + |x|^2.
 //   split: the products left out (lo.lo, rest.x, x.rest) are at most 3 (1 + 2^-18) 2^-18 |q_t x_t| each;
 //   accumulation: a sum reaches the result through at most R fp32 additions, R = 3 * (columns per
@@ -164,12 +176,16 @@ __global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, c
 //   centring: q' = fl(q - mu), x' = fl(x - mu) are off by 2^-24 relative per coordinate, which moves
 //   |q' - x'|^2 by at most 2 |q - x| 2^-24 (|q'| + |x'|) <= 4 2^-24 (|q'|^2 + |x'|^2) (and a second-order term).
 // 5 % on top for the norms themselves being rounded values.  q, x here are the centred rows.
-__host__ __device__ inline double tile_error_coeff(int d, bool two_level)
+// high_only: the tiles multiply the high parts alone (one product per coordinate): what is left out is then
+// q ex + eq x - eq ex with |eq| <= 2^-9 |q|, |ex| <= 2^-9 |x|, at most (2^-8 + 2^-18) |q_t x_t|.
+__host__ __device__ inline double tile_error_coeff(int d, bool two_level, bool high_only = false)
 {
     const int dp = (d + SLAB - 1) / SLAB * SLAB;
-    const double R = two_level ? 3.0 * KFLUSH + (double)((dp + KFLUSH - 1) / KFLUSH) : 3.0 * dp;
+    const double per = high_only ? 1.0 : 3.0;      // products per coordinate
+    const double R = two_level ? per * KFLUSH + (double)((dp + KFLUSH - 1) / KFLUSH) : per * dp;
     const double u = 1.1920928955078125e-07;   // 2^-23
-    const double split = 3.0 * (1.0 + 3.814697265625e-06) * 3.814697265625e-06;
+    const double split = high_only ? 0.00390625 + 3.814697265625e-06
+                                   : 3.0 * (1.0 + 3.814697265625e-06) * 3.814697265625e-06;
     const double accum = 1.0079 * R * u / (1.0 - R * u);
     return 1.05 * (split + accum + (16.0 + 4.2) * 5.9604644775390625e-08);
 }
@@ -208,10 +224,12 @@ __device__ __noinline__ void append_queue(const lds_u32 *qrow, const lds_u64 *qk
 // qid (or null): the tile's query rows are not consecutive; qid[ql] is the row of the lane's query.
 __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0, const lds_f32 *qn, float nj, float dot,
                                         int fill, int qcap, lds_u64 *qkey, lds_u32 *qrow, int *__restrict__ cnt,
-                                        uint64_t *__restrict__ cand, int cap, const lds_u32 *qid, int exclude_self)
+                                        uint64_t *__restrict__ cand, int cap, const lds_u32 *qid, int exclude_self,
+                                        const int *__restrict__ selfmap)
 {
     const int q = qid ? (int)qid[ql] : qa + ql;
-    const bool take = near && (j != q || !exclude_self);
+    // (selfmap: query q is row selfmap[q] of the database)
+    const bool take = near && (!exclude_self || j != (selfmap ? selfmap[q] : q));
     const uint64_t m = __ballot(take);
     if (m == 0) return fill;
     if (fill + WAVE > qcap) { append_queue_inline(qrow, qkey, fill, cnt, cand, cap); fill = 0; }
@@ -237,13 +255,15 @@ __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0
 // the current rank are pairq[pairptr[L] .. pairptr[L+1]) (row numbers, any order); a launch takes the rows
 // chunk * DBC .. of every list.  Workgroup t < tptr[nlist] belongs to the list L with tptr[L] <= t < tptr[L+1] and
 // is tile (a, b) of its ceil(queries / TQ) x ceil(rows of the chunk / TN) tiles; workgroups past the end leave.
-template <int MB, bool TWO, bool GATHER>
+// ONE: the rows hold high parts only, 64 columns per 128-byte piece (split_high), one product per coordinate.
+template <int MB, bool TWO, bool GATHER, bool ONE = false>
 __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict__ Xs, int dp, int q0, int qend, int j0,
                                                         int jend, const float *__restrict__ norms,
                                                         const float *__restrict__ tau, int *__restrict__ cnt,
                                                         uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount,
                                                         const uint4 *__restrict__ Xb, const float *__restrict__ norms_b,
-                                                        int exclude_self, const int *__restrict__ tptr, int nlist,
+                                                        int exclude_self, const int *__restrict__ selfmap,
+                                                        const int *__restrict__ tptr, int nlist,
                                                         const int *__restrict__ pairptr, const int *__restrict__ pairq,
                                                         const int *__restrict__ cellptr, int chunk)
 {
@@ -274,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
         jend = min(re, ja + TN);
         qa = 0;
     }
-    const int row16 = dp / 4;              // 16-byte pieces per row of Xs
+    const int row16 = ONE ? dp / 8 : dp / 4;   // 16-byte pieces per row of Xs
     const int piece = tid & 7, lrow = tid >> 3;
     floatx16 acc[TWO ? MB : 1][TWO ? 2 : 1], part[MB][2];
 #pragma unroll
@@ -306,7 +326,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
     };
     load(0);
     const int r32 = lane & 31, h = lane >> 5;
-    const int nslab = dp / SLAB;
+    const int nslab = ONE ? dp / (2 * SLAB) : dp / SLAB;
     for (int slab = 0; slab < nslab; ++slab) {
         __syncthreads();
 #pragma unroll
@@ -321,7 +341,24 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
         // Both operands use the same assignment, so the products pair up whatever order the
         // hardware sums them in.
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ONE && ks < 4; ++ks) {
+            bf16x8 ah[MB], bh[2];
+            const unsigned char *pa = As + (wm * 32 * MB + r32) * LDS_ROW + ks * 32 + h * 16;
+            const unsigned char *pb = Bs + (wn * 64 + r32) * LDS_ROW + ks * 32 + h * 16;
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+                ah[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW));
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                bh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW));
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], part[a][b], 0, 0, 0);
+        }
+#pragma unroll
+        for (int ks = 0; !ONE && ks < 2; ++ks) {
             // low.high, high.high, high.low, in that order so that at most three fragment sets are live
             bf16x8 ah[MB], al[MB], bh[2], bl[2];
             const unsigned char *pa = As + (wm * 32 * MB + r32) * LDS_ROW + ks * 32 + h * 16;
@@ -354,7 +391,8 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
                 for (int b = 0; b < 2; ++b)
                     part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], part[a][b], 0, 0, 0);
         }
-        if (TWO && ((slab % (KFLUSH / SLAB)) == (KFLUSH / SLAB) - 1 || slab + 1 == nslab)) {
+        constexpr int FLUSH_SLABS = ONE ? 1 : KFLUSH / SLAB;
+        if (TWO && ((slab % FLUSH_SLABS) == FLUSH_SLABS - 1 || slab + 1 == nslab)) {
 #pragma unroll
             for (int a = 0; a < MB; ++a)
 #pragma unroll
@@ -411,7 +449,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
                         fill = __builtin_amdgcn_readfirstlane(queue_pairs(near, j, ql0 + ii, qa, q0, (const lds_f32 *)qn, nj, dot, fill, QCAP,
                                                                           qkey, qrow, cnt, cand, cap,
                                                                           GATHER ? (const lds_u32 *)qid : (const lds_u32 *)nullptr,
-                                                                          exclude_self));
+                                                                          exclude_self, selfmap));
                 }
             }
         }
@@ -712,10 +750,12 @@ __global__ __launch_bounds__(THREADS) void knn_compact(float *__restrict__ tau, 
 // Query number i = q0 + block is row qmap[i] of X (row i if qmap is null); candidate number j is row cmap[j] of Y
 // (row j); distances are taken from those rows, equal distances are ordered by the candidates' row numbers, which
 // are also what is written, to row omap[i] (row i) of the result.  n_all: how many candidates a query can have at
-// all (one that has them all needs no certificate).  norms_q by query number, norm_max over the database.
+// all (one that has them all needs no certificate).  norms_q by query number, norm_max over the database; coeff:
+// tile_error_coeff() of the tiles that found the candidates.  A query without a certificate is listed as failmap[i] (i).
 __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, int nx, int d, const int *__restrict__ qmap,
                                                   const float *__restrict__ Y, int ny, const int *__restrict__ cmap,
-                                                  const int *__restrict__ omap, int q0, int rows, int k, int kp, int n_all,
+                                                  const int *__restrict__ omap, const int *__restrict__ failmap, int q0,
+                                                  int rows, int k, int kp, int n_all, double coeff,
                                                   const float *__restrict__ norms_q, float norm_max,
                                                   const float *__restrict__ tau, const int *__restrict__ cnt,
                                                   const uint64_t *__restrict__ cand, int cap,
@@ -808,11 +848,11 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
         bool ok = c >= k;
         if (ok && c < n_all) {
             // (the additive term covers matrix cores that flush denormal bf16 parts to zero)
-            const double E = tile_error_coeff(d, d > KFLUSH) * ((double)norms_q[i] + (double)norm_max) + 1e-30 * d;
+            const double E = coeff * ((double)norms_q[i] + (double)norm_max) + 1e-30 * d;
             const double Dk = dd[order[k - 1]];
             ok = (double)tau[row] - E > Dk;
         }
-        if (!ok) fail_rows[atomicAdd(fail_count, 1)] = i;
+        if (!ok) fail_rows[atomicAdd(fail_count, 1)] = failmap ? failmap[i] : i;
     }
 }
 
@@ -1281,6 +1321,9 @@ struct Layout {
     double *mu_part;         // their partial sums, MEAN_CHUNKS x d
     uint64_t *cand, *sort_scratch;
     uint16_t *xs;            // the split copy of X
+    uint16_t *xh, *xsf;      // long rows: the high parts alone; the split copy of the rows of the second sweep
+    float *norms_f;          // their norms
+    int *fail2_count, *fail2_rows;
     int *clist, *ccount;     // rows of the current query block that need compaction, and how many (two counters take turns)
     int32_t *knn_idx;
     double *knn_d2, *cond;
@@ -1321,6 +1364,13 @@ size_t carve(Layout *L, int n, int d, int k, char *base)
     q = take(8 * (size_t)n * k); if (L) L->knn_d2 = (double *)q;
     q = take(8 * (size_t)n * k); if (L) L->cond = (double *)q;
     q = take(4 * (size_t)n * ((d + SLAB - 1) / SLAB * SLAB)); if (L) L->xs = (uint16_t *)q;
+    if (d >= HIGH_FIRST_MIN_D) {
+        q = take(2 * (size_t)n * ((d + 2 * SLAB - 1) / (2 * SLAB) * (2 * SLAB))); if (L) L->xh = (uint16_t *)q;
+        q = take(4 * qb * ((d + SLAB - 1) / SLAB * SLAB)); if (L) L->xsf = (uint16_t *)q;
+        q = take(4 * qb); if (L) L->norms_f = (float *)q;
+        q = take(4); if (L) L->fail2_count = (int *)q;
+        q = take(4 * (size_t)n); if (L) L->fail2_rows = (int *)q;
+    }
     if (L) { L->kp = kp; L->cap = cap; }
     return off;
 }
@@ -1442,8 +1492,8 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
                 hipLaunchKernelGGL(tile_count, dim3(lb), dim3(256), 0, s, L.pairptr, cellptr, nlist, c, 128, L.tcnt);
                 hipLaunchKernelGGL(excl_scan_k, dim3(1), dim3(1024), 0, s, L.tcnt, nlist, L.tptr);
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, true>), dim3(bound), dim3(256), 0, s, (const uint4 *)L.xs, dp, q0,
-                                   q0 + rows, 0, 0, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount, (const uint4 *)L.xs, L.norms, 1, L.tptr,
-                                   nlist, L.pairptr, L.pairq, cellptr, c);
+                                   q0 + rows, 0, 0, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount, (const uint4 *)L.xs, L.norms, 1,
+                                   (const int *)nullptr, L.tptr, nlist, L.pairptr, L.pairq, cellptr, c);
                 const int force = r == tau - 1 && c == nchunks - 1 ? 1 : 0;
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, L.ccount);
@@ -1456,8 +1506,8 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
                     hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, L.ccount);
             }
         }
-        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, lorder, X, n, lorder, lorder, q0, rows, k,
-                           kp, 0x7FFFFFFF, L.norms, norm_max, L.tau, L.cnt, L.cand, cap, knn_idx, knn_d2, L.fail_count,
+        hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, lorder, X, n, lorder, lorder, (const int *)nullptr, q0,
+                           rows, k, kp, 0x7FFFFFFF, tile_error_coeff(d, d > KFLUSH), L.norms, norm_max, L.tau, L.cnt, L.cand, cap, knn_idx, knn_d2, L.fail_count,
                            L.fail_rows);
         HIPCHK(hipGetLastError());
     }
@@ -1583,13 +1633,13 @@ int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int
             if (d > KFLUSH)
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                    (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap, L.ccount,
-                                   (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 0, (const int *)nullptr,
-                                   (const int *)nullptr, (const int *)nullptr, 0);
+                                   (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, (const int *)nullptr, 0,
+                                   (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
             else
                 hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
                                    0, s, (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap,
-                                   L.ccount, (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 0, (const int *)nullptr,
-                                   (const int *)nullptr, (const int *)nullptr, 0);
+                                   L.ccount, (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, (const int *)nullptr, 0,
+                                   (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
             hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                L.clist, L.ccount);
             const unsigned cg = (unsigned)(rows < 4096 ? rows : 4096);
@@ -1597,7 +1647,8 @@ int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int
                                L.ccount);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, rowmap, C, nlist, (const int *)nullptr,
-                           (const int *)nullptr, q0, rows, tau, kp, nlist, L.norms_q, norm_max, L.tau, L.cnt, L.cand, cap, probe,
+                           (const int *)nullptr, (const int *)nullptr, q0, rows, tau, kp, nlist, tile_error_coeff(d, d > KFLUSH),
+                           L.norms_q, norm_max, L.tau, L.cnt, L.cand, cap, probe,
                            (double *)nullptr, L.fail_count, L.fail_rows);
         HIPCHK(hipGetLastError());
     }
@@ -1698,6 +1749,23 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&knn_tile_resident<2>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)resident_lds_bytes(2)));
     const size_t rerank_smem = up((size_t)d * 4) + 8 * (size_t)MAX_KP;
+    const unsigned cgmax = 4096;
+    auto compact = [&](int rows, const int *cc) {
+        const unsigned cg = (unsigned)rows < cgmax ? (unsigned)rows : cgmax;
+        if (kp <= 320)
+            hipLaunchKernelGGL((knn_compact<512, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
+        else if (kp <= 832)
+            hipLaunchKernelGGL((knn_compact<1024, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
+        else
+            hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
+    };
+    // Long rows: a first sweep with the high parts alone (a third of the matrix work, half the bytes, a coarser
+    // bound: 2^-8 of the norms instead of 2^-16); its certificate still holds wherever the k-th and the k'-th
+    // neighbour are farther apart than that, and only the rows it fails go through the three-product tiles.
+    const bool high_first = d >= HIGH_FIRST_MIN_D;
+    const int dph = (d + 2 * SLAB - 1) / (2 * SLAB) * (2 * SLAB);
+    if (high_first)
+        hipLaunchKernelGGL(split_high, wide_grid((size_t)n * dph), dim3(256), 0, s, d_X, L.mu, n, d, dph, L.xh);
     for (int q0 = 0; q0 < n; q0 += QB) {
         const int qend = q0 + QB < n ? q0 + QB : n, rows = qend - q0;
         hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows, L.ccount);
@@ -1723,45 +1791,79 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                                        (const uint4 *)L.xs, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, kp, force,
                                        L.clist, cc, cc_next);
             } else {
-                if (d > KFLUSH)
+                if (high_first)
+                    hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false, true>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy),
+                                       dim3(256), 0, s, (const uint4 *)L.xh, dph, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand,
+                                       cap, cc, (const uint4 *)L.xh, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
+                                       (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
+                else if (d > KFLUSH)
                     hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                        (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 0, (const int *)nullptr,
-                                       (const int *)nullptr, (const int *)nullptr, 0);
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
+                                       (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
                 else
                     hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
                                        0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 0, (const int *)nullptr,
-                                       (const int *)nullptr, (const int *)nullptr, 0);
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
+                                       (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, cc);
             }
-            const unsigned cg = (unsigned)(rows < 4096 ? rows : 4096);
             // (every second slab after the resident kernel, where accepted pairs are cheap; the rows stay listed)
             if (resident && !force && step >= DBC && launch % COMPACT_EVERY != COMPACT_EVERY - 1) continue;
-            if (kp <= 320)
-                hipLaunchKernelGGL((knn_compact<512, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
-            else if (kp <= 832)
-                hipLaunchKernelGGL((knn_compact<1024, 128>), dim3(cg), dim3(128), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
-            else
-                hipLaunchKernelGGL((knn_compact<4096, 256>), dim3(cg), dim3(256), 0, s, L.tau, L.cnt, L.cand, cap, kp, rows, L.clist, cc);
+            compact(rows, cc);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, (const int *)nullptr, d_X, n,
-                           (const int *)nullptr, (const int *)nullptr, q0, rows, k, kp, n - 1, L.norms,
-                           norm_max, L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
+                           (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, q0, rows, k, kp, n - 1,
+                           high_first ? tile_error_coeff(d, false, true) : tile_error_coeff(d, d > KFLUSH), L.norms, norm_max,
+                           L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
         HIPCHK(hipGetLastError());
     }
     int nfail = 0;
     HIPCHK(hipMemcpyAsync(&nfail, L.fail_count, 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
+    const int *exact_rows = L.fail_rows;
+    if (high_first && nfail > 0) {
+        // second sweep: the rows the first one could not certify, QB at a time, as queries of their own (a split
+        // copy of just these rows) against all rows
+        HIPCHK(hipMemsetAsync(L.fail2_count, 0, 4, s));
+        for (int f0 = 0; f0 < nfail; f0 += QB) {
+            const int rows = nfail - f0 < QB ? nfail - f0 : QB;
+            const int *fr = L.fail_rows + f0;
+            hipLaunchKernelGGL(row_norms, wide_grid((size_t)rows * WAVE), dim3(256), 0, s, d_X, L.mu, rows, d, fr, n, L.norms_f);
+            hipLaunchKernelGGL(split_bf16, wide_grid((size_t)rows * dp), dim3(256), 0, s, d_X, L.mu, rows, d, dp, fr, n, L.xsf);
+            hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows, L.ccount);
+            int step = kp + 64 <= 256 ? 256 : DBC;
+            for (int j0 = 0, jend; j0 < n; j0 = jend) {
+                jend = j0 + step < n ? j0 + step : n;
+                if (jend > step && step < DBC) step *= 2;
+                const unsigned gy = (unsigned)((jend - j0 + TN - 1) / TN);
+                const int force = jend >= n ? 1 : 0;
+                hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
+                                   (const uint4 *)L.xsf, dp, 0, rows, j0, jend, L.norms_f, L.tau, L.cnt, L.cand, cap, L.ccount,
+                                   (const uint4 *)L.xs, L.norms, 1, fr, (const int *)nullptr, 0, (const int *)nullptr,
+                                   (const int *)nullptr, (const int *)nullptr, 0);
+                hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
+                                   L.clist, L.ccount);
+                compact(rows, L.ccount);
+            }
+            hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, fr, d_X, n, (const int *)nullptr, fr, fr,
+                               0, rows, k, kp, n - 1, tile_error_coeff(d, true), L.norms_f, norm_max, L.tau, L.cnt, L.cand, cap,
+                               L.knn_idx, L.knn_d2, L.fail2_count, L.fail2_rows);
+            HIPCHK(hipGetLastError());
+        }
+        HIPCHK(hipMemcpyAsync(&nfail, L.fail2_count, 4, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
+        exact_rows = L.fail2_rows;
+    }
     // Rows without a certificate (ties at the k-th distance, duplicates): exact distances to every row, 2k failed
     // rows a launch (their n keys each fit the space the symmetrisation sorts in later, 2 n k words).
     for (int f0 = 0; f0 < nfail; f0 += 2 * k) {
         const int nb = nfail - f0 < 2 * k ? nfail - f0 : 2 * k;
         hipLaunchKernelGGL(knn_exact_dists, wide_grid((size_t)n * WAVE), dim3(256), 0, s, d_X, n, (const int *)nullptr, d_X, n, d,
-                           L.fail_rows + f0, nb, 1, L.sort_scratch);
+                           exact_rows + f0, nb, 1, L.sort_scratch);
         hipLaunchKernelGGL(knn_exact_select, dim3(nb), dim3(1024), 0, s, L.sort_scratch, (size_t)n, n, (const int *)nullptr,
-                           (const int *)nullptr, k, L.fail_rows + f0, (const int *)nullptr, n, L.knn_idx, L.knn_d2);
+                           (const int *)nullptr, k, exact_rows + f0, (const int *)nullptr, n, L.knn_idx, L.knn_d2);
         HIPCHK(hipGetLastError());
     }
     return finish_P(L, n, k, perplexity, d_row_ptr, d_col, d_val, cap_nnz, nnz, d_knn_idx, d_knn_d2, n_unconverged, s);

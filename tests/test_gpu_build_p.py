@@ -139,3 +139,29 @@ def test_many_long_rows_sampled(clusters, scale):
     rows = np.sort(np.random.default_rng(2).choice(n, 192, replace=False).astype(np.int32))
     rows[0], rows[-1] = 0, n - 1
     _check_against_oracle(X, 20.0, k, rows=np.unique(rows))
+
+
+@pytest.mark.parametrize("name", ["plane", "lattice", "copies", "blobs"])
+def test_rows_of_256_and_more_coordinates(name):
+    """Rows this long are swept with the high parts of the split values first and only the rows without a
+    certificate go on to the three-product tiles and, failing that, to the exact pass.
+    plane: a densely sampled plane in 300 dimensions (neighbours closer together than 2^-8 of the norms: the first
+    sweep certifies nobody, the second everybody); lattice: integer points with exact ties (nobody is certified by
+    either); copies: every row five times; blobs: clustered data that the first sweep settles."""
+    r = np.random.default_rng(21)
+    if name == "plane":
+        n, d, k = 20_000, 300, 90
+        basis, _ = np.linalg.qr(r.standard_normal((d, 2)))
+        X = (r.uniform(0.0, 100.0, (n, 2)) @ basis.T).astype(np.float32)
+    elif name == "lattice":
+        n, d, k = 3000, 256, 40
+        X = np.zeros((n, d), np.float32)
+        X[:, :3] = r.integers(0, 6, (n, 3)).astype(np.float32)
+    elif name == "copies":
+        n, d, k = 2500, 320, 23
+        X = np.repeat(r.standard_normal((500, d)).astype(np.float32), 5, axis=0)
+    else:
+        n, d, k = 70_000, 257, 60
+        X, _ = synth.gaussian_mixture(n, d, 50, 3.0, 1.0, seed=22)
+    rows = None if n <= 3000 else np.unique(np.sort(r.choice(n, 128, replace=False).astype(np.int32)))
+    _check_against_oracle(X, min(20.0, k / 3.0), k, rows=rows)
