@@ -129,6 +129,7 @@ constexpr int SLAB_ROW = 4 * SLAB;        // bytes of a row's piece of a slab
 constexpr int LDS_ROW = SLAB_ROW + 16;    // padded: 8 consecutive rows' 16-byte reads hit distinct banks
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ uint32_t bf16_rne(float x)
 {
@@ -153,15 +154,29 @@ __global__ __launch_bounds__(256) void split_bf16(const float *__restrict__ X, c
     o[SLAB] = (uint16_t)lo;
 }
 
-// The high parts alone, for the first sweep over long rows: row-major, rows padded to a multiple of 64 columns.
+// The values in half precision, for the first sweep over long rows: row-major, rows padded to a multiple of 64
+// columns, scaled by a power of two (`scale`) that brings the largest magnitude just below 2^15: nothing overflows,
+// and what is too small for a normal half is below 2^-28 of the largest magnitude.
 __global__ __launch_bounds__(256) void split_high(const float *__restrict__ X, const float *__restrict__ mu, int n, int d,
-                                                  int dph, uint16_t *__restrict__ Xh)
+                                                  int dph, float scale, uint16_t *__restrict__ Xh)
 {
     const size_t e = global_index();
     if (e >= (size_t)n * dph) return;
     const size_t row = e / dph;
     const int k = (int)(e % dph);
-    Xh[e] = (uint16_t)(k < d ? bf16_rne(X[row * d + k] - mu[k]) : 0u);
+    const _Float16 h = (_Float16)(k < d ? (X[row * d + k] - mu[k]) * scale : 0.f);     // round to nearest even
+    Xh[e] = __builtin_bit_cast(uint16_t, h);
+}
+
+// max |x - mu| over all values, as the bits of a non-negative float (they order like the values)
+__global__ __launch_bounds__(256) void max_abs_centred(const float *__restrict__ X, const float *__restrict__ mu, size_t total,
+                                                       int d, unsigned int *__restrict__ out)
+{
+    float v = 0.f;
+    for (size_t i = global_index(); i < total; i += (size_t)gridDim.x * gridDim.y * blockDim.x)
+        v = fmaxf(v, fabsf(X[i] - mu[i % d]));
+    v = wave_max(v);
+    if (lane_id() == 0) atomicMax(out, __float_as_uint(v));
 }
 
 // Bound on |computed - exact| of one tile distance, as a multiple of |q|^2 + |x|^2.
@@ -176,15 +191,16 @@ __global__ __launch_bounds__(256) void split_high(const float *__restrict__ X, c
 //   centring: q' = fl(q - mu), x' = fl(x - mu) are off by 2^-24 relative per coordinate, which moves
 //   |q' - x'|^2 by at most 2 |q - x| 2^-24 (|q'| + |x'|) <= 4 2^-24 (|q'|^2 + |x'|^2) (and a second-order term).
 // 5 % on top for the norms themselves being rounded values.  q, x here are the centred rows.
-// high_only: the tiles multiply the high parts alone (one product per coordinate): what is left out is then
-// q ex + eq x - eq ex with |eq| <= 2^-9 |q|, |ex| <= 2^-9 |x|, at most (2^-8 + 2^-18) |q_t x_t|.
+// high_only: the tiles multiply the values rounded to half precision (one product per coordinate): what is left
+// out is then q ex + eq x - eq ex with |eq| <= 2^-11 |q|, |ex| <= 2^-11 |x|, at most (2^-10 + 2^-22) |q_t x_t|
+// (values too small for a normal half are covered by an additive term, see high_first_extra()).
 __host__ __device__ inline double tile_error_coeff(int d, bool two_level, bool high_only = false)
 {
     const int dp = (d + SLAB - 1) / SLAB * SLAB;
     const double per = high_only ? 1.0 : 3.0;      // products per coordinate
     const double R = two_level ? per * KFLUSH + (double)((dp + KFLUSH - 1) / KFLUSH) : per * dp;
     const double u = 1.1920928955078125e-07;   // 2^-23
-    const double split = high_only ? 0.00390625 + 3.814697265625e-06
+    const double split = high_only ? 0.0009765625 + 2.384185791015625e-07
                                    : 3.0 * (1.0 + 3.814697265625e-06) * 3.814697265625e-06;
     const double accum = 1.0079 * R * u / (1.0 - R * u);
     return 1.05 * (split + accum + (16.0 + 4.2) * 5.9604644775390625e-08);
@@ -255,14 +271,15 @@ __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0
 // the current rank are pairq[pairptr[L] .. pairptr[L+1]) (row numbers, any order); a launch takes the rows
 // chunk * DBC .. of every list.  Workgroup t < tptr[nlist] belongs to the list L with tptr[L] <= t < tptr[L+1] and
 // is tile (a, b) of its ceil(queries / TQ) x ceil(rows of the chunk / TN) tiles; workgroups past the end leave.
-// ONE: the rows hold high parts only, 64 columns per 128-byte piece (split_high), one product per coordinate.
+// ONE: the rows hold the values in half precision, 64 columns per 128-byte piece (split_high), one product per
+// coordinate; dot_scale undoes the scaling of that copy (1 otherwise).
 template <int MB, bool TWO, bool GATHER, bool ONE = false>
 __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict__ Xs, int dp, int q0, int qend, int j0,
                                                         int jend, const float *__restrict__ norms,
                                                         const float *__restrict__ tau, int *__restrict__ cnt,
                                                         uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount,
                                                         const uint4 *__restrict__ Xb, const float *__restrict__ norms_b,
-                                                        int exclude_self, const int *__restrict__ selfmap,
+                                                        int exclude_self, const int *__restrict__ selfmap, float dot_scale,
                                                         const int *__restrict__ tptr, int nlist,
                                                         const int *__restrict__ pairptr, const int *__restrict__ pairq,
                                                         const int *__restrict__ cellptr, int chunk)
@@ -342,20 +359,20 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
         // hardware sums them in.
 #pragma unroll
         for (int ks = 0; ONE && ks < 4; ++ks) {
-            bf16x8 ah[MB], bh[2];
+            halfx8 ah[MB], bh[2];
             const unsigned char *pa = As + (wm * 32 * MB + r32) * LDS_ROW + ks * 32 + h * 16;
             const unsigned char *pb = Bs + (wn * 64 + r32) * LDS_ROW + ks * 32 + h * 16;
 #pragma unroll
             for (int a = 0; a < MB; ++a)
-                ah[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW));
+                ah[a] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW));
 #pragma unroll
             for (int b = 0; b < 2; ++b)
-                bh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW));
+                bh[b] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW));
 #pragma unroll
             for (int a = 0; a < MB; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
-                    part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], part[a][b], 0, 0, 0);
+                    part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], bh[b], part[a][b], 0, 0, 0);
         }
 #pragma unroll
         for (int ks = 0; !ONE && ks < 2; ++ks) {
@@ -443,7 +460,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
 #pragma unroll
                 for (int ii = 0; ii < 4; ++ii) {
                     const int i = 4 * i4 + ii;
-                    const float dot = TWO ? acc[TWO ? a : 0][TWO ? b : 0][i] : part[a][b][i];
+                    const float dot = (TWO ? acc[TWO ? a : 0][TWO ? b : 0][i] : part[a][b][i]) * (ONE ? dot_scale : 1.0f);
                     const bool near = fmaf(-2.0f, dot, nj) < dq[ii];
                     if (__ballot(near) != 0)
                         fill = __builtin_amdgcn_readfirstlane(queue_pairs(near, j, ql0 + ii, qa, q0, (const lds_f32 *)qn, nj, dot, fill, QCAP,
@@ -751,11 +768,11 @@ __global__ __launch_bounds__(THREADS) void knn_compact(float *__restrict__ tau, 
 // (row j); distances are taken from those rows, equal distances are ordered by the candidates' row numbers, which
 // are also what is written, to row omap[i] (row i) of the result.  n_all: how many candidates a query can have at
 // all (one that has them all needs no certificate).  norms_q by query number, norm_max over the database; coeff:
-// tile_error_coeff() of the tiles that found the candidates.  A query without a certificate is listed as failmap[i] (i).
+// tile_error_coeff() of the tiles that found the candidates, e_add: what else their distances may be off by.  A query without a certificate is listed as failmap[i] (i).
 __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, int nx, int d, const int *__restrict__ qmap,
                                                   const float *__restrict__ Y, int ny, const int *__restrict__ cmap,
                                                   const int *__restrict__ omap, const int *__restrict__ failmap, int q0,
-                                                  int rows, int k, int kp, int n_all, double coeff,
+                                                  int rows, int k, int kp, int n_all, double coeff, double e_add,
                                                   const float *__restrict__ norms_q, float norm_max,
                                                   const float *__restrict__ tau, const int *__restrict__ cnt,
                                                   const uint64_t *__restrict__ cand, int cap,
@@ -848,7 +865,7 @@ __global__ __launch_bounds__(256) void knn_rerank(const float *__restrict__ X, i
         bool ok = c >= k;
         if (ok && c < n_all) {
             // (the additive term covers matrix cores that flush denormal bf16 parts to zero)
-            const double E = coeff * ((double)norms_q[i] + (double)norm_max) + 1e-30 * d;
+            const double E = coeff * ((double)norms_q[i] + (double)norm_max) + 1e-30 * d + e_add;
             const double Dk = dd[order[k - 1]];
             ok = (double)tau[row] - E > Dk;
         }
@@ -1493,7 +1510,7 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
                 hipLaunchKernelGGL(excl_scan_k, dim3(1), dim3(1024), 0, s, L.tcnt, nlist, L.tptr);
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, true>), dim3(bound), dim3(256), 0, s, (const uint4 *)L.xs, dp, q0,
                                    q0 + rows, 0, 0, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount, (const uint4 *)L.xs, L.norms, 1,
-                                   (const int *)nullptr, L.tptr, nlist, L.pairptr, L.pairq, cellptr, c);
+                                   (const int *)nullptr, 1.0f, L.tptr, nlist, L.pairptr, L.pairq, cellptr, c);
                 const int force = r == tau - 1 && c == nchunks - 1 ? 1 : 0;
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, L.ccount);
@@ -1507,7 +1524,7 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
             }
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, lorder, X, n, lorder, lorder, (const int *)nullptr, q0,
-                           rows, k, kp, 0x7FFFFFFF, tile_error_coeff(d, d > KFLUSH), L.norms, norm_max, L.tau, L.cnt, L.cand, cap, knn_idx, knn_d2, L.fail_count,
+                           rows, k, kp, 0x7FFFFFFF, tile_error_coeff(d, d > KFLUSH), 0.0, L.norms, norm_max, L.tau, L.cnt, L.cand, cap, knn_idx, knn_d2, L.fail_count,
                            L.fail_rows);
         HIPCHK(hipGetLastError());
     }
@@ -1633,12 +1650,12 @@ int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int
             if (d > KFLUSH)
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                    (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap, L.ccount,
-                                   (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, (const int *)nullptr, 0,
+                                   (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
                                    (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
             else
                 hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
                                    0, s, (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap,
-                                   L.ccount, (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, (const int *)nullptr, 0,
+                                   L.ccount, (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
                                    (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
             hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                L.clist, L.ccount);
@@ -1647,7 +1664,7 @@ int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int
                                L.ccount);
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, rowmap, C, nlist, (const int *)nullptr,
-                           (const int *)nullptr, (const int *)nullptr, q0, rows, tau, kp, nlist, tile_error_coeff(d, d > KFLUSH),
+                           (const int *)nullptr, (const int *)nullptr, q0, rows, tau, kp, nlist, tile_error_coeff(d, d > KFLUSH), 0.0,
                            L.norms_q, norm_max, L.tau, L.cnt, L.cand, cap, probe,
                            (double *)nullptr, L.fail_count, L.fail_rows);
         HIPCHK(hipGetLastError());
@@ -1762,10 +1779,32 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
     // Long rows: a first sweep with the high parts alone (a third of the matrix work, half the bytes, a coarser
     // bound: 2^-8 of the norms instead of 2^-16); its certificate still holds wherever the k-th and the k'-th
     // neighbour are farther apart than that, and only the rows it fails go through the three-product tiles.
-    const bool high_first = d >= HIGH_FIRST_MIN_D;
+    bool high_first = d >= HIGH_FIRST_MIN_D;
     const int dph = (d + 2 * SLAB - 1) / (2 * SLAB) * (2 * SLAB);
-    if (high_first)
-        hipLaunchKernelGGL(split_high, wide_grid((size_t)n * dph), dim3(256), 0, s, d_X, L.mu, n, d, dph, L.xh);
+    float dot_scale = 1.0f;
+    double e_add = 0.0;
+    if (high_first) {
+        HIPCHK(hipMemsetAsync(L.fail2_count, 0, 4, s));            // (borrowed for the largest magnitude)
+        hipLaunchKernelGGL(max_abs_centred, dim3(2048), dim3(256), 0, s, d_X, L.mu, (size_t)n * d, d,
+                           reinterpret_cast<unsigned int *>(L.fail2_count));
+        float xmax = 0.f;
+        HIPCHK(hipMemcpyAsync(&xmax, L.fail2_count, 4, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
+        if (!(xmax > 0.f) || !(xmax < 1e15f)) {
+            high_first = false;                                     // all rows equal, or values half precision cannot scale
+        } else {
+            int e = 0;
+            (void)frexpf(xmax, &e);                                 // xmax < 2^e
+            const float scale = ldexpf(1.0f, 15 - e);               // |x| scale < 2^15
+            dot_scale = ldexpf(1.0f, 2 * (e - 15));
+            // a scaled value below 2^-14 may be rounded to a subnormal half or flushed to zero: off by at most
+            // delta = 2^-14 / scale per value, the dot product by delta (sum |q_t| + sum |x_t|) + D delta^2, the
+            // distance by twice that; sum |x_t| <= sqrt(D) |x|
+            const double delta = ldexp(1.0, -14) / (double)scale;
+            e_add = 2.0 * (delta * 2.0 * sqrt((double)d) * sqrt((double)norm_max) + (double)d * delta * delta);
+            hipLaunchKernelGGL(split_high, wide_grid((size_t)n * dph), dim3(256), 0, s, d_X, L.mu, n, d, dph, scale, L.xh);
+        }
+    }
     for (int q0 = 0; q0 < n; q0 += QB) {
         const int qend = q0 + QB < n ? q0 + QB : n, rows = qend - q0;
         hipLaunchKernelGGL(knn_reset, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, rows, L.ccount);
@@ -1794,17 +1833,17 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                 if (high_first)
                     hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false, true>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy),
                                        dim3(256), 0, s, (const uint4 *)L.xh, dph, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand,
-                                       cap, cc, (const uint4 *)L.xh, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
+                                       cap, cc, (const uint4 *)L.xh, L.norms, 1, (const int *)nullptr, dot_scale, (const int *)nullptr, 0,
                                        (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
                 else if (d > KFLUSH)
                     hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                        (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
                                        (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
                 else
                     hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
                                        0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
                                        (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, cc);
@@ -1815,7 +1854,7 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, (const int *)nullptr, d_X, n,
                            (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, q0, rows, k, kp, n - 1,
-                           high_first ? tile_error_coeff(d, false, true) : tile_error_coeff(d, d > KFLUSH), L.norms, norm_max,
+                           high_first ? tile_error_coeff(d, false, true) : tile_error_coeff(d, d > KFLUSH), e_add, L.norms, norm_max,
                            L.tau, L.cnt, L.cand, cap, L.knn_idx, L.knn_d2, L.fail_count, L.fail_rows);
         HIPCHK(hipGetLastError());
     }
@@ -1841,14 +1880,14 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                 const int force = jend >= n ? 1 : 0;
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                    (const uint4 *)L.xsf, dp, 0, rows, j0, jend, L.norms_f, L.tau, L.cnt, L.cand, cap, L.ccount,
-                                   (const uint4 *)L.xs, L.norms, 1, fr, (const int *)nullptr, 0, (const int *)nullptr,
+                                   (const uint4 *)L.xs, L.norms, 1, fr, 1.0f, (const int *)nullptr, 0, (const int *)nullptr,
                                    (const int *)nullptr, (const int *)nullptr, 0);
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, L.ccount);
                 compact(rows, L.ccount);
             }
             hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, d_X, n, d, fr, d_X, n, (const int *)nullptr, fr, fr,
-                               0, rows, k, kp, n - 1, tile_error_coeff(d, true), L.norms_f, norm_max, L.tau, L.cnt, L.cand, cap,
+                               0, rows, k, kp, n - 1, tile_error_coeff(d, true), 0.0, L.norms_f, norm_max, L.tau, L.cnt, L.cand, cap,
                                L.knn_idx, L.knn_d2, L.fail2_count, L.fail2_rows);
             HIPCHK(hipGetLastError());
         }
