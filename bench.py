@@ -175,6 +175,9 @@ def main():
     ap.add_argument("--no-standalone", action="store_true",
                     help="skip the serial re-timing of the kernels on their own (profiling: every launch a profiler "
                          "then sees belongs to warm-up or timed steps)")
+    ap.add_argument("--knn-rows", type=int, default=0,
+                    help="profiling aid: build P from the first R rows of the workload's X and exit (counter runs of the "
+                         "neighbour-search kernels on a subset; prints seconds and nnz)")
     ap.add_argument("--P-cache", default="",
                     help="profiling aid: a path prefix; if <prefix>.npz exists P is loaded from it (X is neither drawn "
                          "nor searched, build_P_s is reported as null), otherwise P is built as usual and saved there")
@@ -220,6 +223,16 @@ def main():
     else:
         X, cfg = workload_inputs(args.workload)
         n, k, perp = cfg["n"], cfg["k"], cfg["perplexity"]
+        if args.knn_rows > 0:
+            Xs = torch.from_numpy(X[:args.knn_rows]).to(dev)
+            for rep in range(2):
+                torch.cuda.synchronize()
+                t0 = time.time()
+                Ps = build_P(Xs, perp, k)
+                torch.cuda.synchronize()
+                print(json.dumps({"knn_rows": int(Xs.shape[0]), "d": int(Xs.shape[1]), "build_P_s": time.time() - t0,
+                                  "nnz": Ps["nnz"]}))
+            return
         Xd = torch.from_numpy(X).to(dev)
         torch.cuda.synchronize()
         t0 = time.time()

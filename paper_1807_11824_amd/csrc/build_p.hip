@@ -271,15 +271,13 @@ __device__ __noinline__ int queue_pairs(bool near, int j, int ql, int qa, int q0
 // the current rank are pairq[pairptr[L] .. pairptr[L+1]) (row numbers, any order); a launch takes the rows
 // chunk * DBC .. of every list.  Workgroup t < tptr[nlist] belongs to the list L with tptr[L] <= t < tptr[L+1] and
 // is tile (a, b) of its ceil(queries / TQ) x ceil(rows of the chunk / TN) tiles; workgroups past the end leave.
-// ONE: the rows hold the values in half precision, 64 columns per 128-byte piece (split_high), one product per
-// coordinate; dot_scale undoes the scaling of that copy (1 otherwise).
-template <int MB, bool TWO, bool GATHER, bool ONE = false>
+template <int MB, bool TWO, bool GATHER>
 __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict__ Xs, int dp, int q0, int qend, int j0,
                                                         int jend, const float *__restrict__ norms,
                                                         const float *__restrict__ tau, int *__restrict__ cnt,
                                                         uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount,
                                                         const uint4 *__restrict__ Xb, const float *__restrict__ norms_b,
-                                                        int exclude_self, const int *__restrict__ selfmap, float dot_scale,
+                                                        int exclude_self, const int *__restrict__ selfmap,
                                                         const int *__restrict__ tptr, int nlist,
                                                         const int *__restrict__ pairptr, const int *__restrict__ pairq,
                                                         const int *__restrict__ cellptr, int chunk)
@@ -311,7 +309,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
         jend = min(re, ja + TN);
         qa = 0;
     }
-    const int row16 = ONE ? dp / 8 : dp / 4;   // 16-byte pieces per row of Xs
+    const int row16 = dp / 4;              // 16-byte pieces per row of Xs
     const int piece = tid & 7, lrow = tid >> 3;
     floatx16 acc[TWO ? MB : 1][TWO ? 2 : 1], part[MB][2];
 #pragma unroll
@@ -343,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
     };
     load(0);
     const int r32 = lane & 31, h = lane >> 5;
-    const int nslab = ONE ? dp / (2 * SLAB) : dp / SLAB;
+    const int nslab = dp / SLAB;
     for (int slab = 0; slab < nslab; ++slab) {
         __syncthreads();
 #pragma unroll
@@ -358,24 +356,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
         // Both operands use the same assignment, so the products pair up whatever order the
         // hardware sums them in.
 #pragma unroll
-        for (int ks = 0; ONE && ks < 4; ++ks) {
-            halfx8 ah[MB], bh[2];
-            const unsigned char *pa = As + (wm * 32 * MB + r32) * LDS_ROW + ks * 32 + h * 16;
-            const unsigned char *pb = Bs + (wn * 64 + r32) * LDS_ROW + ks * 32 + h * 16;
-#pragma unroll
-            for (int a = 0; a < MB; ++a)
-                ah[a] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW));
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-                bh[b] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW));
-#pragma unroll
-            for (int a = 0; a < MB; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], bh[b], part[a][b], 0, 0, 0);
-        }
-#pragma unroll
-        for (int ks = 0; !ONE && ks < 2; ++ks) {
+        for (int ks = 0; ks < 2; ++ks) {
             // low.high, high.high, high.low, in that order so that at most three fragment sets are live
             bf16x8 ah[MB], al[MB], bh[2], bl[2];
             const unsigned char *pa = As + (wm * 32 * MB + r32) * LDS_ROW + ks * 32 + h * 16;
@@ -408,8 +389,7 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
                 for (int b = 0; b < 2; ++b)
                     part[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], part[a][b], 0, 0, 0);
         }
-        constexpr int FLUSH_SLABS = ONE ? 1 : KFLUSH / SLAB;
-        if (TWO && ((slab % FLUSH_SLABS) == FLUSH_SLABS - 1 || slab + 1 == nslab)) {
+        if (TWO && ((slab % (KFLUSH / SLAB)) == (KFLUSH / SLAB) - 1 || slab + 1 == nslab)) {
 #pragma unroll
             for (int a = 0; a < MB; ++a)
 #pragma unroll
@@ -460,13 +440,160 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
 #pragma unroll
                 for (int ii = 0; ii < 4; ++ii) {
                     const int i = 4 * i4 + ii;
-                    const float dot = (TWO ? acc[TWO ? a : 0][TWO ? b : 0][i] : part[a][b][i]) * (ONE ? dot_scale : 1.0f);
+                    const float dot = TWO ? acc[TWO ? a : 0][TWO ? b : 0][i] : part[a][b][i];
                     const bool near = fmaf(-2.0f, dot, nj) < dq[ii];
                     if (__ballot(near) != 0)
                         fill = __builtin_amdgcn_readfirstlane(queue_pairs(near, j, ql0 + ii, qa, q0, (const lds_f32 *)qn, nj, dot, fill, QCAP,
                                                                           qkey, qrow, cnt, cand, cap,
                                                                           GATHER ? (const lds_u32 *)qid : (const lds_u32 *)nullptr,
                                                                           exclude_self, selfmap));
+                }
+            }
+        }
+    }
+    append_queue(qrow, qkey, fill, cnt, cand, cap);
+}
+
+// ---- the first sweep over long rows: half precision, 256 x 256 tiles
+// One product per coordinate makes the operands, not the matrix work, the cost: with 256 x 128 tiles two workgroups
+// per compute unit pull 10 TB/s out of the second-level cache.  A 256 x 256 tile needs a third less per product.  One
+// workgroup of eight waves per compute unit (a wave owns 128 x 64 outputs, eight 32 x 32 blocks), and the overlap that
+// several workgroups would give comes from the kernel itself: the slabs alternate between two LDS buffers, the slab
+// after the next is in flight to registers while the next one is being stored and the current one multiplied, and
+// there is a single barrier per slab.  Rows as split_high leaves them (128 bytes per 64 columns); dot_scale undoes
+// their scaling.
+constexpr int HT = 256;                                 // tile: query rows = database rows
+constexpr int HALF_THREADS = 512;
+constexpr size_t HALF_TILE_LDS = 2 * (size_t)(2 * HT) * LDS_ROW;
+
+__global__ __launch_bounds__(HALF_THREADS, 1) void knn_tile_half(const uint4 *__restrict__ Xh, int dph, int q0, int qend, int j0,
+                                                                 int jend, const float *__restrict__ norms,
+                                                                 const float *__restrict__ tau, int *__restrict__ cnt,
+                                                                 uint64_t *__restrict__ cand, int cap, int *__restrict__ ccount,
+                                                                 float dot_scale)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *ccount = 0;   // for the compaction pass that follows
+    extern __shared__ __align__(16) unsigned char hsm[];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wm = w >> 2, wn = w & 3;
+    // Workgroups go to the eight XCDs in turn, and each XCD has a second-level cache of its own.  Workgroup number
+    // 8 l + x is XCD x's l-th: XCD x takes a strip of the query tiles and walks it query tile by query tile, all
+    // database tiles of one query tile next to each other, so that the 32 workgroups an XCD runs at a time are a few
+    // query tiles against all database tiles of the launch and find each other's rows in that cache (taken in plain
+    // row-major order, every tile's rows came from memory: 3-4 TB/s of re-reads, which is what bounded the kernel).
+    const int nqt = (qend - q0 + HT - 1) / HT, njt = (jend - j0 + HT - 1) / HT, per = (nqt + 7) / 8;
+    const int xcd = (int)(blockIdx.x & 7u), local = (int)(blockIdx.x >> 3);
+    const int qt = xcd * per + local / njt, jt = local % njt;
+    if (qt >= nqt || local / njt >= per) return;       // (the grid is 8 per njt workgroups; the same for all lanes)
+    const int qa = q0 + qt * HT, ja = j0 + jt * HT;
+    const int row16 = dph / 8;              // 16-byte pieces per row
+    const int piece = tid & 7, lrow = tid >> 3;        // 64 rows a trip
+    const int r32 = lane & 31, h = lane >> 5;
+    const int nslab = dph / (2 * SLAB);
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    // rows this thread moves (past the end: zeros)
+    const uint4 *pa_g[4], *pb_g[4];
+    bool aok[4], bok[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int ra_ = qa + lrow + 64 * it, rb_ = ja + lrow + 64 * it;
+        aok[it] = ra_ < qend;
+        bok[it] = rb_ < jend;
+        pa_g[it] = Xh + (size_t)(aok[it] ? ra_ : 0) * row16 + piece;
+        pb_g[it] = Xh + (size_t)(bok[it] ? rb_ : 0) * row16 + piece;
+    }
+    uint4 ra[4], rb[4];
+    auto load = [&](int slab) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            ra[it] = aok[it] ? pa_g[it][(size_t)slab * 8] : make_uint4(0u, 0u, 0u, 0u);
+            rb[it] = bok[it] ? pb_g[it][(size_t)slab * 8] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto store = [&](int buf) {
+        unsigned char *As = hsm + (size_t)buf * (2 * HT) * LDS_ROW, *Bs = As + (size_t)HT * LDS_ROW;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            *reinterpret_cast<uint4 *>(As + (lrow + 64 * it) * LDS_ROW + piece * 16) = ra[it];
+            *reinterpret_cast<uint4 *>(Bs + (lrow + 64 * it) * LDS_ROW + piece * 16) = rb[it];
+        }
+    };
+    load(0);
+    store(0);
+    __syncthreads();
+    if (nslab > 1) load(1);
+    for (int slab = 0; slab < nslab; ++slab) {
+        const unsigned char *As = hsm + (size_t)(slab & 1) * (2 * HT) * LDS_ROW, *Bs = As + (size_t)HT * LDS_ROW;
+        const unsigned char *pa = As + (wm * 128 + r32) * LDS_ROW + h * 16;
+        const unsigned char *pb = Bs + (wn * 64 + r32) * LDS_ROW + h * 16;
+        // the fragments of step ks + 1 are requested before the products of step ks are issued
+        halfx8 fa[2][4], fb[2][2];
+        auto frags = [&](int ks, int set) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                fa[set][a] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW + ks * 32));
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                fb[set][b] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW + ks * 32));
+        };
+        frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) frags(ks + 1, (ks + 1) & 1);
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][a], fb[ks & 1][b], acc[a][b], 0, 0, 0);
+            // half-way through: the next slab (requested a whole slab ago) goes to the other buffer, and the one
+            // after it is requested
+            if (ks == 1) {
+                if (slab + 1 < nslab) store((slab + 1) & 1);
+                if (slab + 2 < nslab) load(slab + 2);
+            }
+        }
+        __syncthreads();        // the other buffer is complete; everybody is done reading this one
+    }
+    // epilogue, as in knn_tile_mfma: lane holds column (lane % 32) and rows 8 (i / 4) + 4 (lane / 32) + i % 4 of each
+    // block; norms and cut-offs of the tile's queries staged in LDS, accepted pairs queued per wave
+    float *qn = reinterpret_cast<float *>(hsm), *qd = qn + HT;
+    for (int t = tid; t < HT; t += HALF_THREADS) {
+        const int q = qa + t < qend ? qa + t : -1;
+        const float nrm = q >= 0 ? norms[q] : 0.f;
+        qn[t] = nrm;
+        qd[t] = q >= 0 ? tau[q - q0] - nrm : -INFINITY;     // rows past the end accept nothing
+    }
+    __syncthreads();
+    constexpr int QCAP = 320;
+    unsigned char *qbase = hsm + 4096;
+    lds_u64 *qkey = (lds_u64 *)(qbase) + w * QCAP;
+    lds_u32 *qrow = (lds_u32 *)(qbase + 8 * QCAP * 8) + w * QCAP;
+    int fill = 0;       // wave-uniform
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int j = ja + wn * 64 + b * 32 + r32;
+        const float nj = j < jend ? norms[j] : INFINITY;    // rows past the end are never closer than any cut-off
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int ql0 = wm * 128 + a * 32 + 8 * i4 + 4 * h;
+                const float4 d4 = *reinterpret_cast<const float4 *>(qd + ql0);
+                const float dq[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii) {
+                    const float dot = acc[a][b][4 * i4 + ii] * dot_scale;
+                    const bool near = fmaf(-2.0f, dot, nj) < dq[ii];
+                    if (__ballot(near) != 0)
+                        fill = __builtin_amdgcn_readfirstlane(queue_pairs(near, j, ql0 + ii, qa, q0, (const lds_f32 *)qn, nj, dot, fill, QCAP,
+                                                                          qkey, qrow, cnt, cand, cap, (const lds_u32 *)nullptr, 1,
+                                                                          (const int *)nullptr));
                 }
             }
         }
@@ -1510,7 +1637,7 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
                 hipLaunchKernelGGL(excl_scan_k, dim3(1), dim3(1024), 0, s, L.tcnt, nlist, L.tptr);
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, true>), dim3(bound), dim3(256), 0, s, (const uint4 *)L.xs, dp, q0,
                                    q0 + rows, 0, 0, L.norms, L.tau, L.cnt, L.cand, cap, L.ccount, (const uint4 *)L.xs, L.norms, 1,
-                                   (const int *)nullptr, 1.0f, L.tptr, nlist, L.pairptr, L.pairq, cellptr, c);
+                                   (const int *)nullptr, L.tptr, nlist, L.pairptr, L.pairq, cellptr, c);
                 const int force = r == tau - 1 && c == nchunks - 1 ? 1 : 0;
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, L.ccount);
@@ -1650,12 +1777,12 @@ int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int
             if (d > KFLUSH)
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                    (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap, L.ccount,
-                                   (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
+                                   (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, (const int *)nullptr, 0,
                                    (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
             else
                 hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
                                    0, s, (const uint4 *)L.xs, dp, q0, q0 + rows, j0, jend, L.norms_q, L.tau, L.cnt, L.cand, cap,
-                                   L.ccount, (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
+                                   L.ccount, (const uint4 *)L.cs, L.norms_c, 0, (const int *)nullptr, (const int *)nullptr, 0,
                                    (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
             hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                L.clist, L.ccount);
@@ -1765,6 +1892,8 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)resident_lds_bytes(1)));
     HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&knn_tile_resident<2>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)resident_lds_bytes(2)));
+    HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&knn_tile_half), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)HALF_TILE_LDS));
     const size_t rerank_smem = up((size_t)d * 4) + 8 * (size_t)MAX_KP;
     const unsigned cgmax = 4096;
     auto compact = [&](int rows, const int *cc) {
@@ -1831,19 +1960,18 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                                        L.clist, cc, cc_next);
             } else {
                 if (high_first)
-                    hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false, true>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy),
-                                       dim3(256), 0, s, (const uint4 *)L.xh, dph, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand,
-                                       cap, cc, (const uint4 *)L.xh, L.norms, 1, (const int *)nullptr, dot_scale, (const int *)nullptr, 0,
-                                       (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
+                    hipLaunchKernelGGL(knn_tile_half, dim3((unsigned)(8 * (((rows + HT - 1) / HT + 7) / 8) * ((jend - j0 + HT - 1) / HT))), dim3(HALF_THREADS),
+                                       HALF_TILE_LDS, s, (const uint4 *)L.xh, dph, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand,
+                                       cap, cc, dot_scale);
                 else if (d > KFLUSH)
                     hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                        (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
                                        (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
                 else
                     hipLaunchKernelGGL((knn_tile_mfma<KNN_MB, false, false>), dim3((rows + 64 * KNN_MB - 1) / (64 * KNN_MB), gy), dim3(256),
                                        0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
-                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, 1.0f, (const int *)nullptr, 0,
+                                       (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
                                        (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, cc);
@@ -1880,7 +2008,7 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                 const int force = jend >= n ? 1 : 0;
                 hipLaunchKernelGGL((knn_tile_mfma<2, true, false>), dim3((rows + 127) / 128, gy), dim3(256), 0, s,
                                    (const uint4 *)L.xsf, dp, 0, rows, j0, jend, L.norms_f, L.tau, L.cnt, L.cand, cap, L.ccount,
-                                   (const uint4 *)L.xs, L.norms, 1, fr, 1.0f, (const int *)nullptr, 0, (const int *)nullptr,
+                                   (const uint4 *)L.xs, L.norms, 1, fr, (const int *)nullptr, 0, (const int *)nullptr,
                                    (const int *)nullptr, (const int *)nullptr, 0);
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, L.ccount);
