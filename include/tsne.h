@@ -168,7 +168,9 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
  * Workspace (tsne_ivf_workspace_bytes; use the figure for the largest tau to be passed): 8 n d bytes for
  *   the copy of X grouped by list, 4 n tau, and a scratch of min(8 GiB, 4 n min(n, 4096)) bytes for one
  *   float per (query, candidate); more workspace than asked for is used (up to 8 GiB of scratch) to take
- *   more queries per pass.
+ *   more queries per pass.  Rows of more than 64 coordinates are searched on the matrix cores (candidates from
+ *   tiles of split values, exact re-rank, an exact pass where the re-rank cannot vouch for the result): the
+ *   figure then also holds a split copy of X (4 n d bytes) and 8 (k + 4176) bytes per query of a pass of 131,072.
  * Limits: nlist <= min(n, 65536), tau <= min(nlist, 32), k <= 1920, d <= 4096, n tau < 2^31.
  * Both calls synchronise the stream before returning.
  */
