@@ -1735,8 +1735,10 @@ size_t ivf_tiles_workspace(int n, int d, int k, int nlist, int tau)
     return a > b ? a : b;
 }
 
+// reuse_queries: the workspace still holds the query side (column means, sample rows, norms and split copy) of the
+// previous call, which had the same X, n, d and m (the rounds of k-means: only the centroids change).
 int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int tau, int m, int32_t *probe, void *ws,
-                    size_t ws_bytes, hipStream_t s)
+                    size_t ws_bytes, hipStream_t s, int reuse_queries)
 {
     if (n < 2 || d < 1 || d > 4096 || nlist < 1 || tau < 1 || tau > nlist || m < 1 || m > n) return TSNE_EINVAL;
     if (ws_bytes < tp_carve(nullptr, n, d, nlist, tau, nullptr)) return TSNE_ENOSPC;
@@ -1745,15 +1747,14 @@ int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int
     const int kp = probe_kp(nlist, tau), cap = kp + COMPACT_SLACK + COMPACT_EVERY * DBC;
     const int dp = (d + SLAB - 1) / SLAB * SLAB;
     const int rows_per_chunk = (n + MEAN_CHUNKS - 1) / MEAN_CHUNKS, nchunks_mu = (n + rows_per_chunk - 1) / rows_per_chunk;
-    hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks_mu), dim3(256), 0, s, X, n, d, rows_per_chunk, L.mu_part);
-    hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks_mu, n, d, dp, L.mu);
-    const int *rowmap = nullptr;
-    if (m < n) {
-        hipLaunchKernelGGL(sample_rows_k, dim3((m + 255) / 256), dim3(256), 0, s, L.qrows, n, m);
-        rowmap = L.qrows;
+    const int *rowmap = m < n ? L.qrows : nullptr;
+    if (!reuse_queries) {
+        hipLaunchKernelGGL(col_mean_part, dim3((d + 63) / 64, nchunks_mu), dim3(256), 0, s, X, n, d, rows_per_chunk, L.mu_part);
+        hipLaunchKernelGGL(col_mean_final, dim3((dp + 255) / 256), dim3(256), 0, s, L.mu_part, nchunks_mu, n, d, dp, L.mu);
+        if (m < n) hipLaunchKernelGGL(sample_rows_k, dim3((m + 255) / 256), dim3(256), 0, s, L.qrows, n, m);
+        hipLaunchKernelGGL(row_norms, wide_grid((size_t)m * WAVE), dim3(256), 0, s, X, L.mu, m, d, rowmap, n, L.norms_q);
+        hipLaunchKernelGGL(split_bf16, wide_grid((size_t)m * dp), dim3(256), 0, s, X, L.mu, m, d, dp, rowmap, n, L.xs);
     }
-    hipLaunchKernelGGL(row_norms, wide_grid((size_t)m * WAVE), dim3(256), 0, s, X, L.mu, m, d, rowmap, n, L.norms_q);
-    hipLaunchKernelGGL(split_bf16, wide_grid((size_t)m * dp), dim3(256), 0, s, X, L.mu, m, d, dp, rowmap, n, L.xs);
     hipLaunchKernelGGL(row_norms, wide_grid((size_t)nlist * WAVE), dim3(256), 0, s, C, L.mu, nlist, d, (const int *)nullptr, nlist,
                        L.norms_c);
     hipLaunchKernelGGL(split_bf16, wide_grid((size_t)nlist * dp), dim3(256), 0, s, C, L.mu, nlist, d, dp, (const int *)nullptr,

@@ -803,9 +803,11 @@ size_t chunk_lds(int d, int waves) { return d > IVF_DC ? 4 * (size_t)IVF_DC * WA
 // Eq. (10) for the rows floor(i n / m), i < m, of X.  Long rows go through the matrix-core tiles when the caller has
 // their workspace (C: the centroids as floats); Cd: the centroids as doubles, rows padded to dp.
 int launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nlist, int tau, int32_t *probe, int m,
-                 hipStream_t s, const float *C = nullptr, void *tiles_ws = nullptr, size_t tiles_bytes = 0)
+                 hipStream_t s, const float *C = nullptr, void *tiles_ws = nullptr, size_t tiles_bytes = 0,
+                 int reuse_queries = 0)
 {
-    if (d > IVF_DC && C && tiles_bytes > 0) return ivf_probe_tiles(X, n, d, C, nlist, tau, m, probe, tiles_ws, tiles_bytes, s);
+    if (d > IVF_DC && C && tiles_bytes > 0)
+        return ivf_probe_tiles(X, n, d, C, nlist, tau, m, probe, tiles_ws, tiles_bytes, s, reuse_queries);
     const size_t lists = 12 * (size_t)WAVE * tau;
     if (d > IVF_DC)
         hipLaunchKernelGGL(ivf_probe<true>, dim3((m + WAVE - 1) / WAVE), dim3(WAVE), lists + chunk_lds(d, 1), s, X, n, d, dp, Cd,
@@ -948,7 +950,7 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
     for (int it = 0; it < iters; ++it) {
         hipLaunchKernelGGL(to_double_k, (blocks((size_t)nlist * dp)), dim3(256), 0, s, C, (size_t)nlist, d, dp, L.Cd);
         {
-            const int rc = launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, ms, s, C, L.tiles_ws, L.tiles_bytes);
+            const int rc = launch_probe(X, n, d, dp, L.Cd, nlist, 1, L.probe, ms, s, C, L.tiles_ws, L.tiles_bytes, it > 0);
             if (rc != TSNE_OK) return rc;
         }
         hipLaunchKernelGGL(fill_u64_k, (blocks(cd)), dim3(256), 0, s, L.sums, cd);

@@ -145,7 +145,7 @@ int ivf_train_device(const float *X, int n, int d, int nlist, int iters, float *
 // ivf_tiles_workspace: bytes for ivf_probe_tiles and (k > 0) ivf_search_tiles, or 0 if the sizes are beyond them.
 size_t ivf_tiles_workspace(int n, int d, int k, int nlist, int tau);
 int ivf_probe_tiles(const float *X, int n, int d, const float *C, int nlist, int tau, int m, int32_t *probe, void *ws,
-                    size_t ws_bytes, hipStream_t s);
+                    size_t ws_bytes, hipStream_t s, int reuse_queries);
 int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, const int32_t *probe, const int *lorder,
                      const int *cellptr, int max_list, long long max_cand, int32_t *knn_idx, double *knn_d2, void *ws,
                      size_t ws_bytes, hipStream_t s);
