@@ -141,7 +141,7 @@ def test_many_long_rows_sampled(clusters, scale):
     _check_against_oracle(X, 20.0, k, rows=np.unique(rows))
 
 
-@pytest.mark.parametrize("name", ["plane", "lattice", "copies", "blobs"])
+@pytest.mark.parametrize("name", ["plane", "lattice", "copies", "blobs", "tiny", "one_tile_and_a_row"])
 def test_rows_of_256_and_more_coordinates(name):
     """Rows this long are swept with the high parts of the split values first and only the rows without a
     certificate go on to the three-product tiles and, failing that, to the exact pass.
@@ -160,6 +160,12 @@ def test_rows_of_256_and_more_coordinates(name):
     elif name == "copies":
         n, d, k = 2500, 320, 23
         X = np.repeat(r.standard_normal((500, d)).astype(np.float32), 5, axis=0)
+    elif name == "tiny":
+        n, d, k = 70, 260, 10
+        X = r.standard_normal((n, d)).astype(np.float32)
+    elif name == "one_tile_and_a_row":       # 257 rows: a second tile with a single row in it
+        n, d, k = 257, 512, 30
+        X, _ = synth.gaussian_mixture(n, d, 3, 2.0, 1.0, seed=23)
     else:
         n, d, k = 70_000, 257, 60
         X, _ = synth.gaussian_mixture(n, d, 50, 3.0, 1.0, seed=22)
