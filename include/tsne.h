@@ -128,13 +128,15 @@ void tsne_destroy(tsne_ctx *ctx);
  * *n_unconverged (host, may be NULL) receives the number of rows whose entropy could not be
  * brought within 1e-5 of the target (e.g. all neighbours equidistant).
  * X must be finite with |x| < 1e38.  Candidate neighbours are found with reduced-precision products
- * (each value, minus its column's mean, as two bf16 parts), every row's list is then re-ranked in double
- * precision from X itself and checked against a bound on the candidate search's error; rows that cannot be
- * certified (ties at the k-th distance) are redone exactly against all n rows, 2k rows a launch, so the
- * lists do not depend on the reduced precision.
- * Workspace: about 4 n (d rounded up to 32) bytes for the split copy of X, 20 n k for neighbour
- * lists and probabilities, 16 n k for sorting, and 8 * 65536 * (k' + 4160) with k' = k + max(k/2, 32)
- * for the candidate buffers (tsne_build_P_workspace_bytes() gives the exact figure).
+ * (each value, minus its column's mean, as two bf16 parts; rows of 256 and more coordinates first as one
+ * half-precision value), every row's list is then re-ranked in double precision from X itself and checked
+ * against a bound on the candidate search's error; rows that cannot be certified go on to the next finer
+ * search and finally (ties at the k-th distance) are redone exactly against all n rows, 2k rows a launch, so
+ * the lists do not depend on the reduced precision.
+ * Workspace: about 4 n (d rounded up to 32) bytes for the split copy of X (half as much again for rows of
+ * 256 and more coordinates), 20 n k for neighbour lists and probabilities, 16 n k for sorting, and
+ * 8 * 65536 * (k' + 4160) with k' = k + max(k/2, 32) for the candidate buffers
+ * (tsne_build_P_workspace_bytes() gives the exact figure).
  * Limits: k' <= 1920, d <= 4096, 2 n k < 2^31.
  * Synchronises the stream before returning.
  */
