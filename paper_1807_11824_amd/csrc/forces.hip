@@ -351,7 +351,6 @@ constexpr int FT_THREADS = 512;
 constexpr int FT_UNROLL = 8;
 constexpr size_t FT_LDS = (size_t)FT_ROWS * 16;
 
-typedef __attribute__((address_space(3))) double ft_lds_f64;
 typedef __attribute__((address_space(1))) double ft_glb_f64;
 
 __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *__restrict__ ptr, const int32_t *__restrict__ tcol,
@@ -364,7 +363,7 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     extern __shared__ __align__(16) unsigned char ft_smem[];
     // x sums, then y sums; row r of the tile at slot r ^ (r / 32 % 32): rows a fixed stride apart
     // (entries arrive roughly in row order) would otherwise meet in the same LDS banks
-    double *acc = reinterpret_cast<double *>(ft_smem);
+    long long *acc = reinterpret_cast<long long *>(ft_smem);      // integer sums: the terms are whole numbers
     const uint32_t tid = threadIdx.x;
     const int rt = blockIdx.x, row0 = rt * FT_ROWS;
     // this workgroup's share of the row tile's entries
@@ -373,7 +372,7 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     const int s0 = t0 + (int)blockIdx.y * per, s1 = min(t1, s0 + per);
     if (s0 >= s1) return;                   // the same for every thread
     const int shift = ft_shift(meta);
-    for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) acc[t] = 0.0;
+    for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) acc[t] = 0ll;
     __syncthreads();
     // Entries past the end of the share are read as the share's last entry with weight 0 (they add 0).
     // The entries of the next trip are requested before the gathers of this one.
@@ -413,16 +412,16 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
             const float dx = yi[u].x - yj[u].x, dy = yi[u].y - yj[u].y;
             const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
             const float pw = v[u] * w;
-            const double fx = trunc(ldexp((double)(pw * dx), shift)), fy = trunc(ldexp((double)(pw * dy), shift));
+            const long long fx = (long long)ldexp((double)(pw * dx), shift), fy = (long long)ldexp((double)(pw * dy), shift);
             const uint32_t slot = rl[u] ^ ((rl[u] >> 5) & 31u);
-            (void)__builtin_amdgcn_ds_atomic_fadd_f64((ft_lds_f64 *)(acc + slot), fx);
-            (void)__builtin_amdgcn_ds_atomic_fadd_f64((ft_lds_f64 *)(acc + FT_ROWS + slot), fy);
+            atomicAdd(reinterpret_cast<unsigned long long *>(acc + slot), (unsigned long long)fx);
+            atomicAdd(reinterpret_cast<unsigned long long *>(acc + FT_ROWS + slot), (unsigned long long)fy);
         }
     }
     __syncthreads();
     for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) {
         const uint32_t r = t / 2, slot = r ^ ((r >> 5) & 31u);
-        const double a = acc[(t & 1u) * FT_ROWS + slot];
+        const double a = (double)acc[(t & 1u) * FT_ROWS + slot];
         if (a != 0.0 && row0 + (int)r < n) {
             if (gridDim.y == 1) gacc[2 * (size_t)row0 + t] = a;      // the only workgroup of this row tile
             else (void)__builtin_amdgcn_global_atomic_fadd_f64((ft_glb_f64 *)(gacc + 2 * (size_t)row0 + t), a);
