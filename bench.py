@@ -27,7 +27,7 @@ def workload_inputs(name):
     """Synthetic X for the named configuration (recipes in paper_1807_11824_amd/synth.py).
 
     cfg5 is the headline configuration as stated: N = 1,281,167, D = 2048 (10.5 GB of X, about 20 s to draw on
-    the host and 25 s for the exact tsne_build_P).  cfg5_standin is a quick substitute for kernel work: the same
+    the host and 7 s for the exact tsne_build_P).  cfg5_standin is a quick substitute for kernel work: the same
     1000-cluster ReLU-Gaussian mixture drawn in D' = 64 dimensions with the cluster means at scale 2, which gives
     the same neighbourhood structure (every point's neighbours lie in its own cluster) in a second; it is never
     what the default run reports.
