@@ -37,7 +37,7 @@ size_t carve(tsne_ctx *c, const tsne_params *p, char *base)
         return (void *)ptr;
     };
     const int32_t cap = (int32_t)cell_capacity(p->n, p->morton_bits, p->leaf_cap);   // < 2^31: check_params
-    const size_t nblk_sort = (n + SORT_TILE - 1) / SORT_TILE;
+    const size_t nblk_sort = (n + SORT_TILE_MIN - 1) / SORT_TILE_MIN;   // the most tiles any tile size gives
     const size_t nblk_lev = (n + LEVEL_TILE - 1) / LEVEL_TILE;
     const size_t ngroups = (n + WAVE - 1) / WAVE;
     void *q;
@@ -301,6 +301,7 @@ int tsne_create(tsne_ctx **out, const tsne_params *p, void *stream, void *d_work
             return TSNE_EHIP;
         }
     }
+    c->sort_items = sort_items(p->n, c->num_cu);
     if (p->overlap) {
         // default priority on purpose; non-blocking so that it does not serialise with stream 0
         if ((e = hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking)) != hipSuccess ||

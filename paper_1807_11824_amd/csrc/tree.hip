@@ -250,6 +250,8 @@ __device__ __forceinline__ uint32_t digit_of(uint64_t w, int lo, uint32_t mask) 
 
 // Root square (already reduced), grid key and word of every point, and the digit counts of the
 // first radix pass.
+// (ITEMS words per thread: the tile size is chosen per context, see sort_items())
+template <int ITEMS>
 __global__ __launch_bounds__(SORT_THREADS) void morton_encode_hist(const float2 *__restrict__ Y, int n,
                                                                    const float4 *__restrict__ root, int bits, int ks,
                                                                    uint32_t mask, uint64_t *__restrict__ words,
@@ -260,9 +262,9 @@ __global__ __launch_bounds__(SORT_THREADS) void morton_encode_hist(const float2 
     __syncthreads();
     const float4 r = *root;
     const uint32_t qmax = (1u << bits) - 1u;
-    const int base = blockIdx.x * SORT_TILE;
+    const int base = blockIdx.x * (SORT_THREADS * ITEMS);
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k) {
+    for (int k = 0; k < ITEMS; ++k) {
         const int e = base + k * SORT_THREADS + (int)threadIdx.x;
         if (e < n) {
             const uint64_t w = (grid_key(Y[e], r, qmax) << ks) | (uint32_t)e;
@@ -274,21 +276,22 @@ __global__ __launch_bounds__(SORT_THREADS) void morton_encode_hist(const float2 
     for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) hist[(size_t)blockIdx.x * RADIX + d] = h[d];
 }
 
+template <int ITEMS>
 __global__ __launch_bounds__(SORT_THREADS) void radix_hist(const uint64_t *__restrict__ words, int n, int lo, uint32_t mask,
                                                            uint32_t *__restrict__ hist, int nblk)
 {
     __shared__ uint32_t h[RADIX];
     for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) h[d] = 0u;
     __syncthreads();
-    const int base = blockIdx.x * SORT_TILE;
-    uint64_t w[SORT_ITEMS];
+    const int base = blockIdx.x * (SORT_THREADS * ITEMS);
+    uint64_t w[ITEMS];
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k) {          // all loads in flight before the first count
+    for (int k = 0; k < ITEMS; ++k) {          // all loads in flight before the first count
         const int e = base + k * SORT_THREADS + (int)threadIdx.x;
         w[k] = e < n ? words[e] : 0ull;
     }
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k)
+    for (int k = 0; k < ITEMS; ++k)
         if (base + k * SORT_THREADS + (int)threadIdx.x < n) atomicAdd(&h[digit_of(w[k], lo, mask)], 1u);
     __syncthreads();
     for (int d = threadIdx.x; d < RADIX; d += SORT_THREADS) hist[(size_t)blockIdx.x * RADIX + d] = h[d];
@@ -358,16 +361,18 @@ __device__ __forceinline__ int scatter_tile(int block, int nblk)
     return (block % 8) * per + block / 8;
 }
 
+template <int ITEMS>
 __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
                                                               int n, int lo, uint32_t mask,
                                                               const uint32_t *__restrict__ hist,
                                                               const uint32_t *__restrict__ dtot, int nblk)
 {
     constexpr int NW = SORT_THREADS / WAVE, DPT = RADIX / SORT_THREADS;   // digits per thread
+    constexpr int TILE = SORT_THREADS * ITEMS;
     // per-wave running digit counts, later per-wave starts; once every word knows its place in the
     // locally sorted tile the same memory holds that tile
-    constexpr size_t OVERLAY = sizeof(uint16_t) * NW * RADIX > (size_t)SORT_TILE * 8 ? sizeof(uint16_t) * NW * RADIX
-                                                                                   : (size_t)SORT_TILE * 8;
+    constexpr size_t OVERLAY = sizeof(uint16_t) * NW * RADIX > (size_t)TILE * 8 ? sizeof(uint16_t) * NW * RADIX
+                                                                                   : (size_t)TILE * 8;
     __shared__ __align__(16) unsigned char overlay[OVERLAY];
     uint16_t (*whist)[RADIX] = reinterpret_cast<uint16_t (*)[RADIX]>(overlay);
     uint64_t *sorted = reinterpret_cast<uint64_t *>(overlay);
@@ -377,12 +382,12 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint64_t *__
     const int tile = scatter_tile((int)blockIdx.x, nblk);
     if (tile >= nblk) return;               // the same for every thread of the workgroup
     const int tid = (int)threadIdx.x, w = tid >> 6, lane = tid & 63;
-    const int tile0 = tile * SORT_TILE;
-    const int base = tile0 + w * (WAVE * SORT_ITEMS);
-    uint64_t word[SORT_ITEMS];
-    uint32_t rank[SORT_ITEMS];
+    const int tile0 = tile * TILE;
+    const int base = tile0 + w * (WAVE * ITEMS);
+    uint64_t word[ITEMS];
+    uint32_t rank[ITEMS];
 #pragma unroll
-    for (int r = 0; r < SORT_ITEMS; ++r) {       // requested first: they arrive while the offsets below are worked out
+    for (int r = 0; r < ITEMS; ++r) {       // requested first: they arrive while the offsets below are worked out
         const int e = base + r * WAVE + lane;
         word[r] = e < n ? in[e] : 0ull;
     }
@@ -411,7 +416,7 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint64_t *__
     // instructions execute in program order, so the rounds need no barrier between them.
     volatile uint16_t *mine = whist[w];
 #pragma unroll
-    for (int r = 0; r < SORT_ITEMS; ++r) {
+    for (int r = 0; r < ITEMS; ++r) {
         const bool valid = base + r * WAVE + lane < n;
         const uint32_t d = digit_of(word[r], lo, mask);
         uint64_t peers = __ballot(valid);
@@ -449,17 +454,17 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter(const uint64_t *__
     __syncthreads();
     // stable local sort through LDS ...
 #pragma unroll
-    for (int r = 0; r < SORT_ITEMS; ++r) {
+    for (int r = 0; r < ITEMS; ++r) {
         const uint32_t d = digit_of(word[r], lo, mask);
         rank[r] += (uint32_t)lstart[d] + (uint32_t)whist[w][d];
     }
     __syncthreads();      // the counts are no longer needed: their memory becomes the sorted tile
 #pragma unroll
-    for (int r = 0; r < SORT_ITEMS; ++r)
-        if (base + r * WAVE + lane < n) sorted[min(rank[r], (uint32_t)SORT_TILE - 1u)] = word[r];
+    for (int r = 0; r < ITEMS; ++r)
+        if (base + r * WAVE + lane < n) sorted[min(rank[r], (uint32_t)TILE - 1u)] = word[r];
     __syncthreads();
     // ... so that consecutive threads write consecutive addresses within each digit's run
-    const int cnt = min(SORT_TILE, n - tile0);
+    const int cnt = min(TILE, n - tile0);
     for (int j = tid; j < cnt; j += SORT_THREADS) {
         const uint64_t v = sorted[j];
         const uint32_t d = digit_of(v, lo, mask);
@@ -1016,25 +1021,53 @@ static int bbox_blocks(int n)
     return nb < BBOX_MAX_BLOCKS ? nb : BBOX_MAX_BLOCKS;
 }
 
-// Stable LSD radix sort of words[0] on bits [lo, lo + nbits), RADIX_BITS a pass.
-hipError_t launch_sort(tsne_ctx *c, int lo, int nbits, bool hist0, hipStream_t s)
+// Words per thread of the sort's tiles: a tile is a workgroup, and a launch is as long as its busiest compute unit,
+// so the tile size is taken (from 8, 10 or 12 words a thread) to make the number of tiles per compute unit, rounded
+// up, times the tile size smallest: 1,281,167 words are 313 tiles of 4096, which leaves 57 units with two, or 251
+// tiles of 5120, one each.
+int sort_items(int n, int num_cu)
+{
+    int best = 8;
+    long long best_cost = -1;
+    const int cu = num_cu > 0 ? num_cu : 256;
+    for (int items = 8; items <= 12; items += 2) {
+        const long long nblk = ((long long)n + SORT_THREADS * items - 1) / (SORT_THREADS * items);
+        const long long cost = ((nblk + cu - 1) / cu) * items;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = items; }
+    }
+    return best;
+}
+
+template <int ITEMS>
+static void sort_passes(tsne_ctx *c, int lo, int nbits, bool hist0, hipStream_t s)
 {
     const int n = c->p.n;
-    const int nblk = (n + SORT_TILE - 1) / SORT_TILE;
+    const int nblk = (n + SORT_THREADS * ITEMS - 1) / (SORT_THREADS * ITEMS);
     const int grid = 8 * ((nblk + 7) / 8);       // scatter_tile() deals the tiles to the XCDs
     int cur = 0;
     for (int plo = lo; plo < lo + nbits; plo += RADIX_BITS) {
         const int width = lo + nbits - plo < RADIX_BITS ? lo + nbits - plo : RADIX_BITS;
         const uint32_t mask = (1u << width) - 1u;
         if (!(hist0 && plo == lo))
-            hipLaunchKernelGGL(radix_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, c->words[cur], n, plo, mask, c->hist, nblk);
+            hipLaunchKernelGGL(radix_hist<ITEMS>, dim3(nblk), dim3(SORT_THREADS), 0, s, c->words[cur], n, plo, mask, c->hist,
+                               nblk);
         hipLaunchKernelGGL(radix_scan, dim3(RADIX / SCAN_DIGITS), dim3(SCAN_DIGITS * SCAN_SEGS), 0, s, c->hist, nblk,
                            c->dtot);
-        hipLaunchKernelGGL(radix_scatter, dim3(grid), dim3(SORT_THREADS), 0, s, c->words[cur], c->words[cur ^ 1], n, plo,
-                           mask, c->hist, c->dtot, nblk);
+        hipLaunchKernelGGL(radix_scatter<ITEMS>, dim3(grid), dim3(SORT_THREADS), 0, s, c->words[cur], c->words[cur ^ 1], n,
+                           plo, mask, c->hist, c->dtot, nblk);
         cur ^= 1;
     }
     c->sorted_buf = cur;
+}
+
+// Stable LSD radix sort of words[0] on bits [lo, lo + nbits), RADIX_BITS a pass.
+hipError_t launch_sort(tsne_ctx *c, int lo, int nbits, bool hist0, hipStream_t s)
+{
+    switch (c->sort_items) {
+    case 10: sort_passes<10>(c, lo, nbits, hist0, s); break;
+    case 12: sort_passes<12>(c, lo, nbits, hist0, s); break;
+    default: sort_passes<8>(c, lo, nbits, hist0, s); break;
+    }
     return hipGetLastError();
 }
 
@@ -1070,10 +1103,17 @@ hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
     }
     hipLaunchKernelGGL(bbox_final, dim3(1), dim3(c->bbox_nparts > 1024 ? 1024 : 256), 0, s, c->bbox_part, c->bbox_nparts, B,
                        c->root, c->status);
-    const int nblk = (n + SORT_TILE - 1) / SORT_TILE;
+    const int items = c->sort_items, nblk = (n + SORT_THREADS * items - 1) / (SORT_THREADS * items);
     const int width0 = 2 * B < RADIX_BITS ? 2 * B : RADIX_BITS;
-    hipLaunchKernelGGL(morton_encode_hist, dim3(nblk), dim3(SORT_THREADS), 0, s, Y, n, c->root, B, ks, (1u << width0) - 1u,
-                       c->words[0], c->hist, nblk);
+    if (items == 10)
+        hipLaunchKernelGGL(morton_encode_hist<10>, dim3(nblk), dim3(SORT_THREADS), 0, s, Y, n, c->root, B, ks,
+                           (1u << width0) - 1u, c->words[0], c->hist, nblk);
+    else if (items == 12)
+        hipLaunchKernelGGL(morton_encode_hist<12>, dim3(nblk), dim3(SORT_THREADS), 0, s, Y, n, c->root, B, ks,
+                           (1u << width0) - 1u, c->words[0], c->hist, nblk);
+    else
+        hipLaunchKernelGGL(morton_encode_hist<8>, dim3(nblk), dim3(SORT_THREADS), 0, s, Y, n, c->root, B, ks,
+                           (1u << width0) - 1u, c->words[0], c->hist, nblk);
     return launch_sort(c, ks, 2 * B, true, s);
 }
 

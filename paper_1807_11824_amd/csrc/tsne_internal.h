@@ -30,8 +30,7 @@ struct ScanPart {
 constexpr int RADIX_BITS = 11;           // digit width of the radix sort
 constexpr int RADIX = 1 << RADIX_BITS;
 constexpr int SORT_THREADS = 512;
-constexpr int SORT_ITEMS = 8;
-constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;
+constexpr int SORT_TILE_MIN = SORT_THREADS * 8;   // smallest tile of the sort (words per thread: 8, 10 or 12)
 constexpr int MAX_GRID_BITS = 24;        // a float has 24 significant bits
 constexpr int SMALL_SORT_MAX = 8192;  // up to here one workgroup finds root, keys and order in LDS
 constexpr int LEVEL_THREADS = 256;
@@ -123,6 +122,7 @@ struct tsne_ctx {
     double *zpart, *Z;
     double *kl_part;
     int sorted_buf;      // which of words[] holds the sorted result
+    int sort_items;      // words per thread of the sort's tiles (sort_items())
     // optional per-phase timing: 9 events per armed step
     hipEvent_t *tev;
     int t_cap, t_used;
@@ -163,6 +163,7 @@ hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode);   // tile
 hipError_t launch_graph_order(tsne_ctx *c, hipStream_t s);   // leaves the order in c->perm
 // stable sort of words[0] on bits [lo, lo + nbits); result in words[sorted_buf].  hist0: the digit counts of the
 // first pass are already in c->hist (left by the kernel that wrote the words)
+int sort_items(int n, int num_cu);
 hipError_t launch_sort(tsne_ctx *c, int lo, int nbits, bool hist0, hipStream_t s);
 hipError_t launch_unpack_perm(tsne_ctx *c, hipStream_t s);   // c->perm = low 32 bits of words[sorted_buf] (the graph order's words)
 hipError_t launch_scatter2(const float2 *in, const uint32_t *orig, float2 *out, int n, hipStream_t s);
