@@ -1651,7 +1651,7 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
             }
         }
         hipLaunchKernelGGL(knn_rerank, dim3(rows), dim3(256), rerank_smem, s, X, n, d, lorder, X, n, lorder, lorder, (const int *)nullptr, q0,
-                           rows, k, kp, 0x7FFFFFFF, tile_error_coeff(d, d > KFLUSH), 0.0, L.norms, norm_max, L.tau, L.cnt, L.cand, cap, knn_idx, knn_d2, L.fail_count,
+                           rows, k, kp, 0x7FFFFFFF, tile_error_coeff(d, true), 0.0, L.norms, norm_max, L.tau, L.cnt, L.cand, cap, knn_idx, knn_d2, L.fail_count,
                            L.fail_rows);
         HIPCHK(hipGetLastError());
     }
@@ -2060,6 +2060,8 @@ int tsne_build_P_approx_workspace_bytes(int32_t n, int32_t d, int32_t k, int32_t
         const int ksub = n < PQ_KSUB ? n : PQ_KSUB;
         if (tsne_ivfpq_workspace_bytes(n, d, k, nlist, tau, pq_m, ksub, &ivf) != TSNE_OK) return TSNE_EINVAL;
         if (tsne_ivfpq_workspace_bytes(n, d, k, nlist, tau_max, pq_m, ksub, &ivf_max) != TSNE_OK) return TSNE_EINVAL;
+        const size_t coarse = ivf_workspace(n, d, 0, nlist, 1);       // training the coarse centroids comes first
+        if (coarse > ivf) ivf = coarse;
     } else {
         if (tsne_ivf_workspace_bytes(n, d, k, nlist, tau, &ivf) != TSNE_OK) return TSNE_EINVAL;
         if (tsne_ivf_workspace_bytes(n, d, k, nlist, tau_max, &ivf_max) != TSNE_OK) return TSNE_EINVAL;

@@ -33,6 +33,10 @@ constexpr size_t IVF_ALIGN = 256;
 inline size_t up256(size_t v) { return (v + IVF_ALIGN - 1) / IVF_ALIGN * IVF_ALIGN; }
 
 constexpr int IVF_DC = 64;       // coordinates per staged chunk
+// Rows longer than this are searched on the matrix-core tiles; shorter ones by the double-precision kernels here, which
+// are the faster ones there (benchmark stand-in at 64 coordinates: 0.22 s against 0.51 s through the tiles; 5M x 50 with
+// 16 lists probed: 3.1 s against 14.2 s).
+constexpr int TILES_MIN_D = IVF_DC;
 constexpr int IVF_CB = 8;        // list rows per register block
 constexpr int IVF_SAMPLE = 2048;      // keys of a row sampled for the cut
 constexpr int IVF_BUF_MIN = 1024, IVF_BUF_MAX = 4096;   // keys that may pass the cut (3 k within these bounds)
@@ -806,7 +810,7 @@ int launch_probe(const float *X, int n, int d, int dp, const double *Cd, int nli
                  hipStream_t s, const float *C = nullptr, void *tiles_ws = nullptr, size_t tiles_bytes = 0,
                  int reuse_queries = 0)
 {
-    if (d > IVF_DC && C && tiles_bytes > 0)
+    if (d > TILES_MIN_D && C && tiles_bytes > 0)
         return ivf_probe_tiles(X, n, d, C, nlist, tau, m, probe, tiles_ws, tiles_bytes, s, reuse_queries);
     const size_t lists = 12 * (size_t)WAVE * tau;
     if (d > IVF_DC)
@@ -885,7 +889,7 @@ size_t ivf_carve(IvfLayout *L, int n, int d, int nlist, int tau, char *base, siz
     q = take(8 * 8 * (size_t)nlist); if (L) L->mind = (double *)q;
     q = take(4 * (size_t)nlist); if (L) L->sel = (int *)q;
     {
-        const size_t tb = k_tiles >= 0 && d > IVF_DC ? ivf_tiles_workspace(n, d, k_tiles, nlist, tau) : 0;
+        const size_t tb = k_tiles >= 0 && d > TILES_MIN_D ? ivf_tiles_workspace(n, d, k_tiles, nlist, tau) : 0;
         q = take(tb); if (L) { L->tiles_ws = q; L->tiles_bytes = tb; }
     }
     // distance scratch: whatever is left, at least one row of n distances, at most IVF_D_MAX
@@ -999,7 +1003,7 @@ static int ivf_knn_impl(const float *X, int n, int d, const float *C, int nlist,
         if (m - 1 < k) rc = TSNE_ENUM;            // fewer than k other points in the probed lists
         if (m > mmax) mmax = m;
     }
-    if (rc == TSNE_OK && !pq.codes && d > IVF_DC && L.tiles_bytes > 0) {
+    if (rc == TSNE_OK && !pq.codes && d > TILES_MIN_D && L.tiles_bytes > 0) {
         // long rows, flat second stage: the distances of Eq. (11) on the matrix-core tiles of the exact search
         free(mp);
         int *cp = (int *)malloc(4 * ((size_t)nlist + 1));

@@ -238,11 +238,12 @@ def test_ivfpq_bad_arguments():
         ivfpq_train(X, C, 2, 300, 2)          # more than 256 centroids
 
 
-def test_P_from_product_quantised_neighbours():
+@pytest.mark.parametrize("d", [48, 96])      # 96: the coarse centroids are trained through the matrix-core tiles
+def test_P_from_product_quantised_neighbours(d):
     """tsne_build_P_approx with pq_m > 0 against the oracle's pieces in the same order: coarse k-means, codebooks,
     codes and search (Eq. (8), (11)), Eq. (1) on the distances to the codes, symmetric CSR."""
     from paper_1807_11824_amd import build_P_approx
-    X, _ = synth.gaussian_mixture(3000, 48, 4, 10.0, 1.0, seed=1)
+    X, _ = synth.gaussian_mixture(3000, d, 4, 10.0, 1.0, seed=1)
     nlist, tau, k, perp, iters, m = 55, 8, 45, 15.0, 5, 12
     C, _ = ivf.kmeans_train(X, nlist, iters)
     cb = ivf.pq_train(X, C, m, 256, iters)
