@@ -57,11 +57,53 @@ def test_knn_rows_and_P_invariants(full):
     _check_rows(full, 256, 0)
 
 
+def _ivf_rows_against_oracle(X, k, tau, n_rows, seed):
+    """tsne_ivf_knn on all of X (sqrt(N) lists, spread-out start as centroids); for sampled queries the oracle walks
+    all points in exact (distance, index) order and assigns only the ones it meets: the first k whose list is among
+    the query's probed lists are Eq. (11)'s answer."""
+    import torch
+    from oracle import ivf
+    from paper_1807_11824_amd import ivf_knn
+    n, d = X.shape
+    nlist = int(round(n ** 0.5))
+    C = ivf.kmeans_init(X, nlist)
+    dev = torch.device("cuda:0")
+    idx, d2 = ivf_knn(torch.from_numpy(X).to(dev), torch.from_numpy(C).to(dev), tau, k)
+    rows = np.sort(np.random.default_rng(seed).choice(n, n_rows, replace=False))
+    got_idx = idx[rows.tolist()].cpu().numpy()
+    got_d2 = d2[rows.tolist()].cpu().numpy()
+    del idx, d2
+    torch.cuda.empty_cache()
+    for r, q in enumerate(rows):
+        probed = set(ivf.probes(X[q:q + 1], C, tau)[0].tolist())
+        dd = np.empty(n, np.float64)
+        xq = X[q].astype(np.float64)
+        for a in range(0, n, 65536):                  # (a double copy of X would not fit at D = 2048)
+            diff = X[a:a + 65536].astype(np.float64) - xq
+            dd[a:a + 65536] = np.einsum("nd,nd->n", diff, diff)
+        order = np.lexsort((np.arange(n), dd))
+        want, want_d = [], []
+        for a in range(0, n, 512):
+            block = order[a:a + 512]
+            cells, _ = ivf.assign(X[block], C)
+            for j, c in zip(block, cells):
+                if j != q and int(c) in probed:
+                    want.append(int(j)); want_d.append(dd[j])
+            if len(want) >= k:
+                break
+        assert got_idx[r].tolist() == want[:k], f"row {q}"
+        assert np.allclose(got_d2[r], want_d[:k], rtol=1e-13, atol=1e-300)
+
+
 def test_knn_rows_and_P_invariants_as_stated():
-    """The headline configuration as stated, N = 1,281,167 x D = 2048 (the two-level tile kernel, 64 slabs a row):
-    neighbour lists of sampled rows against the oracle's double-precision search over all rows, and P's invariants."""
+    """The headline configuration as stated, N = 1,281,167 x D = 2048 (half-precision first sweep, 32 slabs a row):
+    neighbour lists of sampled rows against the oracle's double-precision search over all rows, and P's invariants;
+    then the inverted-file search on the same X (1132 lists, 4 probed: probes and list tiles on the matrix cores)."""
     built = _build("cfg5")
     _check_rows(built, 40, 3)
+    X, k = built["X"], built["cfg"]["k"]
+    del built
+    _ivf_rows_against_oracle(X, k, 4, 6, 4)
 
 
 def test_P_where_one_launch_axis_is_too_short():
@@ -114,35 +156,5 @@ def test_forces_in_bench_configuration(full):
 
 
 def test_inverted_file_search_on_sampled_rows(full):
-    """tsne_ivf_knn at full size (1132 lists, 4 probed).  The oracle cannot assign 1.28M points to their lists in
-    reasonable time, so for each sampled query it walks all points in exact (distance, index) order and assigns
-    only the ones it meets: the first k whose list is among the query's probed lists are Eq. (11)'s answer."""
-    import torch
-    from oracle import ivf
-    from paper_1807_11824_amd import ivf_knn
-    X, cfg = full["X"], full["cfg"]
-    n, k, tau = cfg["n"], cfg["k"], 4
-    nlist = int(round(n ** 0.5))
-    C = ivf.kmeans_init(X, nlist)
-    dev = torch.device("cuda:0")
-    idx, d2 = ivf_knn(torch.from_numpy(X).to(dev), torch.from_numpy(C).to(dev), tau, k)
-    rows = np.sort(np.random.default_rng(1).choice(n, 16, replace=False))
-    got_idx = idx[rows.tolist()].cpu().numpy()
-    got_d2 = d2[rows.tolist()].cpu().numpy()
-    Xd = X.astype(np.float64)
-    for r, q in enumerate(rows):
-        probed = set(ivf.probes(X[q:q + 1], C, tau)[0].tolist())
-        diff = Xd - Xd[q]
-        dd = np.einsum("nd,nd->n", diff, diff)
-        order = np.lexsort((np.arange(n), dd))
-        want, want_d = [], []
-        for a in range(0, n, 512):
-            block = order[a:a + 512]
-            cells, _ = ivf.assign(X[block], C)
-            for j, c in zip(block, cells):
-                if j != q and int(c) in probed:
-                    want.append(int(j)); want_d.append(dd[j])
-            if len(want) >= k:
-                break
-        assert got_idx[r].tolist() == want[:k], f"row {q}"
-        assert np.allclose(got_d2[r], want_d[:k], rtol=1e-13, atol=1e-300)
+    """tsne_ivf_knn at full size on rows of 64 coordinates (1132 lists, 4 probed; the double-precision kernels)."""
+    _ivf_rows_against_oracle(full["X"], full["cfg"]["k"], 4, 16, 1)
