@@ -498,6 +498,13 @@ struct KeyWindow {
     }
 };
 
+// Keys of positions [lo, ...) in LDS, for searches that are known to stay inside.
+struct LdsKeys {
+    const uint64_t *lds;
+    uint32_t lo;
+    __device__ __forceinline__ uint64_t operator[](uint32_t q) const { return lds[q - lo]; }
+};
+
 // Cooperative fill; the caller synchronises the workgroup afterwards.
 __device__ __forceinline__ KeyWindow key_window_fill(const uint64_t *__restrict__ words, int ks, uint32_t n, uint32_t first,
                                                      uint32_t count, uint64_t *lds)
@@ -514,7 +521,8 @@ __device__ __forceinline__ KeyWindow key_window_fill(const uint64_t *__restrict_
 }
 
 // Sorted keys: the positions whose key shifted right by sh equals pre form one contiguous run.
-__device__ __forceinline__ uint32_t run_end(const KeyWindow &keys, uint32_t n, uint32_t p, int sh, uint64_t pre)
+template <class Keys>
+__device__ __forceinline__ uint32_t run_end(const Keys &keys, uint32_t n, uint32_t p, int sh, uint64_t pre)
 {
     uint32_t lo = p, hi, step = 1;
     for (;;) {
@@ -796,7 +804,8 @@ __global__ __launch_bounds__(LEVEL_THREADS) void downsweep(const float2 *__restr
 }
 
 // First position in [s, e) whose digit (2 bits at sh) is >= q; e if none.
-__device__ __forceinline__ uint32_t digit_lower_bound(const KeyWindow &keys, uint32_t s, uint32_t e,
+template <class Keys>
+__device__ __forceinline__ uint32_t digit_lower_bound(const Keys &keys, uint32_t s, uint32_t e,
                                                       int sh, uint32_t q)
 {
     while (s < e) {
@@ -807,11 +816,35 @@ __device__ __forceinline__ uint32_t digit_lower_bound(const KeyWindow &keys, uin
 }
 
 // One lane per cell (cells are numbered in pre-order, so the cells of a workgroup start at
-// non-decreasing positions and the keys they search sit in one short stretch, staged in LDS).
-// A cell whose run of positions ends inside that stretch is finished on the spot.  The few large
-// cells near the top of the tree would each be a chain of dozens of dependent memory reads in a
-// single lane; they are put on a list instead and finished by write_big_cells, one wave per search.
+// non-decreasing positions and the keys they search sit in one stretch of CELL_WINDOW positions,
+// staged in LDS).  A cell whose run of positions ends inside that stretch is finished on the spot,
+// by searches that never leave LDS.  The large cells near the top of the tree would each be a
+// chain of dozens of dependent memory reads in a single lane; they (and any cell that starts past
+// the stretch) are put on a list instead and finished by write_big_cells, one wave per search.
 constexpr int CELL_WINDOW = 2048;
+
+// End of the cell (p, t) and the first positions of its children after the first; returns their number.
+template <class Keys>
+__device__ __forceinline__ int cell_extent(const Keys &keys, uint32_t lim, uint32_t n, uint32_t p, int t, int B, int C,
+                                           uint64_t key, uint32_t *e_out, bool *leaf_out, uint32_t kid_pos[3])
+{
+    const uint32_t e = (t == 0) ? n : run_end(keys, lim, p, 2 * (B - t), key >> (2 * (B - t)));
+    const bool leaf = e - p <= (uint32_t)C || t == B;
+    int nk = 0;
+    if (!leaf) {
+        const int sh = 2 * (B - t - 1);
+        uint32_t s = p;
+        const uint32_t qfirst = (uint32_t)(key >> sh) & 3u;
+        for (uint32_t q = qfirst + 1; q < 4; ++q) {
+            const uint32_t b = digit_lower_bound(keys, s, e, sh, q);
+            if (b < e && ((uint32_t)(keys[b] >> sh) & 3u) == q) kid_pos[nk++] = b;
+            s = b;
+        }
+    }
+    *e_out = e;
+    *leaf_out = leaf;
+    return nk;
+}
 
 __global__ __launch_bounds__(256) void write_cells(const uint64_t *__restrict__ words, int ks,
                                                    const uint32_t *__restrict__ cellseq,
@@ -827,54 +860,53 @@ __global__ __launch_bounds__(256) void write_cells(const uint64_t *__restrict__ 
     for (uint32_t base = blockIdx.x * 256u; base < m; base += gridDim.x * 256u) {
         const uint32_t id = base + threadIdx.x;
         const bool live = id < m;
-        const uint32_t p_first = cell_p[base], p_last = cell_p[min(base + 255u, m - 1u)];
-        KeyWindow kw;
-        kw.words = words;
-        kw.lds = kwin;
-        kw.ks = ks;
-        kw.lo = p_first;
-        kw.len = min(min((uint32_t)n, p_last + 1u + (uint32_t)KEY_HALO) - p_first, (uint32_t)CELL_WINDOW);
+        const uint32_t p_first = min(cell_p[base], (uint32_t)n - 1u);
+        const uint32_t wlen = min((uint32_t)n - p_first, (uint32_t)CELL_WINDOW), wend = p_first + wlen;
+        // the cell of this lane and the running sum at its first position: requested before the
+        // window so that they travel together with it
+        uint32_t p = 0;
+        int t = 0;
+        double2 s0 = make_double2(0.0, 0.0);
+        if (live) { p = min(cell_p[id], (uint32_t)n - 1u); t = min((int)cell_t[id], B); s0 = ps[p]; }
         __syncthreads();                    // previous round's readers are done with the window
-        for (uint32_t q = threadIdx.x; q < kw.len; q += 256u) kwin[q] = words[p_first + q] >> ks;
+        for (uint32_t q = threadIdx.x; q < wlen; q += 256u) kwin[q] = words[p_first + q] >> ks;
         __syncthreads();
         if (!live) continue;
-        const uint32_t p = cell_p[id];
-        const int t = (int)cell_t[id];
-        const uint64_t key = kw[p];
-        const uint32_t wend = kw.lo + kw.len;                  // one past the last position in the window
-        if (p < wend && wend < (uint32_t)n &&
-            (t == 0 || (kwin[kw.len - 1] >> (2 * (B - t))) == (key >> (2 * (B - t))))) {
-            // the cell runs past the window: a large cell
+        const bool inside = p >= p_first && p < wend;
+        const uint64_t key = inside ? kwin[p - p_first] : words[p] >> ks;
+        // large: starts past the window, or shares its prefix with the window's last position
+        // while the array goes on (the root, t = 0, shares it with every position)
+        const bool big = !inside || (wend < (uint32_t)n &&
+                                     (t == 0 || (kwin[wlen - 1] >> (2 * (B - t))) == (key >> (2 * (B - t)))));
+        uint32_t e, kid_pos[3];
+        bool leaf;
+        int nk;
+        if (big) {
             const uint32_t slot = atomicAdd(big_count, 1u);
             if (slot < big_cap) { big_list[slot] = make_uint2(p, (uint32_t)t); continue; }
-            // list full (cannot happen for capacity n/8 + 1024 unless most cells are huge): finish it here
+            // list full (cannot happen for capacity n/8 + 1024 unless most cells are large): finish it here,
+            // reading keys from memory wherever the window does not hold them
+            KeyWindow kw;
+            kw.words = words; kw.lds = kwin; kw.ks = ks; kw.lo = p_first; kw.len = wlen;
+            nk = cell_extent(kw, (uint32_t)n, (uint32_t)n, p, t, B, C, key, &e, &leaf, kid_pos);
+        } else {
+            // the run ends before the window's last position (which is not part of it), or at n: no probe leaves LDS
+            LdsKeys lk;
+            lk.lds = kwin; lk.lo = p_first;
+            nk = cell_extent(lk, wend < (uint32_t)n ? wend - 1u : (uint32_t)n, (uint32_t)n, p, t, B, C, key, &e, &leaf, kid_pos);
         }
-        const uint32_t e = (t == 0) ? (uint32_t)n : run_end(kw, (uint32_t)n, p, 2 * (B - t), key >> (2 * (B - t)));
+        // the reads from memory that the searches lead to, together
+        const double2 s1 = ps[e];
         const uint32_t cnt = e - p;
-        const double2 s0 = ps[p], s1 = ps[e];
         Cell c;
+        c.c1 = nk > 0 ? cellseq[kid_pos[0]] : TSNE_NONE;
+        c.c2 = nk > 1 ? cellseq[kid_pos[1]] : TSNE_NONE;
+        c.c3 = nk > 2 ? cellseq[kid_pos[2]] : TSNE_NONE;
         c.cx = (float)((s1.x - s0.x) / (double)cnt);
         c.cy = (float)((s1.y - s0.y) / (double)cnt);
         c.cnt = cnt;
-        const bool leaf = cnt <= (uint32_t)C || t == B;
         c.meta = (uint32_t)t | (leaf ? 0x100u : 0u);
         c.lo = p;
-        c.c1 = c.c2 = c.c3 = TSNE_NONE;
-        if (!leaf) {
-            const int sh = 2 * (B - t - 1);
-            uint32_t kids[3];
-            int nk = 0;
-            uint32_t s = p;
-            const uint32_t qfirst = (uint32_t)(key >> sh) & 3u;
-            for (uint32_t q = qfirst + 1; q < 4; ++q) {
-                const uint32_t b = digit_lower_bound(kw, s, e, sh, q);
-                if (b < e && ((uint32_t)(kw[b] >> sh) & 3u) == q) kids[nk++] = cellseq[b];
-                s = b;
-            }
-            if (nk > 0) c.c1 = kids[0];
-            if (nk > 1) c.c2 = kids[1];
-            if (nk > 2) c.c3 = kids[2];
-        }
         cells[id] = c;
     }
 }
@@ -1136,8 +1168,8 @@ hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s)
                            c->lev, c->part, c->big_count);
     hipLaunchKernelGGL(downsweep, dim3(nl), dim3(LEVEL_THREADS), 0, s, c->Ys, c->lev, n, c->part, c->cellseq, c->ps,
                        c->cell_p, c->cell_t, (uint32_t)c->cap_cells, c->ncells, c->status);
-    // grid sized for n cells (a typical tree has about n / 3); the kernel strides if there are more
-    hipLaunchKernelGGL(write_cells, dim3(nb), dim3(256), 0, s, words, ks, c->cellseq, c->ps, c->cell_p, c->cell_t,
+    // grid sized for n / 2 cells (a typical tree has about n / 3); the kernel strides if there are more
+    hipLaunchKernelGGL(write_cells, dim3((nb + 1) / 2), dim3(256), 0, s, words, ks, c->cellseq, c->ps, c->cell_p, c->cell_t,
                        c->ncells, n, B, C, c->cells, (uint32_t)c->cap_cells, c->big_count, c->big_list,
                        (uint32_t)c->big_cap);
     hipLaunchKernelGGL(write_big_cells, dim3(4096), dim3(256), 0, s, words, ks, c->lev,
