@@ -347,9 +347,9 @@ __device__ __forceinline__ int ft_shift(const uint32_t *meta)
     return 52 - e;
 }
 
-constexpr int FT_THREADS = 512;
+constexpr int FT_THREADS = 1024;
 constexpr int FT_UNROLL = 8;
-constexpr size_t FT_LDS = (size_t)FT_ROWS * 16;
+constexpr size_t FT_LDS = (size_t)FT_ROWS * 24;     // two sums and the position of every row
 
 typedef __attribute__((address_space(1))) double ft_glb_f64;
 
@@ -364,6 +364,7 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     // x sums, then y sums; row r of the tile at slot r ^ (r / 32 % 32): rows a fixed stride apart
     // (entries arrive roughly in row order) would otherwise meet in the same LDS banks
     long long *acc = reinterpret_cast<long long *>(ft_smem);      // integer sums: the terms are whole numbers
+    float2 *yrow = reinterpret_cast<float2 *>(ft_smem + (size_t)FT_ROWS * 16);
     const uint32_t tid = threadIdx.x;
     const int rt = blockIdx.x, row0 = rt * FT_ROWS;
     // this workgroup's share of the row tile's entries
@@ -373,6 +374,7 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     if (s0 >= s1) return;                   // the same for every thread
     const int shift = ft_shift(meta);
     for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) acc[t] = 0ll;
+    for (uint32_t t = tid; t < (uint32_t)FT_ROWS; t += FT_THREADS) yrow[t] = Y[min((uint32_t)row0 + t, (uint32_t)n - 1u)];
     __syncthreads();
     // Entries past the end of the share are read as the share's last entry with weight 0 (they add 0).
     // The entries of the next trip are requested before the gathers of this one.
@@ -394,13 +396,12 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     for (uint32_t e0 = (uint32_t)s0 + tid; e0 <= last; e0 += FT_THREADS * FT_UNROLL) {
         uint32_t rl[FT_UNROLL];
         float v[FT_UNROLL];
-        float2 yi[FT_UNROLL], yj[FT_UNROLL];
+        float2 yj[FT_UNROLL];
 #pragma unroll
         for (int u = 0; u < FT_UNROLL; ++u) {
             rl[u] = min((uint32_t)nrl[u], (uint32_t)FT_ROWS - 1u);
             v[u] = e0 + (uint32_t)u * FT_THREADS <= last ? nv[u] : 0.f;
             yj[u] = Y[min((uint32_t)ncj[u], (uint32_t)n - 1u)];
-            yi[u] = Y[min((uint32_t)row0 + rl[u], (uint32_t)n - 1u)];
         }
         // the memory counter is in order: all gathers go out before the next trip's entries are
         // requested, so that waiting for the gathers does not wait for those as well
@@ -409,7 +410,8 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < FT_UNROLL; ++u) {
-            const float dx = yi[u].x - yj[u].x, dy = yi[u].y - yj[u].y;
+            const float2 yi = yrow[rl[u]];
+            const float dx = yi.x - yj[u].x, dy = yi.y - yj[u].y;
             const float w = __builtin_amdgcn_rcpf(fmaf(dy, dy, fmaf(dx, dx, 1.0f)));
             const float pw = v[u] * w;
             const long long fx = (long long)ldexp((double)(pw * dx), shift), fy = (long long)ldexp((double)(pw * dy), shift);
