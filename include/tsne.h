@@ -87,14 +87,14 @@ typedef struct {
                                      fixed shares of every compute unit; used when there are more groups than
                                      resident waves.  0 = one wave per group.  (14) */
     int32_t far_tiles;            /* how the entries of the renumbered P that lie far from the diagonal are
-                                     summed.  1: one row at a time.  2: from a copy bucketed by 4096-row x
+                                     summed.  1: one row at a time.  2: from a copy bucketed by 6144-row x
                                      2048-column tiles, row sums kept in fixed point (every addition exact, so
                                      the result does not depend on the order of the entries).  0: chosen at
                                      tsne_set_P: tiles if the far part holds at least half of the entries and
                                      n >= 2^18, rows otherwise; kept through later renumberings.  (0) */
     int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
                                      20 bytes per entry plus 202 bytes per point (rows are padded) plus 8 bytes
-                                     per pair of a 4096-row and a 2048-column tile (n^2 / 2^20).  0 disables
+                                     per pair of a 6144-row and a 2048-column tile (n^2 / (3 x 2^19)).  0 disables
                                      renumbering; P is then only borrowed and a stop/resume is bitwise
                                      reproducible.  With renumbering a row of the attractive sum is added up
                                      as (entries near the diagonal) + (the others): deterministic, equal to

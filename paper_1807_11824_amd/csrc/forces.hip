@@ -309,38 +309,20 @@ __global__ __launch_bounds__(256) void attract_far(const int32_t *__restrict__ r
 // An entry of the far part costs attract_far a cache line for 8 bytes of Y.  When the far part is
 // large (P without a band structure: one high-dimensional blob per cluster), the entries are taken
 // tile by tile instead: a workgroup owns FT_ROWS rows and streams through their entries, which are
-// stored by column tile of FT_COLS points, so that the positions fetched around the same time share
-// the 16 KB of one column tile and many are served by the first-level cache.  Row sums are kept in
-// fixed point -- doubles that only ever hold integers below 2^53, so every addition is exact --
-// in LDS while the workgroup runs and added to a global array at its end (several workgroups may
-// share a row tile, each taking a range of its entries): the result is exact for the terms as
-// computed and does not depend on any order.
+// stored by column tile of FT_COLS points, so that the positions y_j fetched around the same time
+// share the 16 KB of one column tile and many are served by the first-level cache, which they have
+// to themselves: the rows' own positions y_i sit in LDS beside the sums (24 bytes a row, 144 KB,
+// one workgroup of 1024 lanes per compute unit).  Row sums are kept in fixed point -- 64-bit
+// integers, so every addition is exact -- in LDS while the workgroup runs and added to a global
+// array of doubles (whole numbers below 2^53) at its end (several workgroups may share a row tile,
+// each taking a range of its entries): the result is exact for the terms as computed and does not
+// depend on any order.
 // The scale: a term is p w (y_i - y_j) with w <= 1, so a row sum is below
-// (largest p) x (extent of Y) x (longest far row) < 2^e; terms are multiplied by 2^(52 - e) and
+// (largest p) x (side of the tree's root square, which holds all of Y) x (longest far row) < 2^e; terms are multiplied by 2^(52 - e) and
 // truncated to integers, which keeps every sum below 2^52.
-__global__ __launch_bounds__(256) void ft_extent_k(const float4 *__restrict__ part, int nparts, uint32_t *meta)
+__device__ __forceinline__ int ft_shift(const uint32_t *meta, const float4 *root)
 {
-    if (!meta[0]) return;
-    float mnx = INFINITY, mny = INFINITY, mxx = -INFINITY, mxy = -INFINITY;
-    for (int i = threadIdx.x; i < nparts; i += 256) {
-        const float4 a = part[2 * i], b = part[2 * i + 1];
-        mnx = fminf(mnx, a.x); mny = fminf(mny, a.y);
-        mxx = fmaxf(mxx, b.x); mxy = fmaxf(mxy, b.y);
-    }
-    float ext = fmaxf(mxx - mnx, mxy - mny);
-    ext = wave_max(ext);
-    __shared__ float sw[4];
-    if (lane_id() == 0) sw[threadIdx.x >> 6] = ext;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        ext = fmaxf(fmaxf(sw[0], sw[1]), fmaxf(sw[2], sw[3]));
-        meta[3] = __float_as_uint(ext >= 0.f && ext < INFINITY ? ext : 0.f);
-    }
-}
-
-__device__ __forceinline__ int ft_shift(const uint32_t *meta)
-{
-    const float bound = __uint_as_float(meta[1]) * __uint_as_float(meta[3]) * (float)meta[2];
+    const float bound = __uint_as_float(meta[1]) * root->z * (float)meta[2];
     if (!(bound > 0.f) || !(bound < INFINITY)) return 0;
     int e;
     (void)frexpf(bound, &e);       // bound < 2^e
@@ -357,7 +339,7 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
                                                                 const uint16_t *__restrict__ trow,
                                                                 const float *__restrict__ tval, const float2 *__restrict__ Y,
                                                                 int n, int nct, const uint32_t *__restrict__ meta,
-                                                                double *__restrict__ gacc)
+                                                                const float4 *__restrict__ root, double *__restrict__ gacc)
 {
     if (!meta[0]) return;
     extern __shared__ __align__(16) unsigned char ft_smem[];
@@ -372,7 +354,7 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
     const int per = (int)(((int64_t)(t1 - t0) + gridDim.y - 1) / gridDim.y);
     const int s0 = t0 + (int)blockIdx.y * per, s1 = min(t1, s0 + per);
     if (s0 >= s1) return;                   // the same for every thread
-    const int shift = ft_shift(meta);
+    const int shift = ft_shift(meta, root);
     for (uint32_t t = tid; t < 2u * FT_ROWS; t += FT_THREADS) acc[t] = 0ll;
     for (uint32_t t = tid; t < (uint32_t)FT_ROWS; t += FT_THREADS) yrow[t] = Y[min((uint32_t)row0 + t, (uint32_t)n - 1u)];
     __syncthreads();
@@ -433,12 +415,12 @@ __global__ __launch_bounds__(FT_THREADS) void attract_far_tiled(const int32_t *_
 
 // fixed point -> float, and the accumulators back to zero for the next step
 __global__ __launch_bounds__(256) void ft_finish_k(const uint32_t *__restrict__ far_rows, const uint32_t *__restrict__ far_count,
-                                                   int n, const uint32_t *__restrict__ meta, double *__restrict__ gacc,
-                                                   float2 *__restrict__ Afar)
+                                                   int n, const uint32_t *__restrict__ meta, const float4 *__restrict__ root,
+                                                   double *__restrict__ gacc, float2 *__restrict__ Afar)
 {
     if (!meta[0]) return;
     const uint32_t m = min(*far_count, (uint32_t)n);
-    const int shift = ft_shift(meta);
+    const int shift = ft_shift(meta, root);
     for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < m; i += gridDim.x * 256u) {
         const uint32_t row = min(far_rows[i], (uint32_t)n - 1u);
         const double ax = gacc[2 * (size_t)row], ay = gacc[2 * (size_t)row + 1];
@@ -464,7 +446,7 @@ static int attract_shares(const tsne_ctx *c)
 }
 
 // The far part from its tiles.  A small far part is summed row by row beside the tree build; the
-// tile kernels are heavy and are launched where the walk starts.  Their 64 KB of LDS per workgroup
+// tile kernels are heavy and are launched where the walk starts.  Their 144 KB of LDS per workgroup
 // does not fit beside the walk's resident waves, so they take over the chip as the walk drains.
 static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
 {
@@ -472,11 +454,10 @@ static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
     // enough workgroups to fill the chip: a row tile's entries are shared out when there are few row tiles
     const int nrt = (n + FT_ROWS - 1) / FT_ROWS;
     const int split = max(1, min(64, (8 * c->num_cu + nrt - 1) / nrt));
-    hipLaunchKernelGGL(ft_extent_k, dim3(1), dim3(256), 0, s, c->bbox_part, c->bbox_nparts, c->ft_meta);
     hipLaunchKernelGGL(attract_far_tiled, dim3((unsigned)nrt, (unsigned)split), dim3(FT_THREADS), FT_LDS, s, c->ft_ptr,
-                       c->ft_col, c->ft_row, c->ft_val, c->Yi, n, c->ft_nct, c->ft_meta, c->ft_acc);
+                       c->ft_col, c->ft_row, c->ft_val, c->Yi, n, c->ft_nct, c->ft_meta, c->root, c->ft_acc);
     hipLaunchKernelGGL(ft_finish_k, dim3((unsigned)min((n + 255) / 256, 1024)), dim3(256), 0, s, c->far_rows, c->far_count, n,
-                       c->ft_meta, c->ft_acc, c->Afar);
+                       c->ft_meta, c->root, c->ft_acc, c->Afar);
 }
 
 // The far part of the renumbered P when it is summed row by row (also shares the rows of the

@@ -207,6 +207,63 @@ __global__ __launch_bounds__(256) void ft_scatter_k(const int32_t *__restrict__ 
     }
 }
 
+// The entries of every tile, placed in any order, into the order of their columns, FT_SORT_PIECE entries
+// at a time (a counting sort in LDS over the tile's FT_COLS columns).  A gather instruction pays per cache
+// line of Y that its 64 lanes touch: 64 consecutive entries of a sorted piece of m entries span about
+// 64 / m of the tile's 128 lines instead of some 50 of them.  The row sums do not depend on the order.
+constexpr int FT_SORT_PIECE = 4096;
+__global__ __launch_bounds__(256) void ft_sort_k(const int32_t *__restrict__ ptr, int64_t tiles, int nct,
+                                                 int32_t *__restrict__ tcol, uint16_t *__restrict__ trow,
+                                                 float *__restrict__ tval, const uint32_t *meta)
+{
+    if (!meta[0]) return;
+    __shared__ int32_t scol[FT_SORT_PIECE];
+    __shared__ float sval[FT_SORT_PIECE];
+    __shared__ uint16_t srow[FT_SORT_PIECE];
+    __shared__ uint32_t bin[FT_COLS];
+    __shared__ uint32_t wsum[4];
+    static_assert(FT_COLS % 256 == 0, "columns per thread");
+    constexpr int BPT = FT_COLS / 256;
+    const int tid = (int)threadIdx.x, w = tid >> 6;
+    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int b0 = ptr[t], b1 = ptr[t + 1];
+        const uint32_t c0 = (uint32_t)(t % nct) * (uint32_t)FT_COLS;
+        for (int s0 = b0; s0 < b1; s0 += FT_SORT_PIECE) {     // (b0, b1: the same for every thread)
+            const int m = min(FT_SORT_PIECE, b1 - s0);
+            __syncthreads();                                  // the previous piece is written out
+            for (int i = tid; i < FT_COLS; i += 256) bin[i] = 0u;
+            __syncthreads();
+            for (int i = tid; i < m; i += 256) {
+                const int32_t cj = tcol[s0 + i];
+                scol[i] = cj;
+                srow[i] = trow[s0 + i];
+                sval[i] = tval[s0 + i];
+                atomicAdd(&bin[min((uint32_t)cj - c0, (uint32_t)FT_COLS - 1u)], 1u);
+            }
+            __syncthreads();
+            uint32_t loc[BPT], sum = 0;
+#pragma unroll
+            for (int k = 0; k < BPT; ++k) { loc[k] = bin[tid * BPT + k]; sum += loc[k]; }
+            int tot;
+            const int ex = wave_excl_scan((int)sum, &tot);
+            if (lane_id() == 0) wsum[w] = (uint32_t)tot;
+            __syncthreads();
+            uint32_t run = (uint32_t)ex;
+            for (int k = 0; k < w; ++k) run += wsum[k];
+#pragma unroll
+            for (int k = 0; k < BPT; ++k) { bin[tid * BPT + k] = run; run += loc[k]; }
+            __syncthreads();
+            for (int i = tid; i < m; i += 256) {
+                const int32_t cj = scol[i];
+                const uint32_t pos = min(atomicAdd(&bin[min((uint32_t)cj - c0, (uint32_t)FT_COLS - 1u)], 1u), (uint32_t)m - 1u);
+                tcol[s0 + pos] = cj;
+                trow[s0 + pos] = srow[i];
+                tval[s0 + pos] = sval[i];
+            }
+        }
+    }
+}
+
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode)
 {
     const int n = c->p.n;
@@ -235,6 +292,8 @@ hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode)
                            (const int32_t *)nullptr, c->ft_ptr);
         hipLaunchKernelGGL(ft_scatter_k<true>, dim3(blocks), dim3(256), 0, s, c->rp_far, c->col_far, c->val_s, n, c->ft_nct,
                            c->ft_cnt, c->ft_ptr, c->ft_col, c->ft_row, c->ft_val, c->ft_meta);
+        hipLaunchKernelGGL(ft_sort_k, dim3((unsigned)std::min<int64_t>(c->ft_tiles, 1 << 20)), dim3(256), 0, s, c->ft_ptr,
+                           c->ft_tiles, c->ft_nct, c->ft_col, c->ft_row, c->ft_val, c->ft_meta);
     }
     hipError_t e = launch_iota(c->row_order, n, s);
     if (e != hipSuccess) return e;

@@ -45,7 +45,7 @@ static_assert(ATTRACT_RING * 8 <= 65536, "ring offsets are stored in 16 bits");
 constexpr int ATTRACT_CHUNK = 32;        // near rows are padded to a multiple of this many entries
 constexpr int ATTRACT_SLACK = 64;        // entries readable past the end of col_s / val_s
 constexpr int ATTRACT_MAX_PARTS = 16384; // most resident workgroups of the attraction kernel
-constexpr int FT_ROWS = 4096;            // rows of a tile of the bucketed copy of the far part
+constexpr int FT_ROWS = 6144;            // rows of a tile of the bucketed copy of the far part
 constexpr int FT_COLS = 2048;            // columns of such a tile
 constexpr int64_t FT_MAX_TILES = (int64_t)1 << 27;
 
@@ -87,7 +87,7 @@ struct tsne_ctx {
     float *ft_val;
     double *ft_acc;                   // row sums in fixed point (integer-valued doubles), (x, y) per row; zero between steps
     int ft_active;                    // the tiles are in use (decided at tsne_set_P, kept through later renumberings)
-    uint32_t *ft_meta;                // [0] tiles in use, [1] largest P value (bits), [2] longest far row, [3] extent of Y (bits)
+    uint32_t *ft_meta;                // [0] tiles in use, [1] largest P value (bits), [2] longest far row
     float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
     float4 *bbox_part;   // (min, max) pairs of the bounding box, one per workgroup of the kernel that made them
