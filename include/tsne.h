@@ -91,7 +91,7 @@ typedef struct {
                                      2048-column tiles, row sums kept in fixed point (every addition exact, so
                                      the result does not depend on the order of the entries).  0: chosen at
                                      tsne_set_P: tiles if the far part holds at least half of the entries and
-                                     n >= 2^18, rows otherwise; kept through later renumberings.  (0) */
+                                     n >= 196,608, rows otherwise; kept through later renumberings.  (0) */
     int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
                                      20 bytes per entry plus 202 bytes per point (rows are padded) plus 8 bytes
                                      per pair of a 6144-row and a 2048-column tile (n^2 / (3 x 2^19)).  0 disables

@@ -162,14 +162,15 @@ __global__ __launch_bounds__(256) void ft_stats_k(const float *__restrict__ uval
     }
 }
 
-// mode: 0 = tiles if the far part is at least half of the entries and there are at least 2^18 points
-// (below that all of Y stays in the second-level cache and the row-by-row kernel is as fast; a far part
+// mode: 0 = tiles if the far part is at least half of the entries and there are at least FT_MIN_POINTS points
+// (measured on four 50-dimensional blobs: 0.23 against 0.30 ms per iteration row by row at 128,000 points, 0.57
+// against 0.47 at 256,000: below the limit all of Y stays in the second-level cache; a far part
 // that is a minority -- clusters a little wider than the band -- is quicker row by row beside the tree
 // build: measured on the 400,000-point, 200-cluster workload), 1 = never, 2 = always
 __global__ void ft_decide_k(const int32_t *__restrict__ rp_far, int n, int64_t nnz, int mode, uint32_t *meta)
 {
     const int64_t far_total = (int64_t)rp_far[n] - rp_far[0];
-    meta[0] = far_total > 0 && (mode == 2 || (mode == 0 && far_total * 2 >= nnz && n >= (1 << 18))) ? 1u : 0u;
+    meta[0] = far_total > 0 && (mode == 2 || (mode == 0 && far_total * 2 >= nnz && n >= FT_MIN_POINTS)) ? 1u : 0u;
 }
 
 __global__ __launch_bounds__(256) void ft_zero_k(uint32_t *__restrict__ cnt, int64_t tiles, const uint32_t *meta)

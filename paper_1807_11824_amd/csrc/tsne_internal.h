@@ -47,6 +47,7 @@ constexpr int ATTRACT_SLACK = 64;        // entries readable past the end of col
 constexpr int ATTRACT_MAX_PARTS = 16384; // most resident workgroups of the attraction kernel
 constexpr int FT_ROWS = 6144;            // rows of a tile of the bucketed copy of the far part
 constexpr int FT_COLS = 2048;            // columns of such a tile
+constexpr int FT_MIN_POINTS = 3 << 16;   // fewest points for which the tiles are chosen automatically
 constexpr int64_t FT_MAX_TILES = (int64_t)1 << 27;
 
 struct tsne_ctx {

@@ -264,7 +264,7 @@ def _random_csr(n, k, seed):
 
 @pytest.mark.parametrize("n,k", [(20_000, 12), (4097, 12), (270_000, 5)])
 def test_far_part_from_tiles(n, k):
-    """P without structure: nearly every entry is far from the diagonal.  The bucketed copy (tiles of 4096 rows
+    """P without structure: nearly every entry is far from the diagonal.  The bucketed copy (tiles of 6144 rows
     x 2048 columns, fixed-point row sums) against the oracle, against the row-by-row kernel, chosen automatically,
     and the same bits on every run and stream layout."""
     rp, col, val = _random_csr(n, k, seed=n)
@@ -276,8 +276,8 @@ def test_far_part_from_tiles(n, k):
     assert st == 0 and rel_l2(A_tiles, Ao) <= 1e-6
     assert rel_l2(A_tiles, A_rows) <= 1e-6
     for params in (dict(far_tiles=2), dict(far_tiles=0), dict(far_tiles=2, overlap=0), dict(far_tiles=0, overlap=0)):
-        if params.get("far_tiles") == 0 and n < (1 << 18):
-            continue        # the automatic choice stays with the row-by-row kernel below 2^18 points
+        if params.get("far_tiles") == 0 and n < 196_608:
+            continue        # the automatic choice stays with the row-by-row kernel below 196,608 points
         A, _, _, st = _gpu_forces(Y, rp, col, val, max_nnz=len(col), graph_order_iters=4, **params)
         assert st == 0 and np.array_equal(A, A_tiles), params
 
