@@ -94,7 +94,7 @@ typedef struct {
                                      n >= 196,608, rows otherwise; kept through later renumberings.  (0) */
     int64_t max_nnz;              /* capacity for the private, renumbered copy of P: the workspace grows by
                                      20 bytes per entry plus 202 bytes per point (rows are padded) plus 8 bytes
-                                     per pair of a 6144-row and a 2048-column tile (n^2 / (3 x 2^19)).  0 disables
+                                     per pair of a 6144-row and a 2048-column tile (n^2 / (3 x 2^22)).  0 disables
                                      renumbering; P is then only borrowed and a stop/resume is bitwise
                                      reproducible.  With renumbering a row of the attractive sum is added up
                                      as (entries near the diagonal) + (the others): deterministic, equal to
