@@ -454,17 +454,28 @@ __global__ __launch_bounds__(256, 2) void knn_tile_mfma(const uint4 *__restrict_
     append_queue(qrow, qkey, fill, cnt, cand, cap);
 }
 
+// 16-byte piece c of an unpadded 128-byte LDS row r sits at position c ^ swz(r): see knn_tile_resident below
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ ((row & 1) << 2)) & 7; }
+
 // ---- the first sweep over long rows: half precision, 256 x 256 tiles
 // One product per coordinate makes the operands, not the matrix work, the cost: with 256 x 128 tiles two workgroups
 // per compute unit pull 10 TB/s out of the second-level cache.  A 256 x 256 tile needs a third less per product.  One
 // workgroup of eight waves per compute unit (a wave owns 128 x 64 outputs, eight 32 x 32 blocks), and the overlap that
-// several workgroups would give comes from the kernel itself: the slabs alternate between two LDS buffers, the slab
-// after the next is in flight to registers while the next one is being stored and the current one multiplied, and
-// there is a single barrier per slab.  Rows as split_high leaves them (128 bytes per 64 columns); dot_scale undoes
-// their scaling.
+// several workgroups would give comes from the kernel itself.  The slabs of 64 columns alternate between two LDS
+// buffers, which the loads fill directly (global_load_lds: no registers hold a slab in flight, and no LDS store
+// instructions are issued); a wave's instruction brings eight rows of 128 bytes, unpadded, every lane taking the piece
+// that the swizzle puts at its position.  There is one barrier per slab, in front of its last step: by then every wave
+// has read all it needs of the current buffer, so the loads of the slab after the next go out right behind the barrier
+// and have a whole slab's time to arrive, and the first fragments of the next slab are requested while the last
+// products of this one run.  Within a step the next step's six fragment reads are placed by hand, one behind each
+// of the first six products.  Rows as split_high leaves them (128 bytes per 64 columns); dot_scale undoes their scaling.
 constexpr int HT = 256;                                 // tile: query rows = database rows
 constexpr int HALF_THREADS = 512;
-constexpr size_t HALF_TILE_LDS = 2 * (size_t)(2 * HT) * LDS_ROW;
+constexpr int HALF_BUF = 2 * HT * 128;                  // one buffer: the tile's query rows, then its database rows
+constexpr size_t HALF_TILE_LDS = 2 * (size_t)HALF_BUF;
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_void;
 
 __global__ __launch_bounds__(HALF_THREADS, 1) void knn_tile_half(const uint4 *__restrict__ Xh, int dph, int q0, int qend, int j0,
                                                                  int jend, const float *__restrict__ norms,
@@ -487,7 +498,6 @@ __global__ __launch_bounds__(HALF_THREADS, 1) void knn_tile_half(const uint4 *__
     if (qt >= nqt || local / njt >= per) return;       // (the grid is 8 per njt workgroups; the same for all lanes)
     const int qa = q0 + qt * HT, ja = j0 + jt * HT;
     const int row16 = dph / 8;              // 16-byte pieces per row
-    const int piece = tid & 7, lrow = tid >> 3;        // 64 rows a trip
     const int r32 = lane & 31, h = lane >> 5;
     const int nslab = dph / (2 * SLAB);
     floatx16 acc[4][2];
@@ -497,69 +507,83 @@ __global__ __launch_bounds__(HALF_THREADS, 1) void knn_tile_half(const uint4 *__
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-    // rows this thread moves (past the end: zeros)
-    const uint4 *pa_g[4], *pb_g[4];
-    bool aok[4], bok[4];
+    // What this lane loads: wave w brings rows 32 w .. 32 w + 31 of both operands, eight rows an instruction; the
+    // lane's row is 8 it + lane / 8 of them and its LDS position lane % 8, so it reads piece (lane % 8) ^ swz(row).
+    // A row past the end is read as the last row: its products are finite and the epilogue accepts nothing for it.
+    const uint4 *ga[4], *gb[4];
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        const int ra_ = qa + lrow + 64 * it, rb_ = ja + lrow + 64 * it;
-        aok[it] = ra_ < qend;
-        bok[it] = rb_ < jend;
-        pa_g[it] = Xh + (size_t)(aok[it] ? ra_ : 0) * row16 + piece;
-        pb_g[it] = Xh + (size_t)(bok[it] ? rb_ : 0) * row16 + piece;
+        const int lr = 32 * w + 8 * it + (lane >> 3), c = (lane & 7) ^ swz(lr);
+        ga[it] = Xh + (size_t)min(qa + lr, qend - 1) * row16 + c;
+        gb[it] = Xh + (size_t)min(ja + lr, jend - 1) * row16 + c;
     }
-    uint4 ra[4], rb[4];
-    auto load = [&](int slab) {
+#define HALF_LOAD(slab_, buf_)                                                             \
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {                                     \
+        unsigned char *d_ = hsm + (size_t)(buf_) * HALF_BUF + (32 * w + 8 * it) * 128;     \
+        __builtin_amdgcn_global_load_lds((glb_void *)(ga[it] + (size_t)(slab_) * 8), (lds_void *)d_, 16, 0, 0);              \
+        __builtin_amdgcn_global_load_lds((glb_void *)(gb[it] + (size_t)(slab_) * 8), (lds_void *)(d_ + HT * 128), 16, 0, 0); \
+    }
+    // fragments: lane (r32, h) of block a reads piece 2 ks + h of row 32 a + r32 (swz depends on r32 alone)
+    const int sw = swz(r32);
+    const int fa_off = (wm * 128 + r32) * 128, fb_off = (HT + wn * 64 + r32) * 128;
+    int pk[4];
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            ra[it] = aok[it] ? pa_g[it][(size_t)slab * 8] : make_uint4(0u, 0u, 0u, 0u);
-            rb[it] = bok[it] ? pb_g[it][(size_t)slab * 8] : make_uint4(0u, 0u, 0u, 0u);
-        }
-    };
-    auto store = [&](int buf) {
-        unsigned char *As = hsm + (size_t)buf * (2 * HT) * LDS_ROW, *Bs = As + (size_t)HT * LDS_ROW;
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            *reinterpret_cast<uint4 *>(As + (lrow + 64 * it) * LDS_ROW + piece * 16) = ra[it];
-            *reinterpret_cast<uint4 *>(Bs + (lrow + 64 * it) * LDS_ROW + piece * 16) = rb[it];
-        }
-    };
-    load(0);
-    store(0);
+    for (int ks = 0; ks < 4; ++ks) pk[ks] = ((2 * ks + h) ^ sw) * 16;
+    halfx8 fa[2][4], fb[2][2];
+#define HALF_FRAGS(buf_, ks_, set_)                                                        \
+    {                                                                                      \
+        const unsigned char *b_ = hsm + (size_t)(buf_) * HALF_BUF + pk[ks_];               \
+        _Pragma("unroll") for (int a = 0; a < 4; ++a)                                      \
+            fa[set_][a] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(b_ + fa_off + a * 32 * 128)); \
+        _Pragma("unroll") for (int b = 0; b < 2; ++b)                                      \
+            fb[set_][b] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(b_ + fb_off + b * 32 * 128)); \
+    }
+#define HALF_PRODUCTS(set_)                                                                \
+    _Pragma("unroll") for (int a = 0; a < 4; ++a)                                          \
+        _Pragma("unroll") for (int b = 0; b < 2; ++b)                                      \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[set_][a], fb[set_][b], acc[a][b], 0, 0, 0);
+#define HALF_INTERLEAVE()                                                                  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         /* one matrix product */     \
+    _Pragma("unroll") for (int i_ = 0; i_ < 6; ++i_) {                                     \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     /* one LDS read */           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                 \
+    }                                                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    HALF_LOAD(0, 0)
+    if (nslab > 1) HALF_LOAD(1, 1)
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");     // (the first slab; all of them if there is only one)
+    if (nslab == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (nslab > 1) load(1);
+    HALF_FRAGS(0, 0, 0)
     for (int slab = 0; slab < nslab; ++slab) {
-        const unsigned char *As = hsm + (size_t)(slab & 1) * (2 * HT) * LDS_ROW, *Bs = As + (size_t)HT * LDS_ROW;
-        const unsigned char *pa = As + (wm * 128 + r32) * LDS_ROW + h * 16;
-        const unsigned char *pb = Bs + (wn * 64 + r32) * LDS_ROW + h * 16;
-        // the fragments of step ks + 1 are requested before the products of step ks are issued
-        halfx8 fa[2][4], fb[2][2];
-        auto frags = [&](int ks, int set) {
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                fa[set][a] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDS_ROW + ks * 32));
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-                fb[set][b] = __builtin_bit_cast(halfx8, *reinterpret_cast<const uint4 *>(pb + b * 32 * LDS_ROW + ks * 32));
-        };
-        frags(0, 0);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < 3) frags(ks + 1, (ks + 1) & 1);
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][a], fb[ks & 1][b], acc[a][b], 0, 0, 0);
-            // half-way through: the next slab (requested a whole slab ago) goes to the other buffer, and the one
-            // after it is requested
-            if (ks == 1) {
-                if (slab + 1 < nslab) store((slab + 1) & 1);
-                if (slab + 2 < nslab) load(slab + 2);
-            }
-        }
-        __syncthreads();        // the other buffer is complete; everybody is done reading this one
+        const int cur = slab & 1, oth = cur ^ 1;
+        HALF_FRAGS(cur, 1, 1)
+        HALF_PRODUCTS(0)
+        HALF_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
+        HALF_FRAGS(cur, 2, 0)
+        HALF_PRODUCTS(1)
+        HALF_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
+        HALF_FRAGS(cur, 3, 1)
+        HALF_PRODUCTS(0)
+        HALF_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's part of the next slab has arrived
+        __syncthreads();        // the other buffer is complete; nobody reads this one any more
+        __builtin_amdgcn_sched_barrier(0);
+        if (slab + 2 < nslab) HALF_LOAD(slab + 2, cur)
+        // (past the last slab these fragments are read from a buffer nobody fills any more, and never used)
+        HALF_FRAGS(oth, 0, 0)
+        HALF_PRODUCTS(1)
+        HALF_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
     }
+    __syncthreads();            // (the epilogue reuses the buffers)
+#undef HALF_LOAD
+#undef HALF_FRAGS
+#undef HALF_PRODUCTS
+#undef HALF_INTERLEAVE
     // epilogue, as in knn_tile_mfma: lane holds column (lane % 32) and rows 8 (i / 4) + 4 (lane / 32) + i % 4 of each
     // block; norms and cut-offs of the tile's queries staged in LDS, accepted pairs queued per wave
     float *qn = reinterpret_cast<float *>(hsm), *qd = qn + HT;
@@ -627,7 +651,6 @@ constexpr size_t resident_lds_bytes(int ns)
     return 2 * (size_t)ns * RT * SLAB_ROW + 3 * RQ * 4;
 }
 
-__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ ((row & 1) << 2)) & 7; }
 
 // A workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
 // store of the wave to complete, which would put the appends' trip to memory on the critical path.
