@@ -1997,6 +1997,10 @@ int tsne_build_P(const float *d_X, int32_t n, int32_t d, float perplexity, int32
                                        0, s, (const uint4 *)L.xs, dp, q0, qend, j0, jend, L.norms, L.tau, L.cnt, L.cand, cap, cc,
                                        (const uint4 *)L.xs, L.norms, 1, (const int *)nullptr, (const int *)nullptr, 0,
                                        (const int *)nullptr, (const int *)nullptr, (const int *)nullptr, 0);
+                // (the half-precision sweep, too, compacts every second launch only: a row that is not listed has room
+                // for what two launches can append, and between the sweeps' 503-us launches the two small kernels of a
+                // pass are 8 % of the time)
+                if (high_first && !force && step >= DBC && launch % COMPACT_EVERY != COMPACT_EVERY - 1) continue;
                 hipLaunchKernelGGL(knn_compact_list, dim3((rows + 255) / 256), dim3(256), 0, s, L.tau, L.cnt, cap, kp, rows, force,
                                    L.clist, cc);
             }
