@@ -146,7 +146,12 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
     pts[lane] = me;
     const float bx0 = wave_min(x), bx1 = wave_max(x), by0 = wave_min(y), by1 = wave_max(y);
     const float W = root->z;
-    float fx = 0.f, fy = 0.f, z = -1.0f;
+    // z: the terms of one batch in single precision, moved to the double zsum after every batch (a point's sum over
+    // tens of thousands of nearly equal terms -- theta = 0, or Y0 where every q is close to 1 -- otherwise picks up
+    // the same rounding error at every addition: 1e-4 of Z at 20,000 points).  Starts at -1: the point meets itself
+    // among the members of its own leaf.
+    float fx = 0.f, fy = 0.f, z = 0.f;
+    double zsum = -1.0;
     int sp = 1, np = 0, icc = 0, icp = 0;   // wave-uniform; kept in scalar registers via readfirstlane
     bool overflow = false;
     uint32_t rounds = 0;
@@ -221,10 +226,10 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
         const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
         mtot = __builtin_amdgcn_readfirstlane(mtot);
         const int nacc = __popcll(macc);
-        if (icc + nacc > WALK_CLIST) { drain_cells(clist, icc, x, y, fx, fy, z); icc = 0; }
+        if (icc + nacc > WALK_CLIST) { drain_cells(clist, icc, x, y, fx, fy, z); icc = 0; zsum += (double)z; z = 0.f; }
         if (acc) clist[icc + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
         icc = __builtin_amdgcn_readfirstlane(icc + nacc);
-        if (icp + mtot > WALK_PLIST) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; }
+        if (icp + mtot > WALK_PLIST) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; zsum += (double)z; z = 0.f; }
         if (ofast) {
             float2 q[WALK_FAST_LEAF];
 #pragma unroll
@@ -250,7 +255,7 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
             const int boff = wave_excl_scan(big ? (int)cnt : 0, &tbig);
             tbig = __builtin_amdgcn_readfirstlane(tbig);
             for (int base = 0; base < tbig;) {
-                if (WALK_PLIST - icp < WAVE) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; }
+                if (WALK_PLIST - icp < WAVE) { drain_points(plist, icp, x, y, fx, fy, z); icp = 0; zsum += (double)z; z = 0.f; }
                 const int take = min(tbig - base, WALK_PLIST - icp);
                 for (int k = 0; k < take; k += WAVE) {
                     const int t = base + k + lane;
@@ -288,12 +293,14 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
     }
     if (overflow) {
         if (lane == 0) atomicOr(status, TSNE_STATUS_WALK_OVERFLOW);
-        fx = fy = 0.f; z = 0.f; icc = icp = 0;
+        fx = fy = 0.f; z = 0.f; zsum = 0.0; icc = icp = 0;
     }
     drain_cells(clist, icc, x, y, fx, fy, z);
+    zsum += (double)z; z = 0.f;
     drain_points(plist, icp, x, y, fx, fy, z);
+    zsum += (double)z;
     if (valid) R[min(perm[p], (uint32_t)n - 1u)] = make_float2(fx, fy);
-    double zd = wave_sum(valid ? (double)z : 0.0);
+    double zd = wave_sum(valid ? zsum : 0.0);
     if (lane == 0) zpart[g] = zd;
 }
 

@@ -70,6 +70,23 @@ def test_theta0_is_exact(cfg1):
     assert rel_l2(R, ex["R"]) <= TOL and rel_l2(A, ex["A"]) <= TOL
 
 
+def test_z_of_many_nearly_equal_terms():
+    """theta = 0 at Y0: every point adds 20,010 terms that are all close to 1.  Added up in single precision one after
+    the other they pick up the same rounding error each time (1e-4 of Z); the walk moves every batch's sum to a
+    double.  Z against the sum over all pairs in double precision."""
+    n = 20_011
+    Y = synth.y0(n, seed=0)
+    rp = np.zeros(n + 1, np.int32)
+    A, R, Z, st = _gpu_forces(Y, rp, np.zeros(0, np.int32), np.zeros(0, np.float32), theta=0.0, leaf_cap=8)
+    Yd = Y.astype(np.float64)
+    want = 0.0
+    for a in range(0, n, 1000):
+        d = Yd[a:a + 1000, None, :] - Yd[None, :, :]
+        want += (1.0 / (1.0 + (d * d).sum(-1))).sum() - min(1000, n - a)     # (without the point itself)
+    assert st == 0
+    assert abs(Z - want) / want <= 1e-6
+
+
 @pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 4097])
 def test_small_and_ragged_sizes(n):
     rng = np.random.default_rng(n)
