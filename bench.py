@@ -94,7 +94,7 @@ def cpu_baseline(Y0, P_host, bits, X=None, cfg=None, P_gpu_seconds=None):
     return out
 
 
-def sweep(dev, overlap, sizes, n_iter, reorder_every, approx_tau=0):
+def sweep(dev, overlap, sizes, n_iter, reorder_every, approx_tau=0, sweep_recall=False):
     """Stand-in for the paper's scaling experiment (Sec. IV-B: simulated 50-d data in four clusters): time of a
     whole run of n_iter iterations (exaggeration 12 for the first quarter), the phases of an iteration averaged
     over the run, and the time of tsne_build_P, as N grows.  Perplexity 30, k = 90, theta = 0.5.  With approx_tau > 0
@@ -108,12 +108,21 @@ def sweep(dev, overlap, sizes, n_iter, reorder_every, approx_tau=0):
         del X
         torch.cuda.synchronize()
         t0 = time.time()
+        recall = None
         if approx_tau > 0 and n > 90 * 8:
-            P = build_P_approx(Xd, 30.0, 90, min(approx_tau, int(round(n ** 0.5))))
+            P = build_P_approx(Xd, 30.0, 90, min(approx_tau, int(round(n ** 0.5))), want_knn=sweep_recall)
         else:
             P = build_P(Xd, 30.0, 90)
         torch.cuda.synchronize()
         t_build = time.time() - t0
+        if sweep_recall and approx_tau > 0 and n > 90 * 8:
+            # (untimed) recall of the approximate lists against the exact ones on 20,000 sampled rows
+            ex = build_P(Xd, 30.0, 90, want_knn=True)
+            rows = torch.randperm(n, device=dev, generator=torch.Generator(device=dev).manual_seed(0))[:20000]
+            hit = (P["knn_idx"][rows].long()[:, :, None] == ex["knn_idx"][rows].long()[:, None, :]).any(-1)
+            recall = float(hit.float().mean().item())
+            del ex, hit
+            P["knn_idx"] = P["knn_d2"] = None
         del Xd
         Yd = torch.from_numpy(synth.y0(n)).to(dev)
         ts = Tsne(n, overlap=overlap, max_nnz=P["nnz"], reorder_every=reorder_every, exaggeration_iters=n_iter // 4)
@@ -133,7 +142,8 @@ def sweep(dev, overlap, sizes, n_iter, reorder_every, approx_tau=0):
                           "n_iter": n_iter, "reorder_every": reorder_every, "approx_tau": approx_tau, "run_s": round(dt, 4),
                           "ms_per_step": dt / n_iter * 1e3, "iterations_per_s": n_iter / dt,
                           "phases_ms": {k[:-3]: round(v, 4) for k, v in tm.items() if k.endswith("_ms")},
-                          "build_P_s": round(t_build, 4), "set_P_s": round(t_setp, 4), "status": st}), flush=True)
+                          "build_P_s": round(t_build, 4), "set_P_s": round(t_setp, 4), "status": st,
+                          **({"recall_at_k": recall} if recall is not None else {})}), flush=True)
         del P, Yd
 
 
@@ -189,6 +199,8 @@ def main():
     ap.add_argument("--reorder-every", type=int, default=0, help="--sweep only: tsne_params.reorder_every")
     ap.add_argument("--sweep-approx-tau", type=int, default=0,
                     help="--sweep only: build P with tsne_build_P_approx, this many lists probed (0 = exact)")
+    ap.add_argument("--sweep-recall", action="store_true",
+                    help="--sweep with --sweep-approx-tau: also build the exact lists (untimed) and report recall at k")
     ap.add_argument("--approx-tau", type=int, default=4,
                     help="also time tsne_build_P_approx (inverted-file neighbour search, sqrt(N) lists, this many "
                          "probed per query) on the same X and report its recall against the exact lists; 0 = skip")
@@ -205,7 +217,7 @@ def main():
     dev = torch.device("cuda:0")
     if args.sweep:
         sweep(dev, args.overlap, [int(v) for v in args.sweep_n.split(",")], args.sweep_iters, args.reorder_every,
-              args.sweep_approx_tau)
+              args.sweep_approx_tau, args.sweep_recall)
         return
     cache = args.P_cache + ".npz" if args.P_cache else ""
     approx = None
