@@ -168,15 +168,18 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev, bool cached = 
         if ((e = hipStreamWaitEvent(c->stream2, evt, 0)) != hipSuccess) return fail_hip(c, e, "stream wait");
         return TSNE_OK;
     };
+    // The bucketed far part needs nothing but Y and the root square: with two streams it starts beside the tree build
+    // (which hides behind it), not behind the walk.
+    const bool tiles_early = two && c->ft_active && c->p.n > SMALL_SORT_MAX;
     auto farpart = [&]() -> int {
         if (ev) (void)hipEventRecord(ev[6], sa);
-        if ((e = launch_attract_far(c, sa)) != hipSuccess) return fail_hip(c, e, "attract (far part)");
+        if ((e = launch_attract_far(c, sa, tiles_early)) != hipSuccess) return fail_hip(c, e, "attract (far part)");
         if (ev) (void)hipEventRecord(ev[7], sa);
         return TSNE_OK;
     };
     auto mainpart = [&]() -> int {
         if (ev) (void)hipEventRecord(ev[3], sa);
-        if ((e = launch_attract_main(c, sa)) != hipSuccess) return fail_hip(c, e, "attract");
+        if ((e = launch_attract_main(c, sa, !tiles_early)) != hipSuccess) return fail_hip(c, e, "attract");
         if (ev) (void)hipEventRecord(ev[4], sa);
         if (two && (e = hipEventRecord(c->ev_join, c->stream2)) != hipSuccess) return fail_hip(c, e, "event record");
         return TSNE_OK;
@@ -185,6 +188,8 @@ int enqueue_forces(tsne_ctx *c, const float *d_Y, hipEvent_t *ev, bool cached = 
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     // (inside tsne_run the previous update has already left Y in slot order and its bounding box)
     if (!cached && (e = launch_gather_bbox(c, d_Y, c->stream)) != hipSuccess) return fail_hip(c, e, "gather + bbox");
+    c->root_fresh = 0;
+    if (tiles_early && (e = launch_tree_root(c, c->stream)) != hipSuccess) return fail_hip(c, e, "root square");
     if (two && ((rc = fork(c->ev_fork)) != TSNE_OK || (rc = farpart()) != TSNE_OK)) return rc;
     if ((e = launch_tree_sort(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree sort");
     if ((e = launch_tree_cells(c, c->stream)) != hipSuccess) return fail_hip(c, e, "tree cells");

@@ -445,9 +445,11 @@ static int attract_shares(const tsne_ctx *c)
     return max(1, min(min(per_cu * c->num_cu, ATTRACT_MAX_PARTS / 2), tiles));
 }
 
-// The far part from its tiles.  A small far part is summed row by row beside the tree build; the
-// tile kernels are heavy and are launched where the walk starts.  Their 144 KB of LDS per workgroup
-// does not fit beside the walk's resident waves, so they take over the chip as the walk drains.
+// The far part from its tiles.  They need Y and the root square only: with two streams they are launched
+// beside the tree build (whose kernels squeeze in as their workgroups end: 144 KB of LDS per workgroup
+// leave no room on a compute unit for anything else), so that the step is the far part plus the walk and
+// not tree build plus walk plus far part; with one stream, or when root, keys and order come out of a
+// single launch, behind the walk.
 static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
 {
     const int n = c->p.n;
@@ -462,7 +464,7 @@ static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
 
 // The far part of the renumbered P when it is summed row by row (also shares the rows of the
 // streaming part out, once per P).
-hipError_t launch_attract_far(tsne_ctx *c, hipStream_t s)
+hipError_t launch_attract_far(tsne_ctx *c, hipStream_t s, bool tiles)
 {
     const int n = c->p.n;
     if (!(c->reorder_on && !c->identity)) return hipSuccess;
@@ -471,17 +473,18 @@ hipError_t launch_attract_far(tsne_ctx *c, hipStream_t s)
         hipLaunchKernelGGL(attract_partition, dim3((k + 256) / 256), dim3(256), 0, s, c->rp_near, n, k, c->arow);
         c->arow_valid = 1;
     }
+    if (c->ft_active && tiles) launch_far_tiles(c, s);
     if (!c->ft_active)
         hipLaunchKernelGGL(attract_far, dim3((unsigned)min((n + 15) / 16, FAR_BLOCKS)), dim3(256), 0, s, c->rp_far, c->col_far,
                            c->val_s, c->Yi, n, c->far_rows, c->far_count, c->Afar);
     return hipGetLastError();
 }
 
-hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s)
+hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s, bool tiles)
 {
     const int n = c->p.n;
     if (c->reorder_on && !c->identity) {
-        if (c->ft_active) launch_far_tiles(c, s);
+        if (c->ft_active && tiles) launch_far_tiles(c, s);
         hipLaunchKernelGGL(attract_near, dim3(attract_shares(c)), dim3(AN_THREADS), 0, s, c->rp_near,
                            (const uint4 *)c->col_near, (const float4 *)c->val_s, c->Yi, n, c->arow, c->rp_far, c->Afar, c->A);
     } else {

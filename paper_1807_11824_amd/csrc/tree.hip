@@ -1120,6 +1120,16 @@ hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s)
     return hipGetLastError();
 }
 
+// Step 1 second half on its own, for a step whose attraction wants the root square before the sort is enqueued.
+hipError_t launch_tree_root(tsne_ctx *c, hipStream_t s)
+{
+    if (c->p.n <= SMALL_SORT_MAX) return hipSuccess;      // (there the root comes out of the one launch that also sorts)
+    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(c->bbox_nparts > 1024 ? 1024 : 256), 0, s, c->bbox_part, c->bbox_nparts,
+                       c->p.morton_bits, c->root, c->status);
+    c->root_fresh = 1;
+    return hipGetLastError();
+}
+
 // Step 1 second half, step 2a and step 4: root square, keys, spatial sort.
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
 {
@@ -1133,8 +1143,10 @@ hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s)
         c->sorted_buf = 0;
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(bbox_final, dim3(1), dim3(c->bbox_nparts > 1024 ? 1024 : 256), 0, s, c->bbox_part, c->bbox_nparts, B,
-                       c->root, c->status);
+    if (!c->root_fresh)
+        hipLaunchKernelGGL(bbox_final, dim3(1), dim3(c->bbox_nparts > 1024 ? 1024 : 256), 0, s, c->bbox_part, c->bbox_nparts, B,
+                           c->root, c->status);
+    c->root_fresh = 0;
     const int items = c->sort_items, nblk = (n + SORT_THREADS * items - 1) / (SORT_THREADS * items);
     const int width0 = 2 * B < RADIX_BITS ? 2 * B : RADIX_BITS;
     if (items == 10)

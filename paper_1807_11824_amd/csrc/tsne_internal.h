@@ -93,6 +93,7 @@ struct tsne_ctx {
     // workspace carve-up
     float4 *bbox_part;   // (min, max) pairs of the bounding box, one per workgroup of the kernel that made them
     int bbox_nparts;     // how many pairs are valid
+    int root_fresh;      // the root square of this step is already in place (launch_tree_root)
     int yi_fresh;        // Yi and bbox_part already hold the embedding of the next step (left by update_k)
     float4 *root;        // x0, y0, W, S
     uint32_t *status;    // device status word
@@ -153,11 +154,13 @@ int ivf_search_tiles(const float *X, int n, int d, int k, int nlist, int tau, co
 int ivf_knn_device(const float *X, int n, int d, const float *C, int nlist, int tau, int k, int32_t *knn_idx,
                    double *knn_d2, void *ws, size_t ws_bytes, hipStream_t s);
 hipError_t launch_gather_bbox(tsne_ctx *c, const float *d_Y, hipStream_t s);
+hipError_t launch_tree_root(tsne_ctx *c, hipStream_t s);
 hipError_t launch_tree_sort(tsne_ctx *c, hipStream_t s);
 hipError_t launch_tree_cells(tsne_ctx *c, hipStream_t s);
 hipError_t launch_walk(tsne_ctx *c, hipStream_t s);
-hipError_t launch_attract_far(tsne_ctx *c, hipStream_t s);    // the far part of the renumbered P (no-op otherwise)
-hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s);
+// the far part of the renumbered P (no-op otherwise); tiles: the bucketed copy is summed here rather than in launch_attract_main
+hipError_t launch_attract_far(tsne_ctx *c, hipStream_t s, bool tiles);
+hipError_t launch_attract_main(tsne_ctx *c, hipStream_t s, bool tiles);
 hipError_t launch_update(tsne_ctx *c, float *d_Y, float alpha, float momentum, int keep, int write_user,
                          hipStream_t s);
 hipError_t launch_reorder(tsne_ctx *c, hipStream_t s, int tiles_mode);   // tiles_mode: 0 decide, 1 rows, 2 tiles
