@@ -364,6 +364,7 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
     c->nnz = nnz;
     c->arow_valid = 0;
     c->have_P = 1;
+    c->ft_far_entries = 0;
     if (c->reorder_on && c->p.graph_order_iters > 0 && nnz > 0) {
         hipError_t e;
         if ((e = launch_graph_order(c, c->stream)) != hipSuccess ||
@@ -373,11 +374,12 @@ int tsne_set_P(tsne_ctx *c, const int32_t *d_row_ptr, const int32_t *d_col, cons
         // later renumberings keep the choice
         c->ft_active = 0;
         if (c->ft_tiles > 0) {
-            uint32_t in_use = 0u;
-            if ((e = hipMemcpyAsync(&in_use, c->ft_meta, sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream)) != hipSuccess ||
+            uint32_t meta_h[5] = {0u, 0u, 0u, 0u, 0u};
+            if ((e = hipMemcpyAsync(meta_h, c->ft_meta, sizeof(meta_h), hipMemcpyDeviceToHost, c->stream)) != hipSuccess ||
                 (e = hipStreamSynchronize(c->stream)) != hipSuccess)
                 return fail_hip(c, e, "graph order");
-            c->ft_active = in_use ? 1 : 0;
+            c->ft_active = meta_h[0] ? 1 : 0;
+            c->ft_far_entries = (int64_t)meta_h[4];
         }
     } else {
         c->ft_active = c->ft_tiles > 0 && c->p.far_tiles == 2;

@@ -455,7 +455,12 @@ static void launch_far_tiles(tsne_ctx *c, hipStream_t s)
     const int n = c->p.n;
     // enough workgroups to fill the chip: a row tile's entries are shared out when there are few row tiles
     const int nrt = (n + FT_ROWS - 1) / FT_ROWS;
-    const int split = max(1, min(64, (8 * c->num_cu + nrt - 1) / nrt));
+    // ... but no more than leave a workgroup some 64k entries: each one clears, fills and adds up to 6144 rows' sums
+    int split = max(1, min(64, (8 * c->num_cu + nrt - 1) / nrt));
+    if (c->ft_far_entries > 0) {
+        const int64_t by_size = c->ft_far_entries / ((int64_t)nrt * 65536);
+        if (by_size < split) split = by_size < 1 ? 1 : (int)by_size;
+    }
     hipLaunchKernelGGL(attract_far_tiled, dim3((unsigned)nrt, (unsigned)split), dim3(FT_THREADS), FT_LDS, s, c->ft_ptr,
                        c->ft_col, c->ft_row, c->ft_val, c->Yi, n, c->ft_nct, c->ft_meta, c->root, c->ft_acc);
     hipLaunchKernelGGL(ft_finish_k, dim3((unsigned)min((n + 255) / 256, 1024)), dim3(256), 0, s, c->far_rows, c->far_count, n,

@@ -171,6 +171,7 @@ __global__ void ft_decide_k(const int32_t *__restrict__ rp_far, int n, int64_t n
 {
     const int64_t far_total = (int64_t)rp_far[n] - rp_far[0];
     meta[0] = far_total > 0 && (mode == 2 || (mode == 0 && far_total * 2 >= nnz && n >= FT_MIN_POINTS)) ? 1u : 0u;
+    meta[4] = (uint32_t)far_total;      // for the host: how many workgroups the tile kernel is worth
 }
 
 __global__ __launch_bounds__(256) void ft_zero_k(uint32_t *__restrict__ cnt, int64_t tiles, const uint32_t *meta)

@@ -80,6 +80,7 @@ struct tsne_ctx {
     // the far part once more, bucketed by tiles of FT_ROWS x FT_COLS (row tile major); an entry is
     // (column, row within the row tile, value), in any order inside its tile
     int64_t ft_tiles;                 // number of tiles, 0 if the context has no room for them
+    int64_t ft_far_entries;           // entries of the far part when P was set (0: not known)
     int ft_nct;                       // column tiles per row
     uint32_t *ft_cnt;                 // per tile: entries not yet placed (0 outside ft_fill_k)
     int32_t *ft_ptr;                  // per tile: first entry (+ end)
@@ -88,7 +89,7 @@ struct tsne_ctx {
     float *ft_val;
     double *ft_acc;                   // row sums in fixed point (integer-valued doubles), (x, y) per row; zero between steps
     int ft_active;                    // the tiles are in use (decided at tsne_set_P, kept through later renumberings)
-    uint32_t *ft_meta;                // [0] tiles in use, [1] largest P value (bits), [2] longest far row
+    uint32_t *ft_meta;                // [0] tiles in use, [1] largest P value (bits), [2] longest far row, [4] entries of the far part
     float2 *Yi, *uYb[2], *gainsb[2];
     // workspace carve-up
     float4 *bbox_part;   // (min, max) pairs of the bounding box, one per workgroup of the kernel that made them
