@@ -43,6 +43,13 @@ def _rng_cases():
         # every point twice: with leaf_cap = 1 a chain of one-child cells runs to the deepest level under each pair
         # (about 4.7 cells per point, more than any other case here)
         "pairs_20000": np.repeat(r.random((10_000, 2)).astype(np.float32), 2, axis=0),
+        # many points in single squares of 1/2048 of the root's side (long runs of equal leading key bits, as the
+        # clusters of a late embedding give): copies of one point, a tight clump, twenty clumps of 150-400 points, a
+        # uniform background
+        "clumps_20011": np.vstack(
+            [np.full((3000, 2), 0.3)] + [[0.7, 0.2] + 1e-6 * r.random((2000, 2))]
+            + [r.random(2) + 2e-5 * r.random((int(m), 2)) for m in r.integers(150, 400, 20)]
+            + [r.random((20011, 2))])[:20011].astype(np.float32),
     }
 
 
