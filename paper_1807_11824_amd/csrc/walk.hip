@@ -38,6 +38,7 @@ constexpr int WALK_FAST_LEAF = 8;    // leaves up to this size are copied by the
 constexpr int WALK_CLIST = 96;       // accepted cells waiting for the drain (16 B each), >= 64
 constexpr int WALK_PLIST = 512;      // points of opened leaves waiting (8 B each), >= 64 * WALK_FAST_LEAF
 static_assert(WALK_CLIST >= WAVE && WALK_PLIST >= WAVE * WALK_FAST_LEAF, "one round must fit");
+static_assert(WAVE * WALK_FAST_LEAF < 65536, "two counts share one prefix sum");
 
 // side^2 < theta^2 * d2, with d2 = fma(dy, dy, dx*dx): one rounding per operation.
 __device__ __forceinline__ float dist2_rounded(float dx, float dy)
@@ -222,9 +223,13 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
         const bool desc = act && decided && !pass && !leaf;
         const bool ofast = open && cnt <= (uint32_t)WALK_FAST_LEAF;
         const uint64_t macc = __ballot(acc);
-        int mtot;
-        const int moff = wave_excl_scan(ofast ? (int)cnt : 0, &mtot);
-        mtot = __builtin_amdgcn_readfirstlane(mtot);
+        // one prefix sum for two lists: members of small opened leaves (low half: at most 64 * WALK_FAST_LEAF) and
+        // children of rejected inner cells (high half: at most 256)
+        const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
+        int both_tot;
+        const int both_off = wave_excl_scan((ofast ? (int)cnt : 0) | (nch << 16), &both_tot);
+        both_tot = __builtin_amdgcn_readfirstlane(both_tot);
+        const int moff = both_off & 0xFFFF, mtot = both_tot & 0xFFFF;
         const int nacc = __popcll(macc);
         if (icc + nacc > WALK_CLIST) { drain_cells(clist, icc, x, y, fx, fy, z); icc = 0; zsum += (double)z; z = 0.f; }
         if (acc) clist[icc + __popcll(macc & lanemask_lt())] = make_float4(cx, cy, (float)cnt, 0.f);
@@ -276,10 +281,7 @@ __device__ __forceinline__ void walk_group(const int g, uint32_t *stack, uint32_
             }
         }
         // children of rejected inner cells
-        const int nch = desc ? 1 + (cb.y != TSNE_NONE) + (cb.z != TSNE_NONE) + (cb.w != TSNE_NONE) : 0;
-        int ctot;
-        const int coff = wave_excl_scan(nch, &ctot);
-        ctot = __builtin_amdgcn_readfirstlane(ctot);
+        const int coff = both_off >> 16, ctot = both_tot >> 16;
         if (sp + ctot > WALK_STACK) { overflow = true; break; }   // unreachable for a well-formed tree
         if (desc) {
             int o = sp + coff;
