@@ -141,22 +141,33 @@ def morton(Y, bits=16):
     return root, keys
 
 
-def sort_keys(keys):
+def _tie(tie_rank, n):
+    """Rank that orders points of equal key (None: the original index)."""
+    if tie_rank is None:
+        return None, None
+    t = _i32(tie_rank)
+    if t.shape != (n,):
+        raise ValueError("tie_rank: one rank per point")
+    return t, _p(t, C.c_int32)
+
+
+def sort_keys(keys, tie_rank=None):
     keys = np.ascontiguousarray(keys, np.uint64)
     n = keys.shape[0]
     sk = np.empty(n, np.uint64)
     perm = np.empty(n, np.int32)
-    if _L().oracle_sort(_p(keys, C.c_uint64), n, _p(sk, C.c_uint64), _p(perm, C.c_int32)) != 0:
+    _keep, tp = _tie(tie_rank, n)
+    if _L().oracle_sort_ties(_p(keys, C.c_uint64), n, tp, _p(sk, C.c_uint64), _p(perm, C.c_int32)) != 0:
         raise MemoryError
     return sk, perm
 
 
-def tree(Y, bits=16, leaf_cap=8):
+def tree(Y, bits=16, leaf_cap=8, tie_rank=None):
     """Bounding box, keys, sort and the quad tree (pre-order) with summaries."""
     Y = _f32(Y)
     n = Y.shape[0]
     root, keys = morton(Y, bits)
-    sk, perm = sort_keys(keys)
+    sk, perm = sort_keys(keys, tie_rank)
     Ys = np.ascontiguousarray(Y[perm])
     cap = n * (bits + 1) + 1        # every level holds at most n cells
     depth = np.empty(cap, np.int32); lo = np.empty(cap, np.int32); hi = np.empty(cap, np.int32)
@@ -173,32 +184,34 @@ def tree(Y, bits=16, leaf_cap=8):
                 hi=hi[:m].copy(), leaf=leaf[:m].copy(), child=child[:m].copy(), com=com[:m].copy())
 
 
-def repulse_bh(Y, theta=0.5, leaf_cap=8, group=64, bits=16):
+def repulse_bh(Y, theta=0.5, leaf_cap=8, group=64, bits=16, tie_rank=None):
     Y = _f32(Y)
     n = Y.shape[0]
     R = np.empty((n, 2)); z = np.empty(n)
     Z = C.c_double(0)
     stats = np.zeros(3, np.int64)
-    m = _L().oracle_repulse_bh(_p(Y, C.c_float), n, C.c_float(theta), leaf_cap, group, bits,
-                               _p(R, C.c_double), _p(z, C.c_double), C.byref(Z),
-                               _p(stats, C.c_int64))
+    _keep, tp = _tie(tie_rank, n)
+    m = _L().oracle_repulse_bh_ties(_p(Y, C.c_float), n, C.c_float(theta), leaf_cap, group, bits, tp,
+                                    _p(R, C.c_double), _p(z, C.c_double), C.byref(Z),
+                                    _p(stats, C.c_int64))
     if m < 0:
         raise ValueError("oracle_repulse_bh: bad arguments")
     return dict(R=R, z=z, Z=Z.value, n_cells=m, accepted=int(stats[0]), opened=int(stats[1]),
                 point_terms=int(stats[2]))
 
 
-def grad_bh(Y, row_ptr, col, val, theta=0.5, leaf_cap=8, group=64, bits=16, alpha=1.0):
+def grad_bh(Y, row_ptr, col, val, theta=0.5, leaf_cap=8, group=64, bits=16, alpha=1.0, tie_rank=None):
     Y = _f32(Y)
     n = Y.shape[0]
     row_ptr, col, val = _i32(row_ptr), _i32(col), _f64(val)
     A = np.empty((n, 2)); R = np.empty((n, 2)); g = np.empty((n, 2))
     Z = C.c_double(0)
     stats = np.zeros(3, np.int64)
-    m = _L().oracle_grad_bh(_p(Y, C.c_float), n, _p(row_ptr, C.c_int32), _p(col, C.c_int32),
-                            _p(val, C.c_double), C.c_float(theta), leaf_cap, group, bits,
-                            C.c_double(alpha), _p(A, C.c_double), _p(R, C.c_double), C.byref(Z),
-                            _p(g, C.c_double), _p(stats, C.c_int64))
+    _keep, tp = _tie(tie_rank, n)
+    m = _L().oracle_grad_bh_ties(_p(Y, C.c_float), n, _p(row_ptr, C.c_int32), _p(col, C.c_int32),
+                                 _p(val, C.c_double), C.c_float(theta), leaf_cap, group, bits, tp,
+                                 C.c_double(alpha), _p(A, C.c_double), _p(R, C.c_double), C.byref(Z),
+                                 _p(g, C.c_double), _p(stats, C.c_int64))
     if m < 0:
         raise ValueError("oracle_grad_bh: bad arguments")
     return dict(A=A, R=R, Z=Z.value, grad=g, n_cells=m, accepted=int(stats[0]),

@@ -23,6 +23,8 @@
  *   Sec. III-C steps 1, 2, 4 (bounding box, quad tree, spatial sort) oracle_morton, oracle_sort, oracle_tree
  *   Sec. III-C step 3 (cell count and centre)                        inside oracle_tree
  *   Sec. III-C step 5, Eq. (14), (15), Z estimate                    oracle_grad_bh
+ *   (the ..._ties forms take a rank that orders points of equal key in step 4, which the paper
+ *    leaves open; without one it is the index)
  *   Alg. 1 line 8 (apply forces)                                     oracle_update
  *   Alg. 1 lines 3-9                                                 oracle_run
  *
@@ -332,26 +334,36 @@ int oracle_morton(const float *Y, int32_t n, int32_t bits, float *root, uint64_t
     return 0;
 }
 
-/* Sec. III-C step 4: order points along the curve; ties by original index. */
-typedef struct { uint64_t key; int32_t idx; } keyidx_t;
+/* Sec. III-C step 4: order points along the curve.  The paper leaves the    */
+/* order of points with equal keys open; the reading here is: by original    */
+/* index.  tie_rank (may be NULL) replaces the index in that role: a test    */
+/* that checks an implementation which orders equal keys otherwise passes    */
+/* the rank it found there, after checking that the order is a sorted one.   */
+typedef struct { uint64_t key; int32_t tie, idx; } keyidx_t;
 
 static int cmp_keyidx(const void *a, const void *b)
 {
     const keyidx_t *x = (const keyidx_t *)a, *y = (const keyidx_t *)b;
     if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    if (x->tie != y->tie) return x->tie < y->tie ? -1 : 1;
     if (x->idx != y->idx) return x->idx < y->idx ? -1 : 1;
+    return 0;
+}
+
+int oracle_sort_ties(const uint64_t *keys, int32_t n, const int32_t *tie_rank, uint64_t *sorted_keys, int32_t *perm)
+{
+    keyidx_t *t = (keyidx_t *)malloc((size_t)n * sizeof(keyidx_t));
+    if (!t) return -1;
+    for (int32_t i = 0; i < n; ++i) { t[i].key = keys[i]; t[i].tie = tie_rank ? tie_rank[i] : i; t[i].idx = i; }
+    qsort(t, (size_t)n, sizeof(keyidx_t), cmp_keyidx);
+    for (int32_t i = 0; i < n; ++i) { sorted_keys[i] = t[i].key; perm[i] = t[i].idx; }
+    free(t);
     return 0;
 }
 
 int oracle_sort(const uint64_t *keys, int32_t n, uint64_t *sorted_keys, int32_t *perm)
 {
-    keyidx_t *t = (keyidx_t *)malloc((size_t)n * sizeof(keyidx_t));
-    if (!t) return -1;
-    for (int32_t i = 0; i < n; ++i) { t[i].key = keys[i]; t[i].idx = i; }
-    qsort(t, (size_t)n, sizeof(keyidx_t), cmp_keyidx);
-    for (int32_t i = 0; i < n; ++i) { sorted_keys[i] = t[i].key; perm[i] = t[i].idx; }
-    free(t);
-    return 0;
+    return oracle_sort_ties(keys, n, NULL, sorted_keys, perm);
 }
 
 /* ------------------------------------------------------------------------ */
@@ -485,8 +497,9 @@ static void walk_rec(walk_t *K, int32_t id)
 
 /* Whole repulsive side at fixed Y (single precision in, widened).          */
 /* Returns the number of tree cells, or -1.                                 */
-int32_t oracle_repulse_bh(const float *Y, int32_t n, float theta, int32_t leaf_cap, int32_t group,
-                          int32_t bits, double *R, double *z, double *Zout, int64_t *stats)
+int32_t oracle_repulse_bh_ties(const float *Y, int32_t n, float theta, int32_t leaf_cap, int32_t group,
+                               int32_t bits, const int32_t *tie_rank, double *R, double *z, double *Zout,
+                               int64_t *stats)
 {
     if (!Y || n < 1 || group < 1 || !(theta >= 0.0f)) return -1;
     /* leaves are disjoint and non-empty (at most n of them); an inner cell holds more than
@@ -505,7 +518,7 @@ int32_t oracle_repulse_bh(const float *Y, int32_t n, float theta, int32_t leaf_c
     float root[3];
     int32_t m = -1;
     if (keys && skeys && perm && Ys && depth && lo && hi && leaf && child && prefix && com &&
-        oracle_morton(Y, n, bits, root, keys) == 0 && oracle_sort(keys, n, skeys, perm) == 0) {
+        oracle_morton(Y, n, bits, root, keys) == 0 && oracle_sort_ties(keys, n, tie_rank, skeys, perm) == 0) {
         for (int32_t p = 0; p < n; ++p) { Ys[2 * p] = Y[2 * perm[p]]; Ys[2 * p + 1] = Y[2 * perm[p] + 1]; }
         m = oracle_tree(skeys, Ys, n, bits, leaf_cap, cap, depth, prefix, lo, hi, leaf, child, com);
     }
@@ -541,11 +554,18 @@ int32_t oracle_repulse_bh(const float *Y, int32_t n, float theta, int32_t leaf_c
     return m;
 }
 
+int32_t oracle_repulse_bh(const float *Y, int32_t n, float theta, int32_t leaf_cap, int32_t group,
+                          int32_t bits, double *R, double *z, double *Zout, int64_t *stats)
+{
+    return oracle_repulse_bh_ties(Y, n, theta, leaf_cap, group, bits, NULL, R, z, Zout, stats);
+}
+
 /* Barnes-Hut gradient at fixed Y: Eq. (7) with the attractive term summed  */
 /* over the stored entries of P and the repulsive term / Z from the walk.   */
-int32_t oracle_grad_bh(const float *Y, int32_t n, const int32_t *row_ptr, const int32_t *col,
-                       const double *val, float theta, int32_t leaf_cap, int32_t group, int32_t bits,
-                       double alpha, double *A, double *R, double *Zout, double *grad, int64_t *stats)
+int32_t oracle_grad_bh_ties(const float *Y, int32_t n, const int32_t *row_ptr, const int32_t *col,
+                            const double *val, float theta, int32_t leaf_cap, int32_t group, int32_t bits,
+                            const int32_t *tie_rank, double alpha, double *A, double *R, double *Zout,
+                            double *grad, int64_t *stats)
 {
     double *Yd = malloc((size_t)n * 16);
     if (!Yd) return -1;
@@ -553,12 +573,20 @@ int32_t oracle_grad_bh(const float *Y, int32_t n, const int32_t *row_ptr, const 
     oracle_attract(Yd, n, row_ptr, col, val, A);
     free(Yd);
     double Z = 0.0;
-    int32_t m = oracle_repulse_bh(Y, n, theta, leaf_cap, group, bits, R, NULL, &Z, stats);
+    int32_t m = oracle_repulse_bh_ties(Y, n, theta, leaf_cap, group, bits, tie_rank, R, NULL, &Z, stats);
     if (m < 0) return m;
     if (Zout) *Zout = Z;
     if (grad)
         for (int32_t i = 0; i < 2 * n; ++i) grad[i] = 4.0 * (alpha * A[i] - R[i] / Z);
     return m;
+}
+
+int32_t oracle_grad_bh(const float *Y, int32_t n, const int32_t *row_ptr, const int32_t *col,
+                       const double *val, float theta, int32_t leaf_cap, int32_t group, int32_t bits,
+                       double alpha, double *A, double *R, double *Zout, double *grad, int64_t *stats)
+{
+    return oracle_grad_bh_ties(Y, n, row_ptr, col, val, theta, leaf_cap, group, bits, NULL, alpha, A, R, Zout, grad,
+                               stats);
 }
 
 /* ------------------------------------------------------------------------ */

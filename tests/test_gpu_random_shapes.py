@@ -91,9 +91,11 @@ def _points_like(rng, n, kind, seed):
 
 
 def test_tree_and_forces_on_random_parameters():
-    """Point sets with equal grid keys (kinds 3 and 4, or a coarse grid) are run without renumbering: with it, points of
-    equal key are ordered by the library's internal number, the groups of 64 differ among them, and the forces
-    agree with the oracle's only to the size of the approximation."""
+    """Sec. III-C step 4 leaves the order of points with equal grid keys open.  Without renumbering the library
+    orders them by index, as the oracle does by default, and everything is compared as it is.  With renumbering it
+    orders them by its internal number: the test then checks that its order is a sorted one (a permutation along
+    which the keys do not decrease), hands the oracle that order as the rank for equal keys, and compares cells,
+    order and forces with the oracle's for that rank (kinds 3 and 4 and the coarse grids have many equal keys)."""
     import torch
     from paper_1807_11824_amd import Tsne
     rng = np.random.default_rng(5)
@@ -111,7 +113,8 @@ def test_tree_and_forces_on_random_parameters():
         params = dict(theta=theta, leaf_cap=leaf_cap, morton_bits=bits)
         want = oracle.tree(Y, bits=bits, leaf_cap=leaf_cap)
         ties = len(np.unique(want["keys"])) < n
-        if not ties and rng.integers(0, 2):
+        renumber = bool(rng.integers(0, 2))
+        if renumber:
             params.update(max_nnz=len(col), far_tiles=int(rng.choice([0, 1, 2])))
         print(f"case {case}: n={n} kind={kind} deg={deg} ties={ties} {params}", flush=True)
         t = Tsne(n, **params)
@@ -122,10 +125,19 @@ def test_tree_and_forces_on_random_parameters():
         tree = {k: (v.cpu().numpy() if hasattr(v, "cpu") else v) for k, v in t.export_tree().items()}
         t.close()
         assert st == 0
+        tie_rank = None
+        if renumber and ties:
+            perm = tree["perm"].astype(np.int64)
+            assert np.array_equal(np.sort(perm), np.arange(n)), case
+            assert np.all(np.diff(want["keys"][perm].astype(np.int64)) >= 0), case       # (keys < 2^44)
+            tie_rank = np.empty(n, np.int32)
+            tie_rank[perm] = np.arange(n, dtype=np.int32)
+            want = oracle.tree(Y, bits=bits, leaf_cap=leaf_cap, tie_rank=tie_rank)
         assert tree["m"] == want["m"] and np.array_equal(tree["keys"].view(np.uint64), want["keys"]), case
         for f in ("depth", "lo", "hi", "leaf", "perm"):
             assert np.array_equal(tree[f], want[f]), (case, f)
-        o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=theta, leaf_cap=leaf_cap, group=64, alpha=1.0, bits=bits)
+        o = oracle.grad_bh(Y, rp, col, val.astype(np.float64), theta=theta, leaf_cap=leaf_cap, group=64, alpha=1.0, bits=bits,
+                           tie_rank=tie_rank)
         assert rel_l2(A, o["A"]) <= 1e-4 and rel_l2(R, o["R"]) <= 1e-4, case
         if o["Z"] > n:        # (a few points very far apart: the point's own term limits Z to 2^-24 absolute per point)
             assert abs(Z - o["Z"]) <= 1e-5 * o["Z"], case

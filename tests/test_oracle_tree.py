@@ -145,3 +145,36 @@ def test_deep_grid_splits_what_16_levels_cannot():
     topb = b["depth"] < 16
     assert np.array_equal(a["lo"][top], b["lo"][topb]) and np.array_equal(a["hi"][top], b["hi"][topb])
     assert np.array_equal(b["sorted_keys"] >> np.uint64(12), a["sorted_keys"])
+
+
+def test_rank_for_equal_keys_only_moves_points_inside_their_runs():
+    """Sec. III-C step 4 does not say how points with equal keys are ordered.  The default (by index) and a caller's
+    rank must give the same keys and cells; only the members of a run of equal keys change places, as the rank says.
+    With theta = 0 nothing is approximated, so the forces do not depend on that order either."""
+    rng = np.random.default_rng(3)
+    n = 3000
+    Y = np.repeat(rng.standard_normal((n // 5, 2)).astype(np.float32), 5, axis=0)      # every point five times
+    Y[::7] += rng.standard_normal((len(Y[::7]), 2)).astype(np.float32) * 1e-3           # and some near copies
+    a = oracle.tree(Y, bits=12, leaf_cap=4)
+    assert len(np.unique(a["keys"])) < n
+    same = oracle.tree(Y, bits=12, leaf_cap=4, tie_rank=np.arange(n))
+    for f in ("perm", "depth", "lo", "hi", "leaf", "com"):
+        assert np.array_equal(a[f], same[f]), f
+    rank = rng.permutation(n).astype(np.int32)
+    b = oracle.tree(Y, bits=12, leaf_cap=4, tie_rank=rank)
+    for f in ("sorted_keys", "depth", "lo", "hi", "leaf"):
+        assert np.array_equal(a[f], b[f]), f
+    assert not np.array_equal(a["perm"], b["perm"])
+    assert np.array_equal(np.sort(b["perm"]), np.arange(n))
+    sk = a["sorted_keys"]
+    ends = np.flatnonzero(np.r_[True, sk[1:] != sk[:-1], True])
+    for s, e in zip(ends[:-1], ends[1:]):
+        assert sorted(a["perm"][s:e]) == sorted(b["perm"][s:e])          # the same points share the run
+        assert np.all(np.diff(rank[b["perm"][s:e]]) > 0)                  # in the order of the rank
+        assert np.all(np.diff(a["perm"][s:e]) > 0)                        # by index without one
+    # centres of mass: the same points summed in another order
+    assert np.abs(a["com"].astype(np.float64) - b["com"]).max() <= 1e-6 * float(a["root"][2])
+    r0 = oracle.repulse_bh(Y, theta=0.0, leaf_cap=4, bits=12)
+    r1 = oracle.repulse_bh(Y, theta=0.0, leaf_cap=4, bits=12, tie_rank=rank)
+    assert np.abs(r0["R"] - r1["R"]).max() <= 1e-12 * np.abs(r0["R"]).max()
+    assert abs(r0["Z"] - r1["Z"]) <= 1e-12 * r0["Z"]
